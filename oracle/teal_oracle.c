@@ -1,0 +1,226 @@
+/*
+ * CPU oracle for the TEAL decode path: magnitude thresholding of a hidden
+ * state followed by the matrix-vector product over the thresholded state.
+ *
+ * THIS IS TEST INFRASTRUCTURE.  It exists to check the GPU library and to be
+ * timed as a CPU baseline.  Only tests, the smoke check and the benchmark's
+ * cpu_baseline leg may call it; the product never does.  It shares no code,
+ * header, table or helper with the GPU library.
+ *
+ * The method computes exactly (up to rounding order) a result with a plain
+ * definition, so the oracle is that definition written out in fp64:
+ *
+ *   Definition 1 (Section 4.2):  s_t(x)_i = 0 if |x_i| <= t, else x_i.
+ *   Layer forward (Section 4.2): Y = s_t(x) W^T, W in R^{n x m}, x in R^m
+ *                                (orientation as in Section 3).
+ *   Kernel contract (Section 4.4): mask s = [|x| > t]; result (x . s) W^T.
+ *
+ * The product loop is dense: it multiplies by the explicit zeros and knows
+ * nothing about skipping channels, compaction, tiling or split-K.
+ *
+ * Storage formats are decoded from their bit patterns here (IEEE 754
+ * binary16 for x and the scales; bfloat16 = the upper 16 bits of a binary32
+ * for W), so that no rounding happens anywhere before the fp64 arithmetic.
+ *
+ * Pins (tests/test_oracle_*.py): decoders against numpy/torch on all 65536
+ * patterns; mask against brute-force enumeration incl. ties; t = 0 against
+ * a dense numpy fp64 product; general t against the dense product on an
+ * explicitly zeroed x; exact rational arithmetic on tiny shapes; measured
+ * sparsity against the order statistic that chose t; the closed-form
+ * relative error of Theorem A.1.  The int4 nibble order and the scale
+ * indexing of the quantised variants are conventions of this build, not of
+ * the paper (Section 5.3 only names the bit widths): for those two layout
+ * conventions parity is unpinned by the paper and pinned only by hand-built
+ * single-entry matrices.
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* ---- storage formats ---------------------------------------------------- */
+
+/* IEEE 754 binary16: 1 sign, 5 exponent (bias 15), 10 fraction bits. */
+double oracle_f16_bits_to_f64(uint16_t h)
+{
+    int sign = (h >> 15) & 1;
+    int e = (h >> 10) & 0x1F;
+    int f = h & 0x3FF;
+    double v;
+    if (e == 0)
+        v = ldexp((double)f, -24);               /* subnormal: f * 2^-10 * 2^-14 */
+    else if (e == 0x1F)
+        v = f ? (double)NAN : (double)INFINITY;
+    else
+        v = ldexp((double)(0x400 + f), e - 25);  /* (1 + f/1024) * 2^(e-15) */
+    return sign ? -v : v;
+}
+
+/* bfloat16: 1 sign, 8 exponent (bias 127), 7 fraction bits. */
+double oracle_bf16_bits_to_f64(uint16_t b)
+{
+    int sign = (b >> 15) & 1;
+    int e = (b >> 7) & 0xFF;
+    int f = b & 0x7F;
+    double v;
+    if (e == 0)
+        v = ldexp((double)f, -133);              /* subnormal: f * 2^-7 * 2^-126 */
+    else if (e == 0xFF)
+        v = f ? (double)NAN : (double)INFINITY;
+    else
+        v = ldexp((double)(0x80 + f), e - 134);  /* (1 + f/128) * 2^(e-127) */
+    return sign ? -v : v;
+}
+
+/* ---- Definition 1 ------------------------------------------------------- */
+
+/*
+ * xs[i] = s_t(x)_i in fp64; mask[i] = 1 where the entry is kept (|x_i| > t,
+ * strictly: an entry equal to the threshold is zeroed); idx = ascending list
+ * of kept positions; returns their number.  NaN compares false and is
+ * dropped.  Any of xs / mask / idx may be NULL.
+ */
+int32_t oracle_sparsify(const uint16_t *x_f16, int32_t m, float t,
+                        double *xs, uint8_t *mask, int32_t *idx)
+{
+    const double td = (double)t;
+    int32_t count = 0;
+    for (int32_t i = 0; i < m; ++i) {
+        double xd = oracle_f16_bits_to_f64(x_f16[i]);
+        int keep = fabs(xd) > td;
+        if (xs) xs[i] = keep ? xd : 0.0;
+        if (mask) mask[i] = (uint8_t)keep;
+        if (keep) {
+            if (idx) idx[count] = i;
+            ++count;
+        }
+    }
+    return count;
+}
+
+/* ---- Y = s_t(x) W^T ----------------------------------------------------- */
+
+/*
+ * W is canonical: n rows (output channels) of m bf16 values (input channels),
+ * row-major.  xs is the already thresholded state in fp64.  y[j] = sum_i
+ * xs[i] * W[j][i], summed in index order.
+ */
+static void dense_rows_bf16(const uint16_t *W_bf16, const double *xs,
+                            double *y, int32_t m, int32_t n)
+{
+#pragma omp parallel for schedule(static)
+    for (int32_t j = 0; j < n; ++j) {
+        const uint16_t *row = W_bf16 + (size_t)j * (size_t)m;
+        double acc = 0.0;
+        for (int32_t i = 0; i < m; ++i)
+            acc += xs[i] * oracle_bf16_bits_to_f64(row[i]);
+        y[j] = acc;
+    }
+}
+
+/* scratch_xs: caller-provided m doubles. Returns the number of kept entries. */
+int32_t oracle_sparse_gemv_bf16(const uint16_t *W_bf16, const uint16_t *x_f16,
+                                float t, double *y, int32_t m, int32_t n,
+                                double *scratch_xs)
+{
+    int32_t count = oracle_sparsify(x_f16, m, t, scratch_xs, NULL, NULL);
+    dense_rows_bf16(W_bf16, scratch_xs, y, m, n);
+    return count;
+}
+
+/* Selected output channels only: y[r] = sum_i xs[i] * W[rows[r]][i]. */
+int32_t oracle_sparse_gemv_bf16_rows(const uint16_t *W_bf16,
+                                     const uint16_t *x_f16, float t,
+                                     const int32_t *rows, int32_t nrows,
+                                     double *y, int32_t m, int32_t n,
+                                     double *scratch_xs)
+{
+    int32_t count = oracle_sparsify(x_f16, m, t, scratch_xs, NULL, NULL);
+    for (int32_t r = 0; r < nrows; ++r) {
+        int32_t j = rows[r];
+        if (j < 0 || j >= n) { y[r] = (double)NAN; continue; }
+        const uint16_t *row = W_bf16 + (size_t)j * (size_t)m;
+        double acc = 0.0;
+        for (int32_t i = 0; i < m; ++i)
+            acc += scratch_xs[i] * oracle_bf16_bits_to_f64(row[i]);
+        y[r] = acc;
+    }
+    return count;
+}
+
+/*
+ * 8-bit weights (Section 5.3, channel-wise): the stored arrays are
+ * q[m][n] (input-channel-major int8) and scale[n] (fp16, one per output
+ * channel); they DEFINE W[j][i] = q[i][j] * scale[j].
+ */
+int32_t oracle_sparse_gemv_w8(const int8_t *q, const uint16_t *scale_f16,
+                              const uint16_t *x_f16, float t, double *y,
+                              int32_t m, int32_t n, double *scratch_xs)
+{
+    int32_t count = oracle_sparsify(x_f16, m, t, scratch_xs, NULL, NULL);
+#pragma omp parallel for schedule(static)
+    for (int32_t j = 0; j < n; ++j) {
+        double s = oracle_f16_bits_to_f64(scale_f16[j]);
+        double acc = 0.0;
+        for (int32_t i = 0; i < m; ++i) {
+            double w = (double)q[(size_t)i * (size_t)n + (size_t)j] * s;
+            acc += scratch_xs[i] * w;
+        }
+        y[j] = acc;
+    }
+    return count;
+}
+
+/*
+ * 4-bit weights with group scales: q is [m][n/2] bytes, two two's-complement
+ * nibbles per byte along the output axis (low nibble = even j); scale is
+ * fp16 [m/group][n].  They DEFINE W[j][i] = nibble(i, j) * scale[i/group][j].
+ */
+static int nibble_value(const uint8_t *q, int32_t n, int32_t i, int32_t j)
+{
+    uint8_t byte = q[(size_t)i * (size_t)(n / 2) + (size_t)(j / 2)];
+    int v = (j & 1) ? (byte >> 4) : (byte & 0x0F);
+    return v >= 8 ? v - 16 : v;
+}
+
+int32_t oracle_sparse_gemv_w4(const uint8_t *q, const uint16_t *scale_f16,
+                              int32_t group, const uint16_t *x_f16, float t,
+                              double *y, int32_t m, int32_t n,
+                              double *scratch_xs)
+{
+    int32_t count = oracle_sparsify(x_f16, m, t, scratch_xs, NULL, NULL);
+#pragma omp parallel for schedule(static)
+    for (int32_t j = 0; j < n; ++j) {
+        double acc = 0.0;
+        for (int32_t i = 0; i < m; ++i) {
+            double s = oracle_f16_bits_to_f64(
+                scale_f16[(size_t)(i / group) * (size_t)n + (size_t)j]);
+            double w = (double)nibble_value(q, n, i, j) * s;
+            acc += scratch_xs[i] * w;
+        }
+        y[j] = acc;
+    }
+    return count;
+}
+
+/* Threads the parallel loops above use (1 when built without OpenMP). */
+int32_t oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return (int32_t)omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+void oracle_set_num_threads(int32_t k)
+{
+#ifdef _OPENMP
+    if (k > 0) omp_set_num_threads(k);
+#else
+    (void)k;
+#endif
+}

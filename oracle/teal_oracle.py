@@ -1,0 +1,188 @@
+"""Python face of the CPU oracle (oracle/teal_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: tests, the smoke check and the benchmark's
+cpu_baseline leg may import this; the product path never does, and this
+module imports nothing from the GPU package.
+
+It only marshals numpy arrays into the C functions; the arithmetic -- the
+sparsification function of Definition 1 (Section 4.2) and the thresholded
+matrix-vector product Y = s_t(x) W^T (Sections 3, 4.2, 4.4) in fp64 -- is in
+the C file.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "teal_oracle.c")
+_LIB = os.path.join(_HERE, "libteal_oracle.so")
+
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (plain -O2 + OpenMP, no tuning flags)."""
+    stale = (not os.path.exists(_LIB)
+             or os.path.getmtime(_LIB) < os.path.getmtime(_SRC))
+    if force or stale:
+        tmp = _LIB + f".tmp{os.getpid()}"
+        subprocess.run(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11",
+                        "-Wall", "-Wextra", "-o", tmp, _SRC, "-lm"], check=True)
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    lib = ctypes.CDLL(build())
+    c = ctypes
+    u16p, u8p, i8p = c.POINTER(c.c_uint16), c.POINTER(c.c_uint8), c.POINTER(c.c_int8)
+    i32p, f64p = c.POINTER(c.c_int32), c.POINTER(c.c_double)
+    lib.oracle_f16_bits_to_f64.restype = c.c_double
+    lib.oracle_f16_bits_to_f64.argtypes = [c.c_uint16]
+    lib.oracle_bf16_bits_to_f64.restype = c.c_double
+    lib.oracle_bf16_bits_to_f64.argtypes = [c.c_uint16]
+    lib.oracle_sparsify.restype = c.c_int32
+    lib.oracle_sparsify.argtypes = [u16p, c.c_int32, c.c_float, f64p, u8p, i32p]
+    lib.oracle_sparse_gemv_bf16.restype = c.c_int32
+    lib.oracle_sparse_gemv_bf16.argtypes = [u16p, u16p, c.c_float, f64p,
+                                            c.c_int32, c.c_int32, f64p]
+    lib.oracle_sparse_gemv_bf16_rows.restype = c.c_int32
+    lib.oracle_sparse_gemv_bf16_rows.argtypes = [u16p, u16p, c.c_float, i32p, c.c_int32,
+                                                 f64p, c.c_int32, c.c_int32, f64p]
+    lib.oracle_sparse_gemv_w8.restype = c.c_int32
+    lib.oracle_sparse_gemv_w8.argtypes = [i8p, u16p, u16p, c.c_float, f64p,
+                                          c.c_int32, c.c_int32, f64p]
+    lib.oracle_sparse_gemv_w4.restype = c.c_int32
+    lib.oracle_sparse_gemv_w4.argtypes = [u8p, u16p, c.c_int32, u16p, c.c_float, f64p,
+                                          c.c_int32, c.c_int32, f64p]
+    lib.oracle_num_threads.restype = c.c_int32
+    lib.oracle_set_num_threads.argtypes = [c.c_int32]
+    _lib = lib
+    return lib
+
+
+def _ptr(a: np.ndarray, ctype):
+    return a.ctypes.data_as(ctypes.POINTER(ctype))
+
+
+def _x_bits(x_f16) -> np.ndarray:
+    x = np.ascontiguousarray(x_f16)
+    if x.dtype != np.float16 or x.ndim != 1:
+        raise TypeError("x must be a 1-D float16 array")
+    return x.view(np.uint16)
+
+
+def _f32(t) -> float:
+    tf = float(np.float32(t))
+    if tf != float(t):
+        raise ValueError("threshold must be exactly representable in fp32")
+    return tf
+
+
+def num_threads() -> int:
+    return int(_load().oracle_num_threads())
+
+
+def set_num_threads(k: int) -> None:
+    _load().oracle_set_num_threads(int(k))
+
+
+def f16_bits_to_f64(bits: int) -> float:
+    return float(_load().oracle_f16_bits_to_f64(int(bits)))
+
+
+def bf16_bits_to_f64(bits: int) -> float:
+    return float(_load().oracle_bf16_bits_to_f64(int(bits)))
+
+
+def sparsify(x_f16, t):
+    """Definition 1. Returns (xs float64[m], mask uint8[m], idx int32[count], count)."""
+    xb = _x_bits(x_f16)
+    m = xb.size
+    xs = np.empty(m, np.float64)
+    mask = np.empty(m, np.uint8)
+    idx = np.empty(max(m, 1), np.int32)
+    count = _load().oracle_sparsify(_ptr(xb, ctypes.c_uint16), m, _f32(t),
+                                    _ptr(xs, ctypes.c_double), _ptr(mask, ctypes.c_uint8),
+                                    _ptr(idx, ctypes.c_int32))
+    return xs, mask, idx[:count].copy(), int(count)
+
+
+def sparse_gemv_bf16(w_bits, x_f16, t) -> np.ndarray:
+    """y float64[n] = s_t(x) W^T for canonical W[n][m] given as bf16 bit patterns."""
+    w = np.ascontiguousarray(w_bits)
+    if w.dtype != np.uint16 or w.ndim != 2:
+        raise TypeError("W must be a 2-D uint16 array of bf16 bit patterns, [n][m]")
+    xb = _x_bits(x_f16)
+    n, m = w.shape
+    if xb.size != m:
+        raise ValueError("x length must equal W's input dimension")
+    y = np.empty(n, np.float64)
+    xs = np.empty(m, np.float64)
+    _load().oracle_sparse_gemv_bf16(_ptr(w, ctypes.c_uint16), _ptr(xb, ctypes.c_uint16),
+                                    _f32(t), _ptr(y, ctypes.c_double), m, n,
+                                    _ptr(xs, ctypes.c_double))
+    return y
+
+
+def sparse_gemv_bf16_rows(w_bits, x_f16, t, rows) -> np.ndarray:
+    """Selected output channels of sparse_gemv_bf16, one by one."""
+    w = np.ascontiguousarray(w_bits)
+    if w.dtype != np.uint16 or w.ndim != 2:
+        raise TypeError("W must be a 2-D uint16 array of bf16 bit patterns, [n][m]")
+    xb = _x_bits(x_f16)
+    n, m = w.shape
+    if xb.size != m:
+        raise ValueError("x length must equal W's input dimension")
+    r = np.ascontiguousarray(rows, dtype=np.int32)
+    y = np.empty(r.size, np.float64)
+    xs = np.empty(m, np.float64)
+    _load().oracle_sparse_gemv_bf16_rows(_ptr(w, ctypes.c_uint16), _ptr(xb, ctypes.c_uint16),
+                                         _f32(t), _ptr(r, ctypes.c_int32), r.size,
+                                         _ptr(y, ctypes.c_double), m, n,
+                                         _ptr(xs, ctypes.c_double))
+    return y
+
+
+def sparse_gemv_w8(q, scale_f16, x_f16, t) -> np.ndarray:
+    """q int8 [m][n], scale fp16 [n]; W[j][i] = q[i][j] * scale[j]."""
+    q = np.ascontiguousarray(q)
+    s = np.ascontiguousarray(scale_f16)
+    if q.dtype != np.int8 or q.ndim != 2 or s.dtype != np.float16:
+        raise TypeError("q must be int8 [m][n], scale fp16 [n]")
+    xb = _x_bits(x_f16)
+    m, n = q.shape
+    if xb.size != m or s.shape != (n,):
+        raise ValueError("shape mismatch")
+    y = np.empty(n, np.float64)
+    xs = np.empty(m, np.float64)
+    _load().oracle_sparse_gemv_w8(_ptr(q, ctypes.c_int8), _ptr(s.view(np.uint16), ctypes.c_uint16),
+                                  _ptr(xb, ctypes.c_uint16), _f32(t), _ptr(y, ctypes.c_double),
+                                  m, n, _ptr(xs, ctypes.c_double))
+    return y
+
+
+def sparse_gemv_w4(packed, scale_f16, group, x_f16, t) -> np.ndarray:
+    """packed uint8 [m][n/2] (low nibble = even j), scale fp16 [m/group][n]."""
+    p = np.ascontiguousarray(packed)
+    s = np.ascontiguousarray(scale_f16)
+    if p.dtype != np.uint8 or p.ndim != 2 or s.dtype != np.float16 or s.ndim != 2:
+        raise TypeError("packed must be uint8 [m][n/2], scale fp16 [m/group][n]")
+    xb = _x_bits(x_f16)
+    m, half = p.shape
+    n = 2 * half
+    if xb.size != m or m % group or s.shape != (m // group, n):
+        raise ValueError("shape mismatch")
+    y = np.empty(n, np.float64)
+    xs = np.empty(m, np.float64)
+    _load().oracle_sparse_gemv_w4(_ptr(p, ctypes.c_uint8), _ptr(s.view(np.uint16), ctypes.c_uint16),
+                                  int(group), _ptr(xb, ctypes.c_uint16), _f32(t),
+                                  _ptr(y, ctypes.c_double), m, n, _ptr(xs, ctypes.c_double))
+    return y
