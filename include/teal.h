@@ -1,0 +1,156 @@
+/*
+ * teal.h -- C ABI of the MI355X (gfx950) library for TEAL's decode-time hot
+ * path: magnitude thresholding of a hidden state fused with a matrix-vector
+ * product that reads from HBM only the weight channels whose activation
+ * survived.
+ *
+ * Notation (Section 3): x in R^m is the hidden state, W in R^{n x m} the
+ * weight matrix ("out x in"), y = x W^T in R^n.  The sparsification function
+ * of Definition 1 (Section 4.2) is s_t(x)_i = 0 if |x_i| <= t, else x_i, and
+ * the layer forward is Y = s_t(x) W^T (Section 4.2).
+ *
+ * Storage.  W is kept input-channel-major ("column-major" in the wording of
+ * Sections 3 and 4.4): Wt[m][n], row i = the n weights of input channel i,
+ * contiguous.  A dropped channel is then one contiguous row that is never
+ * fetched.
+ *
+ * Conventions for every call.
+ *   - Every pointer is DEVICE memory owned by the caller, unless it says
+ *     "host".  The library never allocates, frees or keeps a pointer.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls only enqueue work; results are valid once the caller has
+ *     synchronised the stream.  Calls on one stream run in order.
+ *   - x is IEEE binary16 (fp16).  t is fp32, finite and >= 0 (it is a
+ *     quantile of |x|, Definition 1).  The comparison |x_i| > t is done in
+ *     fp32 on exactly converted values, so it involves no rounding.  NaN in x
+ *     compares false (dropped); +-Inf is kept.  t = 0 is the dense product
+ *     (only entries equal to zero are skipped).
+ *   - y is fp32, fully overwritten (all zeros when nothing survives).
+ *     Products are formed and summed in fp32, in a fixed order: results are
+ *     bitwise reproducible from run to run for a given shape.
+ *   - All argument checks happen on the host before any GPU work and return
+ *     a status; nothing aborts, throws or prints.
+ *   - `workspace` is caller-provided device scratch of at least
+ *     teal_workspace_bytes(m, n) bytes, 256-byte aligned.  Calls that may run
+ *     concurrently need distinct workspaces.  Contents need no
+ *     initialisation and are undefined afterwards.
+ *   - No global state; any host thread may call with any current device, as
+ *     long as the pointers belong to it.
+ */
+#ifndef TEAL_H
+#define TEAL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum teal_status {
+    TEAL_OK = 0,
+    TEAL_ERR_NULL = 1,        /* a required pointer is NULL */
+    TEAL_ERR_SHAPE = 2,       /* m or n out of range or not a multiple of the format's vector width */
+    TEAL_ERR_ALIGN = 3,       /* a pointer is not aligned as required */
+    TEAL_ERR_THRESHOLD = 4,   /* t is negative, NaN or infinite */
+    TEAL_ERR_WORKSPACE = 5,   /* workspace too small */
+    TEAL_ERR_UNSUPPORTED = 6, /* group size or launch parameters not supported */
+    TEAL_ERR_HIP = 7          /* the HIP runtime reported an error at launch */
+} teal_status;
+
+/* Static, NUL-terminated description of a status (host memory, never freed). */
+const char *teal_status_string(teal_status s);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int teal_version(void);
+
+/* Device scratch needed by any teal_sparse_gemv_* call with these dimensions.
+ * Returns 0 if m or n is out of range. */
+size_t teal_workspace_bytes(int m, int n);
+
+/*
+ * Definition 1 (Section 4.2) alone, as the mask s = [|x| > t] of Section 4.4.
+ *   x_f16 [m] fp16 (2-byte aligned), 1 <= m < 2^31 (m = 0 is accepted: count = 0).
+ *   mask  [m] bytes, 1 = kept, 0 = zeroed.                 May be NULL.
+ *   idx   [m] int32 capacity; the first `count` entries are the kept
+ *         positions in ascending order, the rest is untouched. May be NULL.
+ *   count one int32: number of kept entries.               May be NULL.
+ */
+teal_status teal_sparsify(const void *x_f16, int m, float t,
+                          uint8_t *mask, int32_t *idx, int32_t *count,
+                          void *stream);
+
+/*
+ * y = s_t(x) W^T (Section 4.2), computed as in Section 4.4: the mask is built
+ * inside the kernel from x and t, only rows Wt[i][:] with |x_i| > t are read,
+ * the input dimension is split across thread blocks, and the per-split
+ * partial sums (fp32) are combined in a fixed order.
+ *   Wt_bf16 [m][n] bfloat16, input-channel-major, 16-byte aligned.
+ *   x_f16   [m] fp16, 2-byte aligned.
+ *   y       [n] fp32, 4-byte aligned.
+ *   1 <= m <= 2^24, 8 <= n <= 2^24, n % 8 == 0.
+ */
+teal_status teal_sparse_gemv_bf16(const void *Wt_bf16, const void *x_f16, float t,
+                                  float *y, int m, int n,
+                                  void *workspace, size_t workspace_bytes,
+                                  void *stream);
+
+/*
+ * The same product for 8-bit channel-wise quantised weights (Section 5.3):
+ * W[j][i] = Wq[i][j] * scale[j].
+ *   Wq    [m][n] int8 (symmetric, two's complement), 16-byte aligned.
+ *   scale [n] fp16, one per output channel, 2-byte aligned.
+ *   n % 16 == 0; x, y and the ranges of m, n as for teal_sparse_gemv_bf16.
+ */
+teal_status teal_sparse_gemv_w8(const int8_t *Wq, const void *scale_f16,
+                                const void *x_f16, float t, float *y, int m, int n,
+                                void *workspace, size_t workspace_bytes,
+                                void *stream);
+
+/*
+ * The same product for 4-bit group-quantised weights (Section 5.3):
+ * W[j][i] = nibble(i, j) * scale[i / group][j].
+ *   Wq    [m][n/2] bytes, two two's-complement nibbles per byte along the
+ *         output axis, low nibble = even j; 16-byte aligned.
+ *   scale [m/group][n] fp16, 16-byte aligned.
+ *   group == 128, m % 128 == 0, n % 32 == 0; x, y and the ranges of m, n as
+ *   for teal_sparse_gemv_bf16.
+ */
+teal_status teal_sparse_gemv_w4(const uint8_t *Wq, const void *scale_f16, int group,
+                                const void *x_f16, float t, float *y, int m, int n,
+                                void *workspace, size_t workspace_bytes,
+                                void *stream);
+
+/*
+ * One-time layout step (Sections 3 and 4.4: weights used under input sparsity
+ * must be stored channel-contiguous): canonical row-major W[n][m] bf16 ->
+ * Wt[m][n].  Device to device, out of place; both 2-byte aligned; any m, n >= 1.
+ */
+teal_status teal_pack_bf16(const void *W_rowmajor, void *Wt, int m, int n,
+                           void *stream);
+
+/*
+ * teal_sparse_gemv_bf16 with the launch shape chosen by the caller instead
+ * of by the library; for tuning and for tests that walk the kernel variants.
+ * Results are identical in meaning (the summation order differs with the
+ * shape).  0 means "library's choice" for each field.
+ *   lanes_per_row  64, 32 or 16: lanes that share one weight row per load
+ *                  (each lane reads 16 bytes), i.e. an output tile of 512,
+ *                  256 or 128 columns per thread block.
+ *   splits         1..128: thread blocks along the input dimension (split-K,
+ *                  Section 4.4).
+ *   waves          4 or 8 wavefronts per thread block.
+ *   unroll         4 or 8 row loads in flight per wavefront.
+ * Unsupported combinations return TEAL_ERR_UNSUPPORTED.
+ */
+teal_status teal_sparse_gemv_bf16_ex(const void *Wt_bf16, const void *x_f16, float t,
+                                     float *y, int m, int n,
+                                     void *workspace, size_t workspace_bytes,
+                                     void *stream,
+                                     int lanes_per_row, int splits, int waves, int unroll);
+
+#ifdef __cplusplus
+}
+#endif
+
+#endif /* TEAL_H */

@@ -1,0 +1,15 @@
+"""MI355X-native TEAL decode path: thresholded sparse GEMV behind a C ABI.
+
+The work is done by libteal.so (hand-written HIP for gfx950, include/teal.h).
+This package only marshals arguments; PyTorch supplies device memory and
+streams.  There is no CPU fallback: without the built library every call
+raises.
+"""
+from .binding import (  # noqa: F401
+    TEAL_OK, TEAL_ERR_NULL, TEAL_ERR_SHAPE, TEAL_ERR_ALIGN, TEAL_ERR_THRESHOLD,
+    TEAL_ERR_WORKSPACE, TEAL_ERR_UNSUPPORTED, TEAL_ERR_HIP,
+    TealError, check, library_path, load_library,
+    teal_status_string, teal_version, teal_workspace_bytes,
+    teal_sparsify, teal_sparse_gemv_bf16, teal_sparse_gemv_bf16_ex,
+    teal_sparse_gemv_w8, teal_sparse_gemv_w4, teal_pack_bf16,
+)

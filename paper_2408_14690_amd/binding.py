@@ -1,0 +1,157 @@
+"""ctypes binding of libteal.so: the same names as include/teal.h, argument
+marshalling only.  Pointer arguments may be torch tensors (their data_ptr() is
+passed; they must be contiguous), plain integer addresses, or None.  `stream`
+defaults to torch's current stream on the current device.  Every function
+returns the library's status code; check() turns a non-zero one into TealError.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+TEAL_OK = 0
+TEAL_ERR_NULL = 1
+TEAL_ERR_SHAPE = 2
+TEAL_ERR_ALIGN = 3
+TEAL_ERR_THRESHOLD = 4
+TEAL_ERR_WORKSPACE = 5
+TEAL_ERR_UNSUPPORTED = 6
+TEAL_ERR_HIP = 7
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libteal.so")
+_lib = None
+
+EXPORTS = (
+    "teal_status_string", "teal_version", "teal_workspace_bytes", "teal_sparsify",
+    "teal_sparse_gemv_bf16", "teal_sparse_gemv_bf16_ex", "teal_sparse_gemv_w8",
+    "teal_sparse_gemv_w4", "teal_pack_bf16",
+)
+
+
+class TealError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = int(status)
+        super().__init__(f"libteal status {self.status}: {teal_status_string(self.status)}")
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Loads the built library; raises if it is not there (no fallback)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise FileNotFoundError(
+            f"{_LIB_PATH} is not built; run `python -m paper_2408_14690_amd.build`")
+    lib = ctypes.CDLL(_LIB_PATH)
+    c = ctypes
+    vp, i, f, sz = c.c_void_p, c.c_int, c.c_float, c.c_size_t
+    lib.teal_status_string.restype = c.c_char_p
+    lib.teal_status_string.argtypes = [i]
+    lib.teal_version.restype = i
+    lib.teal_version.argtypes = []
+    lib.teal_workspace_bytes.restype = sz
+    lib.teal_workspace_bytes.argtypes = [i, i]
+    lib.teal_sparsify.restype = i
+    lib.teal_sparsify.argtypes = [vp, i, f, vp, vp, vp, vp]
+    lib.teal_sparse_gemv_bf16.restype = i
+    lib.teal_sparse_gemv_bf16.argtypes = [vp, vp, f, vp, i, i, vp, sz, vp]
+    lib.teal_sparse_gemv_bf16_ex.restype = i
+    lib.teal_sparse_gemv_bf16_ex.argtypes = [vp, vp, f, vp, i, i, vp, sz, vp, i, i, i, i]
+    lib.teal_sparse_gemv_w8.restype = i
+    lib.teal_sparse_gemv_w8.argtypes = [vp, vp, vp, f, vp, i, i, vp, sz, vp]
+    lib.teal_sparse_gemv_w4.restype = i
+    lib.teal_sparse_gemv_w4.argtypes = [vp, vp, i, vp, f, vp, i, i, vp, sz, vp]
+    lib.teal_pack_bf16.restype = i
+    lib.teal_pack_bf16.argtypes = [vp, vp, i, i, vp]
+    _lib = lib
+    return lib
+
+
+def _ptr(a):
+    if a is None:
+        return None
+    if isinstance(a, int):
+        return a
+    if hasattr(a, "data_ptr"):
+        if not a.is_contiguous():
+            raise ValueError("tensor arguments must be contiguous")
+        return a.data_ptr()
+    raise TypeError(f"cannot pass {type(a).__name__} as a device pointer")
+
+
+def _nbytes(a, given):
+    if given is not None:
+        return int(given)
+    if hasattr(a, "numel"):
+        return a.numel() * a.element_size()
+    raise TypeError("workspace_bytes is required when workspace is a raw address")
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def check(status: int) -> None:
+    if status != TEAL_OK:
+        raise TealError(status)
+
+
+def teal_status_string(status: int) -> str:
+    return load_library().teal_status_string(int(status)).decode()
+
+
+def teal_version() -> int:
+    return int(load_library().teal_version())
+
+
+def teal_workspace_bytes(m: int, n: int) -> int:
+    return int(load_library().teal_workspace_bytes(int(m), int(n)))
+
+
+def teal_sparsify(x_f16, m, t, mask=None, idx=None, count=None, stream=None) -> int:
+    return load_library().teal_sparsify(_ptr(x_f16), int(m), float(t), _ptr(mask), _ptr(idx),
+                                        _ptr(count), _stream(stream))
+
+
+def teal_sparse_gemv_bf16(Wt_bf16, x_f16, t, y, m, n, workspace, workspace_bytes=None,
+                          stream=None) -> int:
+    return load_library().teal_sparse_gemv_bf16(
+        _ptr(Wt_bf16), _ptr(x_f16), float(t), _ptr(y), int(m), int(n), _ptr(workspace),
+        _nbytes(workspace, workspace_bytes), _stream(stream))
+
+
+def teal_sparse_gemv_bf16_ex(Wt_bf16, x_f16, t, y, m, n, workspace, workspace_bytes=None,
+                             stream=None, lanes_per_row=0, splits=0, waves=0, unroll=0) -> int:
+    return load_library().teal_sparse_gemv_bf16_ex(
+        _ptr(Wt_bf16), _ptr(x_f16), float(t), _ptr(y), int(m), int(n), _ptr(workspace),
+        _nbytes(workspace, workspace_bytes), _stream(stream), int(lanes_per_row), int(splits),
+        int(waves), int(unroll))
+
+
+def teal_sparse_gemv_w8(Wq, scale_f16, x_f16, t, y, m, n, workspace, workspace_bytes=None,
+                        stream=None) -> int:
+    return load_library().teal_sparse_gemv_w8(
+        _ptr(Wq), _ptr(scale_f16), _ptr(x_f16), float(t), _ptr(y), int(m), int(n),
+        _ptr(workspace), _nbytes(workspace, workspace_bytes), _stream(stream))
+
+
+def teal_sparse_gemv_w4(Wq, scale_f16, group, x_f16, t, y, m, n, workspace,
+                        workspace_bytes=None, stream=None) -> int:
+    return load_library().teal_sparse_gemv_w4(
+        _ptr(Wq), _ptr(scale_f16), int(group), _ptr(x_f16), float(t), _ptr(y), int(m), int(n),
+        _ptr(workspace), _nbytes(workspace, workspace_bytes), _stream(stream))
+
+
+def teal_pack_bf16(W_rowmajor, Wt, m, n, stream=None) -> int:
+    return load_library().teal_pack_bf16(_ptr(W_rowmajor), _ptr(Wt), int(m), int(n),
+                                         _stream(stream))

@@ -1,0 +1,267 @@
+// Device-side building blocks of the fused threshold + sparse GEMV kernels
+// (gfx950, wave64).  One thread block owns an output tile and a slice of the
+// input dimension (split-K, Section 4.4).  It (1) builds the mask
+// s = [|x| > t] of its slice in-kernel (Definition 1; Section 4.4 fuses the
+// mask creation) and compacts the survivors into an LDS list with wavefront
+// ballots and an LDS prefix sum, (2) streams only the surviving rows of the
+// input-channel-major weights with 16-byte non-temporal loads and fp32 FMAs,
+// (3) sums its wavefronts' accumulators through LDS and writes one fp32
+// partial row.  A second kernel adds the partial rows in a fixed order.
+#pragma once
+
+#include <hip/hip_fp16.h>
+#include <hip/hip_runtime.h>
+
+#include "teal_internal.h"
+
+namespace teal {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kMaxSegs = kMaxSlice / 64;   // 64-channel segments per slice
+
+// Weight bytes are used exactly once: load them non-temporal so they do not
+// displace x and the partial sums from the caches (the counterpart of the
+// eviction-policy hint of Section 4.4).
+__device__ __forceinline__ u32x4 load_stream16(const void *p)
+{
+    return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+}
+
+// Number of set bits of a wavefront ballot in lanes below the calling lane.
+__device__ __forceinline__ int lanes_below(unsigned long long b)
+{
+    return (int)__builtin_amdgcn_mbcnt_hi((unsigned)(b >> 32),
+                                          __builtin_amdgcn_mbcnt_lo((unsigned)b, 0u));
+}
+
+// Definition 1 on one element: fp16 -> fp32 is exact, the compare is fp32.
+__device__ __forceinline__ bool survives(float xv, float t) { return fabsf(xv) > t; }
+
+// Compacts the survivors of channels [k0, k1) into list[] as (channel, x as
+// fp32 bits), ascending.  seg_prefix[] (LDS, kMaxSegs + 1 ints) ends up
+// holding the exclusive prefix of the per-64-channel-segment counts, with
+// the total in seg_prefix[nseg].  Returns the total (same in all threads).
+// Needs k1 - k0 <= kMaxSlice.  All threads of the block must call it.
+template <int WAVES>
+__device__ __forceinline__ int compact_slice(const __half *__restrict__ x, float t,
+                                             int k0, int k1, int2 *list, int *seg_prefix)
+{
+    const int lane = threadIdx.x & 63;
+    const int w = threadIdx.x >> 6;
+    const int nseg = (k1 - k0 + 63) >> 6;
+
+    for (int seg = w; seg < nseg; seg += WAVES) {
+        const int i = k0 + seg * 64 + lane;
+        const bool keep = i < k1 && survives(__half2float(x[i]), t);
+        const unsigned long long b = __ballot(keep);
+        if (lane == 0) seg_prefix[seg] = __popcll(b);
+    }
+    __syncthreads();
+    if (w == 0) {
+        const int c = lane < nseg ? seg_prefix[lane] : 0;
+        int incl = c;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int up = __shfl_up(incl, d);
+            if (lane >= d) incl += up;
+        }
+        if (lane < nseg) seg_prefix[lane] = incl - c;
+        if (lane == 63) seg_prefix[nseg] = incl;
+    }
+    __syncthreads();
+    for (int seg = w; seg < nseg; seg += WAVES) {
+        const int i = k0 + seg * 64 + lane;
+        float xv = 0.f;
+        bool keep = false;
+        if (i < k1) {
+            xv = __half2float(x[i]);
+            keep = survives(xv, t);
+        }
+        const unsigned long long b = __ballot(keep);
+        if (keep) list[seg_prefix[seg] + lanes_below(b)] = make_int2(i, __float_as_int(xv));
+    }
+    __syncthreads();
+    return seg_prefix[nseg];
+}
+
+// Streams `mine` consecutive list entries starting at list[start] and adds
+// x_i * W[i][cols of this lane] into acc.  LPR lanes share one row per load
+// (64 / LPR rows per wavefront load); U loads are in flight per wavefront.
+// `start` and `mine` are wavefront-uniform.
+template <class F, int LPR, int U>
+__device__ __forceinline__ void stream_rows(float (&acc)[F::kElemsPerLane], const int2 *list,
+                                            int start, int mine,
+                                            const unsigned char *__restrict__ wbase,
+                                            size_t row_bytes, unsigned lane_off)
+{
+    constexpr int R = 64 / LPR;
+    const int lane = threadIdx.x & 63;
+    if (mine <= 0) return;
+    if constexpr (R == 1) {
+        // The row index is wavefront-uniform: it lives in a scalar register and
+        // the load is (scalar row base) + (per-lane column offset).
+        for (int b = 0; b < mine; b += 64) {
+            const int2 ent = list[start + min(b + lane, mine - 1)];
+            const int nb = min(64, mine - b);
+            int k = 0;
+            for (; k + U <= nb; k += U) {
+                u32x4 v[U];
+                float xv[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int idx = __builtin_amdgcn_readlane(ent.x, k + u);
+                    xv[u] = __int_as_float(__builtin_amdgcn_readlane(ent.y, k + u));
+                    v[u] = load_stream16(wbase + (size_t)idx * row_bytes + lane_off);
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) F::fma(acc, v[u], xv[u]);
+            }
+            if (k < nb) {
+                // Last, partial batch: keep U loads in flight by repeating the
+                // final row with a zero multiplier (same address: no new traffic).
+                u32x4 v[U];
+                float xv[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int kk = min(k + u, nb - 1);
+                    const int idx = __builtin_amdgcn_readlane(ent.x, kk);
+                    const float xr = __int_as_float(__builtin_amdgcn_readlane(ent.y, kk));
+                    xv[u] = (k + u < nb) ? xr : 0.f;
+                    v[u] = load_stream16(wbase + (size_t)idx * row_bytes + lane_off);
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) F::fma(acc, v[u], xv[u]);
+            }
+        }
+    } else {
+        const int g = lane / LPR;
+        const int loads = (mine + R - 1) / R;
+        for (int it = 0; it < loads; it += U) {
+            u32x4 v[U];
+            float xv[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int e = (it + u) * R + g;
+                const int2 ent = list[start + min(e, mine - 1)];
+                xv[u] = e < mine ? __int_as_float(ent.y) : 0.f;
+                v[u] = load_stream16(wbase + (size_t)ent.x * row_bytes + lane_off);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) F::fma(acc, v[u], xv[u]);
+        }
+    }
+}
+
+// Adds the accumulators of the 64 / LPR row groups of a wavefront.
+template <int LPR, int N>
+__device__ __forceinline__ void fold_row_groups(float (&acc)[N])
+{
+#pragma unroll
+    for (int off = LPR; off < 64; off <<= 1) {
+#pragma unroll
+        for (int e = 0; e < N; ++e) acc[e] += __shfl_xor(acc[e], off);
+    }
+}
+
+// Wavefront-uniform contiguous share of `cnt` items for wavefront w of WAVES.
+__device__ __forceinline__ void wave_share(int cnt, int w, int waves, int &start, int &mine)
+{
+    const int per = cnt / waves, rem = cnt - per * waves;
+    start = w * per + min(w, rem);
+    mine = per + (w < rem ? 1 : 0);
+}
+
+// Sums the wavefronts' accumulators through LDS and writes this block's row
+// of outputs: out[col] for the tile's valid columns.
+template <class F, int LPR, int WAVES>
+__device__ __forceinline__ void block_combine(const float (&acc)[F::kElemsPerLane], float *red,
+                                              float *__restrict__ out, int tile, int n,
+                                              const typename F::Args &a)
+{
+    constexpr int EPL = F::kElemsPerLane;
+    constexpr int TN = LPR * EPL;
+    const int lane = threadIdx.x & 63;
+    const int w = threadIdx.x >> 6;
+    if (lane < LPR) {
+        float4 *dst = reinterpret_cast<float4 *>(red + w * TN + lane * EPL);
+#pragma unroll
+        for (int q = 0; q < EPL / 4; ++q)
+            dst[q] = make_float4(acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
+    }
+    __syncthreads();
+    for (int c = threadIdx.x; c < TN; c += WAVES * 64) {
+        const int col = tile * TN + c;
+        if (col < n) {
+            float sum = 0.f;
+#pragma unroll
+            for (int ww = 0; ww < WAVES; ++ww) sum += red[ww * TN + c];
+            out[col] = F::finish(sum, a, col);
+        }
+    }
+}
+
+// Generic kernel for formats with no per-group state (bf16, int8).
+template <class F, int LPR, int WAVES, int U>
+__global__ __launch_bounds__(WAVES * 64) void sparse_gemv_kernel(
+    typename F::Args a, const __half *__restrict__ x, float t, float *__restrict__ out, int m,
+    int n, int ks, int tiles)
+{
+    constexpr int EPL = F::kElemsPerLane;
+    constexpr int TN = LPR * EPL;
+    extern __shared__ __align__(16) unsigned char smem[];
+    int2 *list = reinterpret_cast<int2 *>(smem);
+    float *red = reinterpret_cast<float *>(smem + (size_t)ks * sizeof(int2));
+    __shared__ int seg_prefix[kMaxSegs + 1];
+
+    const int tile = blockIdx.x % tiles;
+    const int s = blockIdx.x / tiles;
+    const int k0 = s * ks;
+    const int k1 = min(m, k0 + ks);
+    const int cnt = __builtin_amdgcn_readfirstlane(compact_slice<WAVES>(x, t, k0, k1, list, seg_prefix));
+
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    int start, mine;
+    wave_share(cnt, w, WAVES, start, mine);
+
+    // Lanes past a ragged right edge re-read the last valid vector; their sums are not written.
+    int col = tile * TN + (lane % LPR) * EPL;
+    if (col > n - EPL) col = n - EPL;
+    const size_t row_bytes = (size_t)n * F::kBitsPerElem / 8;
+    const unsigned lane_off = (unsigned)((size_t)col * F::kBitsPerElem / 8);
+
+    float acc[EPL];
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
+    stream_rows<F, LPR, U>(acc, list, start, mine, static_cast<const unsigned char *>(a.W),
+                           row_bytes, lane_off);
+    fold_row_groups<LPR>(acc);
+    block_combine<F, LPR, WAVES>(acc, red, out + (size_t)s * n, tile, n, a);
+}
+
+// Host-side launch geometry shared by the formats.
+struct GemvGeometry {
+    int tiles;      // blocks along the output dimension
+    int ks;         // input channels per block
+    int splits;     // blocks along the input dimension (may be below the request)
+    size_t lds;     // dynamic LDS bytes
+};
+
+inline GemvGeometry gemv_geometry(int m, int n, const GemvShape &sh, int elems_per_lane,
+                                  int ks_multiple)
+{
+    GemvGeometry g;
+    const int tn = sh.lanes_per_row * elems_per_lane;
+    g.tiles = (n + tn - 1) / tn;
+    int splits = sh.splits < 1 ? 1 : sh.splits;
+    int ks = (m + splits - 1) / splits;
+    ks = (ks + ks_multiple - 1) / ks_multiple * ks_multiple;
+    if (ks > kMaxSlice) ks = kMaxSlice;
+    g.ks = ks;
+    g.splits = (m + ks - 1) / ks;
+    g.lds = (size_t)ks * sizeof(int2) + (size_t)sh.waves * tn * sizeof(float);
+    return g;
+}
+
+}  // namespace teal

@@ -1,0 +1,162 @@
+// y = s_t(x) W^T for weight-quantised W (Section 5.3 names the formats; a kernel
+// that is both sparse and quantised is what that section leaves open).
+//   int8: W[j][i] = q[i][j] * scale[j]            (channel-wise)
+//   int4: W[j][i] = nibble(i, j) * scale[i/128][j] (groups of 128 input channels)
+// Dequantisation happens in registers; only surviving rows are read.
+#include "gemv_common.h"
+#include "gemv_dispatch.h"
+
+namespace teal {
+
+struct FmtW8 {
+    static constexpr int kElemsPerLane = 16;   // 16 bytes = 16 int8
+    static constexpr int kBitsPerElem = 8;
+    struct Args {
+        const void *W;
+        const __half *scale;
+    };
+    static __device__ __forceinline__ void fma(float (&acc)[16], u32x4 v, float xv)
+    {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const int wq = (int)(v[q] << (24 - 8 * b)) >> 24;   // sign-extend byte b
+                acc[4 * q + b] = fmaf(xv, (float)wq, acc[4 * q + b]);
+            }
+        }
+    }
+    // The per-output-channel scale factors out of the sum over input channels.
+    static __device__ __forceinline__ float finish(float sum, const Args &a, int col)
+    {
+        return sum * __half2float(a.scale[col]);
+    }
+};
+
+struct FmtW4 {
+    static constexpr int kElemsPerLane = 32;   // 16 bytes = 32 nibbles
+    static constexpr int kBitsPerElem = 4;
+    struct Args {
+        const void *W;
+        const __half *scale;
+    };
+    static __device__ __forceinline__ void fma(float (&acc)[32], u32x4 v, float xv)
+    {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int wq = (int)(v[q] << (28 - 4 * k)) >> 28;   // sign-extend nibble k
+                acc[8 * q + k] = fmaf(xv, (float)wq, acc[8 * q + k]);
+            }
+        }
+    }
+    static __device__ __forceinline__ float finish(float sum, const Args &, int) { return sum; }
+};
+
+constexpr int kGroup = 128;
+
+// int4: the compacted list is ascending, so each 128-channel group is a run
+// of it, delimited by the segment prefix (two 64-channel segments per group).
+// Per group the block's wavefronts split the run, accumulate sum_i x_i q[i][j]
+// unscaled, then fold it into the running sums with that group's scales.
+template <int LPR, int WAVES, int U>
+__global__ __launch_bounds__(WAVES * 64) void sparse_gemv_w4_kernel(
+    FmtW4::Args a, const __half *__restrict__ x, float t, float *__restrict__ out, int m, int n,
+    int ks, int tiles)
+{
+    using F = FmtW4;
+    constexpr int EPL = F::kElemsPerLane;
+    constexpr int TN = LPR * EPL;
+    extern __shared__ __align__(16) unsigned char smem[];
+    int2 *list = reinterpret_cast<int2 *>(smem);
+    float *red = reinterpret_cast<float *>(smem + (size_t)ks * sizeof(int2));
+    __shared__ int seg_prefix[kMaxSegs + 1];
+
+    const int tile = blockIdx.x % tiles;
+    const int s = blockIdx.x / tiles;
+    const int k0 = s * ks;                       // multiple of 128
+    const int k1 = min(m, k0 + ks);
+    compact_slice<WAVES>(x, t, k0, k1, list, seg_prefix);
+
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    int col = tile * TN + (lane % LPR) * EPL;
+    if (col > n - EPL) col = n - EPL;
+    const size_t row_bytes = (size_t)n / 2;
+    const unsigned lane_off = (unsigned)(col / 2);
+
+    float acc[EPL];
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
+
+    const int ngroups = (k1 - k0) / kGroup;
+    for (int gi = 0; gi < ngroups; ++gi) {
+        const int g0 = __builtin_amdgcn_readfirstlane(seg_prefix[2 * gi]);
+        const int g1 = __builtin_amdgcn_readfirstlane(seg_prefix[2 * gi + 2]);
+        int start, mine;
+        wave_share(g1 - g0, w, WAVES, start, mine);
+        if (mine <= 0) continue;
+        float gacc[EPL];
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) gacc[e] = 0.f;
+        stream_rows<F, LPR, U>(gacc, list, g0 + start, mine,
+                               static_cast<const unsigned char *>(a.W), row_bytes, lane_off);
+        const uint4 *sp = reinterpret_cast<const uint4 *>(
+            a.scale + (size_t)(k0 / kGroup + gi) * n + col);
+#pragma unroll
+        for (int q = 0; q < EPL / 8; ++q) {
+            const uint4 sv = sp[q];
+            const unsigned sw[4] = {sv.x, sv.y, sv.z, sv.w};
+#pragma unroll
+            for (int h = 0; h < 4; ++h) {
+                const float s0 = __half2float(__ushort_as_half((unsigned short)(sw[h] & 0xffffu)));
+                const float s1 = __half2float(__ushort_as_half((unsigned short)(sw[h] >> 16)));
+                acc[8 * q + 2 * h] = fmaf(s0, gacc[8 * q + 2 * h], acc[8 * q + 2 * h]);
+                acc[8 * q + 2 * h + 1] = fmaf(s1, gacc[8 * q + 2 * h + 1], acc[8 * q + 2 * h + 1]);
+            }
+        }
+    }
+    fold_row_groups<LPR>(acc);
+    block_combine<F, LPR, WAVES>(acc, red, out + (size_t)s * n, tile, n, a);
+}
+
+hipError_t launch_gemv_w8(const int8_t *Wq, const void *scale_f16, const void *x_f16, float t,
+                          float *y, int m, int n, float *partial, const GemvShape &sh,
+                          hipStream_t stream)
+{
+    const GemvGeometry g = gemv_geometry(m, n, sh, FmtW8::kElemsPerLane, 64);
+    float *out = g.splits == 1 ? y : partial;
+    FmtW8::Args a{Wq, static_cast<const __half *>(scale_f16)};
+    const __half *x = static_cast<const __half *>(x_f16);
+#define TEAL_LAUNCH(F, LPR, WAVES, U)                                                        \
+    hipLaunchKernelGGL((sparse_gemv_kernel<F, LPR, WAVES, U>), dim3(g.tiles * g.splits),     \
+                       dim3(WAVES * 64), g.lds, stream, a, x, t, out, m, n, g.ks, g.tiles)
+    TEAL_DISPATCH(TEAL_LAUNCH, FmtW8, sh);
+#undef TEAL_LAUNCH
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || g.splits == 1) return e;
+    return launch_reduce_partials(partial, y, n, g.splits, stream);
+}
+
+hipError_t launch_gemv_w4(const uint8_t *Wq, const void *scale_f16, const void *x_f16, float t,
+                          float *y, int m, int n, float *partial, const GemvShape &sh,
+                          hipStream_t stream)
+{
+    const GemvGeometry g = gemv_geometry(m, n, sh, FmtW4::kElemsPerLane, kGroup);
+    float *out = g.splits == 1 ? y : partial;
+    FmtW4::Args a{Wq, static_cast<const __half *>(scale_f16)};
+    const __half *x = static_cast<const __half *>(x_f16);
+#define TEAL_LAUNCH(F, LPR, WAVES, U)                                                        \
+    hipLaunchKernelGGL((sparse_gemv_w4_kernel<LPR, WAVES, U>), dim3(g.tiles * g.splits),     \
+                       dim3(WAVES * 64), g.lds, stream, a, x, t, out, m, n, g.ks, g.tiles)
+    // 64 lanes per row would be a 2048-column tile: not offered for int4.
+    if (sh.lanes_per_row == 32) TEAL_DISPATCH_WU(TEAL_LAUNCH, FmtW4, 32, sh);
+    else TEAL_DISPATCH_WU(TEAL_LAUNCH, FmtW4, 16, sh);
+#undef TEAL_LAUNCH
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || g.splits == 1) return e;
+    return launch_reduce_partials(partial, y, n, g.splits, stream);
+}
+
+}  // namespace teal

@@ -1,0 +1,183 @@
+// C ABI of the library (include/teal.h): argument checks on the host, choice
+// of the launch shape, then the kernel launches.  Nothing here allocates,
+// synchronises or keeps state.
+#include "teal.h"
+
+#include <cmath>
+
+#include "teal_internal.h"
+
+namespace {
+
+using teal::GemvShape;
+
+constexpr size_t kAlignWorkspace = 256;
+constexpr int kComputeUnits = 256;
+
+bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+bool threshold_ok(float t) { return std::isfinite(t) && t >= 0.0f; }
+
+int max_splits_for(int m)
+{
+    const int forced = (m + teal::kMaxSlice - 1) / teal::kMaxSlice;   // LDS list capacity
+    return forced > teal::kMaxSplits ? forced : teal::kMaxSplits;
+}
+
+// Split-K depth (Section 4.4) such that the grid covers the chip several times over
+// while each block still has a few rows per wavefront to stream.
+GemvShape auto_shape(int m, int n, int elems_per_lane, int lanes_per_row)
+{
+    GemvShape s;
+    s.lanes_per_row = lanes_per_row;
+    s.waves = 4;
+    s.unroll = 8;
+    const int tn = lanes_per_row * elems_per_lane;
+    const int tiles = (n + tn - 1) / tn;
+    const int want_blocks = kComputeUnits * 8;
+    int splits = (want_blocks + tiles - 1) / tiles;
+    const int max_by_rows = (m + 63) / 64;            // at least 64 channels per block
+    if (splits > max_by_rows) splits = max_by_rows;
+    if (splits > teal::kMaxSplits) splits = teal::kMaxSplits;
+    if (splits < 1) splits = 1;
+    s.splits = splits;
+    return s;
+}
+
+struct GemvArgs {
+    const void *W;
+    const void *x;
+    float t;
+    float *y;
+    int m, n;
+    void *workspace;
+    size_t workspace_bytes;
+};
+
+teal_status check_gemv(const GemvArgs &a, int n_multiple)
+{
+    if (!a.W || !a.x || !a.y || !a.workspace) return TEAL_ERR_NULL;
+    if (a.m < 1 || a.m > teal::kMaxDim || a.n < n_multiple || a.n > teal::kMaxDim ||
+        a.n % n_multiple != 0)
+        return TEAL_ERR_SHAPE;
+    if (!aligned(a.W, 16) || !aligned(a.x, 2) || !aligned(a.y, 4) ||
+        !aligned(a.workspace, kAlignWorkspace))
+        return TEAL_ERR_ALIGN;
+    if (!threshold_ok(a.t)) return TEAL_ERR_THRESHOLD;
+    if (a.workspace_bytes < teal_workspace_bytes(a.m, a.n)) return TEAL_ERR_WORKSPACE;
+    return TEAL_OK;
+}
+
+teal_status from_hip(hipError_t e) { return e == hipSuccess ? TEAL_OK : TEAL_ERR_HIP; }
+
+}  // namespace
+
+extern "C" {
+
+const char *teal_status_string(teal_status s)
+{
+    switch (s) {
+    case TEAL_OK: return "ok";
+    case TEAL_ERR_NULL: return "a required pointer is NULL";
+    case TEAL_ERR_SHAPE: return "dimension out of range or not a multiple of the vector width";
+    case TEAL_ERR_ALIGN: return "pointer not aligned as required";
+    case TEAL_ERR_THRESHOLD: return "threshold must be finite and non-negative";
+    case TEAL_ERR_WORKSPACE: return "workspace too small";
+    case TEAL_ERR_UNSUPPORTED: return "unsupported group size or launch shape";
+    case TEAL_ERR_HIP: return "HIP runtime error at launch";
+    }
+    return "unknown status";
+}
+
+int teal_version(void) { return 100; }
+
+size_t teal_workspace_bytes(int m, int n)
+{
+    if (m < 1 || m > teal::kMaxDim || n < 1 || n > teal::kMaxDim) return 0;
+    const size_t rows = (size_t)max_splits_for(m);
+    const size_t bytes = rows * (size_t)n * sizeof(float);
+    return (bytes + kAlignWorkspace - 1) / kAlignWorkspace * kAlignWorkspace;
+}
+
+teal_status teal_sparsify(const void *x_f16, int m, float t, uint8_t *mask, int32_t *idx,
+                          int32_t *count, void *stream)
+{
+    if (m < 0) return TEAL_ERR_SHAPE;
+    if (!x_f16 && m > 0) return TEAL_ERR_NULL;
+    if (!aligned(x_f16, 2) || !aligned(idx, 4) || !aligned(count, 4)) return TEAL_ERR_ALIGN;
+    if (!threshold_ok(t)) return TEAL_ERR_THRESHOLD;
+    if (!mask && !idx && !count) return TEAL_OK;
+    return from_hip(teal::launch_sparsify(x_f16, m, t, mask, idx, count,
+                                          static_cast<hipStream_t>(stream)));
+}
+
+teal_status teal_sparse_gemv_bf16_ex(const void *Wt_bf16, const void *x_f16, float t, float *y,
+                                     int m, int n, void *workspace, size_t workspace_bytes,
+                                     void *stream, int lanes_per_row, int splits, int waves,
+                                     int unroll)
+{
+    const GemvArgs a{Wt_bf16, x_f16, t, y, m, n, workspace, workspace_bytes};
+    const teal_status st = check_gemv(a, 8);
+    if (st != TEAL_OK) return st;
+    GemvShape sh = auto_shape(m, n, 8, lanes_per_row ? lanes_per_row : 64);
+    if (splits) sh.splits = splits;
+    if (waves) sh.waves = waves;
+    if (unroll) sh.unroll = unroll;
+    if (!teal::gemv_shape_supported(sh)) return TEAL_ERR_UNSUPPORTED;
+    return from_hip(teal::launch_gemv_bf16(Wt_bf16, x_f16, t, y, m, n,
+                                           static_cast<float *>(workspace), sh,
+                                           static_cast<hipStream_t>(stream)));
+}
+
+teal_status teal_sparse_gemv_bf16(const void *Wt_bf16, const void *x_f16, float t, float *y,
+                                  int m, int n, void *workspace, size_t workspace_bytes,
+                                  void *stream)
+{
+    return teal_sparse_gemv_bf16_ex(Wt_bf16, x_f16, t, y, m, n, workspace, workspace_bytes,
+                                    stream, 0, 0, 0, 0);
+}
+
+teal_status teal_sparse_gemv_w8(const int8_t *Wq, const void *scale_f16, const void *x_f16,
+                                float t, float *y, int m, int n, void *workspace,
+                                size_t workspace_bytes, void *stream)
+{
+    const GemvArgs a{Wq, x_f16, t, y, m, n, workspace, workspace_bytes};
+    if (!scale_f16) return TEAL_ERR_NULL;
+    const teal_status st = check_gemv(a, 16);
+    if (st != TEAL_OK) return st;
+    if (!aligned(scale_f16, 2)) return TEAL_ERR_ALIGN;
+    const GemvShape sh = auto_shape(m, n, 16, 32);
+    return from_hip(teal::launch_gemv_w8(Wq, scale_f16, x_f16, t, y, m, n,
+                                         static_cast<float *>(workspace), sh,
+                                         static_cast<hipStream_t>(stream)));
+}
+
+teal_status teal_sparse_gemv_w4(const uint8_t *Wq, const void *scale_f16, int group,
+                                const void *x_f16, float t, float *y, int m, int n,
+                                void *workspace, size_t workspace_bytes, void *stream)
+{
+    const GemvArgs a{Wq, x_f16, t, y, m, n, workspace, workspace_bytes};
+    if (!scale_f16) return TEAL_ERR_NULL;
+    const teal_status st = check_gemv(a, 32);
+    if (st != TEAL_OK) return st;
+    if (!aligned(scale_f16, 16)) return TEAL_ERR_ALIGN;
+    if (group != 128 || m % 128 != 0) return TEAL_ERR_UNSUPPORTED;
+    GemvShape sh = auto_shape(m, n, 32, 16);
+    const int max_by_groups = m / 128;
+    if (sh.splits > max_by_groups) sh.splits = max_by_groups;
+    return from_hip(teal::launch_gemv_w4(Wq, scale_f16, x_f16, t, y, m, n,
+                                         static_cast<float *>(workspace), sh,
+                                         static_cast<hipStream_t>(stream)));
+}
+
+teal_status teal_pack_bf16(const void *W_rowmajor, void *Wt, int m, int n, void *stream)
+{
+    if (!W_rowmajor || !Wt) return TEAL_ERR_NULL;
+    if (m < 1 || n < 1 || m > teal::kMaxDim || n > teal::kMaxDim ||
+        (long long)m * (long long)n > (1LL << 40))
+        return TEAL_ERR_SHAPE;
+    if (!aligned(W_rowmajor, 2) || !aligned(Wt, 2)) return TEAL_ERR_ALIGN;
+    return from_hip(teal::launch_pack_bf16(W_rowmajor, Wt, m, n, static_cast<hipStream_t>(stream)));
+}
+
+}  // extern "C"

@@ -1,0 +1,47 @@
+// Internal interface between the C-ABI layer (teal_api.cpp: argument checks,
+// launch-shape choice) and the gfx950 kernels (*.hip).  Not installed.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace teal {
+
+constexpr int kMaxSplits = 128;     // upper bound on split-K blocks along the input dimension
+constexpr int kMaxSlice = 2048;     // most input channels one block compacts (LDS list capacity)
+constexpr int kMaxDim = 1 << 24;    // largest m or n accepted
+
+// How one sparse GEMV is laid over the chip.
+struct GemvShape {
+    int lanes_per_row;   // 64, 32 or 16 lanes read one weight row per load (16 bytes each)
+    int splits;          // blocks along the input dimension
+    int waves;           // wavefronts per block (4 or 8)
+    int unroll;          // row loads in flight per wavefront (4 or 8)
+};
+
+bool gemv_shape_supported(const GemvShape &s);
+
+// Each returns the HIP status of its launches; all are asynchronous on `stream`.
+hipError_t launch_sparsify(const void *x_f16, int m, float t, uint8_t *mask,
+                           int32_t *idx, int32_t *count, hipStream_t stream);
+
+hipError_t launch_gemv_bf16(const void *Wt, const void *x_f16, float t, float *y,
+                            int m, int n, float *partial, const GemvShape &shape,
+                            hipStream_t stream);
+
+hipError_t launch_gemv_w8(const int8_t *Wq, const void *scale_f16, const void *x_f16,
+                          float t, float *y, int m, int n, float *partial,
+                          const GemvShape &shape, hipStream_t stream);
+
+hipError_t launch_gemv_w4(const uint8_t *Wq, const void *scale_f16, const void *x_f16,
+                          float t, float *y, int m, int n, float *partial,
+                          const GemvShape &shape, hipStream_t stream);
+
+hipError_t launch_reduce_partials(const float *partial, float *y, int n, int splits,
+                                  hipStream_t stream);
+
+hipError_t launch_pack_bf16(const void *W_rowmajor, void *Wt, int m, int n,
+                            hipStream_t stream);
+
+}  // namespace teal

@@ -1,0 +1,135 @@
+"""The C-ABI boundary without a GPU: the library loads, exports what
+include/teal.h declares, and rejects bad arguments on the host before any GPU
+work (so these calls are safe on a machine with no device)."""
+import ctypes
+import math
+import os
+import re
+
+import pytest
+
+import paper_2408_14690_amd as T
+from paper_2408_14690_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+# fake, suitably aligned device addresses: never dereferenced by the checks
+W, X, Y, WS, SC = 0x10000, 0x20000, 0x30000, 0x40000, 0x50000
+BIG = 1 << 40
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _built():
+    if not os.path.exists(T.library_path()):
+        from paper_2408_14690_amd import build
+        build.build(verbose=False)
+    T.load_library()
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "teal.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(teal_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = _declared_functions()
+    assert set(names) == set(binding.EXPORTS)
+    lib = ctypes.CDLL(T.library_path())
+    for name in names:
+        assert getattr(lib, name) is not None
+    # and the Python binding offers the same names
+    for name in names:
+        assert callable(getattr(T, name))
+
+
+def test_version_and_status_strings():
+    assert T.teal_version() >= 100
+    seen = set()
+    for code in range(8):
+        s = T.teal_status_string(code)
+        assert s and s not in seen
+        seen.add(s)
+    assert T.teal_status_string(0) == "ok"
+
+
+def test_workspace_bytes():
+    assert T.teal_workspace_bytes(0, 8) == 0 and T.teal_workspace_bytes(8, 0) == 0
+    assert T.teal_workspace_bytes(4096, 4096) == 128 * 4096 * 4
+    assert T.teal_workspace_bytes(4096, 14336) % 256 == 0
+    # very long inputs force more than 128 splits (one block compacts at most 2048 channels)
+    assert T.teal_workspace_bytes(1 << 20, 8) >= (1 << 20) // 2048 * 8 * 4
+    assert T.teal_workspace_bytes((1 << 24) + 1, 8) == 0
+
+
+def test_gemv_bf16_argument_errors():
+    ok_args = dict(Wt_bf16=W, x_f16=X, t=0.5, y=Y, m=4096, n=4096, workspace=WS,
+                   workspace_bytes=BIG, stream=0)
+
+    def call(**kw):
+        a = dict(ok_args)
+        a.update(kw)
+        return T.teal_sparse_gemv_bf16(**a)
+
+    assert call(Wt_bf16=None) == T.TEAL_ERR_NULL
+    assert call(x_f16=None) == T.TEAL_ERR_NULL
+    assert call(y=None) == T.TEAL_ERR_NULL
+    assert call(workspace=None) == T.TEAL_ERR_NULL
+    assert call(m=0) == T.TEAL_ERR_SHAPE
+    assert call(n=0) == T.TEAL_ERR_SHAPE
+    assert call(n=4100) == T.TEAL_ERR_SHAPE           # not a multiple of 8
+    assert call(m=(1 << 24) + 1) == T.TEAL_ERR_SHAPE
+    assert call(Wt_bf16=W + 8) == T.TEAL_ERR_ALIGN
+    assert call(x_f16=X + 1) == T.TEAL_ERR_ALIGN
+    assert call(y=Y + 2) == T.TEAL_ERR_ALIGN
+    assert call(workspace=WS + 128) == T.TEAL_ERR_ALIGN
+    assert call(t=-0.25) == T.TEAL_ERR_THRESHOLD
+    assert call(t=math.nan) == T.TEAL_ERR_THRESHOLD
+    assert call(t=math.inf) == T.TEAL_ERR_THRESHOLD
+    assert call(workspace_bytes=T.teal_workspace_bytes(4096, 4096) - 1) == T.TEAL_ERR_WORKSPACE
+
+
+def test_gemv_bf16_ex_rejects_unsupported_shapes():
+    base = (W, X, 0.5, Y, 4096, 4096, WS, BIG, 0)
+    assert T.teal_sparse_gemv_bf16_ex(*base, lanes_per_row=48) == T.TEAL_ERR_UNSUPPORTED
+    assert T.teal_sparse_gemv_bf16_ex(*base, splits=129) == T.TEAL_ERR_UNSUPPORTED
+    assert T.teal_sparse_gemv_bf16_ex(*base, splits=-1) == T.TEAL_ERR_UNSUPPORTED
+    assert T.teal_sparse_gemv_bf16_ex(*base, waves=3) == T.TEAL_ERR_UNSUPPORTED
+    assert T.teal_sparse_gemv_bf16_ex(*base, unroll=5) == T.TEAL_ERR_UNSUPPORTED
+    # argument errors win over shape errors
+    assert T.teal_sparse_gemv_bf16_ex(None, X, 0.5, Y, 4096, 4096, WS, BIG, 0,
+                                      lanes_per_row=48) == T.TEAL_ERR_NULL
+
+
+def test_quantised_argument_errors():
+    assert T.teal_sparse_gemv_w8(W, None, X, 0.5, Y, 4096, 4096, WS, BIG, 0) == T.TEAL_ERR_NULL
+    assert T.teal_sparse_gemv_w8(W, SC, X, 0.5, Y, 4096, 4104, WS, BIG, 0) == T.TEAL_ERR_SHAPE
+    assert T.teal_sparse_gemv_w8(W, SC + 1, X, 0.5, Y, 4096, 4096, WS, BIG, 0) == T.TEAL_ERR_ALIGN
+    assert T.teal_sparse_gemv_w8(W, SC, X, -1.0, Y, 4096, 4096, WS, BIG, 0) == T.TEAL_ERR_THRESHOLD
+    assert T.teal_sparse_gemv_w4(W, None, 128, X, 0.5, Y, 4096, 4096, WS, BIG, 0) == T.TEAL_ERR_NULL
+    assert T.teal_sparse_gemv_w4(W, SC, 128, X, 0.5, Y, 4096, 4112, WS, BIG, 0) == T.TEAL_ERR_SHAPE
+    assert T.teal_sparse_gemv_w4(W, SC, 64, X, 0.5, Y, 4096, 4096, WS, BIG, 0) == T.TEAL_ERR_UNSUPPORTED
+    assert T.teal_sparse_gemv_w4(W, SC, 128, X, 0.5, Y, 4160, 4096, WS, BIG, 0) == T.TEAL_ERR_UNSUPPORTED
+    assert T.teal_sparse_gemv_w4(W, SC + 8, 128, X, 0.5, Y, 4096, 4096, WS, BIG, 0) == T.TEAL_ERR_ALIGN
+    assert T.teal_sparse_gemv_w4(W, SC, 128, X, 0.5, Y, 4096, 4096, WS, 16, 0) == T.TEAL_ERR_WORKSPACE
+
+
+def test_sparsify_and_pack_argument_errors():
+    assert T.teal_sparsify(None, 16, 0.5, Y, None, None, stream=0) == T.TEAL_ERR_NULL
+    assert T.teal_sparsify(X, -1, 0.5, Y, None, None, stream=0) == T.TEAL_ERR_SHAPE
+    assert T.teal_sparsify(X + 1, 16, 0.5, Y, None, None, stream=0) == T.TEAL_ERR_ALIGN
+    assert T.teal_sparsify(X, 16, 0.5, None, Y + 2, None, stream=0) == T.TEAL_ERR_ALIGN
+    assert T.teal_sparsify(X, 16, -0.5, Y, None, None, stream=0) == T.TEAL_ERR_THRESHOLD
+    # nothing requested: accepted, nothing launched
+    assert T.teal_sparsify(X, 16, 0.5, None, None, None, stream=0) == T.TEAL_OK
+    assert T.teal_pack_bf16(None, Y, 8, 8, stream=0) == T.TEAL_ERR_NULL
+    assert T.teal_pack_bf16(X, None, 8, 8, stream=0) == T.TEAL_ERR_NULL
+    assert T.teal_pack_bf16(X, Y, 0, 8, stream=0) == T.TEAL_ERR_SHAPE
+    assert T.teal_pack_bf16(X + 1, Y, 8, 8, stream=0) == T.TEAL_ERR_ALIGN
+
+
+def test_check_raises_with_message():
+    with pytest.raises(T.TealError) as e:
+        T.check(T.TEAL_ERR_WORKSPACE)
+    assert "workspace" in str(e.value) and e.value.status == T.TEAL_ERR_WORKSPACE
+    T.check(T.TEAL_OK)

@@ -1,0 +1,310 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle
+on the same seeded inputs.  Masks, index lists and counts must be bit-exact;
+y must agree to relative L2 <= 2e-3 (bf16 W) / 5e-3 (quantised W)."""
+import numpy as np
+import pytest
+
+import teal_inputs as ti
+from oracle import teal_oracle as orc
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+TOL_BF16 = 2e-3
+TOL_WQ = 5e-3
+# What fp32 accumulation of exact products should achieve; looser bars above are
+# the contract, this one catches a wrong-but-close kernel (e.g. a dropped row).
+TIGHT = 2e-5
+
+
+@pytest.fixture(scope="module")
+def T():
+    import paper_2408_14690_amd as T
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    T.load_library()          # raises if the HIP library is not built: no fallback
+    return T
+
+
+def dev(a: np.ndarray):
+    """numpy -> device tensor of the same bytes (16-bit types travel as int16)."""
+    a = np.ascontiguousarray(a)
+    if a.dtype in (np.uint16, np.float16):
+        return torch.from_numpy(a.view(np.int16)).cuda()
+    return torch.from_numpy(a).cuda()
+
+
+def rel_l2(got, want):
+    den = np.linalg.norm(want)
+    if den == 0.0:
+        return 0.0 if not np.any(got) else np.inf
+    return float(np.linalg.norm(got.astype(np.float64) - want) / den)
+
+
+def workspace(T, m, n):
+    return torch.empty(T.teal_workspace_bytes(m, n), dtype=torch.uint8, device="cuda")
+
+
+def run_bf16(T, wt_dev, x_dev, t, m, n, ws, **shape):
+    # poison y: the call must overwrite every element
+    y = torch.full((n,), float("nan"), dtype=torch.float32, device="cuda")
+    if shape:
+        T.check(T.teal_sparse_gemv_bf16_ex(wt_dev, x_dev, t, y, m, n, ws, **shape))
+    else:
+        T.check(T.teal_sparse_gemv_bf16(wt_dev, x_dev, t, y, m, n, ws))
+    torch.cuda.synchronize()
+    return y.cpu().numpy()
+
+
+# ---------------------------------------------------------------------------
+# teal_sparsify
+# ---------------------------------------------------------------------------
+
+def gpu_sparsify(T, x, t):
+    m = x.size
+    xd = dev(x) if m else torch.empty(1, dtype=torch.int16, device="cuda")
+    mask = torch.full((max(m, 1),), 7, dtype=torch.uint8, device="cuda")
+    idx = torch.full((max(m, 1),), -1, dtype=torch.int32, device="cuda")
+    count = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+    T.check(T.teal_sparsify(xd, m, t, mask, idx, count))
+    torch.cuda.synchronize()
+    c = int(count.item())
+    return mask.cpu().numpy()[:m], idx.cpu().numpy(), c
+
+
+@pytest.mark.parametrize("m", [1, 63, 64, 65, 1000, 1024, 1025, 4096, 11008, 14336, 28672])
+@pytest.mark.parametrize("dist", ["gaussian", "laplace"])
+def test_sparsify_bit_exact(T, m, dist):
+    x = ti.make_x(m, 7000 + m, dist)
+    for p in (0.0, 0.25, 0.4, 0.5, 0.65, 0.9, 1.0):
+        t = ti.quantile_threshold(x, p)
+        _, mask_o, idx_o, count_o = orc.sparsify(x, t)
+        mask, idx, count = gpu_sparsify(T, x, t)
+        assert count == count_o
+        assert np.array_equal(mask, mask_o)
+        assert np.array_equal(idx[:count], idx_o)
+        assert np.all(idx[count:] == -1)              # capacity beyond count untouched
+
+
+def test_sparsify_ties_special_values_and_empty(T):
+    x = np.array([1.0, -1.0, 1.0009765625, 0.0, -0.0, np.nan, np.inf, -np.inf, 6e-8, -65504.0] * 13,
+                 dtype=np.float16)
+    for t in (0.0, 1.0, 6e-8, 65504.0):
+        t = float(np.float32(t))
+        _, mask_o, idx_o, count_o = orc.sparsify(x, t)
+        mask, idx, count = gpu_sparsify(T, x, t)
+        assert count == count_o and np.array_equal(mask, mask_o)
+        assert np.array_equal(idx[:count], idx_o)
+    mask, idx, count = gpu_sparsify(T, np.zeros(0, np.float16), 0.5)
+    assert count == 0 and mask.size == 0
+    # outputs are optional
+    xd = dev(x)
+    count_only = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+    T.check(T.teal_sparsify(xd, x.size, 1.0, None, None, count_only))
+    torch.cuda.synchronize()
+    assert int(count_only.item()) == orc.sparsify(x, 1.0)[3]
+
+
+# ---------------------------------------------------------------------------
+# teal_pack_bf16
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("n,m", [(1, 1), (8, 5), (64, 64), (65, 63), (200, 333), (1024, 4096)])
+def test_pack_is_the_transpose(T, n, m):
+    w = ti.weights_bf16(n, m, seed=n * 31 + m)
+    wd = dev(w)
+    wt = torch.zeros((m, n), dtype=torch.int16, device="cuda")
+    T.check(T.teal_pack_bf16(wd, wt, m, n))
+    torch.cuda.synchronize()
+    assert np.array_equal(wt.cpu().numpy().view(np.uint16), ti.to_input_channel_major(w))
+
+
+# ---------------------------------------------------------------------------
+# teal_sparse_gemv_bf16: small and ragged shapes, every kernel variant
+# ---------------------------------------------------------------------------
+
+SMALL = [(8, 1), (8, 64), (24, 40), (136, 65), (520, 333), (1032, 2049), (2056, 4100), (4096, 4096)]
+
+
+@pytest.mark.parametrize("n,m", SMALL)
+def test_gemv_bf16_small_shapes_default_launch(T, n, m):
+    w = ti.weights_bf16(n, m, seed=11 * n + m)
+    wt = dev(ti.to_input_channel_major(w))
+    ws = workspace(T, m, n)
+    for dist in ("gaussian", "laplace"):
+        x = ti.make_x(m, 77 + m, dist)
+        xd = dev(x)
+        for p in (0.0, 0.4, 0.5, 0.9):
+            t = ti.quantile_threshold(x, p)
+            want = orc.sparse_gemv_bf16(w, x, t)
+            got = run_bf16(T, wt, xd, t, m, n, ws)
+            assert rel_l2(got, want) <= TIGHT, (n, m, dist, p)
+            assert rel_l2(got, want) <= TOL_BF16
+
+
+@pytest.mark.parametrize("lanes", [64, 32, 16])
+@pytest.mark.parametrize("waves", [4, 8])
+@pytest.mark.parametrize("unroll", [4, 8])
+def test_gemv_bf16_every_variant(T, lanes, waves, unroll):
+    for (n, m) in [(520, 333), (1032, 2049), (4096, 4096)]:
+        w = ti.weights_bf16(n, m, seed=3 * n + m)
+        wt = dev(ti.to_input_channel_major(w))
+        x = ti.laplace_x(m, 5 + m)
+        xd = dev(x)
+        ws = workspace(T, m, n)
+        for p in (0.0, 0.5):
+            t = ti.quantile_threshold(x, p)
+            want = orc.sparse_gemv_bf16(w, x, t)
+            for splits in (1, 3, 16, 128):
+                got = run_bf16(T, wt, xd, t, m, n, ws, lanes_per_row=lanes, splits=splits,
+                               waves=waves, unroll=unroll)
+                assert rel_l2(got, want) <= TIGHT, (n, m, p, lanes, waves, unroll, splits)
+
+
+def test_gemv_bf16_degenerate_sparsity(T):
+    n, m = 1032, 2049
+    w = ti.weights_bf16(n, m, seed=9)
+    wt = dev(ti.to_input_channel_major(w))
+    x = ti.gaussian_x(m, 10)
+    xd = dev(x)
+    ws = workspace(T, m, n)
+    tmax = float(np.abs(x.astype(np.float32)).max())
+    got = run_bf16(T, wt, xd, tmax, m, n, ws)          # nothing survives
+    assert np.all(got == 0.0) and not np.any(np.signbit(got))
+    # exactly one survivor: y is that one weight row times x_i, exactly
+    second = float(np.sort(np.abs(x.astype(np.float32)))[-2])
+    got = run_bf16(T, wt, xd, second, m, n, ws)
+    want = orc.sparse_gemv_bf16(w, x, second)
+    assert np.array_equal(got.astype(np.float64), want)
+    # a state of zeros at t = 0: |0| > 0 is false, nothing is read
+    zd = dev(np.zeros(m, np.float16))
+    assert np.all(run_bf16(T, wt, zd, 0.0, m, n, ws) == 0.0)
+
+
+def test_gemv_bf16_ties_at_threshold_are_dropped(T):
+    n, m = 256, 512
+    w = ti.weights_bf16(n, m, seed=21)
+    wt = dev(ti.to_input_channel_major(w))
+    x = (np.arange(m) % 5 - 2).astype(np.float16)     # magnitudes 0, 1, 2 with many ties
+    ws = workspace(T, m, n)
+    for t in (0.0, 1.0, 2.0):
+        got = run_bf16(T, wt, dev(x), t, m, n, ws)
+        want = orc.sparse_gemv_bf16(w, x, t)
+        assert rel_l2(got, want) <= TIGHT
+
+
+def test_gemv_bf16_is_bitwise_reproducible(T):
+    n, m = 4096, 4096
+    w = ti.weights_bf16(n, m, seed=33)
+    wt = dev(ti.to_input_channel_major(w))
+    x = ti.gaussian_x(m, 34)
+    xd = dev(x)
+    t = ti.quantile_threshold(x, 0.5)
+    ws = workspace(T, m, n)
+    first = run_bf16(T, wt, xd, t, m, n, ws)
+    for _ in range(5):
+        ws.random_(0, 255)                            # workspace content must not matter
+        assert np.array_equal(run_bf16(T, wt, xd, t, m, n, ws), first)
+
+
+# ---------------------------------------------------------------------------
+# full-size projections in the launch configuration the benchmark times
+# ---------------------------------------------------------------------------
+
+FULL = [("llama2_7b", p) for p in ("q", "gate", "down")] + \
+       [("llama3_8b", p) for p in ("k", "up", "down")]
+
+
+@pytest.mark.parametrize("model,proj", FULL)
+def test_gemv_bf16_full_size(T, model, proj):
+    n, m = ti.LAYER_SHAPES[model][proj]
+    cfg = ti.CONFIG_INDEX[model]
+    w = ti.weights_bf16(n, m, ti.weight_seed(cfg, 0, proj))
+    x = ti.make_x(m, ti.x_seed(cfg, 0, proj), ti.PROJ_DIST[proj])
+    # upload canonical W and lay it out on the device, as the benchmark does
+    wd = dev(w)
+    wt = torch.empty((m, n), dtype=torch.int16, device="cuda")
+    T.check(T.teal_pack_bf16(wd, wt, m, n))
+    del wd
+    xd = dev(x)
+    ws = workspace(T, m, n)
+    for p in (0.0, 0.4, 0.5, 0.9):
+        t = ti.quantile_threshold(x, p)
+        want = orc.sparse_gemv_bf16(w, x, t)
+        got = run_bf16(T, wt, xd, t, m, n, ws)
+        assert rel_l2(got, want) <= TIGHT, (model, proj, p)
+        mask, idx, count = gpu_sparsify(T, x, t)
+        _, mask_o, idx_o, count_o = orc.sparsify(x, t)
+        assert count == count_o and np.array_equal(mask, mask_o)
+        assert np.array_equal(idx[:count], idx_o)
+
+
+def test_gemv_bf16_70b_shape_sampled_rows(T):
+    """28672 x 8192 (gate/up of the 70B-shaped block): sampled outputs one by one."""
+    n, m = ti.LAYER_SHAPES["llama_70b"]["gate"]
+    w = ti.weights_bf16(n, m, ti.weight_seed(4, 0, "gate"))
+    x = ti.gaussian_x(m, ti.x_seed(4, 0, "gate"))
+    wd = dev(w)
+    wt = torch.empty((m, n), dtype=torch.int16, device="cuda")
+    T.check(T.teal_pack_bf16(wd, wt, m, n))
+    del wd
+    ws = workspace(T, m, n)
+    t = ti.quantile_threshold(x, 0.5)
+    got = run_bf16(T, wt, dev(x), t, m, n, ws)
+    rows = np.unique(np.concatenate([np.arange(0, n, 97), [n - 1, n - 8, 511, 512]])).astype(np.int32)
+    want = orc.sparse_gemv_bf16_rows(w, x, t, rows)
+    assert rel_l2(got[rows], want) <= TIGHT
+    assert np.all(np.isfinite(got))
+
+
+# ---------------------------------------------------------------------------
+# weight-quantised variants
+# ---------------------------------------------------------------------------
+
+def run_w8(T, q_dev, s_dev, x_dev, t, m, n, ws):
+    y = torch.full((n,), float("nan"), dtype=torch.float32, device="cuda")
+    T.check(T.teal_sparse_gemv_w8(q_dev, s_dev, x_dev, t, y, m, n, ws))
+    torch.cuda.synchronize()
+    return y.cpu().numpy()
+
+
+def run_w4(T, q_dev, s_dev, x_dev, t, m, n, ws):
+    y = torch.full((n,), float("nan"), dtype=torch.float32, device="cuda")
+    T.check(T.teal_sparse_gemv_w4(q_dev, s_dev, 128, x_dev, t, y, m, n, ws))
+    torch.cuda.synchronize()
+    return y.cpu().numpy()
+
+
+@pytest.mark.parametrize("n,m", [(16, 1), (48, 100), (528, 333), (1040, 2049), (4096, 4096),
+                                 (1024, 4096), (14336, 4096), (4096, 14336)])
+def test_gemv_w8(T, n, m):
+    w = ti.weights_bf16(n, m, seed=7 * n + m)
+    q, scale = ti.quantize_w8(w)
+    qd, sd = dev(q), dev(scale)
+    ws = workspace(T, m, n)
+    dist = "laplace" if m > n else "gaussian"
+    x = ti.make_x(m, 13 + m, dist)
+    xd = dev(x)
+    for p in (0.0, 0.4, 0.5, 1.0):
+        t = ti.quantile_threshold(x, p)
+        want = orc.sparse_gemv_w8(q, scale, x, t)
+        got = run_w8(T, qd, sd, xd, t, m, n, ws)
+        assert rel_l2(got, want) <= TIGHT, (n, m, p)
+        assert rel_l2(got, want) <= TOL_WQ
+
+
+@pytest.mark.parametrize("n,m", [(32, 128), (96, 384), (544, 256), (1056, 2176), (4096, 4096),
+                                 (1024, 4096), (14336, 4096), (4096, 14336)])
+def test_gemv_w4(T, n, m):
+    w = ti.weights_bf16(n, m, seed=5 * n + m)
+    packed, scale = ti.quantize_w4(w, 128)
+    qd, sd = dev(packed), dev(scale)
+    ws = workspace(T, m, n)
+    dist = "laplace" if m > n else "gaussian"
+    x = ti.make_x(m, 17 + m, dist)
+    xd = dev(x)
+    for p in (0.0, 0.4, 0.5, 1.0):
+        t = ti.quantile_threshold(x, p)
+        want = orc.sparse_gemv_w4(packed, scale, 128, x, t)
+        got = run_w4(T, qd, sd, xd, t, m, n, ws)
+        assert rel_l2(got, want) <= TIGHT, (n, m, p)
+        assert rel_l2(got, want) <= TOL_WQ
