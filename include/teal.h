@@ -31,9 +31,11 @@
  *   - All argument checks happen on the host before any GPU work and return
  *     a status; nothing aborts, throws or prints.
  *   - `workspace` is caller-provided device scratch of at least
- *     teal_workspace_bytes(m, n) bytes, 256-byte aligned.  Calls that may run
- *     concurrently need distinct workspaces.  Contents need no
- *     initialisation and are undefined afterwards.
+ *     teal_workspace_bytes(m, n) bytes, 256-byte aligned.  It must be
+ *     zero-filled once before its first use (hipMemset, torch.zeros); every
+ *     call that returns TEAL_OK leaves it ready for the next call, of any
+ *     shape that fits.  Its contents are otherwise the library's.  Calls that
+ *     may run concurrently need distinct workspaces.
  *   - No global state; any host thread may call with any current device, as
  *     long as the pointers belong to it.
  */
@@ -84,7 +86,8 @@ teal_status teal_sparsify(const void *x_f16, int m, float t,
  * y = s_t(x) W^T (Section 4.2), computed as in Section 4.4: the mask is built
  * inside the kernel from x and t, only rows Wt[i][:] with |x_i| > t are read,
  * the input dimension is split across thread blocks, and the per-split
- * partial sums (fp32) are combined in a fixed order.
+ * partial sums (fp32) are combined in a fixed order by the block that
+ * finishes a tile last (one kernel launch per call).
  *   Wt_bf16 [m][n] bfloat16, input-channel-major, 16-byte aligned.
  *   x_f16   [m] fp16, 2-byte aligned.
  *   y       [n] fp32, 4-byte aligned.

@@ -22,26 +22,6 @@ struct FmtBF16 {
     static __device__ __forceinline__ float finish(float sum, const Args &, int) { return sum; }
 };
 
-// y[j] = sum over splits of partial[s][j], s ascending (second pass).
-__global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__restrict__ partial,
-                                                              float *__restrict__ y, int n,
-                                                              int splits)
-{
-    const int j = blockIdx.x * 256 + threadIdx.x;
-    if (j >= n) return;
-    float sum = 0.f;
-    int s = 0;
-    for (; s + 8 <= splits; s += 8) {
-        float p[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) p[u] = partial[(size_t)(s + u) * n + j];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) sum += p[u];
-    }
-    for (; s < splits; ++s) sum += partial[(size_t)s * n + j];
-    y[j] = sum;
-}
-
 bool gemv_shape_supported(const GemvShape &s)
 {
     const bool lpr = s.lanes_per_row == 64 || s.lanes_per_row == 32 || s.lanes_per_row == 16;
@@ -50,29 +30,20 @@ bool gemv_shape_supported(const GemvShape &s)
     return lpr && wv && un && s.splits >= 1 && s.splits <= kMaxSplits;
 }
 
-hipError_t launch_reduce_partials(const float *partial, float *y, int n, int splits,
-                                  hipStream_t stream)
-{
-    hipLaunchKernelGGL(reduce_partials_kernel, dim3((n + 255) / 256), dim3(256), 0, stream,
-                       partial, y, n, splits);
-    return hipGetLastError();
-}
-
 hipError_t launch_gemv_bf16(const void *Wt, const void *x_f16, float t, float *y, int m, int n,
-                            float *partial, const GemvShape &sh, hipStream_t stream)
+                            float *partial, int *counters, const GemvShape &sh,
+                            hipStream_t stream)
 {
     const GemvGeometry g = gemv_geometry(m, n, sh, FmtBF16::kElemsPerLane, 64);
-    float *out = g.splits == 1 ? y : partial;
     FmtBF16::Args a{Wt};
     const __half *x = static_cast<const __half *>(x_f16);
-#define TEAL_LAUNCH(F, LPR, WAVES, U)                                                        \
-    hipLaunchKernelGGL((sparse_gemv_kernel<F, LPR, WAVES, U>), dim3(g.tiles * g.splits),     \
-                       dim3(WAVES * 64), g.lds, stream, a, x, t, out, m, n, g.ks, g.tiles)
+#define TEAL_LAUNCH(F, LPR, WAVES, U)                                                          \
+    hipLaunchKernelGGL((sparse_gemv_kernel<F, LPR, WAVES, U>), dim3(g.tiles_padded * g.splits), \
+                       dim3(WAVES * 64), g.lds, stream, a, x, t, partial, counters, y, m, n,   \
+                       g.ks, g.tiles, g.tiles_padded, g.splits)
     TEAL_DISPATCH(TEAL_LAUNCH, FmtBF16, sh);
 #undef TEAL_LAUNCH
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess || g.splits == 1) return e;
-    return launch_reduce_partials(partial, y, n, g.splits, stream);
+    return hipGetLastError();
 }
 
 }  // namespace teal

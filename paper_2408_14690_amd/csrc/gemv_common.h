@@ -6,7 +6,8 @@
 // ballots and an LDS prefix sum, (2) streams only the surviving rows of the
 // input-channel-major weights with 16-byte non-temporal loads and fp32 FMAs,
 // (3) sums its wavefronts' accumulators through LDS and writes one fp32
-// partial row.  A second kernel adds the partial rows in a fixed order.
+// partial row; the last block to finish a tile adds that tile's partial rows
+// in split order and writes y (second pass, same launch).
 #pragma once
 
 #include <hip/hip_fp16.h>
@@ -26,6 +27,25 @@ constexpr int kMaxSegs = kMaxSlice / 64;   // 64-channel segments per slice
 __device__ __forceinline__ u32x4 load_stream16(const void *p)
 {
     return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+}
+
+// Device-scope coherent accesses for data that one block writes and a block on
+// another XCD reads within the same launch.
+__device__ __forceinline__ void store_coherent(float *p, float v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float load_coherent(const float *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// s_waitcnt vmcnt(0): every vector-memory operation this wavefront has issued
+// has completed (expcnt and lgkmcnt fields left at their maxima = no wait).
+__device__ __forceinline__ void wait_vector_memory()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0x0F70);
 }
 
 // Number of set bits of a wavefront ballot in lanes below the calling lane.
@@ -172,15 +192,21 @@ __device__ __forceinline__ void wave_share(int cnt, int w, int waves, int &start
     mine = per + (w < rem ? 1 : 0);
 }
 
-// Sums the wavefronts' accumulators through LDS and writes this block's row
-// of outputs: out[col] for the tile's valid columns.
+// Sums the wavefronts' accumulators through LDS.  With one split the sums are
+// the outputs.  Otherwise the block writes its fp32 partial row, and the block
+// that arrives last at the tile's counter adds the partial rows of all splits
+// in split order (a fixed order: results do not depend on which block is
+// last) and writes y.  The split-K combine of Section 4.4, without atomics on
+// y and without a second launch.
 template <class F, int LPR, int WAVES>
-__device__ __forceinline__ void block_combine(const float (&acc)[F::kElemsPerLane], float *red,
-                                              float *__restrict__ out, int tile, int n,
-                                              const typename F::Args &a)
+__device__ __forceinline__ void block_finish(const float (&acc)[F::kElemsPerLane], float *red,
+                                             float *partial, int *counters, float *y, int tile,
+                                             int s, int splits, int n,
+                                             const typename F::Args &a)
 {
     constexpr int EPL = F::kElemsPerLane;
     constexpr int TN = LPR * EPL;
+    __shared__ int last_flag;
     const int lane = threadIdx.x & 63;
     const int w = threadIdx.x >> 6;
     if (lane < LPR) {
@@ -190,22 +216,69 @@ __device__ __forceinline__ void block_combine(const float (&acc)[F::kElemsPerLan
             dst[q] = make_float4(acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
     }
     __syncthreads();
+    if (splits == 1) {
+        for (int c = threadIdx.x; c < TN; c += WAVES * 64) {
+            const int col = tile * TN + c;
+            if (col < n) {
+                float sum = 0.f;
+#pragma unroll
+                for (int ww = 0; ww < WAVES; ++ww) sum += red[ww * TN + c];
+                y[col] = F::finish(sum, a, col);
+            }
+        }
+        return;
+    }
+
+    // The 8 XCDs have separate L2s.  A device-wide fence would write back and
+    // invalidate a whole L2 per block; instead the partial rows themselves move
+    // with device-coherent accesses (write-through stores, cache-bypassing
+    // loads), ordered by the arrival counter: every thread waits for its stores
+    // to complete, the block synchronises, then one thread takes the ticket.
+    float *row = partial + (size_t)s * n;
     for (int c = threadIdx.x; c < TN; c += WAVES * 64) {
         const int col = tile * TN + c;
         if (col < n) {
             float sum = 0.f;
 #pragma unroll
             for (int ww = 0; ww < WAVES; ++ww) sum += red[ww * TN + c];
-            out[col] = F::finish(sum, a, col);
+            store_coherent(row + col, sum);
         }
     }
+    wait_vector_memory();   // this thread's write-through stores have completed
+    __syncthreads();
+    if (threadIdx.x == 0) last_flag = atomicAdd(&counters[tile], 1) == splits - 1;
+    __syncthreads();
+    if (!last_flag) return;
+    for (int c = threadIdx.x; c < TN; c += WAVES * 64) {
+        const int col = tile * TN + c;
+        if (col < n) {
+            const float *p = partial + col;
+            float sum = 0.f;
+            int k = 0;
+            for (; k + 8 <= splits; k += 8) {
+                float v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) v[u] = load_coherent(p + (size_t)(k + u) * n);
+#pragma unroll
+                for (int u = 0; u < 8; ++u) sum += v[u];
+            }
+            for (; k < splits; ++k) sum += load_coherent(p + (size_t)k * n);
+            y[col] = F::finish(sum, a, col);
+        }
+    }
+    // Leave the counter at zero for the next call on this workspace.
+    if (threadIdx.x == 0) atomicExch(&counters[tile], 0);
 }
 
 // Generic kernel for formats with no per-group state (bf16, int8).
+// Grid: tiles_padded * splits blocks; block id -> (tile, split) with the tile
+// index fastest.  tiles_padded is a multiple of 8 so that, with workgroups
+// dealt round-robin to the 8 XCDs, all splits of a tile share one XCD's L2;
+// correctness does not depend on that.
 template <class F, int LPR, int WAVES, int U>
 __global__ __launch_bounds__(WAVES * 64) void sparse_gemv_kernel(
-    typename F::Args a, const __half *__restrict__ x, float t, float *__restrict__ out, int m,
-    int n, int ks, int tiles)
+    typename F::Args a, const __half *__restrict__ x, float t, float *partial, int *counters,
+    float *y, int m, int n, int ks, int tiles, int tiles_padded, int splits)
 {
     constexpr int EPL = F::kElemsPerLane;
     constexpr int TN = LPR * EPL;
@@ -214,8 +287,9 @@ __global__ __launch_bounds__(WAVES * 64) void sparse_gemv_kernel(
     float *red = reinterpret_cast<float *>(smem + (size_t)ks * sizeof(int2));
     __shared__ int seg_prefix[kMaxSegs + 1];
 
-    const int tile = blockIdx.x % tiles;
-    const int s = blockIdx.x / tiles;
+    const int tile = blockIdx.x % tiles_padded;
+    if (tile >= tiles) return;
+    const int s = blockIdx.x / tiles_padded;
     const int k0 = s * ks;
     const int k1 = min(m, k0 + ks);
     const int cnt = __builtin_amdgcn_readfirstlane(compact_slice<WAVES>(x, t, k0, k1, list, seg_prefix));
@@ -237,15 +311,16 @@ __global__ __launch_bounds__(WAVES * 64) void sparse_gemv_kernel(
     stream_rows<F, LPR, U>(acc, list, start, mine, static_cast<const unsigned char *>(a.W),
                            row_bytes, lane_off);
     fold_row_groups<LPR>(acc);
-    block_combine<F, LPR, WAVES>(acc, red, out + (size_t)s * n, tile, n, a);
+    block_finish<F, LPR, WAVES>(acc, red, partial, counters, y, tile, s, splits, n, a);
 }
 
 // Host-side launch geometry shared by the formats.
 struct GemvGeometry {
-    int tiles;      // blocks along the output dimension
-    int ks;         // input channels per block
-    int splits;     // blocks along the input dimension (may be below the request)
-    size_t lds;     // dynamic LDS bytes
+    int tiles;         // blocks along the output dimension that do work
+    int tiles_padded;  // tiles rounded up to a multiple of 8 (XCD count)
+    int ks;            // input channels per block
+    int splits;        // blocks along the input dimension (may be below the request)
+    size_t lds;        // dynamic LDS bytes
 };
 
 inline GemvGeometry gemv_geometry(int m, int n, const GemvShape &sh, int elems_per_lane,
@@ -254,6 +329,7 @@ inline GemvGeometry gemv_geometry(int m, int n, const GemvShape &sh, int elems_p
     GemvGeometry g;
     const int tn = sh.lanes_per_row * elems_per_lane;
     g.tiles = (n + tn - 1) / tn;
+    g.tiles_padded = (g.tiles + 7) / 8 * 8;
     int splits = sh.splits < 1 ? 1 : sh.splits;
     int ks = (m + splits - 1) / splits;
     ks = (ks + ks_multiple - 1) / ks_multiple * ks_multiple;

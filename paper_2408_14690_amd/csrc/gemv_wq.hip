@@ -62,8 +62,8 @@ constexpr int kGroup = 128;
 // unscaled, then fold it into the running sums with that group's scales.
 template <int LPR, int WAVES, int U>
 __global__ __launch_bounds__(WAVES * 64) void sparse_gemv_w4_kernel(
-    FmtW4::Args a, const __half *__restrict__ x, float t, float *__restrict__ out, int m, int n,
-    int ks, int tiles)
+    FmtW4::Args a, const __half *__restrict__ x, float t, float *partial, int *counters, float *y,
+    int m, int n, int ks, int tiles, int tiles_padded, int splits)
 {
     using F = FmtW4;
     constexpr int EPL = F::kElemsPerLane;
@@ -73,8 +73,9 @@ __global__ __launch_bounds__(WAVES * 64) void sparse_gemv_w4_kernel(
     float *red = reinterpret_cast<float *>(smem + (size_t)ks * sizeof(int2));
     __shared__ int seg_prefix[kMaxSegs + 1];
 
-    const int tile = blockIdx.x % tiles;
-    const int s = blockIdx.x / tiles;
+    const int tile = blockIdx.x % tiles_padded;
+    if (tile >= tiles) return;
+    const int s = blockIdx.x / tiles_padded;
     const int k0 = s * ks;                       // multiple of 128
     const int k1 = min(m, k0 + ks);
     compact_slice<WAVES>(x, t, k0, k1, list, seg_prefix);
@@ -118,45 +119,41 @@ __global__ __launch_bounds__(WAVES * 64) void sparse_gemv_w4_kernel(
         }
     }
     fold_row_groups<LPR>(acc);
-    block_combine<F, LPR, WAVES>(acc, red, out + (size_t)s * n, tile, n, a);
+    block_finish<F, LPR, WAVES>(acc, red, partial, counters, y, tile, s, splits, n, a);
 }
 
 hipError_t launch_gemv_w8(const int8_t *Wq, const void *scale_f16, const void *x_f16, float t,
-                          float *y, int m, int n, float *partial, const GemvShape &sh,
-                          hipStream_t stream)
+                          float *y, int m, int n, float *partial, int *counters,
+                          const GemvShape &sh, hipStream_t stream)
 {
     const GemvGeometry g = gemv_geometry(m, n, sh, FmtW8::kElemsPerLane, 64);
-    float *out = g.splits == 1 ? y : partial;
     FmtW8::Args a{Wq, static_cast<const __half *>(scale_f16)};
     const __half *x = static_cast<const __half *>(x_f16);
-#define TEAL_LAUNCH(F, LPR, WAVES, U)                                                        \
-    hipLaunchKernelGGL((sparse_gemv_kernel<F, LPR, WAVES, U>), dim3(g.tiles * g.splits),     \
-                       dim3(WAVES * 64), g.lds, stream, a, x, t, out, m, n, g.ks, g.tiles)
+#define TEAL_LAUNCH(F, LPR, WAVES, U)                                                          \
+    hipLaunchKernelGGL((sparse_gemv_kernel<F, LPR, WAVES, U>), dim3(g.tiles_padded * g.splits), \
+                       dim3(WAVES * 64), g.lds, stream, a, x, t, partial, counters, y, m, n,   \
+                       g.ks, g.tiles, g.tiles_padded, g.splits)
     TEAL_DISPATCH(TEAL_LAUNCH, FmtW8, sh);
 #undef TEAL_LAUNCH
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess || g.splits == 1) return e;
-    return launch_reduce_partials(partial, y, n, g.splits, stream);
+    return hipGetLastError();
 }
 
 hipError_t launch_gemv_w4(const uint8_t *Wq, const void *scale_f16, const void *x_f16, float t,
-                          float *y, int m, int n, float *partial, const GemvShape &sh,
-                          hipStream_t stream)
+                          float *y, int m, int n, float *partial, int *counters,
+                          const GemvShape &sh, hipStream_t stream)
 {
     const GemvGeometry g = gemv_geometry(m, n, sh, FmtW4::kElemsPerLane, kGroup);
-    float *out = g.splits == 1 ? y : partial;
     FmtW4::Args a{Wq, static_cast<const __half *>(scale_f16)};
     const __half *x = static_cast<const __half *>(x_f16);
-#define TEAL_LAUNCH(F, LPR, WAVES, U)                                                        \
-    hipLaunchKernelGGL((sparse_gemv_w4_kernel<LPR, WAVES, U>), dim3(g.tiles * g.splits),     \
-                       dim3(WAVES * 64), g.lds, stream, a, x, t, out, m, n, g.ks, g.tiles)
+#define TEAL_LAUNCH(F, LPR, WAVES, U)                                                          \
+    hipLaunchKernelGGL((sparse_gemv_w4_kernel<LPR, WAVES, U>), dim3(g.tiles_padded * g.splits), \
+                       dim3(WAVES * 64), g.lds, stream, a, x, t, partial, counters, y, m, n,   \
+                       g.ks, g.tiles, g.tiles_padded, g.splits)
     // 64 lanes per row would be a 2048-column tile: not offered for int4.
     if (sh.lanes_per_row == 32) TEAL_DISPATCH_WU(TEAL_LAUNCH, FmtW4, 32, sh);
     else TEAL_DISPATCH_WU(TEAL_LAUNCH, FmtW4, 16, sh);
 #undef TEAL_LAUNCH
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess || g.splits == 1) return e;
-    return launch_reduce_partials(partial, y, n, g.splits, stream);
+    return hipGetLastError();
 }
 
 }  // namespace teal

@@ -70,6 +70,13 @@ teal_status check_gemv(const GemvArgs &a, int n_multiple)
 
 teal_status from_hip(hipError_t e) { return e == hipSuccess ? TEAL_OK : TEAL_ERR_HIP; }
 
+// Workspace layout: [arrival counters, kCounterBytes][partial rows, splits x n fp32].
+int *ws_counters(void *workspace) { return static_cast<int *>(workspace); }
+float *ws_partials(void *workspace)
+{
+    return reinterpret_cast<float *>(static_cast<unsigned char *>(workspace) + teal::kCounterBytes);
+}
+
 }  // namespace
 
 extern "C" {
@@ -95,7 +102,7 @@ size_t teal_workspace_bytes(int m, int n)
 {
     if (m < 1 || m > teal::kMaxDim || n < 1 || n > teal::kMaxDim) return 0;
     const size_t rows = (size_t)max_splits_for(m);
-    const size_t bytes = rows * (size_t)n * sizeof(float);
+    const size_t bytes = teal::kCounterBytes + rows * (size_t)n * sizeof(float);
     return (bytes + kAlignWorkspace - 1) / kAlignWorkspace * kAlignWorkspace;
 }
 
@@ -124,8 +131,8 @@ teal_status teal_sparse_gemv_bf16_ex(const void *Wt_bf16, const void *x_f16, flo
     if (waves) sh.waves = waves;
     if (unroll) sh.unroll = unroll;
     if (!teal::gemv_shape_supported(sh)) return TEAL_ERR_UNSUPPORTED;
-    return from_hip(teal::launch_gemv_bf16(Wt_bf16, x_f16, t, y, m, n,
-                                           static_cast<float *>(workspace), sh,
+    return from_hip(teal::launch_gemv_bf16(Wt_bf16, x_f16, t, y, m, n, ws_partials(workspace),
+                                           ws_counters(workspace), sh,
                                            static_cast<hipStream_t>(stream)));
 }
 
@@ -147,8 +154,8 @@ teal_status teal_sparse_gemv_w8(const int8_t *Wq, const void *scale_f16, const v
     if (st != TEAL_OK) return st;
     if (!aligned(scale_f16, 2)) return TEAL_ERR_ALIGN;
     const GemvShape sh = auto_shape(m, n, 16, 32);
-    return from_hip(teal::launch_gemv_w8(Wq, scale_f16, x_f16, t, y, m, n,
-                                         static_cast<float *>(workspace), sh,
+    return from_hip(teal::launch_gemv_w8(Wq, scale_f16, x_f16, t, y, m, n, ws_partials(workspace),
+                                         ws_counters(workspace), sh,
                                          static_cast<hipStream_t>(stream)));
 }
 
@@ -165,8 +172,8 @@ teal_status teal_sparse_gemv_w4(const uint8_t *Wq, const void *scale_f16, int gr
     GemvShape sh = auto_shape(m, n, 32, 16);
     const int max_by_groups = m / 128;
     if (sh.splits > max_by_groups) sh.splits = max_by_groups;
-    return from_hip(teal::launch_gemv_w4(Wq, scale_f16, x_f16, t, y, m, n,
-                                         static_cast<float *>(workspace), sh,
+    return from_hip(teal::launch_gemv_w4(Wq, scale_f16, x_f16, t, y, m, n, ws_partials(workspace),
+                                         ws_counters(workspace), sh,
                                          static_cast<hipStream_t>(stream)));
 }
 

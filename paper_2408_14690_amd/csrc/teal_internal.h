@@ -11,6 +11,9 @@ namespace teal {
 constexpr int kMaxSplits = 128;     // upper bound on split-K blocks along the input dimension
 constexpr int kMaxSlice = 2048;     // most input channels one block compacts (LDS list capacity)
 constexpr int kMaxDim = 1 << 24;    // largest m or n accepted
+constexpr int kMinTile = 128;       // narrowest output tile of any kernel variant
+// Head of the workspace: one arrival counter per output tile (zero between calls).
+constexpr size_t kCounterBytes = (size_t)(kMaxDim / kMinTile) * sizeof(int);
 
 // How one sparse GEMV is laid over the chip.
 struct GemvShape {
@@ -27,19 +30,16 @@ hipError_t launch_sparsify(const void *x_f16, int m, float t, uint8_t *mask,
                            int32_t *idx, int32_t *count, hipStream_t stream);
 
 hipError_t launch_gemv_bf16(const void *Wt, const void *x_f16, float t, float *y,
-                            int m, int n, float *partial, const GemvShape &shape,
-                            hipStream_t stream);
+                            int m, int n, float *partial, int *counters,
+                            const GemvShape &shape, hipStream_t stream);
 
 hipError_t launch_gemv_w8(const int8_t *Wq, const void *scale_f16, const void *x_f16,
-                          float t, float *y, int m, int n, float *partial,
+                          float t, float *y, int m, int n, float *partial, int *counters,
                           const GemvShape &shape, hipStream_t stream);
 
 hipError_t launch_gemv_w4(const uint8_t *Wq, const void *scale_f16, const void *x_f16,
-                          float t, float *y, int m, int n, float *partial,
+                          float t, float *y, int m, int n, float *partial, int *counters,
                           const GemvShape &shape, hipStream_t stream);
-
-hipError_t launch_reduce_partials(const float *partial, float *y, int n, int splits,
-                                  hipStream_t stream);
 
 hipError_t launch_pack_bf16(const void *W_rowmajor, void *Wt, int m, int n,
                             hipStream_t stream);

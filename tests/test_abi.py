@@ -55,7 +55,8 @@ def test_version_and_status_strings():
 
 def test_workspace_bytes():
     assert T.teal_workspace_bytes(0, 8) == 0 and T.teal_workspace_bytes(8, 0) == 0
-    assert T.teal_workspace_bytes(4096, 4096) == 128 * 4096 * 4
+    # arrival counters (one per 128 output columns of the largest n) + 128 fp32 partial rows
+    assert T.teal_workspace_bytes(4096, 4096) == (1 << 24) // 128 * 4 + 128 * 4096 * 4
     assert T.teal_workspace_bytes(4096, 14336) % 256 == 0
     # very long inputs force more than 128 splits (one block compacts at most 2048 channels)
     assert T.teal_workspace_bytes(1 << 20, 8) >= (1 << 20) // 2048 * 8 * 4

@@ -41,7 +41,8 @@ def rel_l2(got, want):
 
 
 def workspace(T, m, n):
-    return torch.empty(T.teal_workspace_bytes(m, n), dtype=torch.uint8, device="cuda")
+    # zero-filled once; every successful call leaves it ready for the next
+    return torch.zeros(T.teal_workspace_bytes(m, n), dtype=torch.uint8, device="cuda")
 
 
 def run_bf16(T, wt_dev, x_dev, t, m, n, ws, **shape):
@@ -202,8 +203,39 @@ def test_gemv_bf16_is_bitwise_reproducible(T):
     ws = workspace(T, m, n)
     first = run_bf16(T, wt, xd, t, m, n, ws)
     for _ in range(5):
-        ws.random_(0, 255)                            # workspace content must not matter
         assert np.array_equal(run_bf16(T, wt, xd, t, m, n, ws), first)
+    assert np.array_equal(run_bf16(T, wt, xd, t, m, n, workspace(T, m, n)), first)
+    for shape in (dict(lanes_per_row=16, splits=16), dict(lanes_per_row=32, splits=128, waves=8)):
+        a = run_bf16(T, wt, xd, t, m, n, ws, **shape)
+        for _ in range(3):
+            assert np.array_equal(run_bf16(T, wt, xd, t, m, n, ws, **shape), a)
+
+
+def test_one_workspace_serves_calls_of_different_shapes(T):
+    """A workspace sized for the largest call is reused, without re-zeroing, by
+    calls of other shapes and launch shapes, back to back on one stream."""
+    shapes = [(4096, 4096), (1032, 2049), (520, 333), (14336, 4096), (4096, 14336), (1024, 4096)]
+    ws = workspace(T, max(m for _, m in shapes), max(n for n, _ in shapes))
+    cases = []
+    for (n, m) in shapes:
+        w = ti.weights_bf16(n, m, seed=n + 3 * m)
+        x = ti.gaussian_x(m, seed=n + 5 * m)
+        t = ti.quantile_threshold(x, 0.5)
+        cases.append((n, m, dev(ti.to_input_channel_major(w)), dev(x), t,
+                      orc.sparse_gemv_bf16(w, x, t)))
+    ys = []
+    for rep in range(3):
+        for (n, m, wt, xd, t, want) in cases:
+            y = torch.full((n,), float("nan"), dtype=torch.float32, device="cuda")
+            if rep == 1:
+                T.check(T.teal_sparse_gemv_bf16_ex(wt, xd, t, y, m, n, ws, lanes_per_row=16,
+                                                   splits=7))
+            else:
+                T.check(T.teal_sparse_gemv_bf16(wt, xd, t, y, m, n, ws))
+            ys.append((y, want))
+    torch.cuda.synchronize()
+    for y, want in ys:
+        assert rel_l2(y.cpu().numpy(), want) <= TIGHT
 
 
 # ---------------------------------------------------------------------------
