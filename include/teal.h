@@ -137,20 +137,34 @@ teal_status teal_pack_bf16(const void *W_rowmajor, void *Wt, int m, int n,
  * of by the library; for tuning and for tests that walk the kernel variants.
  * Results are identical in meaning (the summation order differs with the
  * shape).  0 means "library's choice" for each field.
- *   lanes_per_row  64, 32 or 16: lanes that share one weight row per load
- *                  (each lane reads 16 bytes), i.e. an output tile of 512,
- *                  256 or 128 columns per thread block.
+ *   lanes_per_row  64, 32, 16 or 8: lanes that share one weight row per load
+ *                  (each lane reads 16 bytes), i.e. an output tile of up to
+ *                  512, 256, 128 or 64 columns per thread block.
+ *   tile_cols      output columns per thread block: a multiple of 8, at most
+ *                  8 * lanes_per_row.
  *   splits         1..128: thread blocks along the input dimension (split-K,
  *                  Section 4.4).
- *   waves          4 or 8 wavefronts per thread block.
- *   unroll         4 or 8 row loads in flight per wavefront.
+ *   waves          4, 8 or 16 wavefronts per thread block.
+ *   unroll         4 or 8 row loads per batch (two batches in flight per
+ *                  wavefront); 4 with 16 wavefronts.
  * Unsupported combinations return TEAL_ERR_UNSUPPORTED.
  */
 teal_status teal_sparse_gemv_bf16_ex(const void *Wt_bf16, const void *x_f16, float t,
                                      float *y, int m, int n,
                                      void *workspace, size_t workspace_bytes,
                                      void *stream,
-                                     int lanes_per_row, int splits, int waves, int unroll);
+                                     int lanes_per_row, int tile_cols, int splits, int waves,
+                                     int unroll);
+
+/*
+ * The launch shape the library chooses for teal_sparse_gemv_{bf16,w8,w4} at
+ * these dimensions (weight_bits = 16, 8 or 4), in the terms of
+ * teal_sparse_gemv_bf16_ex.  Host-only; every output pointer is HOST memory
+ * and may be NULL.  Split-K (Section 4.4) is `splits` blocks along the input
+ * dimension; the grid is ceil(n / tile_cols) * splits blocks.
+ */
+teal_status teal_gemv_plan(int weight_bits, int m, int n, int *lanes_per_row, int *tile_cols,
+                           int *splits, int *waves, int *unroll);
 
 #ifdef __cplusplus
 }

@@ -11,5 +11,5 @@ from .binding import (  # noqa: F401
     TealError, check, library_path, load_library,
     teal_status_string, teal_version, teal_workspace_bytes,
     teal_sparsify, teal_sparse_gemv_bf16, teal_sparse_gemv_bf16_ex,
-    teal_sparse_gemv_w8, teal_sparse_gemv_w4, teal_pack_bf16,
+    teal_sparse_gemv_w8, teal_sparse_gemv_w4, teal_pack_bf16, teal_gemv_plan,
 )

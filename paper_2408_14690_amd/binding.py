@@ -25,7 +25,7 @@ _lib = None
 EXPORTS = (
     "teal_status_string", "teal_version", "teal_workspace_bytes", "teal_sparsify",
     "teal_sparse_gemv_bf16", "teal_sparse_gemv_bf16_ex", "teal_sparse_gemv_w8",
-    "teal_sparse_gemv_w4", "teal_pack_bf16",
+    "teal_sparse_gemv_w4", "teal_pack_bf16", "teal_gemv_plan",
 )
 
 
@@ -61,13 +61,16 @@ def load_library():
     lib.teal_sparse_gemv_bf16.restype = i
     lib.teal_sparse_gemv_bf16.argtypes = [vp, vp, f, vp, i, i, vp, sz, vp]
     lib.teal_sparse_gemv_bf16_ex.restype = i
-    lib.teal_sparse_gemv_bf16_ex.argtypes = [vp, vp, f, vp, i, i, vp, sz, vp, i, i, i, i]
+    lib.teal_sparse_gemv_bf16_ex.argtypes = [vp, vp, f, vp, i, i, vp, sz, vp, i, i, i, i, i]
     lib.teal_sparse_gemv_w8.restype = i
     lib.teal_sparse_gemv_w8.argtypes = [vp, vp, vp, f, vp, i, i, vp, sz, vp]
     lib.teal_sparse_gemv_w4.restype = i
     lib.teal_sparse_gemv_w4.argtypes = [vp, vp, i, vp, f, vp, i, i, vp, sz, vp]
     lib.teal_pack_bf16.restype = i
     lib.teal_pack_bf16.argtypes = [vp, vp, i, i, vp]
+    ip = c.POINTER(c.c_int)
+    lib.teal_gemv_plan.restype = i
+    lib.teal_gemv_plan.argtypes = [i, i, i, ip, ip, ip, ip, ip]
     _lib = lib
     return lib
 
@@ -131,11 +134,12 @@ def teal_sparse_gemv_bf16(Wt_bf16, x_f16, t, y, m, n, workspace, workspace_bytes
 
 
 def teal_sparse_gemv_bf16_ex(Wt_bf16, x_f16, t, y, m, n, workspace, workspace_bytes=None,
-                             stream=None, lanes_per_row=0, splits=0, waves=0, unroll=0) -> int:
+                             stream=None, lanes_per_row=0, tile_cols=0, splits=0, waves=0,
+                             unroll=0) -> int:
     return load_library().teal_sparse_gemv_bf16_ex(
         _ptr(Wt_bf16), _ptr(x_f16), float(t), _ptr(y), int(m), int(n), _ptr(workspace),
-        _nbytes(workspace, workspace_bytes), _stream(stream), int(lanes_per_row), int(splits),
-        int(waves), int(unroll))
+        _nbytes(workspace, workspace_bytes), _stream(stream), int(lanes_per_row), int(tile_cols),
+        int(splits), int(waves), int(unroll))
 
 
 def teal_sparse_gemv_w8(Wq, scale_f16, x_f16, t, y, m, n, workspace, workspace_bytes=None,
@@ -155,3 +159,12 @@ def teal_sparse_gemv_w4(Wq, scale_f16, group, x_f16, t, y, m, n, workspace,
 def teal_pack_bf16(W_rowmajor, Wt, m, n, stream=None) -> int:
     return load_library().teal_pack_bf16(_ptr(W_rowmajor), _ptr(Wt), int(m), int(n),
                                          _stream(stream))
+
+
+def teal_gemv_plan(weight_bits: int, m: int, n: int):
+    """Returns (status, dict(lanes_per_row, tile_cols, splits, waves, unroll))."""
+    vals = [ctypes.c_int(0) for _ in range(5)]
+    st = load_library().teal_gemv_plan(int(weight_bits), int(m), int(n),
+                                       *[ctypes.byref(v) for v in vals])
+    keys = ("lanes_per_row", "tile_cols", "splits", "waves", "unroll")
+    return st, {k: v.value for k, v in zip(keys, vals)}

@@ -24,10 +24,12 @@ struct FmtBF16 {
 
 bool gemv_shape_supported(const GemvShape &s)
 {
-    const bool lpr = s.lanes_per_row == 64 || s.lanes_per_row == 32 || s.lanes_per_row == 16;
-    const bool wv = s.waves == 4 || s.waves == 8;
-    const bool un = s.unroll == 4 || s.unroll == 8;
-    return lpr && wv && un && s.splits >= 1 && s.splits <= kMaxSplits;
+    const bool lpr = s.lanes_per_row == 64 || s.lanes_per_row == 32 || s.lanes_per_row == 16 ||
+                     s.lanes_per_row == 8;
+    const bool wv = s.waves == 4 || s.waves == 8 || s.waves == 16;
+    const bool un = s.unroll == 4 || (s.unroll == 8 && s.waves != 16);
+    const bool tc = s.tile_cols >= 0 && s.tile_cols % 8 == 0 && s.tile_cols <= s.lanes_per_row * 8;
+    return lpr && wv && un && tc && s.splits >= 1 && s.splits <= kMaxSplits;
 }
 
 hipError_t launch_gemv_bf16(const void *Wt, const void *x_f16, float t, float *y, int m, int n,
@@ -38,9 +40,9 @@ hipError_t launch_gemv_bf16(const void *Wt, const void *x_f16, float t, float *y
     FmtBF16::Args a{Wt};
     const __half *x = static_cast<const __half *>(x_f16);
 #define TEAL_LAUNCH(F, LPR, WAVES, U)                                                          \
-    hipLaunchKernelGGL((sparse_gemv_kernel<F, LPR, WAVES, U>), dim3(g.tiles_padded * g.splits), \
+    hipLaunchKernelGGL((sparse_gemv_kernel<F, LPR, WAVES, U>), dim3(g.tiles * g.splits), \
                        dim3(WAVES * 64), g.lds, stream, a, x, t, partial, counters, y, m, n,   \
-                       g.ks, g.tiles, g.tiles_padded, g.splits)
+                       g.ks, g.tiles, g.tile_cols, g.splits)
     TEAL_DISPATCH(TEAL_LAUNCH, FmtBF16, sh);
 #undef TEAL_LAUNCH
     return hipGetLastError();

@@ -105,71 +105,65 @@ __device__ __forceinline__ int compact_slice(const __half *__restrict__ x, float
     return seg_prefix[nseg];
 }
 
+// One batch of row loads in flight: U 16-byte vectors per lane and the
+// activations they are to be multiplied with.
+template <int U>
+struct RowBatch {
+    u32x4 v[U];
+    float xv[U];
+};
+
 // Streams `mine` consecutive list entries starting at list[start] and adds
 // x_i * W[i][cols of this lane] into acc.  LPR lanes share one row per load
-// (64 / LPR rows per wavefront load); U loads are in flight per wavefront.
-// `start` and `mine` are wavefront-uniform.
+// (64 / LPR rows per wavefront load).  Two batches of U loads are kept in
+// flight per wavefront: while one batch is multiplied out, the next is
+// already on its way.  Slots past the end of the share repeat the last row
+// with a zero multiplier (same address as a live load: no new traffic).
+// `start` and `mine` are wavefront-uniform; lane_base = weights + this
+// lane's column offset.
 template <class F, int LPR, int U>
 __device__ __forceinline__ void stream_rows(float (&acc)[F::kElemsPerLane], const int2 *list,
                                             int start, int mine,
-                                            const unsigned char *__restrict__ wbase,
-                                            size_t row_bytes, unsigned lane_off)
+                                            const unsigned char *__restrict__ lane_base,
+                                            unsigned row_bytes)
 {
     constexpr int R = 64 / LPR;
-    const int lane = threadIdx.x & 63;
     if (mine <= 0) return;
-    if constexpr (R == 1) {
-        // The row index is wavefront-uniform: it lives in a scalar register and
-        // the load is (scalar row base) + (per-lane column offset).
-        for (int b = 0; b < mine; b += 64) {
-            const int2 ent = list[start + min(b + lane, mine - 1)];
-            const int nb = min(64, mine - b);
-            int k = 0;
-            for (; k + U <= nb; k += U) {
-                u32x4 v[U];
-                float xv[U];
+    const int g = (threadIdx.x & 63) / LPR;
+    const int last = mine - 1;
+    const int batches = (mine + U * R - 1) / (U * R);
+
+    auto issue = [&](RowBatch<U> &b, int batch) {
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int idx = __builtin_amdgcn_readlane(ent.x, k + u);
-                    xv[u] = __int_as_float(__builtin_amdgcn_readlane(ent.y, k + u));
-                    v[u] = load_stream16(wbase + (size_t)idx * row_bytes + lane_off);
-                }
-#pragma unroll
-                for (int u = 0; u < U; ++u) F::fma(acc, v[u], xv[u]);
-            }
-            if (k < nb) {
-                // Last, partial batch: keep U loads in flight by repeating the
-                // final row with a zero multiplier (same address: no new traffic).
-                u32x4 v[U];
-                float xv[U];
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int kk = min(k + u, nb - 1);
-                    const int idx = __builtin_amdgcn_readlane(ent.x, kk);
-                    const float xr = __int_as_float(__builtin_amdgcn_readlane(ent.y, kk));
-                    xv[u] = (k + u < nb) ? xr : 0.f;
-                    v[u] = load_stream16(wbase + (size_t)idx * row_bytes + lane_off);
-                }
-#pragma unroll
-                for (int u = 0; u < U; ++u) F::fma(acc, v[u], xv[u]);
-            }
+        for (int u = 0; u < U; ++u) {
+            const int e = (batch * U + u) * R + g;
+            const int2 ent = list[start + min(e, last)];
+            b.xv[u] = e <= last ? __int_as_float(ent.y) : 0.f;
+            b.v[u] = load_stream16(lane_base + (size_t)(unsigned)ent.x * row_bytes);
         }
+    };
+    auto consume = [&](const RowBatch<U> &b) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) F::fma(acc, b.v[u], b.xv[u]);
+    };
+
+    // The steady-state loop has no conditional issue, so that each consume
+    // waits only for its own batch while the other batch stays in flight.
+    RowBatch<U> b0, b1;
+    issue(b0, 0);
+    int it = 0;
+    for (; it + 2 < batches; it += 2) {
+        issue(b1, it + 1);
+        consume(b0);
+        issue(b0, it + 2);
+        consume(b1);
+    }
+    if (it + 1 < batches) {
+        issue(b1, it + 1);
+        consume(b0);
+        consume(b1);
     } else {
-        const int g = lane / LPR;
-        const int loads = (mine + R - 1) / R;
-        for (int it = 0; it < loads; it += U) {
-            u32x4 v[U];
-            float xv[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int e = (it + u) * R + g;
-                const int2 ent = list[start + min(e, mine - 1)];
-                xv[u] = e < mine ? __int_as_float(ent.y) : 0.f;
-                v[u] = load_stream16(wbase + (size_t)ent.x * row_bytes + lane_off);
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u) F::fma(acc, v[u], xv[u]);
-        }
+        consume(b0);
     }
 }
 
@@ -195,20 +189,22 @@ __device__ __forceinline__ void wave_share(int cnt, int w, int waves, int &start
 // Sums the wavefronts' accumulators through LDS.  With one split the sums are
 // the outputs.  Otherwise the block writes its fp32 partial row, and the block
 // that arrives last at the tile's counter adds the partial rows of all splits
-// in split order (a fixed order: results do not depend on which block is
-// last) and writes y.  The split-K combine of Section 4.4, without atomics on
-// y and without a second launch.
+// in a fixed order (results do not depend on which block is last) and writes
+// y.  The split-K combine of Section 4.4, without atomics on y and without a
+// second launch.  The tile is columns [col0, col0 + cols) of y, cols <= TN.
 template <class F, int LPR, int WAVES>
 __device__ __forceinline__ void block_finish(const float (&acc)[F::kElemsPerLane], float *red,
                                              float *partial, int *counters, float *y, int tile,
-                                             int s, int splits, int n,
+                                             int col0, int cols, int s, int splits, int n,
                                              const typename F::Args &a)
 {
     constexpr int EPL = F::kElemsPerLane;
     constexpr int TN = LPR * EPL;
+    constexpr int THREADS = WAVES * 64;
     __shared__ int last_flag;
     const int lane = threadIdx.x & 63;
     const int w = threadIdx.x >> 6;
+    if (cols > n - col0) cols = n - col0;
     if (lane < LPR) {
         float4 *dst = reinterpret_cast<float4 *>(red + w * TN + lane * EPL);
 #pragma unroll
@@ -217,14 +213,11 @@ __device__ __forceinline__ void block_finish(const float (&acc)[F::kElemsPerLane
     }
     __syncthreads();
     if (splits == 1) {
-        for (int c = threadIdx.x; c < TN; c += WAVES * 64) {
-            const int col = tile * TN + c;
-            if (col < n) {
-                float sum = 0.f;
+        for (int c = threadIdx.x; c < cols; c += THREADS) {
+            float sum = 0.f;
 #pragma unroll
-                for (int ww = 0; ww < WAVES; ++ww) sum += red[ww * TN + c];
-                y[col] = F::finish(sum, a, col);
-            }
+            for (int ww = 0; ww < WAVES; ++ww) sum += red[ww * TN + c];
+            y[col0 + c] = F::finish(sum, a, col0 + c);
         }
         return;
     }
@@ -234,51 +227,84 @@ __device__ __forceinline__ void block_finish(const float (&acc)[F::kElemsPerLane
     // with device-coherent accesses (write-through stores, cache-bypassing
     // loads), ordered by the arrival counter: every thread waits for its stores
     // to complete, the block synchronises, then one thread takes the ticket.
-    float *row = partial + (size_t)s * n;
-    for (int c = threadIdx.x; c < TN; c += WAVES * 64) {
-        const int col = tile * TN + c;
-        if (col < n) {
-            float sum = 0.f;
+    float *row = partial + (size_t)s * n + col0;
+    for (int c = threadIdx.x; c < cols; c += THREADS) {
+        float sum = 0.f;
 #pragma unroll
-            for (int ww = 0; ww < WAVES; ++ww) sum += red[ww * TN + c];
-            store_coherent(row + col, sum);
-        }
+        for (int ww = 0; ww < WAVES; ++ww) sum += red[ww * TN + c];
+        store_coherent(row + c, sum);
     }
     wait_vector_memory();   // this thread's write-through stores have completed
     __syncthreads();
     if (threadIdx.x == 0) last_flag = atomicAdd(&counters[tile], 1) == splits - 1;
     __syncthreads();
     if (!last_flag) return;
-    for (int c = threadIdx.x; c < TN; c += WAVES * 64) {
-        const int col = tile * TN + c;
-        if (col < n) {
-            const float *p = partial + col;
-            float sum = 0.f;
-            int k = 0;
-            for (; k + 8 <= splits; k += 8) {
-                float v[8];
+
+    // Second pass.  The block's threads form PARTS groups of TN; group q adds
+    // the rows s = q, q + PARTS, ... in ascending order, all its loads in
+    // flight at once, and the groups' sums are added in group order through
+    // LDS: a fixed order, whichever block happens to be last.
+    constexpr int PARTS = THREADS >= TN ? THREADS / TN : 1;
+    constexpr int MAXLD = 8;
+    for (int c0 = 0; c0 < TN; c0 += THREADS) {
+        const int c = c0 + (int)threadIdx.x % (PARTS > 1 ? TN : THREADS);
+        const int q = PARTS > 1 ? (int)threadIdx.x / TN : 0;
+        float sum = 0.f;
+        if (c < cols) {
+            const float *p = partial + col0 + c;
+            for (int k = q; k < splits; k += PARTS * MAXLD) {
+                float v[MAXLD];
 #pragma unroll
-                for (int u = 0; u < 8; ++u) v[u] = load_coherent(p + (size_t)(k + u) * n);
+                for (int u = 0; u < MAXLD; ++u) {
+                    const int sk = k + u * PARTS;
+                    v[u] = sk < splits ? load_coherent(p + (size_t)sk * n) : 0.f;
+                }
 #pragma unroll
-                for (int u = 0; u < 8; ++u) sum += v[u];
+                for (int u = 0; u < MAXLD; ++u) sum += v[u];
             }
-            for (; k < splits; ++k) sum += load_coherent(p + (size_t)k * n);
-            y[col] = F::finish(sum, a, col);
+        }
+        if (PARTS > 1) {
+            __syncthreads();            // red[] is free: everyone has read its wave sums
+            red[q * TN + c] = sum;
+            __syncthreads();
+            if (q == 0 && c < cols) {
+                float total = red[c];
+#pragma unroll
+                for (int qq = 1; qq < PARTS; ++qq) total += red[qq * TN + c];
+                y[col0 + c] = F::finish(total, a, col0 + c);
+            }
+        } else if (c < cols) {
+            y[col0 + c] = F::finish(sum, a, col0 + c);
         }
     }
     // Leave the counter at zero for the next call on this workspace.
     if (threadIdx.x == 0) atomicExch(&counters[tile], 0);
 }
 
+// This lane's first column: lane l of a row group covers EPL columns starting at
+// col0 + l * EPL.  Lanes past the tile's (or the matrix's) right edge re-read
+// the last valid vector: same cache line as a live lane, and their sums are
+// never written.
+template <int EPL>
+__device__ __forceinline__ int lane_column(int col0, int cols, int n, int l)
+{
+    int c = l * EPL;
+    if (c > cols - EPL) c = cols - EPL;
+    int col = col0 + c;
+    if (col > n - EPL) col = n - EPL;
+    return col;
+}
+
 // Generic kernel for formats with no per-group state (bf16, int8).
-// Grid: tiles_padded * splits blocks; block id -> (tile, split) with the tile
-// index fastest.  tiles_padded is a multiple of 8 so that, with workgroups
-// dealt round-robin to the 8 XCDs, all splits of a tile share one XCD's L2;
-// correctness does not depend on that.
+// Grid: tiles * splits blocks; block id -> (tile, split) with the tile index
+// fastest, so that the blocks dealt round-robin to the 8 XCDs at any moment
+// read neighbouring column ranges of the same rows, and every XCD gets the
+// same number of blocks (+-1).  tile_cols (a multiple of EPL, <= LPR * EPL)
+// is the width of an output tile.
 template <class F, int LPR, int WAVES, int U>
 __global__ __launch_bounds__(WAVES * 64) void sparse_gemv_kernel(
     typename F::Args a, const __half *__restrict__ x, float t, float *partial, int *counters,
-    float *y, int m, int n, int ks, int tiles, int tiles_padded, int splits)
+    float *y, int m, int n, int ks, int tiles, int tile_cols, int splits)
 {
     constexpr int EPL = F::kElemsPerLane;
     constexpr int TN = LPR * EPL;
@@ -287,9 +313,8 @@ __global__ __launch_bounds__(WAVES * 64) void sparse_gemv_kernel(
     float *red = reinterpret_cast<float *>(smem + (size_t)ks * sizeof(int2));
     __shared__ int seg_prefix[kMaxSegs + 1];
 
-    const int tile = blockIdx.x % tiles_padded;
-    if (tile >= tiles) return;
-    const int s = blockIdx.x / tiles_padded;
+    const int tile = blockIdx.x % tiles;
+    const int s = blockIdx.x / tiles;
     const int k0 = s * ks;
     const int k1 = min(m, k0 + ks);
     const int cnt = __builtin_amdgcn_readfirstlane(compact_slice<WAVES>(x, t, k0, k1, list, seg_prefix));
@@ -299,25 +324,26 @@ __global__ __launch_bounds__(WAVES * 64) void sparse_gemv_kernel(
     int start, mine;
     wave_share(cnt, w, WAVES, start, mine);
 
-    // Lanes past a ragged right edge re-read the last valid vector; their sums are not written.
-    int col = tile * TN + (lane % LPR) * EPL;
-    if (col > n - EPL) col = n - EPL;
-    const size_t row_bytes = (size_t)n * F::kBitsPerElem / 8;
-    const unsigned lane_off = (unsigned)((size_t)col * F::kBitsPerElem / 8);
+    const int col0 = tile * tile_cols;
+    const int col = lane_column<EPL>(col0, tile_cols, n, lane % LPR);
+    const unsigned row_bytes = (unsigned)((size_t)n * F::kBitsPerElem / 8);
+    const unsigned char *lane_base =
+        static_cast<const unsigned char *>(a.W) + (size_t)col * F::kBitsPerElem / 8;
 
     float acc[EPL];
 #pragma unroll
     for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
-    stream_rows<F, LPR, U>(acc, list, start, mine, static_cast<const unsigned char *>(a.W),
-                           row_bytes, lane_off);
+    stream_rows<F, LPR, U>(acc, list, start, mine, lane_base, row_bytes);
     fold_row_groups<LPR>(acc);
-    block_finish<F, LPR, WAVES>(acc, red, partial, counters, y, tile, s, splits, n, a);
+    block_finish<F, LPR, WAVES>(acc, red, partial, counters, y, tile, col0, tile_cols, s, splits, n,
+                                a);
+    (void)TN;
 }
 
 // Host-side launch geometry shared by the formats.
 struct GemvGeometry {
-    int tiles;         // blocks along the output dimension that do work
-    int tiles_padded;  // tiles rounded up to a multiple of 8 (XCD count)
+    int tiles;         // blocks along the output dimension
+    int tile_cols;     // output columns per tile
     int ks;            // input channels per block
     int splits;        // blocks along the input dimension (may be below the request)
     size_t lds;        // dynamic LDS bytes
@@ -328,8 +354,8 @@ inline GemvGeometry gemv_geometry(int m, int n, const GemvShape &sh, int elems_p
 {
     GemvGeometry g;
     const int tn = sh.lanes_per_row * elems_per_lane;
-    g.tiles = (n + tn - 1) / tn;
-    g.tiles_padded = (g.tiles + 7) / 8 * 8;
+    g.tile_cols = sh.tile_cols > 0 ? sh.tile_cols : tn;
+    g.tiles = (n + g.tile_cols - 1) / g.tile_cols;
     int splits = sh.splits < 1 ? 1 : sh.splits;
     int ks = (m + splits - 1) / splits;
     ks = (ks + ks_multiple - 1) / ks_multiple * ks_multiple;

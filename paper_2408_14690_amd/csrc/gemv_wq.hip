@@ -63,7 +63,7 @@ constexpr int kGroup = 128;
 template <int LPR, int WAVES, int U>
 __global__ __launch_bounds__(WAVES * 64) void sparse_gemv_w4_kernel(
     FmtW4::Args a, const __half *__restrict__ x, float t, float *partial, int *counters, float *y,
-    int m, int n, int ks, int tiles, int tiles_padded, int splits)
+    int m, int n, int ks, int tiles, int tile_cols, int splits)
 {
     using F = FmtW4;
     constexpr int EPL = F::kElemsPerLane;
@@ -73,19 +73,18 @@ __global__ __launch_bounds__(WAVES * 64) void sparse_gemv_w4_kernel(
     float *red = reinterpret_cast<float *>(smem + (size_t)ks * sizeof(int2));
     __shared__ int seg_prefix[kMaxSegs + 1];
 
-    const int tile = blockIdx.x % tiles_padded;
-    if (tile >= tiles) return;
-    const int s = blockIdx.x / tiles_padded;
+    const int tile = blockIdx.x % tiles;
+    const int s = blockIdx.x / tiles;
     const int k0 = s * ks;                       // multiple of 128
     const int k1 = min(m, k0 + ks);
     compact_slice<WAVES>(x, t, k0, k1, list, seg_prefix);
 
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    int col = tile * TN + (lane % LPR) * EPL;
-    if (col > n - EPL) col = n - EPL;
-    const size_t row_bytes = (size_t)n / 2;
-    const unsigned lane_off = (unsigned)(col / 2);
+    const int col0 = tile * tile_cols;
+    const int col = lane_column<EPL>(col0, tile_cols, n, lane % LPR);
+    const unsigned row_bytes = (unsigned)(n / 2);
+    const unsigned char *lane_base = static_cast<const unsigned char *>(a.W) + col / 2;
 
     float acc[EPL];
 #pragma unroll
@@ -101,8 +100,7 @@ __global__ __launch_bounds__(WAVES * 64) void sparse_gemv_w4_kernel(
         float gacc[EPL];
 #pragma unroll
         for (int e = 0; e < EPL; ++e) gacc[e] = 0.f;
-        stream_rows<F, LPR, U>(gacc, list, g0 + start, mine,
-                               static_cast<const unsigned char *>(a.W), row_bytes, lane_off);
+        stream_rows<F, LPR, U>(gacc, list, g0 + start, mine, lane_base, row_bytes);
         const uint4 *sp = reinterpret_cast<const uint4 *>(
             a.scale + (size_t)(k0 / kGroup + gi) * n + col);
 #pragma unroll
@@ -119,7 +117,9 @@ __global__ __launch_bounds__(WAVES * 64) void sparse_gemv_w4_kernel(
         }
     }
     fold_row_groups<LPR>(acc);
-    block_finish<F, LPR, WAVES>(acc, red, partial, counters, y, tile, s, splits, n, a);
+    block_finish<F, LPR, WAVES>(acc, red, partial, counters, y, tile, col0, tile_cols, s, splits, n,
+                                a);
+    (void)TN;
 }
 
 hipError_t launch_gemv_w8(const int8_t *Wq, const void *scale_f16, const void *x_f16, float t,
@@ -130,9 +130,9 @@ hipError_t launch_gemv_w8(const int8_t *Wq, const void *scale_f16, const void *x
     FmtW8::Args a{Wq, static_cast<const __half *>(scale_f16)};
     const __half *x = static_cast<const __half *>(x_f16);
 #define TEAL_LAUNCH(F, LPR, WAVES, U)                                                          \
-    hipLaunchKernelGGL((sparse_gemv_kernel<F, LPR, WAVES, U>), dim3(g.tiles_padded * g.splits), \
+    hipLaunchKernelGGL((sparse_gemv_kernel<F, LPR, WAVES, U>), dim3(g.tiles * g.splits), \
                        dim3(WAVES * 64), g.lds, stream, a, x, t, partial, counters, y, m, n,   \
-                       g.ks, g.tiles, g.tiles_padded, g.splits)
+                       g.ks, g.tiles, g.tile_cols, g.splits)
     TEAL_DISPATCH(TEAL_LAUNCH, FmtW8, sh);
 #undef TEAL_LAUNCH
     return hipGetLastError();
@@ -146,9 +146,9 @@ hipError_t launch_gemv_w4(const uint8_t *Wq, const void *scale_f16, const void *
     FmtW4::Args a{Wq, static_cast<const __half *>(scale_f16)};
     const __half *x = static_cast<const __half *>(x_f16);
 #define TEAL_LAUNCH(F, LPR, WAVES, U)                                                          \
-    hipLaunchKernelGGL((sparse_gemv_w4_kernel<LPR, WAVES, U>), dim3(g.tiles_padded * g.splits), \
+    hipLaunchKernelGGL((sparse_gemv_w4_kernel<LPR, WAVES, U>), dim3(g.tiles * g.splits), \
                        dim3(WAVES * 64), g.lds, stream, a, x, t, partial, counters, y, m, n,   \
-                       g.ks, g.tiles, g.tiles_padded, g.splits)
+                       g.ks, g.tiles, g.tile_cols, g.splits)
     // 64 lanes per row would be a 2048-column tile: not offered for int4.
     if (sh.lanes_per_row == 32) TEAL_DISPATCH_WU(TEAL_LAUNCH, FmtW4, 32, sh);
     else TEAL_DISPATCH_WU(TEAL_LAUNCH, FmtW4, 16, sh);

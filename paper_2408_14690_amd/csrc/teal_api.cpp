@@ -24,24 +24,54 @@ int max_splits_for(int m)
     return forced > teal::kMaxSplits ? forced : teal::kMaxSplits;
 }
 
-// Split-K depth (Section 4.4) such that the grid covers the chip several times over
-// while each block still has a few rows per wavefront to stream.
-GemvShape auto_shape(int m, int n, int elems_per_lane, int lanes_per_row)
+// Launch shape for one GEMV.  Measured on MI355X, the time of a call is a fixed
+// latency chain (load x, compact, first weight rows; then publish partial rows,
+// ticket, second pass) plus the row stream at HBM speed, and is flat over a wide
+// range of shapes as long as (a) every compute unit has one block of 8
+// wavefronts, (b) the split-K depth (Section 4.4) stays small, so that the
+// partial rows and the second pass are cheap, and (c) a row segment per block is
+// 256 B .. 1 KiB.  So: aim at tiles * splits == number of compute units, prefer
+// about 8 splits, and size the output tile to fit.
+GemvShape auto_shape(int m, int n, int elems_per_lane, int min_lanes, int max_lanes,
+                     int ks_multiple)
 {
-    GemvShape s;
-    s.lanes_per_row = lanes_per_row;
-    s.waves = 4;
-    s.unroll = 8;
-    const int tn = lanes_per_row * elems_per_lane;
-    const int tiles = (n + tn - 1) / tn;
-    const int want_blocks = kComputeUnits * 8;
-    int splits = (want_blocks + tiles - 1) / tiles;
-    const int max_by_rows = (m + 63) / 64;            // at least 64 channels per block
-    if (splits > max_by_rows) splits = max_by_rows;
-    if (splits > teal::kMaxSplits) splits = teal::kMaxSplits;
-    if (splits < 1) splits = 1;
-    s.splits = splits;
-    return s;
+    static const int preferred_splits[] = {8, 7, 6, 5, 4, 12, 14, 16, 10, 3, 2, 24, 32, 1, 48, 64, 128};
+    const int tc_min = min_lanes * elems_per_lane, tc_max = max_lanes * elems_per_lane;
+    GemvShape best{};
+    double best_cost = 1e30;
+    int rank = 0;
+    for (int asked : preferred_splits) {
+        ++rank;
+        int ks = (m + asked - 1) / asked;
+        ks = (ks + ks_multiple - 1) / ks_multiple * ks_multiple;
+        if (ks > teal::kMaxSlice) continue;
+        if (asked > 1 && ks < 128) continue;                // too few channels per block
+        const int splits = (m + ks - 1) / ks;               // after rounding the slice up
+        const int tiles_wanted = (kComputeUnits + splits / 2) / splits;
+        int tc = (n + tiles_wanted - 1) / tiles_wanted;
+        tc = (tc + elems_per_lane - 1) / elems_per_lane * elems_per_lane;
+        if (tc < tc_min) tc = tc_min;
+        if (tc > tc_max) tc = tc_max;
+        const int tiles = (n + tc - 1) / tc;
+        const double blocks = (double)tiles * splits;
+        double cost = (blocks > kComputeUnits ? (blocks - kComputeUnits) * 2.0 : kComputeUnits - blocks)
+                      / kComputeUnits + 0.01 * rank;
+        if (cost < best_cost) {
+            best_cost = cost;
+            best.splits = splits;
+            best.tile_cols = tc;
+        }
+    }
+    if (best_cost == 1e30) {     // very long input: as few splits as the LDS list allows
+        best.splits = (m + teal::kMaxSlice - 1) / teal::kMaxSlice;
+        best.tile_cols = tc_max;
+    }
+    int lanes = min_lanes;
+    while (lanes * elems_per_lane < best.tile_cols) lanes *= 2;
+    best.lanes_per_row = lanes;
+    best.waves = 8;
+    best.unroll = 4;
+    return best;
 }
 
 struct GemvArgs {
@@ -120,14 +150,19 @@ teal_status teal_sparsify(const void *x_f16, int m, float t, uint8_t *mask, int3
 
 teal_status teal_sparse_gemv_bf16_ex(const void *Wt_bf16, const void *x_f16, float t, float *y,
                                      int m, int n, void *workspace, size_t workspace_bytes,
-                                     void *stream, int lanes_per_row, int splits, int waves,
-                                     int unroll)
+                                     void *stream, int lanes_per_row, int tile_cols, int splits,
+                                     int waves, int unroll)
 {
     const GemvArgs a{Wt_bf16, x_f16, t, y, m, n, workspace, workspace_bytes};
     const teal_status st = check_gemv(a, 8);
     if (st != TEAL_OK) return st;
-    GemvShape sh = auto_shape(m, n, 8, lanes_per_row ? lanes_per_row : 64);
+    GemvShape sh = auto_shape(m, n, 8, 16, 64, 64);
+    if (lanes_per_row) {
+        sh.lanes_per_row = lanes_per_row;
+        if (!tile_cols && sh.tile_cols > lanes_per_row * 8) sh.tile_cols = lanes_per_row * 8;
+    }
     if (splits) sh.splits = splits;
+    if (tile_cols) sh.tile_cols = tile_cols;
     if (waves) sh.waves = waves;
     if (unroll) sh.unroll = unroll;
     if (!teal::gemv_shape_supported(sh)) return TEAL_ERR_UNSUPPORTED;
@@ -136,12 +171,29 @@ teal_status teal_sparse_gemv_bf16_ex(const void *Wt_bf16, const void *x_f16, flo
                                            static_cast<hipStream_t>(stream)));
 }
 
+teal_status teal_gemv_plan(int weight_bits, int m, int n, int *lanes_per_row, int *tile_cols,
+                           int *splits, int *waves, int *unroll)
+{
+    if (m < 1 || m > teal::kMaxDim || n < 1 || n > teal::kMaxDim) return TEAL_ERR_SHAPE;
+    GemvShape sh;
+    if (weight_bits == 16) sh = auto_shape(m, n, 8, 16, 64, 64);
+    else if (weight_bits == 8) sh = auto_shape(m, n, 16, 16, 64, 64);
+    else if (weight_bits == 4) sh = auto_shape(m, n, 32, 16, 32, 128);
+    else return TEAL_ERR_UNSUPPORTED;
+    if (lanes_per_row) *lanes_per_row = sh.lanes_per_row;
+    if (tile_cols) *tile_cols = sh.tile_cols;
+    if (splits) *splits = sh.splits;
+    if (waves) *waves = sh.waves;
+    if (unroll) *unroll = sh.unroll;
+    return TEAL_OK;
+}
+
 teal_status teal_sparse_gemv_bf16(const void *Wt_bf16, const void *x_f16, float t, float *y,
                                   int m, int n, void *workspace, size_t workspace_bytes,
                                   void *stream)
 {
     return teal_sparse_gemv_bf16_ex(Wt_bf16, x_f16, t, y, m, n, workspace, workspace_bytes,
-                                    stream, 0, 0, 0, 0);
+                                    stream, 0, 0, 0, 0, 0);
 }
 
 teal_status teal_sparse_gemv_w8(const int8_t *Wq, const void *scale_f16, const void *x_f16,
@@ -153,7 +205,7 @@ teal_status teal_sparse_gemv_w8(const int8_t *Wq, const void *scale_f16, const v
     const teal_status st = check_gemv(a, 16);
     if (st != TEAL_OK) return st;
     if (!aligned(scale_f16, 2)) return TEAL_ERR_ALIGN;
-    const GemvShape sh = auto_shape(m, n, 16, 32);
+    const GemvShape sh = auto_shape(m, n, 16, 16, 64, 64);
     return from_hip(teal::launch_gemv_w8(Wq, scale_f16, x_f16, t, y, m, n, ws_partials(workspace),
                                          ws_counters(workspace), sh,
                                          static_cast<hipStream_t>(stream)));
@@ -169,9 +221,7 @@ teal_status teal_sparse_gemv_w4(const uint8_t *Wq, const void *scale_f16, int gr
     if (st != TEAL_OK) return st;
     if (!aligned(scale_f16, 16)) return TEAL_ERR_ALIGN;
     if (group != 128 || m % 128 != 0) return TEAL_ERR_UNSUPPORTED;
-    GemvShape sh = auto_shape(m, n, 32, 16);
-    const int max_by_groups = m / 128;
-    if (sh.splits > max_by_groups) sh.splits = max_by_groups;
+    const GemvShape sh = auto_shape(m, n, 32, 16, 32, 128);
     return from_hip(teal::launch_gemv_w4(Wq, scale_f16, x_f16, t, y, m, n, ws_partials(workspace),
                                          ws_counters(workspace), sh,
                                          static_cast<hipStream_t>(stream)));

@@ -9,18 +9,19 @@
 namespace teal {
 
 constexpr int kMaxSplits = 128;     // upper bound on split-K blocks along the input dimension
-constexpr int kMaxSlice = 2048;     // most input channels one block compacts (LDS list capacity)
+constexpr int kMaxSlice = 4096;     // most input channels one block compacts (LDS list capacity)
 constexpr int kMaxDim = 1 << 24;    // largest m or n accepted
-constexpr int kMinTile = 128;       // narrowest output tile of any kernel variant
+constexpr int kMinTile = 64;        // narrowest output tile of any kernel variant
 // Head of the workspace: one arrival counter per output tile (zero between calls).
 constexpr size_t kCounterBytes = (size_t)(kMaxDim / kMinTile) * sizeof(int);
 
 // How one sparse GEMV is laid over the chip.
 struct GemvShape {
-    int lanes_per_row;   // 64, 32 or 16 lanes read one weight row per load (16 bytes each)
+    int lanes_per_row;   // 64, 32, 16 or 8 lanes read one weight row per load (16 bytes each)
     int splits;          // blocks along the input dimension
-    int waves;           // wavefronts per block (4 or 8)
-    int unroll;          // row loads in flight per wavefront (4 or 8)
+    int tile_cols;       // output columns per block; 0 = lanes_per_row * elements per lane
+    int waves;           // wavefronts per block (4, 8 or 16)
+    int unroll;          // row loads per batch, two batches in flight per wavefront (4 or 8; 4 with 16 waves)
 };
 
 bool gemv_shape_supported(const GemvShape &s);

@@ -55,11 +55,11 @@ def test_version_and_status_strings():
 
 def test_workspace_bytes():
     assert T.teal_workspace_bytes(0, 8) == 0 and T.teal_workspace_bytes(8, 0) == 0
-    # arrival counters (one per 128 output columns of the largest n) + 128 fp32 partial rows
-    assert T.teal_workspace_bytes(4096, 4096) == (1 << 24) // 128 * 4 + 128 * 4096 * 4
+    # arrival counters (one per 64 output columns of the largest n) + 128 fp32 partial rows
+    assert T.teal_workspace_bytes(4096, 4096) == (1 << 24) // 64 * 4 + 128 * 4096 * 4
     assert T.teal_workspace_bytes(4096, 14336) % 256 == 0
-    # very long inputs force more than 128 splits (one block compacts at most 2048 channels)
-    assert T.teal_workspace_bytes(1 << 20, 8) >= (1 << 20) // 2048 * 8 * 4
+    # very long inputs force more than 128 splits (one block compacts at most 4096 channels)
+    assert T.teal_workspace_bytes(1 << 20, 8) >= (1 << 20) // 4096 * 8 * 4
     assert T.teal_workspace_bytes((1 << 24) + 1, 8) == 0
 
 
@@ -97,6 +97,9 @@ def test_gemv_bf16_ex_rejects_unsupported_shapes():
     assert T.teal_sparse_gemv_bf16_ex(*base, splits=-1) == T.TEAL_ERR_UNSUPPORTED
     assert T.teal_sparse_gemv_bf16_ex(*base, waves=3) == T.TEAL_ERR_UNSUPPORTED
     assert T.teal_sparse_gemv_bf16_ex(*base, unroll=5) == T.TEAL_ERR_UNSUPPORTED
+    assert T.teal_sparse_gemv_bf16_ex(*base, waves=16, unroll=8) == T.TEAL_ERR_UNSUPPORTED
+    assert T.teal_sparse_gemv_bf16_ex(*base, tile_cols=12) == T.TEAL_ERR_UNSUPPORTED
+    assert T.teal_sparse_gemv_bf16_ex(*base, lanes_per_row=16, tile_cols=136) == T.TEAL_ERR_UNSUPPORTED
     # argument errors win over shape errors
     assert T.teal_sparse_gemv_bf16_ex(None, X, 0.5, Y, 4096, 4096, WS, BIG, 0,
                                       lanes_per_row=48) == T.TEAL_ERR_NULL

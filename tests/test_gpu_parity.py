@@ -142,9 +142,8 @@ def test_gemv_bf16_small_shapes_default_launch(T, n, m):
             assert rel_l2(got, want) <= TOL_BF16
 
 
-@pytest.mark.parametrize("lanes", [64, 32, 16])
-@pytest.mark.parametrize("waves", [4, 8])
-@pytest.mark.parametrize("unroll", [4, 8])
+@pytest.mark.parametrize("lanes", [64, 32, 16, 8])
+@pytest.mark.parametrize("waves,unroll", [(4, 4), (4, 8), (8, 4), (8, 8), (16, 4)])
 def test_gemv_bf16_every_variant(T, lanes, waves, unroll):
     for (n, m) in [(520, 333), (1032, 2049), (4096, 4096)]:
         w = ti.weights_bf16(n, m, seed=3 * n + m)
@@ -156,9 +155,12 @@ def test_gemv_bf16_every_variant(T, lanes, waves, unroll):
             t = ti.quantile_threshold(x, p)
             want = orc.sparse_gemv_bf16(w, x, t)
             for splits in (1, 3, 16, 128):
-                got = run_bf16(T, wt, xd, t, m, n, ws, lanes_per_row=lanes, splits=splits,
-                               waves=waves, unroll=unroll)
-                assert rel_l2(got, want) <= TIGHT, (n, m, p, lanes, waves, unroll, splits)
+                # full-width tiles, and narrower ones that leave lanes idle and a ragged last tile
+                for tile_cols in (0, lanes * 8 - 8, 24):
+                    got = run_bf16(T, wt, xd, t, m, n, ws, lanes_per_row=lanes, splits=splits,
+                                   waves=waves, unroll=unroll, tile_cols=tile_cols)
+                    assert rel_l2(got, want) <= TIGHT, (n, m, p, lanes, waves, unroll, splits,
+                                                        tile_cols)
 
 
 def test_gemv_bf16_degenerate_sparsity(T):
@@ -205,7 +207,7 @@ def test_gemv_bf16_is_bitwise_reproducible(T):
     for _ in range(5):
         assert np.array_equal(run_bf16(T, wt, xd, t, m, n, ws), first)
     assert np.array_equal(run_bf16(T, wt, xd, t, m, n, workspace(T, m, n)), first)
-    for shape in (dict(lanes_per_row=16, splits=16), dict(lanes_per_row=32, splits=128, waves=8)):
+    for shape in (dict(lanes_per_row=16, splits=16), dict(lanes_per_row=64, splits=128, waves=8, tile_cols=448)):
         a = run_bf16(T, wt, xd, t, m, n, ws, **shape)
         for _ in range(3):
             assert np.array_equal(run_bf16(T, wt, xd, t, m, n, ws, **shape), a)
