@@ -30,6 +30,11 @@ import teal_inputs as ti
 HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published
 CACHE_DEFEAT_BYTES = 3 << 30    # distinct weight bytes walked before a copy is reused
 SPARSITIES = (0.5, 0.4, 0.0)    # headline first
+# HBM bytes per launch of sparse_gemv_kernel at 50% (average over the 7 launches of a step),
+# from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script, scaled by the factors a
+# plain copy of known size gives on the same box (2.0 and 1.0):
+# profiles/sparse_gemv_kernel_llama2_7b_hbm_traffic.txt.
+MEASURED_TRAFFIC_BYTES = {"llama2_7b": (200310.07 + 1555.31) * 1024 / 7}
 
 
 def algorithmic_bytes(nnz: int, m: int, n: int) -> int:
@@ -116,7 +121,7 @@ def cpu_baseline(layer, p: float, budget_s: float = 12.0):
     for L in layer[:1]:
         orc.sparse_gemv_bf16(L["w_host"], L["x_host"], L["t"][p])      # warm-up
     passes, spent = 0, 0.0
-    while spent < budget_s and passes < 50:
+    while spent < budget_s and passes < 1000:
         t0 = time.perf_counter()
         for L in layer:
             orc.sparse_gemv_bf16(L["w_host"], L["x_host"], L["t"][p])
@@ -213,7 +218,7 @@ def main() -> int:
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
-            "traffic": None,
+            "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
             "kernel": "sparse_gemv_kernel (one launch per projection; 7 launches per step, 50%)",
             "bytes_per_launch_avg": calls_bytes / launches_per_step,
             "kernel_avg_us": kernel_avg_us,

@@ -59,50 +59,59 @@ __device__ __forceinline__ int lanes_below(unsigned long long b)
 __device__ __forceinline__ bool survives(float xv, float t) { return fabsf(xv) > t; }
 
 // Compacts the survivors of channels [k0, k1) into list[] as (channel, x as
-// fp32 bits), ascending.  seg_prefix[] (LDS, kMaxSegs + 1 ints) ends up
-// holding the exclusive prefix of the per-64-channel-segment counts, with
-// the total in seg_prefix[nseg].  Returns the total (same in all threads).
-// Needs k1 - k0 <= kMaxSlice.  All threads of the block must call it.
+// fp32 bits), ascending.  Each wavefront ballots its 64-channel segments and
+// leaves their popcounts in seg_cnt[] (LDS, kMaxSegs ints); after one barrier
+// every wavefront computes the exclusive prefix over the segment counts
+// itself (lane j holds the prefix of segment j in `seg_excl`; lanes past the
+// last segment hold the total) and scatters its survivors.  The x values and
+// ballots stay in registers between the two steps, and all of a wavefront's
+// loads of x are issued together.  Returns the total (same in all threads).
+// Needs k1 - k0 <= kMaxSlice.  All threads of the block must call it; ends
+// with a barrier after which list[] is complete.
 template <int WAVES>
-__device__ __forceinline__ int compact_slice(const __half *__restrict__ x, float t,
-                                             int k0, int k1, int2 *list, int *seg_prefix)
+__device__ __forceinline__ int compact_slice(const __half *__restrict__ x, float t, int k0,
+                                             int k1, int2 *list, int *seg_cnt, int &seg_excl)
 {
+    constexpr int PER_WAVE = kMaxSegs / WAVES;
     const int lane = threadIdx.x & 63;
     const int w = threadIdx.x >> 6;
     const int nseg = (k1 - k0 + 63) >> 6;
 
-    for (int seg = w; seg < nseg; seg += WAVES) {
-        const int i = k0 + seg * 64 + lane;
-        const bool keep = i < k1 && survives(__half2float(x[i]), t);
-        const unsigned long long b = __ballot(keep);
-        if (lane == 0) seg_prefix[seg] = __popcll(b);
-    }
-    __syncthreads();
-    if (w == 0) {
-        const int c = lane < nseg ? seg_prefix[lane] : 0;
-        int incl = c;
+    float xv[PER_WAVE];
+    unsigned long long bal[PER_WAVE];
 #pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const int up = __shfl_up(incl, d);
-            if (lane >= d) incl += up;
-        }
-        if (lane < nseg) seg_prefix[lane] = incl - c;
-        if (lane == 63) seg_prefix[nseg] = incl;
+    for (int j = 0; j < PER_WAVE; ++j) {
+        const int i = k0 + (w + j * WAVES) * 64 + lane;
+        xv[j] = i < k1 ? __half2float(x[i]) : 0.f;    // x = 0 never survives (t >= 0)
+    }
+#pragma unroll
+    for (int j = 0; j < PER_WAVE; ++j) {
+        const int seg = w + j * WAVES;
+        bal[j] = __ballot(survives(xv[j], t));
+        if (lane == 0 && seg < nseg) seg_cnt[seg] = __popcll(bal[j]);
     }
     __syncthreads();
-    for (int seg = w; seg < nseg; seg += WAVES) {
-        const int i = k0 + seg * 64 + lane;
-        float xv = 0.f;
-        bool keep = false;
-        if (i < k1) {
-            xv = __half2float(x[i]);
-            keep = survives(xv, t);
+    const int c = lane < nseg ? seg_cnt[lane] : 0;
+    int incl = c;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int up = __shfl_up(incl, d);
+        if (lane >= d) incl += up;
+    }
+    seg_excl = incl - c;
+    const int total = __builtin_amdgcn_readlane(incl, 63);
+#pragma unroll
+    for (int j = 0; j < PER_WAVE; ++j) {
+        const int seg = w + j * WAVES;
+        if (seg < nseg) {                              // wavefront-uniform
+            const int base = __builtin_amdgcn_readlane(seg_excl, seg);
+            if (survives(xv[j], t))
+                list[base + lanes_below(bal[j])] =
+                    make_int2(k0 + seg * 64 + lane, __float_as_int(xv[j]));
         }
-        const unsigned long long b = __ballot(keep);
-        if (keep) list[seg_prefix[seg] + lanes_below(b)] = make_int2(i, __float_as_int(xv));
     }
     __syncthreads();
-    return seg_prefix[nseg];
+    return total;
 }
 
 // One batch of row loads in flight: U 16-byte vectors per lane and the
@@ -311,13 +320,14 @@ __global__ __launch_bounds__(WAVES * 64) void sparse_gemv_kernel(
     extern __shared__ __align__(16) unsigned char smem[];
     int2 *list = reinterpret_cast<int2 *>(smem);
     float *red = reinterpret_cast<float *>(smem + (size_t)ks * sizeof(int2));
-    __shared__ int seg_prefix[kMaxSegs + 1];
+    __shared__ int seg_cnt[kMaxSegs];
 
     const int tile = blockIdx.x % tiles;
     const int s = blockIdx.x / tiles;
     const int k0 = s * ks;
     const int k1 = min(m, k0 + ks);
-    const int cnt = __builtin_amdgcn_readfirstlane(compact_slice<WAVES>(x, t, k0, k1, list, seg_prefix));
+    int seg_excl;
+    const int cnt = compact_slice<WAVES>(x, t, k0, k1, list, seg_cnt, seg_excl);
 
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);

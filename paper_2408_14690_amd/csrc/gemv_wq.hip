@@ -57,7 +57,7 @@ struct FmtW4 {
 constexpr int kGroup = 128;
 
 // int4: the compacted list is ascending, so each 128-channel group is a run
-// of it, delimited by the segment prefix (two 64-channel segments per group).
+// of it, delimited by the segment prefixes (two 64-channel segments per group).
 // Per group the block's wavefronts split the run, accumulate sum_i x_i q[i][j]
 // unscaled, then fold it into the running sums with that group's scales.
 template <int LPR, int WAVES, int U>
@@ -71,13 +71,14 @@ __global__ __launch_bounds__(WAVES * 64) void sparse_gemv_w4_kernel(
     extern __shared__ __align__(16) unsigned char smem[];
     int2 *list = reinterpret_cast<int2 *>(smem);
     float *red = reinterpret_cast<float *>(smem + (size_t)ks * sizeof(int2));
-    __shared__ int seg_prefix[kMaxSegs + 1];
+    __shared__ int seg_cnt[kMaxSegs];
 
     const int tile = blockIdx.x % tiles;
     const int s = blockIdx.x / tiles;
     const int k0 = s * ks;                       // multiple of 128
     const int k1 = min(m, k0 + ks);
-    compact_slice<WAVES>(x, t, k0, k1, list, seg_prefix);
+    int seg_excl;
+    const int cnt = compact_slice<WAVES>(x, t, k0, k1, list, seg_cnt, seg_excl);
 
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -92,8 +93,9 @@ __global__ __launch_bounds__(WAVES * 64) void sparse_gemv_w4_kernel(
 
     const int ngroups = (k1 - k0) / kGroup;
     for (int gi = 0; gi < ngroups; ++gi) {
-        const int g0 = __builtin_amdgcn_readfirstlane(seg_prefix[2 * gi]);
-        const int g1 = __builtin_amdgcn_readfirstlane(seg_prefix[2 * gi + 2]);
+        // two 64-channel segments per group; the prefix of segment j sits in lane j
+        const int g0 = __builtin_amdgcn_readlane(seg_excl, 2 * gi);
+        const int g1 = 2 * gi + 2 < 64 ? __builtin_amdgcn_readlane(seg_excl, 2 * gi + 2) : cnt;
         int start, mine;
         wave_share(g1 - g0, w, WAVES, start, mine);
         if (mine <= 0) continue;

@@ -24,54 +24,46 @@ int max_splits_for(int m)
     return forced > teal::kMaxSplits ? forced : teal::kMaxSplits;
 }
 
-// Launch shape for one GEMV.  Measured on MI355X, the time of a call is a fixed
-// latency chain (load x, compact, first weight rows; then publish partial rows,
-// ticket, second pass) plus the row stream at HBM speed, and is flat over a wide
-// range of shapes as long as (a) every compute unit has one block of 8
-// wavefronts, (b) the split-K depth (Section 4.4) stays small, so that the
-// partial rows and the second pass are cheap, and (c) a row segment per block is
-// 256 B .. 1 KiB.  So: aim at tiles * splits == number of compute units, prefer
-// about 8 splits, and size the output tile to fit.
+// Launch shape for one GEMV, from sweeps on MI355X.  A call costs a fixed latency
+// chain (load x, compact, first weight rows), the row stream, and with split-K
+// (Section 4.4) the publish / ticket / second-pass chain, which grows with the
+// number of splits.  Measured times are flat over a wide range of shapes as long
+// as (a) there is about one block of 8 wavefronts per compute unit and never a
+// nearly empty second round, (b) the split-K depth is about 8, at most 16, and
+// (c) a block's row segment is 256 B .. 1 KiB and starts on a 128-byte boundary
+// (or neighbouring blocks would each fetch the cache line they share).
 GemvShape auto_shape(int m, int n, int elems_per_lane, int min_lanes, int max_lanes,
                      int ks_multiple)
 {
-    static const int preferred_splits[] = {8, 7, 6, 5, 4, 12, 14, 16, 10, 3, 2, 24, 32, 1, 48, 64, 128};
     const int tc_min = min_lanes * elems_per_lane, tc_max = max_lanes * elems_per_lane;
-    GemvShape best{};
-    double best_cost = 1e30;
-    int rank = 0;
-    for (int asked : preferred_splits) {
-        ++rank;
-        int ks = (m + asked - 1) / asked;
-        ks = (ks + ks_multiple - 1) / ks_multiple * ks_multiple;
-        if (ks > teal::kMaxSlice) continue;
-        if (asked > 1 && ks < 128) continue;                // too few channels per block
-        const int splits = (m + ks - 1) / ks;               // after rounding the slice up
-        const int tiles_wanted = (kComputeUnits + splits / 2) / splits;
-        int tc = (n + tiles_wanted - 1) / tiles_wanted;
-        tc = (tc + elems_per_lane - 1) / elems_per_lane * elems_per_lane;
-        if (tc < tc_min) tc = tc_min;
-        if (tc > tc_max) tc = tc_max;
-        const int tiles = (n + tc - 1) / tc;
-        const double blocks = (double)tiles * splits;
-        double cost = (blocks > kComputeUnits ? (blocks - kComputeUnits) * 2.0 : kComputeUnits - blocks)
-                      / kComputeUnits + 0.01 * rank;
-        if (cost < best_cost) {
-            best_cost = cost;
-            best.splits = splits;
-            best.tile_cols = tc;
-        }
+    const int unit = 8 * elems_per_lane;                       // 128 bytes of a row
+    int tc = (n + 31) / 32;                                    // 32 tiles x 8 splits = 256 blocks
+    tc = (tc + unit - 1) / unit * unit;
+    if (tc < tc_min) tc = tc_min;
+    if (tc > tc_max) tc = tc_max;
+    const int tiles = (n + tc - 1) / tc;
+    int splits = 8;
+    if (tiles * splits > kComputeUnits) splits = kComputeUnits / tiles;
+    if (tiles * splits < 200) {
+        splits = kComputeUnits / tiles;
+        if (splits > 16) splits = 16;
     }
-    if (best_cost == 1e30) {     // very long input: as few splits as the LDS list allows
-        best.splits = (m + teal::kMaxSlice - 1) / teal::kMaxSlice;
-        best.tile_cols = tc_max;
-    }
+    const int most = (m + 127) / 128;                          // at least 128 channels per block
+    if (splits > most) splits = most;
+    const int least = (m + teal::kMaxSlice - 1) / teal::kMaxSlice;   // LDS list capacity
+    if (splits < least) splits = least;
+    if (splits < 1) splits = 1;
+    int ks = (m + splits - 1) / splits;
+    ks = (ks + ks_multiple - 1) / ks_multiple * ks_multiple;
+    GemvShape sh;
+    sh.splits = (m + ks - 1) / ks;
+    sh.tile_cols = tc;
     int lanes = min_lanes;
-    while (lanes * elems_per_lane < best.tile_cols) lanes *= 2;
-    best.lanes_per_row = lanes;
-    best.waves = 8;
-    best.unroll = 4;
-    return best;
+    while (lanes * elems_per_lane < tc) lanes *= 2;
+    sh.lanes_per_row = lanes;
+    sh.waves = 8;
+    sh.unroll = 4;
+    return sh;
 }
 
 struct GemvArgs {
