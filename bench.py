@@ -1,17 +1,22 @@
 #!/usr/bin/env python3
 """Benchmark of the TEAL decode hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llama2_7b]
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+                    [--workload llama2_7b|llama3_8b|llama_70b] [--format bf16|w8|w4]
+                    [--sparsities 0.5,0.4,0] [--layers L]
 
-A step is one pass of the whole hot path over one synthetic decoder block at
+A step is one pass of the whole hot path over a synthetic decoder block at
 batch 1: for each of the seven projections, threshold the hidden state, compact
-the survivors and stream only the surviving weight rows (one C-ABI call per
-projection).  The headline value is the effective HBM bandwidth of that pass at
-50% sparsity (algorithmic bytes / time); the same pass at 40% and at 0% (t = 0,
-the same kernels run dense) gives the speed-up over dense.  Weights, states and
-the workspace are resident in HBM before the timed region.  Consecutive steps
-walk over several copies of the weights so that no step finds its rows in the
-256 MB last-level cache.
+the survivors and stream only the surviving weight rows (one C-ABI call = one
+kernel launch per projection).  The headline value is the effective HBM
+bandwidth of that pass at the first listed sparsity (50% by default):
+algorithmic bytes / time.  The same pass at the other sparsities, and at 0%
+(t = 0, the same kernels run dense), gives the speed-up over dense.  Weights,
+states and the workspace are resident in HBM before the timed region.
+Consecutive steps walk over several copies of the weights so that no step
+finds its rows in the 256 MB last-level cache.  With --layers L > 1 a step is
+a stack of L blocks with their own weights and states (the 80-block
+70B-shaped stack is 137 GB resident), and no copies are needed.
 
 Prints ONE JSON line.  More than one GPU is not supported.
 """
@@ -29,105 +34,193 @@ import teal_inputs as ti
 
 HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published
 CACHE_DEFEAT_BYTES = 3 << 30    # distinct weight bytes walked before a copy is reused
-SPARSITIES = (0.5, 0.4, 0.0)    # headline first
+BITS = {"bf16": 16, "w8": 8, "w4": 4}
+KERNEL = {"bf16": "sparse_gemv_kernel<FmtBF16>", "w8": "sparse_gemv_kernel<FmtW8>",
+          "w4": "sparse_gemv_w4_kernel"}
 # HBM bytes per launch of sparse_gemv_kernel at 50% (average over the 7 launches of a step),
 # from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script, scaled by the factors a
 # plain copy of known size gives on the same box (2.0 and 1.0):
 # profiles/sparse_gemv_kernel_llama2_7b_hbm_traffic.txt.
-MEASURED_TRAFFIC_BYTES = {"llama2_7b": (200310.07 + 1555.31) * 1024 / 7}
+MEASURED_TRAFFIC_BYTES = {("llama2_7b", "bf16", 0.5, 1): (200310.07 + 1555.31) * 1024 / 7}
 
 
-def algorithmic_bytes(nnz: int, m: int, n: int) -> int:
-    """Bytes the method must move for one projection: surviving bf16 rows + x + y."""
-    return nnz * n * 2 + 2 * m + 4 * n
+def algorithmic_bytes(fmt: str, nnz: int, m: int, n: int) -> int:
+    """Bytes the method must move for one projection: surviving rows + x + y + scales."""
+    scales = {"bf16": 0, "w8": 2 * n, "w4": 2 * n * (m // 128)}[fmt]
+    return nnz * n * BITS[fmt] // 8 + 2 * m + 4 * n + scales
 
 
-def build_layer(T, torch, model: str, copies: int):
-    """Seeded block on the host -> device, laid out input-channel-major by the library."""
-    layer = []
-    for proj, n, m, w, x in ti.layer_inputs(model):
-        wd = torch.from_numpy(w.view(np.int16)).cuda()
-        wts = []
-        for c in range(copies):
+class Projection:
+    """One weight matrix resident on the device in the format under test."""
+
+    def __init__(self, T, torch, name, n, m, fmt, x_host, sparsities, copies, w_host=None,
+                 device_seed=None):
+        self.name, self.n, self.m, self.fmt = name, n, m, fmt
+        self.x_host, self.w_host = x_host, w_host
+        self.host_q = None
+        if w_host is None:
+            # weights drawn on the device (harness only), canonical layout, then laid out by the library
+            g = torch.Generator(device="cuda")
+            g.manual_seed(int(device_seed))
+            wd = (torch.randn((n, m), generator=g, device="cuda", dtype=torch.float32) * 0.02) \
+                .to(torch.bfloat16).view(torch.int16)
+        else:
+            wd = torch.from_numpy(w_host.view(np.int16)).cuda()
+        if fmt == "bf16":
             wt = torch.empty((m, n), dtype=torch.int16, device="cuda")
-            if c == 0:
-                T.check(T.teal_pack_bf16(wd, wt, m, n))
+            T.check(T.teal_pack_bf16(wd, wt, m, n))
+            first = (wt,)
+        else:
+            if w_host is None:
+                raise ValueError("quantised formats need host weights")
+            if fmt == "w8":
+                q, scale = ti.quantize_w8(w_host)
             else:
-                wt.copy_(wts[0])
-            wts.append(wt)
+                q, scale = ti.quantize_w4(w_host, 128)
+            self.host_q = (q, scale)
+            first = (torch.from_numpy(q).cuda(), torch.from_numpy(scale.view(np.int16)).cuda())
         del wd
-        thresholds, nnz = {}, {}
-        for p in SPARSITIES:
-            t = ti.quantile_threshold(x, p)
-            thresholds[p] = t
-            nnz[p] = int(np.count_nonzero(np.abs(x.astype(np.float32)) > np.float32(t)))
-        layer.append(dict(
-            proj=proj, n=n, m=m, w_host=w, x_host=x, wt=wts,
-            x=torch.from_numpy(x.view(np.int16)).cuda(),
-            y=torch.empty(n, dtype=torch.float32, device="cuda"),
-            ws=torch.zeros(T.teal_workspace_bytes(m, n), dtype=torch.uint8, device="cuda"),
-            t=thresholds, nnz=nnz))
+        self.weights = [first] + [tuple(t.clone() for t in first) for _ in range(copies - 1)]
+        self.x = torch.from_numpy(x_host.view(np.int16)).cuda()
+        self.y = torch.empty(n, dtype=torch.float32, device="cuda")
+        self.ws = torch.zeros(T.teal_workspace_bytes(m, n), dtype=torch.uint8, device="cuda")
+        self.t, self.nnz = {}, {}
+        for p in sparsities:
+            t = ti.quantile_threshold(x_host, p)
+            self.t[p] = t
+            self.nnz[p] = int(np.count_nonzero(np.abs(x_host.astype(np.float32)) > np.float32(t)))
+
+    def launch(self, T, copy: int, p: float) -> int:
+        w = self.weights[copy % len(self.weights)]
+        if self.fmt == "bf16":
+            return T.teal_sparse_gemv_bf16(w[0], self.x, self.t[p], self.y, self.m, self.n, self.ws)
+        if self.fmt == "w8":
+            return T.teal_sparse_gemv_w8(w[0], w[1], self.x, self.t[p], self.y, self.m, self.n,
+                                         self.ws)
+        return T.teal_sparse_gemv_w4(w[0], w[1], 128, self.x, self.t[p], self.y, self.m, self.n,
+                                     self.ws)
+
+    def bytes(self, p: float) -> int:
+        return algorithmic_bytes(self.fmt, self.nnz[p], self.m, self.n)
+
+    def oracle(self, orc, p: float):
+        if self.fmt == "bf16":
+            return orc.sparse_gemv_bf16(self.w_host, self.x_host, self.t[p])
+        if self.fmt == "w8":
+            return orc.sparse_gemv_w8(self.host_q[0], self.host_q[1], self.x_host, self.t[p])
+        return orc.sparse_gemv_w4(self.host_q[0], self.host_q[1], 128, self.x_host, self.t[p])
+
+
+class FusedGroup:
+    """Projections that read the same hidden state, launched as one kernel (bf16 only)."""
+
+    def __init__(self, T, torch, members):
+        self.members = members
+        self.name = "+".join(P.name for P in members)
+        self.m = members[0].m
+        self.ns = [P.n for P in members]
+        self.ys = [P.y for P in members]
+        self.ws = torch.zeros(T.teal_workspace_bytes(self.m, sum(self.ns)), dtype=torch.uint8,
+                              device="cuda")
+
+    def launch(self, T, copy: int, p: float) -> int:
+        wts = [P.weights[copy % len(P.weights)][0] for P in self.members]
+        return T.teal_sparse_gemv_bf16_multi(wts, [P.t[p] for P in self.members], self.ys, self.ns,
+                                             self.members[0].x, self.m, self.ws)
+
+    def bytes(self, p: float) -> int:
+        # x is read once for the group
+        return sum(P.bytes(p) for P in self.members) - 2 * self.m * (len(self.members) - 1)
+
+
+def fuse(T, torch, stack):
+    """Group consecutive projections of each block that share their input (Appendix A.3)."""
+    out, i = [], 0
+    while i < len(stack):
+        j = i + 1
+        while (j < len(stack) and stack[j].m == stack[i].m
+               and ti.PROJ_XGROUP[stack[j].name] == ti.PROJ_XGROUP[stack[i].name]
+               and ti.PROJ_ORDER.index(stack[j].name) > ti.PROJ_ORDER.index(stack[j - 1].name)):
+            j += 1
+        out.append(FusedGroup(T, torch, stack[i:j]))
+        i = j
+    return out
+
+
+def build_stack(T, torch, model, fmt, sparsities, layers, copies):
+    """`layers` synthetic blocks.  Block 0 comes from the seeded host recipe (so the CPU
+    baseline sees the same numbers); further blocks of a bf16 stack draw their weights on
+    the device."""
+    cfg = ti.CONFIG_INDEX[model]
+    stack = []
+    for layer in range(layers):
+        host = layer == 0 or fmt != "bf16"
+        for proj in ti.PROJ_ORDER:
+            n, m = ti.LAYER_SHAPES[model][proj]
+            x = ti.make_x(m, ti.x_seed(cfg, layer, proj), ti.PROJ_DIST[proj])
+            w = ti.weights_bf16(n, m, ti.weight_seed(cfg, layer, proj)) if host else None
+            stack.append(Projection(T, torch, proj, n, m, fmt, x, sparsities, copies, w_host=w,
+                                    device_seed=ti.weight_seed(cfg, layer, proj)))
+            if layer > 0:
+                stack[-1].w_host = None          # keep host memory flat for deep stacks
+                stack[-1].host_q = None
     torch.cuda.synchronize()
-    return layer
+    return stack
 
 
-def one_step(T, layer, p: float, copy: int) -> None:
-    for L in layer:
-        st = T.teal_sparse_gemv_bf16(L["wt"][copy], L["x"], L["t"][p], L["y"], L["m"], L["n"],
-                                     L["ws"])
+def one_step(T, stack, p: float, copy: int) -> None:
+    for P in stack:
+        st = P.launch(T, copy, p)
         if st != 0:
             T.check(st)
 
 
-def time_steps(T, torch, layer, p: float, steps: int, warmup: int, copies: int) -> float:
-    """Seconds for `steps` back-to-back passes (HIP events on the launch stream)."""
+def time_steps(T, torch, stack, p, steps, warmup) -> float:
+    """Seconds per step over `steps` back-to-back passes (HIP events on the launch stream)."""
     for k in range(warmup):
-        one_step(T, layer, p, k % copies)
+        one_step(T, stack, p, k)
     torch.cuda.synchronize()
     start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     start.record()
     for k in range(steps):
-        one_step(T, layer, p, k % copies)
+        one_step(T, stack, p, k)
     stop.record()
     torch.cuda.synchronize()
-    return start.elapsed_time(stop) * 1e-3
+    return start.elapsed_time(stop) * 1e-3 / steps
 
 
-def time_projection(T, torch, L, p: float, launches: int, copies: int) -> float:
-    """Seconds per call for one projection launched back to back (one kernel per call),
-    walking the weight copies; HIP events on the launch stream around the whole batch."""
-    def run(k):
-        st = T.teal_sparse_gemv_bf16(L["wt"][k % copies], L["x"], L["t"][p], L["y"], L["m"],
-                                     L["n"], L["ws"])
-        if st != 0:
-            T.check(st)
+def time_projection(T, torch, P, p, launches) -> float:
+    """Seconds per call for one projection launched back to back, walking its weight copies."""
     for k in range(20):
-        run(k)
+        P.launch(T, k, p)
     torch.cuda.synchronize()
     start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     start.record()
     for k in range(launches):
-        run(k)
+        P.launch(T, k, p)
     stop.record()
     torch.cuda.synchronize()
     return start.elapsed_time(stop) * 1e-3 / launches
 
 
-def cpu_baseline(layer, p: float, budget_s: float = 12.0):
-    """The fp64 oracle, as it stands, on the host cores: whole passes over the
-    same block until about `budget_s` seconds of CPU work have been spent."""
+def cpu_baseline(block, p: float, budget_s: float = 12.0):
+    """The fp64 oracle, as it stands, on the host cores: whole passes over block 0 until
+    about `budget_s` seconds of CPU work have been spent."""
     from oracle import teal_oracle as orc
     threads = orc.num_threads()
-    for L in layer[:1]:
-        orc.sparse_gemv_bf16(L["w_host"], L["x_host"], L["t"][p])      # warm-up
+    block[0].oracle(orc, p)                                   # warm-up
     passes, spent = 0, 0.0
     while spent < budget_s and passes < 1000:
         t0 = time.perf_counter()
-        for L in layer:
-            orc.sparse_gemv_bf16(L["w_host"], L["x_host"], L["t"][p])
+        for P in block:
+            P.oracle(orc, p)
         spent += time.perf_counter() - t0
         passes += 1
     return spent / passes, passes, threads
+
+
+def pct(p: float) -> str:
+    return f"{int(round(p * 100))}%"
 
 
 def main() -> int:
@@ -136,8 +229,16 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--workload", default="llama2_7b", choices=sorted(ti.LAYER_SHAPES))
+    ap.add_argument("--format", default="bf16", choices=sorted(BITS))
+    ap.add_argument("--sparsities", default="0.5,0.4,0",
+                    help="comma-separated; the first is the headline, 0 (dense) is always included")
+    ap.add_argument("--layers", type=int, default=1, help="blocks per step (a stack when > 1)")
     ap.add_argument("--copies", type=int, default=0, help="weight copies to walk (0 = auto)")
+    ap.add_argument("--fused", action="store_true",
+                    help="one launch per group of projections that share their input "
+                         "(q+k+v, o, gate+up, down) instead of one per projection; bf16 only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-per-projection", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only; --gpus must be 1", file=sys.stderr)
@@ -153,63 +254,80 @@ def main() -> int:
         build.build(verbose=False)
     T.load_library()
 
+    sparsities = [float(s) for s in args.sparsities.split(",")]
+    if 0.0 not in sparsities:
+        sparsities.append(0.0)
+    head = sparsities[0]
+    fmt = args.format
     shapes = ti.LAYER_SHAPES[args.workload]
-    dense_bytes = sum(n * m * 2 for n, m in shapes.values())
-    copies = args.copies or max(2, -(-CACHE_DEFEAT_BYTES // dense_bytes))
-    layer = build_layer(T, torch, args.workload, copies)
+    block_bytes = sum(n * m * BITS[fmt] // 8 for n, m in shapes.values())
+    if args.layers > 1:
+        copies = args.copies or 1
+    else:
+        copies = args.copies or max(2, -(-CACHE_DEFEAT_BYTES // block_bytes))
+    stack = build_stack(T, torch, args.workload, fmt, sparsities, args.layers, copies)
+    block0 = stack[:7]
+    if args.fused:
+        if fmt != "bf16":
+            print("bench.py: --fused is available for bf16 only", file=sys.stderr)
+            return 2
+        stack = fuse(T, torch, stack)
+    launches_per_step = len(stack)
 
     detail, seconds = {}, {}
-    for p in SPARSITIES:
-        sec = time_steps(T, torch, layer, p, args.steps, args.warmup, copies)
-        seconds[p] = sec / args.steps
-        eff = sum(algorithmic_bytes(L["nnz"][p], L["m"], L["n"]) for L in layer)
-        detail[f"{int(round(p * 100))}%"] = {
+    for p in sparsities:
+        seconds[p] = time_steps(T, torch, stack, p, args.steps, args.warmup)
+        eff = sum(P.bytes(p) for P in stack)
+        detail[pct(p)] = {
             "us_per_step": seconds[p] * 1e6,
             "effective_bytes": eff,
             "effective_GBps": eff / seconds[p] / 1e9,
             "frac_of_hbm_peak": eff / seconds[p] / 1e9 / HBM_PEAK_GBS,
         }
-    for p in SPARSITIES:
-        detail[f"{int(round(p * 100))}%"]["speedup_vs_dense"] = seconds[0.0] / seconds[p]
+    for p in sparsities:
+        detail[pct(p)]["speedup_vs_dense"] = seconds[0.0] / seconds[p]
 
-    # Dominant kernel: sparse_gemv_kernel, the only kernel of a call (one launch per
-    # projection).  Its average launch duration is the timed region of the 50% pass
-    # divided by the launches in it; the algorithmic bytes are those of the 7 calls.
-    calls_bytes = sum(algorithmic_bytes(L["nnz"][0.5], L["m"], L["n"]) for L in layer)
-    launches_per_step = len(layer)
-    kernel_avg_us = seconds[0.5] * 1e6 / launches_per_step
-    achieved = calls_bytes / seconds[0.5] / 1e9
+    # Dominant kernel: the sparse GEMV kernel, the only kernel of a call.  Its average launch
+    # duration is the timed region of the headline pass divided by the launches in it.
+    head_bytes = sum(P.bytes(head) for P in stack)
+    achieved = head_bytes / seconds[head] / 1e9
+
     per_proj = {}
-    for L in layer:
-        b = algorithmic_bytes(L["nnz"][0.5], L["m"], L["n"])
-        us = time_projection(T, torch, L, 0.5, 300, copies) * 1e6
-        us_dense = time_projection(T, torch, L, 0.0, 300, copies) * 1e6
-        _, plan = T.teal_gemv_plan(16, L["m"], L["n"])
-        per_proj[L["proj"]] = {
-            "n": L["n"], "m": L["m"], "nnz": L["nnz"][0.5], "us": us, "us_dense": us_dense,
-            "effective_GBps": b / us / 1e3, "frac_of_hbm_peak": b / us / 1e3 / HBM_PEAK_GBS,
-            "speedup_vs_dense": us_dense / us, "launch": plan,
-        }
+    if not args.no_per_projection and not args.fused:
+        for P in block0:
+            us = time_projection(T, torch, P, head, 300) * 1e6
+            us_dense = time_projection(T, torch, P, 0.0, 300) * 1e6
+            _, plan = T.teal_gemv_plan(BITS[fmt], P.m, P.n)
+            b = P.bytes(head)
+            per_proj[P.name] = {
+                "n": P.n, "m": P.m, "nnz": P.nnz[head], "us": us, "us_dense": us_dense,
+                "effective_GBps": b / us / 1e3, "frac_of_hbm_peak": b / us / 1e3 / HBM_PEAK_GBS,
+                "speedup_vs_dense": us_dense / us, "launch": plan,
+            }
 
     out = {
-        "metric": "sparse GEMV effective HBM GB/s at 50% sparsity (one decoder-block pass); "
-                  "us and speedup vs dense at 0/40/50% in detail",
-        "value": detail["50%"]["effective_GBps"],
+        "metric": f"sparse GEMV effective HBM GB/s at {pct(head)} sparsity (one decoder-block "
+                  f"pass); us and speedup vs dense per sparsity in detail",
+        "value": detail[pct(head)]["effective_GBps"],
         "unit": "GB/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": seconds[0.5] * 1e3,
+        "ms_per_step": seconds[head] * 1e3,
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
         "config": {
-            "workload": f"{args.workload}-shaped decoder block, 7 projections, batch 1, bf16 W "
-                        f"(N(0,0.02^2)), fp16 x (Gaussian / Laplace by role), t at the 50% "
-                        f"quantile of |x| per projection",
-            "dense_weight_bytes": dense_bytes,
+            "workload": f"{args.workload}-shaped decoder block x {args.layers}, 7 projections "
+                        f"each, batch 1, {fmt} W from N(0,0.02^2), fp16 x (Gaussian / Laplace by "
+                        f"role), t at the {pct(head)} quantile of |x| per projection",
+            "weight_format": fmt,
+            "weight_bytes_per_block": block_bytes,
+            "blocks_per_step": args.layers,
+            "launches": "one per group of projections sharing their input (q+k+v, o, gate+up, "
+                        "down)" if args.fused else "one per projection",
             "weight_copies_walked": copies,
         },
         "roofline": {
@@ -218,24 +336,26 @@ def main() -> int:
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
-            "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
-            "kernel": "sparse_gemv_kernel (one launch per projection; 7 launches per step, 50%)",
-            "bytes_per_launch_avg": calls_bytes / launches_per_step,
-            "kernel_avg_us": kernel_avg_us,
+            "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, fmt, head, args.layers)),
+            "kernel": f"{'sparse_gemv_multi_kernel<FmtBF16>' if args.fused else KERNEL[fmt]} "
+                      f"({launches_per_step} launches per step, {pct(head)})",
+            "bytes_per_launch_avg": head_bytes / launches_per_step,
+            "kernel_avg_us": seconds[head] * 1e6 / launches_per_step,
         },
         "detail": detail,
-        "per_projection_50%": per_proj,
+        f"per_projection_{pct(head)}": per_proj,
     }
     if not args.no_cpu_baseline:
-        sec, passes, threads = cpu_baseline(layer, 0.5)
+        sec, passes, threads = cpu_baseline(block0, head)
+        block_head_bytes = sum(P.bytes(head) for P in block0)
         out["cpu_baseline"] = {
-            "value": calls_bytes / sec / 1e9,
+            "value": block_head_bytes / sec / 1e9,
             "unit": "GB/s",
             "cores": threads,
             "kind": "oracle",
-            "sample": f"{passes} whole passes over the same block at 50% (fp64 dense loop over "
+            "sample": f"{passes} whole passes over block 0 at {pct(head)} (fp64 dense loop over "
                       f"the zeroed x), {sec * 1e3:.1f} ms per pass",
-            "ms_per_step": sec * 1e3,
+            "ms_per_step": sec * 1e3 * args.layers,
         }
     print(json.dumps(out))
     return 0

@@ -99,6 +99,25 @@ teal_status teal_sparse_gemv_bf16(const void *Wt_bf16, const void *x_f16, float 
                                   void *stream);
 
 /*
+ * Several matrices that read the same hidden state, in one kernel launch:
+ * y_k = s_{t_k}(x) W_k^T for k = 0 .. count-1.  Within a Transformer block
+ * W_q, W_k, W_v share their input, and so do W_gate and W_up (Appendix A.3);
+ * each matrix keeps its own threshold (the per-matrix sparsity levels of
+ * Section 4.2).  Results are bitwise those of count separate calls of
+ * teal_sparse_gemv_bf16_ex with the same launch shape.
+ *   count   1..4.
+ *   Wt_bf16, t, y, n   HOST arrays of length count: device pointers to the
+ *           matrices ([m][n_k] bf16, 16-byte aligned), thresholds, device
+ *           pointers to the outputs (y_k: n_k fp32) and the output widths
+ *           (n_k % 8 == 0).  Read during the call only.
+ *   x_f16   [m] fp16, shared.
+ *   workspace  at least teal_workspace_bytes(m, n_0 + ... + n_{count-1}).
+ */
+teal_status teal_sparse_gemv_bf16_multi(int count, const void *const *Wt_bf16, const float *t,
+                                        float *const *y, const int *n, const void *x_f16, int m,
+                                        void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * The same product for 8-bit channel-wise quantised weights (Section 5.3):
  * W[j][i] = Wq[i][j] * scale[j].
  *   Wq    [m][n] int8 (symmetric, two's complement), 16-byte aligned.

@@ -25,7 +25,7 @@ _lib = None
 EXPORTS = (
     "teal_status_string", "teal_version", "teal_workspace_bytes", "teal_sparsify",
     "teal_sparse_gemv_bf16", "teal_sparse_gemv_bf16_ex", "teal_sparse_gemv_w8",
-    "teal_sparse_gemv_w4", "teal_pack_bf16", "teal_gemv_plan",
+    "teal_sparse_gemv_w4", "teal_pack_bf16", "teal_gemv_plan", "teal_sparse_gemv_bf16_multi",
 )
 
 
@@ -68,6 +68,9 @@ def load_library():
     lib.teal_sparse_gemv_w4.argtypes = [vp, vp, i, vp, f, vp, i, i, vp, sz, vp]
     lib.teal_pack_bf16.restype = i
     lib.teal_pack_bf16.argtypes = [vp, vp, i, i, vp]
+    lib.teal_sparse_gemv_bf16_multi.restype = i
+    lib.teal_sparse_gemv_bf16_multi.argtypes = [i, c.POINTER(vp), c.POINTER(f), c.POINTER(vp),
+                                                c.POINTER(i), vp, i, vp, sz, vp]
     ip = c.POINTER(c.c_int)
     lib.teal_gemv_plan.restype = i
     lib.teal_gemv_plan.argtypes = [i, i, i, ip, ip, ip, ip, ip]
@@ -168,3 +171,18 @@ def teal_gemv_plan(weight_bits: int, m: int, n: int):
                                        *[ctypes.byref(v) for v in vals])
     keys = ("lanes_per_row", "tile_cols", "splits", "waves", "unroll")
     return st, {k: v.value for k, v in zip(keys, vals)}
+
+
+def teal_sparse_gemv_bf16_multi(Wt_list, t_list, y_list, n_list, x_f16, m, workspace,
+                                workspace_bytes=None, stream=None) -> int:
+    """count = len(Wt_list) matrices sharing x; the per-matrix lists become host arrays."""
+    count = len(Wt_list)
+    if not (len(t_list) == len(y_list) == len(n_list) == count):
+        raise ValueError("per-matrix lists must have the same length")
+    W = (ctypes.c_void_p * count)(*[_ptr(w) for w in Wt_list])
+    Y = (ctypes.c_void_p * count)(*[_ptr(y) for y in y_list])
+    Tt = (ctypes.c_float * count)(*[float(t) for t in t_list])
+    N = (ctypes.c_int * count)(*[int(n) for n in n_list])
+    return load_library().teal_sparse_gemv_bf16_multi(
+        count, W, Tt, Y, N, _ptr(x_f16), int(m), _ptr(workspace),
+        _nbytes(workspace, workspace_bytes), _stream(stream))

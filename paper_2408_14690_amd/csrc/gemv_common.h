@@ -304,26 +304,20 @@ __device__ __forceinline__ int lane_column(int col0, int cols, int n, int l)
     return col;
 }
 
-// Generic kernel for formats with no per-group state (bf16, int8).
-// Grid: tiles * splits blocks; block id -> (tile, split) with the tile index
-// fastest, so that the blocks dealt round-robin to the 8 XCDs at any moment
-// read neighbouring column ranges of the same rows, and every XCD gets the
-// same number of blocks (+-1).  tile_cols (a multiple of EPL, <= LPR * EPL)
-// is the width of an output tile.
+// Work of one block for formats with no per-group state (bf16, int8): output
+// tile `tile` (tile_cols columns) x K-slice `s` (ks channels) of one matrix.
 template <class F, int LPR, int WAVES, int U>
-__global__ __launch_bounds__(WAVES * 64) void sparse_gemv_kernel(
-    typename F::Args a, const __half *__restrict__ x, float t, float *partial, int *counters,
-    float *y, int m, int n, int ks, int tiles, int tile_cols, int splits)
+__device__ __forceinline__ void gemv_block(const typename F::Args &a, const __half *__restrict__ x,
+                                           float t, float *partial, int *counters, float *y, int m,
+                                           int n, int ks, int tile, int s, int tile_cols,
+                                           int splits)
 {
     constexpr int EPL = F::kElemsPerLane;
-    constexpr int TN = LPR * EPL;
     extern __shared__ __align__(16) unsigned char smem[];
     int2 *list = reinterpret_cast<int2 *>(smem);
     float *red = reinterpret_cast<float *>(smem + (size_t)ks * sizeof(int2));
     __shared__ int seg_cnt[kMaxSegs];
 
-    const int tile = blockIdx.x % tiles;
-    const int s = blockIdx.x / tiles;
     const int k0 = s * ks;
     const int k1 = min(m, k0 + ks);
     int seg_excl;
@@ -347,7 +341,59 @@ __global__ __launch_bounds__(WAVES * 64) void sparse_gemv_kernel(
     fold_row_groups<LPR>(acc);
     block_finish<F, LPR, WAVES>(acc, red, partial, counters, y, tile, col0, tile_cols, s, splits, n,
                                 a);
-    (void)TN;
+}
+
+// One matrix per launch.  Grid: tiles * splits blocks; block id -> (tile,
+// split) with the tile index fastest, so that the blocks dealt round-robin to
+// the 8 XCDs at any moment read neighbouring column ranges of the same rows,
+// and every XCD gets the same number of blocks (+-1).  tile_cols (a multiple
+// of EPL, <= LPR * EPL) is the width of an output tile.
+template <class F, int LPR, int WAVES, int U>
+__global__ __launch_bounds__(WAVES * 64) void sparse_gemv_kernel(
+    typename F::Args a, const __half *__restrict__ x, float t, float *partial, int *counters,
+    float *y, int m, int n, int ks, int tiles, int tile_cols, int splits)
+{
+    gemv_block<F, LPR, WAVES, U>(a, x, t, partial, counters, y, m, n, ks, blockIdx.x % tiles,
+                                 blockIdx.x / tiles, tile_cols, splits);
+}
+
+// Several matrices that read the same hidden state (q/k/v, or gate/up:
+// Appendix A.3), each with its own threshold (the per-matrix sparsity levels of
+// Section 4.2), in one launch: the launch latency and the serial ends of a
+// call are paid once.  The matrices' tiles are laid side by side; a block
+// finds its matrix from its tile index.
+constexpr int kMaxMulti = 4;
+
+template <class F>
+struct MultiArgs {
+    typename F::Args a[kMaxMulti];
+    float *y[kMaxMulti];
+    float t[kMaxMulti];
+    int n[kMaxMulti];
+    int tile_begin[kMaxMulti + 1];   // first tile of each matrix; [count] = all tiles
+    int count;
+};
+
+template <class F, int LPR, int WAVES, int U>
+__global__ __launch_bounds__(WAVES * 64) void sparse_gemv_multi_kernel(
+    MultiArgs<F> ma, const __half *__restrict__ x, float *partial, int *counters, int m, int ks,
+    int tile_cols, int splits)
+{
+    const int tiles = ma.tile_begin[ma.count];
+    const int gtile = blockIdx.x % tiles;
+    const int s = blockIdx.x / tiles;
+    int k = 0;
+    size_t partial_off = 0;            // each matrix owns splits * n floats of partial rows
+#pragma unroll
+    for (int j = 1; j < kMaxMulti; ++j) {
+        if (j < ma.count && gtile >= ma.tile_begin[j]) {
+            partial_off += (size_t)splits * ma.n[j - 1];
+            k = j;
+        }
+    }
+    gemv_block<F, LPR, WAVES, U>(ma.a[k], x, ma.t[k], partial + partial_off,
+                                 counters + ma.tile_begin[k], ma.y[k], m, ma.n[k], ks,
+                                 gtile - ma.tile_begin[k], s, tile_cols, splits);
 }
 
 // Host-side launch geometry shared by the formats.

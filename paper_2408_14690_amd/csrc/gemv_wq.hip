@@ -56,18 +56,32 @@ struct FmtW4 {
 
 constexpr int kGroup = 128;
 
+// One 128-channel group's worth of work of one wavefront: its share of the
+// group's surviving rows (at most 128 / WAVES of them, LOADS wavefront loads)
+// and the group's scales for this lane's 32 columns.
+template <int LOADS>
+struct GroupBatch {
+    u32x4 v[LOADS];
+    float xv[LOADS];
+    uint4 sc[4];      // 32 fp16 scales
+    int mine;         // rows in this batch (wavefront-uniform)
+};
+
 // int4: the compacted list is ascending, so each 128-channel group is a run
 // of it, delimited by the segment prefixes (two 64-channel segments per group).
 // Per group the block's wavefronts split the run, accumulate sum_i x_i q[i][j]
 // unscaled, then fold it into the running sums with that group's scales.
-template <int LPR, int WAVES, int U>
+// Groups are software-pipelined: the rows and scales of the next group are in
+// flight while the current one is multiplied out.
+template <int LPR, int WAVES>
 __global__ __launch_bounds__(WAVES * 64) void sparse_gemv_w4_kernel(
     FmtW4::Args a, const __half *__restrict__ x, float t, float *partial, int *counters, float *y,
     int m, int n, int ks, int tiles, int tile_cols, int splits)
 {
     using F = FmtW4;
     constexpr int EPL = F::kElemsPerLane;
-    constexpr int TN = LPR * EPL;
+    constexpr int R = 64 / LPR;
+    constexpr int LOADS = (kGroup / WAVES + R - 1) / R;   // covers a group in which every row survives
     extern __shared__ __align__(16) unsigned char smem[];
     int2 *list = reinterpret_cast<int2 *>(smem);
     float *red = reinterpret_cast<float *>(smem + (size_t)ks * sizeof(int2));
@@ -81,34 +95,49 @@ __global__ __launch_bounds__(WAVES * 64) void sparse_gemv_w4_kernel(
     const int cnt = compact_slice<WAVES>(x, t, k0, k1, list, seg_cnt, seg_excl);
 
     const int lane = threadIdx.x & 63;
+    const int g = lane / LPR;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int col0 = tile * tile_cols;
     const int col = lane_column<EPL>(col0, tile_cols, n, lane % LPR);
     const unsigned row_bytes = (unsigned)(n / 2);
     const unsigned char *lane_base = static_cast<const unsigned char *>(a.W) + col / 2;
+    const __half *scale_base = a.scale + (size_t)(k0 / kGroup) * n + col;
 
     float acc[EPL];
 #pragma unroll
     for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
 
-    const int ngroups = (k1 - k0) / kGroup;
-    for (int gi = 0; gi < ngroups; ++gi) {
+    auto issue = [&](GroupBatch<LOADS> &b, int gi) {
         // two 64-channel segments per group; the prefix of segment j sits in lane j
         const int g0 = __builtin_amdgcn_readlane(seg_excl, 2 * gi);
         const int g1 = 2 * gi + 2 < 64 ? __builtin_amdgcn_readlane(seg_excl, 2 * gi + 2) : cnt;
         int start, mine;
         wave_share(g1 - g0, w, WAVES, start, mine);
-        if (mine <= 0) continue;
+        b.mine = mine;
+        if (mine <= 0) return;                    // wavefront-uniform
+        const int last = mine - 1;
+#pragma unroll
+        for (int u = 0; u < LOADS; ++u) {
+            const int e = u * R + g;
+            const int2 ent = list[g0 + start + min(e, last)];
+            b.xv[u] = e <= last ? __int_as_float(ent.y) : 0.f;
+            b.v[u] = load_stream16(lane_base + (size_t)(unsigned)ent.x * row_bytes);
+        }
+        const uint4 *sp = reinterpret_cast<const uint4 *>(scale_base + (size_t)gi * n);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) b.sc[q] = sp[q];
+    };
+    auto consume = [&](const GroupBatch<LOADS> &b) {
+        if (b.mine <= 0) return;
         float gacc[EPL];
 #pragma unroll
         for (int e = 0; e < EPL; ++e) gacc[e] = 0.f;
-        stream_rows<F, LPR, U>(gacc, list, g0 + start, mine, lane_base, row_bytes);
-        const uint4 *sp = reinterpret_cast<const uint4 *>(
-            a.scale + (size_t)(k0 / kGroup + gi) * n + col);
 #pragma unroll
-        for (int q = 0; q < EPL / 8; ++q) {
-            const uint4 sv = sp[q];
-            const unsigned sw[4] = {sv.x, sv.y, sv.z, sv.w};
+        for (int u = 0; u < LOADS; ++u)
+            if (u * R < b.mine) F::fma(gacc, b.v[u], b.xv[u]);      // wavefront-uniform
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const unsigned sw[4] = {b.sc[q].x, b.sc[q].y, b.sc[q].z, b.sc[q].w};
 #pragma unroll
             for (int h = 0; h < 4; ++h) {
                 const float s0 = __half2float(__ushort_as_half((unsigned short)(sw[h] & 0xffffu)));
@@ -117,11 +146,28 @@ __global__ __launch_bounds__(WAVES * 64) void sparse_gemv_w4_kernel(
                 acc[8 * q + 2 * h + 1] = fmaf(s1, gacc[8 * q + 2 * h + 1], acc[8 * q + 2 * h + 1]);
             }
         }
+    };
+
+    const int ngroups = (k1 - k0) / kGroup;       // >= 1
+    GroupBatch<LOADS> b0, b1;
+    issue(b0, 0);
+    int gi = 0;
+    for (; gi + 2 < ngroups; gi += 2) {
+        issue(b1, gi + 1);
+        consume(b0);
+        issue(b0, gi + 2);
+        consume(b1);
+    }
+    if (gi + 1 < ngroups) {
+        issue(b1, gi + 1);
+        consume(b0);
+        consume(b1);
+    } else {
+        consume(b0);
     }
     fold_row_groups<LPR>(acc);
     block_finish<F, LPR, WAVES>(acc, red, partial, counters, y, tile, col0, tile_cols, s, splits, n,
                                 a);
-    (void)TN;
 }
 
 hipError_t launch_gemv_w8(const int8_t *Wq, const void *scale_f16, const void *x_f16, float t,
@@ -144,17 +190,20 @@ hipError_t launch_gemv_w4(const uint8_t *Wq, const void *scale_f16, const void *
                           float *y, int m, int n, float *partial, int *counters,
                           const GemvShape &sh, hipStream_t stream)
 {
-    const GemvGeometry g = gemv_geometry(m, n, sh, FmtW4::kElemsPerLane, kGroup);
+    GemvShape w4 = sh;
+    w4.waves = 8;                                 // the int4 kernel is built for 8 wavefronts
+    const GemvGeometry g = gemv_geometry(m, n, w4, FmtW4::kElemsPerLane, kGroup);
     FmtW4::Args a{Wq, static_cast<const __half *>(scale_f16)};
     const __half *x = static_cast<const __half *>(x_f16);
-#define TEAL_LAUNCH(F, LPR, WAVES, U)                                                          \
-    hipLaunchKernelGGL((sparse_gemv_w4_kernel<LPR, WAVES, U>), dim3(g.tiles * g.splits), \
+#define TEAL_LAUNCH_W4(LPR, WAVES)                                                             \
+    hipLaunchKernelGGL((sparse_gemv_w4_kernel<LPR, WAVES>), dim3(g.tiles * g.splits),           \
                        dim3(WAVES * 64), g.lds, stream, a, x, t, partial, counters, y, m, n,   \
                        g.ks, g.tiles, g.tile_cols, g.splits)
-    // 64 lanes per row would be a 2048-column tile: not offered for int4.
-    if (sh.lanes_per_row == 32) TEAL_DISPATCH_WU(TEAL_LAUNCH, FmtW4, 32, sh);
-    else TEAL_DISPATCH_WU(TEAL_LAUNCH, FmtW4, 16, sh);
-#undef TEAL_LAUNCH
+    // A lane covers 32 columns: 16 lanes per row (tiles up to 512 columns) or 32 lanes
+    // per row (up to 1024 columns).
+    if (sh.lanes_per_row == 32) TEAL_LAUNCH_W4(32, 8);
+    else TEAL_LAUNCH_W4(16, 8);
+#undef TEAL_LAUNCH_W4
     return hipGetLastError();
 }
 

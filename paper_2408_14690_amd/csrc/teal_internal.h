@@ -11,6 +11,7 @@ namespace teal {
 constexpr int kMaxSplits = 128;     // upper bound on split-K blocks along the input dimension
 constexpr int kMaxSlice = 4096;     // most input channels one block compacts (LDS list capacity)
 constexpr int kMaxDim = 1 << 24;    // largest m or n accepted
+constexpr int kMaxMatrices = 4;     // matrices per fused launch
 constexpr int kMinTile = 64;        // narrowest output tile of any kernel variant
 // Head of the workspace: one arrival counter per output tile (zero between calls).
 constexpr size_t kCounterBytes = (size_t)(kMaxDim / kMinTile) * sizeof(int);
@@ -33,6 +34,11 @@ hipError_t launch_sparsify(const void *x_f16, int m, float t, uint8_t *mask,
 hipError_t launch_gemv_bf16(const void *Wt, const void *x_f16, float t, float *y,
                             int m, int n, float *partial, int *counters,
                             const GemvShape &shape, hipStream_t stream);
+
+hipError_t launch_gemv_bf16_multi(int count, const void *const *Wt, const float *t,
+                                  float *const *y, const int *n, const void *x_f16, int m,
+                                  float *partial, int *counters, const GemvShape &shape,
+                                  hipStream_t stream);
 
 hipError_t launch_gemv_w8(const int8_t *Wq, const void *scale_f16, const void *x_f16,
                           float t, float *y, int m, int n, float *partial, int *counters,

@@ -118,6 +118,37 @@ def test_quantised_argument_errors():
     assert T.teal_sparse_gemv_w4(W, SC, 128, X, 0.5, Y, 4096, 4096, WS, 16, 0) == T.TEAL_ERR_WORKSPACE
 
 
+def test_multi_argument_errors():
+    ok = dict(Wt_list=[W, W + 0x1000], t_list=[0.5, 0.25], y_list=[Y, Y + 0x1000],
+              n_list=[4096, 1024], x_f16=X, m=4096, workspace=WS, workspace_bytes=BIG, stream=0)
+
+    def call(**kw):
+        a = dict(ok)
+        a.update(kw)
+        return T.teal_sparse_gemv_bf16_multi(**a)
+
+    assert call(Wt_list=[W, None]) == T.TEAL_ERR_NULL
+    assert call(y_list=[None, Y]) == T.TEAL_ERR_NULL
+    assert call(x_f16=None) == T.TEAL_ERR_NULL
+    assert call(n_list=[4096, 1020]) == T.TEAL_ERR_SHAPE
+    assert call(m=0) == T.TEAL_ERR_SHAPE
+    assert call(Wt_list=[W, W + 8]) == T.TEAL_ERR_ALIGN
+    assert call(t_list=[0.5, -1.0]) == T.TEAL_ERR_THRESHOLD
+    assert call(workspace_bytes=T.teal_workspace_bytes(4096, 5120) - 1) == T.TEAL_ERR_WORKSPACE
+    five = dict(Wt_list=[W] * 5, t_list=[0.5] * 5, y_list=[Y] * 5, n_list=[64] * 5)
+    assert call(**five) == T.TEAL_ERR_UNSUPPORTED
+    assert T.teal_sparse_gemv_bf16_multi([], [], [], [], X, 4096, WS, BIG, 0) == T.TEAL_ERR_UNSUPPORTED
+
+
+def test_plan_is_reported():
+    st, plan = T.teal_gemv_plan(16, 4096, 14336)
+    assert st == T.TEAL_OK
+    assert plan["tile_cols"] % 64 == 0 and plan["tile_cols"] <= 8 * plan["lanes_per_row"]
+    assert 1 <= plan["splits"] <= 16 and plan["waves"] in (4, 8, 16)
+    assert T.teal_gemv_plan(12, 4096, 4096)[0] == T.TEAL_ERR_UNSUPPORTED
+    assert T.teal_gemv_plan(16, 0, 4096)[0] == T.TEAL_ERR_SHAPE
+
+
 def test_sparsify_and_pack_argument_errors():
     assert T.teal_sparsify(None, 16, 0.5, Y, None, None, stream=0) == T.TEAL_ERR_NULL
     assert T.teal_sparsify(X, -1, 0.5, Y, None, None, stream=0) == T.TEAL_ERR_SHAPE

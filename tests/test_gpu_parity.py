@@ -291,6 +291,51 @@ def test_gemv_bf16_70b_shape_sampled_rows(T):
 
 
 # ---------------------------------------------------------------------------
+# several matrices sharing one hidden state in one launch
+# ---------------------------------------------------------------------------
+
+MULTI = [
+    ("llama3 q,k,v", [4096, 1024, 1024], 4096, [0.5, 0.4, 0.25]),
+    ("llama2 gate,up", [11008, 11008], 4096, [0.5, 0.5]),
+    ("llama3 gate,up", [14336, 14336], 4096, [0.4, 0.5]),
+    ("ragged", [520, 24, 136, 8], 333, [0.0, 0.5, 0.9, 1.0]),
+    ("single", [1032], 2049, [0.5]),
+]
+
+
+@pytest.mark.parametrize("name,ns,m,ps", MULTI, ids=[c[0] for c in MULTI])
+def test_gemv_bf16_multi(T, name, ns, m, ps):
+    x = ti.gaussian_x(m, 900 + m)
+    xd = dev(x)
+    ws = workspace(T, m, sum(ns))
+    ws1 = workspace(T, m, max(ns))
+    ws_host, wts, ts, ys = [], [], [], []
+    for k, (n, p) in enumerate(zip(ns, ps)):
+        w = ti.weights_bf16(n, m, seed=1000 * k + n + m)
+        ws_host.append(w)
+        wts.append(dev(ti.to_input_channel_major(w)))
+        ts.append(ti.quantile_threshold(x, p))
+        ys.append(torch.full((n,), float("nan"), dtype=torch.float32, device="cuda"))
+    T.check(T.teal_sparse_gemv_bf16_multi(wts, ts, ys, ns, xd, m, ws))
+    torch.cuda.synchronize()
+    st, plan = T.teal_gemv_plan(16, m, sum(ns))
+    assert st == 0
+    for k, n in enumerate(ns):
+        got = ys[k].cpu().numpy()
+        want = orc.sparse_gemv_bf16(ws_host[k], x, ts[k])
+        assert rel_l2(got, want) <= TIGHT, (name, k)
+        # bitwise the separate call with the same launch shape
+        alone = run_bf16(T, wts[k], xd, ts[k], m, n, ws1, **plan)
+        assert np.array_equal(got, alone), (name, k)
+    # the shared workspace is left ready: a second fused call gives the same bits
+    ys2 = [torch.full((n,), float("nan"), dtype=torch.float32, device="cuda") for n in ns]
+    T.check(T.teal_sparse_gemv_bf16_multi(wts, ts, ys2, ns, xd, m, ws))
+    torch.cuda.synchronize()
+    for a, b in zip(ys, ys2):
+        assert torch.equal(a, b)
+
+
+# ---------------------------------------------------------------------------
 # weight-quantised variants
 # ---------------------------------------------------------------------------
 
