@@ -40,14 +40,27 @@ struct FmtW4 {
         const void *W;
         const __half *scale;
     };
+    // Converting a nibble to fp32 the plain way costs two instructions per element.
+    // Instead: q + 8 (the nibble with its top bit flipped) is placed in the top four
+    // mantissa bits of an fp16 1.0, two nibbles per 32-bit operation, which gives
+    // v = 1 + (q + 8) / 16 in [1, 2), i.e. q = 16 (v - 1.5).  The FMA then reads the
+    // fp16 halves directly, and the affine map is undone once per group from
+    // sum x*v and sum x (both exact products, fp32 sums).
+    static constexpr float kAffineScale = 16.f;    // q = kAffineScale * (v - kAffineOffset)
+    static constexpr float kAffineOffset = 1.5f;
     static __device__ __forceinline__ void fma(float (&acc)[32], u32x4 v, float xv)
     {
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
+            const uint32_t d = v[q] ^ 0x88888888u;
 #pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                const int wq = (int)(v[q] << (28 - 4 * k)) >> 28;   // sign-extend nibble k
-                acc[8 * q + k] = fmaf(xv, (float)wq, acc[8 * q + k]);
+            for (int k = 0; k < 4; ++k) {
+                // nibble k -> bits 6..9, nibble k + 4 -> bits 22..25
+                const uint32_t sh = k == 0 ? d << 6 : k == 1 ? d << 2 : k == 2 ? d >> 2 : d >> 6;
+                const uint32_t pair = (sh & 0x03C003C0u) | 0x3C003C00u;
+                const __half2 h = *reinterpret_cast<const __half2 *>(&pair);
+                acc[8 * q + k] = fmaf(__low2float(h), xv, acc[8 * q + k]);
+                acc[8 * q + k + 4] = fmaf(__high2float(h), xv, acc[8 * q + k + 4]);
             }
         }
     }
@@ -132,18 +145,26 @@ __global__ __launch_bounds__(WAVES * 64) void sparse_gemv_w4_kernel(
         float gacc[EPL];
 #pragma unroll
         for (int e = 0; e < EPL; ++e) gacc[e] = 0.f;
+        float xsum = 0.f;                         // sum of x over this lane's rows of the group
 #pragma unroll
-        for (int u = 0; u < LOADS; ++u)
-            if (u * R < b.mine) F::fma(gacc, b.v[u], b.xv[u]);      // wavefront-uniform
+        for (int u = 0; u < LOADS; ++u) {
+            if (u * R < b.mine) {                 // wavefront-uniform
+                F::fma(gacc, b.v[u], b.xv[u]);
+                xsum += b.xv[u];
+            }
+        }
+        // sum x*q = 16 (sum x*v - 1.5 sum x); then times the group's scale
+        const float corr = -F::kAffineScale * F::kAffineOffset * xsum;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const unsigned sw[4] = {b.sc[q].x, b.sc[q].y, b.sc[q].z, b.sc[q].w};
 #pragma unroll
             for (int h = 0; h < 4; ++h) {
-                const float s0 = __half2float(__ushort_as_half((unsigned short)(sw[h] & 0xffffu)));
-                const float s1 = __half2float(__ushort_as_half((unsigned short)(sw[h] >> 16)));
-                acc[8 * q + 2 * h] = fmaf(s0, gacc[8 * q + 2 * h], acc[8 * q + 2 * h]);
-                acc[8 * q + 2 * h + 1] = fmaf(s1, gacc[8 * q + 2 * h + 1], acc[8 * q + 2 * h + 1]);
+                const __half2 sh = *reinterpret_cast<const __half2 *>(&sw[h]);
+                const float q0 = fmaf(gacc[8 * q + 2 * h], F::kAffineScale, corr);
+                const float q1 = fmaf(gacc[8 * q + 2 * h + 1], F::kAffineScale, corr);
+                acc[8 * q + 2 * h] = fmaf(__low2float(sh), q0, acc[8 * q + 2 * h]);
+                acc[8 * q + 2 * h + 1] = fmaf(__high2float(sh), q1, acc[8 * q + 2 * h + 1]);
             }
         }
     };
