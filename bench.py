@@ -251,6 +251,7 @@ def main() -> int:
                          "(q+k+v, o, gate+up, down) instead of one per projection; bf16 only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-per-projection", action="store_true")
+    ap.add_argument("--no-fused-detail", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only; --gpus must be 1", file=sys.stderr)
@@ -305,6 +306,22 @@ def main() -> int:
     head_bytes = sum(P.bytes(head) for P in stack)
     achieved = head_bytes / seconds[head] / 1e9
 
+    # The same pass with one launch per group of projections that share their input
+    # (q+k+v, o, gate+up, down: Appendix A.3) through teal_sparse_gemv_bf16_multi.
+    fused_detail = {}
+    if fmt == "bf16" and not args.fused and not args.no_fused_detail:
+        groups = fuse(T, torch, stack)
+        fsec = {p: time_steps(T, torch, groups, p, args.steps, args.warmup) for p in sparsities}
+        for p in sparsities:
+            eff = sum(G.bytes(p) for G in groups)
+            fused_detail[pct(p)] = {
+                "us_per_step": fsec[p] * 1e6, "launches_per_step": len(groups),
+                "effective_GBps": eff / fsec[p] / 1e9,
+                "frac_of_hbm_peak": eff / fsec[p] / 1e9 / HBM_PEAK_GBS,
+                "speedup_vs_dense": fsec[0.0] / fsec[p],
+            }
+        del groups
+
     per_proj = {}
     if not args.no_per_projection and not args.fused:
         for P in block0:
@@ -356,6 +373,7 @@ def main() -> int:
             "kernel_avg_us": seconds[head] * 1e6 / launches_per_step,
         },
         "detail": detail,
+        "detail_fused_launches": fused_detail,
         f"per_projection_{pct(head)}": per_proj,
     }
     if not args.no_cpu_baseline:

@@ -55,6 +55,21 @@ __device__ __forceinline__ int lanes_below(unsigned long long b)
                                           __builtin_amdgcn_mbcnt_lo((unsigned)b, 0u));
 }
 
+// Inclusive prefix sum over the 64 lanes of a wavefront with data-parallel
+// primitives (no LDS round trips): shifts by 1, 2, 4, 8 within each row of 16
+// lanes, then lane 15 of row 0 / 2 is added to row 1 / 3 and lane 31 to rows
+// 2 and 3.  Lanes shifted in from outside a row contribute zero.
+__device__ __forceinline__ int wave_inclusive_scan(int v)
+{
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xF, 0xF, true);   // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xF, 0xF, true);   // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xF, 0xF, true);   // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xF, 0xF, true);   // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xA, 0xF, true);   // row_bcast:15 -> rows 1, 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xC, 0xF, true);   // row_bcast:31 -> rows 2, 3
+    return v;
+}
+
 // Definition 1 on one element: fp16 -> fp32 is exact, the compare is fp32.
 __device__ __forceinline__ bool survives(float xv, float t) { return fabsf(xv) > t; }
 
@@ -92,12 +107,7 @@ __device__ __forceinline__ int compact_slice(const __half *__restrict__ x, float
     }
     __syncthreads();
     const int c = lane < nseg ? seg_cnt[lane] : 0;
-    int incl = c;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const int up = __shfl_up(incl, d);
-        if (lane >= d) incl += up;
-    }
+    const int incl = wave_inclusive_scan(c);
     seg_excl = incl - c;
     const int total = __builtin_amdgcn_readlane(incl, 63);
 #pragma unroll
