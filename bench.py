@@ -41,7 +41,7 @@ KERNEL = {"bf16": "sparse_gemv_kernel<FmtBF16>", "w8": "sparse_gemv_kernel<FmtW8
 # from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script, scaled by the factors a
 # plain copy of known size gives on the same box (2.0 and 1.0):
 # profiles/sparse_gemv_kernel_llama2_7b_hbm_traffic.txt.
-MEASURED_TRAFFIC_BYTES = {("llama2_7b", "bf16", 0.5, 1): (200310.07 + 1555.31) * 1024 / 7}
+MEASURED_TRAFFIC_BYTES = {("llama2_7b", "bf16", 0.5, 1): (200319.57 + 1555.31) * 1024 / 7}
 
 
 def algorithmic_bytes(fmt: str, nnz: int, m: int, n: int) -> int:
