@@ -224,3 +224,59 @@ void oracle_set_num_threads(int32_t k)
     (void)k;
 #endif
 }
+
+/* ---- threshold calibration (Section 4.2) -------------------------------- */
+
+/*
+ * Section 4.2 estimates t_p from an empirical distribution of activations
+ * collected offline.  The plain definition used here: over a sample of N
+ * values (NaNs left out), t_p is the smallest sample magnitude t with
+ * #{|x| <= t} >= p N, i.e. the k-th smallest |x| with k = ceil(p N); p = 0
+ * gives t = 0.  Found by sorting the magnitudes.
+ */
+#include <stdlib.h>
+#include <string.h>
+
+static int cmp_u16(const void *a, const void *b)
+{
+    uint16_t x = *(const uint16_t *)a, y = *(const uint16_t *)b;
+    return (x > y) - (x < y);
+}
+
+/* Rank of the order statistic for level p among n_valid values (0 = "t is 0").
+ * The subtraction guards binary round-off in p*n (0.3 * 10 is slightly above 3). */
+uint64_t oracle_quantile_rank(uint64_t n_valid, double p)
+{
+    double prod = p * (double)n_valid;
+    double k = ceil(prod - 1e-9);
+    if (k < 0.0) k = 0.0;
+    if (k > (double)n_valid) k = (double)n_valid;
+    return (uint64_t)k;
+}
+
+/* Returns t_p as a float (an fp16 value, exactly). scratch: count uint16. */
+float oracle_quantile_threshold(const uint16_t *x_f16, uint64_t count, double p,
+                                uint16_t *scratch)
+{
+    uint64_t n_valid = 0;
+    for (uint64_t i = 0; i < count; ++i) {
+        uint16_t mag = x_f16[i] & 0x7FFF;            /* |x|: clear the sign bit */
+        if (mag > 0x7C00) continue;                   /* NaN */
+        scratch[n_valid++] = mag;
+    }
+    uint64_t k = oracle_quantile_rank(n_valid, p);
+    if (k == 0) return 0.0f;
+    /* non-negative fp16 values order like their bit patterns */
+    qsort(scratch, (size_t)n_valid, sizeof(uint16_t), cmp_u16);
+    return (float)oracle_f16_bits_to_f64(scratch[k - 1]);
+}
+
+/* hist[b] += number of non-NaN samples whose magnitude has bit pattern b (b < 32768). */
+void oracle_abs_histogram(const uint16_t *x_f16, uint64_t count, uint64_t *hist)
+{
+    for (uint64_t i = 0; i < count; ++i) {
+        uint16_t mag = x_f16[i] & 0x7FFF;
+        if (mag > 0x7C00) continue;
+        hist[mag] += 1;
+    }
+}

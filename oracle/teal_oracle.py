@@ -62,6 +62,13 @@ def _load():
     lib.oracle_sparse_gemv_w4.restype = c.c_int32
     lib.oracle_sparse_gemv_w4.argtypes = [u8p, u16p, c.c_int32, u16p, c.c_float, f64p,
                                           c.c_int32, c.c_int32, f64p]
+    u64p = c.POINTER(c.c_uint64)
+    lib.oracle_quantile_rank.restype = c.c_uint64
+    lib.oracle_quantile_rank.argtypes = [c.c_uint64, c.c_double]
+    lib.oracle_quantile_threshold.restype = c.c_float
+    lib.oracle_quantile_threshold.argtypes = [u16p, c.c_uint64, c.c_double, u16p]
+    lib.oracle_abs_histogram.restype = None
+    lib.oracle_abs_histogram.argtypes = [u16p, c.c_uint64, u64p]
     lib.oracle_num_threads.restype = c.c_int32
     lib.oracle_set_num_threads.argtypes = [c.c_int32]
     _lib = lib
@@ -186,3 +193,30 @@ def sparse_gemv_w4(packed, scale_f16, group, x_f16, t) -> np.ndarray:
                                   int(group), _ptr(xb, ctypes.c_uint16), _f32(t),
                                   _ptr(y, ctypes.c_double), m, n, _ptr(xs, ctypes.c_double))
     return y
+
+
+def quantile_rank(n_valid: int, p: float) -> int:
+    return int(_load().oracle_quantile_rank(int(n_valid), float(p)))
+
+
+def quantile_threshold(x_f16, p: float) -> float:
+    """Section 4.2: t_p from a sample, the ceil(p N)-th smallest |x| (NaNs left out)."""
+    x = np.ascontiguousarray(x_f16).reshape(-1)
+    if x.dtype != np.float16:
+        raise TypeError("x must be float16")
+    xb = x.view(np.uint16)
+    scratch = np.empty(max(xb.size, 1), np.uint16)
+    return float(_load().oracle_quantile_threshold(_ptr(xb, ctypes.c_uint16), xb.size, float(p),
+                                                   _ptr(scratch, ctypes.c_uint16)))
+
+
+def abs_histogram(x_f16, hist=None) -> np.ndarray:
+    """Counts per fp16 magnitude bit pattern (32768 bins), added into hist if given."""
+    x = np.ascontiguousarray(x_f16).reshape(-1)
+    if x.dtype != np.float16:
+        raise TypeError("x must be float16")
+    xb = x.view(np.uint16)
+    if hist is None:
+        hist = np.zeros(32768, np.uint64)
+    _load().oracle_abs_histogram(_ptr(xb, ctypes.c_uint16), xb.size, _ptr(hist, ctypes.c_uint64))
+    return hist
