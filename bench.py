@@ -231,6 +231,101 @@ def cpu_baseline(block, p: float, budget_s: float = 12.0):
     return spent / passes, passes, threads
 
 
+CALIBRATION_LEVELS = [0.25, 0.4, 0.5, 0.65, 0.9]
+
+
+def run_calibration(T, torch, args) -> int:
+    """Threshold calibration (Section 4.2) for one decoder block: a histogram pass over a
+    sample of `tokens` hidden states for each of the block's four distinct projection inputs
+    (attention input, attention output, MLP input: width d; MLP intermediate: width d_ff),
+    then the thresholds for the levels of Section 5 read off each histogram."""
+    import numpy as np
+    shapes = ti.LAYER_SHAPES[args.workload]
+    d, d_ff = shapes["q"][1], shapes["down"][1]
+    tokens = args.calibration_tokens
+    sites = [("attn_in", d, "gaussian"), ("attn_out", d, "laplace"),
+             ("mlp_in", d, "gaussian"), ("mlp_mid", d_ff, "laplace")]
+    samples, hists, ts = [], [], []
+    for k, (_, width, dist) in enumerate(sites):
+        # one seeded row block of 64 tokens, tiled: the kernel's work does not depend on repeats
+        base = ti.make_x(64 * width, 7000 + k, dist)
+        xd = torch.from_numpy(base.view(np.int16)).cuda().repeat(tokens // 64)
+        samples.append(xd)
+        hists.append(torch.zeros(T.TEAL_HIST_BINS, dtype=torch.int64, device="cuda"))
+        ts.append(torch.zeros(len(CALIBRATION_LEVELS), dtype=torch.float32, device="cuda"))
+    counts = [x.numel() for x in samples]
+
+    def step():
+        for x, h, t in zip(samples, hists, ts):
+            T.check(T.teal_abs_histogram(x, x.numel(), h))
+            T.check(T.teal_histogram_thresholds(h, CALIBRATION_LEVELS, t))
+
+    def timed(fn, reps):
+        start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        start.record()
+        for _ in range(reps):
+            fn()
+        stop.record()
+        torch.cuda.synchronize()
+        return start.elapsed_time(stop) * 1e-3 / reps
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    sec = timed(step, args.steps)
+    # the histogram kernel alone, per site (the dominant kernel)
+    per_site, hist_sec = {}, 0.0
+    for (name, width, dist), x, h in zip(sites, samples, hists):
+        s1 = timed(lambda: T.check(T.teal_abs_histogram(x, x.numel(), h)), args.steps)
+        hist_sec += s1
+        per_site[name] = {"values": x.numel(), "width": width, "dist": dist, "us": s1 * 1e6,
+                          "GBps": 2 * x.numel() / s1 / 1e9}
+    # the same kernel over growing prefixes of the widest sample: the counting phase streams at
+    # the HBM rate, the per-block flush of LDS counters (global atomics) is a fixed cost
+    sweep = {}
+    x, h = samples[3], hists[3]
+    for frac in (1 / 16, 1 / 4, 1):
+        cnt = int(x.numel() * frac)
+        s1 = timed(lambda: T.check(T.teal_abs_histogram(x, cnt, h)), args.steps)
+        sweep[f"{2 * cnt / 1e6:.0f}MB"] = {"us": s1 * 1e6, "GBps": 2 * cnt / s1 / 1e9}
+    total_bytes = 2 * sum(counts)
+    achieved = total_bytes / hist_sec / 1e9
+    out = {
+        "metric": "threshold calibration: fp16 activation sample scanned, GB/s (histogram of "
+                  "|x| + thresholds at 5 levels, 4 projection inputs of one decoder block)",
+        "value": total_bytes / sec / 1e9, "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": sec * 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "u16/u64", "data": "synthetic",
+        "config": {"workload": f"{args.workload} calibration sample, {tokens} tokens: 3 x "
+                               f"[{tokens} x {d}] + [{tokens} x {d_ff}] fp16",
+                   "levels": CALIBRATION_LEVELS},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "abs_histogram_kernel (4 launches per step)",
+                     "bytes_per_launch_avg": total_bytes / 4, "kernel_avg_us": hist_sec * 1e6 / 4},
+        "per_site": per_site,
+        "size_sweep_mlp_mid": sweep,
+    }
+    if not args.no_cpu_baseline:
+        from oracle import teal_oracle as orc
+        x = np.tile(ti.make_x(64 * d, 7000, "gaussian"), 64)        # 4096 tokens: ~15-20 s of sorting
+        t0 = time.perf_counter()
+        want = [orc.quantile_threshold(x, p) for p in CALIBRATION_LEVELS]
+        cpu = time.perf_counter() - t0
+        h = torch.zeros(T.TEAL_HIST_BINS, dtype=torch.int64, device="cuda")
+        t = torch.zeros(len(CALIBRATION_LEVELS), dtype=torch.float32, device="cuda")
+        xd = torch.from_numpy(x.view(np.int16)).cuda()
+        T.check(T.teal_abs_histogram(xd, x.size, h))
+        T.check(T.teal_histogram_thresholds(h, CALIBRATION_LEVELS, t))
+        torch.cuda.synchronize()
+        out["cpu_baseline"] = {
+            "value": 2 * x.size / cpu / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": f"{x.size} values ({x.size // d} tokens x {d}), one sort per level, "
+                      f"{cpu:.1f} s", "matches_gpu": [float(v) for v in t.cpu()] == want}
+    print(json.dumps(out))
+    return 0
+
+
 def pct(p: float) -> str:
     return f"{int(round(p * 100))}%"
 
@@ -249,6 +344,9 @@ def main() -> int:
     ap.add_argument("--fused", action="store_true",
                     help="one launch per group of projections that share their input "
                          "(q+k+v, o, gate+up, down) instead of one per projection; bf16 only")
+    ap.add_argument("--calibration", action="store_true",
+                    help="time threshold calibration (histogram + thresholds) instead of the GEMV path")
+    ap.add_argument("--calibration-tokens", type=int, default=16384)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-per-projection", action="store_true")
     ap.add_argument("--no-fused-detail", action="store_true")
@@ -266,6 +364,11 @@ def main() -> int:
         from paper_2408_14690_amd import build
         build.build(verbose=False)
     T.load_library()
+    if args.calibration:
+        if args.calibration_tokens % 64 or args.calibration_tokens <= 0:
+            print("bench.py: --calibration-tokens must be a positive multiple of 64", file=sys.stderr)
+            return 2
+        return run_calibration(T, torch, args)
 
     sparsities = [float(s) for s in args.sparsities.split(",")]
     if 0.0 not in sparsities:

@@ -54,7 +54,7 @@ typedef enum teal_status {
     TEAL_ERR_NULL = 1,        /* a required pointer is NULL */
     TEAL_ERR_SHAPE = 2,       /* m or n out of range or not a multiple of the format's vector width */
     TEAL_ERR_ALIGN = 3,       /* a pointer is not aligned as required */
-    TEAL_ERR_THRESHOLD = 4,   /* t is negative, NaN or infinite */
+    TEAL_ERR_THRESHOLD = 4,   /* t is negative, NaN or infinite; a level p is outside [0, 1] */
     TEAL_ERR_WORKSPACE = 5,   /* workspace too small */
     TEAL_ERR_UNSUPPORTED = 6, /* group size or launch parameters not supported */
     TEAL_ERR_HIP = 7          /* the HIP runtime reported an error at launch */
@@ -174,6 +174,30 @@ teal_status teal_sparse_gemv_bf16_ex(const void *Wt_bf16, const void *x_f16, flo
                                      void *stream,
                                      int lanes_per_row, int tile_cols, int splits, int waves,
                                      int unroll);
+
+/*
+ * Threshold calibration (Section 4.2: t_p is estimated from an empirical
+ * distribution of activations collected offline).  fp16 magnitudes have 32768
+ * bit patterns, ordered like the values, so an exact histogram over them gives
+ * exact order statistics over any number of batches.
+ *
+ * teal_abs_histogram adds to hist[b] the number of entries of x whose
+ * magnitude has bit pattern b (NaNs are left out; +-Inf is pattern 0x7C00).
+ *   x_f16 [count] fp16, 0 <= count <= 2^38 (more returns TEAL_ERR_SHAPE).
+ *   hist  [TEAL_HIST_BINS] uint64, device memory, 8-byte aligned, zero-filled
+ *         by the caller before the first batch.
+ *
+ * teal_histogram_thresholds reads, for each level p[l] in [0, 1], the
+ * threshold t[l] = the k-th smallest magnitude of the N samples counted,
+ * k = ceil(p[l] N) (so that the fraction of samples with |x| <= t reaches p,
+ * Definition 1); t[l] = 0 when k = 0.
+ *   p  HOST array of np doubles, 1 <= np <= 16.
+ *   t  device array of np floats (each an fp16 value, exactly).
+ */
+#define TEAL_HIST_BINS 32768
+teal_status teal_abs_histogram(const void *x_f16, size_t count, uint64_t *hist, void *stream);
+teal_status teal_histogram_thresholds(const uint64_t *hist, const double *p, int np, float *t,
+                                      void *stream);
 
 /*
  * The launch shape the library chooses for teal_sparse_gemv_{bf16,w8,w4} at

@@ -12,5 +12,5 @@ from .binding import (  # noqa: F401
     teal_status_string, teal_version, teal_workspace_bytes,
     teal_sparsify, teal_sparse_gemv_bf16, teal_sparse_gemv_bf16_ex,
     teal_sparse_gemv_w8, teal_sparse_gemv_w4, teal_pack_bf16, teal_gemv_plan,
-    teal_sparse_gemv_bf16_multi,
+    teal_sparse_gemv_bf16_multi, teal_abs_histogram, teal_histogram_thresholds, TEAL_HIST_BINS,
 )

@@ -26,7 +26,9 @@ EXPORTS = (
     "teal_status_string", "teal_version", "teal_workspace_bytes", "teal_sparsify",
     "teal_sparse_gemv_bf16", "teal_sparse_gemv_bf16_ex", "teal_sparse_gemv_w8",
     "teal_sparse_gemv_w4", "teal_pack_bf16", "teal_gemv_plan", "teal_sparse_gemv_bf16_multi",
+    "teal_abs_histogram", "teal_histogram_thresholds",
 )
+TEAL_HIST_BINS = 32768
 
 
 class TealError(RuntimeError):
@@ -71,6 +73,10 @@ def load_library():
     lib.teal_sparse_gemv_bf16_multi.restype = i
     lib.teal_sparse_gemv_bf16_multi.argtypes = [i, c.POINTER(vp), c.POINTER(f), c.POINTER(vp),
                                                 c.POINTER(i), vp, i, vp, sz, vp]
+    lib.teal_abs_histogram.restype = i
+    lib.teal_abs_histogram.argtypes = [vp, sz, vp, vp]
+    lib.teal_histogram_thresholds.restype = i
+    lib.teal_histogram_thresholds.argtypes = [vp, c.POINTER(c.c_double), i, vp, vp]
     ip = c.POINTER(c.c_int)
     lib.teal_gemv_plan.restype = i
     lib.teal_gemv_plan.argtypes = [i, i, i, ip, ip, ip, ip, ip]
@@ -186,3 +192,14 @@ def teal_sparse_gemv_bf16_multi(Wt_list, t_list, y_list, n_list, x_f16, m, works
     return load_library().teal_sparse_gemv_bf16_multi(
         count, W, Tt, Y, N, _ptr(x_f16), int(m), _ptr(workspace),
         _nbytes(workspace, workspace_bytes), _stream(stream))
+
+
+def teal_abs_histogram(x_f16, count, hist, stream=None) -> int:
+    return load_library().teal_abs_histogram(_ptr(x_f16), int(count), _ptr(hist), _stream(stream))
+
+
+def teal_histogram_thresholds(hist, p_list, t, stream=None) -> int:
+    """p_list: host levels in [0, 1]; t: device float32 array of the same length."""
+    np_ = len(p_list)
+    P = (ctypes.c_double * max(np_, 1))(*[float(p) for p in p_list])
+    return load_library().teal_histogram_thresholds(_ptr(hist), P, np_, _ptr(t), _stream(stream))

@@ -245,6 +245,29 @@ teal_status teal_sparse_gemv_w4(const uint8_t *Wq, const void *scale_f16, int gr
                                          static_cast<hipStream_t>(stream)));
 }
 
+teal_status teal_abs_histogram(const void *x_f16, size_t count, uint64_t *hist, void *stream)
+{
+    if (!hist || (!x_f16 && count > 0)) return TEAL_ERR_NULL;
+    if (!aligned(x_f16, 2) || !aligned(hist, 8)) return TEAL_ERR_ALIGN;
+    if (count > ((size_t)1 << 38)) return TEAL_ERR_SHAPE;   // 512 GiB of fp16: beyond any one device
+    return from_hip(teal::launch_abs_histogram(x_f16, count,
+                                               reinterpret_cast<unsigned long long *>(hist),
+                                               static_cast<hipStream_t>(stream)));
+}
+
+teal_status teal_histogram_thresholds(const uint64_t *hist, const double *p, int np, float *t,
+                                      void *stream)
+{
+    if (!hist || !p || !t) return TEAL_ERR_NULL;
+    if (np < 1 || np > 16) return TEAL_ERR_SHAPE;
+    if (!aligned(hist, 8) || !aligned(t, 4)) return TEAL_ERR_ALIGN;
+    for (int l = 0; l < np; ++l)
+        if (!(p[l] >= 0.0 && p[l] <= 1.0)) return TEAL_ERR_THRESHOLD;
+    return from_hip(teal::launch_histogram_thresholds(
+        reinterpret_cast<const unsigned long long *>(hist), p, np, t,
+        static_cast<hipStream_t>(stream)));
+}
+
 teal_status teal_pack_bf16(const void *W_rowmajor, void *Wt, int m, int n, void *stream)
 {
     if (!W_rowmajor || !Wt) return TEAL_ERR_NULL;

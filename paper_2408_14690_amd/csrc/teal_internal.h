@@ -48,6 +48,12 @@ hipError_t launch_gemv_w4(const uint8_t *Wq, const void *scale_f16, const void *
                           float t, float *y, int m, int n, float *partial, int *counters,
                           const GemvShape &shape, hipStream_t stream);
 
+hipError_t launch_abs_histogram(const void *x_f16, size_t count, unsigned long long *hist,
+                                hipStream_t stream);
+
+hipError_t launch_histogram_thresholds(const unsigned long long *hist, const double *p, int np,
+                                       float *t_out, hipStream_t stream);
+
 hipError_t launch_pack_bf16(const void *W_rowmajor, void *Wt, int m, int n,
                             hipStream_t stream);
 

@@ -163,6 +163,23 @@ def test_sparsify_and_pack_argument_errors():
     assert T.teal_pack_bf16(X + 1, Y, 8, 8, stream=0) == T.TEAL_ERR_ALIGN
 
 
+def test_calibration_argument_errors():
+    H = 0x60000
+    assert T.teal_abs_histogram(None, 16, H, stream=0) == T.TEAL_ERR_NULL
+    assert T.teal_abs_histogram(X, 16, None, stream=0) == T.TEAL_ERR_NULL
+    assert T.teal_abs_histogram(X + 1, 16, H, stream=0) == T.TEAL_ERR_ALIGN
+    assert T.teal_abs_histogram(X, 16, H + 4, stream=0) == T.TEAL_ERR_ALIGN
+    assert T.teal_abs_histogram(X, (1 << 38) + 1, H, stream=0) == T.TEAL_ERR_SHAPE
+    assert T.teal_abs_histogram(None, 0, H, stream=0) == T.TEAL_OK        # empty batch: nothing to do
+    assert T.teal_histogram_thresholds(None, [0.5], Y, stream=0) == T.TEAL_ERR_NULL
+    assert T.teal_histogram_thresholds(H, [0.5], None, stream=0) == T.TEAL_ERR_NULL
+    assert T.teal_histogram_thresholds(H, [], Y, stream=0) == T.TEAL_ERR_SHAPE
+    assert T.teal_histogram_thresholds(H, [0.5] * 17, Y, stream=0) == T.TEAL_ERR_SHAPE
+    assert T.teal_histogram_thresholds(H, [1.5], Y, stream=0) == T.TEAL_ERR_THRESHOLD
+    assert T.teal_histogram_thresholds(H, [float("nan")], Y, stream=0) == T.TEAL_ERR_THRESHOLD
+    assert T.teal_histogram_thresholds(H + 4, [0.5], Y, stream=0) == T.TEAL_ERR_ALIGN
+
+
 def test_check_raises_with_message():
     with pytest.raises(T.TealError) as e:
         T.check(T.TEAL_ERR_WORKSPACE)

@@ -82,3 +82,25 @@ def test_histogram_counts_every_pattern_and_selects_the_same_threshold():
         k = orc.quantile_rank(int(cum[-1]), p)
         t = 0.0 if k == 0 else float(np.array([np.searchsorted(cum, k)], np.uint16).view(np.float16)[0])
         assert t == orc.quantile_threshold(x, p), p
+
+
+def test_threshold_approaches_the_closed_form_quantiles():
+    """|N(0,1)| has quantile sqrt(2) erfinv(p); |Laplace(0,1)| is Exp(1): -ln(1 - p)."""
+    from scipy.special import erfinv
+    n = 400_000
+    g, l = ti.gaussian_x(n, 77), ti.laplace_x(n, 78)
+    for p in (0.25, 0.4, 0.5, 0.65, 0.9):
+        tg, tl = orc.quantile_threshold(g, p), orc.quantile_threshold(l, p)
+        # sampling error of an order statistic: sqrt(p(1-p)/n)/density, a few 1e-3 here; fp16 grid 1e-3
+        assert abs(tg - np.sqrt(2) * erfinv(p)) < 0.01, (p, tg)
+        assert abs(tl + np.log1p(-p)) < 0.015, (p, tl)
+
+
+def test_threshold_realises_the_level_through_definition_1():
+    x = ti.laplace_x(14336, 5)
+    for p in (0.25, 0.5, 0.9):
+        t = orc.quantile_threshold(x, p)
+        kept = orc.sparsify(x, t)[3]
+        k = orc.quantile_rank(x.size, p)
+        ties = int(np.count_nonzero(np.abs(x.astype(np.float64)) == t))
+        assert k <= x.size - kept <= k + ties - 1
