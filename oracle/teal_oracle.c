@@ -27,7 +27,9 @@
  * a dense numpy fp64 product; general t against the dense product on an
  * explicitly zeroed x; exact rational arithmetic on tiny shapes; measured
  * sparsity against the order statistic that chose t; the closed-form
- * relative error of Theorem A.1.  The int4 nibble order and the scale
+ * relative error of Theorem A.1; the batched criterion of Section 5.4.4
+ * against exact rational arithmetic, its reduction to Definition 1 at batch
+ * size 1 and on a batch of identical rows, and a dense numpy product.  The int4 nibble order and the scale
  * indexing of the quantised variants are conventions of this build, not of
  * the paper (Section 5.3 only names the bit widths): for those two layout
  * conventions parity is unpinned by the paper and pinned only by hand-built
@@ -202,6 +204,67 @@ int32_t oracle_sparse_gemv_w4(const uint8_t *q, const uint16_t *scale_f16,
             acc += scratch_xs[i] * w;
         }
         y[j] = acc;
+    }
+    return count;
+}
+
+/* ---- batched sparsification (Section 5.4.4) ------------------------------ */
+
+/*
+ * Section 5.4.4 extends the method to a small batch: one set of channels is
+ * dropped for the whole batch, chosen by the magnitude of the activations
+ * averaged over the batch dimension, and the criterion is still a single
+ * threshold.  X is [batch][m] fp16 (one hidden state per row).  Channel i is
+ * kept iff
+ *
+ *     (1 / batch) * sum_b |X[b][i]|  >  t .
+ *
+ * The inequality is evaluated as  sum_b |X[b][i]| > batch * t : fp16
+ * magnitudes are multiples of 2^-24 below 2^16, so the sum of a few thousand
+ * of them is exact in fp64, and batch * t is exact as well; no division, no
+ * rounding, the same decision whatever the order of the batch.  A NaN anywhere
+ * in a channel makes the sum NaN, which compares false: the channel is dropped
+ * for every row.  mean_abs (may be NULL) receives sum / batch for inspection.
+ * mask / idx as in oracle_sparsify; returns the number of kept channels.
+ */
+int32_t oracle_sparsify_batch(const uint16_t *X_f16, int32_t batch, int32_t m,
+                              float t, double *mean_abs, uint8_t *mask,
+                              int32_t *idx)
+{
+    const double bound = (double)batch * (double)t;
+    int32_t count = 0;
+    for (int32_t i = 0; i < m; ++i) {
+        double sum = 0.0;
+        for (int32_t b = 0; b < batch; ++b)
+            sum += fabs(oracle_f16_bits_to_f64(X_f16[(size_t)b * (size_t)m + (size_t)i]));
+        int keep = sum > bound;
+        if (mean_abs) mean_abs[i] = sum / (double)batch;
+        if (mask) mask[i] = (uint8_t)keep;
+        if (keep) {
+            if (idx) idx[count] = i;
+            ++count;
+        }
+    }
+    return count;
+}
+
+/*
+ * Y[b][j] = sum_i s_i * X[b][i] * W[j][i] with the batch-wide mask s above:
+ * every row of the batch is multiplied with the same thresholded set of
+ * channels.  Dense loop in index order on canonical W[n][m], fp64.
+ * scratch_mask: m bytes; scratch_xs: m doubles.  Returns the kept count.
+ */
+int32_t oracle_sparse_gemv_bf16_batch(const uint16_t *W_bf16,
+                                      const uint16_t *X_f16, int32_t batch,
+                                      float t, double *Y, int32_t m, int32_t n,
+                                      uint8_t *scratch_mask, double *scratch_xs)
+{
+    int32_t count = oracle_sparsify_batch(X_f16, batch, m, t, NULL, scratch_mask, NULL);
+    for (int32_t b = 0; b < batch; ++b) {
+        for (int32_t i = 0; i < m; ++i)
+            scratch_xs[i] = scratch_mask[i]
+                ? oracle_f16_bits_to_f64(X_f16[(size_t)b * (size_t)m + (size_t)i]) : 0.0;
+        dense_rows_bf16(W_bf16, scratch_xs, Y + (size_t)b * (size_t)n, m, n);
     }
     return count;
 }

@@ -62,6 +62,11 @@ def _load():
     lib.oracle_sparse_gemv_w4.restype = c.c_int32
     lib.oracle_sparse_gemv_w4.argtypes = [u8p, u16p, c.c_int32, u16p, c.c_float, f64p,
                                           c.c_int32, c.c_int32, f64p]
+    lib.oracle_sparsify_batch.restype = c.c_int32
+    lib.oracle_sparsify_batch.argtypes = [u16p, c.c_int32, c.c_int32, c.c_float, f64p, u8p, i32p]
+    lib.oracle_sparse_gemv_bf16_batch.restype = c.c_int32
+    lib.oracle_sparse_gemv_bf16_batch.argtypes = [u16p, u16p, c.c_int32, c.c_float, f64p,
+                                                  c.c_int32, c.c_int32, u8p, f64p]
     u64p = c.POINTER(c.c_uint64)
     lib.oracle_quantile_rank.restype = c.c_uint64
     lib.oracle_quantile_rank.argtypes = [c.c_uint64, c.c_double]
@@ -193,6 +198,47 @@ def sparse_gemv_w4(packed, scale_f16, group, x_f16, t) -> np.ndarray:
                                   int(group), _ptr(xb, ctypes.c_uint16), _f32(t),
                                   _ptr(y, ctypes.c_double), m, n, _ptr(xs, ctypes.c_double))
     return y
+
+
+def _X_bits(X_f16) -> np.ndarray:
+    X = np.ascontiguousarray(X_f16)
+    if X.dtype != np.float16 or X.ndim != 2 or X.shape[0] < 1:
+        raise TypeError("X must be a 2-D float16 array, [batch][m]")
+    return X.view(np.uint16)
+
+
+def sparsify_batch(X_f16, t):
+    """Section 5.4.4: one mask for the batch from the batch-averaged magnitude.
+
+    Returns (mean_abs float64[m], mask uint8[m], idx int32[count], count)."""
+    Xb = _X_bits(X_f16)
+    batch, m = Xb.shape
+    mean_abs = np.empty(m, np.float64)
+    mask = np.empty(m, np.uint8)
+    idx = np.empty(max(m, 1), np.int32)
+    count = _load().oracle_sparsify_batch(_ptr(Xb, ctypes.c_uint16), batch, m, _f32(t),
+                                          _ptr(mean_abs, ctypes.c_double),
+                                          _ptr(mask, ctypes.c_uint8), _ptr(idx, ctypes.c_int32))
+    return mean_abs, mask, idx[:count].copy(), int(count)
+
+
+def sparse_gemv_bf16_batch(w_bits, X_f16, t) -> np.ndarray:
+    """Y float64[batch][n]: every row of X times W^T over the batch-wide kept channels."""
+    w = np.ascontiguousarray(w_bits)
+    if w.dtype != np.uint16 or w.ndim != 2:
+        raise TypeError("W must be a 2-D uint16 array of bf16 bit patterns, [n][m]")
+    Xb = _X_bits(X_f16)
+    batch, m = Xb.shape
+    n = w.shape[0]
+    if w.shape[1] != m:
+        raise ValueError("X row length must equal W's input dimension")
+    Y = np.empty((batch, n), np.float64)
+    mask = np.empty(m, np.uint8)
+    xs = np.empty(m, np.float64)
+    _load().oracle_sparse_gemv_bf16_batch(_ptr(w, ctypes.c_uint16), _ptr(Xb, ctypes.c_uint16),
+                                          batch, _f32(t), _ptr(Y, ctypes.c_double), m, n,
+                                          _ptr(mask, ctypes.c_uint8), _ptr(xs, ctypes.c_double))
+    return Y
 
 
 def quantile_rank(n_valid: int, p: float) -> int:

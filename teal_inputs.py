@@ -108,6 +108,40 @@ def quantile_threshold(x_f16: np.ndarray, p: float) -> float:
     return float(np.partition(a, k - 1)[k - 1])
 
 
+def make_X(batch: int, m: int, seed: int, dist: str) -> np.ndarray:
+    """A small batch of independent hidden states, [batch][m] fp16 (rows drawn
+    one after the other from one seeded stream)."""
+    rng = _rng(seed)
+    if dist == "gaussian":
+        X = rng.standard_normal((batch, m))
+    elif dist == "laplace":
+        X = rng.laplace(0.0, 1.0, (batch, m))
+    else:
+        raise ValueError(f"unknown distribution {dist!r}")
+    return X.astype(np.float16)
+
+
+def batch_quantile_threshold(X_f16: np.ndarray, p: float) -> float:
+    """A threshold for a batch: an fp32 value t such that at least ceil(p*m)
+    channels have a batch-averaged magnitude <= t.
+
+    The k-th smallest average magnitude is in general not an fp32 value, so it
+    is rounded UP to fp32 (then the k smallest averages are all <= t).  p == 0
+    gives t == 0.
+    """
+    X = np.asarray(X_f16, dtype=np.float16)
+    batch, m = X.shape
+    k = quantile_rank(m, p)
+    if k == 0:
+        return 0.0
+    mean = np.abs(X.astype(np.float64)).sum(axis=0) / batch
+    kth = float(np.partition(mean, k - 1)[k - 1])
+    t = np.float32(kth)
+    if float(t) < kth:
+        t = np.nextafter(t, np.float32(np.inf))
+    return float(t)
+
+
 # ----------------------------------------------------------------------------
 # weight quantisers (round to nearest, symmetric); produce what both sides read
 # ----------------------------------------------------------------------------
