@@ -200,6 +200,44 @@ teal_status teal_histogram_thresholds(const uint64_t *hist, const double *p, int
                                       void *stream);
 
 /*
+ * Small batches (Section 5.4.4).  One set of channels is dropped for the whole
+ * batch, chosen by the magnitude of the activations averaged over the batch
+ * dimension; the criterion is still one threshold:
+ *     channel i is kept  iff  (1 / batch) * sum_b |X[b][i]| > t.
+ * It is evaluated as sum_b |X[b][i]| > batch * t in fp64, which is exact for
+ * fp16 data (no division, no rounding, independent of the order of the rows).
+ * A NaN in any row of a channel drops the channel; +-Inf keeps it.
+ *   X_f16 [batch][m] fp16, one hidden state per row, 2-byte aligned.
+ *   1 <= batch <= TEAL_MAX_BATCH.  batch = 1 is Definition 1.
+ *
+ * teal_sparsify_batch: mask / idx / count as for teal_sparsify, one mask for
+ * the batch.
+ *
+ * teal_sparse_gemv_bf16_batch: Y[b][:] = (X[b][:] . s) W^T for every row b with
+ * the batch-wide mask s; each surviving weight row is read once for the whole
+ * batch.  Y is [batch][n] fp32, fully overwritten.  Wt, m, n as for
+ * teal_sparse_gemv_bf16; workspace of at least
+ * teal_workspace_bytes_batch(m, n, batch) bytes, same rules as above.
+ *
+ * teal_sparse_gemv_bf16_batch_ex: the same with a caller-chosen launch shape
+ * (0 = library's choice): lanes_per_row 64, 32 or 16 with
+ * lanes_per_row * B <= 256, B = batch rounded up to 2, 4 or 8; tile_cols a
+ * multiple of 8, at most 8 * lanes_per_row; splits such that a block's slice,
+ * ceil(m / splits) rounded up to 64, is at most 2048 channels.
+ */
+#define TEAL_MAX_BATCH 8
+size_t teal_workspace_bytes_batch(int m, int n, int batch);
+teal_status teal_sparsify_batch(const void *X_f16, int batch, int m, float t,
+                                uint8_t *mask, int32_t *idx, int32_t *count, void *stream);
+teal_status teal_sparse_gemv_bf16_batch(const void *Wt_bf16, const void *X_f16, int batch,
+                                        float t, float *Y, int m, int n,
+                                        void *workspace, size_t workspace_bytes, void *stream);
+teal_status teal_sparse_gemv_bf16_batch_ex(const void *Wt_bf16, const void *X_f16, int batch,
+                                           float t, float *Y, int m, int n,
+                                           void *workspace, size_t workspace_bytes, void *stream,
+                                           int lanes_per_row, int tile_cols, int splits);
+
+/*
  * The launch shape the library chooses for teal_sparse_gemv_{bf16,w8,w4} at
  * these dimensions (weight_bits = 16, 8 or 4), in the terms of
  * teal_sparse_gemv_bf16_ex.  Host-only; every output pointer is HOST memory

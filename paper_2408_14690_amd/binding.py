@@ -26,9 +26,11 @@ EXPORTS = (
     "teal_status_string", "teal_version", "teal_workspace_bytes", "teal_sparsify",
     "teal_sparse_gemv_bf16", "teal_sparse_gemv_bf16_ex", "teal_sparse_gemv_w8",
     "teal_sparse_gemv_w4", "teal_pack_bf16", "teal_gemv_plan", "teal_sparse_gemv_bf16_multi",
-    "teal_abs_histogram", "teal_histogram_thresholds",
+    "teal_abs_histogram", "teal_histogram_thresholds", "teal_workspace_bytes_batch",
+    "teal_sparsify_batch", "teal_sparse_gemv_bf16_batch", "teal_sparse_gemv_bf16_batch_ex",
 )
 TEAL_HIST_BINS = 32768
+TEAL_MAX_BATCH = 8
 
 
 class TealError(RuntimeError):
@@ -77,6 +79,14 @@ def load_library():
     lib.teal_abs_histogram.argtypes = [vp, sz, vp, vp]
     lib.teal_histogram_thresholds.restype = i
     lib.teal_histogram_thresholds.argtypes = [vp, c.POINTER(c.c_double), i, vp, vp]
+    lib.teal_workspace_bytes_batch.restype = sz
+    lib.teal_workspace_bytes_batch.argtypes = [i, i, i]
+    lib.teal_sparsify_batch.restype = i
+    lib.teal_sparsify_batch.argtypes = [vp, i, i, f, vp, vp, vp, vp]
+    lib.teal_sparse_gemv_bf16_batch.restype = i
+    lib.teal_sparse_gemv_bf16_batch.argtypes = [vp, vp, i, f, vp, i, i, vp, sz, vp]
+    lib.teal_sparse_gemv_bf16_batch_ex.restype = i
+    lib.teal_sparse_gemv_bf16_batch_ex.argtypes = [vp, vp, i, f, vp, i, i, vp, sz, vp, i, i, i]
     ip = c.POINTER(c.c_int)
     lib.teal_gemv_plan.restype = i
     lib.teal_gemv_plan.argtypes = [i, i, i, ip, ip, ip, ip, ip]
@@ -192,6 +202,31 @@ def teal_sparse_gemv_bf16_multi(Wt_list, t_list, y_list, n_list, x_f16, m, works
     return load_library().teal_sparse_gemv_bf16_multi(
         count, W, Tt, Y, N, _ptr(x_f16), int(m), _ptr(workspace),
         _nbytes(workspace, workspace_bytes), _stream(stream))
+
+
+def teal_workspace_bytes_batch(m: int, n: int, batch: int) -> int:
+    return int(load_library().teal_workspace_bytes_batch(int(m), int(n), int(batch)))
+
+
+def teal_sparsify_batch(X_f16, batch, m, t, mask=None, idx=None, count=None, stream=None) -> int:
+    return load_library().teal_sparsify_batch(_ptr(X_f16), int(batch), int(m), float(t),
+                                              _ptr(mask), _ptr(idx), _ptr(count), _stream(stream))
+
+
+def teal_sparse_gemv_bf16_batch(Wt_bf16, X_f16, batch, t, Y, m, n, workspace,
+                                workspace_bytes=None, stream=None) -> int:
+    return load_library().teal_sparse_gemv_bf16_batch(
+        _ptr(Wt_bf16), _ptr(X_f16), int(batch), float(t), _ptr(Y), int(m), int(n),
+        _ptr(workspace), _nbytes(workspace, workspace_bytes), _stream(stream))
+
+
+def teal_sparse_gemv_bf16_batch_ex(Wt_bf16, X_f16, batch, t, Y, m, n, workspace,
+                                   workspace_bytes=None, stream=None, lanes_per_row=0,
+                                   tile_cols=0, splits=0) -> int:
+    return load_library().teal_sparse_gemv_bf16_batch_ex(
+        _ptr(Wt_bf16), _ptr(X_f16), int(batch), float(t), _ptr(Y), int(m), int(n),
+        _ptr(workspace), _nbytes(workspace, workspace_bytes), _stream(stream),
+        int(lanes_per_row), int(tile_cols), int(splits))
 
 
 def teal_abs_histogram(x_f16, count, hist, stream=None) -> int:

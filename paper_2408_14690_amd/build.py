@@ -17,7 +17,8 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libteal.so")
 
-SOURCES = ("teal_api.cpp", "sparsify_pack.hip", "gemv_bf16.hip", "gemv_wq.hip", "calibrate.hip")
+SOURCES = ("teal_api.cpp", "sparsify_pack.hip", "gemv_bf16.hip", "gemv_wq.hip", "gemv_batch.hip",
+           "calibrate.hip")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -1,0 +1,370 @@
+// Small-batch variant of the thresholded product (Section 5.4.4): one set of
+// channels is dropped for the whole batch, chosen by the magnitude averaged
+// over the batch dimension, and every row of the batch is multiplied with the
+// surviving rows of the input-channel-major weights.  The weight stream is the
+// same as for one vector (each surviving row is read once); a block keeps one
+// accumulator set per batch row.
+#include "gemv_common.h"
+
+namespace teal {
+
+namespace {
+
+// Channel i survives iff (1 / batch) * sum_b |X[b][i]| > t.  Evaluated as
+// sum > batch * t in fp64: fp16 -> fp32 -> fp64 and |.| are exact, a sum of
+// up to kMaxBatch fp16 magnitudes is exact in fp64 and so is batch * t, so the
+// decision involves no rounding and does not depend on the order of the batch.
+// A NaN makes the sum NaN, which compares false (the channel is dropped).
+template <int NB>
+__device__ __forceinline__ bool survives_batch(const float (&xv)[NB], double bound)
+{
+    double s = 0.0;
+#pragma unroll
+    for (int b = 0; b < NB; ++b) s += (double)fabsf(xv[b]);
+    return s > bound;
+}
+
+// compact_slice for a batch: list_idx[] receives the surviving channels of
+// [k0, k1) in ascending order and list_x[] their NB activations each (rows at
+// or past `batch` are zero).  Same scheme: ballots and popcounts per
+// 64-channel segment, segment counts through LDS, every wavefront scans them.
+template <int NB, int WAVES>
+__device__ __forceinline__ int compact_slice_batch(const __half *__restrict__ X, int batch, int m,
+                                                   double bound, int k0, int k1, int *list_idx,
+                                                   float *list_x, int *seg_cnt)
+{
+    constexpr int PER_WAVE = kMaxSliceBatch / 64 / WAVES;
+    const int lane = threadIdx.x & 63;
+    const int w = threadIdx.x >> 6;
+    const int nseg = (k1 - k0 + 63) >> 6;
+
+    float xv[PER_WAVE][NB];
+    unsigned long long bal[PER_WAVE];
+#pragma unroll
+    for (int j = 0; j < PER_WAVE; ++j) {
+        const int i = k0 + (w + j * WAVES) * 64 + lane;
+#pragma unroll
+        for (int b = 0; b < NB; ++b)
+            xv[j][b] = (i < k1 && b < batch) ? __half2float(X[(size_t)b * m + i]) : 0.f;
+    }
+#pragma unroll
+    for (int j = 0; j < PER_WAVE; ++j) {
+        const int seg = w + j * WAVES;
+        bal[j] = __ballot(survives_batch<NB>(xv[j], bound));
+        if (lane == 0 && seg < nseg) seg_cnt[seg] = __popcll(bal[j]);
+    }
+    __syncthreads();
+    const int c = lane < nseg ? seg_cnt[lane] : 0;
+    const int incl = wave_inclusive_scan(c);
+    const int seg_excl = incl - c;
+    const int total = __builtin_amdgcn_readlane(incl, 63);
+#pragma unroll
+    for (int j = 0; j < PER_WAVE; ++j) {
+        const int seg = w + j * WAVES;
+        if (seg < nseg) {                              // wavefront-uniform
+            const int base = __builtin_amdgcn_readlane(seg_excl, seg);
+            if ((bal[j] >> lane) & 1ull) {
+                const int slot = base + lanes_below(bal[j]);
+                list_idx[slot] = k0 + seg * 64 + lane;
+#pragma unroll
+                for (int b = 0; b < NB; ++b) list_x[slot * NB + b] = xv[j][b];
+            }
+        }
+    }
+    __syncthreads();
+    return total;
+}
+
+// stream_rows for a batch: per surviving row one 16-byte load per lane, the 8
+// weights converted once and multiplied into NB accumulator sets.  The NB
+// activations of a row are read from LDS when the row is consumed; slots past
+// the end of the wavefront's share point at an all-zero entry (zero_slot).
+template <int NB, int LPR, int U>
+__device__ __forceinline__ void stream_rows_batch(float (&acc)[NB][8], const int *list_idx,
+                                                  const float *list_x, int zero_slot, int start,
+                                                  int mine,
+                                                  const unsigned char *__restrict__ lane_base,
+                                                  unsigned row_bytes)
+{
+    constexpr int R = 64 / LPR;
+    if (mine <= 0) return;
+    const int g = (threadIdx.x & 63) / LPR;
+    const int last = mine - 1;
+    const int batches = (mine + U * R - 1) / (U * R);
+
+    struct Batch {
+        u32x4 v[U];
+        int slot[U];
+    };
+    auto issue = [&](Batch &b, int batch_no) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int e = (batch_no * U + u) * R + g;
+            const int row = list_idx[start + min(e, last)];
+            b.slot[u] = e <= last ? start + e : zero_slot;
+            b.v[u] = load_stream16(lane_base + (size_t)(unsigned)row * row_bytes);
+        }
+    };
+    auto consume = [&](const Batch &b) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            float xs[NB];
+            if constexpr (NB >= 4) {
+#pragma unroll
+                for (int q = 0; q < NB / 4; ++q) {
+                    const float4 f =
+                        *reinterpret_cast<const float4 *>(list_x + b.slot[u] * NB + 4 * q);
+                    xs[4 * q] = f.x; xs[4 * q + 1] = f.y; xs[4 * q + 2] = f.z; xs[4 * q + 3] = f.w;
+                }
+            } else {
+                const float2 f = *reinterpret_cast<const float2 *>(list_x + b.slot[u] * NB);
+                xs[0] = f.x; xs[1] = f.y;
+            }
+            float wv[8];                       // bf16 -> fp32 is a 16-bit shift
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                wv[2 * q] = __uint_as_float(b.v[u][q] << 16);
+                wv[2 * q + 1] = __uint_as_float(b.v[u][q] & 0xffff0000u);
+            }
+#pragma unroll
+            for (int bb = 0; bb < NB; ++bb)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[bb][e] = fmaf(xs[bb], wv[e], acc[bb][e]);
+        }
+    };
+
+    Batch b0, b1;
+    issue(b0, 0);
+    int it = 0;
+    for (; it + 2 < batches; it += 2) {
+        issue(b1, it + 1);
+        consume(b0);
+        issue(b0, it + 2);
+        consume(b1);
+    }
+    if (it + 1 < batches) {
+        issue(b1, it + 1);
+        consume(b0);
+        consume(b1);
+    } else {
+        consume(b0);
+    }
+}
+
+// block_finish for a batch.  red[] (WAVES x NB x TN floats) lies over the list,
+// which is dead once every wavefront has left the row stream.  Partial rows are
+// laid out [split][batch row][n]; the block that arrives last at the tile's
+// counter adds them in split order for every batch row and writes Y.
+template <int NB, int LPR, int WAVES>
+__device__ __forceinline__ void block_finish_batch(const float (&acc)[NB][8], float *red,
+                                                   float *partial, int *counters, float *Y,
+                                                   int tile, int col0, int cols, int s, int splits,
+                                                   int n, int batch)
+{
+    constexpr int TN = LPR * 8;
+    constexpr int THREADS = WAVES * 64;
+    __shared__ int last_flag;
+    const int lane = threadIdx.x & 63;
+    const int w = threadIdx.x >> 6;
+    if (cols > n - col0) cols = n - col0;
+    __syncthreads();                   // every wavefront is done with the list
+    if (lane < LPR) {
+#pragma unroll
+        for (int bb = 0; bb < NB; ++bb) {
+            float4 *dst = reinterpret_cast<float4 *>(red + (w * NB + bb) * TN + lane * 8);
+            dst[0] = make_float4(acc[bb][0], acc[bb][1], acc[bb][2], acc[bb][3]);
+            dst[1] = make_float4(acc[bb][4], acc[bb][5], acc[bb][6], acc[bb][7]);
+        }
+    }
+    __syncthreads();
+    const int total = batch * cols;
+    auto wave_sum = [&](int bb, int c) {
+        float sum = 0.f;
+#pragma unroll
+        for (int ww = 0; ww < WAVES; ++ww) sum += red[(ww * NB + bb) * TN + c];
+        return sum;
+    };
+    if (splits == 1) {
+        for (int k = threadIdx.x; k < total; k += THREADS) {
+            const int bb = k / cols, c = k - bb * cols;
+            Y[(size_t)bb * n + col0 + c] = wave_sum(bb, c);
+        }
+        return;
+    }
+    for (int k = threadIdx.x; k < total; k += THREADS) {
+        const int bb = k / cols, c = k - bb * cols;
+        store_coherent(partial + ((size_t)s * batch + bb) * n + col0 + c, wave_sum(bb, c));
+    }
+    wait_vector_memory();
+    __syncthreads();
+    if (threadIdx.x == 0) last_flag = atomicAdd(&counters[tile], 1) == splits - 1;
+    __syncthreads();
+    if (!last_flag) return;
+
+    constexpr int MAXLD = 8;
+    const size_t split_stride = (size_t)batch * n;
+    for (int k = threadIdx.x; k < total; k += THREADS) {
+        const int bb = k / cols, c = k - bb * cols;
+        const float *p = partial + (size_t)bb * n + col0 + c;
+        float sum = 0.f;
+        for (int k0 = 0; k0 < splits; k0 += MAXLD) {
+            float v[MAXLD];
+#pragma unroll
+            for (int u = 0; u < MAXLD; ++u)
+                v[u] = k0 + u < splits ? load_coherent(p + (size_t)(k0 + u) * split_stride) : 0.f;
+#pragma unroll
+            for (int u = 0; u < MAXLD; ++u) sum += v[u];
+        }
+        Y[(size_t)bb * n + col0 + c] = sum;
+    }
+    if (threadIdx.x == 0) atomicExch(&counters[tile], 0);
+}
+
+template <int NB, int LPR, int WAVES, int U>
+__global__ __launch_bounds__(WAVES * 64) void sparse_gemv_batch_kernel(
+    const void *__restrict__ W, const __half *__restrict__ X, int batch, double bound,
+    float *partial, int *counters, float *Y, int m, int n, int ks, int tiles, int tile_cols,
+    int splits)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    // [list_x: (ks + 1) x NB floats][list_idx: ks ints]; red[] reuses the front.
+    float *list_x = reinterpret_cast<float *>(smem);
+    int *list_idx = reinterpret_cast<int *>(smem + (size_t)(ks + 1) * NB * sizeof(float));
+    float *red = reinterpret_cast<float *>(smem);
+    __shared__ int seg_cnt[kMaxSliceBatch / 64];
+
+    const int tile = blockIdx.x % tiles;
+    const int s = blockIdx.x / tiles;
+    const int k0 = s * ks;
+    const int k1 = min(m, k0 + ks);
+    if (threadIdx.x < NB) list_x[ks * NB + threadIdx.x] = 0.f;    // the all-zero entry
+    const int cnt = compact_slice_batch<NB, WAVES>(X, batch, m, bound, k0, k1, list_idx, list_x,
+                                                   seg_cnt);
+
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    int start, mine;
+    wave_share(cnt, w, WAVES, start, mine);
+
+    const int col0 = tile * tile_cols;
+    const int col = lane_column<8>(col0, tile_cols, n, lane % LPR);
+    const unsigned row_bytes = (unsigned)n * 2u;
+    const unsigned char *lane_base = static_cast<const unsigned char *>(W) + (size_t)col * 2;
+
+    float acc[NB][8];
+#pragma unroll
+    for (int bb = 0; bb < NB; ++bb)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[bb][e] = 0.f;
+    stream_rows_batch<NB, LPR, U>(acc, list_idx, list_x, ks, start, mine, lane_base, row_bytes);
+#pragma unroll
+    for (int off = LPR; off < 64; off <<= 1)
+#pragma unroll
+        for (int bb = 0; bb < NB; ++bb)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[bb][e] += __shfl_xor(acc[bb][e], off);
+    block_finish_batch<NB, LPR, WAVES>(acc, red, partial, counters, Y, tile, col0, tile_cols, s,
+                                       splits, n, batch);
+}
+
+constexpr int kBatchWaves = 8;
+constexpr int kBatchUnroll = 4;
+
+// One block thresholds the batch like sparsify_kernel does one vector, 1024
+// channels per step.
+constexpr int kSparsifyWaves = 16;
+__global__ __launch_bounds__(kSparsifyWaves * 64) void sparsify_batch_kernel(
+    const __half *__restrict__ X, int batch, int m, double bound, uint8_t *__restrict__ mask,
+    int32_t *__restrict__ idx, int32_t *__restrict__ count)
+{
+    __shared__ int wave_cnt[2][kSparsifyWaves];
+    const int lane = threadIdx.x & 63;
+    const int w = threadIdx.x >> 6;
+    int base = 0;
+    int buf = 0;
+    for (int c0 = 0; c0 < m; c0 += kSparsifyWaves * 64, buf ^= 1) {
+        const int i = c0 + (int)threadIdx.x;
+        bool keep = false;
+        if (i < m) {
+            double s = 0.0;
+            for (int b = 0; b < batch; ++b)
+                s += (double)fabsf(__half2float(X[(size_t)b * m + i]));
+            keep = s > bound;
+            if (mask) mask[i] = keep ? 1 : 0;
+        }
+        const unsigned long long bal = __ballot(keep);
+        if (lane == 0) wave_cnt[buf][w] = __popcll(bal);
+        __syncthreads();
+        int below = 0, total = 0;
+#pragma unroll
+        for (int ww = 0; ww < kSparsifyWaves; ++ww) {
+            const int c = wave_cnt[buf][ww];
+            below += ww < w ? c : 0;
+            total += c;
+        }
+        if (keep && idx) idx[base + below + lanes_below(bal)] = i;
+        base += total;
+        // wave_cnt is double-buffered: the next step writes the other half, and
+        // that step's barrier orders it against this step's reads.
+    }
+    if (threadIdx.x == 0 && count) *count = base;
+}
+
+}  // namespace
+
+bool gemv_batch_shape_supported(int batch, const GemvShape &s)
+{
+    if (batch < 1 || batch > kMaxBatch) return false;
+    const int nb = batch <= 2 ? 2 : batch <= 4 ? 4 : 8;
+    const bool lpr = s.lanes_per_row == 64 || s.lanes_per_row == 32 || s.lanes_per_row == 16;
+    const bool tc = s.tile_cols >= 0 && s.tile_cols % 8 == 0 && s.tile_cols <= s.lanes_per_row * 8;
+    // the block combine holds waves x nb x (8 * lanes) floats in LDS: at most 64 KiB
+    const bool fits = nb * s.lanes_per_row <= 256;
+    return lpr && tc && fits && s.waves == kBatchWaves && s.unroll == kBatchUnroll &&
+           s.splits >= 1 && s.splits <= kMaxSplits;
+}
+
+hipError_t launch_gemv_bf16_batch(const void *Wt, const void *X_f16, int batch, float t, float *Y,
+                                  int m, int n, float *partial, int *counters,
+                                  const GemvShape &sh, hipStream_t stream)
+{
+    const GemvGeometry g = gemv_geometry(m, n, sh, 8, 64);
+    if (g.ks > kMaxSliceBatch || !gemv_batch_shape_supported(batch, sh)) return hipErrorInvalidValue;
+    const int nb = batch <= 2 ? 2 : batch <= 4 ? 4 : 8;
+    const size_t list_bytes = (size_t)(g.ks + 1) * nb * sizeof(float) + (size_t)g.ks * sizeof(int);
+    const size_t red_bytes = (size_t)kBatchWaves * nb * sh.lanes_per_row * 8 * sizeof(float);
+    const size_t lds = list_bytes > red_bytes ? list_bytes : red_bytes;
+    const double bound = (double)batch * (double)t;
+    const __half *X = static_cast<const __half *>(X_f16);
+#define TEAL_LAUNCH_B(NB, LPR)                                                                   \
+    hipLaunchKernelGGL((sparse_gemv_batch_kernel<NB, LPR, kBatchWaves, kBatchUnroll>),           \
+                       dim3(g.tiles * g.splits), dim3(kBatchWaves * 64), lds, stream, Wt, X,     \
+                       batch, bound, partial, counters, Y, m, n, g.ks, g.tiles, g.tile_cols,     \
+                       g.splits)
+    const int lpr = sh.lanes_per_row;
+    if (nb == 2) {
+        if (lpr == 64) TEAL_LAUNCH_B(2, 64);
+        else if (lpr == 32) TEAL_LAUNCH_B(2, 32);
+        else TEAL_LAUNCH_B(2, 16);
+    } else if (nb == 4) {
+        if (lpr == 64) TEAL_LAUNCH_B(4, 64);
+        else if (lpr == 32) TEAL_LAUNCH_B(4, 32);
+        else TEAL_LAUNCH_B(4, 16);
+    } else {
+        if (lpr == 32) TEAL_LAUNCH_B(8, 32);
+        else TEAL_LAUNCH_B(8, 16);
+    }
+#undef TEAL_LAUNCH_B
+    return hipGetLastError();
+}
+
+hipError_t launch_sparsify_batch(const void *X_f16, int batch, int m, float t, uint8_t *mask,
+                                 int32_t *idx, int32_t *count, hipStream_t stream)
+{
+    hipLaunchKernelGGL(sparsify_batch_kernel, dim3(1), dim3(kSparsifyWaves * 64), 0, stream,
+                       static_cast<const __half *>(X_f16), batch, m, (double)batch * (double)t,
+                       mask, idx, count);
+    return hipGetLastError();
+}
+
+}  // namespace teal

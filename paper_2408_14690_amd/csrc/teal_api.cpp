@@ -33,7 +33,7 @@ int max_splits_for(int m)
 // (c) a block's row segment is 256 B .. 1 KiB and starts on a 128-byte boundary
 // (or neighbouring blocks would each fetch the cache line they share).
 GemvShape auto_shape(int m, int n, int elems_per_lane, int min_lanes, int max_lanes,
-                     int ks_multiple)
+                     int ks_multiple, int max_slice = teal::kMaxSlice)
 {
     const int tc_min = min_lanes * elems_per_lane, tc_max = max_lanes * elems_per_lane;
     const int unit = 8 * elems_per_lane;                       // 128 bytes of a row
@@ -50,7 +50,7 @@ GemvShape auto_shape(int m, int n, int elems_per_lane, int min_lanes, int max_la
     }
     const int most = (m + 127) / 128;                          // at least 128 channels per block
     if (splits > most) splits = most;
-    const int least = (m + teal::kMaxSlice - 1) / teal::kMaxSlice;   // LDS list capacity
+    const int least = (m + max_slice - 1) / max_slice;         // LDS list capacity
     if (splits < least) splits = least;
     if (splits < 1) splits = 1;
     int ks = (m + splits - 1) / splits;
@@ -65,6 +65,15 @@ GemvShape auto_shape(int m, int n, int elems_per_lane, int min_lanes, int max_la
     sh.unroll = 4;
     return sh;
 }
+
+// Partial rows a batched call may need: one per (split, batch row).
+int batch_split_rows(int m)
+{
+    const int forced = (m + teal::kMaxSliceBatch - 1) / teal::kMaxSliceBatch;
+    return forced > 16 ? forced : 16;
+}
+
+int batch_accumulators(int batch) { return batch <= 2 ? 2 : batch <= 4 ? 4 : 8; }
 
 struct GemvArgs {
     const void *W;
@@ -118,7 +127,7 @@ const char *teal_status_string(teal_status s)
     return "unknown status";
 }
 
-int teal_version(void) { return 100; }
+int teal_version(void) { return 200; }
 
 size_t teal_workspace_bytes(int m, int n)
 {
@@ -212,6 +221,70 @@ teal_status teal_sparse_gemv_bf16_multi(int count, const void *const *Wt_bf16, c
     return from_hip(teal::launch_gemv_bf16_multi(count, Wt_bf16, t, y, n, x_f16, m,
                                                  ws_partials(workspace), ws_counters(workspace),
                                                  sh, static_cast<hipStream_t>(stream)));
+}
+
+size_t teal_workspace_bytes_batch(int m, int n, int batch)
+{
+    if (m < 1 || m > teal::kMaxDim || n < 1 || n > teal::kMaxDim || batch < 1 ||
+        batch > teal::kMaxBatch)
+        return 0;
+    const size_t rows = (size_t)batch_split_rows(m) * (size_t)batch;
+    const size_t bytes = teal::kCounterBytes + rows * (size_t)n * sizeof(float);
+    return (bytes + kAlignWorkspace - 1) / kAlignWorkspace * kAlignWorkspace;
+}
+
+teal_status teal_sparsify_batch(const void *X_f16, int batch, int m, float t, uint8_t *mask,
+                                int32_t *idx, int32_t *count, void *stream)
+{
+    if (m < 0 || batch < 1 || batch > teal::kMaxBatch) return TEAL_ERR_SHAPE;
+    if (!X_f16 && m > 0) return TEAL_ERR_NULL;
+    if (!aligned(X_f16, 2) || !aligned(idx, 4) || !aligned(count, 4)) return TEAL_ERR_ALIGN;
+    if (!threshold_ok(t)) return TEAL_ERR_THRESHOLD;
+    if (!mask && !idx && !count) return TEAL_OK;
+    return from_hip(teal::launch_sparsify_batch(X_f16, batch, m, t, mask, idx, count,
+                                                static_cast<hipStream_t>(stream)));
+}
+
+teal_status teal_sparse_gemv_bf16_batch_ex(const void *Wt_bf16, const void *X_f16, int batch,
+                                           float t, float *Y, int m, int n, void *workspace,
+                                           size_t workspace_bytes, void *stream,
+                                           int lanes_per_row, int tile_cols, int splits)
+{
+    if (!Wt_bf16 || !X_f16 || !Y || !workspace) return TEAL_ERR_NULL;
+    if (batch < 1 || batch > teal::kMaxBatch || m < 1 || m > teal::kMaxDim || n < 8 ||
+        n > teal::kMaxDim || n % 8 != 0)
+        return TEAL_ERR_SHAPE;
+    if (!aligned(Wt_bf16, 16) || !aligned(X_f16, 2) || !aligned(Y, 4) ||
+        !aligned(workspace, kAlignWorkspace))
+        return TEAL_ERR_ALIGN;
+    if (!threshold_ok(t)) return TEAL_ERR_THRESHOLD;
+    if (workspace_bytes < teal_workspace_bytes_batch(m, n, batch)) return TEAL_ERR_WORKSPACE;
+    // the block combine keeps one accumulator set per batch row in LDS: narrower tiles for
+    // larger batches
+    const int max_lanes = 256 / batch_accumulators(batch);
+    GemvShape sh = auto_shape(m, n, 8, 16, max_lanes > 64 ? 64 : max_lanes, 64,
+                              teal::kMaxSliceBatch);
+    if (lanes_per_row) {
+        sh.lanes_per_row = lanes_per_row;
+        if (!tile_cols && sh.tile_cols > lanes_per_row * 8) sh.tile_cols = lanes_per_row * 8;
+    }
+    if (splits) sh.splits = splits;
+    if (tile_cols) sh.tile_cols = tile_cols;
+    if (!teal::gemv_batch_shape_supported(batch, sh)) return TEAL_ERR_UNSUPPORTED;
+    const int ks = ((m + sh.splits - 1) / sh.splits + 63) / 64 * 64;
+    if (ks > teal::kMaxSliceBatch) return TEAL_ERR_UNSUPPORTED;
+    if ((m + ks - 1) / ks > batch_split_rows(m)) return TEAL_ERR_UNSUPPORTED;   // partial rows
+    return from_hip(teal::launch_gemv_bf16_batch(Wt_bf16, X_f16, batch, t, Y, m, n,
+                                                 ws_partials(workspace), ws_counters(workspace),
+                                                 sh, static_cast<hipStream_t>(stream)));
+}
+
+teal_status teal_sparse_gemv_bf16_batch(const void *Wt_bf16, const void *X_f16, int batch, float t,
+                                        float *Y, int m, int n, void *workspace,
+                                        size_t workspace_bytes, void *stream)
+{
+    return teal_sparse_gemv_bf16_batch_ex(Wt_bf16, X_f16, batch, t, Y, m, n, workspace,
+                                          workspace_bytes, stream, 0, 0, 0);
 }
 
 teal_status teal_sparse_gemv_w8(const int8_t *Wq, const void *scale_f16, const void *x_f16,

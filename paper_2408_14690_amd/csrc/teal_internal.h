@@ -13,6 +13,8 @@ constexpr int kMaxSlice = 4096;     // most input channels one block compacts (L
 constexpr int kMaxDim = 1 << 24;    // largest m or n accepted
 constexpr int kMaxMatrices = 4;     // matrices per fused launch
 constexpr int kMinTile = 64;        // narrowest output tile of any kernel variant
+constexpr int kMaxBatch = 8;        // rows of a small batch (Section 5.4.4)
+constexpr int kMaxSliceBatch = 2048;  // most input channels one block compacts for a batch
 // Head of the workspace: one arrival counter per output tile (zero between calls).
 constexpr size_t kCounterBytes = (size_t)(kMaxDim / kMinTile) * sizeof(int);
 
@@ -39,6 +41,17 @@ hipError_t launch_gemv_bf16_multi(int count, const void *const *Wt, const float 
                                   float *const *y, const int *n, const void *x_f16, int m,
                                   float *partial, int *counters, const GemvShape &shape,
                                   hipStream_t stream);
+
+// Small batch (Section 5.4.4).  The slice of a block, ceil(m / splits) rounded up to 64,
+// must not exceed kMaxSliceBatch.
+bool gemv_batch_shape_supported(int batch, const GemvShape &s);
+
+hipError_t launch_gemv_bf16_batch(const void *Wt, const void *X_f16, int batch, float t, float *Y,
+                                  int m, int n, float *partial, int *counters,
+                                  const GemvShape &shape, hipStream_t stream);
+
+hipError_t launch_sparsify_batch(const void *X_f16, int batch, int m, float t, uint8_t *mask,
+                                 int32_t *idx, int32_t *count, hipStream_t stream);
 
 hipError_t launch_gemv_w8(const int8_t *Wq, const void *scale_f16, const void *x_f16,
                           float t, float *y, int m, int n, float *partial, int *counters,

@@ -180,6 +180,49 @@ def test_calibration_argument_errors():
     assert T.teal_histogram_thresholds(H + 4, [0.5], Y, stream=0) == T.TEAL_ERR_ALIGN
 
 
+def test_batch_argument_errors():
+    ok = dict(Wt_bf16=W, X_f16=X, batch=4, t=0.5, Y=Y, m=4096, n=4096, workspace=WS,
+              workspace_bytes=BIG, stream=0)
+
+    def call(**kw):
+        a = dict(ok)
+        a.update(kw)
+        return T.teal_sparse_gemv_bf16_batch(**a)
+
+    assert call(Wt_bf16=None) == T.TEAL_ERR_NULL
+    assert call(X_f16=None) == T.TEAL_ERR_NULL
+    assert call(Y=None) == T.TEAL_ERR_NULL
+    assert call(workspace=None) == T.TEAL_ERR_NULL
+    assert call(batch=0) == T.TEAL_ERR_SHAPE
+    assert call(batch=T.TEAL_MAX_BATCH + 1) == T.TEAL_ERR_SHAPE
+    assert call(n=4100) == T.TEAL_ERR_SHAPE
+    assert call(m=0) == T.TEAL_ERR_SHAPE
+    assert call(Wt_bf16=W + 8) == T.TEAL_ERR_ALIGN
+    assert call(X_f16=X + 1) == T.TEAL_ERR_ALIGN
+    assert call(t=-1.0) == T.TEAL_ERR_THRESHOLD
+    assert call(t=math.nan) == T.TEAL_ERR_THRESHOLD
+    need = T.teal_workspace_bytes_batch(4096, 4096, 4)
+    assert need % 256 == 0 and need >= (1 << 24) // 64 * 4 + 16 * 4 * 4096 * 4
+    assert call(workspace_bytes=need - 1) == T.TEAL_ERR_WORKSPACE
+    assert T.teal_workspace_bytes_batch(4096, 4096, 0) == 0
+    assert T.teal_workspace_bytes_batch(4096, 4096, 9) == 0
+    # long inputs: a block compacts at most 2048 channels of a batch, so more partial rows
+    assert T.teal_workspace_bytes_batch(1 << 16, 8, 2) >= (1 << 16) // 2048 * 2 * 8 * 4
+    base = (W, X, 8, 0.5, Y, 4096, 4096, WS, BIG, 0)
+    assert T.teal_sparse_gemv_bf16_batch_ex(*base, lanes_per_row=64) == T.TEAL_ERR_UNSUPPORTED
+    assert T.teal_sparse_gemv_bf16_batch_ex(*base, lanes_per_row=8) == T.TEAL_ERR_UNSUPPORTED
+    assert T.teal_sparse_gemv_bf16_batch_ex(*base, splits=1) == T.TEAL_ERR_UNSUPPORTED   # slice of 4096
+    assert T.teal_sparse_gemv_bf16_batch_ex(*base, splits=64) == T.TEAL_ERR_UNSUPPORTED  # partial rows
+    assert T.teal_sparse_gemv_bf16_batch_ex(*base, tile_cols=12) == T.TEAL_ERR_UNSUPPORTED
+    assert T.teal_sparsify_batch(None, 2, 16, 0.5, Y, None, None, stream=0) == T.TEAL_ERR_NULL
+    assert T.teal_sparsify_batch(X, 0, 16, 0.5, Y, None, None, stream=0) == T.TEAL_ERR_SHAPE
+    assert T.teal_sparsify_batch(X, 9, 16, 0.5, Y, None, None, stream=0) == T.TEAL_ERR_SHAPE
+    assert T.teal_sparsify_batch(X, 2, -1, 0.5, Y, None, None, stream=0) == T.TEAL_ERR_SHAPE
+    assert T.teal_sparsify_batch(X + 1, 2, 16, 0.5, Y, None, None, stream=0) == T.TEAL_ERR_ALIGN
+    assert T.teal_sparsify_batch(X, 2, 16, -0.5, Y, None, None, stream=0) == T.TEAL_ERR_THRESHOLD
+    assert T.teal_sparsify_batch(X, 2, 16, 0.5, None, None, None, stream=0) == T.TEAL_OK
+
+
 def test_check_raises_with_message():
     with pytest.raises(T.TealError) as e:
         T.check(T.TEAL_ERR_WORKSPACE)
