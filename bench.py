@@ -44,18 +44,21 @@ KERNEL = {"bf16": "sparse_gemv_kernel<FmtBF16>", "w8": "sparse_gemv_kernel<FmtW8
 MEASURED_TRAFFIC_BYTES = {("llama2_7b", "bf16", 0.5, 1): (200319.57 + 1555.31) * 1024 / 7}
 
 
-def algorithmic_bytes(fmt: str, nnz: int, m: int, n: int) -> int:
-    """Bytes the method must move for one projection: surviving rows + x + y + scales."""
+def algorithmic_bytes(fmt: str, nnz: int, m: int, n: int, batch: int = 1) -> int:
+    """Bytes the method must move for one projection: surviving rows (once, whatever the
+    batch) + x + y per batch row + scales."""
     scales = {"bf16": 0, "w8": 2 * n, "w4": 2 * n * (m // 128)}[fmt]
-    return nnz * n * BITS[fmt] // 8 + 2 * m + 4 * n + scales
+    return nnz * n * BITS[fmt] // 8 + batch * (2 * m + 4 * n) + scales
 
 
 class Projection:
     """One weight matrix resident on the device in the format under test."""
 
     def __init__(self, T, torch, name, n, m, fmt, x_host, sparsities, copies, w_host=None,
-                 device_seed=None):
-        self.name, self.n, self.m, self.fmt = name, n, m, fmt
+                 device_seed=None, batch=0):
+        """batch = 0: one hidden state x_host[m] (Definition 1); batch >= 1: x_host is
+        [batch][m] and the batch-wide criterion of Section 5.4.4 applies."""
+        self.name, self.n, self.m, self.fmt, self.batch = name, n, m, fmt, batch
         self.x_host, self.w_host = x_host, w_host
         self.host_q = None
         if w_host is None:
@@ -82,13 +85,19 @@ class Projection:
         del wd
         self.weights = [first] + [tuple(t.clone() for t in first) for _ in range(copies - 1)]
         self.x = torch.from_numpy(x_host.view(np.int16)).cuda()
-        self.y = torch.empty(n, dtype=torch.float32, device="cuda")
-        self.ws = torch.zeros(T.teal_workspace_bytes(m, n), dtype=torch.uint8, device="cuda")
+        self.y = torch.empty(max(batch, 1) * n, dtype=torch.float32, device="cuda")
+        ws_bytes = T.teal_workspace_bytes_batch(m, n, batch) if batch else T.teal_workspace_bytes(m, n)
+        self.ws = torch.zeros(ws_bytes, dtype=torch.uint8, device="cuda")
         self.t, self.nnz = {}, {}
         for p in sparsities:
-            t = ti.quantile_threshold(x_host, p)
+            if batch:
+                t = ti.batch_quantile_threshold(x_host, p)
+                total = np.abs(x_host.astype(np.float64)).sum(axis=0)
+                self.nnz[p] = int(np.count_nonzero(total > batch * float(np.float32(t))))
+            else:
+                t = ti.quantile_threshold(x_host, p)
+                self.nnz[p] = int(np.count_nonzero(np.abs(x_host.astype(np.float32)) > np.float32(t)))
             self.t[p] = t
-            self.nnz[p] = int(np.count_nonzero(np.abs(x_host.astype(np.float32)) > np.float32(t)))
         # raw device addresses, so that the timed loop spends its host time in the library call
         self.wp = [tuple(t.data_ptr() for t in w) for w in self.weights]
         self.xp, self.yp, self.wsp = self.x.data_ptr(), self.y.data_ptr(), self.ws.data_ptr()
@@ -97,6 +106,10 @@ class Projection:
 
     def launch(self, T, copy: int, p: float) -> int:
         w = self.wp[copy % len(self.wp)]
+        if self.batch:
+            return T.teal_sparse_gemv_bf16_batch(w[0], self.xp, self.batch, self.t[p], self.yp,
+                                                 self.m, self.n, self.wsp, self.ws_bytes,
+                                                 self.stream)
         if self.fmt == "bf16":
             return T.teal_sparse_gemv_bf16(w[0], self.xp, self.t[p], self.yp, self.m, self.n,
                                            self.wsp, self.ws_bytes, self.stream)
@@ -107,9 +120,11 @@ class Projection:
                                      self.wsp, self.ws_bytes, self.stream)
 
     def bytes(self, p: float) -> int:
-        return algorithmic_bytes(self.fmt, self.nnz[p], self.m, self.n)
+        return algorithmic_bytes(self.fmt, self.nnz[p], self.m, self.n, max(self.batch, 1))
 
     def oracle(self, orc, p: float):
+        if self.batch:
+            return orc.sparse_gemv_bf16_batch(self.w_host, self.x_host, self.t[p])
         if self.fmt == "bf16":
             return orc.sparse_gemv_bf16(self.w_host, self.x_host, self.t[p])
         if self.fmt == "w8":
@@ -156,7 +171,7 @@ def fuse(T, torch, stack):
     return out
 
 
-def build_stack(T, torch, model, fmt, sparsities, layers, copies):
+def build_stack(T, torch, model, fmt, sparsities, layers, copies, batch=0):
     """`layers` synthetic blocks.  Block 0 comes from the seeded host recipe (so the CPU
     baseline sees the same numbers); further blocks of a bf16 stack draw their weights on
     the device."""
@@ -166,10 +181,13 @@ def build_stack(T, torch, model, fmt, sparsities, layers, copies):
         host = layer == 0 or fmt != "bf16"
         for proj in ti.PROJ_ORDER:
             n, m = ti.LAYER_SHAPES[model][proj]
-            x = ti.make_x(m, ti.x_seed(cfg, layer, proj), ti.PROJ_DIST[proj])
+            if batch:
+                x = ti.make_X(batch, m, ti.x_seed(cfg, layer, proj), ti.PROJ_DIST[proj])
+            else:
+                x = ti.make_x(m, ti.x_seed(cfg, layer, proj), ti.PROJ_DIST[proj])
             w = ti.weights_bf16(n, m, ti.weight_seed(cfg, layer, proj)) if host else None
             stack.append(Projection(T, torch, proj, n, m, fmt, x, sparsities, copies, w_host=w,
-                                    device_seed=ti.weight_seed(cfg, layer, proj)))
+                                    device_seed=ti.weight_seed(cfg, layer, proj), batch=batch))
             if layer > 0:
                 stack[-1].w_host = None          # keep host memory flat for deep stacks
                 stack[-1].host_q = None
@@ -344,6 +362,9 @@ def main() -> int:
     ap.add_argument("--fused", action="store_true",
                     help="one launch per group of projections that share their input "
                          "(q+k+v, o, gate+up, down) instead of one per projection; bf16 only")
+    ap.add_argument("--batch", type=int, default=0,
+                    help="B >= 1: a small batch of B hidden states per projection with the batch-wide "
+                         "mask of the averaged magnitude (Section 5.4.4); bf16 only. 0 = one state")
     ap.add_argument("--calibration", action="store_true",
                     help="time threshold calibration (histogram + thresholds) instead of the GEMV path")
     ap.add_argument("--calibration-tokens", type=int, default=16384)
@@ -381,7 +402,10 @@ def main() -> int:
         copies = args.copies or 1
     else:
         copies = args.copies or max(2, -(-CACHE_DEFEAT_BYTES // block_bytes))
-    stack = build_stack(T, torch, args.workload, fmt, sparsities, args.layers, copies)
+    if args.batch and (fmt != "bf16" or args.fused or not 1 <= args.batch <= T.TEAL_MAX_BATCH):
+        print("bench.py: --batch needs bf16, no --fused, and 1 <= B <= 8", file=sys.stderr)
+        return 2
+    stack = build_stack(T, torch, args.workload, fmt, sparsities, args.layers, copies, args.batch)
     block0 = stack[:7]
     if args.fused:
         if fmt != "bf16":
@@ -412,7 +436,7 @@ def main() -> int:
     # The same pass with one launch per group of projections that share their input
     # (q+k+v, o, gate+up, down: Appendix A.3) through teal_sparse_gemv_bf16_multi.
     fused_detail = {}
-    if fmt == "bf16" and not args.fused and not args.no_fused_detail:
+    if fmt == "bf16" and not args.fused and not args.no_fused_detail and not args.batch:
         groups = fuse(T, torch, stack)
         fsec = {p: time_steps(T, torch, groups, p, args.steps, args.warmup) for p in sparsities}
         for p in sparsities:
@@ -431,6 +455,8 @@ def main() -> int:
             us = time_projection(T, torch, P, head, 300) * 1e6
             us_dense = time_projection(T, torch, P, 0.0, 300) * 1e6
             _, plan = T.teal_gemv_plan(BITS[fmt], P.m, P.n)
+            if args.batch:
+                plan = {"note": "batched launch shape is chosen inside teal_sparse_gemv_bf16_batch"}
             b = P.bytes(head)
             per_proj[P.name] = {
                 "n": P.n, "m": P.m, "nnz": P.nnz[head], "us": us, "us_dense": us_dense,
@@ -454,8 +480,9 @@ def main() -> int:
         "data": "synthetic",
         "config": {
             "workload": f"{args.workload}-shaped decoder block x {args.layers}, 7 projections "
-                        f"each, batch 1, {fmt} W from N(0,0.02^2), fp16 x (Gaussian / Laplace by "
-                        f"role), t at the {pct(head)} quantile of |x| per projection",
+                        f"each, batch {max(args.batch, 1)}, {fmt} W from N(0,0.02^2), fp16 x (Gaussian / "
+                        f"Laplace by role), t at the {pct(head)} quantile of "
+                        f"{'the batch-averaged |x|' if args.batch else '|x|'} per projection",
             "weight_format": fmt,
             "weight_bytes_per_block": block_bytes,
             "blocks_per_step": args.layers,
@@ -470,7 +497,7 @@ def main() -> int:
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
             "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, fmt, head, args.layers)),
-            "kernel": f"{'sparse_gemv_multi_kernel<FmtBF16>' if args.fused else KERNEL[fmt]} "
+            "kernel": f"{'sparse_gemv_multi_kernel<FmtBF16>' if args.fused else 'sparse_gemv_batch_kernel' if args.batch else KERNEL[fmt]} "
                       f"({launches_per_step} launches per step, {pct(head)})",
             "bytes_per_launch_avg": head_bytes / launches_per_step,
             "kernel_avg_us": seconds[head] * 1e6 / launches_per_step,

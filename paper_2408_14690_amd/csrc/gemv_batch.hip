@@ -40,12 +40,17 @@ __device__ __forceinline__ int compact_slice_batch(const __half *__restrict__ X,
 
     float xv[PER_WAVE][NB];
     unsigned long long bal[PER_WAVE];
+    // Unconditional loads from clamped positions (k1 > k0, batch >= 1), zeroed afterwards
+    // where out of range, so that all loads are in flight together.
 #pragma unroll
     for (int j = 0; j < PER_WAVE; ++j) {
         const int i = k0 + (w + j * WAVES) * 64 + lane;
+        const int ic = min(i, k1 - 1);
 #pragma unroll
-        for (int b = 0; b < NB; ++b)
-            xv[j][b] = (i < k1 && b < batch) ? __half2float(X[(size_t)b * m + i]) : 0.f;
+        for (int b = 0; b < NB; ++b) {
+            const float v = __half2float(X[(size_t)min(b, batch - 1) * m + ic]);
+            xv[j][b] = (i < k1 && b < batch) ? v : 0.f;
+        }
     }
 #pragma unroll
     for (int j = 0; j < PER_WAVE; ++j) {
@@ -75,12 +80,66 @@ __device__ __forceinline__ int compact_slice_batch(const __half *__restrict__ X,
     return total;
 }
 
-// stream_rows for a batch: per surviving row one 16-byte load per lane, the 8
-// weights converted once and multiplied into NB accumulator sets.  The NB
-// activations of a row are read from LDS when the row is consumed; slots past
-// the end of the wavefront's share point at an all-zero entry (zero_slot).
+// The accumulators of one lane: a[bb][e] belongs to batch row bb and to column e
+// of the lane's 8 columns.  Plain fp32 FMAs; products are exact in fp32 (8 + 11
+// significand bits) and each accumulator sees its rows in list order.  (An
+// outer-product formulation on the matrix cores, v_mfma_f32_4x4x1_16b_f32 with
+// the weights as A and the batch's activations as B, computes the same sums
+// but measured slower than the FMAs at 4 and 8 rows.)
+template <int NB>
+struct BatchAcc {
+    float a[NB][8];
+    __device__ __forceinline__ void clear()
+    {
+#pragma unroll
+        for (int bb = 0; bb < NB; ++bb)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) a[bb][e] = 0.f;
+    }
+};
+
+// The NB activations of one surviving row.
+template <int NB>
+struct RowX {
+    float v[NB];
+};
+
+template <int NB>
+__device__ __forceinline__ RowX<NB> load_row_x(const float *entry)
+{
+    RowX<NB> r;
+    if constexpr (NB == 2) {
+        const float2 f = *reinterpret_cast<const float2 *>(entry);
+        r.v[0] = f.x; r.v[1] = f.y;
+    } else {
+#pragma unroll
+        for (int q = 0; q < NB / 4; ++q) {
+            const float4 f = *reinterpret_cast<const float4 *>(entry + 4 * q);
+            r.v[4 * q] = f.x; r.v[4 * q + 1] = f.y; r.v[4 * q + 2] = f.z; r.v[4 * q + 3] = f.w;
+        }
+    }
+    return r;
+}
+
+template <int NB>
+__device__ __forceinline__ void multiply_row(BatchAcc<NB> &acc, u32x4 w, const RowX<NB> &x)
+{
+    float wv[8];                       // bf16 -> fp32 is a 16-bit shift
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        wv[2 * q] = __uint_as_float(w[q] << 16);
+        wv[2 * q + 1] = __uint_as_float(w[q] & 0xffff0000u);
+    }
+#pragma unroll
+    for (int bb = 0; bb < NB; ++bb)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc.a[bb][e] = fmaf(x.v[bb], wv[e], acc.a[bb][e]);
+}
+
+// stream_rows for a batch: per surviving row one 16-byte load per lane.  Slots
+// past the end of the wavefront's share point at an all-zero entry (zero_slot).
 template <int NB, int LPR, int U>
-__device__ __forceinline__ void stream_rows_batch(float (&acc)[NB][8], const int *list_idx,
+__device__ __forceinline__ void stream_rows_batch(BatchAcc<NB> &acc, const int *list_idx,
                                                   const float *list_x, int zero_slot, int start,
                                                   int mine,
                                                   const unsigned char *__restrict__ lane_base,
@@ -94,56 +153,42 @@ __device__ __forceinline__ void stream_rows_batch(float (&acc)[NB][8], const int
 
     struct Batch {
         u32x4 v[U];
-        int slot[U];
+        RowX<NB> x[U];
     };
+    // The activations are fetched from LDS when the row load is issued, so that they
+    // are in registers long before the weights arrive.
     auto issue = [&](Batch &b, int batch_no) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int e = (batch_no * U + u) * R + g;
             const int row = list_idx[start + min(e, last)];
-            b.slot[u] = e <= last ? start + e : zero_slot;
             b.v[u] = load_stream16(lane_base + (size_t)(unsigned)row * row_bytes);
+            b.x[u] = load_row_x<NB>(list_x + (e <= last ? start + e : zero_slot) * NB);
         }
     };
     auto consume = [&](const Batch &b) {
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            float xs[NB];
-            if constexpr (NB >= 4) {
-#pragma unroll
-                for (int q = 0; q < NB / 4; ++q) {
-                    const float4 f =
-                        *reinterpret_cast<const float4 *>(list_x + b.slot[u] * NB + 4 * q);
-                    xs[4 * q] = f.x; xs[4 * q + 1] = f.y; xs[4 * q + 2] = f.z; xs[4 * q + 3] = f.w;
-                }
-            } else {
-                const float2 f = *reinterpret_cast<const float2 *>(list_x + b.slot[u] * NB);
-                xs[0] = f.x; xs[1] = f.y;
-            }
-            float wv[8];                       // bf16 -> fp32 is a 16-bit shift
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                wv[2 * q] = __uint_as_float(b.v[u][q] << 16);
-                wv[2 * q + 1] = __uint_as_float(b.v[u][q] & 0xffff0000u);
-            }
-#pragma unroll
-            for (int bb = 0; bb < NB; ++bb)
-#pragma unroll
-                for (int e = 0; e < 8; ++e) acc[bb][e] = fmaf(xs[bb], wv[e], acc[bb][e]);
-        }
+        for (int u = 0; u < U; ++u) multiply_row<NB>(acc, b.v[u], b.x[u]);
     };
 
+    // Scheduling fences keep the two batches apart: without them the compiler issues both
+    // batches back to back and drains the queue before the next pair.
     Batch b0, b1;
     issue(b0, 0);
     int it = 0;
     for (; it + 2 < batches; it += 2) {
         issue(b1, it + 1);
+        __builtin_amdgcn_sched_barrier(0);
         consume(b0);
+        __builtin_amdgcn_sched_barrier(0);
         issue(b0, it + 2);
+        __builtin_amdgcn_sched_barrier(0);
         consume(b1);
+        __builtin_amdgcn_sched_barrier(0);
     }
     if (it + 1 < batches) {
         issue(b1, it + 1);
+        __builtin_amdgcn_sched_barrier(0);
         consume(b0);
         consume(b1);
     } else {
@@ -151,37 +196,51 @@ __device__ __forceinline__ void stream_rows_batch(float (&acc)[NB][8], const int
     }
 }
 
-// block_finish for a batch.  red[] (WAVES x NB x TN floats) lies over the list,
+// Leaves every lane's accumulators in red[], laid out [wavefront x row group]
+// [batch row][tile column].
+template <int NB, int LPR>
+__device__ __forceinline__ void accumulators_to_lds(const BatchAcc<NB> &acc, float *red)
+{
+    constexpr int TN = LPR * 8;
+    constexpr int R = 64 / LPR;
+    const int lane = threadIdx.x & 63;
+    const int w = threadIdx.x >> 6;
+    const int g = lane / LPR, l = lane % LPR;
+    float *mine = red + (size_t)((w * R + g) * NB) * TN;
+#pragma unroll
+    for (int bb = 0; bb < NB; ++bb) {
+        float4 *dst = reinterpret_cast<float4 *>(mine + bb * TN + l * 8);
+        dst[0] = make_float4(acc.a[bb][0], acc.a[bb][1], acc.a[bb][2], acc.a[bb][3]);
+        dst[1] = make_float4(acc.a[bb][4], acc.a[bb][5], acc.a[bb][6], acc.a[bb][7]);
+    }
+}
+
+// block_finish for a batch.  red[] (WAVES x 64 lanes x NB x 8 floats) lies over the list,
 // which is dead once every wavefront has left the row stream.  Partial rows are
 // laid out [split][batch row][n]; the block that arrives last at the tile's
 // counter adds them in split order for every batch row and writes Y.
 template <int NB, int LPR, int WAVES>
-__device__ __forceinline__ void block_finish_batch(const float (&acc)[NB][8], float *red,
+__device__ __forceinline__ void block_finish_batch(const BatchAcc<NB> &acc, float *red,
                                                    float *partial, int *counters, float *Y,
                                                    int tile, int col0, int cols, int s, int splits,
                                                    int n, int batch)
 {
     constexpr int TN = LPR * 8;
     constexpr int THREADS = WAVES * 64;
+    constexpr int R = 64 / LPR;
     __shared__ int last_flag;
-    const int lane = threadIdx.x & 63;
-    const int w = threadIdx.x >> 6;
     if (cols > n - col0) cols = n - col0;
     __syncthreads();                   // every wavefront is done with the list
-    if (lane < LPR) {
-#pragma unroll
-        for (int bb = 0; bb < NB; ++bb) {
-            float4 *dst = reinterpret_cast<float4 *>(red + (w * NB + bb) * TN + lane * 8);
-            dst[0] = make_float4(acc[bb][0], acc[bb][1], acc[bb][2], acc[bb][3]);
-            dst[1] = make_float4(acc[bb][4], acc[bb][5], acc[bb][6], acc[bb][7]);
-        }
-    }
+    // Every lane leaves its accumulators in LDS: WAVES x R row groups per output.  (Folding
+    // the R row groups of a wavefront with lane shuffles first costs more than the extra
+    // LDS reads below once there are several accumulator sets.)
+    accumulators_to_lds<NB, LPR>(acc, red);
     __syncthreads();
     const int total = batch * cols;
     auto wave_sum = [&](int bb, int c) {
         float sum = 0.f;
 #pragma unroll
-        for (int ww = 0; ww < WAVES; ++ww) sum += red[(ww * NB + bb) * TN + c];
+        for (int q = 0; q < WAVES * R; ++q) sum += red[(q * NB + bb) * TN + c];
         return sum;
     };
     if (splits == 1) {
@@ -201,21 +260,41 @@ __device__ __forceinline__ void block_finish_batch(const float (&acc)[NB][8], fl
     __syncthreads();
     if (!last_flag) return;
 
-    constexpr int MAXLD = 8;
+    // Second pass.  A thread owns up to OUT outputs (batch row, column) and keeps the
+    // loads of MAXLD splits of all of them in flight at once; each output is summed in
+    // split order, so the result does not depend on which block is last.
+    constexpr int OUT = (NB * TN + THREADS - 1) / THREADS;
+    constexpr int MAXLD = 16;
     const size_t split_stride = (size_t)batch * n;
-    for (int k = threadIdx.x; k < total; k += THREADS) {
-        const int bb = k / cols, c = k - bb * cols;
-        const float *p = partial + (size_t)bb * n + col0 + c;
-        float sum = 0.f;
-        for (int k0 = 0; k0 < splits; k0 += MAXLD) {
-            float v[MAXLD];
+    const float *p[OUT];
+    float sum[OUT];
+#pragma unroll
+    for (int o = 0; o < OUT; ++o) {
+        const int k = (int)threadIdx.x + o * THREADS;
+        const int bb = k < total ? k / cols : 0, c = k < total ? k - bb * cols : 0;
+        p[o] = partial + (size_t)bb * n + col0 + c;
+        sum[o] = 0.f;
+    }
+    for (int k0 = 0; k0 < splits; k0 += MAXLD) {
+        float v[OUT][MAXLD];
+#pragma unroll
+        for (int o = 0; o < OUT; ++o)
 #pragma unroll
             for (int u = 0; u < MAXLD; ++u)
-                v[u] = k0 + u < splits ? load_coherent(p + (size_t)(k0 + u) * split_stride) : 0.f;
+                v[o][u] = ((int)threadIdx.x + o * THREADS < total && k0 + u < splits)
+                              ? load_coherent(p[o] + (size_t)(k0 + u) * split_stride) : 0.f;
 #pragma unroll
-            for (int u = 0; u < MAXLD; ++u) sum += v[u];
+        for (int o = 0; o < OUT; ++o)
+#pragma unroll
+            for (int u = 0; u < MAXLD; ++u) sum[o] += v[o][u];
+    }
+#pragma unroll
+    for (int o = 0; o < OUT; ++o) {
+        const int k = (int)threadIdx.x + o * THREADS;
+        if (k < total) {
+            const int bb = k / cols, c = k - bb * cols;
+            Y[(size_t)bb * n + col0 + c] = sum[o];
         }
-        Y[(size_t)bb * n + col0 + c] = sum;
     }
     if (threadIdx.x == 0) atomicExch(&counters[tile], 0);
 }
@@ -251,18 +330,9 @@ __global__ __launch_bounds__(WAVES * 64) void sparse_gemv_batch_kernel(
     const unsigned row_bytes = (unsigned)n * 2u;
     const unsigned char *lane_base = static_cast<const unsigned char *>(W) + (size_t)col * 2;
 
-    float acc[NB][8];
-#pragma unroll
-    for (int bb = 0; bb < NB; ++bb)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) acc[bb][e] = 0.f;
+    BatchAcc<NB> acc;
+    acc.clear();
     stream_rows_batch<NB, LPR, U>(acc, list_idx, list_x, ks, start, mine, lane_base, row_bytes);
-#pragma unroll
-    for (int off = LPR; off < 64; off <<= 1)
-#pragma unroll
-        for (int bb = 0; bb < NB; ++bb)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) acc[bb][e] += __shfl_xor(acc[bb][e], off);
     block_finish_batch<NB, LPR, WAVES>(acc, red, partial, counters, Y, tile, col0, tile_cols, s,
                                        splits, n, batch);
 }
@@ -318,7 +388,7 @@ bool gemv_batch_shape_supported(int batch, const GemvShape &s)
     const int nb = batch <= 2 ? 2 : batch <= 4 ? 4 : 8;
     const bool lpr = s.lanes_per_row == 64 || s.lanes_per_row == 32 || s.lanes_per_row == 16;
     const bool tc = s.tile_cols >= 0 && s.tile_cols % 8 == 0 && s.tile_cols <= s.lanes_per_row * 8;
-    // the block combine holds waves x nb x (8 * lanes) floats in LDS: at most 64 KiB
+    // a thread of the second pass owns at most 4 outputs: nb x (8 * lanes) <= 2048
     const bool fits = nb * s.lanes_per_row <= 256;
     return lpr && tc && fits && s.waves == kBatchWaves && s.unroll == kBatchUnroll &&
            s.splits >= 1 && s.splits <= kMaxSplits;
@@ -332,7 +402,7 @@ hipError_t launch_gemv_bf16_batch(const void *Wt, const void *X_f16, int batch, 
     if (g.ks > kMaxSliceBatch || !gemv_batch_shape_supported(batch, sh)) return hipErrorInvalidValue;
     const int nb = batch <= 2 ? 2 : batch <= 4 ? 4 : 8;
     const size_t list_bytes = (size_t)(g.ks + 1) * nb * sizeof(float) + (size_t)g.ks * sizeof(int);
-    const size_t red_bytes = (size_t)kBatchWaves * nb * sh.lanes_per_row * 8 * sizeof(float);
+    const size_t red_bytes = (size_t)kBatchWaves * 64 * nb * 8 * sizeof(float);
     const size_t lds = list_bytes > red_bytes ? list_bytes : red_bytes;
     const double bound = (double)batch * (double)t;
     const __half *X = static_cast<const __half *>(X_f16);

@@ -94,10 +94,13 @@ __device__ __forceinline__ int compact_slice(const __half *__restrict__ x, float
 
     float xv[PER_WAVE];
     unsigned long long bal[PER_WAVE];
+    // Unconditional loads from a clamped position (k1 > k0), the out-of-range lanes zeroed
+    // afterwards: a load inside a branch is waited for before the next one is issued.
 #pragma unroll
     for (int j = 0; j < PER_WAVE; ++j) {
         const int i = k0 + (w + j * WAVES) * 64 + lane;
-        xv[j] = i < k1 ? __half2float(x[i]) : 0.f;    // x = 0 never survives (t >= 0)
+        const float v = __half2float(x[min(i, k1 - 1)]);
+        xv[j] = i < k1 ? v : 0.f;                     // x = 0 never survives (t >= 0)
     }
 #pragma unroll
     for (int j = 0; j < PER_WAVE; ++j) {

@@ -259,11 +259,10 @@ teal_status teal_sparse_gemv_bf16_batch_ex(const void *Wt_bf16, const void *X_f1
         return TEAL_ERR_ALIGN;
     if (!threshold_ok(t)) return TEAL_ERR_THRESHOLD;
     if (workspace_bytes < teal_workspace_bytes_batch(m, n, batch)) return TEAL_ERR_WORKSPACE;
-    // the block combine keeps one accumulator set per batch row in LDS: narrower tiles for
-    // larger batches
-    const int max_lanes = 256 / batch_accumulators(batch);
-    GemvShape sh = auto_shape(m, n, 8, 16, max_lanes > 64 ? 64 : max_lanes, 64,
-                              teal::kMaxSliceBatch);
+    // With several accumulator sets per lane, sweeps favour narrow tiles (128 columns) and
+    // correspondingly fewer splits over the wide tiles of the single-vector kernel.
+    const int max_lanes = batch_accumulators(batch) >= 4 ? 16 : 64;
+    GemvShape sh = auto_shape(m, n, 8, 16, max_lanes, 64, teal::kMaxSliceBatch);
     if (lanes_per_row) {
         sh.lanes_per_row = lanes_per_row;
         if (!tile_cols && sh.tile_cols > lanes_per_row * 8) sh.tile_cols = lanes_per_row * 8;
