@@ -3,20 +3,26 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W]
                     [--workload llama2_7b|llama3_8b|llama_70b] [--format bf16|w8|w4]
-                    [--sparsities 0.5,0.4,0] [--layers L]
+                    [--sparsities 0.5,0.4,0] [--layers L] [--unfused] [--batch B]
+                    [--calibration]
 
 A step is one pass of the whole hot path over a synthetic decoder block at
 batch 1: for each of the seven projections, threshold the hidden state, compact
-the survivors and stream only the surviving weight rows (one C-ABI call = one
-kernel launch per projection).  The headline value is the effective HBM
-bandwidth of that pass at the first listed sparsity (50% by default):
-algorithmic bytes / time.  The same pass at the other sparsities, and at 0%
-(t = 0, the same kernels run dense), gives the speed-up over dense.  Weights,
-states and the workspace are resident in HBM before the timed region.
+the survivors and stream only the surviving weight rows.  By default (bf16) the
+projections that read the same hidden state -- q+k+v, o, gate+up, down, each
+projection with its own threshold -- go out as one C-ABI call = one kernel
+launch per group, 4 launches per block; --unfused launches every projection
+on its own (7 per block), and both are timed and reported.  The headline value
+is the effective HBM bandwidth of that pass at the first listed sparsity (50%
+by default): algorithmic bytes / time.  The same pass at the other sparsities,
+and at 0% (t = 0, the same kernels run dense), gives the speed-up over dense.
+Weights, states and the workspace are resident in HBM before the timed region.
 Consecutive steps walk over several copies of the weights so that no step
 finds its rows in the 256 MB last-level cache.  With --layers L > 1 a step is
 a stack of L blocks with their own weights and states (the 80-block
-70B-shaped stack is 137 GB resident), and no copies are needed.
+70B-shaped stack is 137 GB resident), and no copies are needed.  --batch B
+runs the small-batch variant (one mask per batch from the averaged magnitude),
+--calibration the threshold calibration pass.
 
 Prints ONE JSON line.  More than one GPU is not supported.
 """
@@ -41,7 +47,7 @@ KERNEL = {"bf16": "sparse_gemv_kernel<FmtBF16>", "w8": "sparse_gemv_kernel<FmtW8
 # from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script, scaled by the factors a
 # plain copy of known size gives on the same box (2.0 and 1.0):
 # profiles/sparse_gemv_kernel_llama2_7b_hbm_traffic.txt.
-MEASURED_TRAFFIC_BYTES = {("llama2_7b", "bf16", 0.5, 1): (200319.57 + 1555.31) * 1024 / 7}
+MEASURED_TRAFFIC_BYTES = {("llama2_7b", "bf16", 0.5, 1, False): (200319.57 + 1555.31) * 1024 / 7}
 
 
 def algorithmic_bytes(fmt: str, nnz: int, m: int, n: int, batch: int = 1) -> int:
@@ -360,8 +366,10 @@ def main() -> int:
     ap.add_argument("--layers", type=int, default=1, help="blocks per step (a stack when > 1)")
     ap.add_argument("--copies", type=int, default=0, help="weight copies to walk (0 = auto)")
     ap.add_argument("--fused", action="store_true",
-                    help="one launch per group of projections that share their input "
-                         "(q+k+v, o, gate+up, down) instead of one per projection; bf16 only")
+                    help="(default for bf16 at batch 1) one launch per group of projections that "
+                         "read the same hidden state: q+k+v, o, gate+up, down")
+    ap.add_argument("--unfused", action="store_true",
+                    help="one launch per projection (7 per block) as the headline")
     ap.add_argument("--batch", type=int, default=0,
                     help="B >= 1: a small batch of B hidden states per projection with the batch-wide "
                          "mask of the averaged magnitude (Section 5.4.4); bf16 only. 0 = one state")
@@ -370,7 +378,8 @@ def main() -> int:
     ap.add_argument("--calibration-tokens", type=int, default=16384)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-per-projection", action="store_true")
-    ap.add_argument("--no-fused-detail", action="store_true")
+    ap.add_argument("--no-other-mode", action="store_true",
+                    help="skip timing the pass in the launch mode that is not the headline")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only; --gpus must be 1", file=sys.stderr)
@@ -396,74 +405,82 @@ def main() -> int:
         sparsities.append(0.0)
     head = sparsities[0]
     fmt = args.format
+    fused = fmt == "bf16" and not args.batch and not args.unfused
+    if args.fused and not fused:
+        print("bench.py: fused launches exist for bf16 at batch 1 only", file=sys.stderr)
+        return 2
     shapes = ti.LAYER_SHAPES[args.workload]
     block_bytes = sum(n * m * BITS[fmt] // 8 for n, m in shapes.values())
     if args.layers > 1:
         copies = args.copies or 1
     else:
         copies = args.copies or max(2, -(-CACHE_DEFEAT_BYTES // block_bytes))
-    if args.batch and (fmt != "bf16" or args.fused or not 1 <= args.batch <= T.TEAL_MAX_BATCH):
-        print("bench.py: --batch needs bf16, no --fused, and 1 <= B <= 8", file=sys.stderr)
+    if args.batch and (fmt != "bf16" or not 1 <= args.batch <= T.TEAL_MAX_BATCH):
+        print("bench.py: --batch needs bf16 and 1 <= B <= 8", file=sys.stderr)
         return 2
-    stack = build_stack(T, torch, args.workload, fmt, sparsities, args.layers, copies, args.batch)
-    block0 = stack[:7]
-    if args.fused:
-        if fmt != "bf16":
-            print("bench.py: --fused is available for bf16 only", file=sys.stderr)
-            return 2
-        stack = fuse(T, torch, stack)
+    projections = build_stack(T, torch, args.workload, fmt, sparsities, args.layers, copies,
+                              args.batch)
+    block0 = projections[:7]
+    groups = fuse(T, torch, projections) if fmt == "bf16" and not args.batch else None
+    stack = groups if fused else projections
     launches_per_step = len(stack)
 
-    detail, seconds = {}, {}
-    for p in sparsities:
-        seconds[p] = time_steps(T, torch, stack, p, args.steps, args.warmup)
-        eff = sum(P.bytes(p) for P in stack)
-        detail[pct(p)] = {
-            "us_per_step": seconds[p] * 1e6,
-            "effective_bytes": eff,
-            "effective_GBps": eff / seconds[p] / 1e9,
-            "frac_of_hbm_peak": eff / seconds[p] / 1e9 / HBM_PEAK_GBS,
-            "host_issue_us_per_step": time_steps.host_issue_us,
-        }
-    for p in sparsities:
-        detail[pct(p)]["speedup_vs_dense"] = seconds[0.0] / seconds[p]
+    def timed_passes(calls):
+        sec = {p: time_steps(T, torch, calls, p, args.steps, args.warmup) for p in sparsities}
+        out = {}
+        for p in sparsities:
+            eff = sum(C.bytes(p) for C in calls)
+            out[pct(p)] = {
+                "us_per_step": sec[p] * 1e6, "launches_per_step": len(calls),
+                "effective_bytes": eff,
+                "effective_GBps": eff / sec[p] / 1e9,
+                "frac_of_hbm_peak": eff / sec[p] / 1e9 / HBM_PEAK_GBS,
+                "speedup_vs_dense": sec[0.0] / sec[p],
+            }
+        return sec, out
+
+    seconds, detail = timed_passes(stack)
+    detail[pct(head)]["host_issue_us_per_step"] = time_steps.host_issue_us
 
     # Dominant kernel: the sparse GEMV kernel, the only kernel of a call.  Its average launch
     # duration is the timed region of the headline pass divided by the launches in it.
-    head_bytes = sum(P.bytes(head) for P in stack)
+    head_bytes = sum(C.bytes(head) for C in stack)
     achieved = head_bytes / seconds[head] / 1e9
 
-    # The same pass with one launch per group of projections that share their input
-    # (q+k+v, o, gate+up, down: Appendix A.3) through teal_sparse_gemv_bf16_multi.
-    fused_detail = {}
-    if fmt == "bf16" and not args.fused and not args.no_fused_detail and not args.batch:
-        groups = fuse(T, torch, stack)
-        fsec = {p: time_steps(T, torch, groups, p, args.steps, args.warmup) for p in sparsities}
-        for p in sparsities:
-            eff = sum(G.bytes(p) for G in groups)
-            fused_detail[pct(p)] = {
-                "us_per_step": fsec[p] * 1e6, "launches_per_step": len(groups),
-                "effective_GBps": eff / fsec[p] / 1e9,
-                "frac_of_hbm_peak": eff / fsec[p] / 1e9 / HBM_PEAK_GBS,
-                "speedup_vs_dense": fsec[0.0] / fsec[p],
-            }
-        del groups
+    # The same pass launched the other way: one launch per projection when the headline
+    # groups the projections that share their input (q+k+v, o, gate+up, down: Appendix A.3,
+    # teal_sparse_gemv_bf16_multi), or the grouped launches when the headline does not.
+    other_detail = {}
+    if groups is not None and not args.no_other_mode:
+        _, other_detail = timed_passes(projections if fused else groups)
 
-    per_proj = {}
-    if not args.no_per_projection and not args.fused:
-        for P in block0:
-            us = time_projection(T, torch, P, head, 300) * 1e6
-            us_dense = time_projection(T, torch, P, 0.0, 300) * 1e6
-            _, plan = T.teal_gemv_plan(BITS[fmt], P.m, P.n)
-            if args.batch:
-                plan = {"note": "batched launch shape is chosen inside teal_sparse_gemv_bf16_batch"}
-            b = P.bytes(head)
-            per_proj[P.name] = {
-                "n": P.n, "m": P.m, "nnz": P.nnz[head], "us": us, "us_dense": us_dense,
+    def alone(calls):
+        table = {}
+        for C in calls:
+            us = time_projection(T, torch, C, head, 300) * 1e6
+            us_dense = time_projection(T, torch, C, 0.0, 300) * 1e6
+            b = C.bytes(head)
+            table[C.name] = {
+                "n": C.ns if hasattr(C, "ns") else C.n, "m": C.m, "us": us, "us_dense": us_dense,
                 "effective_GBps": b / us / 1e3, "frac_of_hbm_peak": b / us / 1e3 / HBM_PEAK_GBS,
-                "speedup_vs_dense": us_dense / us, "launch": plan,
+                "speedup_vs_dense": us_dense / us,
             }
+        return table
 
+    per_proj, per_group = {}, {}
+    if not args.no_per_projection:
+        per_proj = alone(block0)
+        for P in block0:
+            if args.batch:
+                per_proj[P.name]["launch"] = "chosen inside teal_sparse_gemv_bf16_batch"
+            else:
+                per_proj[P.name]["launch"] = T.teal_gemv_plan(BITS[fmt], P.m, P.n)[1]
+            per_proj[P.name]["nnz"] = P.nnz[head]
+        if groups is not None:
+            per_group = alone(groups[:4])
+
+    kernel = ("sparse_gemv_multi_kernel<FmtBF16>" if fused
+              else "sparse_gemv_batch_kernel" if args.batch else KERNEL[fmt])
     out = {
         "metric": f"sparse GEMV effective HBM GB/s at {pct(head)} sparsity (one decoder-block "
                   f"pass); us and speedup vs dense per sparsity in detail",
@@ -486,8 +503,9 @@ def main() -> int:
             "weight_format": fmt,
             "weight_bytes_per_block": block_bytes,
             "blocks_per_step": args.layers,
-            "launches": "one per group of projections sharing their input (q+k+v, o, gate+up, "
-                        "down)" if args.fused else "one per projection",
+            "launches": "one per group of projections that read the same hidden state (q+k+v, o, "
+                        "gate+up, down), each projection with its own threshold" if fused
+                        else "one per projection",
             "weight_copies_walked": copies,
         },
         "roofline": {
@@ -496,15 +514,15 @@ def main() -> int:
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
-            "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, fmt, head, args.layers)),
-            "kernel": f"{'sparse_gemv_multi_kernel<FmtBF16>' if args.fused else 'sparse_gemv_batch_kernel' if args.batch else KERNEL[fmt]} "
-                      f"({launches_per_step} launches per step, {pct(head)})",
+            "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, fmt, head, args.layers, fused)),
+            "kernel": f"{kernel} ({launches_per_step} launches per step, {pct(head)})",
             "bytes_per_launch_avg": head_bytes / launches_per_step,
             "kernel_avg_us": seconds[head] * 1e6 / launches_per_step,
         },
         "detail": detail,
-        "detail_fused_launches": fused_detail,
-        f"per_projection_{pct(head)}": per_proj,
+        ("detail_one_launch_per_projection" if fused else "detail_grouped_launches"): other_detail,
+        f"per_projection_alone_{pct(head)}": per_proj,
+        f"per_group_alone_{pct(head)}": per_group,
     }
     if not args.no_cpu_baseline:
         sec, passes, threads = cpu_baseline(block0, head)
