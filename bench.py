@@ -139,7 +139,7 @@ class Projection:
 
 
 class FusedGroup:
-    """Projections that read the same hidden state, launched as one kernel (bf16 only)."""
+    """Projections that read the same hidden state, launched as one kernel (bf16, int8)."""
 
     def __init__(self, T, torch, members):
         self.members = members
@@ -153,6 +153,12 @@ class FusedGroup:
         self.stream = members[0].stream
 
     def launch(self, T, copy: int, p: float) -> int:
+        if self.members[0].fmt == "w8":
+            ws = [P.wp[copy % len(P.wp)] for P in self.members]
+            return T.teal_sparse_gemv_w8_multi([w[0] for w in ws], [w[1] for w in ws],
+                                               [P.t[p] for P in self.members], self.ys, self.ns,
+                                               self.members[0].xp, self.m, self.wsp,
+                                               self.ws_bytes, self.stream)
         wts = [P.wp[copy % len(P.wp)][0] for P in self.members]
         return T.teal_sparse_gemv_bf16_multi(wts, [P.t[p] for P in self.members], self.ys, self.ns,
                                              self.members[0].xp, self.m, self.wsp, self.ws_bytes,
@@ -405,9 +411,9 @@ def main() -> int:
         sparsities.append(0.0)
     head = sparsities[0]
     fmt = args.format
-    fused = fmt == "bf16" and not args.batch and not args.unfused
+    fused = fmt in ("bf16", "w8") and not args.batch and not args.unfused
     if args.fused and not fused:
-        print("bench.py: fused launches exist for bf16 at batch 1 only", file=sys.stderr)
+        print("bench.py: fused launches exist for bf16 and w8 at batch 1 only", file=sys.stderr)
         return 2
     shapes = ti.LAYER_SHAPES[args.workload]
     block_bytes = sum(n * m * BITS[fmt] // 8 for n, m in shapes.values())
@@ -421,7 +427,7 @@ def main() -> int:
     projections = build_stack(T, torch, args.workload, fmt, sparsities, args.layers, copies,
                               args.batch)
     block0 = projections[:7]
-    groups = fuse(T, torch, projections) if fmt == "bf16" and not args.batch else None
+    groups = fuse(T, torch, projections) if fmt in ("bf16", "w8") and not args.batch else None
     stack = groups if fused else projections
     launches_per_step = len(stack)
 
@@ -479,7 +485,7 @@ def main() -> int:
         if groups is not None:
             per_group = alone(groups[:4])
 
-    kernel = ("sparse_gemv_multi_kernel<FmtBF16>" if fused
+    kernel = (f"sparse_gemv_multi_kernel<{'FmtBF16' if fmt == 'bf16' else 'FmtW8'}>" if fused
               else "sparse_gemv_batch_kernel" if args.batch else KERNEL[fmt])
     out = {
         "metric": f"sparse GEMV effective HBM GB/s at {pct(head)} sparsity (one decoder-block "

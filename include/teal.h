@@ -130,6 +130,19 @@ teal_status teal_sparse_gemv_w8(const int8_t *Wq, const void *scale_f16,
                                 void *stream);
 
 /*
+ * teal_sparse_gemv_bf16_multi for 8-bit channel-wise weights: count matrices
+ * (1..4) that read the same hidden state, one kernel launch.  Wq, scale_f16, t,
+ * y, n are HOST arrays of length count (device pointers / values per matrix,
+ * formats as for teal_sparse_gemv_w8, n_k % 16 == 0).  Results are bitwise
+ * those of separate calls with the same launch shape.  workspace of at least
+ * teal_workspace_bytes(m, n_0 + ... + n_{count-1}).
+ */
+teal_status teal_sparse_gemv_w8_multi(int count, const int8_t *const *Wq,
+                                      const void *const *scale_f16, const float *t,
+                                      float *const *y, const int *n, const void *x_f16, int m,
+                                      void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * The same product for 4-bit group-quantised weights (Section 5.3):
  * W[j][i] = nibble(i, j) * scale[i / group][j].
  *   Wq    [m][n/2] bytes, two two's-complement nibbles per byte along the

@@ -14,5 +14,5 @@ from .binding import (  # noqa: F401
     teal_sparse_gemv_w8, teal_sparse_gemv_w4, teal_pack_bf16, teal_gemv_plan,
     teal_sparse_gemv_bf16_multi, teal_abs_histogram, teal_histogram_thresholds, TEAL_HIST_BINS,
     teal_workspace_bytes_batch, teal_sparsify_batch, teal_sparse_gemv_bf16_batch,
-    teal_sparse_gemv_bf16_batch_ex, TEAL_MAX_BATCH,
+    teal_sparse_gemv_bf16_batch_ex, TEAL_MAX_BATCH, teal_sparse_gemv_w8_multi,
 )

@@ -301,6 +301,33 @@ teal_status teal_sparse_gemv_w8(const int8_t *Wq, const void *scale_f16, const v
                                          static_cast<hipStream_t>(stream)));
 }
 
+teal_status teal_sparse_gemv_w8_multi(int count, const int8_t *const *Wq,
+                                      const void *const *scale_f16, const float *t,
+                                      float *const *y, const int *n, const void *x_f16, int m,
+                                      void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (count < 1 || count > teal::kMaxMatrices) return TEAL_ERR_UNSUPPORTED;
+    if (!Wq || !scale_f16 || !t || !y || !n || !x_f16 || !workspace) return TEAL_ERR_NULL;
+    long long n_total = 0;
+    for (int k = 0; k < count; ++k) {
+        if (!Wq[k] || !scale_f16[k] || !y[k]) return TEAL_ERR_NULL;
+        if (n[k] < 16 || n[k] > teal::kMaxDim || n[k] % 16 != 0) return TEAL_ERR_SHAPE;
+        n_total += n[k];
+    }
+    if (m < 1 || m > teal::kMaxDim || n_total > teal::kMaxDim) return TEAL_ERR_SHAPE;
+    for (int k = 0; k < count; ++k)
+        if (!aligned(Wq[k], 16) || !aligned(scale_f16[k], 2) || !aligned(y[k], 4))
+            return TEAL_ERR_ALIGN;
+    if (!aligned(x_f16, 2) || !aligned(workspace, kAlignWorkspace)) return TEAL_ERR_ALIGN;
+    for (int k = 0; k < count; ++k)
+        if (!threshold_ok(t[k])) return TEAL_ERR_THRESHOLD;
+    if (workspace_bytes < teal_workspace_bytes(m, (int)n_total)) return TEAL_ERR_WORKSPACE;
+    const GemvShape sh = auto_shape(m, (int)n_total, 16, 16, 64, 64);
+    return from_hip(teal::launch_gemv_w8_multi(count, Wq, scale_f16, t, y, n, x_f16, m,
+                                               ws_partials(workspace), ws_counters(workspace), sh,
+                                               static_cast<hipStream_t>(stream)));
+}
+
 teal_status teal_sparse_gemv_w4(const uint8_t *Wq, const void *scale_f16, int group,
                                 const void *x_f16, float t, float *y, int m, int n,
                                 void *workspace, size_t workspace_bytes, void *stream)

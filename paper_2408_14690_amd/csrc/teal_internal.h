@@ -57,6 +57,11 @@ hipError_t launch_gemv_w8(const int8_t *Wq, const void *scale_f16, const void *x
                           float t, float *y, int m, int n, float *partial, int *counters,
                           const GemvShape &shape, hipStream_t stream);
 
+hipError_t launch_gemv_w8_multi(int count, const int8_t *const *Wq, const void *const *scale_f16,
+                                const float *t, float *const *y, const int *n, const void *x_f16,
+                                int m, float *partial, int *counters, const GemvShape &shape,
+                                hipStream_t stream);
+
 hipError_t launch_gemv_w4(const uint8_t *Wq, const void *scale_f16, const void *x_f16,
                           float t, float *y, int m, int n, float *partial, int *counters,
                           const GemvShape &shape, hipStream_t stream);

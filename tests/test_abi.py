@@ -140,6 +140,31 @@ def test_multi_argument_errors():
     assert T.teal_sparse_gemv_bf16_multi([], [], [], [], X, 4096, WS, BIG, 0) == T.TEAL_ERR_UNSUPPORTED
 
 
+def test_w8_multi_argument_errors():
+    ok = dict(Wq_list=[W, W + 0x1000], scale_list=[SC, SC + 0x100], t_list=[0.5, 0.25],
+              y_list=[Y, Y + 0x1000], n_list=[4096, 1024], x_f16=X, m=4096, workspace=WS,
+              workspace_bytes=BIG, stream=0)
+
+    def call(**kw):
+        a = dict(ok)
+        a.update(kw)
+        return T.teal_sparse_gemv_w8_multi(**a)
+
+    assert call(Wq_list=[W, None]) == T.TEAL_ERR_NULL
+    assert call(scale_list=[SC, None]) == T.TEAL_ERR_NULL
+    assert call(y_list=[None, Y]) == T.TEAL_ERR_NULL
+    assert call(x_f16=None) == T.TEAL_ERR_NULL
+    assert call(n_list=[4096, 1032]) == T.TEAL_ERR_SHAPE          # not a multiple of 16
+    assert call(m=0) == T.TEAL_ERR_SHAPE
+    assert call(Wq_list=[W, W + 8]) == T.TEAL_ERR_ALIGN
+    assert call(scale_list=[SC, SC + 1]) == T.TEAL_ERR_ALIGN
+    assert call(t_list=[0.5, math.inf]) == T.TEAL_ERR_THRESHOLD
+    assert call(workspace_bytes=T.teal_workspace_bytes(4096, 5120) - 1) == T.TEAL_ERR_WORKSPACE
+    five = dict(Wq_list=[W] * 5, scale_list=[SC] * 5, t_list=[0.5] * 5, y_list=[Y] * 5,
+                n_list=[64] * 5)
+    assert call(**five) == T.TEAL_ERR_UNSUPPORTED
+
+
 def test_plan_is_reported():
     st, plan = T.teal_gemv_plan(16, 4096, 14336)
     assert st == T.TEAL_OK

@@ -371,6 +371,42 @@ def test_gemv_w8(T, n, m):
         assert rel_l2(got, want) <= TOL_WQ
 
 
+@pytest.mark.parametrize("name,ns,m,ps", [
+    ("llama3 q,k,v", [4096, 1024, 1024], 4096, [0.5, 0.4, 0.25]),
+    ("llama3 gate,up", [14336, 14336], 4096, [0.4, 0.5]),
+    ("ragged", [528, 32, 144, 16], 333, [0.0, 0.5, 0.9, 1.0]),
+    ("single", [1040], 2049, [0.5]),
+], ids=["qkv", "gate_up", "ragged", "single"])
+def test_gemv_w8_multi(T, name, ns, m, ps):
+    x = ti.laplace_x(m, 700 + m)
+    xd = dev(x)
+    ws = workspace(T, m, sum(ns))
+    ws1 = workspace(T, m, max(ns))
+    qs_host, qs, scs, ts, ys = [], [], [], [], []
+    for k, (n, p) in enumerate(zip(ns, ps)):
+        q, scale = ti.quantize_w8(ti.weights_bf16(n, m, seed=2000 * k + n + m))
+        qs_host.append((q, scale))
+        qs.append(dev(q))
+        scs.append(dev(scale))
+        ts.append(ti.quantile_threshold(x, p))
+        ys.append(torch.full((n,), float("nan"), dtype=torch.float32, device="cuda"))
+    T.check(T.teal_sparse_gemv_w8_multi(qs, scs, ts, ys, ns, xd, m, ws))
+    torch.cuda.synchronize()
+    for k, n in enumerate(ns):
+        got = ys[k].cpu().numpy()
+        want = orc.sparse_gemv_w8(qs_host[k][0], qs_host[k][1], x, ts[k])
+        assert rel_l2(got, want) <= TIGHT, (name, k)
+        assert rel_l2(got, want) <= TOL_WQ
+        # the separate call computes the same sums (its launch shape may differ)
+        alone = run_w8(T, qs[k], scs[k], xd, ts[k], m, n, ws1)
+        assert rel_l2(got, alone.astype(np.float64)) <= TIGHT
+    ys2 = [torch.full((n,), float("nan"), dtype=torch.float32, device="cuda") for n in ns]
+    T.check(T.teal_sparse_gemv_w8_multi(qs, scs, ts, ys2, ns, xd, m, ws))
+    torch.cuda.synchronize()
+    for a, b in zip(ys, ys2):
+        assert torch.equal(a, b)
+
+
 @pytest.mark.parametrize("n,m", [(32, 128), (96, 384), (544, 256), (1056, 2176), (4096, 4096),
                                  (1024, 4096), (14336, 4096), (4096, 14336)])
 def test_gemv_w4(T, n, m):
