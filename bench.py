@@ -139,7 +139,7 @@ class Projection:
 
 
 class FusedGroup:
-    """Projections that read the same hidden state, launched as one kernel (bf16, int8)."""
+    """Projections that read the same hidden state, launched as one kernel."""
 
     def __init__(self, T, torch, members):
         self.members = members
@@ -153,6 +153,12 @@ class FusedGroup:
         self.stream = members[0].stream
 
     def launch(self, T, copy: int, p: float) -> int:
+        if self.members[0].fmt == "w4":
+            ws = [P.wp[copy % len(P.wp)] for P in self.members]
+            return T.teal_sparse_gemv_w4_multi([w[0] for w in ws], [w[1] for w in ws], 128,
+                                               [P.t[p] for P in self.members], self.ys, self.ns,
+                                               self.members[0].xp, self.m, self.wsp,
+                                               self.ws_bytes, self.stream)
         if self.members[0].fmt == "w8":
             ws = [P.wp[copy % len(P.wp)] for P in self.members]
             return T.teal_sparse_gemv_w8_multi([w[0] for w in ws], [w[1] for w in ws],
@@ -229,6 +235,46 @@ def time_steps(T, torch, stack, p, steps, warmup) -> float:
     torch.cuda.synchronize()
     time_steps.host_issue_us = issue * 1e6 / steps      # host time to enqueue one step
     return start.elapsed_time(stop) * 1e-3 / steps
+
+
+def time_steps_graph(T, torch, stack, p, steps, copies) -> float:
+    """Seconds per step when the launches of `copies` consecutive steps (one walk over the
+    weight copies) are captured once into a HIP graph and the graph is replayed."""
+    side = torch.cuda.Stream()
+    calls = set()
+    for C in stack:
+        calls.add(C)
+        calls.update(getattr(C, "members", ()))
+    saved = {C: C.stream for C in calls}
+    side.wait_stream(torch.cuda.current_stream())
+    try:
+        for C in calls:
+            C.stream = side.cuda_stream
+        with torch.cuda.stream(side):
+            for k in range(copies):
+                one_step(T, stack, p, k)                     # warm the capture stream
+        side.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            for k in range(copies):
+                one_step(T, stack, p, k)
+        replays = max(1, steps // copies)
+        with torch.cuda.stream(side):
+            graph.replay()
+            side.synchronize()
+            start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            start.record(side)
+            for _ in range(replays):
+                graph.replay()
+            stop.record(side)
+        side.synchronize()
+        sec = start.elapsed_time(stop) * 1e-3 / (replays * copies)
+        del graph
+    finally:
+        for C, st in saved.items():
+            C.stream = st
+    torch.cuda.current_stream().wait_stream(side)
+    return sec
 
 
 def time_projection(T, torch, P, p, launches) -> float:
@@ -379,6 +425,8 @@ def main() -> int:
     ap.add_argument("--batch", type=int, default=0,
                     help="B >= 1: a small batch of B hidden states per projection with the batch-wide "
                          "mask of the averaged magnitude (Section 5.4.4); bf16 only. 0 = one state")
+    ap.add_argument("--graph", action="store_true",
+                    help="also time the headline pass replayed from a captured HIP graph")
     ap.add_argument("--calibration", action="store_true",
                     help="time threshold calibration (histogram + thresholds) instead of the GEMV path")
     ap.add_argument("--calibration-tokens", type=int, default=16384)
@@ -411,9 +459,9 @@ def main() -> int:
         sparsities.append(0.0)
     head = sparsities[0]
     fmt = args.format
-    fused = fmt in ("bf16", "w8") and not args.batch and not args.unfused
+    fused = not args.batch and not args.unfused
     if args.fused and not fused:
-        print("bench.py: fused launches exist for bf16 and w8 at batch 1 only", file=sys.stderr)
+        print("bench.py: fused launches exist at batch 1 only", file=sys.stderr)
         return 2
     shapes = ti.LAYER_SHAPES[args.workload]
     block_bytes = sum(n * m * BITS[fmt] // 8 for n, m in shapes.values())
@@ -427,7 +475,7 @@ def main() -> int:
     projections = build_stack(T, torch, args.workload, fmt, sparsities, args.layers, copies,
                               args.batch)
     block0 = projections[:7]
-    groups = fuse(T, torch, projections) if fmt in ("bf16", "w8") and not args.batch else None
+    groups = fuse(T, torch, projections) if not args.batch else None
     stack = groups if fused else projections
     launches_per_step = len(stack)
 
@@ -473,6 +521,15 @@ def main() -> int:
             }
         return table
 
+    graph_detail = {}
+    if args.graph:
+        for p in (head, 0.0):
+            gsec = time_steps_graph(T, torch, stack, p, args.steps, copies)
+            graph_detail[pct(p)] = {"us_per_step": gsec * 1e6,
+                                    "vs_direct_launches": seconds[p] / gsec}
+        graph_detail[pct(head)]["speedup_vs_dense"] = (graph_detail[pct(0.0)]["us_per_step"]
+                                                       / graph_detail[pct(head)]["us_per_step"])
+
     per_proj, per_group = {}, {}
     if not args.no_per_projection:
         per_proj = alone(block0)
@@ -485,7 +542,9 @@ def main() -> int:
         if groups is not None:
             per_group = alone(groups[:4])
 
-    kernel = (f"sparse_gemv_multi_kernel<{'FmtBF16' if fmt == 'bf16' else 'FmtW8'}>" if fused
+    multi_kernel = {"bf16": "sparse_gemv_multi_kernel<FmtBF16>", "w8": "sparse_gemv_multi_kernel<FmtW8>",
+                    "w4": "sparse_gemv_w4_multi_kernel"}[fmt]
+    kernel = (multi_kernel if fused
               else "sparse_gemv_batch_kernel" if args.batch else KERNEL[fmt])
     out = {
         "metric": f"sparse GEMV effective HBM GB/s at {pct(head)} sparsity (one decoder-block "
@@ -527,6 +586,7 @@ def main() -> int:
         },
         "detail": detail,
         ("detail_one_launch_per_projection" if fused else "detail_grouped_launches"): other_detail,
+        "detail_hip_graph_replay": graph_detail,
         f"per_projection_alone_{pct(head)}": per_proj,
         f"per_group_alone_{pct(head)}": per_group,
     }

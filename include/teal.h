@@ -157,6 +157,19 @@ teal_status teal_sparse_gemv_w4(const uint8_t *Wq, const void *scale_f16, int gr
                                 void *stream);
 
 /*
+ * teal_sparse_gemv_bf16_multi for 4-bit group-quantised weights: count matrices
+ * (1..4) that read the same hidden state, one kernel launch.  Wq, scale_f16, t,
+ * y, n are HOST arrays of length count (device pointers / values per matrix,
+ * formats as for teal_sparse_gemv_w4, n_k % 32 == 0); group == 128,
+ * m % 128 == 0.  workspace of at least
+ * teal_workspace_bytes(m, n_0 + ... + n_{count-1}).
+ */
+teal_status teal_sparse_gemv_w4_multi(int count, const uint8_t *const *Wq,
+                                      const void *const *scale_f16, int group, const float *t,
+                                      float *const *y, const int *n, const void *x_f16, int m,
+                                      void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * One-time layout step (Sections 3 and 4.4: weights used under input sparsity
  * must be stored channel-contiguous): canonical row-major W[n][m] bf16 ->
  * Wt[m][n].  Device to device, out of place; both 2-byte aligned; any m, n >= 1.

@@ -28,7 +28,7 @@ EXPORTS = (
     "teal_sparse_gemv_w4", "teal_pack_bf16", "teal_gemv_plan", "teal_sparse_gemv_bf16_multi",
     "teal_abs_histogram", "teal_histogram_thresholds", "teal_workspace_bytes_batch",
     "teal_sparsify_batch", "teal_sparse_gemv_bf16_batch", "teal_sparse_gemv_bf16_batch_ex",
-    "teal_sparse_gemv_w8_multi",
+    "teal_sparse_gemv_w8_multi", "teal_sparse_gemv_w4_multi",
 )
 TEAL_HIST_BINS = 32768
 TEAL_MAX_BATCH = 8
@@ -78,6 +78,9 @@ def load_library():
                                                 c.POINTER(i), vp, i, vp, sz, vp]
     lib.teal_sparse_gemv_w8_multi.restype = i
     lib.teal_sparse_gemv_w8_multi.argtypes = [i, c.POINTER(vp), c.POINTER(vp), c.POINTER(f),
+                                              c.POINTER(vp), c.POINTER(i), vp, i, vp, sz, vp]
+    lib.teal_sparse_gemv_w4_multi.restype = i
+    lib.teal_sparse_gemv_w4_multi.argtypes = [i, c.POINTER(vp), c.POINTER(vp), i, c.POINTER(f),
                                               c.POINTER(vp), c.POINTER(i), vp, i, vp, sz, vp]
     lib.teal_abs_histogram.restype = i
     lib.teal_abs_histogram.argtypes = [vp, sz, vp, vp]
@@ -246,6 +249,22 @@ def teal_sparse_gemv_w8_multi(Wq_list, scale_list, t_list, y_list, n_list, x_f16
     N = (ctypes.c_int * count)(*[int(n) for n in n_list])
     return load_library().teal_sparse_gemv_w8_multi(
         count, W, S, Tt, Y, N, _ptr(x_f16), int(m), _ptr(workspace),
+        _nbytes(workspace, workspace_bytes), _stream(stream))
+
+
+def teal_sparse_gemv_w4_multi(Wq_list, scale_list, group, t_list, y_list, n_list, x_f16, m,
+                              workspace, workspace_bytes=None, stream=None) -> int:
+    """count = len(Wq_list) int4 matrices sharing x; the per-matrix lists become host arrays."""
+    count = len(Wq_list)
+    if not (len(scale_list) == len(t_list) == len(y_list) == len(n_list) == count):
+        raise ValueError("per-matrix lists must have the same length")
+    W = (ctypes.c_void_p * count)(*[_ptr(w) for w in Wq_list])
+    S = (ctypes.c_void_p * count)(*[_ptr(sc) for sc in scale_list])
+    Y = (ctypes.c_void_p * count)(*[_ptr(y) for y in y_list])
+    Tt = (ctypes.c_float * count)(*[float(t) for t in t_list])
+    N = (ctypes.c_int * count)(*[int(n) for n in n_list])
+    return load_library().teal_sparse_gemv_w4_multi(
+        count, W, S, int(group), Tt, Y, N, _ptr(x_f16), int(m), _ptr(workspace),
         _nbytes(workspace, workspace_bytes), _stream(stream))
 
 

@@ -68,40 +68,47 @@ struct FmtW4 {
 };
 
 constexpr int kGroup = 128;
+constexpr int kW4Waves = 8;
+constexpr int kW4Unroll = 4;
 
-// One 128-channel group's worth of work of one wavefront: its share of the
-// group's surviving rows (at most 128 / WAVES of them, LOADS wavefront loads)
-// and the group's scales for this lane's 32 columns.
-template <int LOADS>
-struct GroupBatch {
-    u32x4 v[LOADS];
-    float xv[LOADS];
-    uint4 sc[4];      // 32 fp16 scales
-    int mine;         // rows in this batch (wavefront-uniform)
+// One batch of row loads of the int4 kernel: up to U wavefront loads, all from
+// one 128-channel group, and, if the batch is the wavefront's last of that
+// group, the group's scales for this lane's 32 columns.
+template <int U>
+struct W4Batch {
+    u32x4 v[U];
+    float xv[U];
+    uint4 sc[4];      // 32 fp16 scales (loaded only when ends_run)
+    int rows;         // live rows in this batch (wavefront-uniform); 0 = the share is exhausted
+    bool ends_run;    // wavefront-uniform
 };
 
-// int4: the compacted list is ascending, so each 128-channel group is a run
-// of it, delimited by the segment prefixes (two 64-channel segments per group).
-// Per group the block's wavefronts split the run, accumulate sum_i x_i q[i][j]
-// unscaled, then fold it into the running sums with that group's scales.
-// Groups are software-pipelined: the rows and scales of the next group are in
-// flight while the current one is multiplied out.
-template <int LPR, int WAVES>
-__global__ __launch_bounds__(WAVES * 64) void sparse_gemv_w4_kernel(
-    FmtW4::Args a, const __half *__restrict__ x, float t, float *partial, int *counters, float *y,
-    int m, int n, int ks, int tiles, int tile_cols, int splits)
+// Work of one block for int4 weights with group scales: output tile `tile`
+// (tile_cols columns) x K-slice `s` (ks channels, a multiple of 128).
+//
+// The wavefronts take equal contiguous shares of the compacted list, as for
+// the other formats.  The list is ascending, so each 128-channel group is a
+// run of it, delimited by the segment prefixes (two 64-channel segments per
+// group), and a wavefront's share crosses few group boundaries.  Within a group
+// a wavefront accumulates sum_i x_i v[i][j] unscaled (v = the nibble mapped
+// into [1, 2), see FmtW4); at the end of its rows of that group it undoes the
+// affine map and folds the sums into the running sums with the group's scales:
+// once per (wavefront, group it touches), not once per row.  Batches never
+// straddle a group, and two batches are in flight per wavefront across group
+// boundaries.
+template <int LPR, int WAVES, int U>
+__device__ __forceinline__ void w4_block(const FmtW4::Args &a, const __half *__restrict__ x,
+                                         float t, float *partial, int *counters, float *y, int m,
+                                         int n, int ks, int tile, int s, int tile_cols, int splits)
 {
     using F = FmtW4;
     constexpr int EPL = F::kElemsPerLane;
     constexpr int R = 64 / LPR;
-    constexpr int LOADS = (kGroup / WAVES + R - 1) / R;   // covers a group in which every row survives
     extern __shared__ __align__(16) unsigned char smem[];
     int2 *list = reinterpret_cast<int2 *>(smem);
     float *red = reinterpret_cast<float *>(smem + (size_t)ks * sizeof(int2));
     __shared__ int seg_cnt[kMaxSegs];
 
-    const int tile = blockIdx.x % tiles;
-    const int s = blockIdx.x / tiles;
     const int k0 = s * ks;                       // multiple of 128
     const int k1 = min(m, k0 + ks);
     int seg_excl;
@@ -116,43 +123,61 @@ __global__ __launch_bounds__(WAVES * 64) void sparse_gemv_w4_kernel(
     const unsigned char *lane_base = static_cast<const unsigned char *>(a.W) + col / 2;
     const __half *scale_base = a.scale + (size_t)(k0 / kGroup) * n + col;
 
-    float acc[EPL];
+    float acc[EPL], gacc[EPL];
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
+    for (int e = 0; e < EPL; ++e) acc[e] = gacc[e] = 0.f;
+    float xsum = 0.f;                             // sum of x over this lane's rows of the current run
 
-    auto issue = [&](GroupBatch<LOADS> &b, int gi) {
-        // two 64-channel segments per group; the prefix of segment j sits in lane j
-        const int g0 = __builtin_amdgcn_readlane(seg_excl, 2 * gi);
-        const int g1 = 2 * gi + 2 < 64 ? __builtin_amdgcn_readlane(seg_excl, 2 * gi + 2) : cnt;
-        int start, mine;
-        wave_share(g1 - g0, w, WAVES, start, mine);
-        b.mine = mine;
-        if (mine <= 0) return;                    // wavefront-uniform
-        const int last = mine - 1;
+    int start, mine;
+    wave_share(cnt, w, WAVES, start, mine);
+    // Walk state (all wavefront-uniform): next list position, end of the share, current
+    // group of the slice and the end of this wavefront's rows in it.
+    int cur = start;
+    const int end = start + mine;
+    int gi = -1, gend = start;
+    // list offset at which group j of the slice begins: the prefix of segment 2j (lanes past
+    // the last segment hold the total)
+    auto group_begin = [&](int j) {
+        return 2 * j < 64 ? __builtin_amdgcn_readlane(seg_excl, 2 * j) : cnt;
+    };
+
+    auto issue = [&](W4Batch<U> &b) {
+        if (cur >= end) {
+            b.rows = 0;
+            b.ends_run = false;
+            return;
+        }
+        while (cur >= gend) {                     // next group with rows in this share
+            ++gi;
+            gend = min(end, group_begin(gi + 1));
+        }
+        const int nb = min(U * R, gend - cur);
+        const int last = cur + nb - 1;
 #pragma unroll
-        for (int u = 0; u < LOADS; ++u) {
-            const int e = u * R + g;
-            const int2 ent = list[g0 + start + min(e, last)];
+        for (int u = 0; u < U; ++u) {
+            const int e = cur + u * R + g;
+            const int2 ent = list[min(e, last)];
             b.xv[u] = e <= last ? __int_as_float(ent.y) : 0.f;
             b.v[u] = load_stream16(lane_base + (size_t)(unsigned)ent.x * row_bytes);
         }
-        const uint4 *sp = reinterpret_cast<const uint4 *>(scale_base + (size_t)gi * n);
+        b.rows = nb;
+        b.ends_run = cur + nb == gend;
+        if (b.ends_run) {
+            const uint4 *sp = reinterpret_cast<const uint4 *>(scale_base + (size_t)gi * n);
 #pragma unroll
-        for (int q = 0; q < 4; ++q) b.sc[q] = sp[q];
+            for (int q = 0; q < 4; ++q) b.sc[q] = sp[q];
+        }
+        cur += nb;
     };
-    auto consume = [&](const GroupBatch<LOADS> &b) {
-        if (b.mine <= 0) return;
-        float gacc[EPL];
+    auto consume = [&](const W4Batch<U> &b) {
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) gacc[e] = 0.f;
-        float xsum = 0.f;                         // sum of x over this lane's rows of the group
-#pragma unroll
-        for (int u = 0; u < LOADS; ++u) {
-            if (u * R < b.mine) {                 // wavefront-uniform
+        for (int u = 0; u < U; ++u) {
+            if (u * R < b.rows) {                 // wavefront-uniform
                 F::fma(gacc, b.v[u], b.xv[u]);
                 xsum += b.xv[u];
             }
         }
+        if (!b.ends_run) return;
         // sum x*q = 16 (sum x*v - 1.5 sum x); then times the group's scale
         const float corr = -F::kAffineScale * F::kAffineOffset * xsum;
 #pragma unroll
@@ -165,30 +190,58 @@ __global__ __launch_bounds__(WAVES * 64) void sparse_gemv_w4_kernel(
                 const float q1 = fmaf(gacc[8 * q + 2 * h + 1], F::kAffineScale, corr);
                 acc[8 * q + 2 * h] = fmaf(__low2float(sh), q0, acc[8 * q + 2 * h]);
                 acc[8 * q + 2 * h + 1] = fmaf(__high2float(sh), q1, acc[8 * q + 2 * h + 1]);
+                gacc[8 * q + 2 * h] = 0.f;
+                gacc[8 * q + 2 * h + 1] = 0.f;
             }
         }
+        xsum = 0.f;
     };
 
-    const int ngroups = (k1 - k0) / kGroup;       // >= 1
-    GroupBatch<LOADS> b0, b1;
-    issue(b0, 0);
-    int gi = 0;
-    for (; gi + 2 < ngroups; gi += 2) {
-        issue(b1, gi + 1);
+    W4Batch<U> b0, b1;
+    issue(b0);
+    while (b0.rows > 0) {
+        issue(b1);
         consume(b0);
-        issue(b0, gi + 2);
+        if (b1.rows <= 0) break;
+        issue(b0);
         consume(b1);
-    }
-    if (gi + 1 < ngroups) {
-        issue(b1, gi + 1);
-        consume(b0);
-        consume(b1);
-    } else {
-        consume(b0);
     }
     fold_row_groups<LPR>(acc);
     block_finish<F, LPR, WAVES>(acc, red, partial, counters, y, tile, col0, tile_cols, s, splits, n,
                                 a);
+}
+
+template <int LPR, int WAVES, int U>
+__global__ __launch_bounds__(WAVES * 64) void sparse_gemv_w4_kernel(
+    FmtW4::Args a, const __half *__restrict__ x, float t, float *partial, int *counters, float *y,
+    int m, int n, int ks, int tiles, int tile_cols, int splits)
+{
+    w4_block<LPR, WAVES, U>(a, x, t, partial, counters, y, m, n, ks, blockIdx.x % tiles,
+                            blockIdx.x / tiles, tile_cols, splits);
+}
+
+// Several int4 matrices that read the same hidden state in one launch; the block finds its
+// matrix from its tile index as in sparse_gemv_multi_kernel.
+template <int LPR, int WAVES, int U>
+__global__ __launch_bounds__(WAVES * 64) void sparse_gemv_w4_multi_kernel(
+    MultiArgs<FmtW4> ma, const __half *__restrict__ x, float *partial, int *counters, int m,
+    int ks, int tile_cols, int splits)
+{
+    const int tiles = ma.tile_begin[ma.count];
+    const int gtile = blockIdx.x % tiles;
+    const int s = blockIdx.x / tiles;
+    int k = 0;
+    size_t partial_off = 0;
+#pragma unroll
+    for (int j = 1; j < kMaxMulti; ++j) {
+        if (j < ma.count && gtile >= ma.tile_begin[j]) {
+            partial_off += (size_t)splits * ma.n[j - 1];
+            k = j;
+        }
+    }
+    w4_block<LPR, WAVES, U>(ma.a[k], x, ma.t[k], partial + partial_off,
+                            counters + ma.tile_begin[k], ma.y[k], m, ma.n[k], ks,
+                            gtile - ma.tile_begin[k], s, tile_cols, splits);
 }
 
 hipError_t launch_gemv_w8(const int8_t *Wq, const void *scale_f16, const void *x_f16, float t,
@@ -243,19 +296,52 @@ hipError_t launch_gemv_w4(const uint8_t *Wq, const void *scale_f16, const void *
                           const GemvShape &sh, hipStream_t stream)
 {
     GemvShape w4 = sh;
-    w4.waves = 8;                                 // the int4 kernel is built for 8 wavefronts
+    w4.waves = kW4Waves;                          // the int4 kernel is built for 8 wavefronts
     const GemvGeometry g = gemv_geometry(m, n, w4, FmtW4::kElemsPerLane, kGroup);
     FmtW4::Args a{Wq, static_cast<const __half *>(scale_f16)};
     const __half *x = static_cast<const __half *>(x_f16);
-#define TEAL_LAUNCH_W4(LPR, WAVES)                                                             \
-    hipLaunchKernelGGL((sparse_gemv_w4_kernel<LPR, WAVES>), dim3(g.tiles * g.splits),           \
-                       dim3(WAVES * 64), g.lds, stream, a, x, t, partial, counters, y, m, n,   \
-                       g.ks, g.tiles, g.tile_cols, g.splits)
+#define TEAL_LAUNCH_W4(LPR)                                                                    \
+    hipLaunchKernelGGL((sparse_gemv_w4_kernel<LPR, kW4Waves, kW4Unroll>),                      \
+                       dim3(g.tiles * g.splits), dim3(kW4Waves * 64), g.lds, stream, a, x, t,  \
+                       partial, counters, y, m, n, g.ks, g.tiles, g.tile_cols, g.splits)
     // A lane covers 32 columns: 16 lanes per row (tiles up to 512 columns) or 32 lanes
     // per row (up to 1024 columns).
-    if (sh.lanes_per_row == 32) TEAL_LAUNCH_W4(32, 8);
-    else TEAL_LAUNCH_W4(16, 8);
+    if (sh.lanes_per_row == 32) TEAL_LAUNCH_W4(32);
+    else TEAL_LAUNCH_W4(16);
 #undef TEAL_LAUNCH_W4
+    return hipGetLastError();
+}
+
+hipError_t launch_gemv_w4_multi(int count, const uint8_t *const *Wq, const void *const *scale_f16,
+                                const float *t, float *const *y, const int *n, const void *x_f16,
+                                int m, float *partial, int *counters, const GemvShape &sh,
+                                hipStream_t stream)
+{
+    int n_max = 0;
+    for (int k = 0; k < count; ++k) n_max = n[k] > n_max ? n[k] : n_max;
+    GemvShape w4 = sh;
+    w4.waves = kW4Waves;
+    const GemvGeometry g = gemv_geometry(m, n_max, w4, FmtW4::kElemsPerLane, kGroup);
+    MultiArgs<FmtW4> ma{};
+    ma.count = count;
+    ma.tile_begin[0] = 0;
+    for (int k = 0; k < count; ++k) {
+        ma.a[k].W = Wq[k];
+        ma.a[k].scale = static_cast<const __half *>(scale_f16[k]);
+        ma.y[k] = y[k];
+        ma.t[k] = t[k];
+        ma.n[k] = n[k];
+        ma.tile_begin[k + 1] = ma.tile_begin[k] + (n[k] + g.tile_cols - 1) / g.tile_cols;
+    }
+    const int tiles = ma.tile_begin[count];
+    const __half *x = static_cast<const __half *>(x_f16);
+#define TEAL_LAUNCH_W4M(LPR)                                                                   \
+    hipLaunchKernelGGL((sparse_gemv_w4_multi_kernel<LPR, kW4Waves, kW4Unroll>),                \
+                       dim3(tiles * g.splits), dim3(kW4Waves * 64), g.lds, stream, ma, x,      \
+                       partial, counters, m, g.ks, g.tile_cols, g.splits)
+    if (sh.lanes_per_row == 32) TEAL_LAUNCH_W4M(32);
+    else TEAL_LAUNCH_W4M(16);
+#undef TEAL_LAUNCH_W4M
     return hipGetLastError();
 }
 

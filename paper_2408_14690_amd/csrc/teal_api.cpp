@@ -344,6 +344,34 @@ teal_status teal_sparse_gemv_w4(const uint8_t *Wq, const void *scale_f16, int gr
                                          static_cast<hipStream_t>(stream)));
 }
 
+teal_status teal_sparse_gemv_w4_multi(int count, const uint8_t *const *Wq,
+                                      const void *const *scale_f16, int group, const float *t,
+                                      float *const *y, const int *n, const void *x_f16, int m,
+                                      void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (count < 1 || count > teal::kMaxMatrices) return TEAL_ERR_UNSUPPORTED;
+    if (!Wq || !scale_f16 || !t || !y || !n || !x_f16 || !workspace) return TEAL_ERR_NULL;
+    long long n_total = 0;
+    for (int k = 0; k < count; ++k) {
+        if (!Wq[k] || !scale_f16[k] || !y[k]) return TEAL_ERR_NULL;
+        if (n[k] < 32 || n[k] > teal::kMaxDim || n[k] % 32 != 0) return TEAL_ERR_SHAPE;
+        n_total += n[k];
+    }
+    if (m < 1 || m > teal::kMaxDim || n_total > teal::kMaxDim) return TEAL_ERR_SHAPE;
+    for (int k = 0; k < count; ++k)
+        if (!aligned(Wq[k], 16) || !aligned(scale_f16[k], 16) || !aligned(y[k], 4))
+            return TEAL_ERR_ALIGN;
+    if (!aligned(x_f16, 2) || !aligned(workspace, kAlignWorkspace)) return TEAL_ERR_ALIGN;
+    for (int k = 0; k < count; ++k)
+        if (!threshold_ok(t[k])) return TEAL_ERR_THRESHOLD;
+    if (group != 128 || m % 128 != 0) return TEAL_ERR_UNSUPPORTED;
+    if (workspace_bytes < teal_workspace_bytes(m, (int)n_total)) return TEAL_ERR_WORKSPACE;
+    const GemvShape sh = auto_shape(m, (int)n_total, 32, 16, 32, 128);
+    return from_hip(teal::launch_gemv_w4_multi(count, Wq, scale_f16, t, y, n, x_f16, m,
+                                               ws_partials(workspace), ws_counters(workspace), sh,
+                                               static_cast<hipStream_t>(stream)));
+}
+
 teal_status teal_abs_histogram(const void *x_f16, size_t count, uint64_t *hist, void *stream)
 {
     if (!hist || (!x_f16 && count > 0)) return TEAL_ERR_NULL;

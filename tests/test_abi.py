@@ -165,6 +165,27 @@ def test_w8_multi_argument_errors():
     assert call(**five) == T.TEAL_ERR_UNSUPPORTED
 
 
+def test_w4_multi_argument_errors():
+    ok = dict(Wq_list=[W, W + 0x1000], scale_list=[SC, SC + 0x100], group=128, t_list=[0.5, 0.25],
+              y_list=[Y, Y + 0x1000], n_list=[4096, 1024], x_f16=X, m=4096, workspace=WS,
+              workspace_bytes=BIG, stream=0)
+
+    def call(**kw):
+        a = dict(ok)
+        a.update(kw)
+        return T.teal_sparse_gemv_w4_multi(**a)
+
+    assert call(Wq_list=[None, W]) == T.TEAL_ERR_NULL
+    assert call(scale_list=[SC, None]) == T.TEAL_ERR_NULL
+    assert call(n_list=[4096, 1040]) == T.TEAL_ERR_SHAPE          # not a multiple of 32
+    assert call(scale_list=[SC, SC + 8]) == T.TEAL_ERR_ALIGN
+    assert call(t_list=[-0.5, 0.5]) == T.TEAL_ERR_THRESHOLD
+    assert call(group=64) == T.TEAL_ERR_UNSUPPORTED
+    assert call(m=4160) == T.TEAL_ERR_UNSUPPORTED
+    assert call(workspace_bytes=16) == T.TEAL_ERR_WORKSPACE
+    assert T.teal_sparse_gemv_w4_multi([], [], 128, [], [], [], X, 4096, WS, BIG, 0) == T.TEAL_ERR_UNSUPPORTED
+
+
 def test_plan_is_reported():
     st, plan = T.teal_gemv_plan(16, 4096, 14336)
     assert st == T.TEAL_OK

@@ -423,3 +423,103 @@ def test_gemv_w4(T, n, m):
         got = run_w4(T, qd, sd, xd, t, m, n, ws)
         assert rel_l2(got, want) <= TIGHT, (n, m, p)
         assert rel_l2(got, want) <= TOL_WQ
+
+
+@pytest.mark.parametrize("name,ns,m,ps", [
+    ("llama3 q,k,v", [4096, 1024, 1024], 4096, [0.5, 0.4, 0.25]),
+    ("llama3 gate,up", [14336, 14336], 4096, [0.4, 0.5]),
+    ("ragged", [544, 32, 160, 64], 384, [0.0, 0.5, 0.9, 1.0]),
+    ("single", [1056], 2176, [0.5]),
+], ids=["qkv", "gate_up", "ragged", "single"])
+def test_gemv_w4_multi(T, name, ns, m, ps):
+    x = ti.gaussian_x(m, 800 + m)
+    xd = dev(x)
+    ws = workspace(T, m, sum(ns))
+    ws1 = workspace(T, m, max(ns))
+    qs_host, qs, scs, ts, ys = [], [], [], [], []
+    for k, (n, p) in enumerate(zip(ns, ps)):
+        q, scale = ti.quantize_w4(ti.weights_bf16(n, m, seed=3000 * k + n + m), 128)
+        qs_host.append((q, scale))
+        qs.append(dev(q))
+        scs.append(dev(scale))
+        ts.append(ti.quantile_threshold(x, p))
+        ys.append(torch.full((n,), float("nan"), dtype=torch.float32, device="cuda"))
+    T.check(T.teal_sparse_gemv_w4_multi(qs, scs, 128, ts, ys, ns, xd, m, ws))
+    torch.cuda.synchronize()
+    for k, n in enumerate(ns):
+        got = ys[k].cpu().numpy()
+        want = orc.sparse_gemv_w4(qs_host[k][0], qs_host[k][1], 128, x, ts[k])
+        assert rel_l2(got, want) <= TOL_WQ, (name, k)
+        assert rel_l2(got, want) <= 1e-4, (name, k)
+        alone = run_w4(T, qs[k], scs[k], xd, ts[k], m, n, ws1)
+        assert rel_l2(got, alone.astype(np.float64)) <= 1e-4
+    ys2 = [torch.full((n,), float("nan"), dtype=torch.float32, device="cuda") for n in ns]
+    T.check(T.teal_sparse_gemv_w4_multi(qs, scs, 128, ts, ys2, ns, xd, m, ws))
+    torch.cuda.synchronize()
+    for a, b in zip(ys, ys2):
+        assert torch.equal(a, b)
+
+
+# ---------------------------------------------------------------------------
+# captured into a HIP graph
+# ---------------------------------------------------------------------------
+
+def test_calls_replay_from_a_hip_graph(T):
+    """The calls only enqueue kernels on the given stream (no allocation, no host
+    synchronisation, no memset), so a sequence of them can be captured once and replayed.
+    Every replay must give the bits of the eager calls, with eager work in between."""
+    m, n = 4096, 1032
+    w = ti.weights_bf16(n, m, 41)
+    wt = dev(ti.to_input_channel_major(w))
+    q, scale = ti.quantize_w8(ti.weights_bf16(1040, m, 42))
+    qd, sd = dev(q), dev(scale)
+    x = ti.gaussian_x(m, 43)
+    X = ti.make_X(4, m, 44, "laplace")
+    xd, Xd = dev(x), dev(X)
+    t = ti.quantile_threshold(x, 0.5)
+    tb = ti.batch_quantile_threshold(X, 0.5)
+    ws = workspace(T, m, 2 * n + 1040)
+    wsb = torch.zeros(T.teal_workspace_bytes_batch(m, n, 4), dtype=torch.uint8, device="cuda")
+    outs = [torch.zeros(n, dtype=torch.float32, device="cuda") for _ in range(3)]
+    y8 = torch.zeros(1040, dtype=torch.float32, device="cuda")
+    Yb = torch.zeros((4, n), dtype=torch.float32, device="cuda")
+
+    def enqueue(stream):
+        T.check(T.teal_sparse_gemv_bf16(wt, xd, t, outs[0], m, n, ws, stream=stream))
+        T.check(T.teal_sparse_gemv_bf16_multi([wt, wt], [t, 0.0], [outs[1], outs[2]], [n, n], xd, m,
+                                              ws, stream=stream))
+        T.check(T.teal_sparse_gemv_w8(qd, sd, xd, t, y8, m, 1040, ws, stream=stream))
+        T.check(T.teal_sparse_gemv_bf16_batch(wt, Xd, 4, tb, Yb, m, n, wsb, stream=stream))
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [o.clone() for o in outs] + [y8.clone(), Yb.clone()]
+
+    def poison():
+        for o in outs + [y8, Yb]:
+            o.fill_(float("nan"))
+
+    enqueue(torch.cuda.current_stream())
+    eager = snapshot()
+    assert rel_l2(eager[0].cpu().numpy(), orc.sparse_gemv_bf16(w, x, t)) <= TIGHT
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        enqueue(side)
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        enqueue(side)
+    for replay in range(4):
+        poison()
+        torch.cuda.synchronize()
+        graph.replay()
+        got = snapshot()
+        for a, b in zip(eager, got):
+            assert torch.equal(a, b), replay
+        # eager work of the program itself between replays, on the same workspaces
+        poison()
+        enqueue(torch.cuda.current_stream())
+        for a, b in zip(eager, snapshot()):
+            assert torch.equal(a, b), replay
