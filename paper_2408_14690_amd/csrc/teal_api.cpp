@@ -178,7 +178,7 @@ teal_status teal_gemv_plan(int weight_bits, int m, int n, int *lanes_per_row, in
     if (m < 1 || m > teal::kMaxDim || n < 1 || n > teal::kMaxDim) return TEAL_ERR_SHAPE;
     GemvShape sh;
     if (weight_bits == 16) sh = auto_shape(m, n, 8, 16, 64, 64);
-    else if (weight_bits == 8) sh = auto_shape(m, n, 16, 16, 64, 64);
+    else if (weight_bits == 8) sh = auto_shape(m, n, 16, 8, 64, 64);
     else if (weight_bits == 4) sh = auto_shape(m, n, 32, 16, 32, 128);
     else return TEAL_ERR_UNSUPPORTED;
     if (lanes_per_row) *lanes_per_row = sh.lanes_per_row;
@@ -295,7 +295,7 @@ teal_status teal_sparse_gemv_w8(const int8_t *Wq, const void *scale_f16, const v
     const teal_status st = check_gemv(a, 16);
     if (st != TEAL_OK) return st;
     if (!aligned(scale_f16, 2)) return TEAL_ERR_ALIGN;
-    const GemvShape sh = auto_shape(m, n, 16, 16, 64, 64);
+    const GemvShape sh = auto_shape(m, n, 16, 8, 64, 64);
     return from_hip(teal::launch_gemv_w8(Wq, scale_f16, x_f16, t, y, m, n, ws_partials(workspace),
                                          ws_counters(workspace), sh,
                                          static_cast<hipStream_t>(stream)));
@@ -322,7 +322,7 @@ teal_status teal_sparse_gemv_w8_multi(int count, const int8_t *const *Wq,
     for (int k = 0; k < count; ++k)
         if (!threshold_ok(t[k])) return TEAL_ERR_THRESHOLD;
     if (workspace_bytes < teal_workspace_bytes(m, (int)n_total)) return TEAL_ERR_WORKSPACE;
-    const GemvShape sh = auto_shape(m, (int)n_total, 16, 16, 64, 64);
+    const GemvShape sh = auto_shape(m, (int)n_total, 16, 8, 64, 64);
     return from_hip(teal::launch_gemv_w8_multi(count, Wq, scale_f16, t, y, n, x_f16, m,
                                                ws_partials(workspace), ws_counters(workspace), sh,
                                                static_cast<hipStream_t>(stream)));
