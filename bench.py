@@ -43,11 +43,15 @@ CACHE_DEFEAT_BYTES = 3 << 30    # distinct weight bytes walked before a copy is 
 BITS = {"bf16": 16, "w8": 8, "w4": 4}
 KERNEL = {"bf16": "sparse_gemv_kernel<FmtBF16>", "w8": "sparse_gemv_kernel<FmtW8>",
           "w4": "sparse_gemv_w4_kernel"}
-# HBM bytes per launch of sparse_gemv_kernel at 50% (average over the 7 launches of a step),
-# from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script, scaled by the factors a
-# plain copy of known size gives on the same box (2.0 and 1.0):
+# HBM bytes per launch at 50% (average over the launches of a step), from rocprofv3 --pmc
+# FETCH_SIZE / WRITE_SIZE runs of this script, scaled by the factors a plain copy of known
+# size gives on the same box (2.0 and 1.0).  Keyed by (workload, format, sparsity, layers,
+# grouped launches): profiles/sparse_gemv_multi_kernel_llama2_7b_hbm_traffic.txt and
 # profiles/sparse_gemv_kernel_llama2_7b_hbm_traffic.txt.
-MEASURED_TRAFFIC_BYTES = {("llama2_7b", "bf16", 0.5, 1, False): (200319.57 + 1555.31) * 1024 / 7}
+MEASURED_TRAFFIC_BYTES = {
+    ("llama2_7b", "bf16", 0.5, 1, True): (199550.86 + 1271.53) * 1024 / 4,
+    ("llama2_7b", "bf16", 0.5, 1, False): (200319.57 + 1555.31) * 1024 / 7,
+}
 
 
 def algorithmic_bytes(fmt: str, nnz: int, m: int, n: int, batch: int = 1) -> int:
