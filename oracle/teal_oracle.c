@@ -29,7 +29,9 @@
  * sparsity against the order statistic that chose t; the closed-form
  * relative error of Theorem A.1; the batched criterion of Section 5.4.4
  * against exact rational arithmetic, its reduction to Definition 1 at batch
- * size 1 and on a batch of identical rows, and a dense numpy product.  The int4 nibble order and the scale
+ * size 1 and on a batch of identical rows, and a dense numpy product; the
+ * binary32 arithmetic of the MLP intermediate against the fp64 formula and
+ * the binary16 rounding against numpy on every boundary case.  The int4 nibble order and the scale
  * indexing of the quantised variants are conventions of this build, not of
  * the paper (Section 5.3 only names the bit widths): for those two layout
  * conventions parity is unpinned by the paper and pinned only by hand-built
@@ -38,6 +40,7 @@
 #include <math.h>
 #include <stddef.h>
 #include <stdint.h>
+#include <string.h>
 
 #ifdef _OPENMP
 #include <omp.h>
@@ -267,6 +270,106 @@ int32_t oracle_sparse_gemv_bf16_batch(const uint16_t *W_bf16,
         dense_rows_bf16(W_bf16, scratch_xs, Y + (size_t)b * (size_t)n, m, n);
     }
     return count;
+}
+
+/* ---- the MLP intermediate as the input of W_down (Appendix A.3) ----------- */
+
+/*
+ * Appendix A.3: MLP(x) = (SiLU(x W_gate^T) . x W_up^T) W_down^T with
+ * SiLU(v) = v * sigma(v).  Under the method the input of W_down, the
+ * intermediate h = SiLU(g) . u, is thresholded like any other hidden state
+ * (Section 4.2).  A kernel that forms h itself from g = x W_gate^T and
+ * u = x W_up^T (both fp32, as the products leave the previous calls) has to
+ * fix h's arithmetic, because h decides the mask: which side of t an entry
+ * falls on must not depend on who evaluates exp.  So this part of the oracle
+ * is NOT fp64: it states, operation by operation in IEEE binary32 with
+ * round-to-nearest-even, the arithmetic that defines h (the kernel's
+ * precision), and the tests pin it against the fp64 formula to a few units in
+ * the last place.  Everything after h (Definition 1, the product) is the fp64
+ * oracle above.
+ *
+ *   z  = clamp(-g, -80, 80)               (exp(+-80) is far inside binary32;
+ *                                          beyond it sigma is 1 or 0 to rounding)
+ *   k  = rint(z * log2(e))
+ *   r  = fma(k, -ln2_hi, z); r = fma(k, -ln2_lo, r)       (|r| <= ln2 / 2)
+ *   p  = 1 + r + r^2/2! + ... + r^7/7!   by Horner's rule with fma
+ *   e  = p * 2^k                          (exact scaling)
+ *   sg = 1 / (1 + e);  SiLU = g * sg;  h32 = SiLU * u;  h = binary16(h32)
+ * A NaN in g or u gives h = NaN (dropped by Definition 1's comparison).
+ */
+static float exp_neg_f32(float g)
+{
+    float z = -g;
+    if (z > 80.0f) z = 80.0f;
+    if (z < -80.0f) z = -80.0f;
+    const float k = rintf(z * 1.44269502f);             /* log2(e) in binary32 */
+    float r = fmaf(k, -0.693145752f, z);                /* ln 2, high part (0x3f317200) */
+    r = fmaf(k, -1.42860677e-06f, r);                   /* ln 2, low part */
+    float p = 1.0f / 5040.0f;
+    p = fmaf(p, r, 1.0f / 720.0f);
+    p = fmaf(p, r, 1.0f / 120.0f);
+    p = fmaf(p, r, 1.0f / 24.0f);
+    p = fmaf(p, r, 1.0f / 6.0f);
+    p = fmaf(p, r, 0.5f);
+    p = fmaf(p, r, 1.0f);
+    p = fmaf(p, r, 1.0f);
+    return ldexpf(p, (int)k);
+}
+
+float oracle_silu_f32(float g)
+{
+    if (g != g) return g;
+    const float e = exp_neg_f32(g);
+    const float sg = 1.0f / (1.0f + e);
+    return g * sg;
+}
+
+/* binary32 -> binary16 bit pattern, round to nearest even (overflow -> Inf). */
+uint16_t oracle_f32_to_f16_bits(float v)
+{
+    uint32_t u;
+    memcpy(&u, &v, sizeof u);
+    const uint16_t sign = (uint16_t)((u >> 16) & 0x8000u);
+    const uint32_t mag = u & 0x7FFFFFFFu;
+    if (mag > 0x7F800000u) return (uint16_t)(sign | 0x7E00u);          /* NaN */
+    if (mag >= 0x47800000u) return (uint16_t)(sign | 0x7C00u);          /* >= 65536: Inf (also Inf) */
+    if (mag < 0x33000000u) return sign;                                 /* < 2^-25: rounds to zero */
+    const int e = (int)(mag >> 23) - 127;                               /* unbiased exponent */
+    uint32_t frac = (mag & 0x7FFFFFu) | 0x800000u;                      /* 24-bit significand */
+    /* number of low bits to drop: 13 for normal halves, more for subnormal ones */
+    int drop = e >= -14 ? 13 : 13 + (-14 - e);
+    uint32_t kept = frac >> drop;
+    const uint32_t rem = frac & ((1u << drop) - 1u);
+    const uint32_t half = 1u << (drop - 1);
+    if (rem > half || (rem == half && (kept & 1u))) ++kept;
+    uint32_t out;
+    if (e >= -14)
+        out = ((uint32_t)(e + 15) << 10) + (kept - 0x400u);            /* a carry bumps the exponent */
+    else
+        out = kept;                                                     /* subnormal (0x400 = smallest normal) */
+    return (uint16_t)(sign | (uint16_t)out);                            /* 65520..65535.99 round to 0x7C00 = Inf */
+}
+
+/* h[i] = binary16(SiLU(gate[i]) * up[i]) as defined above. */
+void oracle_swiglu_f16(const float *gate, const float *up, int32_t m, uint16_t *h_f16)
+{
+    for (int32_t i = 0; i < m; ++i) {
+        const float h32 = oracle_silu_f32(gate[i]) * up[i];
+        h_f16[i] = oracle_f32_to_f16_bits(h32);
+    }
+}
+
+/*
+ * y = s_t(h) W_down^T with h formed from gate and up as above; W is canonical
+ * [n][m].  scratch_h: m uint16; scratch_xs: m doubles.  Returns the kept count.
+ */
+int32_t oracle_sparse_gemv_bf16_swiglu(const uint16_t *W_bf16, const float *gate,
+                                       const float *up, float t, double *y,
+                                       int32_t m, int32_t n, uint16_t *scratch_h,
+                                       double *scratch_xs)
+{
+    oracle_swiglu_f16(gate, up, m, scratch_h);
+    return oracle_sparse_gemv_bf16(W_bf16, scratch_h, t, y, m, n, scratch_xs);
 }
 
 /* Threads the parallel loops above use (1 when built without OpenMP). */

@@ -67,6 +67,16 @@ def _load():
     lib.oracle_sparse_gemv_bf16_batch.restype = c.c_int32
     lib.oracle_sparse_gemv_bf16_batch.argtypes = [u16p, u16p, c.c_int32, c.c_float, f64p,
                                                   c.c_int32, c.c_int32, u8p, f64p]
+    f32p = c.POINTER(c.c_float)
+    lib.oracle_silu_f32.restype = c.c_float
+    lib.oracle_silu_f32.argtypes = [c.c_float]
+    lib.oracle_f32_to_f16_bits.restype = c.c_uint16
+    lib.oracle_f32_to_f16_bits.argtypes = [c.c_float]
+    lib.oracle_swiglu_f16.restype = None
+    lib.oracle_swiglu_f16.argtypes = [f32p, f32p, c.c_int32, u16p]
+    lib.oracle_sparse_gemv_bf16_swiglu.restype = c.c_int32
+    lib.oracle_sparse_gemv_bf16_swiglu.argtypes = [u16p, f32p, f32p, c.c_float, f64p,
+                                                   c.c_int32, c.c_int32, u16p, f64p]
     u64p = c.POINTER(c.c_uint64)
     lib.oracle_quantile_rank.restype = c.c_uint64
     lib.oracle_quantile_rank.argtypes = [c.c_uint64, c.c_double]
@@ -239,6 +249,52 @@ def sparse_gemv_bf16_batch(w_bits, X_f16, t) -> np.ndarray:
                                           batch, _f32(t), _ptr(Y, ctypes.c_double), m, n,
                                           _ptr(mask, ctypes.c_uint8), _ptr(xs, ctypes.c_double))
     return Y
+
+
+def silu_f32(g: float) -> float:
+    """SiLU in the binary32 arithmetic that defines the MLP intermediate."""
+    return float(_load().oracle_silu_f32(float(np.float32(g))))
+
+
+def f32_to_f16_bits(v: float) -> int:
+    return int(_load().oracle_f32_to_f16_bits(float(np.float32(v))))
+
+
+def _f32_vec(a, name) -> np.ndarray:
+    a = np.ascontiguousarray(a)
+    if a.dtype != np.float32 or a.ndim != 1:
+        raise TypeError(f"{name} must be a 1-D float32 array")
+    return a
+
+
+def swiglu_f16(gate_f32, up_f32) -> np.ndarray:
+    """Appendix A.3: h = SiLU(gate) * up, rounded to fp16 (returned as float16[m])."""
+    g, u = _f32_vec(gate_f32, "gate"), _f32_vec(up_f32, "up")
+    if g.size != u.size:
+        raise ValueError("gate and up must have the same length")
+    h = np.empty(g.size, np.uint16)
+    _load().oracle_swiglu_f16(_ptr(g, ctypes.c_float), _ptr(u, ctypes.c_float), g.size,
+                              _ptr(h, ctypes.c_uint16))
+    return h.view(np.float16)
+
+
+def sparse_gemv_bf16_swiglu(w_bits, gate_f32, up_f32, t) -> np.ndarray:
+    """y float64[n] = s_t(SiLU(gate) * up) W^T for canonical W[n][m] (the W_down step)."""
+    w = np.ascontiguousarray(w_bits)
+    if w.dtype != np.uint16 or w.ndim != 2:
+        raise TypeError("W must be a 2-D uint16 array of bf16 bit patterns, [n][m]")
+    g, u = _f32_vec(gate_f32, "gate"), _f32_vec(up_f32, "up")
+    n, m = w.shape
+    if g.size != m or u.size != m:
+        raise ValueError("gate / up length must equal W's input dimension")
+    y = np.empty(n, np.float64)
+    h = np.empty(m, np.uint16)
+    xs = np.empty(m, np.float64)
+    _load().oracle_sparse_gemv_bf16_swiglu(_ptr(w, ctypes.c_uint16), _ptr(g, ctypes.c_float),
+                                           _ptr(u, ctypes.c_float), _f32(t),
+                                           _ptr(y, ctypes.c_double), m, n,
+                                           _ptr(h, ctypes.c_uint16), _ptr(xs, ctypes.c_double))
+    return y
 
 
 def quantile_rank(n_valid: int, p: float) -> int:

@@ -108,6 +108,17 @@ def quantile_threshold(x_f16: np.ndarray, p: float) -> float:
     return float(np.partition(a, k - 1)[k - 1])
 
 
+def mlp_gate_up(m: int, seed: int):
+    """The two fp32 vectors from which the input of W_down is formed (Appendix A.3):
+    gate = x W_gate^T and up = x W_up^T of a synthetic block, both Gaussian-shaped
+    (N(0, 1.5^2) and N(0, 1)); their SiLU-gated product is Laplacian-shaped like the
+    real MLP intermediate (Section 4.1, Figure 2).  Returns (gate, up) float32[m]."""
+    rng = _rng(seed)
+    gate = (rng.standard_normal(m) * 1.5).astype(np.float32)
+    up = rng.standard_normal(m).astype(np.float32)
+    return gate, up
+
+
 def make_X(batch: int, m: int, seed: int, dist: str) -> np.ndarray:
     """A small batch of independent hidden states, [batch][m] fp16 (rows drawn
     one after the other from one seeded stream)."""
