@@ -4,7 +4,7 @@
     python bench.py [--gpus 1] [--steps K] [--warmup W]
                     [--workload llama2_7b|llama3_8b|llama_70b] [--format bf16|w8|w4]
                     [--sparsities 0.5,0.4,0] [--layers L] [--unfused] [--batch B]
-                    [--calibration]
+                    [--calibration] [--swiglu] [--graph]
 
 A step is one pass of the whole hot path over a synthetic decoder block at
 batch 1: for each of the seven projections, threshold the hidden state, compact
@@ -22,7 +22,8 @@ finds its rows in the 256 MB last-level cache.  With --layers L > 1 a step is
 a stack of L blocks with their own weights and states (the 80-block
 70B-shaped stack is 137 GB resident), and no copies are needed.  --batch B
 runs the small-batch variant (one mask per batch from the averaged magnitude),
---calibration the threshold calibration pass.
+--calibration the threshold calibration pass, --swiglu the W_down step with its
+input formed in the kernel.
 
 Prints ONE JSON line.  More than one GPU is not supported.
 """
@@ -406,6 +407,93 @@ def run_calibration(T, torch, args) -> int:
     return 0
 
 
+def run_swiglu(T, torch, args) -> int:
+    """The W_down step including the formation of its input h = SiLU(gate) * up
+    (Appendix A.3), two ways: the element-wise producer kernel followed by the sparse
+    GEMV (two launches, h written to and read back from HBM), and the fused call."""
+    n, m = ti.LAYER_SHAPES[args.workload]["down"]
+    cfg = ti.CONFIG_INDEX[args.workload]
+    gate, up = ti.mlp_gate_up(m, ti.x_seed(cfg, 0, "down"))
+    from oracle import teal_oracle as orc            # harness: h on the host only to pick t
+    h = orc.swiglu_f16(gate, up)
+    w = ti.weights_bf16(n, m, ti.weight_seed(cfg, 0, "down"))
+    copies = max(2, -(-CACHE_DEFEAT_BYTES // (n * m * 2)))
+    wd = torch.from_numpy(w.view(np.int16)).cuda()
+    wt0 = torch.empty((m, n), dtype=torch.int16, device="cuda")
+    T.check(T.teal_pack_bf16(wd, wt0, m, n))
+    wts = [wt0] + [wt0.clone() for _ in range(copies - 1)]
+    gd, ud = torch.from_numpy(gate).cuda(), torch.from_numpy(up).cuda()
+    hd = torch.empty(m, dtype=torch.int16, device="cuda")
+    y = torch.empty(n, dtype=torch.float32, device="cuda")
+    ws = torch.zeros(T.teal_workspace_bytes(m, n), dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    wp = [t.data_ptr() for t in wts]
+    gp, up_, hp, yp, wsp, wsb = gd.data_ptr(), ud.data_ptr(), hd.data_ptr(), y.data_ptr(), ws.data_ptr(), ws.numel()
+
+    def two_launch(k, t):
+        T.teal_swiglu_f16(gp, up_, hp, m, stream)
+        T.check(T.teal_sparse_gemv_bf16(wp[k % copies], hp, t, yp, m, n, wsp, wsb, stream))
+
+    def fused(k, t):
+        T.check(T.teal_sparse_gemv_bf16_swiglu(wp[k % copies], gp, up_, t, yp, m, n, wsp, wsb, stream))
+
+    def timed(fn, t):
+        for k in range(args.warmup):
+            fn(k, t)
+        torch.cuda.synchronize()
+        start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        start.record()
+        for k in range(args.steps):
+            fn(k, t)
+        stop.record()
+        torch.cuda.synchronize()
+        return start.elapsed_time(stop) * 1e-3 / args.steps
+
+    sparsities = [float(v) for v in args.sparsities.split(",")]
+    if 0.0 not in sparsities:
+        sparsities.append(0.0)
+    head = sparsities[0]
+    detail, sec_f = {}, {}
+    for p in sparsities:
+        t = ti.quantile_threshold(h, p)
+        nnz = int(np.count_nonzero(np.abs(h.astype(np.float32)) > np.float32(t)))
+        sf, s2 = timed(fused, t), timed(two_launch, t)
+        sec_f[p] = sf
+        b = nnz * n * 2 + 8 * m + 4 * n              # surviving rows + gate + up (fp32) + y
+        detail[pct(p)] = {"nnz": nnz, "fused_us": sf * 1e6, "two_launch_us": s2 * 1e6,
+                          "saved_us": (s2 - sf) * 1e6, "effective_bytes": b,
+                          "effective_GBps": b / sf / 1e9,
+                          "frac_of_hbm_peak": b / sf / 1e9 / HBM_PEAK_GBS}
+    for p in sparsities:
+        detail[pct(p)]["speedup_vs_dense"] = sec_f[0.0] / sec_f[p]
+    # check the fused result against the oracle once
+    t = ti.quantile_threshold(h, head)
+    fused(0, t)
+    torch.cuda.synchronize()
+    want = orc.sparse_gemv_bf16_swiglu(w, gate, up, t)
+    rel = float(np.linalg.norm(y.cpu().numpy().astype(np.float64) - want) / np.linalg.norm(want))
+    d = detail[pct(head)]
+    out = {
+        "metric": f"W_down step with its input formed in the kernel, effective HBM GB/s at "
+                  f"{pct(head)} sparsity of the MLP intermediate",
+        "value": d["effective_GBps"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": d["fused_us"] * 1e-3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{args.workload}-shaped W_down ({n} x {m}, bf16), input "
+                               f"h = fp16(SiLU(gate) * up) from fp32 gate ~ N(0,1.5^2), up ~ N(0,1); "
+                               f"t at the {pct(head)} quantile of |h|",
+                   "weight_copies_walked": copies},
+        "roofline": {"bound": "hbm", "achieved": d["effective_GBps"], "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": d["frac_of_hbm_peak"], "traffic": None,
+                     "kernel": "sparse_gemv_swiglu_kernel<FmtBF16> (1 launch per step)",
+                     "bytes_per_launch_avg": d["effective_bytes"], "kernel_avg_us": d["fused_us"]},
+        "detail": detail,
+        "rel_l2_vs_oracle": rel,
+    }
+    print(json.dumps(out))
+    return 0
+
+
 def pct(p: float) -> str:
     return f"{int(round(p * 100))}%"
 
@@ -431,6 +519,9 @@ def main() -> int:
                          "mask of the averaged magnitude (Section 5.4.4); bf16 only. 0 = one state")
     ap.add_argument("--graph", action="store_true",
                     help="also time the headline pass replayed from a captured HIP graph")
+    ap.add_argument("--swiglu", action="store_true",
+                    help="time the W_down step with its input formed from gate and up in the kernel "
+                         "against the two-launch path (Appendix A.3)")
     ap.add_argument("--calibration", action="store_true",
                     help="time threshold calibration (histogram + thresholds) instead of the GEMV path")
     ap.add_argument("--calibration-tokens", type=int, default=16384)
@@ -452,6 +543,8 @@ def main() -> int:
         from paper_2408_14690_amd import build
         build.build(verbose=False)
     T.load_library()
+    if args.swiglu:
+        return run_swiglu(T, torch, args)
     if args.calibration:
         if args.calibration_tokens % 64 or args.calibration_tokens <= 0:
             print("bench.py: --calibration-tokens must be a positive multiple of 64", file=sys.stderr)

@@ -118,6 +118,33 @@ teal_status teal_sparse_gemv_bf16_multi(int count, const void *const *Wt_bf16, c
                                         void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The W_down step with its input formed on the fly (Appendix A.3:
+ * MLP(x) = (SiLU(x W_gate^T) . x W_up^T) W_down^T; Section 4.2 thresholds the
+ * intermediate h = SiLU(g) . u like any other input).
+ *
+ * h_i = fp16(SiLU(gate_i) * up_i) in the following binary32 arithmetic, every
+ * operation rounded to nearest even (the value decides the mask, so it is part
+ * of the interface): z = clamp(-g, -80, 80); k = rint(z * 1.44269502f);
+ * r = fma(k, -0.693145752f, z); r = fma(k, -1.42860677e-06f, r);
+ * p = the degree-7 Taylor polynomial of exp at r by Horner's rule with fma;
+ * e = p * 2^k; sigma = 1 / (1 + e); SiLU = g * sigma; h32 = SiLU * u;
+ * h = binary16(h32).  NaN in g or u gives NaN (dropped).
+ *
+ * teal_swiglu_f16: the producer alone, h_f16[i] for i < m (0 <= m <= 2^24).
+ *   gate, up [m] fp32, 4-byte aligned; h_f16 [m] fp16.
+ *
+ * teal_sparse_gemv_bf16_swiglu: y = s_t(h) W_down^T in one launch; results are
+ * bitwise those of teal_swiglu_f16 followed by teal_sparse_gemv_bf16, without
+ * the element-wise launch and without h travelling through HBM.
+ *   Wt_bf16, t, y, m, n, workspace as for teal_sparse_gemv_bf16 (m = the MLP
+ *   width, n = the model width).
+ */
+teal_status teal_swiglu_f16(const float *gate, const float *up, void *h_f16, int m, void *stream);
+teal_status teal_sparse_gemv_bf16_swiglu(const void *Wt_bf16, const float *gate, const float *up,
+                                         float t, float *y, int m, int n,
+                                         void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * The same product for 8-bit channel-wise quantised weights (Section 5.3):
  * W[j][i] = Wq[i][j] * scale[j].
  *   Wq    [m][n] int8 (symmetric, two's complement), 16-byte aligned.

@@ -15,5 +15,5 @@ from .binding import (  # noqa: F401
     teal_sparse_gemv_bf16_multi, teal_abs_histogram, teal_histogram_thresholds, TEAL_HIST_BINS,
     teal_workspace_bytes_batch, teal_sparsify_batch, teal_sparse_gemv_bf16_batch,
     teal_sparse_gemv_bf16_batch_ex, TEAL_MAX_BATCH, teal_sparse_gemv_w8_multi,
-    teal_sparse_gemv_w4_multi,
+    teal_sparse_gemv_w4_multi, teal_swiglu_f16, teal_sparse_gemv_bf16_swiglu,
 )

@@ -29,6 +29,7 @@ EXPORTS = (
     "teal_abs_histogram", "teal_histogram_thresholds", "teal_workspace_bytes_batch",
     "teal_sparsify_batch", "teal_sparse_gemv_bf16_batch", "teal_sparse_gemv_bf16_batch_ex",
     "teal_sparse_gemv_w8_multi", "teal_sparse_gemv_w4_multi",
+    "teal_swiglu_f16", "teal_sparse_gemv_bf16_swiglu",
 )
 TEAL_HIST_BINS = 32768
 TEAL_MAX_BATCH = 8
@@ -82,6 +83,10 @@ def load_library():
     lib.teal_sparse_gemv_w4_multi.restype = i
     lib.teal_sparse_gemv_w4_multi.argtypes = [i, c.POINTER(vp), c.POINTER(vp), i, c.POINTER(f),
                                               c.POINTER(vp), c.POINTER(i), vp, i, vp, sz, vp]
+    lib.teal_swiglu_f16.restype = i
+    lib.teal_swiglu_f16.argtypes = [vp, vp, vp, i, vp]
+    lib.teal_sparse_gemv_bf16_swiglu.restype = i
+    lib.teal_sparse_gemv_bf16_swiglu.argtypes = [vp, vp, vp, f, vp, i, i, vp, sz, vp]
     lib.teal_abs_histogram.restype = i
     lib.teal_abs_histogram.argtypes = [vp, sz, vp, vp]
     lib.teal_histogram_thresholds.restype = i
@@ -265,6 +270,18 @@ def teal_sparse_gemv_w4_multi(Wq_list, scale_list, group, t_list, y_list, n_list
     N = (ctypes.c_int * count)(*[int(n) for n in n_list])
     return load_library().teal_sparse_gemv_w4_multi(
         count, W, S, int(group), Tt, Y, N, _ptr(x_f16), int(m), _ptr(workspace),
+        _nbytes(workspace, workspace_bytes), _stream(stream))
+
+
+def teal_swiglu_f16(gate, up, h_f16, m, stream=None) -> int:
+    return load_library().teal_swiglu_f16(_ptr(gate), _ptr(up), _ptr(h_f16), int(m),
+                                          _stream(stream))
+
+
+def teal_sparse_gemv_bf16_swiglu(Wt_bf16, gate, up, t, y, m, n, workspace, workspace_bytes=None,
+                                 stream=None) -> int:
+    return load_library().teal_sparse_gemv_bf16_swiglu(
+        _ptr(Wt_bf16), _ptr(gate), _ptr(up), float(t), _ptr(y), int(m), int(n), _ptr(workspace),
         _nbytes(workspace, workspace_bytes), _stream(stream))
 
 

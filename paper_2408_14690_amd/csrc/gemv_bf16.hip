@@ -48,6 +48,21 @@ hipError_t launch_gemv_bf16(const void *Wt, const void *x_f16, float t, float *y
     return hipGetLastError();
 }
 
+hipError_t launch_gemv_bf16_swiglu(const void *Wt, const float *gate, const float *up, float t,
+                                   float *y, int m, int n, float *partial, int *counters,
+                                   const GemvShape &sh, hipStream_t stream)
+{
+    const GemvGeometry g = gemv_geometry(m, n, sh, FmtBF16::kElemsPerLane, 64);
+    FmtBF16::Args a{Wt};
+#define TEAL_LAUNCH(F, LPR, WAVES, U)                                                          \
+    hipLaunchKernelGGL((sparse_gemv_swiglu_kernel<F, LPR, WAVES, U>), dim3(g.tiles * g.splits), \
+                       dim3(WAVES * 64), g.lds, stream, a, gate, up, t, partial, counters, y,  \
+                       m, n, g.ks, g.tiles, g.tile_cols, g.splits)
+    TEAL_DISPATCH(TEAL_LAUNCH, FmtBF16, sh);
+#undef TEAL_LAUNCH
+    return hipGetLastError();
+}
+
 hipError_t launch_gemv_bf16_multi(int count, const void *const *Wt, const float *t,
                                   float *const *y, const int *n, const void *x_f16, int m,
                                   float *partial, int *counters, const GemvShape &sh,

@@ -70,6 +70,56 @@ __device__ __forceinline__ int wave_inclusive_scan(int v)
     return v;
 }
 
+// Where a block's activations come from.  A source returns channel i as an fp32
+// value that is exactly an fp16 value.
+struct HalfSource {                   // the hidden state itself, fp16 in memory
+    const __half *x;
+    __device__ __forceinline__ float operator()(int i) const { return __half2float(x[i]); }
+};
+
+// SiLU(g) * u rounded to fp16 (Appendix A.3: the input of W_down), in stated
+// binary32 arithmetic, because this value decides the mask: clamp -g to
+// [-80, 80]; exp by k = rint(z log2 e), r = z - k ln2 (two fmas, ln2 split
+// high / low), the degree-7 Taylor polynomial by Horner's rule with fmas, exact
+// scaling by 2^k; sigma = 1 / (1 + e) (correctly rounded division);
+// SiLU = g * sigma; times u; round to nearest even.  NaN in, NaN out.
+__device__ __forceinline__ float swiglu_value(float g, float u)
+{
+#pragma clang fp contract(off)
+    float z = -g;
+    z = z > 80.0f ? 80.0f : z;
+    z = z < -80.0f ? -80.0f : z;
+    const float k = rintf(z * 1.44269502f);
+    float r = fmaf(k, -0.693145752f, z);
+    r = fmaf(k, -1.42860677e-06f, r);
+    float p = 1.0f / 5040.0f;
+    p = fmaf(p, r, 1.0f / 720.0f);
+    p = fmaf(p, r, 1.0f / 120.0f);
+    p = fmaf(p, r, 1.0f / 24.0f);
+    p = fmaf(p, r, 1.0f / 6.0f);
+    p = fmaf(p, r, 0.5f);
+    p = fmaf(p, r, 1.0f);
+    p = fmaf(p, r, 1.0f);
+    const float e = ldexpf(p, (int)k);
+    const float sg = 1.0f / (1.0f + e);
+    const float silu = g != g ? g : g * sg;
+    float h32 = silu * u;
+    // The product is rounded to binary32 first and to binary16 second.  Without this
+    // fence the compiler folds the two into one mixed-precision instruction that rounds
+    // the exact product once, which differs from the stated arithmetic near ties.
+    asm volatile("" : "+v"(h32));
+    return __half2float(__float2half_rn(h32));
+}
+
+struct SwigluSource {                 // gate = x W_gate^T and up = x W_up^T, fp32 in memory
+    const float *gate;
+    const float *up;
+    __device__ __forceinline__ float operator()(int i) const
+    {
+        return swiglu_value(gate[i], up[i]);
+    }
+};
+
 // Definition 1 on one element: fp16 -> fp32 is exact, the compare is fp32.
 __device__ __forceinline__ bool survives(float xv, float t) { return fabsf(xv) > t; }
 
@@ -83,8 +133,8 @@ __device__ __forceinline__ bool survives(float xv, float t) { return fabsf(xv) >
 // loads of x are issued together.  Returns the total (same in all threads).
 // Needs k1 - k0 <= kMaxSlice.  All threads of the block must call it; ends
 // with a barrier after which list[] is complete.
-template <int WAVES>
-__device__ __forceinline__ int compact_slice(const __half *__restrict__ x, float t, int k0,
+template <int WAVES, class XS>
+__device__ __forceinline__ int compact_slice(const XS &x, float t, int k0,
                                              int k1, int2 *list, int *seg_cnt, int &seg_excl)
 {
     constexpr int PER_WAVE = kMaxSegs / WAVES;
@@ -99,7 +149,7 @@ __device__ __forceinline__ int compact_slice(const __half *__restrict__ x, float
 #pragma unroll
     for (int j = 0; j < PER_WAVE; ++j) {
         const int i = k0 + (w + j * WAVES) * 64 + lane;
-        const float v = __half2float(x[min(i, k1 - 1)]);
+        const float v = x(min(i, k1 - 1));
         xv[j] = i < k1 ? v : 0.f;                     // x = 0 never survives (t >= 0)
     }
 #pragma unroll
@@ -319,8 +369,8 @@ __device__ __forceinline__ int lane_column(int col0, int cols, int n, int l)
 
 // Work of one block for formats with no per-group state (bf16, int8): output
 // tile `tile` (tile_cols columns) x K-slice `s` (ks channels) of one matrix.
-template <class F, int LPR, int WAVES, int U>
-__device__ __forceinline__ void gemv_block(const typename F::Args &a, const __half *__restrict__ x,
+template <class F, int LPR, int WAVES, int U, class XS>
+__device__ __forceinline__ void gemv_block(const typename F::Args &a, const XS &x,
                                            float t, float *partial, int *counters, float *y, int m,
                                            int n, int ks, int tile, int s, int tile_cols,
                                            int splits)
@@ -366,8 +416,21 @@ __global__ __launch_bounds__(WAVES * 64) void sparse_gemv_kernel(
     typename F::Args a, const __half *__restrict__ x, float t, float *partial, int *counters,
     float *y, int m, int n, int ks, int tiles, int tile_cols, int splits)
 {
-    gemv_block<F, LPR, WAVES, U>(a, x, t, partial, counters, y, m, n, ks, blockIdx.x % tiles,
-                                 blockIdx.x / tiles, tile_cols, splits);
+    gemv_block<F, LPR, WAVES, U>(a, HalfSource{x}, t, partial, counters, y, m, n, ks,
+                                 blockIdx.x % tiles, blockIdx.x / tiles, tile_cols, splits);
+}
+
+// The W_down step with its input formed in the kernel from the two products that
+// precede it (Appendix A.3): one launch instead of an element-wise kernel plus
+// the product, and the intermediate never travels through HBM.
+template <class F, int LPR, int WAVES, int U>
+__global__ __launch_bounds__(WAVES * 64) void sparse_gemv_swiglu_kernel(
+    typename F::Args a, const float *__restrict__ gate, const float *__restrict__ up, float t,
+    float *partial, int *counters, float *y, int m, int n, int ks, int tiles, int tile_cols,
+    int splits)
+{
+    gemv_block<F, LPR, WAVES, U>(a, SwigluSource{gate, up}, t, partial, counters, y, m, n, ks,
+                                 blockIdx.x % tiles, blockIdx.x / tiles, tile_cols, splits);
 }
 
 // Several matrices that read the same hidden state (q/k/v, or gate/up:
@@ -404,7 +467,7 @@ __global__ __launch_bounds__(WAVES * 64) void sparse_gemv_multi_kernel(
             k = j;
         }
     }
-    gemv_block<F, LPR, WAVES, U>(ma.a[k], x, ma.t[k], partial + partial_off,
+    gemv_block<F, LPR, WAVES, U>(ma.a[k], HalfSource{x}, ma.t[k], partial + partial_off,
                                  counters + ma.tile_begin[k], ma.y[k], m, ma.n[k], ks,
                                  gtile - ma.tile_begin[k], s, tile_cols, splits);
 }

@@ -3,6 +3,7 @@
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 
+#include "gemv_common.h"
 #include "teal_internal.h"
 
 namespace teal {
@@ -54,6 +55,16 @@ __global__ __launch_bounds__(kSparsifyWaves * 64) void sparsify_kernel(
     if (threadIdx.x == 0 && count) *count = base;
 }
 
+// h[i] = fp16(SiLU(gate[i]) * up[i]): the producer of W_down's input on its own
+// (Appendix A.3), in the arithmetic the fused kernel uses.
+__global__ __launch_bounds__(256) void swiglu_f16_kernel(const float *__restrict__ gate,
+                                                         const float *__restrict__ up,
+                                                         __half *__restrict__ h, int m)
+{
+    const int i = (int)(blockIdx.x * 256 + threadIdx.x);
+    if (i < m) h[i] = __float2half_rn(swiglu_value(gate[i], up[i]));
+}
+
 constexpr int kPackTile = 64;
 
 // 64 x 64 tile transpose through LDS: reads run along m (contiguous in W),
@@ -85,6 +96,15 @@ hipError_t launch_sparsify(const void *x_f16, int m, float t, uint8_t *mask, int
 {
     hipLaunchKernelGGL(sparsify_kernel, dim3(1), dim3(kSparsifyWaves * 64), 0, stream,
                        static_cast<const __half *>(x_f16), m, t, mask, idx, count);
+    return hipGetLastError();
+}
+
+hipError_t launch_swiglu_f16(const float *gate, const float *up, void *h_f16, int m,
+                             hipStream_t stream)
+{
+    if (m == 0) return hipSuccess;
+    hipLaunchKernelGGL(swiglu_f16_kernel, dim3((unsigned)((m + 255) / 256)), dim3(256), 0, stream,
+                       gate, up, static_cast<__half *>(h_f16), m);
     return hipGetLastError();
 }
 

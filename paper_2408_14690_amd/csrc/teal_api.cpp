@@ -197,6 +197,29 @@ teal_status teal_sparse_gemv_bf16(const void *Wt_bf16, const void *x_f16, float 
                                     stream, 0, 0, 0, 0, 0);
 }
 
+teal_status teal_swiglu_f16(const float *gate, const float *up, void *h_f16, int m, void *stream)
+{
+    if (m < 0 || m > teal::kMaxDim) return TEAL_ERR_SHAPE;
+    if ((!gate || !up || !h_f16) && m > 0) return TEAL_ERR_NULL;
+    if (!aligned(gate, 4) || !aligned(up, 4) || !aligned(h_f16, 2)) return TEAL_ERR_ALIGN;
+    return from_hip(teal::launch_swiglu_f16(gate, up, h_f16, m, static_cast<hipStream_t>(stream)));
+}
+
+teal_status teal_sparse_gemv_bf16_swiglu(const void *Wt_bf16, const float *gate, const float *up,
+                                         float t, float *y, int m, int n, void *workspace,
+                                         size_t workspace_bytes, void *stream)
+{
+    if (!up) return TEAL_ERR_NULL;
+    const GemvArgs a{Wt_bf16, gate, t, y, m, n, workspace, workspace_bytes};
+    const teal_status st = check_gemv(a, 8);
+    if (st != TEAL_OK) return st;
+    if (!aligned(gate, 4) || !aligned(up, 4)) return TEAL_ERR_ALIGN;
+    const GemvShape sh = auto_shape(m, n, 8, 16, 64, 64);
+    return from_hip(teal::launch_gemv_bf16_swiglu(Wt_bf16, gate, up, t, y, m, n,
+                                                  ws_partials(workspace), ws_counters(workspace),
+                                                  sh, static_cast<hipStream_t>(stream)));
+}
+
 teal_status teal_sparse_gemv_bf16_multi(int count, const void *const *Wt_bf16, const float *t,
                                         float *const *y, const int *n, const void *x_f16, int m,
                                         void *workspace, size_t workspace_bytes, void *stream)

@@ -37,6 +37,13 @@ hipError_t launch_gemv_bf16(const void *Wt, const void *x_f16, float t, float *y
                             int m, int n, float *partial, int *counters,
                             const GemvShape &shape, hipStream_t stream);
 
+hipError_t launch_gemv_bf16_swiglu(const void *Wt, const float *gate, const float *up, float t,
+                                   float *y, int m, int n, float *partial, int *counters,
+                                   const GemvShape &shape, hipStream_t stream);
+
+hipError_t launch_swiglu_f16(const float *gate, const float *up, void *h_f16, int m,
+                             hipStream_t stream);
+
 hipError_t launch_gemv_bf16_multi(int count, const void *const *Wt, const float *t,
                                   float *const *y, const int *n, const void *x_f16, int m,
                                   float *partial, int *counters, const GemvShape &shape,

@@ -186,6 +186,33 @@ def test_w4_multi_argument_errors():
     assert T.teal_sparse_gemv_w4_multi([], [], 128, [], [], [], X, 4096, WS, BIG, 0) == T.TEAL_ERR_UNSUPPORTED
 
 
+def test_swiglu_argument_errors():
+    G, U, H = 0x70000, 0x80000, 0x90000
+    assert T.teal_swiglu_f16(None, U, H, 16, stream=0) == T.TEAL_ERR_NULL
+    assert T.teal_swiglu_f16(G, None, H, 16, stream=0) == T.TEAL_ERR_NULL
+    assert T.teal_swiglu_f16(G, U, None, 16, stream=0) == T.TEAL_ERR_NULL
+    assert T.teal_swiglu_f16(G, U, H, -1, stream=0) == T.TEAL_ERR_SHAPE
+    assert T.teal_swiglu_f16(G + 2, U, H, 16, stream=0) == T.TEAL_ERR_ALIGN
+    assert T.teal_swiglu_f16(G, U, H + 1, 16, stream=0) == T.TEAL_ERR_ALIGN
+    assert T.teal_swiglu_f16(None, None, None, 0, stream=0) == T.TEAL_OK
+    ok = dict(Wt_bf16=W, gate=G, up=U, t=0.5, y=Y, m=14336, n=4096, workspace=WS,
+              workspace_bytes=BIG, stream=0)
+
+    def call(**kw):
+        a = dict(ok)
+        a.update(kw)
+        return T.teal_sparse_gemv_bf16_swiglu(**a)
+
+    assert call(gate=None) == T.TEAL_ERR_NULL
+    assert call(up=None) == T.TEAL_ERR_NULL
+    assert call(Wt_bf16=None) == T.TEAL_ERR_NULL
+    assert call(n=4100) == T.TEAL_ERR_SHAPE
+    assert call(gate=G + 2) == T.TEAL_ERR_ALIGN
+    assert call(up=U + 1) == T.TEAL_ERR_ALIGN
+    assert call(t=-1.0) == T.TEAL_ERR_THRESHOLD
+    assert call(workspace_bytes=16) == T.TEAL_ERR_WORKSPACE
+
+
 def test_plan_is_reported():
     st, plan = T.teal_gemv_plan(16, 4096, 14336)
     assert st == T.TEAL_OK
