@@ -70,11 +70,15 @@ __device__ __forceinline__ int wave_inclusive_scan(int v)
     return v;
 }
 
-// Where a block's activations come from.  A source returns channel i as an fp32
-// value that is exactly an fp16 value.
+// Where a block's activations come from.  A source loads what it needs for
+// channel i (load) and turns it into an fp32 value that is exactly an fp16 value
+// (value); kHeavy says that value() is worth skipping for segments past the slice.
 struct HalfSource {                   // the hidden state itself, fp16 in memory
+    static constexpr bool kHeavy = false;
+    typedef __half Raw;
     const __half *x;
-    __device__ __forceinline__ float operator()(int i) const { return __half2float(x[i]); }
+    __device__ __forceinline__ Raw load(int i) const { return x[i]; }
+    __device__ __forceinline__ float value(Raw r) const { return __half2float(r); }
 };
 
 // SiLU(g) * u rounded to fp16 (Appendix A.3: the input of W_down), in stated
@@ -112,12 +116,12 @@ __device__ __forceinline__ float swiglu_value(float g, float u)
 }
 
 struct SwigluSource {                 // gate = x W_gate^T and up = x W_up^T, fp32 in memory
+    static constexpr bool kHeavy = true;
+    typedef float2 Raw;
     const float *gate;
     const float *up;
-    __device__ __forceinline__ float operator()(int i) const
-    {
-        return swiglu_value(gate[i], up[i]);
-    }
+    __device__ __forceinline__ Raw load(int i) const { return make_float2(gate[i], up[i]); }
+    __device__ __forceinline__ float value(Raw r) const { return swiglu_value(r.x, r.y); }
 };
 
 // Definition 1 on one element: fp16 -> fp32 is exact, the compare is fp32.
@@ -146,10 +150,16 @@ __device__ __forceinline__ int compact_slice(const XS &x, float t, int k0,
     unsigned long long bal[PER_WAVE];
     // Unconditional loads from a clamped position (k1 > k0), the out-of-range lanes zeroed
     // afterwards: a load inside a branch is waited for before the next one is issued.
+    typename XS::Raw raw[PER_WAVE];
+#pragma unroll
+    for (int j = 0; j < PER_WAVE; ++j)
+        raw[j] = x.load(min(k0 + (w + j * WAVES) * 64 + lane, k1 - 1));
+    const int w_uniform = __builtin_amdgcn_readfirstlane(w);
 #pragma unroll
     for (int j = 0; j < PER_WAVE; ++j) {
         const int i = k0 + (w + j * WAVES) * 64 + lane;
-        const float v = x(min(i, k1 - 1));
+        float v = 0.f;
+        if (!XS::kHeavy || w_uniform + j * WAVES < nseg) v = x.value(raw[j]);   // wavefront-uniform
         xv[j] = i < k1 ? v : 0.f;                     // x = 0 never survives (t >= 0)
     }
 #pragma unroll
