@@ -152,12 +152,20 @@ class FusedGroup:
         self.m = members[0].m
         self.ns = [P.n for P in members]
         self.ys = [P.yp for P in members]
-        self.ws = torch.zeros(T.teal_workspace_bytes(self.m, sum(self.ns)), dtype=torch.uint8,
-                              device="cuda")
+        self.batch = members[0].batch
+        nbytes = (T.teal_workspace_bytes_batch(self.m, sum(self.ns), self.batch) if self.batch
+                  else T.teal_workspace_bytes(self.m, sum(self.ns)))
+        self.ws = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
         self.wsp, self.ws_bytes = self.ws.data_ptr(), self.ws.numel()
         self.stream = members[0].stream
 
     def launch(self, T, copy: int, p: float) -> int:
+        if self.batch:
+            wts = [P.wp[copy % len(P.wp)][0] for P in self.members]
+            return T.teal_sparse_gemv_bf16_batch_multi(wts, [P.t[p] for P in self.members],
+                                                       self.ys, self.ns, self.members[0].xp,
+                                                       self.batch, self.m, self.wsp,
+                                                       self.ws_bytes, self.stream)
         if self.members[0].fmt == "w4":
             ws = [P.wp[copy % len(P.wp)] for P in self.members]
             return T.teal_sparse_gemv_w4_multi([w[0] for w in ws], [w[1] for w in ws], 128,
@@ -177,7 +185,8 @@ class FusedGroup:
 
     def bytes(self, p: float) -> int:
         # x is read once for the group
-        return sum(P.bytes(p) for P in self.members) - 2 * self.m * (len(self.members) - 1)
+        return (sum(P.bytes(p) for P in self.members)
+                - 2 * self.m * max(self.batch, 1) * (len(self.members) - 1))
 
 
 def fuse(T, torch, stack):
@@ -556,10 +565,7 @@ def main() -> int:
         sparsities.append(0.0)
     head = sparsities[0]
     fmt = args.format
-    fused = not args.batch and not args.unfused
-    if args.fused and not fused:
-        print("bench.py: fused launches exist at batch 1 only", file=sys.stderr)
-        return 2
+    fused = not args.unfused
     shapes = ti.LAYER_SHAPES[args.workload]
     block_bytes = sum(n * m * BITS[fmt] // 8 for n, m in shapes.values())
     if args.layers > 1:
@@ -572,7 +578,7 @@ def main() -> int:
     projections = build_stack(T, torch, args.workload, fmt, sparsities, args.layers, copies,
                               args.batch)
     block0 = projections[:7]
-    groups = fuse(T, torch, projections) if not args.batch else None
+    groups = fuse(T, torch, projections)
     stack = groups if fused else projections
     launches_per_step = len(stack)
 
@@ -641,8 +647,10 @@ def main() -> int:
 
     multi_kernel = {"bf16": "sparse_gemv_multi_kernel<FmtBF16>", "w8": "sparse_gemv_multi_kernel<FmtW8>",
                     "w4": "sparse_gemv_w4_multi_kernel"}[fmt]
-    kernel = (multi_kernel if fused
-              else "sparse_gemv_batch_kernel" if args.batch else KERNEL[fmt])
+    if args.batch:
+        kernel = "sparse_gemv_batch_multi_kernel" if fused else "sparse_gemv_batch_kernel"
+    else:
+        kernel = multi_kernel if fused else KERNEL[fmt]
     out = {
         "metric": f"sparse GEMV effective HBM GB/s at {pct(head)} sparsity (one decoder-block "
                   f"pass); us and speedup vs dense per sparsity in detail",

@@ -277,6 +277,12 @@ teal_status teal_histogram_thresholds(const uint64_t *hist, const double *p, int
  * lanes_per_row * B <= 256, B = batch rounded up to 2, 4 or 8; tile_cols a
  * multiple of 8, at most 8 * lanes_per_row; splits such that a block's slice,
  * ceil(m / splits) rounded up to 64, is at most 2048 channels.
+ *
+ * teal_sparse_gemv_bf16_batch_multi: count (1..4) matrices that read the same
+ * batch, one kernel launch, each matrix with its own threshold; Wt_bf16, t, Y, n
+ * are HOST arrays of length count as for teal_sparse_gemv_bf16_multi (Y_k is
+ * [batch][n_k]).  workspace of at least
+ * teal_workspace_bytes_batch(m, n_0 + ... + n_{count-1}, batch).
  */
 #define TEAL_MAX_BATCH 8
 size_t teal_workspace_bytes_batch(int m, int n, int batch);
@@ -289,6 +295,11 @@ teal_status teal_sparse_gemv_bf16_batch_ex(const void *Wt_bf16, const void *X_f1
                                            float t, float *Y, int m, int n,
                                            void *workspace, size_t workspace_bytes, void *stream,
                                            int lanes_per_row, int tile_cols, int splits);
+teal_status teal_sparse_gemv_bf16_batch_multi(int count, const void *const *Wt_bf16,
+                                              const float *t, float *const *Y, const int *n,
+                                              const void *X_f16, int batch, int m,
+                                              void *workspace, size_t workspace_bytes,
+                                              void *stream);
 
 /*
  * The launch shape the library chooses for teal_sparse_gemv_{bf16,w8,w4} at

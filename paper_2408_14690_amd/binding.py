@@ -29,7 +29,7 @@ EXPORTS = (
     "teal_abs_histogram", "teal_histogram_thresholds", "teal_workspace_bytes_batch",
     "teal_sparsify_batch", "teal_sparse_gemv_bf16_batch", "teal_sparse_gemv_bf16_batch_ex",
     "teal_sparse_gemv_w8_multi", "teal_sparse_gemv_w4_multi",
-    "teal_swiglu_f16", "teal_sparse_gemv_bf16_swiglu",
+    "teal_swiglu_f16", "teal_sparse_gemv_bf16_swiglu", "teal_sparse_gemv_bf16_batch_multi",
 )
 TEAL_HIST_BINS = 32768
 TEAL_MAX_BATCH = 8
@@ -83,6 +83,9 @@ def load_library():
     lib.teal_sparse_gemv_w4_multi.restype = i
     lib.teal_sparse_gemv_w4_multi.argtypes = [i, c.POINTER(vp), c.POINTER(vp), i, c.POINTER(f),
                                               c.POINTER(vp), c.POINTER(i), vp, i, vp, sz, vp]
+    lib.teal_sparse_gemv_bf16_batch_multi.restype = i
+    lib.teal_sparse_gemv_bf16_batch_multi.argtypes = [i, c.POINTER(vp), c.POINTER(f), c.POINTER(vp),
+                                                      c.POINTER(i), vp, i, i, vp, sz, vp]
     lib.teal_swiglu_f16.restype = i
     lib.teal_swiglu_f16.argtypes = [vp, vp, vp, i, vp]
     lib.teal_sparse_gemv_bf16_swiglu.restype = i
@@ -270,6 +273,21 @@ def teal_sparse_gemv_w4_multi(Wq_list, scale_list, group, t_list, y_list, n_list
     N = (ctypes.c_int * count)(*[int(n) for n in n_list])
     return load_library().teal_sparse_gemv_w4_multi(
         count, W, S, int(group), Tt, Y, N, _ptr(x_f16), int(m), _ptr(workspace),
+        _nbytes(workspace, workspace_bytes), _stream(stream))
+
+
+def teal_sparse_gemv_bf16_batch_multi(Wt_list, t_list, Y_list, n_list, X_f16, batch, m, workspace,
+                                      workspace_bytes=None, stream=None) -> int:
+    """count = len(Wt_list) matrices sharing the batch X; per-matrix lists become host arrays."""
+    count = len(Wt_list)
+    if not (len(t_list) == len(Y_list) == len(n_list) == count):
+        raise ValueError("per-matrix lists must have the same length")
+    W = (ctypes.c_void_p * count)(*[_ptr(w) for w in Wt_list])
+    Y = (ctypes.c_void_p * count)(*[_ptr(y) for y in Y_list])
+    Tt = (ctypes.c_float * count)(*[float(t) for t in t_list])
+    N = (ctypes.c_int * count)(*[int(n) for n in n_list])
+    return load_library().teal_sparse_gemv_bf16_batch_multi(
+        count, W, Tt, Y, N, _ptr(X_f16), int(batch), int(m), _ptr(workspace),
         _nbytes(workspace, workspace_bytes), _stream(stream))
 
 

@@ -299,11 +299,12 @@ __device__ __forceinline__ void block_finish_batch(const BatchAcc<NB> &acc, floa
     if (threadIdx.x == 0) atomicExch(&counters[tile], 0);
 }
 
+// Work of one block: output tile `tile` x K-slice `s` of one matrix, all batch rows.
 template <int NB, int LPR, int WAVES, int U>
-__global__ __launch_bounds__(WAVES * 64) void sparse_gemv_batch_kernel(
-    const void *__restrict__ W, const __half *__restrict__ X, int batch, double bound,
-    float *partial, int *counters, float *Y, int m, int n, int ks, int tiles, int tile_cols,
-    int splits)
+__device__ __forceinline__ void batch_block(const void *__restrict__ W,
+                                            const __half *__restrict__ X, int batch, double bound,
+                                            float *partial, int *counters, float *Y, int m, int n,
+                                            int ks, int tile, int s, int tile_cols, int splits)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     // [list_x: (ks + 1) x NB floats][list_idx: ks ints]; red[] reuses the front.
@@ -312,8 +313,6 @@ __global__ __launch_bounds__(WAVES * 64) void sparse_gemv_batch_kernel(
     float *red = reinterpret_cast<float *>(smem);
     __shared__ int seg_cnt[kMaxSliceBatch / 64];
 
-    const int tile = blockIdx.x % tiles;
-    const int s = blockIdx.x / tiles;
     const int k0 = s * ks;
     const int k1 = min(m, k0 + ks);
     if (threadIdx.x < NB) list_x[ks * NB + threadIdx.x] = 0.f;    // the all-zero entry
@@ -335,6 +334,50 @@ __global__ __launch_bounds__(WAVES * 64) void sparse_gemv_batch_kernel(
     stream_rows_batch<NB, LPR, U>(acc, list_idx, list_x, ks, start, mine, lane_base, row_bytes);
     block_finish_batch<NB, LPR, WAVES>(acc, red, partial, counters, Y, tile, col0, tile_cols, s,
                                        splits, n, batch);
+}
+
+template <int NB, int LPR, int WAVES, int U>
+__global__ __launch_bounds__(WAVES * 64) void sparse_gemv_batch_kernel(
+    const void *__restrict__ W, const __half *__restrict__ X, int batch, double bound,
+    float *partial, int *counters, float *Y, int m, int n, int ks, int tiles, int tile_cols,
+    int splits)
+{
+    batch_block<NB, LPR, WAVES, U>(W, X, batch, bound, partial, counters, Y, m, n, ks,
+                                   blockIdx.x % tiles, blockIdx.x / tiles, tile_cols, splits);
+}
+
+// Several matrices that read the same batch of hidden states (q/k/v, gate/up:
+// Appendix A.3), each with its own threshold, in one launch; the block finds its
+// matrix from its tile index as in sparse_gemv_multi_kernel.
+struct BatchMultiArgs {
+    const void *W[kMaxMulti];
+    float *Y[kMaxMulti];
+    double bound[kMaxMulti];          // batch * t_k
+    int n[kMaxMulti];
+    int tile_begin[kMaxMulti + 1];
+    int count;
+};
+
+template <int NB, int LPR, int WAVES, int U>
+__global__ __launch_bounds__(WAVES * 64) void sparse_gemv_batch_multi_kernel(
+    BatchMultiArgs ma, const __half *__restrict__ X, int batch, float *partial, int *counters,
+    int m, int ks, int tile_cols, int splits)
+{
+    const int tiles = ma.tile_begin[ma.count];
+    const int gtile = blockIdx.x % tiles;
+    const int s = blockIdx.x / tiles;
+    int k = 0;
+    size_t partial_off = 0;            // each matrix owns splits * batch * n floats of partial rows
+#pragma unroll
+    for (int j = 1; j < kMaxMulti; ++j) {
+        if (j < ma.count && gtile >= ma.tile_begin[j]) {
+            partial_off += (size_t)splits * batch * ma.n[j - 1];
+            k = j;
+        }
+    }
+    batch_block<NB, LPR, WAVES, U>(ma.W[k], X, batch, ma.bound[k], partial + partial_off,
+                                   counters + ma.tile_begin[k], ma.Y[k], m, ma.n[k], ks,
+                                   gtile - ma.tile_begin[k], s, tile_cols, splits);
 }
 
 constexpr int kBatchWaves = 8;
@@ -425,6 +468,52 @@ hipError_t launch_gemv_bf16_batch(const void *Wt, const void *X_f16, int batch, 
         else TEAL_LAUNCH_B(8, 16);
     }
 #undef TEAL_LAUNCH_B
+    return hipGetLastError();
+}
+
+hipError_t launch_gemv_bf16_batch_multi(int count, const void *const *Wt, const float *t,
+                                        float *const *Y, const int *n, const void *X_f16,
+                                        int batch, int m, float *partial, int *counters,
+                                        const GemvShape &sh, hipStream_t stream)
+{
+    int n_max = 0;
+    for (int k = 0; k < count; ++k) n_max = n[k] > n_max ? n[k] : n_max;
+    const GemvGeometry g = gemv_geometry(m, n_max, sh, 8, 64);
+    if (g.ks > kMaxSliceBatch || !gemv_batch_shape_supported(batch, sh)) return hipErrorInvalidValue;
+    const int nb = batch <= 2 ? 2 : batch <= 4 ? 4 : 8;
+    const size_t list_bytes = (size_t)(g.ks + 1) * nb * sizeof(float) + (size_t)g.ks * sizeof(int);
+    const size_t red_bytes = (size_t)kBatchWaves * 64 * nb * 8 * sizeof(float);
+    const size_t lds = list_bytes > red_bytes ? list_bytes : red_bytes;
+    BatchMultiArgs ma{};
+    ma.count = count;
+    ma.tile_begin[0] = 0;
+    for (int k = 0; k < count; ++k) {
+        ma.W[k] = Wt[k];
+        ma.Y[k] = Y[k];
+        ma.bound[k] = (double)batch * (double)t[k];
+        ma.n[k] = n[k];
+        ma.tile_begin[k + 1] = ma.tile_begin[k] + (n[k] + g.tile_cols - 1) / g.tile_cols;
+    }
+    const int tiles = ma.tile_begin[count];
+    const __half *X = static_cast<const __half *>(X_f16);
+#define TEAL_LAUNCH_BM(NB, LPR)                                                                  \
+    hipLaunchKernelGGL((sparse_gemv_batch_multi_kernel<NB, LPR, kBatchWaves, kBatchUnroll>),     \
+                       dim3(tiles * g.splits), dim3(kBatchWaves * 64), lds, stream, ma, X,       \
+                       batch, partial, counters, m, g.ks, g.tile_cols, g.splits)
+    const int lpr = sh.lanes_per_row;
+    if (nb == 2) {
+        if (lpr == 64) TEAL_LAUNCH_BM(2, 64);
+        else if (lpr == 32) TEAL_LAUNCH_BM(2, 32);
+        else TEAL_LAUNCH_BM(2, 16);
+    } else if (nb == 4) {
+        if (lpr == 64) TEAL_LAUNCH_BM(4, 64);
+        else if (lpr == 32) TEAL_LAUNCH_BM(4, 32);
+        else TEAL_LAUNCH_BM(4, 16);
+    } else {
+        if (lpr == 32) TEAL_LAUNCH_BM(8, 32);
+        else TEAL_LAUNCH_BM(8, 16);
+    }
+#undef TEAL_LAUNCH_BM
     return hipGetLastError();
 }
 

@@ -197,6 +197,38 @@ teal_status teal_sparse_gemv_bf16(const void *Wt_bf16, const void *x_f16, float 
                                     stream, 0, 0, 0, 0, 0);
 }
 
+teal_status teal_sparse_gemv_bf16_batch_multi(int count, const void *const *Wt_bf16,
+                                              const float *t, float *const *Y, const int *n,
+                                              const void *X_f16, int batch, int m,
+                                              void *workspace, size_t workspace_bytes,
+                                              void *stream)
+{
+    if (count < 1 || count > teal::kMaxMatrices) return TEAL_ERR_UNSUPPORTED;
+    if (!Wt_bf16 || !t || !Y || !n || !X_f16 || !workspace) return TEAL_ERR_NULL;
+    if (batch < 1 || batch > teal::kMaxBatch) return TEAL_ERR_SHAPE;
+    long long n_total = 0;
+    for (int k = 0; k < count; ++k) {
+        if (!Wt_bf16[k] || !Y[k]) return TEAL_ERR_NULL;
+        if (n[k] < 8 || n[k] > teal::kMaxDim || n[k] % 8 != 0) return TEAL_ERR_SHAPE;
+        n_total += n[k];
+    }
+    if (m < 1 || m > teal::kMaxDim || n_total > teal::kMaxDim) return TEAL_ERR_SHAPE;
+    for (int k = 0; k < count; ++k)
+        if (!aligned(Wt_bf16[k], 16) || !aligned(Y[k], 4)) return TEAL_ERR_ALIGN;
+    if (!aligned(X_f16, 2) || !aligned(workspace, kAlignWorkspace)) return TEAL_ERR_ALIGN;
+    for (int k = 0; k < count; ++k)
+        if (!threshold_ok(t[k])) return TEAL_ERR_THRESHOLD;
+    if (workspace_bytes < teal_workspace_bytes_batch(m, (int)n_total, batch))
+        return TEAL_ERR_WORKSPACE;
+    const int max_lanes = batch_accumulators(batch) >= 4 ? 16 : 64;
+    const GemvShape sh = auto_shape(m, (int)n_total, 8, 16, max_lanes, 64, teal::kMaxSliceBatch);
+    if (!teal::gemv_batch_shape_supported(batch, sh)) return TEAL_ERR_UNSUPPORTED;
+    return from_hip(teal::launch_gemv_bf16_batch_multi(count, Wt_bf16, t, Y, n, X_f16, batch, m,
+                                                       ws_partials(workspace),
+                                                       ws_counters(workspace), sh,
+                                                       static_cast<hipStream_t>(stream)));
+}
+
 teal_status teal_swiglu_f16(const float *gate, const float *up, void *h_f16, int m, void *stream)
 {
     if (m < 0 || m > teal::kMaxDim) return TEAL_ERR_SHAPE;

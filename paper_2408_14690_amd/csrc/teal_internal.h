@@ -57,6 +57,11 @@ hipError_t launch_gemv_bf16_batch(const void *Wt, const void *X_f16, int batch, 
                                   int m, int n, float *partial, int *counters,
                                   const GemvShape &shape, hipStream_t stream);
 
+hipError_t launch_gemv_bf16_batch_multi(int count, const void *const *Wt, const float *t,
+                                        float *const *Y, const int *n, const void *X_f16,
+                                        int batch, int m, float *partial, int *counters,
+                                        const GemvShape &shape, hipStream_t stream);
+
 hipError_t launch_sparsify_batch(const void *X_f16, int batch, int m, float t, uint8_t *mask,
                                  int32_t *idx, int32_t *count, hipStream_t stream);
 

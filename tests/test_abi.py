@@ -296,6 +296,28 @@ def test_batch_argument_errors():
     assert T.teal_sparsify_batch(X, 2, 16, 0.5, None, None, None, stream=0) == T.TEAL_OK
 
 
+def test_batch_multi_argument_errors():
+    ok = dict(Wt_list=[W, W + 0x1000], t_list=[0.5, 0.25], Y_list=[Y, Y + 0x1000],
+              n_list=[4096, 1024], X_f16=X, batch=4, m=4096, workspace=WS, workspace_bytes=BIG,
+              stream=0)
+
+    def call(**kw):
+        a = dict(ok)
+        a.update(kw)
+        return T.teal_sparse_gemv_bf16_batch_multi(**a)
+
+    assert call(Wt_list=[W, None]) == T.TEAL_ERR_NULL
+    assert call(X_f16=None) == T.TEAL_ERR_NULL
+    assert call(batch=0) == T.TEAL_ERR_SHAPE
+    assert call(batch=9) == T.TEAL_ERR_SHAPE
+    assert call(n_list=[4096, 1020]) == T.TEAL_ERR_SHAPE
+    assert call(Wt_list=[W, W + 8]) == T.TEAL_ERR_ALIGN
+    assert call(t_list=[0.5, -1.0]) == T.TEAL_ERR_THRESHOLD
+    assert call(workspace_bytes=T.teal_workspace_bytes_batch(4096, 5120, 4) - 1) == T.TEAL_ERR_WORKSPACE
+    five = dict(Wt_list=[W] * 5, t_list=[0.5] * 5, Y_list=[Y] * 5, n_list=[64] * 5)
+    assert call(**five) == T.TEAL_ERR_UNSUPPORTED
+
+
 def test_check_raises_with_message():
     with pytest.raises(T.TealError) as e:
         T.check(T.TEAL_ERR_WORKSPACE)

@@ -161,3 +161,37 @@ def test_gemv_batch_full_size(T, batch, proj):
     mask, _, count = gpu_sparsify_batch(T, X, t)
     assert np.array_equal(mask, orc.sparsify_batch(X, t)[1])
     assert abs(count - m / 2) <= 2
+
+
+@pytest.mark.parametrize("name,ns,m,ps,batch", [
+    ("llama3 q,k,v", [4096, 1024, 1024], 4096, [0.5, 0.4, 0.25], 4),
+    ("llama3 gate,up", [14336, 14336], 4096, [0.4, 0.5], 8),
+    ("ragged", [520, 24, 136, 8], 333, [0.0, 0.5, 0.9, 1.0], 3),
+    ("single", [1032], 2049, [0.5], 2),
+    ("one row", [264, 72], 1000, [0.5, 0.5], 1),
+], ids=["qkv_b4", "gate_up_b8", "ragged_b3", "single_b2", "pair_b1"])
+def test_gemv_batch_multi(T, name, ns, m, ps, batch):
+    X = ti.make_X(batch, m, 900 + m + batch, "gaussian")
+    Xd = dev(X)
+    ws = torch.zeros(T.teal_workspace_bytes_batch(m, sum(ns), batch), dtype=torch.uint8, device="cuda")
+    ws_host, wts, ts, Ys = [], [], [], []
+    for k, (n, p) in enumerate(zip(ns, ps)):
+        w = ti.weights_bf16(n, m, seed=1000 * k + n + m)
+        ws_host.append(w)
+        wts.append(dev(ti.to_input_channel_major(w)))
+        ts.append(ti.batch_quantile_threshold(X, p))
+        Ys.append(torch.full((batch, n), float("nan"), dtype=torch.float32, device="cuda"))
+    T.check(T.teal_sparse_gemv_bf16_batch_multi(wts, ts, Ys, ns, Xd, batch, m, ws))
+    torch.cuda.synchronize()
+    for k, n in enumerate(ns):
+        got = Ys[k].cpu().numpy()
+        want = orc.sparse_gemv_bf16_batch(ws_host[k], X, ts[k])
+        assert not np.isnan(got).any()
+        for b in range(batch):
+            assert rel_l2(got[b], want[b]) <= TIGHT, (name, k, b)
+    # the shared workspace is left ready: a second call gives the same bits
+    Ys2 = [torch.full((batch, n), float("nan"), dtype=torch.float32, device="cuda") for n in ns]
+    T.check(T.teal_sparse_gemv_bf16_batch_multi(wts, ts, Ys2, ns, Xd, batch, m, ws))
+    torch.cuda.synchronize()
+    for a, b in zip(Ys, Ys2):
+        assert torch.equal(a, b)
