@@ -523,3 +523,41 @@ def test_calls_replay_from_a_hip_graph(T):
         enqueue(torch.cuda.current_stream())
         for a, b in zip(eager, snapshot()):
             assert torch.equal(a, b), replay
+
+
+# ---------------------------------------------------------------------------
+# seeded random shapes through the default launch of every format
+# ---------------------------------------------------------------------------
+
+def _random_cases(count, seed):
+    rng = np.random.Generator(np.random.PCG64(seed))
+    cases = []
+    for _ in range(count):
+        n = int(rng.integers(1, 70)) * 32                     # multiple of 32: valid for every format
+        m = int(rng.integers(1, 40)) * 128                    # multiple of 128: valid for int4 groups
+        if rng.random() < 0.5:
+            m += int(rng.integers(1, 128))                    # ragged for bf16 / int8
+        p = float(rng.choice([0.0, 0.1, 0.5, 0.77, 0.95, 1.0]))
+        dist = "laplace" if rng.random() < 0.5 else "gaussian"
+        cases.append((n, m, p, dist))
+    return cases
+
+
+@pytest.mark.parametrize("chunk", range(4))
+def test_random_shapes_every_format(T, chunk):
+    for n, m, p, dist in _random_cases(10, 1234 + chunk):
+        w = ti.weights_bf16(n, m, seed=n * 7 + m)
+        x = ti.make_x(m, n + m + 1, dist)
+        t = ti.quantile_threshold(x, p)
+        xd = dev(x)
+        ws = workspace(T, m, n)
+        tag = (n, m, p, dist)
+        got = run_bf16(T, dev(ti.to_input_channel_major(w)), xd, t, m, n, ws)
+        assert rel_l2(got, orc.sparse_gemv_bf16(w, x, t)) <= TIGHT, ("bf16",) + tag
+        q, scale = ti.quantize_w8(w)
+        got = run_w8(T, dev(q), dev(scale), xd, t, m, n, ws)
+        assert rel_l2(got, orc.sparse_gemv_w8(q, scale, x, t)) <= TIGHT, ("w8",) + tag
+        if m % 128 == 0:
+            q4, s4 = ti.quantize_w4(w, 128)
+            got = run_w4(T, dev(q4), dev(s4), xd, t, m, n, ws)
+            assert rel_l2(got, orc.sparse_gemv_w4(q4, s4, 128, x, t)) <= 1e-4, ("w4",) + tag
