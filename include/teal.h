@@ -311,6 +311,15 @@ teal_status teal_sparse_gemv_bf16_batch_multi(int count, const void *const *Wt_b
 teal_status teal_gemv_plan(int weight_bits, int m, int n, int *lanes_per_row, int *tile_cols,
                            int *splits, int *waves, int *unroll);
 
+/*
+ * The same for a grouped launch (teal_sparse_gemv_{bf16,w8,w4}_multi) of count
+ * matrices of widths n[0..count-1] (HOST array): the tile width is chosen so that
+ * the matrices divide evenly and the blocks fill the chip once.
+ */
+teal_status teal_gemv_plan_multi(int weight_bits, int m, const int *n, int count,
+                                 int *lanes_per_row, int *tile_cols, int *splits, int *waves,
+                                 int *unroll);
+
 #ifdef __cplusplus
 }
 #endif

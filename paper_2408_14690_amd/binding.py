@@ -30,6 +30,7 @@ EXPORTS = (
     "teal_sparsify_batch", "teal_sparse_gemv_bf16_batch", "teal_sparse_gemv_bf16_batch_ex",
     "teal_sparse_gemv_w8_multi", "teal_sparse_gemv_w4_multi",
     "teal_swiglu_f16", "teal_sparse_gemv_bf16_swiglu", "teal_sparse_gemv_bf16_batch_multi",
+    "teal_gemv_plan_multi",
 )
 TEAL_HIST_BINS = 32768
 TEAL_MAX_BATCH = 8
@@ -105,6 +106,8 @@ def load_library():
     ip = c.POINTER(c.c_int)
     lib.teal_gemv_plan.restype = i
     lib.teal_gemv_plan.argtypes = [i, i, i, ip, ip, ip, ip, ip]
+    lib.teal_gemv_plan_multi.restype = i
+    lib.teal_gemv_plan_multi.argtypes = [i, i, ip, i, ip, ip, ip, ip, ip]
     _lib = lib
     return lib
 
@@ -200,6 +203,17 @@ def teal_gemv_plan(weight_bits: int, m: int, n: int):
     vals = [ctypes.c_int(0) for _ in range(5)]
     st = load_library().teal_gemv_plan(int(weight_bits), int(m), int(n),
                                        *[ctypes.byref(v) for v in vals])
+    keys = ("lanes_per_row", "tile_cols", "splits", "waves", "unroll")
+    return st, {k: v.value for k, v in zip(keys, vals)}
+
+
+def teal_gemv_plan_multi(weight_bits: int, m: int, n_list):
+    """Returns (status, dict) for a grouped launch of len(n_list) matrices."""
+    count = len(n_list)
+    N = (ctypes.c_int * max(count, 1))(*[int(n) for n in n_list])
+    vals = [ctypes.c_int(0) for _ in range(5)]
+    st = load_library().teal_gemv_plan_multi(int(weight_bits), int(m), N, count,
+                                             *[ctypes.byref(v) for v in vals])
     keys = ("lanes_per_row", "tile_cols", "splits", "waves", "unroll")
     return st, {k: v.value for k, v in zip(keys, vals)}
 

@@ -66,6 +66,57 @@ GemvShape auto_shape(int m, int n, int elems_per_lane, int min_lanes, int max_la
     return sh;
 }
 
+// Launch shape for several matrices in one launch.  The tiles of the matrices lie side by
+// side and a tile never spans two matrices, so the tile count is the sum of the per-matrix
+// counts, and a width that divides the matrices unevenly leaves ragged tiles.  Every
+// candidate (tile width in steps of 128 bytes of a row, 1..16 splits) that fits one block
+// per compute unit is scored by how evenly it spreads the work: total work over 256 times
+// the largest block's work, with a small penalty per split beyond 8 (longer combine chain)
+// and a slight preference for wider row segments.  For one matrix this reproduces the
+// choices of auto_shape above.
+GemvShape auto_shape_multi(int m, const int *n, int count, int elems_per_lane, int min_lanes,
+                           int max_lanes, int ks_multiple, int max_slice = teal::kMaxSlice)
+{
+    long long n_total = 0;
+    for (int k = 0; k < count; ++k) n_total += n[k];
+    const int tc_min = min_lanes * elems_per_lane, tc_max = max_lanes * elems_per_lane;
+    const int unit = 8 * elems_per_lane;
+    double best = -1.0;
+    int best_tc = tc_min, best_splits = 1;
+    for (int tc = tc_min; tc <= tc_max; tc += unit) {
+        long long tiles = 0;
+        for (int k = 0; k < count; ++k) tiles += (n[k] + tc - 1) / tc;
+        for (int splits = 1; splits <= 16; ++splits) {
+            if (splits > 1 && splits > (m + 127) / 128) break;
+            int ks = (m + splits - 1) / splits;
+            ks = (ks + ks_multiple - 1) / ks_multiple * ks_multiple;
+            if (ks > max_slice) continue;
+            const int s = (m + ks - 1) / ks;
+            if (tiles * s > kComputeUnits) continue;
+            double score = (double)n_total * m / ((double)kComputeUnits * tc * ks);
+            for (int e = 8; e < s; ++e) score *= 0.97;
+            score *= 1.0 + 0.00002 * tc;
+            if (score > best) {
+                best = score;
+                best_tc = tc;
+                best_splits = s;
+            }
+        }
+    }
+    if (best < 0.0)                    // more tiles than compute units at every width
+        return auto_shape(m, (int)n_total, elems_per_lane, min_lanes, max_lanes, ks_multiple,
+                          max_slice);
+    GemvShape sh;
+    sh.splits = best_splits;
+    sh.tile_cols = best_tc;
+    int lanes = min_lanes;
+    while (lanes * elems_per_lane < best_tc) lanes *= 2;
+    sh.lanes_per_row = lanes;
+    sh.waves = 8;
+    sh.unroll = 4;
+    return sh;
+}
+
 // Partial rows a batched call may need: one per (split, batch row).
 int batch_split_rows(int m)
 {
@@ -189,6 +240,33 @@ teal_status teal_gemv_plan(int weight_bits, int m, int n, int *lanes_per_row, in
     return TEAL_OK;
 }
 
+teal_status teal_gemv_plan_multi(int weight_bits, int m, const int *n, int count,
+                                 int *lanes_per_row, int *tile_cols, int *splits, int *waves,
+                                 int *unroll)
+{
+    if (!n) return TEAL_ERR_NULL;
+    if (count < 1 || count > teal::kMaxMatrices) return TEAL_ERR_UNSUPPORTED;
+    long long n_total = 0;
+    for (int k = 0; k < count; ++k) {
+        if (n[k] < 1 || n[k] > teal::kMaxDim) return TEAL_ERR_SHAPE;
+        n_total += n[k];
+    }
+    if (m < 1 || m > teal::kMaxDim || n_total > teal::kMaxDim) return TEAL_ERR_SHAPE;
+    if (count == 1)
+        return teal_gemv_plan(weight_bits, m, n[0], lanes_per_row, tile_cols, splits, waves, unroll);
+    GemvShape sh;
+    if (weight_bits == 16) sh = auto_shape_multi(m, n, count, 8, 16, 64, 64);
+    else if (weight_bits == 8) sh = auto_shape_multi(m, n, count, 16, 8, 64, 64);
+    else if (weight_bits == 4) sh = auto_shape_multi(m, n, count, 32, 16, 32, 128);
+    else return TEAL_ERR_UNSUPPORTED;
+    if (lanes_per_row) *lanes_per_row = sh.lanes_per_row;
+    if (tile_cols) *tile_cols = sh.tile_cols;
+    if (splits) *splits = sh.splits;
+    if (waves) *waves = sh.waves;
+    if (unroll) *unroll = sh.unroll;
+    return TEAL_OK;
+}
+
 teal_status teal_sparse_gemv_bf16(const void *Wt_bf16, const void *x_f16, float t, float *y,
                                   int m, int n, void *workspace, size_t workspace_bytes,
                                   void *stream)
@@ -221,7 +299,9 @@ teal_status teal_sparse_gemv_bf16_batch_multi(int count, const void *const *Wt_b
     if (workspace_bytes < teal_workspace_bytes_batch(m, (int)n_total, batch))
         return TEAL_ERR_WORKSPACE;
     const int max_lanes = batch_accumulators(batch) >= 4 ? 16 : 64;
-    const GemvShape sh = auto_shape(m, (int)n_total, 8, 16, max_lanes, 64, teal::kMaxSliceBatch);
+    const GemvShape sh =
+        count > 1 ? auto_shape_multi(m, n, count, 8, 16, max_lanes, 64, teal::kMaxSliceBatch)
+                  : auto_shape(m, (int)n_total, 8, 16, max_lanes, 64, teal::kMaxSliceBatch);
     if (!teal::gemv_batch_shape_supported(batch, sh)) return TEAL_ERR_UNSUPPORTED;
     return from_hip(teal::launch_gemv_bf16_batch_multi(count, Wt_bf16, t, Y, n, X_f16, batch, m,
                                                        ws_partials(workspace),
@@ -272,7 +352,8 @@ teal_status teal_sparse_gemv_bf16_multi(int count, const void *const *Wt_bf16, c
         if (!threshold_ok(t[k])) return TEAL_ERR_THRESHOLD;
     if (workspace_bytes < teal_workspace_bytes(m, (int)n_total)) return TEAL_ERR_WORKSPACE;
     // Shape as for one matrix with all the output columns; a tile never spans two matrices.
-    const GemvShape sh = auto_shape(m, (int)n_total, 8, 16, 64, 64);
+    const GemvShape sh = count > 1 ? auto_shape_multi(m, n, count, 8, 16, 64, 64)
+                                   : auto_shape(m, (int)n_total, 8, 16, 64, 64);
     return from_hip(teal::launch_gemv_bf16_multi(count, Wt_bf16, t, y, n, x_f16, m,
                                                  ws_partials(workspace), ws_counters(workspace),
                                                  sh, static_cast<hipStream_t>(stream)));
@@ -377,7 +458,8 @@ teal_status teal_sparse_gemv_w8_multi(int count, const int8_t *const *Wq,
     for (int k = 0; k < count; ++k)
         if (!threshold_ok(t[k])) return TEAL_ERR_THRESHOLD;
     if (workspace_bytes < teal_workspace_bytes(m, (int)n_total)) return TEAL_ERR_WORKSPACE;
-    const GemvShape sh = auto_shape(m, (int)n_total, 16, 8, 64, 64);
+    const GemvShape sh = count > 1 ? auto_shape_multi(m, n, count, 16, 8, 64, 64)
+                                   : auto_shape(m, (int)n_total, 16, 8, 64, 64);
     return from_hip(teal::launch_gemv_w8_multi(count, Wq, scale_f16, t, y, n, x_f16, m,
                                                ws_partials(workspace), ws_counters(workspace), sh,
                                                static_cast<hipStream_t>(stream)));
@@ -421,7 +503,8 @@ teal_status teal_sparse_gemv_w4_multi(int count, const uint8_t *const *Wq,
         if (!threshold_ok(t[k])) return TEAL_ERR_THRESHOLD;
     if (group != 128 || m % 128 != 0) return TEAL_ERR_UNSUPPORTED;
     if (workspace_bytes < teal_workspace_bytes(m, (int)n_total)) return TEAL_ERR_WORKSPACE;
-    const GemvShape sh = auto_shape(m, (int)n_total, 32, 16, 32, 128);
+    const GemvShape sh = count > 1 ? auto_shape_multi(m, n, count, 32, 16, 32, 128)
+                                   : auto_shape(m, (int)n_total, 32, 16, 32, 128);
     return from_hip(teal::launch_gemv_w4_multi(count, Wq, scale_f16, t, y, n, x_f16, m,
                                                ws_partials(workspace), ws_counters(workspace), sh,
                                                static_cast<hipStream_t>(stream)));

@@ -220,6 +220,19 @@ def test_plan_is_reported():
     assert 1 <= plan["splits"] <= 16 and plan["waves"] in (4, 8, 16)
     assert T.teal_gemv_plan(12, 4096, 4096)[0] == T.TEAL_ERR_UNSUPPORTED
     assert T.teal_gemv_plan(16, 0, 4096)[0] == T.TEAL_ERR_SHAPE
+    # grouped launches: one matrix is the single plan; several fill the chip once
+    assert T.teal_gemv_plan_multi(16, 4096, [14336]) == T.teal_gemv_plan(16, 4096, 14336)
+    for bits, ns in ((16, [4096, 4096, 4096]), (16, [4096, 1024, 1024]), (8, [14336, 14336]),
+                     (4, [4096, 1024, 1024])):
+        st, pl = T.teal_gemv_plan_multi(bits, 4096, ns)
+        assert st == T.TEAL_OK
+        tiles = sum(-(-n // pl["tile_cols"]) for n in ns)
+        assert 128 <= tiles * pl["splits"] <= 256
+        assert pl["tile_cols"] <= pl["lanes_per_row"] * {16: 8, 8: 16, 4: 32}[bits]
+    assert T.teal_gemv_plan_multi(16, 4096, [])[0] == T.TEAL_ERR_UNSUPPORTED
+    assert T.teal_gemv_plan_multi(16, 4096, [64] * 5)[0] == T.TEAL_ERR_UNSUPPORTED
+    assert T.teal_gemv_plan_multi(12, 4096, [64, 64])[0] == T.TEAL_ERR_UNSUPPORTED
+    assert T.teal_gemv_plan_multi(16, 4096, [64, 0])[0] == T.TEAL_ERR_SHAPE
 
 
 def test_sparsify_and_pack_argument_errors():

@@ -318,7 +318,7 @@ def test_gemv_bf16_multi(T, name, ns, m, ps):
         ys.append(torch.full((n,), float("nan"), dtype=torch.float32, device="cuda"))
     T.check(T.teal_sparse_gemv_bf16_multi(wts, ts, ys, ns, xd, m, ws))
     torch.cuda.synchronize()
-    st, plan = T.teal_gemv_plan(16, m, sum(ns))
+    st, plan = T.teal_gemv_plan_multi(16, m, ns)
     assert st == 0
     for k, n in enumerate(ns):
         got = ys[k].cpu().numpy()
