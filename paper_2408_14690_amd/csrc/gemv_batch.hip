@@ -246,7 +246,7 @@ __device__ __forceinline__ void block_finish_batch(const BatchAcc<NB> &acc, floa
     if (splits == 1) {
         for (int k = threadIdx.x; k < total; k += THREADS) {
             const int bb = k / cols, c = k - bb * cols;
-            Y[(size_t)bb * n + col0 + c] = wave_sum(bb, c);
+            store_coherent(Y + (size_t)bb * n + col0 + c, wave_sum(bb, c));
         }
         return;
     }
@@ -293,7 +293,7 @@ __device__ __forceinline__ void block_finish_batch(const BatchAcc<NB> &acc, floa
         const int k = (int)threadIdx.x + o * THREADS;
         if (k < total) {
             const int bb = k / cols, c = k - bb * cols;
-            Y[(size_t)bb * n + col0 + c] = sum[o];
+            store_coherent(Y + (size_t)bb * n + col0 + c, sum[o]);
         }
     }
     if (threadIdx.x == 0) atomicExch(&counters[tile], 0);

@@ -30,7 +30,9 @@ __device__ __forceinline__ u32x4 load_stream16(const void *p)
 }
 
 // Device-scope coherent accesses for data that one block writes and a block on
-// another XCD reads within the same launch.
+// another XCD reads within the same launch.  The outputs are stored this way too
+// (write-through): lines left dirty in an L2 are written back at the end of the
+// kernel, which was measured to add 0.15-0.2 us to every call.
 __device__ __forceinline__ void store_coherent(float *p, float v)
 {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -299,7 +301,7 @@ __device__ __forceinline__ void block_finish(const float (&acc)[F::kElemsPerLane
             float sum = 0.f;
 #pragma unroll
             for (int ww = 0; ww < WAVES; ++ww) sum += red[ww * TN + c];
-            y[col0 + c] = F::finish(sum, a, col0 + c);
+            store_coherent(y + col0 + c, F::finish(sum, a, col0 + c));
         }
         return;
     }
@@ -353,10 +355,10 @@ __device__ __forceinline__ void block_finish(const float (&acc)[F::kElemsPerLane
                 float total = red[c];
 #pragma unroll
                 for (int qq = 1; qq < PARTS; ++qq) total += red[qq * TN + c];
-                y[col0 + c] = F::finish(total, a, col0 + c);
+                store_coherent(y + col0 + c, F::finish(total, a, col0 + c));
             }
         } else if (c < cols) {
-            y[col0 + c] = F::finish(sum, a, col0 + c);
+            store_coherent(y + col0 + c, F::finish(sum, a, col0 + c));
         }
     }
     // Leave the counter at zero for the next call on this workspace.
