@@ -215,7 +215,8 @@ teal_status teal_pack_bf16(const void *W_rowmajor, void *Wt, int m, int n,
  *   tile_cols      output columns per thread block: a multiple of 8, at most
  *                  8 * lanes_per_row.
  *   splits         1..128: thread blocks along the input dimension (split-K,
- *                  Section 4.4).
+ *                  Section 4.4).  A block takes at most 4096 input channels,
+ *                  so m above 128 * 4096 runs with ceil(m / 4096) splits.
  *   waves          4, 8 or 16 wavefronts per thread block.
  *   unroll         4 or 8 row loads per batch (two batches in flight per
  *                  wavefront); 4 with 16 wavefronts.

@@ -434,7 +434,7 @@ bool gemv_batch_shape_supported(int batch, const GemvShape &s)
     // a thread of the second pass owns at most 4 outputs: nb x (8 * lanes) <= 2048
     const bool fits = nb * s.lanes_per_row <= 256;
     return lpr && tc && fits && s.waves == kBatchWaves && s.unroll == kBatchUnroll &&
-           s.splits >= 1 && s.splits <= kMaxSplits;
+           s.splits >= 1;
 }
 
 hipError_t launch_gemv_bf16_batch(const void *Wt, const void *X_f16, int batch, float t, float *Y,

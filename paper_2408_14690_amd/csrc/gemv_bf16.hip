@@ -29,7 +29,7 @@ bool gemv_shape_supported(const GemvShape &s)
     const bool wv = s.waves == 4 || s.waves == 8 || s.waves == 16;
     const bool un = s.unroll == 4 || (s.unroll == 8 && s.waves != 16);
     const bool tc = s.tile_cols >= 0 && s.tile_cols % 8 == 0 && s.tile_cols <= s.lanes_per_row * 8;
-    return lpr && wv && un && tc && s.splits >= 1 && s.splits <= kMaxSplits;
+    return lpr && wv && un && tc && s.splits >= 1;
 }
 
 hipError_t launch_gemv_bf16(const void *Wt, const void *x_f16, float t, float *y, int m, int n,

@@ -218,6 +218,7 @@ teal_status teal_sparse_gemv_bf16_ex(const void *Wt_bf16, const void *x_f16, flo
     if (waves) sh.waves = waves;
     if (unroll) sh.unroll = unroll;
     if (!teal::gemv_shape_supported(sh)) return TEAL_ERR_UNSUPPORTED;
+    if (sh.splits > max_splits_for(m)) return TEAL_ERR_UNSUPPORTED;           // partial rows
     return from_hip(teal::launch_gemv_bf16(Wt_bf16, x_f16, t, y, m, n, ws_partials(workspace),
                                            ws_counters(workspace), sh,
                                            static_cast<hipStream_t>(stream)));

@@ -8,7 +8,7 @@
 
 namespace teal {
 
-constexpr int kMaxSplits = 128;     // upper bound on split-K blocks along the input dimension
+constexpr int kMaxSplits = 128;     // most split-K blocks a caller may ask for (longer inputs force more)
 constexpr int kMaxSlice = 4096;     // most input channels one block compacts (LDS list capacity)
 constexpr int kMaxDim = 1 << 24;    // largest m or n accepted
 constexpr int kMaxMatrices = 4;     // matrices per fused launch

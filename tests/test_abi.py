@@ -229,6 +229,12 @@ def test_plan_is_reported():
         tiles = sum(-(-n // pl["tile_cols"]) for n in ns)
         assert 128 <= tiles * pl["splits"] <= 256
         assert pl["tile_cols"] <= pl["lanes_per_row"] * {16: 8, 8: 16, 4: 32}[bits]
+    # inputs too long for 16 splits: as many as the 4096-channel slices need, and no
+    # more partial rows than the workspace holds
+    for m in (70000, 1 << 20):
+        st, pl = T.teal_gemv_plan_multi(16, m, [4096, 4096])
+        assert st == T.TEAL_OK and pl["splits"] >= -(-m // 4096)
+        assert (pl["splits"] * 8192 * 4 + (1 << 24) // 64 * 4) <= T.teal_workspace_bytes(m, 8192)
     assert T.teal_gemv_plan_multi(16, 4096, [])[0] == T.TEAL_ERR_UNSUPPORTED
     assert T.teal_gemv_plan_multi(16, 4096, [64] * 5)[0] == T.TEAL_ERR_UNSUPPORTED
     assert T.teal_gemv_plan_multi(12, 4096, [64, 64])[0] == T.TEAL_ERR_UNSUPPORTED

@@ -195,3 +195,26 @@ def test_gemv_batch_multi(T, name, ns, m, ps, batch):
     torch.cuda.synchronize()
     for a, b in zip(Ys, Ys2):
         assert torch.equal(a, b)
+
+
+def test_very_long_input(T):
+    """More than 128 x 2048 input channels: a block compacts at most 2048 channels of a
+    batch, so the call runs with more split-K blocks than the usual 16 partial rows."""
+    m, n, batch = 128 * 2048 + 704, 32, 3
+    w = ti.weights_bf16(n, m, seed=515151)
+    wt = dev(ti.to_input_channel_major(w))
+    X = ti.make_X(batch, m, 5151, "laplace")
+    t = ti.batch_quantile_threshold(X, 0.5)
+    want = orc.sparse_gemv_bf16_batch(w, X, t)
+    got = run_batch(T, wt, X, t, m, n)
+    for b in range(batch):
+        assert rel_l2(got[b], want[b]) <= TIGHT, b
+    ws = torch.zeros(T.teal_workspace_bytes_batch(m, 2 * n, batch), dtype=torch.uint8, device="cuda")
+    Ys = [torch.full((batch, n), float("nan"), dtype=torch.float32, device="cuda") for _ in range(2)]
+    t2 = ti.batch_quantile_threshold(X, 0.25)
+    T.check(T.teal_sparse_gemv_bf16_batch_multi([wt, wt], [t, t2], Ys, [n, n], dev(X), batch, m, ws))
+    torch.cuda.synchronize()
+    want2 = orc.sparse_gemv_bf16_batch(w, X, t2)
+    for b in range(batch):
+        assert rel_l2(Ys[0].cpu().numpy()[b], want[b]) <= TIGHT, b
+        assert rel_l2(Ys[1].cpu().numpy()[b], want2[b]) <= TIGHT, b

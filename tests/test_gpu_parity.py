@@ -460,6 +460,45 @@ def test_gemv_w4_multi(T, name, ns, m, ps):
         assert torch.equal(a, b)
 
 
+# An input longer than 128 x 4096 channels: a block compacts at most 4096 channels, so
+# the call runs with more split-K blocks than a caller may ask for, and the workspace
+# holds one partial row for each of them.
+LONG_M = 128 * 4096 + 640
+
+
+def test_very_long_input_every_format(T):
+    m, n = LONG_M, 32
+    w = ti.weights_bf16(n, m, seed=424242)
+    x = ti.laplace_x(m, 4242)
+    xd = dev(x)
+    t = ti.quantile_threshold(x, 0.5)
+    ws = workspace(T, m, 3 * n)
+    assert T.teal_workspace_bytes(m, n) >= (m + 4095) // 4096 * n * 4
+
+    want = orc.sparse_gemv_bf16(w, x, t)
+    wt = dev(ti.to_input_channel_major(w))
+    got = run_bf16(T, wt, xd, t, m, n, ws)
+    assert rel_l2(got, want) <= TIGHT
+    # asking for fewer splits than the length needs gives the same call
+    again = run_bf16(T, wt, xd, t, m, n, ws, splits=128)
+    assert np.array_equal(got, again)
+    ys = [torch.full((k,), float("nan"), dtype=torch.float32, device="cuda") for k in (n, n)]
+    t2 = ti.quantile_threshold(x, 0.9)
+    T.check(T.teal_sparse_gemv_bf16_multi([wt, wt], [t, t2], ys, [n, n], xd, m, ws))
+    torch.cuda.synchronize()
+    assert rel_l2(ys[0].cpu().numpy(), want) <= TIGHT
+    assert rel_l2(ys[1].cpu().numpy(), orc.sparse_gemv_bf16(w, x, t2)) <= TIGHT
+
+    q, scale = ti.quantize_w8(w)
+    got = run_w8(T, dev(q), dev(scale), xd, t, m, n, ws)
+    assert rel_l2(got, orc.sparse_gemv_w8(q, scale, x, t)) <= TIGHT
+
+    q4, scale4 = ti.quantize_w4(w)
+    got = run_w4(T, dev(q4), dev(scale4), xd, t, m, n, ws)
+    assert rel_l2(got, orc.sparse_gemv_w4(q4, scale4, 128, x, t)) <= TIGHT
+
+
+
 # ---------------------------------------------------------------------------
 # captured into a HIP graph
 # ---------------------------------------------------------------------------
