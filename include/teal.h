@@ -71,6 +71,22 @@ int teal_version(void);
 size_t teal_workspace_bytes(int m, int n);
 
 /*
+ * Realised sparsity of a call.  Section 4.2 fixes a target sparsity p per
+ * matrix and estimates its threshold offline, so the share of entries a call
+ * actually zeroes can drift from p with the inputs.  Every teal_sparse_gemv_*
+ * call (all formats, grouped, batched, fused producer) leaves the number of
+ * input channels that survived the threshold of its matrix k (k = 0 for calls
+ * with one matrix) as an int32 at byte offset teal_survivors_offset() + 4 * k
+ * of its workspace; realised sparsity = 1 - count / m.  The values are
+ * complete when the call has completed on its stream and stay until the next
+ * call on that workspace; the caller reads them as it reads any device memory.
+ * They cost no extra launch and no extra pass over x: the thread blocks of a
+ * matrix's first output tile report the counts of their slices, and the block
+ * that finishes that tile adds them.
+ */
+size_t teal_survivors_offset(void);
+
+/*
  * Definition 1 (Section 4.2) alone, as the mask s = [|x| > t] of Section 4.4.
  *   x_f16 [m] fp16 (2-byte aligned), 1 <= m < 2^31 (m = 0 is accepted: count = 0).
  *   mask  [m] bytes, 1 = kept, 0 = zeroed.                 May be NULL.

@@ -30,7 +30,7 @@ EXPORTS = (
     "teal_sparsify_batch", "teal_sparse_gemv_bf16_batch", "teal_sparse_gemv_bf16_batch_ex",
     "teal_sparse_gemv_w8_multi", "teal_sparse_gemv_w4_multi",
     "teal_swiglu_f16", "teal_sparse_gemv_bf16_swiglu", "teal_sparse_gemv_bf16_batch_multi",
-    "teal_gemv_plan_multi",
+    "teal_gemv_plan_multi", "teal_survivors_offset",
 )
 TEAL_HIST_BINS = 32768
 TEAL_MAX_BATCH = 8
@@ -63,6 +63,8 @@ def load_library():
     lib.teal_version.argtypes = []
     lib.teal_workspace_bytes.restype = sz
     lib.teal_workspace_bytes.argtypes = [i, i]
+    lib.teal_survivors_offset.restype = sz
+    lib.teal_survivors_offset.argtypes = []
     lib.teal_sparsify.restype = i
     lib.teal_sparsify.argtypes = [vp, i, f, vp, vp, vp, vp]
     lib.teal_sparse_gemv_bf16.restype = i
@@ -112,7 +114,9 @@ def load_library():
     return lib
 
 
-def _ptr(a):
+def _ptr(a, need=None, what="argument"):
+    """Device address of a tensor (or a raw address).  With `need`, a tensor smaller than
+    that many bytes is refused here: the C ABI sees plain pointers and cannot know."""
     if a is None:
         return None
     if isinstance(a, int):
@@ -120,6 +124,9 @@ def _ptr(a):
     if hasattr(a, "data_ptr"):
         if not a.is_contiguous():
             raise ValueError("tensor arguments must be contiguous")
+        if need is not None and a.numel() * a.element_size() < int(need):
+            raise ValueError(f"{what}: tensor of {a.numel() * a.element_size()} bytes, "
+                             f"the call reads or writes {int(need)}")
         return a.data_ptr()
     raise TypeError(f"cannot pass {type(a).__name__} as a device pointer")
 
@@ -158,15 +165,21 @@ def teal_workspace_bytes(m: int, n: int) -> int:
     return int(load_library().teal_workspace_bytes(int(m), int(n)))
 
 
+def teal_survivors_offset() -> int:
+    return int(load_library().teal_survivors_offset())
+
+
 def teal_sparsify(x_f16, m, t, mask=None, idx=None, count=None, stream=None) -> int:
-    return load_library().teal_sparsify(_ptr(x_f16), int(m), float(t), _ptr(mask), _ptr(idx),
-                                        _ptr(count), _stream(stream))
+    return load_library().teal_sparsify(_ptr(x_f16, 2 * m, "x"), int(m), float(t),
+                                        _ptr(mask, m, "mask"), _ptr(idx, 4 * m, "idx"),
+                                        _ptr(count, 4, "count"), _stream(stream))
 
 
 def teal_sparse_gemv_bf16(Wt_bf16, x_f16, t, y, m, n, workspace, workspace_bytes=None,
                           stream=None) -> int:
     return load_library().teal_sparse_gemv_bf16(
-        _ptr(Wt_bf16), _ptr(x_f16), float(t), _ptr(y), int(m), int(n), _ptr(workspace),
+        _ptr(Wt_bf16, 2 * m * n, "Wt"), _ptr(x_f16, 2 * m, "x"), float(t), _ptr(y, 4 * n, "y"),
+        int(m), int(n), _ptr(workspace),
         _nbytes(workspace, workspace_bytes), _stream(stream))
 
 
@@ -174,7 +187,8 @@ def teal_sparse_gemv_bf16_ex(Wt_bf16, x_f16, t, y, m, n, workspace, workspace_by
                              stream=None, lanes_per_row=0, tile_cols=0, splits=0, waves=0,
                              unroll=0) -> int:
     return load_library().teal_sparse_gemv_bf16_ex(
-        _ptr(Wt_bf16), _ptr(x_f16), float(t), _ptr(y), int(m), int(n), _ptr(workspace),
+        _ptr(Wt_bf16, 2 * m * n, "Wt"), _ptr(x_f16, 2 * m, "x"), float(t), _ptr(y, 4 * n, "y"),
+        int(m), int(n), _ptr(workspace),
         _nbytes(workspace, workspace_bytes), _stream(stream), int(lanes_per_row), int(tile_cols),
         int(splits), int(waves), int(unroll))
 
@@ -182,19 +196,22 @@ def teal_sparse_gemv_bf16_ex(Wt_bf16, x_f16, t, y, m, n, workspace, workspace_by
 def teal_sparse_gemv_w8(Wq, scale_f16, x_f16, t, y, m, n, workspace, workspace_bytes=None,
                         stream=None) -> int:
     return load_library().teal_sparse_gemv_w8(
-        _ptr(Wq), _ptr(scale_f16), _ptr(x_f16), float(t), _ptr(y), int(m), int(n),
-        _ptr(workspace), _nbytes(workspace, workspace_bytes), _stream(stream))
+        _ptr(Wq, m * n, "Wq"), _ptr(scale_f16, 2 * n, "scale"), _ptr(x_f16, 2 * m, "x"), float(t),
+        _ptr(y, 4 * n, "y"), int(m), int(n), _ptr(workspace),
+        _nbytes(workspace, workspace_bytes), _stream(stream))
 
 
 def teal_sparse_gemv_w4(Wq, scale_f16, group, x_f16, t, y, m, n, workspace,
                         workspace_bytes=None, stream=None) -> int:
     return load_library().teal_sparse_gemv_w4(
-        _ptr(Wq), _ptr(scale_f16), int(group), _ptr(x_f16), float(t), _ptr(y), int(m), int(n),
+        _ptr(Wq, m * n // 2, "Wq"), _ptr(scale_f16, 2 * n * (m // max(int(group), 1)), "scale"),
+        int(group), _ptr(x_f16, 2 * m, "x"), float(t), _ptr(y, 4 * n, "y"), int(m), int(n),
         _ptr(workspace), _nbytes(workspace, workspace_bytes), _stream(stream))
 
 
 def teal_pack_bf16(W_rowmajor, Wt, m, n, stream=None) -> int:
-    return load_library().teal_pack_bf16(_ptr(W_rowmajor), _ptr(Wt), int(m), int(n),
+    return load_library().teal_pack_bf16(_ptr(W_rowmajor, 2 * m * n, "W"), _ptr(Wt, 2 * m * n, "Wt"),
+                                         int(m), int(n),
                                          _stream(stream))
 
 
@@ -224,12 +241,12 @@ def teal_sparse_gemv_bf16_multi(Wt_list, t_list, y_list, n_list, x_f16, m, works
     count = len(Wt_list)
     if not (len(t_list) == len(y_list) == len(n_list) == count):
         raise ValueError("per-matrix lists must have the same length")
-    W = (ctypes.c_void_p * count)(*[_ptr(w) for w in Wt_list])
-    Y = (ctypes.c_void_p * count)(*[_ptr(y) for y in y_list])
+    W = (ctypes.c_void_p * count)(*[_ptr(w, 2 * m * n, "Wt") for w, n in zip(Wt_list, n_list)])
+    Y = (ctypes.c_void_p * count)(*[_ptr(y, 4 * n, "y") for y, n in zip(y_list, n_list)])
     Tt = (ctypes.c_float * count)(*[float(t) for t in t_list])
     N = (ctypes.c_int * count)(*[int(n) for n in n_list])
     return load_library().teal_sparse_gemv_bf16_multi(
-        count, W, Tt, Y, N, _ptr(x_f16), int(m), _ptr(workspace),
+        count, W, Tt, Y, N, _ptr(x_f16, 2 * m, "x"), int(m), _ptr(workspace),
         _nbytes(workspace, workspace_bytes), _stream(stream))
 
 
@@ -238,14 +255,17 @@ def teal_workspace_bytes_batch(m: int, n: int, batch: int) -> int:
 
 
 def teal_sparsify_batch(X_f16, batch, m, t, mask=None, idx=None, count=None, stream=None) -> int:
-    return load_library().teal_sparsify_batch(_ptr(X_f16), int(batch), int(m), float(t),
-                                              _ptr(mask), _ptr(idx), _ptr(count), _stream(stream))
+    return load_library().teal_sparsify_batch(_ptr(X_f16, 2 * batch * m, "X"), int(batch), int(m),
+                                              float(t), _ptr(mask, m, "mask"),
+                                              _ptr(idx, 4 * m, "idx"), _ptr(count, 4, "count"),
+                                              _stream(stream))
 
 
 def teal_sparse_gemv_bf16_batch(Wt_bf16, X_f16, batch, t, Y, m, n, workspace,
                                 workspace_bytes=None, stream=None) -> int:
     return load_library().teal_sparse_gemv_bf16_batch(
-        _ptr(Wt_bf16), _ptr(X_f16), int(batch), float(t), _ptr(Y), int(m), int(n),
+        _ptr(Wt_bf16, 2 * m * n, "Wt"), _ptr(X_f16, 2 * batch * m, "X"), int(batch), float(t),
+        _ptr(Y, 4 * batch * n, "Y"), int(m), int(n),
         _ptr(workspace), _nbytes(workspace, workspace_bytes), _stream(stream))
 
 
@@ -253,7 +273,8 @@ def teal_sparse_gemv_bf16_batch_ex(Wt_bf16, X_f16, batch, t, Y, m, n, workspace,
                                    workspace_bytes=None, stream=None, lanes_per_row=0,
                                    tile_cols=0, splits=0) -> int:
     return load_library().teal_sparse_gemv_bf16_batch_ex(
-        _ptr(Wt_bf16), _ptr(X_f16), int(batch), float(t), _ptr(Y), int(m), int(n),
+        _ptr(Wt_bf16, 2 * m * n, "Wt"), _ptr(X_f16, 2 * batch * m, "X"), int(batch), float(t),
+        _ptr(Y, 4 * batch * n, "Y"), int(m), int(n),
         _ptr(workspace), _nbytes(workspace, workspace_bytes), _stream(stream),
         int(lanes_per_row), int(tile_cols), int(splits))
 
@@ -264,13 +285,13 @@ def teal_sparse_gemv_w8_multi(Wq_list, scale_list, t_list, y_list, n_list, x_f16
     count = len(Wq_list)
     if not (len(scale_list) == len(t_list) == len(y_list) == len(n_list) == count):
         raise ValueError("per-matrix lists must have the same length")
-    W = (ctypes.c_void_p * count)(*[_ptr(w) for w in Wq_list])
-    S = (ctypes.c_void_p * count)(*[_ptr(sc) for sc in scale_list])
-    Y = (ctypes.c_void_p * count)(*[_ptr(y) for y in y_list])
+    W = (ctypes.c_void_p * count)(*[_ptr(w, m * n, "Wq") for w, n in zip(Wq_list, n_list)])
+    S = (ctypes.c_void_p * count)(*[_ptr(sc, 2 * n, "scale") for sc, n in zip(scale_list, n_list)])
+    Y = (ctypes.c_void_p * count)(*[_ptr(y, 4 * n, "y") for y, n in zip(y_list, n_list)])
     Tt = (ctypes.c_float * count)(*[float(t) for t in t_list])
     N = (ctypes.c_int * count)(*[int(n) for n in n_list])
     return load_library().teal_sparse_gemv_w8_multi(
-        count, W, S, Tt, Y, N, _ptr(x_f16), int(m), _ptr(workspace),
+        count, W, S, Tt, Y, N, _ptr(x_f16, 2 * m, "x"), int(m), _ptr(workspace),
         _nbytes(workspace, workspace_bytes), _stream(stream))
 
 
@@ -280,13 +301,15 @@ def teal_sparse_gemv_w4_multi(Wq_list, scale_list, group, t_list, y_list, n_list
     count = len(Wq_list)
     if not (len(scale_list) == len(t_list) == len(y_list) == len(n_list) == count):
         raise ValueError("per-matrix lists must have the same length")
-    W = (ctypes.c_void_p * count)(*[_ptr(w) for w in Wq_list])
-    S = (ctypes.c_void_p * count)(*[_ptr(sc) for sc in scale_list])
-    Y = (ctypes.c_void_p * count)(*[_ptr(y) for y in y_list])
+    groups = m // max(int(group), 1)
+    W = (ctypes.c_void_p * count)(*[_ptr(w, m * n // 2, "Wq") for w, n in zip(Wq_list, n_list)])
+    S = (ctypes.c_void_p * count)(*[_ptr(sc, 2 * n * groups, "scale")
+                                    for sc, n in zip(scale_list, n_list)])
+    Y = (ctypes.c_void_p * count)(*[_ptr(y, 4 * n, "y") for y, n in zip(y_list, n_list)])
     Tt = (ctypes.c_float * count)(*[float(t) for t in t_list])
     N = (ctypes.c_int * count)(*[int(n) for n in n_list])
     return load_library().teal_sparse_gemv_w4_multi(
-        count, W, S, int(group), Tt, Y, N, _ptr(x_f16), int(m), _ptr(workspace),
+        count, W, S, int(group), Tt, Y, N, _ptr(x_f16, 2 * m, "x"), int(m), _ptr(workspace),
         _nbytes(workspace, workspace_bytes), _stream(stream))
 
 
@@ -296,33 +319,38 @@ def teal_sparse_gemv_bf16_batch_multi(Wt_list, t_list, Y_list, n_list, X_f16, ba
     count = len(Wt_list)
     if not (len(t_list) == len(Y_list) == len(n_list) == count):
         raise ValueError("per-matrix lists must have the same length")
-    W = (ctypes.c_void_p * count)(*[_ptr(w) for w in Wt_list])
-    Y = (ctypes.c_void_p * count)(*[_ptr(y) for y in Y_list])
+    W = (ctypes.c_void_p * count)(*[_ptr(w, 2 * m * n, "Wt") for w, n in zip(Wt_list, n_list)])
+    Y = (ctypes.c_void_p * count)(*[_ptr(y, 4 * batch * n, "Y") for y, n in zip(Y_list, n_list)])
     Tt = (ctypes.c_float * count)(*[float(t) for t in t_list])
     N = (ctypes.c_int * count)(*[int(n) for n in n_list])
     return load_library().teal_sparse_gemv_bf16_batch_multi(
-        count, W, Tt, Y, N, _ptr(X_f16), int(batch), int(m), _ptr(workspace),
+        count, W, Tt, Y, N, _ptr(X_f16, 2 * batch * m, "X"), int(batch), int(m), _ptr(workspace),
         _nbytes(workspace, workspace_bytes), _stream(stream))
 
 
 def teal_swiglu_f16(gate, up, h_f16, m, stream=None) -> int:
-    return load_library().teal_swiglu_f16(_ptr(gate), _ptr(up), _ptr(h_f16), int(m),
+    return load_library().teal_swiglu_f16(_ptr(gate, 4 * m, "gate"), _ptr(up, 4 * m, "up"),
+                                          _ptr(h_f16, 2 * m, "h"), int(m),
                                           _stream(stream))
 
 
 def teal_sparse_gemv_bf16_swiglu(Wt_bf16, gate, up, t, y, m, n, workspace, workspace_bytes=None,
                                  stream=None) -> int:
     return load_library().teal_sparse_gemv_bf16_swiglu(
-        _ptr(Wt_bf16), _ptr(gate), _ptr(up), float(t), _ptr(y), int(m), int(n), _ptr(workspace),
+        _ptr(Wt_bf16, 2 * m * n, "Wt"), _ptr(gate, 4 * m, "gate"), _ptr(up, 4 * m, "up"), float(t),
+        _ptr(y, 4 * n, "y"), int(m), int(n), _ptr(workspace),
         _nbytes(workspace, workspace_bytes), _stream(stream))
 
 
 def teal_abs_histogram(x_f16, count, hist, stream=None) -> int:
-    return load_library().teal_abs_histogram(_ptr(x_f16), int(count), _ptr(hist), _stream(stream))
+    return load_library().teal_abs_histogram(_ptr(x_f16, 2 * count, "x"), int(count),
+                                             _ptr(hist, 8 * TEAL_HIST_BINS, "hist"),
+                                             _stream(stream))
 
 
 def teal_histogram_thresholds(hist, p_list, t, stream=None) -> int:
     """p_list: host levels in [0, 1]; t: device float32 array of the same length."""
     np_ = len(p_list)
     P = (ctypes.c_double * max(np_, 1))(*[float(p) for p in p_list])
-    return load_library().teal_histogram_thresholds(_ptr(hist), P, np_, _ptr(t), _stream(stream))
+    return load_library().teal_histogram_thresholds(_ptr(hist, 8 * TEAL_HIST_BINS, "hist"), P, np_,
+                                                    _ptr(t, 4 * np_, "t"), _stream(stream))

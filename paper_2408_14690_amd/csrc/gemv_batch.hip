@@ -223,7 +223,8 @@ template <int NB, int LPR, int WAVES>
 __device__ __forceinline__ void block_finish_batch(const BatchAcc<NB> &acc, float *red,
                                                    float *partial, int *counters, float *Y,
                                                    int tile, int col0, int cols, int s, int splits,
-                                                   int n, int batch)
+                                                   int n, int batch, int cnt,
+                                                   const SurvivorReport &report)
 {
     constexpr int TN = LPR * 8;
     constexpr int THREADS = WAVES * 64;
@@ -243,6 +244,7 @@ __device__ __forceinline__ void block_finish_batch(const BatchAcc<NB> &acc, floa
         for (int q = 0; q < WAVES * R; ++q) sum += red[(q * NB + bb) * TN + c];
         return sum;
     };
+    if (tile == 0 && threadIdx.x == 0) report_slice(report, s, splits, cnt);
     if (splits == 1) {
         for (int k = threadIdx.x; k < total; k += THREADS) {
             const int bb = k / cols, c = k - bb * cols;
@@ -259,6 +261,7 @@ __device__ __forceinline__ void block_finish_batch(const BatchAcc<NB> &acc, floa
     if (threadIdx.x == 0) last_flag = atomicAdd(&counters[tile], 1) == splits - 1;
     __syncthreads();
     if (!last_flag) return;
+    if (tile == 0 && threadIdx.x < 64) report_total(report, splits);
 
     // Second pass.  A thread owns up to OUT outputs (batch row, column) and keeps the
     // loads of MAXLD splits of all of them in flight at once; each output is summed in
@@ -304,7 +307,8 @@ template <int NB, int LPR, int WAVES, int U>
 __device__ __forceinline__ void batch_block(const void *__restrict__ W,
                                             const __half *__restrict__ X, int batch, double bound,
                                             float *partial, int *counters, float *Y, int m, int n,
-                                            int ks, int tile, int s, int tile_cols, int splits)
+                                            int ks, int tile, int s, int tile_cols, int splits,
+                                            const SurvivorReport &report)
 {
     extern __shared__ __align__(16) unsigned char smem[];
     // [list_x: (ks + 1) x NB floats][list_idx: ks ints]; red[] reuses the front.
@@ -333,7 +337,7 @@ __device__ __forceinline__ void batch_block(const void *__restrict__ W,
     acc.clear();
     stream_rows_batch<NB, LPR, U>(acc, list_idx, list_x, ks, start, mine, lane_base, row_bytes);
     block_finish_batch<NB, LPR, WAVES>(acc, red, partial, counters, Y, tile, col0, tile_cols, s,
-                                       splits, n, batch);
+                                       splits, n, batch, cnt, report);
 }
 
 template <int NB, int LPR, int WAVES, int U>
@@ -343,7 +347,8 @@ __global__ __launch_bounds__(WAVES * 64) void sparse_gemv_batch_kernel(
     int splits)
 {
     batch_block<NB, LPR, WAVES, U>(W, X, batch, bound, partial, counters, Y, m, n, ks,
-                                   blockIdx.x % tiles, blockIdx.x / tiles, tile_cols, splits);
+                                   blockIdx.x % tiles, blockIdx.x / tiles, tile_cols, splits,
+                                   survivor_report(counters, 0, splits));
 }
 
 // Several matrices that read the same batch of hidden states (q/k/v, gate/up:
@@ -377,7 +382,8 @@ __global__ __launch_bounds__(WAVES * 64) void sparse_gemv_batch_multi_kernel(
     }
     batch_block<NB, LPR, WAVES, U>(ma.W[k], X, batch, ma.bound[k], partial + partial_off,
                                    counters + ma.tile_begin[k], ma.Y[k], m, ma.n[k], ks,
-                                   gtile - ma.tile_begin[k], s, tile_cols, splits);
+                                   gtile - ma.tile_begin[k], s, tile_cols, splits,
+                                   survivor_report(counters, k, splits));
 }
 
 constexpr int kBatchWaves = 8;

@@ -41,6 +41,14 @@ __device__ __forceinline__ float load_coherent(const float *p)
 {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+__device__ __forceinline__ void store_coherent(int *p, int v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ int load_coherent(const int *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 
 // s_waitcnt vmcnt(0): every vector-memory operation this wavefront has issued
 // has completed (expcnt and lgkmcnt fields left at their maxima = no wait).
@@ -70,6 +78,42 @@ __device__ __forceinline__ int wave_inclusive_scan(int v)
     v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xA, 0xF, true);   // row_bcast:15 -> rows 1, 3
     v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xC, 0xF, true);   // row_bcast:31 -> rows 2, 3
     return v;
+}
+
+// Every call leaves the number of input channels that survived its threshold in the
+// workspace: the realised sparsity of a call (Section 4.2 fixes a target p per matrix
+// and a threshold estimated offline, so the two can drift apart).  The blocks of a
+// matrix's first output tile each know the count of their K-slice; they travel like
+// the partial rows (write-through store, then the arrival counter), and the block that
+// finishes that tile last adds them.  The report area follows the arrival counters:
+// int total[kMaxMatrices] (padded to kReportHeaderInts), then one row of `splits`
+// slice counts per matrix.
+struct SurvivorReport {
+    int *total;        // this matrix's slot
+    int *per_split;    // this matrix's row of slice counts
+};
+
+__device__ __forceinline__ SurvivorReport survivor_report(int *counters_base, int matrix, int splits)
+{
+    int *area = counters_base + kCounterBytes / sizeof(int);
+    return SurvivorReport{area + matrix, area + kReportHeaderInts + matrix * splits};
+}
+
+// Called by thread 0 of a block of tile 0 before the block's arrival (or instead of it
+// when there is one split).
+__device__ __forceinline__ void report_slice(const SurvivorReport &r, int s, int splits, int cnt)
+{
+    store_coherent(splits == 1 ? r.total : r.per_split + s, cnt);
+}
+
+// Called by the first wavefront of the block that arrived last at tile 0.
+__device__ __forceinline__ void report_total(const SurvivorReport &r, int splits)
+{
+    const int lane = threadIdx.x & 63;
+    int sum = 0;
+    for (int k = lane; k < splits; k += 64) sum += load_coherent(r.per_split + k);
+    sum = __builtin_amdgcn_readlane(wave_inclusive_scan(sum), 63);
+    if (lane == 0) store_coherent(r.total, sum);
 }
 
 // Where a block's activations come from.  A source loads what it needs for
@@ -280,7 +324,8 @@ template <class F, int LPR, int WAVES>
 __device__ __forceinline__ void block_finish(const float (&acc)[F::kElemsPerLane], float *red,
                                              float *partial, int *counters, float *y, int tile,
                                              int col0, int cols, int s, int splits, int n,
-                                             const typename F::Args &a)
+                                             const typename F::Args &a, int cnt,
+                                             const SurvivorReport &report)
 {
     constexpr int EPL = F::kElemsPerLane;
     constexpr int TN = LPR * EPL;
@@ -296,6 +341,7 @@ __device__ __forceinline__ void block_finish(const float (&acc)[F::kElemsPerLane
             dst[q] = make_float4(acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
     }
     __syncthreads();
+    if (tile == 0 && threadIdx.x == 0) report_slice(report, s, splits, cnt);
     if (splits == 1) {
         for (int c = threadIdx.x; c < cols; c += THREADS) {
             float sum = 0.f;
@@ -323,6 +369,7 @@ __device__ __forceinline__ void block_finish(const float (&acc)[F::kElemsPerLane
     if (threadIdx.x == 0) last_flag = atomicAdd(&counters[tile], 1) == splits - 1;
     __syncthreads();
     if (!last_flag) return;
+    if (tile == 0 && w == 0) report_total(report, splits);
 
     // Second pass.  The block's threads form PARTS groups of TN; group q adds
     // the rows s = q, q + PARTS, ... in ascending order, all its loads in
@@ -385,7 +432,7 @@ template <class F, int LPR, int WAVES, int U, class XS>
 __device__ __forceinline__ void gemv_block(const typename F::Args &a, const XS &x,
                                            float t, float *partial, int *counters, float *y, int m,
                                            int n, int ks, int tile, int s, int tile_cols,
-                                           int splits)
+                                           int splits, const SurvivorReport &report)
 {
     constexpr int EPL = F::kElemsPerLane;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -415,7 +462,7 @@ __device__ __forceinline__ void gemv_block(const typename F::Args &a, const XS &
     stream_rows<F, LPR, U>(acc, list, start, mine, lane_base, row_bytes);
     fold_row_groups<LPR>(acc);
     block_finish<F, LPR, WAVES>(acc, red, partial, counters, y, tile, col0, tile_cols, s, splits, n,
-                                a);
+                                a, cnt, report);
 }
 
 // One matrix per launch.  Grid: tiles * splits blocks; block id -> (tile,
@@ -429,7 +476,8 @@ __global__ __launch_bounds__(WAVES * 64) void sparse_gemv_kernel(
     float *y, int m, int n, int ks, int tiles, int tile_cols, int splits)
 {
     gemv_block<F, LPR, WAVES, U>(a, HalfSource{x}, t, partial, counters, y, m, n, ks,
-                                 blockIdx.x % tiles, blockIdx.x / tiles, tile_cols, splits);
+                                 blockIdx.x % tiles, blockIdx.x / tiles, tile_cols, splits,
+                                 survivor_report(counters, 0, splits));
 }
 
 // The W_down step with its input formed in the kernel from the two products that
@@ -442,7 +490,8 @@ __global__ __launch_bounds__(WAVES * 64) void sparse_gemv_swiglu_kernel(
     int splits)
 {
     gemv_block<F, LPR, WAVES, U>(a, SwigluSource{gate, up}, t, partial, counters, y, m, n, ks,
-                                 blockIdx.x % tiles, blockIdx.x / tiles, tile_cols, splits);
+                                 blockIdx.x % tiles, blockIdx.x / tiles, tile_cols, splits,
+                                 survivor_report(counters, 0, splits));
 }
 
 // Several matrices that read the same hidden state (q/k/v, or gate/up:
@@ -481,7 +530,8 @@ __global__ __launch_bounds__(WAVES * 64) void sparse_gemv_multi_kernel(
     }
     gemv_block<F, LPR, WAVES, U>(ma.a[k], HalfSource{x}, ma.t[k], partial + partial_off,
                                  counters + ma.tile_begin[k], ma.y[k], m, ma.n[k], ks,
-                                 gtile - ma.tile_begin[k], s, tile_cols, splits);
+                                 gtile - ma.tile_begin[k], s, tile_cols, splits,
+                                 survivor_report(counters, k, splits));
 }
 
 // Host-side launch geometry shared by the formats.

@@ -99,7 +99,8 @@ struct W4Batch {
 template <int LPR, int WAVES, int U>
 __device__ __forceinline__ void w4_block(const FmtW4::Args &a, const __half *__restrict__ x,
                                          float t, float *partial, int *counters, float *y, int m,
-                                         int n, int ks, int tile, int s, int tile_cols, int splits)
+                                         int n, int ks, int tile, int s, int tile_cols, int splits,
+                                         const SurvivorReport &report)
 {
     using F = FmtW4;
     constexpr int EPL = F::kElemsPerLane;
@@ -208,7 +209,7 @@ __device__ __forceinline__ void w4_block(const FmtW4::Args &a, const __half *__r
     }
     fold_row_groups<LPR>(acc);
     block_finish<F, LPR, WAVES>(acc, red, partial, counters, y, tile, col0, tile_cols, s, splits, n,
-                                a);
+                                a, cnt, report);
 }
 
 template <int LPR, int WAVES, int U>
@@ -217,7 +218,8 @@ __global__ __launch_bounds__(WAVES * 64) void sparse_gemv_w4_kernel(
     int m, int n, int ks, int tiles, int tile_cols, int splits)
 {
     w4_block<LPR, WAVES, U>(a, x, t, partial, counters, y, m, n, ks, blockIdx.x % tiles,
-                            blockIdx.x / tiles, tile_cols, splits);
+                            blockIdx.x / tiles, tile_cols, splits,
+                            survivor_report(counters, 0, splits));
 }
 
 // Several int4 matrices that read the same hidden state in one launch; the block finds its
@@ -241,7 +243,8 @@ __global__ __launch_bounds__(WAVES * 64) void sparse_gemv_w4_multi_kernel(
     }
     w4_block<LPR, WAVES, U>(ma.a[k], x, ma.t[k], partial + partial_off,
                             counters + ma.tile_begin[k], ma.y[k], m, ma.n[k], ks,
-                            gtile - ma.tile_begin[k], s, tile_cols, splits);
+                            gtile - ma.tile_begin[k], s, tile_cols, splits,
+                            survivor_report(counters, k, splits));
 }
 
 hipError_t launch_gemv_w8(const int8_t *Wq, const void *scale_f16, const void *x_f16, float t,

@@ -152,11 +152,22 @@ teal_status check_gemv(const GemvArgs &a, int n_multiple)
 
 teal_status from_hip(hipError_t e) { return e == hipSuccess ? TEAL_OK : TEAL_ERR_HIP; }
 
-// Workspace layout: [arrival counters, kCounterBytes][partial rows, splits x n fp32].
-int *ws_counters(void *workspace) { return static_cast<int *>(workspace); }
-float *ws_partials(void *workspace)
+// Workspace layout: [arrival counters, kCounterBytes][survivor report, report_bytes(m)]
+// [partial rows, splits x n fp32].  The report holds one total per matrix of the call and,
+// per matrix, one count per split; its size allows for the most splits any call with this
+// m can run with.
+size_t report_bytes(int m)
 {
-    return reinterpret_cast<float *>(static_cast<unsigned char *>(workspace) + teal::kCounterBytes);
+    const int forced = (m + teal::kMaxSliceBatch - 1) / teal::kMaxSliceBatch;
+    const size_t rows = forced > teal::kMaxSplits ? forced : teal::kMaxSplits;
+    const size_t bytes = (teal::kReportHeaderInts + teal::kMaxMatrices * rows) * sizeof(int);
+    return (bytes + kAlignWorkspace - 1) / kAlignWorkspace * kAlignWorkspace;
+}
+int *ws_counters(void *workspace) { return static_cast<int *>(workspace); }
+float *ws_partials(void *workspace, int m)
+{
+    return reinterpret_cast<float *>(static_cast<unsigned char *>(workspace) +
+                                     teal::kCounterBytes + report_bytes(m));
 }
 
 }  // namespace
@@ -178,13 +189,15 @@ const char *teal_status_string(teal_status s)
     return "unknown status";
 }
 
-int teal_version(void) { return 200; }
+int teal_version(void) { return 300; }
+
+size_t teal_survivors_offset(void) { return teal::kCounterBytes; }
 
 size_t teal_workspace_bytes(int m, int n)
 {
     if (m < 1 || m > teal::kMaxDim || n < 1 || n > teal::kMaxDim) return 0;
     const size_t rows = (size_t)max_splits_for(m);
-    const size_t bytes = teal::kCounterBytes + rows * (size_t)n * sizeof(float);
+    const size_t bytes = teal::kCounterBytes + report_bytes(m) + rows * (size_t)n * sizeof(float);
     return (bytes + kAlignWorkspace - 1) / kAlignWorkspace * kAlignWorkspace;
 }
 
@@ -219,7 +232,7 @@ teal_status teal_sparse_gemv_bf16_ex(const void *Wt_bf16, const void *x_f16, flo
     if (unroll) sh.unroll = unroll;
     if (!teal::gemv_shape_supported(sh)) return TEAL_ERR_UNSUPPORTED;
     if (sh.splits > max_splits_for(m)) return TEAL_ERR_UNSUPPORTED;           // partial rows
-    return from_hip(teal::launch_gemv_bf16(Wt_bf16, x_f16, t, y, m, n, ws_partials(workspace),
+    return from_hip(teal::launch_gemv_bf16(Wt_bf16, x_f16, t, y, m, n, ws_partials(workspace, m),
                                            ws_counters(workspace), sh,
                                            static_cast<hipStream_t>(stream)));
 }
@@ -305,7 +318,7 @@ teal_status teal_sparse_gemv_bf16_batch_multi(int count, const void *const *Wt_b
                   : auto_shape(m, (int)n_total, 8, 16, max_lanes, 64, teal::kMaxSliceBatch);
     if (!teal::gemv_batch_shape_supported(batch, sh)) return TEAL_ERR_UNSUPPORTED;
     return from_hip(teal::launch_gemv_bf16_batch_multi(count, Wt_bf16, t, Y, n, X_f16, batch, m,
-                                                       ws_partials(workspace),
+                                                       ws_partials(workspace, m),
                                                        ws_counters(workspace), sh,
                                                        static_cast<hipStream_t>(stream)));
 }
@@ -329,7 +342,7 @@ teal_status teal_sparse_gemv_bf16_swiglu(const void *Wt_bf16, const float *gate,
     if (!aligned(gate, 4) || !aligned(up, 4)) return TEAL_ERR_ALIGN;
     const GemvShape sh = auto_shape(m, n, 8, 16, 64, 64);
     return from_hip(teal::launch_gemv_bf16_swiglu(Wt_bf16, gate, up, t, y, m, n,
-                                                  ws_partials(workspace), ws_counters(workspace),
+                                                  ws_partials(workspace, m), ws_counters(workspace),
                                                   sh, static_cast<hipStream_t>(stream)));
 }
 
@@ -356,7 +369,7 @@ teal_status teal_sparse_gemv_bf16_multi(int count, const void *const *Wt_bf16, c
     const GemvShape sh = count > 1 ? auto_shape_multi(m, n, count, 8, 16, 64, 64)
                                    : auto_shape(m, (int)n_total, 8, 16, 64, 64);
     return from_hip(teal::launch_gemv_bf16_multi(count, Wt_bf16, t, y, n, x_f16, m,
-                                                 ws_partials(workspace), ws_counters(workspace),
+                                                 ws_partials(workspace, m), ws_counters(workspace),
                                                  sh, static_cast<hipStream_t>(stream)));
 }
 
@@ -366,7 +379,7 @@ size_t teal_workspace_bytes_batch(int m, int n, int batch)
         batch > teal::kMaxBatch)
         return 0;
     const size_t rows = (size_t)batch_split_rows(m) * (size_t)batch;
-    const size_t bytes = teal::kCounterBytes + rows * (size_t)n * sizeof(float);
+    const size_t bytes = teal::kCounterBytes + report_bytes(m) + rows * (size_t)n * sizeof(float);
     return (bytes + kAlignWorkspace - 1) / kAlignWorkspace * kAlignWorkspace;
 }
 
@@ -411,7 +424,7 @@ teal_status teal_sparse_gemv_bf16_batch_ex(const void *Wt_bf16, const void *X_f1
     if (ks > teal::kMaxSliceBatch) return TEAL_ERR_UNSUPPORTED;
     if ((m + ks - 1) / ks > batch_split_rows(m)) return TEAL_ERR_UNSUPPORTED;   // partial rows
     return from_hip(teal::launch_gemv_bf16_batch(Wt_bf16, X_f16, batch, t, Y, m, n,
-                                                 ws_partials(workspace), ws_counters(workspace),
+                                                 ws_partials(workspace, m), ws_counters(workspace),
                                                  sh, static_cast<hipStream_t>(stream)));
 }
 
@@ -433,7 +446,7 @@ teal_status teal_sparse_gemv_w8(const int8_t *Wq, const void *scale_f16, const v
     if (st != TEAL_OK) return st;
     if (!aligned(scale_f16, 2)) return TEAL_ERR_ALIGN;
     const GemvShape sh = auto_shape(m, n, 16, 8, 64, 64);
-    return from_hip(teal::launch_gemv_w8(Wq, scale_f16, x_f16, t, y, m, n, ws_partials(workspace),
+    return from_hip(teal::launch_gemv_w8(Wq, scale_f16, x_f16, t, y, m, n, ws_partials(workspace, m),
                                          ws_counters(workspace), sh,
                                          static_cast<hipStream_t>(stream)));
 }
@@ -462,7 +475,7 @@ teal_status teal_sparse_gemv_w8_multi(int count, const int8_t *const *Wq,
     const GemvShape sh = count > 1 ? auto_shape_multi(m, n, count, 16, 8, 64, 64)
                                    : auto_shape(m, (int)n_total, 16, 8, 64, 64);
     return from_hip(teal::launch_gemv_w8_multi(count, Wq, scale_f16, t, y, n, x_f16, m,
-                                               ws_partials(workspace), ws_counters(workspace), sh,
+                                               ws_partials(workspace, m), ws_counters(workspace), sh,
                                                static_cast<hipStream_t>(stream)));
 }
 
@@ -477,7 +490,7 @@ teal_status teal_sparse_gemv_w4(const uint8_t *Wq, const void *scale_f16, int gr
     if (!aligned(scale_f16, 16)) return TEAL_ERR_ALIGN;
     if (group != 128 || m % 128 != 0) return TEAL_ERR_UNSUPPORTED;
     const GemvShape sh = auto_shape(m, n, 32, 16, 32, 128);
-    return from_hip(teal::launch_gemv_w4(Wq, scale_f16, x_f16, t, y, m, n, ws_partials(workspace),
+    return from_hip(teal::launch_gemv_w4(Wq, scale_f16, x_f16, t, y, m, n, ws_partials(workspace, m),
                                          ws_counters(workspace), sh,
                                          static_cast<hipStream_t>(stream)));
 }
@@ -507,7 +520,7 @@ teal_status teal_sparse_gemv_w4_multi(int count, const uint8_t *const *Wq,
     const GemvShape sh = count > 1 ? auto_shape_multi(m, n, count, 32, 16, 32, 128)
                                    : auto_shape(m, (int)n_total, 32, 16, 32, 128);
     return from_hip(teal::launch_gemv_w4_multi(count, Wq, scale_f16, t, y, n, x_f16, m,
-                                               ws_partials(workspace), ws_counters(workspace), sh,
+                                               ws_partials(workspace, m), ws_counters(workspace), sh,
                                                static_cast<hipStream_t>(stream)));
 }
 

@@ -17,6 +17,9 @@ constexpr int kMaxBatch = 8;        // rows of a small batch (Section 5.4.4)
 constexpr int kMaxSliceBatch = 2048;  // most input channels one block compacts for a batch
 // Head of the workspace: one arrival counter per output tile (zero between calls).
 constexpr size_t kCounterBytes = (size_t)(kMaxDim / kMinTile) * sizeof(int);
+// The survivor report follows the counters: kReportHeaderInts ints that start with one
+// total per matrix of the call, then kMaxMatrices rows of per-split counts.
+constexpr int kReportHeaderInts = 64;
 
 // How one sparse GEMV is laid over the chip.
 struct GemvShape {

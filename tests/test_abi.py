@@ -55,8 +55,11 @@ def test_version_and_status_strings():
 
 def test_workspace_bytes():
     assert T.teal_workspace_bytes(0, 8) == 0 and T.teal_workspace_bytes(8, 0) == 0
-    # arrival counters (one per 64 output columns of the largest n) + 128 fp32 partial rows
-    assert T.teal_workspace_bytes(4096, 4096) == (1 << 24) // 64 * 4 + 128 * 4096 * 4
+    # arrival counters (one per 64 output columns of the largest n), the survivor report
+    # (64 ints of totals, then 4 matrices x 128 splits of slice counts), 128 fp32 partial rows
+    assert T.teal_survivors_offset() == (1 << 24) // 64 * 4
+    assert T.teal_workspace_bytes(4096, 4096) == ((1 << 24) // 64 * 4 + (64 + 4 * 128) * 4
+                                                   + 128 * 4096 * 4)
     assert T.teal_workspace_bytes(4096, 14336) % 256 == 0
     # very long inputs force more than 128 splits (one block compacts at most 4096 channels)
     assert T.teal_workspace_bytes(1 << 20, 8) >= (1 << 20) // 4096 * 8 * 4
@@ -342,3 +345,32 @@ def test_check_raises_with_message():
         T.check(T.TEAL_ERR_WORKSPACE)
     assert "workspace" in str(e.value) and e.value.status == T.TEAL_ERR_WORKSPACE
     T.check(T.TEAL_OK)
+
+
+def test_binding_refuses_tensors_smaller_than_the_call_touches():
+    """The C ABI sees plain pointers; the binding knows a tensor's size and refuses a
+    buffer the kernels would run past (CPU tensors stand in: the check is on sizes)."""
+    torch = pytest.importorskip("torch")
+    m = 256
+    ws = torch.zeros(T.teal_workspace_bytes(m, 128), dtype=torch.uint8)
+    x = torch.zeros(m, dtype=torch.int16)
+    wt = torch.zeros(m * 64, dtype=torch.int16)
+    y = torch.zeros(64)
+    with pytest.raises(ValueError, match="Wt"):
+        T.teal_sparse_gemv_bf16(wt, x, 0.5, torch.zeros(128), m, 128, ws, stream=0)
+    with pytest.raises(ValueError, match="y:"):
+        T.teal_sparse_gemv_bf16(wt, x, 0.5, torch.zeros(32), m, 64, ws, stream=0)
+    with pytest.raises(ValueError, match="x:"):
+        T.teal_sparse_gemv_bf16(wt, x[:100].clone(), 0.5, y, m, 64, ws, stream=0)
+    # grouped calls: every per-matrix list must be in the same order
+    q = [torch.zeros(m * n // 2, dtype=torch.uint8) for n in (64, 32)]
+    sc = [torch.zeros(m // 128 * n, dtype=torch.int16) for n in (64, 32)]
+    ys = [torch.zeros(n) for n in (32, 64)]
+    with pytest.raises(ValueError, match="Wq"):
+        T.teal_sparse_gemv_w4_multi(q, sc, 128, [0.1, 0.1], ys, [32, 64], x, m, ws, stream=0)
+    with pytest.raises(ValueError, match="Y:"):
+        T.teal_sparse_gemv_bf16_batch(wt, torch.zeros(2 * m, dtype=torch.int16), 2, 0.5,
+                                      torch.zeros(64), m, 64, ws, stream=0)
+    with pytest.raises(ValueError, match="gate"):
+        T.teal_sparse_gemv_bf16_swiglu(wt, torch.zeros(m - 1), torch.zeros(m), 0.5, y, m, 64, ws,
+                                       stream=0)

@@ -95,13 +95,17 @@ def test_gemv_batch_small_shapes(T, batch, n, m):
     w = ti.weights_bf16(n, m, 100 + n + m)
     wt = dev(ti.to_input_channel_major(w))
     X = ti.make_X(batch, m, 7 * batch + n, "gaussian")
+    ws = torch.zeros(T.teal_workspace_bytes_batch(m, n, batch), dtype=torch.uint8, device="cuda")
+    off = T.teal_survivors_offset()
     for p in (0.0, 0.5, 0.9):
         t = ti.batch_quantile_threshold(X, p)
         want = orc.sparse_gemv_bf16_batch(w, X, t)
-        got = run_batch(T, wt, X, t, m, n)
+        got = run_batch(T, wt, X, t, m, n, ws)
         assert not np.isnan(got).any()
         for b in range(batch):
             assert rel_l2(got[b], want[b]) <= TIGHT, (b, p)
+        # the survivor count the call leaves in its workspace
+        assert ws[off:off + 4].view(torch.int32).item() == orc.sparsify_batch(X, t)[3], p
 
 
 @pytest.mark.parametrize("batch,lanes", [(2, 64), (2, 32), (2, 16), (4, 64), (4, 32), (4, 16),
@@ -183,6 +187,9 @@ def test_gemv_batch_multi(T, name, ns, m, ps, batch):
         Ys.append(torch.full((batch, n), float("nan"), dtype=torch.float32, device="cuda"))
     T.check(T.teal_sparse_gemv_bf16_batch_multi(wts, ts, Ys, ns, Xd, batch, m, ws))
     torch.cuda.synchronize()
+    off = T.teal_survivors_offset()
+    kept = ws[off:off + 4 * len(ns)].view(torch.int32).cpu().tolist()
+    assert kept == [orc.sparsify_batch(X, t)[3] for t in ts]
     for k, n in enumerate(ns):
         got = Ys[k].cpu().numpy()
         want = orc.sparse_gemv_bf16_batch(ws_host[k], X, ts[k])
@@ -206,10 +213,12 @@ def test_very_long_input(T):
     X = ti.make_X(batch, m, 5151, "laplace")
     t = ti.batch_quantile_threshold(X, 0.5)
     want = orc.sparse_gemv_bf16_batch(w, X, t)
-    got = run_batch(T, wt, X, t, m, n)
+    ws = torch.zeros(T.teal_workspace_bytes_batch(m, 2 * n, batch), dtype=torch.uint8, device="cuda")
+    got = run_batch(T, wt, X, t, m, n, ws)
     for b in range(batch):
         assert rel_l2(got[b], want[b]) <= TIGHT, b
-    ws = torch.zeros(T.teal_workspace_bytes_batch(m, 2 * n, batch), dtype=torch.uint8, device="cuda")
+    off = T.teal_survivors_offset()
+    assert ws[off:off + 4].view(torch.int32).item() == orc.sparsify_batch(X, t)[3]
     Ys = [torch.full((batch, n), float("nan"), dtype=torch.float32, device="cuda") for _ in range(2)]
     t2 = ti.batch_quantile_threshold(X, 0.25)
     T.check(T.teal_sparse_gemv_bf16_batch_multi([wt, wt], [t, t2], Ys, [n, n], dev(X), batch, m, ws))

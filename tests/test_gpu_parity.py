@@ -45,6 +45,12 @@ def workspace(T, m, n):
     return torch.zeros(T.teal_workspace_bytes(m, n), dtype=torch.uint8, device="cuda")
 
 
+def survivors(T, ws, count=1):
+    """The survivor counts a completed call left in its workspace."""
+    off = T.teal_survivors_offset()
+    return ws[off:off + 4 * count].view(torch.int32).cpu().tolist()
+
+
 def run_bf16(T, wt_dev, x_dev, t, m, n, ws, **shape):
     # poison y: the call must overwrite every element
     y = torch.full((n,), float("nan"), dtype=torch.float32, device="cuda")
@@ -459,6 +465,81 @@ def test_gemv_w4_multi(T, name, ns, m, ps):
     for a, b in zip(ys, ys2):
         assert torch.equal(a, b)
 
+# ---------------------------------------------------------------------------
+# the survivor count every call leaves in its workspace
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("n,m", [(16, 1), (144, 65), (528, 333), (1040, 2049), (4096, 4096),
+                                 (1024, 14336)])
+def test_survivor_count_one_matrix(T, n, m):
+    n4, m4 = (n + 31) // 32 * 32, (m + 127) // 128 * 128      # a shape the int4 format takes
+    w = ti.weights_bf16(n, m, seed=5 * n + m)
+    wt = dev(ti.to_input_channel_major(w))
+    q8, s8 = ti.quantize_w8(w)
+    q4, s4 = ti.quantize_w4(ti.weights_bf16(n4, m4, seed=6 * n + m))
+    q8d, s8d, q4d, s4d = dev(q8), dev(s8), dev(q4), dev(s4)
+    ws = workspace(T, m4, n4)
+    ws.fill_(0x5A)                     # the report area needs no initial value ...
+    ws[:T.teal_survivors_offset()].zero_()      # ... the arrival counters do
+    x4 = ti.make_x(m4, 31 + m, "laplace")
+    x = x4[:m].copy()
+    xd, x4d = dev(x), dev(x4)
+    for p in (0.0, 0.3, 0.5, 0.97, 1.0):
+        t = ti.quantile_threshold(x, p)
+        want = orc.sparsify(x, t)[3]
+        run_bf16(T, wt, xd, t, m, n, ws)
+        assert survivors(T, ws) == [want], (n, m, p)
+        run_w8(T, q8d, s8d, xd, t, m, n, ws)
+        assert survivors(T, ws) == [want], (n, m, p)
+        t4 = ti.quantile_threshold(x4, p)
+        run_w4(T, q4d, s4d, x4d, t4, m4, n4, ws)
+        assert survivors(T, ws) == [orc.sparsify(x4, t4)[3]], (n, m, p)
+    # every launch shape reports the same count
+    t = ti.quantile_threshold(x, 0.5)
+    want = orc.sparsify(x, t)[3]
+    for splits in (1, 2, 3, 7, 16, 128):
+        if (m + splits - 1) // splits > 4096:
+            continue
+        run_bf16(T, wt, xd, t, m, n, ws, splits=splits)
+        assert survivors(T, ws) == [want], splits
+
+
+def test_survivor_counts_grouped_calls(T):
+    m, ns, ps = 4096, [4096, 1024, 1024, 72], [0.5, 0.4, 0.25, 0.9]
+    x = ti.gaussian_x(m, 808)
+    xd = dev(x)
+    ws = workspace(T, m, sum(ns))
+    ts = [ti.quantile_threshold(x, p) for p in ps]
+    want = [orc.sparsify(x, t)[3] for t in ts]
+    wts = [dev(ti.to_input_channel_major(ti.weights_bf16(n, m, seed=90 + k))) for k, n in enumerate(ns)]
+    ys = [torch.empty(n, dtype=torch.float32, device="cuda") for n in ns]
+    T.check(T.teal_sparse_gemv_bf16_multi(wts, ts, ys, ns, xd, m, ws))
+    torch.cuda.synchronize()
+    assert survivors(T, ws, 4) == want
+    # fewer matrices, other thresholds, same workspace: slots of this call only
+    T.check(T.teal_sparse_gemv_bf16_multi(wts[2:0:-1], ts[2:0:-1], ys[2:0:-1], ns[2:0:-1], xd, m, ws))
+    torch.cuda.synchronize()
+    assert survivors(T, ws, 2) == want[2:0:-1]
+    ns16 = [4096, 1024, 1024]
+    qs, scs = [], []
+    for k, n in enumerate(ns16):
+        q, scale = ti.quantize_w8(ti.weights_bf16(n, m, seed=190 + k))
+        qs.append(dev(q))
+        scs.append(dev(scale))
+    T.check(T.teal_sparse_gemv_w8_multi(qs, scs, ts[:3], ys[:3], ns16, xd, m, ws))
+    torch.cuda.synchronize()
+    assert survivors(T, ws, 3) == want[:3]
+    qs, scs = [], []
+    for k, n in enumerate(ns16):
+        q, scale = ti.quantize_w4(ti.weights_bf16(n, m, seed=290 + k))
+        qs.append(dev(q))
+        scs.append(dev(scale))
+    # the same three matrices in reverse order (every per-matrix list reversed alike)
+    T.check(T.teal_sparse_gemv_w4_multi(qs[::-1], scs[::-1], 128, ts[2::-1], ys[2::-1], ns16[::-1],
+                                        xd, m, ws))
+    torch.cuda.synchronize()
+    assert survivors(T, ws, 3) == want[2::-1]
+
+
 
 # An input longer than 128 x 4096 channels: a block compacts at most 4096 channels, so
 # the call runs with more split-K blocks than a caller may ask for, and the workspace
@@ -479,6 +560,8 @@ def test_very_long_input_every_format(T):
     wt = dev(ti.to_input_channel_major(w))
     got = run_bf16(T, wt, xd, t, m, n, ws)
     assert rel_l2(got, want) <= TIGHT
+    kept = orc.sparsify(x, t)[3]
+    assert survivors(T, ws) == [kept]
     # asking for fewer splits than the length needs gives the same call
     again = run_bf16(T, wt, xd, t, m, n, ws, splits=128)
     assert np.array_equal(got, again)
@@ -488,6 +571,7 @@ def test_very_long_input_every_format(T):
     torch.cuda.synchronize()
     assert rel_l2(ys[0].cpu().numpy(), want) <= TIGHT
     assert rel_l2(ys[1].cpu().numpy(), orc.sparse_gemv_bf16(w, x, t2)) <= TIGHT
+    assert survivors(T, ws, 2) == [kept, orc.sparsify(x, t2)[3]]
 
     q, scale = ti.quantize_w8(w)
     got = run_w8(T, dev(q), dev(scale), xd, t, m, n, ws)
@@ -496,6 +580,7 @@ def test_very_long_input_every_format(T):
     q4, scale4 = ti.quantize_w4(w)
     got = run_w4(T, dev(q4), dev(scale4), xd, t, m, n, ws)
     assert rel_l2(got, orc.sparse_gemv_w4(q4, scale4, 128, x, t)) <= TIGHT
+    assert survivors(T, ws) == [kept]
 
 
 

@@ -108,6 +108,9 @@ def test_fused_product_against_oracle_and_unfused(T, n, m):
         got = run_fused(T, wt, g, u, t, m, n, ws)
         assert rel_l2(got, want) <= TIGHT, p
         assert rel_l2(got, want) <= TOL_BF16
+        # the count of surviving channels the fused call leaves in its workspace
+        off = T.teal_survivors_offset()
+        assert ws[off:off + 4].view(torch.int32).item() == orc.sparsify(h, t)[3], p
         # bitwise the two-launch path: producer kernel, then the plain call
         y2 = torch.full((n,), float("nan"), dtype=torch.float32, device="cuda")
         T.check(T.teal_sparse_gemv_bf16(wt, hd, t, y2, m, n, ws))
