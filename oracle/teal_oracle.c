@@ -372,6 +372,79 @@ int32_t oracle_sparse_gemv_bf16_swiglu(const uint16_t *W_bf16, const float *gate
     return oracle_sparse_gemv_bf16(W_bf16, scratch_h, t, y, m, n, scratch_xs);
 }
 
+/* ---- the normalised hidden state as the input of W_q, W_k, W_v / W_gate, W_up ---- */
+
+/*
+ * The inputs of the attention and MLP projections (Appendix A.3) are the
+ * block's hidden state after the normalisation layer (Section 4.1 attributes
+ * their zero-mean shape to it).  The paper does not print the layer's formula;
+ * the reading taken here is the root-mean-square normalisation of the model
+ * family it evaluates (Section 5):
+ *     x_i = gamma_i * h_i / sqrt(mean_j(h_j^2) + eps).
+ * A kernel that forms x itself from h has to fix x's arithmetic, because x
+ * decides the mask (as for the MLP intermediate above), including the order
+ * of the sum of squares.  Stated here operation by operation, h and gamma
+ * binary32:
+ *   ss = sum of the squares h_j^2 in binary64 (each square is exact there),
+ *        added by pairwise summation: the index range [0, P), P the smallest
+ *        power of two >= m and entries past m zero, is halved recursively and
+ *        the two halves' sums are added (each addition rounded to binary64)
+ *   v  = ss / m + eps                       (binary64: division, then addition)
+ *   r  = binary32(1 / sqrt(v))              (binary64 square root and division)
+ *   a  = h_i * r;  b = a * gamma_i          (binary32, each rounded)
+ *   x_i = binary16(b)
+ * Everything after x (Definition 1, the product) is the fp64 oracle above.
+ */
+static double tree_sum_of_squares(const float *h, size_t lo, size_t size, size_t m)
+{
+    if (lo >= m) return 0.0;
+    if (size == 1) return (double)h[lo] * (double)h[lo];
+    const size_t half = size / 2;
+    return tree_sum_of_squares(h, lo, half, m) + tree_sum_of_squares(h, lo + half, half, m);
+}
+
+/* ss as defined above (0 for m < 1). */
+double oracle_sum_of_squares(const float *h, int32_t m)
+{
+    if (m < 1) return 0.0;
+    size_t P = 1;
+    while (P < (size_t)m) P *= 2;
+    return tree_sum_of_squares(h, 0, P, (size_t)m);
+}
+
+/* r = binary32(1 / sqrt(mean(h^2) + eps)) as defined above (m >= 1). */
+float oracle_rms_scale(const float *h, int32_t m, float eps)
+{
+    const double ss = oracle_sum_of_squares(h, m);
+    const double v = ss / (double)m + (double)eps;
+    return (float)(1.0 / sqrt(v));
+}
+
+/* x[i] = binary16((h[i] * r) * gamma[i]) as defined above. */
+void oracle_rmsnorm_f16(const float *h, const float *gamma, float eps, int32_t m, uint16_t *x_f16)
+{
+    if (m < 1) return;
+    const float r = oracle_rms_scale(h, m, eps);
+    for (int32_t i = 0; i < m; ++i) {
+        const float a = h[i] * r;
+        const float b = a * gamma[i];
+        x_f16[i] = oracle_f32_to_f16_bits(b);
+    }
+}
+
+/*
+ * y = s_t(x) W^T with x formed from h and gamma as above; W is canonical
+ * [n][m].  scratch_x: m uint16; scratch_xs: m doubles.  Returns the kept count.
+ */
+int32_t oracle_sparse_gemv_bf16_rmsnorm(const uint16_t *W_bf16, const float *h,
+                                        const float *gamma, float eps, float t, double *y,
+                                        int32_t m, int32_t n, uint16_t *scratch_x,
+                                        double *scratch_xs)
+{
+    oracle_rmsnorm_f16(h, gamma, eps, m, scratch_x);
+    return oracle_sparse_gemv_bf16(W_bf16, scratch_x, t, y, m, n, scratch_xs);
+}
+
 /* Threads the parallel loops above use (1 when built without OpenMP). */
 int32_t oracle_num_threads(void)
 {

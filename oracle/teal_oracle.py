@@ -74,6 +74,15 @@ def _load():
     lib.oracle_f32_to_f16_bits.argtypes = [c.c_float]
     lib.oracle_swiglu_f16.restype = None
     lib.oracle_swiglu_f16.argtypes = [f32p, f32p, c.c_int32, u16p]
+    lib.oracle_sum_of_squares.restype = c.c_double
+    lib.oracle_sum_of_squares.argtypes = [f32p, c.c_int32]
+    lib.oracle_rms_scale.restype = c.c_float
+    lib.oracle_rms_scale.argtypes = [f32p, c.c_int32, c.c_float]
+    lib.oracle_rmsnorm_f16.restype = None
+    lib.oracle_rmsnorm_f16.argtypes = [f32p, f32p, c.c_float, c.c_int32, u16p]
+    lib.oracle_sparse_gemv_bf16_rmsnorm.restype = c.c_int32
+    lib.oracle_sparse_gemv_bf16_rmsnorm.argtypes = [u16p, f32p, f32p, c.c_float, c.c_float, f64p,
+                                                    c.c_int32, c.c_int32, u16p, f64p]
     lib.oracle_sparse_gemv_bf16_swiglu.restype = c.c_int32
     lib.oracle_sparse_gemv_bf16_swiglu.argtypes = [u16p, f32p, f32p, c.c_float, f64p,
                                                    c.c_int32, c.c_int32, u16p, f64p]
@@ -104,7 +113,7 @@ def _x_bits(x_f16) -> np.ndarray:
 def _f32(t) -> float:
     tf = float(np.float32(t))
     if tf != float(t):
-        raise ValueError("threshold must be exactly representable in fp32")
+        raise ValueError("threshold (or eps) must be exactly representable in fp32")
     return tf
 
 
@@ -294,6 +303,51 @@ def sparse_gemv_bf16_swiglu(w_bits, gate_f32, up_f32, t) -> np.ndarray:
                                            _ptr(u, ctypes.c_float), _f32(t),
                                            _ptr(y, ctypes.c_double), m, n,
                                            _ptr(h, ctypes.c_uint16), _ptr(xs, ctypes.c_double))
+    return y
+
+
+def sum_of_squares(h_f32) -> float:
+    """The binary64 sum of the squares of h by pairwise summation (see rms_scale)."""
+    h = _f32_vec(h_f32, "h")
+    return float(_load().oracle_sum_of_squares(_ptr(h, ctypes.c_float), h.size))
+
+
+def rms_scale(h_f32, eps: float) -> float:
+    """r = binary32(1 / sqrt(mean(h^2) + eps)), the sum of squares by pairwise summation
+    in binary64 (the normalisation that precedes W_q/W_k/W_v and W_gate/W_up, Appendix A.3)."""
+    h = _f32_vec(h_f32, "h")
+    if h.size < 1:
+        raise ValueError("h must not be empty")
+    return float(_load().oracle_rms_scale(_ptr(h, ctypes.c_float), h.size, _f32(eps)))
+
+
+def rmsnorm_f16(h_f32, gamma_f32, eps: float) -> np.ndarray:
+    """x = gamma * h * r rounded to fp16 (returned as float16[m]); r as in rms_scale."""
+    h, g = _f32_vec(h_f32, "h"), _f32_vec(gamma_f32, "gamma")
+    if h.size != g.size:
+        raise ValueError("h and gamma must have the same length")
+    x = np.empty(h.size, np.uint16)
+    _load().oracle_rmsnorm_f16(_ptr(h, ctypes.c_float), _ptr(g, ctypes.c_float), _f32(eps),
+                               h.size, _ptr(x, ctypes.c_uint16))
+    return x.view(np.float16)
+
+
+def sparse_gemv_bf16_rmsnorm(w_bits, h_f32, gamma_f32, eps: float, t) -> np.ndarray:
+    """y float64[n] = s_t(rmsnorm(h)) W^T for canonical W[n][m]."""
+    w = np.ascontiguousarray(w_bits)
+    if w.dtype != np.uint16 or w.ndim != 2:
+        raise TypeError("W must be a 2-D uint16 array of bf16 bit patterns, [n][m]")
+    h, g = _f32_vec(h_f32, "h"), _f32_vec(gamma_f32, "gamma")
+    n, m = w.shape
+    if h.size != m or g.size != m:
+        raise ValueError("h / gamma length must equal W's input dimension")
+    y = np.empty(n, np.float64)
+    x = np.empty(m, np.uint16)
+    xs = np.empty(m, np.float64)
+    _load().oracle_sparse_gemv_bf16_rmsnorm(_ptr(w, ctypes.c_uint16), _ptr(h, ctypes.c_float),
+                                            _ptr(g, ctypes.c_float), _f32(eps), _f32(t),
+                                            _ptr(y, ctypes.c_double), m, n,
+                                            _ptr(x, ctypes.c_uint16), _ptr(xs, ctypes.c_double))
     return y
 
 

@@ -119,6 +119,22 @@ def mlp_gate_up(m: int, seed: int):
     return gate, up
 
 
+def norm_inputs(m: int, seed: int):
+    """The fp32 hidden state h before the normalisation layer and the layer's weights
+    gamma, from which the input of W_q/W_k/W_v (or W_gate/W_up) is formed (Appendix A.3).
+    h is Gaussian-shaped, N(0, 2.5^2), with one channel in 512 scaled by 40 (the few
+    very large channels of a residual stream, which dominate the sum of squares);
+    gamma = 0.5 + 0.1 N(0, 1).  The normalised state comes out Gaussian-shaped with
+    unit-order scale, like the inputs of the attention and MLP blocks (Section 4.1,
+    Figure 2).  Returns (h, gamma) float32[m]."""
+    rng = _rng(seed)
+    h = rng.standard_normal(m) * 2.5
+    big = rng.random(m) < 1.0 / 512.0
+    h = np.where(big, h * 40.0, h).astype(np.float32)
+    gamma = (0.5 + 0.1 * rng.standard_normal(m)).astype(np.float32)
+    return h, gamma
+
+
 def make_X(batch: int, m: int, seed: int, dist: str) -> np.ndarray:
     """A small batch of independent hidden states, [batch][m] fp16 (rows drawn
     one after the other from one seeded stream)."""
