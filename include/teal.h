@@ -134,6 +134,43 @@ teal_status teal_sparse_gemv_bf16_multi(int count, const void *const *Wt_bf16, c
                                         void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The grouped call with its shared input formed on the fly from the hidden
+ * state before the normalisation layer.  Appendix A.3 feeds W_q, W_k, W_v (and
+ * W_gate, W_up) with the block's normalised hidden state (Section 4.1 relates
+ * the zero-mean shape of these inputs to the normalisation); the paper prints
+ * no formula for the layer, and the one taken here is the root-mean-square
+ * normalisation of the models it evaluates (Section 5):
+ *     x_i = gamma_i * h_i / sqrt(mean_j(h_j^2) + eps).
+ * x decides the mask, so its arithmetic is part of the interface.  With h and
+ * gamma binary32: ss = sum of the squares h_j^2 in binary64 (the squares are
+ * exact there) by pairwise summation -- the index range [0, P), P the smallest
+ * power of two >= m and entries past m zero, is halved recursively and the two
+ * halves' sums are added, every addition rounded to binary64;
+ * v = ss / m + eps and r = binary32(1 / sqrt(v)), both in binary64 with
+ * correctly rounded division and square root; a = h_i * r, b = a * gamma_i in
+ * binary32, each rounded to nearest even; x_i = binary16(b).  A NaN in h makes
+ * every x_i NaN (all dropped); a NaN in gamma_i only x_i.
+ *
+ * teal_rmsnorm_f16: the producer alone, x_f16[i] for i < m.
+ *   h [m] fp32, 16-byte aligned; gamma [m] fp32; x_f16 [m] fp16.
+ *   8 <= m <= 16384, m % 8 == 0; eps finite and >= 0 (else TEAL_ERR_THRESHOLD).
+ *
+ * teal_sparse_gemv_bf16_rmsnorm_multi: y_k = s_{t_k}(x) W_k^T for
+ * k = 0 .. count-1, bitwise what teal_rmsnorm_f16 followed by
+ * teal_sparse_gemv_bf16_multi gives, in one launch and without x travelling
+ * through memory (every thread block computes r from all of h, then forms only
+ * the x_i of its slice).  Arguments as for teal_sparse_gemv_bf16_multi, with
+ * h, gamma, eps and the range of m as above in place of x_f16.
+ */
+teal_status teal_rmsnorm_f16(const float *h, const float *gamma, float eps, void *x_f16, int m,
+                             void *stream);
+teal_status teal_sparse_gemv_bf16_rmsnorm_multi(int count, const void *const *Wt_bf16,
+                                                const float *t, float *const *y, const int *n,
+                                                const float *h, const float *gamma, float eps,
+                                                int m, void *workspace, size_t workspace_bytes,
+                                                void *stream);
+
+/*
  * The W_down step with its input formed on the fly (Appendix A.3:
  * MLP(x) = (SiLU(x W_gate^T) . x W_up^T) W_down^T; Section 4.2 thresholds the
  * intermediate h = SiLU(g) . u like any other input).

@@ -30,7 +30,8 @@ EXPORTS = (
     "teal_sparsify_batch", "teal_sparse_gemv_bf16_batch", "teal_sparse_gemv_bf16_batch_ex",
     "teal_sparse_gemv_w8_multi", "teal_sparse_gemv_w4_multi",
     "teal_swiglu_f16", "teal_sparse_gemv_bf16_swiglu", "teal_sparse_gemv_bf16_batch_multi",
-    "teal_gemv_plan_multi", "teal_survivors_offset",
+    "teal_gemv_plan_multi", "teal_survivors_offset", "teal_rmsnorm_f16",
+    "teal_sparse_gemv_bf16_rmsnorm_multi",
 )
 TEAL_HIST_BINS = 32768
 TEAL_MAX_BATCH = 8
@@ -63,6 +64,12 @@ def load_library():
     lib.teal_version.argtypes = []
     lib.teal_workspace_bytes.restype = sz
     lib.teal_workspace_bytes.argtypes = [i, i]
+    lib.teal_rmsnorm_f16.restype = i
+    lib.teal_rmsnorm_f16.argtypes = [vp, vp, f, vp, i, vp]
+    lib.teal_sparse_gemv_bf16_rmsnorm_multi.restype = i
+    lib.teal_sparse_gemv_bf16_rmsnorm_multi.argtypes = [i, c.POINTER(vp), c.POINTER(f),
+                                                        c.POINTER(vp), c.POINTER(i), vp, vp, f, i,
+                                                        vp, sz, vp]
     lib.teal_survivors_offset.restype = sz
     lib.teal_survivors_offset.argtypes = []
     lib.teal_sparsify.restype = i
@@ -340,6 +347,27 @@ def teal_sparse_gemv_bf16_swiglu(Wt_bf16, gate, up, t, y, m, n, workspace, works
         _ptr(Wt_bf16, 2 * m * n, "Wt"), _ptr(gate, 4 * m, "gate"), _ptr(up, 4 * m, "up"), float(t),
         _ptr(y, 4 * n, "y"), int(m), int(n), _ptr(workspace),
         _nbytes(workspace, workspace_bytes), _stream(stream))
+
+
+def teal_rmsnorm_f16(h, gamma, eps, x_f16, m, stream=None) -> int:
+    return load_library().teal_rmsnorm_f16(_ptr(h, 4 * m, "h"), _ptr(gamma, 4 * m, "gamma"),
+                                           float(eps), _ptr(x_f16, 2 * m, "x"), int(m),
+                                           _stream(stream))
+
+
+def teal_sparse_gemv_bf16_rmsnorm_multi(Wt_list, t_list, y_list, n_list, h, gamma, eps, m,
+                                        workspace, workspace_bytes=None, stream=None) -> int:
+    """count = len(Wt_list) matrices fed by the normalised h; per-matrix lists become host arrays."""
+    count = len(Wt_list)
+    if not (len(t_list) == len(y_list) == len(n_list) == count):
+        raise ValueError("per-matrix lists must have the same length")
+    W = (ctypes.c_void_p * count)(*[_ptr(w, 2 * m * n, "Wt") for w, n in zip(Wt_list, n_list)])
+    Y = (ctypes.c_void_p * count)(*[_ptr(y, 4 * n, "y") for y, n in zip(y_list, n_list)])
+    Tt = (ctypes.c_float * count)(*[float(t) for t in t_list])
+    N = (ctypes.c_int * count)(*[int(n) for n in n_list])
+    return load_library().teal_sparse_gemv_bf16_rmsnorm_multi(
+        count, W, Tt, Y, N, _ptr(h, 4 * m, "h"), _ptr(gamma, 4 * m, "gamma"), float(eps), int(m),
+        _ptr(workspace), _nbytes(workspace, workspace_bytes), _stream(stream))
 
 
 def teal_abs_histogram(x_f16, count, hist, stream=None) -> int:

@@ -93,4 +93,37 @@ hipError_t launch_gemv_bf16_multi(int count, const void *const *Wt, const float 
     return hipGetLastError();
 }
 
+hipError_t launch_gemv_bf16_rmsnorm_multi(int count, const void *const *Wt, const float *t,
+                                          float *const *y, const int *n, const float *h,
+                                          const float *gamma, float eps, int m, float *partial,
+                                          int *counters, const GemvShape &sh, hipStream_t stream)
+{
+    if (m < 8 || m > kMaxNormDim || m % 8 != 0 || sh.waves != kNormWaves || sh.unroll != 4 ||
+        !gemv_shape_supported(sh) || sh.lanes_per_row < 16)
+        return hipErrorInvalidValue;
+    int n_max = 0;
+    for (int k = 0; k < count; ++k) n_max = n[k] > n_max ? n[k] : n_max;
+    const GemvGeometry g = gemv_geometry(m, n_max, sh, FmtBF16::kElemsPerLane, 64);
+    MultiArgs<FmtBF16> ma{};
+    ma.count = count;
+    ma.tile_begin[0] = 0;
+    for (int k = 0; k < count; ++k) {
+        ma.a[k].W = Wt[k];
+        ma.y[k] = y[k];
+        ma.t[k] = t[k];
+        ma.n[k] = n[k];
+        ma.tile_begin[k + 1] = ma.tile_begin[k] + (n[k] + g.tile_cols - 1) / g.tile_cols;
+    }
+    const int tiles = ma.tile_begin[count];
+#define TEAL_LAUNCH_N(LPR)                                                                     \
+    hipLaunchKernelGGL((sparse_gemv_rmsnorm_multi_kernel<FmtBF16, LPR, 4>),                    \
+                       dim3(tiles * g.splits), dim3(kNormWaves * 64), g.lds, stream, ma, h,    \
+                       gamma, eps, partial, counters, m, g.ks, g.tile_cols, g.splits)
+    if (sh.lanes_per_row == 64) TEAL_LAUNCH_N(64);
+    else if (sh.lanes_per_row == 32) TEAL_LAUNCH_N(32);
+    else TEAL_LAUNCH_N(16);
+#undef TEAL_LAUNCH_N
+    return hipGetLastError();
+}
+
 }  // namespace teal

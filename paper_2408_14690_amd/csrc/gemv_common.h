@@ -170,6 +170,136 @@ struct SwigluSource {                 // gate = x W_gate^T and up = x W_up^T, fp
     __device__ __forceinline__ float value(Raw r) const { return swiglu_value(r.x, r.y); }
 };
 
+// ---- the normalised hidden state (the input of W_q/W_k/W_v and W_gate/W_up) ----
+//
+// x_i = gamma_i h_i / sqrt(mean(h^2) + eps), in stated arithmetic because x decides the
+// mask: the squares are exact in binary64 and are added by pairwise summation over the
+// index range padded with zeros to a power of two (halve the range, add the two halves'
+// sums, every addition rounded to binary64); v = ss / m + eps, r = binary32(1 / sqrt(v))
+// in binary64; a = h_i r, b = a gamma_i in binary32, each rounded; x_i = binary16(b).
+//
+// A block of kNormWaves wavefronts sums kNormChunk entries per pass, thread T entries
+// 8T .. 8T+7 of the chunk: index bits 0-2 are added inside the thread, bits 3-8 across the
+// wavefront's lanes, bits 9-11 across the wavefronts, the rest across chunks, which is
+// the halving order read from the leaves up.  Adding zero is exact, so padding further
+// than the next power of two changes nothing.
+constexpr int kNormWaves = 8;
+constexpr int kNormChunk = kNormWaves * 64 * 8;
+constexpr int kMaxNormChunks = 4;
+constexpr int kMaxNormDim = kNormChunk * kMaxNormChunks;
+
+template <int CTRL>
+__device__ __forceinline__ double lane_exchange(double v)
+{
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, 0xF, 0xF, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, 0xF, 0xF, false);
+    return __hiloint2double(hi, lo);
+}
+
+__device__ __forceinline__ double read_lane(double v, int lane)
+{
+    return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), lane),
+                            __builtin_amdgcn_readlane(__double2loint(v), lane));
+}
+
+// Sum over the 64 lanes in halving order (lane l next to l ^ 1, pairs next to pairs, ...).
+// After each step all lanes of a group hold the group's sum, so the partner group may be
+// read through a mirror instead of an exchange; a + b == b + a bit for bit.  All 64 lanes
+// must be active.
+__device__ __forceinline__ double wave_tree_sum(double s)
+{
+    s += lane_exchange<0xB1>(s);      // quad_perm [1,0,3,2]: lane ^ 1
+    s += lane_exchange<0x4E>(s);      // quad_perm [2,3,0,1]: lane ^ 2
+    s += lane_exchange<0x141>(s);     // row_half_mirror: the other quad of each 8 lanes
+    s += lane_exchange<0x140>(s);     // row_mirror: the other half of each row of 16
+    const double r0 = read_lane(s, 0), r1 = read_lane(s, 16);
+    const double r2 = read_lane(s, 32), r3 = read_lane(s, 48);
+    return (r0 + r1) + (r2 + r3);
+}
+
+// Sums of squares of the first C chunks' entries, one per wavefront and chunk, into
+// wave_sums[c * kNormWaves + w].  All of a thread's loads are issued before the first is
+// used; a chunk past the end of h is loaded from a clamped position and counted as zeros.
+template <int C>
+__device__ __forceinline__ void chunk_wave_sums(const float *__restrict__ h, int m,
+                                                double *wave_sums)
+{
+#pragma clang fp contract(off)
+    const int lane = threadIdx.x & 63;
+    const int w = threadIdx.x >> 6;
+    float4 v[C][2];
+#pragma unroll
+    for (int c = 0; c < C; ++c) {
+        const int j = min(c * kNormChunk + (int)threadIdx.x * 8, m - 8);
+        const float4 *p = reinterpret_cast<const float4 *>(h + j);
+        v[c][0] = p[0];
+        v[c][1] = p[1];
+    }
+#pragma unroll
+    for (int c = 0; c < C; ++c) {
+        const bool live = c * kNormChunk + (int)threadIdx.x * 8 < m;
+        const float e[8] = {v[c][0].x, v[c][0].y, v[c][0].z, v[c][0].w,
+                            v[c][1].x, v[c][1].y, v[c][1].z, v[c][1].w};
+        double q[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const double d = live ? (double)e[k] : 0.0;
+            q[k] = d * d;
+        }
+        double s = ((q[0] + q[1]) + (q[2] + q[3])) + ((q[4] + q[5]) + (q[6] + q[7]));
+        s = wave_tree_sum(s);
+        if (lane == 0) wave_sums[c * kNormWaves + w] = s;
+    }
+}
+
+// r = binary32(1 / sqrt(mean(h^2) + eps)) as stated above.  All kNormWaves * 64 threads of
+// the block call it; wave_sums is LDS for kMaxNormChunks * kNormWaves doubles.  Needs
+// 8 <= m <= kMaxNormDim, m % 8 == 0, h 16-byte aligned.  Contains one barrier.
+__device__ __forceinline__ float rms_scale(const float *__restrict__ h, int m, float eps,
+                                           double *wave_sums)
+{
+#pragma clang fp contract(off)
+    const int chunks = (m + kNormChunk - 1) / kNormChunk;      // block-uniform
+    if (chunks == 1) chunk_wave_sums<1>(h, m, wave_sums);
+    else if (chunks == 2) chunk_wave_sums<2>(h, m, wave_sums);
+    else chunk_wave_sums<4>(h, m, wave_sums);
+    __syncthreads();
+    double cs[kMaxNormChunks];
+#pragma unroll
+    for (int c = 0; c < kMaxNormChunks; ++c) {
+        const double *ws = wave_sums + c * kNormWaves;
+        cs[c] = c < (chunks == 3 ? 4 : chunks)
+                    ? ((ws[0] + ws[1]) + (ws[2] + ws[3])) + ((ws[4] + ws[5]) + (ws[6] + ws[7]))
+                    : 0.0;
+    }
+    const double ss = (cs[0] + cs[1]) + (cs[2] + cs[3]);
+    const double var = ss / (double)m + (double)eps;
+    return (float)(1.0 / sqrt(var));
+}
+
+__device__ __forceinline__ float rmsnorm_value(float h, float gamma, float r)
+{
+#pragma clang fp contract(off)
+    float a = h * r;
+    asm volatile("" : "+v"(a));       // a and b are rounded to binary32 one by one,
+    float b = a * gamma;
+    asm volatile("" : "+v"(b));       // and b to binary16 after that (no fused forms)
+    return __half2float(__float2half_rn(b));
+}
+
+struct RmsnormSource {                // hidden state and norm weights, fp32 in memory
+    static constexpr bool kHeavy = false;
+    typedef float2 Raw;
+    const float *h;
+    const float *gamma;
+    float r;                          // from rms_scale
+    __device__ __forceinline__ Raw load(int i) const { return make_float2(h[i], gamma[i]); }
+    __device__ __forceinline__ float value(Raw raw) const
+    {
+        return rmsnorm_value(raw.x, raw.y, r);
+    }
+};
+
 // Definition 1 on one element: fp16 -> fp32 is exact, the compare is fp32.
 __device__ __forceinline__ bool survives(float xv, float t) { return fabsf(xv) > t; }
 
@@ -511,10 +641,9 @@ struct MultiArgs {
     int count;
 };
 
-template <class F, int LPR, int WAVES, int U>
-__global__ __launch_bounds__(WAVES * 64) void sparse_gemv_multi_kernel(
-    MultiArgs<F> ma, const __half *__restrict__ x, float *partial, int *counters, int m, int ks,
-    int tile_cols, int splits)
+template <class F, int LPR, int WAVES, int U, class XS>
+__device__ __forceinline__ void multi_block(const MultiArgs<F> &ma, const XS &x, float *partial,
+                                            int *counters, int m, int ks, int tile_cols, int splits)
 {
     const int tiles = ma.tile_begin[ma.count];
     const int gtile = blockIdx.x % tiles;
@@ -528,10 +657,33 @@ __global__ __launch_bounds__(WAVES * 64) void sparse_gemv_multi_kernel(
             k = j;
         }
     }
-    gemv_block<F, LPR, WAVES, U>(ma.a[k], HalfSource{x}, ma.t[k], partial + partial_off,
+    gemv_block<F, LPR, WAVES, U>(ma.a[k], x, ma.t[k], partial + partial_off,
                                  counters + ma.tile_begin[k], ma.y[k], m, ma.n[k], ks,
                                  gtile - ma.tile_begin[k], s, tile_cols, splits,
                                  survivor_report(counters, k, splits));
+}
+
+template <class F, int LPR, int WAVES, int U>
+__global__ __launch_bounds__(WAVES * 64) void sparse_gemv_multi_kernel(
+    MultiArgs<F> ma, const __half *__restrict__ x, float *partial, int *counters, int m, int ks,
+    int tile_cols, int splits)
+{
+    multi_block<F, LPR, WAVES, U>(ma, HalfSource{x}, partial, counters, m, ks, tile_cols, splits);
+}
+
+// The grouped launch with its shared input formed in the kernel from the hidden state
+// before the normalisation layer: one launch instead of a normalisation kernel plus the
+// products, and the normalised state never travels through HBM.  Every block reads all
+// of h (from L2 after the first block of its XCD) for the scale, then only its slice.
+template <class F, int LPR, int U>
+__global__ __launch_bounds__(kNormWaves * 64) void sparse_gemv_rmsnorm_multi_kernel(
+    MultiArgs<F> ma, const float *__restrict__ h, const float *__restrict__ gamma, float eps,
+    float *partial, int *counters, int m, int ks, int tile_cols, int splits)
+{
+    __shared__ double wave_sums[kMaxNormChunks * kNormWaves];
+    const float r = rms_scale(h, m, eps, wave_sums);
+    multi_block<F, LPR, kNormWaves, U>(ma, RmsnormSource{h, gamma, r}, partial, counters, m, ks,
+                                       tile_cols, splits);
 }
 
 // Host-side launch geometry shared by the formats.

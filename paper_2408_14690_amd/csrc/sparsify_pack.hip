@@ -65,6 +65,19 @@ __global__ __launch_bounds__(256) void swiglu_f16_kernel(const float *__restrict
     if (i < m) h[i] = __float2half_rn(swiglu_value(gate[i], up[i]));
 }
 
+// x[i] = fp16(gamma[i] * h[i] * r): the normalisation that produces the input of
+// W_q/W_k/W_v and W_gate/W_up on its own, in the arithmetic the fused kernel uses.
+// Every block computes the scale from all of h and writes its 512 entries.
+__global__ __launch_bounds__(kNormWaves * 64) void rmsnorm_f16_kernel(
+    const float *__restrict__ h, const float *__restrict__ gamma, float eps,
+    __half *__restrict__ x, int m)
+{
+    __shared__ double wave_sums[kMaxNormChunks * kNormWaves];
+    const float r = rms_scale(h, m, eps, wave_sums);
+    const int i = (int)(blockIdx.x * (kNormWaves * 64) + threadIdx.x);
+    if (i < m) x[i] = __float2half_rn(rmsnorm_value(h[i], gamma[i], r));
+}
+
 constexpr int kPackTile = 64;
 
 // 64 x 64 tile transpose through LDS: reads run along m (contiguous in W),
@@ -105,6 +118,16 @@ hipError_t launch_swiglu_f16(const float *gate, const float *up, void *h_f16, in
     if (m == 0) return hipSuccess;
     hipLaunchKernelGGL(swiglu_f16_kernel, dim3((unsigned)((m + 255) / 256)), dim3(256), 0, stream,
                        gate, up, static_cast<__half *>(h_f16), m);
+    return hipGetLastError();
+}
+
+hipError_t launch_rmsnorm_f16(const float *h, const float *gamma, float eps, void *x_f16, int m,
+                              hipStream_t stream)
+{
+    if (m < 8 || m > kMaxNormDim || m % 8 != 0) return hipErrorInvalidValue;
+    const int threads = kNormWaves * 64;
+    hipLaunchKernelGGL(rmsnorm_f16_kernel, dim3((unsigned)((m + threads - 1) / threads)),
+                       dim3(threads), 0, stream, h, gamma, eps, static_cast<__half *>(x_f16), m);
     return hipGetLastError();
 }
 

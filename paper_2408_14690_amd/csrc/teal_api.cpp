@@ -17,6 +17,7 @@ constexpr int kComputeUnits = 256;
 bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
 bool threshold_ok(float t) { return std::isfinite(t) && t >= 0.0f; }
+bool norm_eps_ok(float eps) { return std::isfinite(eps) && eps >= 0.0f; }
 
 int max_splits_for(int m)
 {
@@ -371,6 +372,49 @@ teal_status teal_sparse_gemv_bf16_multi(int count, const void *const *Wt_bf16, c
     return from_hip(teal::launch_gemv_bf16_multi(count, Wt_bf16, t, y, n, x_f16, m,
                                                  ws_partials(workspace, m), ws_counters(workspace),
                                                  sh, static_cast<hipStream_t>(stream)));
+}
+
+teal_status teal_rmsnorm_f16(const float *h, const float *gamma, float eps, void *x_f16, int m,
+                             void *stream)
+{
+    if (m < 8 || m > teal::kMaxNormInput || m % 8 != 0) return TEAL_ERR_SHAPE;
+    if (!h || !gamma || !x_f16) return TEAL_ERR_NULL;
+    if (!aligned(h, 16) || !aligned(gamma, 4) || !aligned(x_f16, 2)) return TEAL_ERR_ALIGN;
+    if (!norm_eps_ok(eps)) return TEAL_ERR_THRESHOLD;
+    return from_hip(teal::launch_rmsnorm_f16(h, gamma, eps, x_f16, m,
+                                             static_cast<hipStream_t>(stream)));
+}
+
+teal_status teal_sparse_gemv_bf16_rmsnorm_multi(int count, const void *const *Wt_bf16,
+                                                const float *t, float *const *y, const int *n,
+                                                const float *h, const float *gamma, float eps,
+                                                int m, void *workspace, size_t workspace_bytes,
+                                                void *stream)
+{
+    if (count < 1 || count > teal::kMaxMatrices) return TEAL_ERR_UNSUPPORTED;
+    if (!Wt_bf16 || !t || !y || !n || !h || !gamma || !workspace) return TEAL_ERR_NULL;
+    long long n_total = 0;
+    for (int k = 0; k < count; ++k) {
+        if (!Wt_bf16[k] || !y[k]) return TEAL_ERR_NULL;
+        if (n[k] < 8 || n[k] > teal::kMaxDim || n[k] % 8 != 0) return TEAL_ERR_SHAPE;
+        n_total += n[k];
+    }
+    if (m < 8 || m > teal::kMaxNormInput || m % 8 != 0 || n_total > teal::kMaxDim)
+        return TEAL_ERR_SHAPE;
+    for (int k = 0; k < count; ++k)
+        if (!aligned(Wt_bf16[k], 16) || !aligned(y[k], 4)) return TEAL_ERR_ALIGN;
+    if (!aligned(h, 16) || !aligned(gamma, 4) || !aligned(workspace, kAlignWorkspace))
+        return TEAL_ERR_ALIGN;
+    for (int k = 0; k < count; ++k)
+        if (!threshold_ok(t[k])) return TEAL_ERR_THRESHOLD;
+    if (!norm_eps_ok(eps)) return TEAL_ERR_THRESHOLD;
+    if (workspace_bytes < teal_workspace_bytes(m, (int)n_total)) return TEAL_ERR_WORKSPACE;
+    // The launch shape of teal_sparse_gemv_bf16_multi: same sums, bit for bit.
+    const GemvShape sh = count > 1 ? auto_shape_multi(m, n, count, 8, 16, 64, 64)
+                                   : auto_shape(m, (int)n_total, 8, 16, 64, 64);
+    return from_hip(teal::launch_gemv_bf16_rmsnorm_multi(
+        count, Wt_bf16, t, y, n, h, gamma, eps, m, ws_partials(workspace, m),
+        ws_counters(workspace), sh, static_cast<hipStream_t>(stream)));
 }
 
 size_t teal_workspace_bytes_batch(int m, int n, int batch)

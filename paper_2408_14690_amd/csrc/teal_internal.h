@@ -13,6 +13,7 @@ constexpr int kMaxSlice = 4096;     // most input channels one block compacts (L
 constexpr int kMaxDim = 1 << 24;    // largest m or n accepted
 constexpr int kMaxMatrices = 4;     // matrices per fused launch
 constexpr int kMinTile = 64;        // narrowest output tile of any kernel variant
+constexpr int kMaxNormInput = 16384; // longest hidden state the fused normalisation takes
 constexpr int kMaxBatch = 8;        // rows of a small batch (Section 5.4.4)
 constexpr int kMaxSliceBatch = 2048;  // most input channels one block compacts for a batch
 // Head of the workspace: one arrival counter per output tile (zero between calls).
@@ -44,6 +45,15 @@ hipError_t launch_gemv_bf16_swiglu(const void *Wt, const float *gate, const floa
                                    float *y, int m, int n, float *partial, int *counters,
                                    const GemvShape &shape, hipStream_t stream);
 
+// The grouped bf16 launch with its shared input formed from the hidden state h before the
+// normalisation layer and the layer's weights gamma.  8 <= m <= 16384, m % 8 == 0; shapes
+// with 8 wavefronts, 4 loads per batch and 16, 32 or 64 lanes per row.
+hipError_t launch_gemv_bf16_rmsnorm_multi(int count, const void *const *Wt, const float *t,
+                                          float *const *y, const int *n, const float *h,
+                                          const float *gamma, float eps, int m, float *partial,
+                                          int *counters, const GemvShape &sh, hipStream_t stream);
+hipError_t launch_rmsnorm_f16(const float *h, const float *gamma, float eps, void *x_f16, int m,
+                              hipStream_t stream);
 hipError_t launch_swiglu_f16(const float *gate, const float *up, void *h_f16, int m,
                              hipStream_t stream);
 

@@ -374,3 +374,33 @@ def test_binding_refuses_tensors_smaller_than_the_call_touches():
     with pytest.raises(ValueError, match="gate"):
         T.teal_sparse_gemv_bf16_swiglu(wt, torch.zeros(m - 1), torch.zeros(m), 0.5, y, m, 64, ws,
                                        stream=0)
+
+
+def test_rmsnorm_argument_errors():
+    H, G = 1 << 20, 2 << 20                       # fake 16-byte aligned device addresses
+    assert T.teal_rmsnorm_f16(None, G, 1e-5, X, 4096, stream=0) == T.TEAL_ERR_NULL
+    assert T.teal_rmsnorm_f16(H, G, 1e-5, X, 0, stream=0) == T.TEAL_ERR_SHAPE
+    assert T.teal_rmsnorm_f16(H, G, 1e-5, X, 4100, stream=0) == T.TEAL_ERR_SHAPE        # m % 8
+    assert T.teal_rmsnorm_f16(H, G, 1e-5, X, 16392, stream=0) == T.TEAL_ERR_SHAPE       # > 16384
+    assert T.teal_rmsnorm_f16(H + 4, G, 1e-5, X, 4096, stream=0) == T.TEAL_ERR_ALIGN
+    assert T.teal_rmsnorm_f16(H, G, -1.0, X, 4096, stream=0) == T.TEAL_ERR_THRESHOLD
+    assert T.teal_rmsnorm_f16(H, G, float("nan"), X, 4096, stream=0) == T.TEAL_ERR_THRESHOLD
+
+    def call(count=2, t=(0.5, 0.5), n=(4096, 1024), h=H, gamma=G, eps=1e-5, m=4096, ws=WS,
+             ws_bytes=BIG, w=None, y=None):
+        w = [W] * count if w is None else w
+        y = [Y] * count if y is None else y
+        return T.teal_sparse_gemv_bf16_rmsnorm_multi(w, list(t), y, list(n), h, gamma, eps, m, ws,
+                                                     ws_bytes, stream=0)
+
+    assert call(h=None) == T.TEAL_ERR_NULL
+    assert call(gamma=None) == T.TEAL_ERR_NULL
+    assert call(w=[W, None]) == T.TEAL_ERR_NULL
+    assert call(m=4100) == T.TEAL_ERR_SHAPE
+    assert call(m=32768) == T.TEAL_ERR_SHAPE
+    assert call(n=(4096, 1020)) == T.TEAL_ERR_SHAPE
+    assert call(h=H + 8) == T.TEAL_ERR_ALIGN
+    assert call(t=(0.5, -1.0)) == T.TEAL_ERR_THRESHOLD
+    assert call(eps=float("inf")) == T.TEAL_ERR_THRESHOLD
+    assert call(ws_bytes=64) == T.TEAL_ERR_WORKSPACE
+    assert call(count=5, t=(0.5,) * 5, n=(64,) * 5) == T.TEAL_ERR_UNSUPPORTED

@@ -1,0 +1,153 @@
+"""GPU parity of the grouped call with its input formed in the kernel from the hidden state
+before the normalisation layer (the input of W_q/W_k/W_v and W_gate/W_up, Appendix A.3):
+the normalised state x must equal the oracle's bit for bit (it decides the mask), the mask
+of x likewise, and every y must agree to relative L2 <= 2e-3."""
+import numpy as np
+import pytest
+
+import teal_inputs as ti
+from oracle import teal_oracle as orc
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+TOL_BF16 = 2e-3
+TIGHT = 2e-5
+EPS = float(np.float32(1e-5))
+
+
+@pytest.fixture(scope="module")
+def T():
+    import paper_2408_14690_amd as T
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    T.load_library()
+    return T
+
+
+def dev(a):
+    a = np.ascontiguousarray(a)
+    if a.dtype in (np.uint16, np.float16):
+        return torch.from_numpy(a.view(np.int16)).cuda()
+    return torch.from_numpy(a).cuda()
+
+
+def rel_l2(got, want):
+    den = np.linalg.norm(want)
+    if den == 0.0:
+        return 0.0 if not np.any(got) else np.inf
+    return float(np.linalg.norm(got.astype(np.float64) - want) / den)
+
+
+def gpu_x(T, h, gamma, eps):
+    m = h.size
+    x = torch.full((m,), 0x7E00, dtype=torch.int16, device="cuda")
+    T.check(T.teal_rmsnorm_f16(dev(h), dev(gamma), eps, x, m))
+    torch.cuda.synchronize()
+    return x.cpu().numpy().view(np.uint16)
+
+
+@pytest.mark.parametrize("m", [8, 64, 1000, 2056, 4096, 4104, 5000, 8192, 11008, 12288, 14336,
+                               16384])
+def test_normalised_state_bit_exact(T, m):
+    for seed in (1, 2):
+        h, gamma = ti.norm_inputs(m, 50 * seed + m)
+        for eps in (EPS, 0.0):
+            want = orc.rmsnorm_f16(h, gamma, eps).view(np.uint16)
+            got = gpu_x(T, h, gamma, eps)
+            assert np.array_equal(got, want), (m, seed, eps)
+
+
+def test_normalised_state_on_special_inputs(T):
+    one = np.ones(8, np.float32)
+    # the hand-worked summation tree: squares 2^54, 1, 1, 1, 4, 1, 1, 1 sum to 2^54 + 8
+    h = np.array([2.0 ** 27, 1, 1, 1, 2, 1, 1, 1], np.float32)
+    assert np.array_equal(gpu_x(T, h, one, 0.0), orc.rmsnorm_f16(h, one, 0.0).view(np.uint16))
+    # the rounding case: h * r rounds to 1, gamma is a binary16 tie (m = 8: pad with +-7)
+    h = np.array([7, -7, 7, 7, -7, 7, 7, -7], np.float32)
+    gamma = np.full(8, 1580.5 / 1024.0, np.float32)
+    got = gpu_x(T, h, gamma, 0.0).view(np.float16)
+    assert np.array_equal(np.abs(got.astype(np.float32)), np.full(8, 1580.0 / 1024.0, np.float32))
+    assert np.array_equal(got.view(np.uint16), orc.rmsnorm_f16(h, gamma, 0.0).view(np.uint16))
+    # very large and very small entries: the squares stay exact in binary64
+    h = np.array([3e38, -1e-30, 5.0, 0.0, -0.0, 1e-45, 2.5e30, -3e38], np.float32)
+    for eps in (0.0, EPS):
+        assert np.array_equal(gpu_x(T, h, one, eps), orc.rmsnorm_f16(h, one, eps).view(np.uint16))
+    # all zeros: x = 0 with eps > 0; with eps = 0 the scale is infinite and 0 * inf is NaN
+    z = np.zeros(4096, np.float32)
+    g = np.ones(4096, np.float32)
+    assert not gpu_x(T, z, g, EPS).view(np.float16).any()
+    assert np.isnan(gpu_x(T, z, g, 0.0).view(np.float16)).all()
+    assert np.isnan(orc.rmsnorm_f16(z, g, 0.0)).all()
+    # a NaN in h poisons every entry, a NaN in gamma only its own
+    h, gamma = ti.norm_inputs(4096, 77)
+    hn = h.copy()
+    hn[1234] = np.nan
+    assert np.isnan(gpu_x(T, hn, gamma, EPS).view(np.float16)).all()
+    gn = gamma.copy()
+    gn[1234] = np.nan
+    got = gpu_x(T, h, gn, EPS)
+    want = orc.rmsnorm_f16(h, gn, EPS).view(np.uint16)
+    assert np.isnan(got.view(np.float16)[1234])
+    keep = np.arange(4096) != 1234
+    assert np.array_equal(got[keep], want[keep])
+
+
+CASES = [
+    ("llama q,k,v", [4096, 1024, 1024], 4096, [0.5, 0.4, 0.25]),
+    ("llama2 gate,up", [11008, 11008], 4096, [0.5, 0.5]),
+    ("ragged", [264, 72, 8], 1000, [0.0, 0.5, 0.9]),
+    ("single", [1032], 2056, [0.5]),
+    ("70b q,k,v", [8192, 1024, 1024], 8192, [0.5, 0.5, 0.4]),
+    ("three chunks", [520, 264], 12288, [0.5, 1.0]),
+]
+
+
+@pytest.mark.parametrize("name,ns,m,ps", CASES, ids=[c[0] for c in CASES])
+def test_fused_grouped_product(T, name, ns, m, ps):
+    h, gamma = ti.norm_inputs(m, 600 + m)
+    hd, gd = dev(h), dev(gamma)
+    x = orc.rmsnorm_f16(h, gamma, EPS)
+    ts = [ti.quantile_threshold(x, p) for p in ps]
+    ws_host = [ti.weights_bf16(n, m, seed=3000 * k + n + m) for k, n in enumerate(ns)]
+    wts = [dev(ti.to_input_channel_major(w)) for w in ws_host]
+    ws = torch.zeros(T.teal_workspace_bytes(m, sum(ns)), dtype=torch.uint8, device="cuda")
+    ys = [torch.full((n,), float("nan"), dtype=torch.float32, device="cuda") for n in ns]
+    T.check(T.teal_sparse_gemv_bf16_rmsnorm_multi(wts, ts, ys, ns, hd, gd, EPS, m, ws))
+    torch.cuda.synchronize()
+    off = T.teal_survivors_offset()
+    kept = ws[off:off + 4 * len(ns)].view(torch.int32).cpu().tolist()
+    assert kept == [orc.sparsify(x, t)[3] for t in ts]
+    for k, n in enumerate(ns):
+        got = ys[k].cpu().numpy()
+        want = orc.sparse_gemv_bf16_rmsnorm(ws_host[k], h, gamma, EPS, ts[k])
+        assert rel_l2(got, want) <= TIGHT, (name, k)
+        assert rel_l2(got, want) <= TOL_BF16
+    # bitwise the two-launch path: normalisation kernel, then the grouped call
+    xd = torch.empty(m, dtype=torch.int16, device="cuda")
+    T.check(T.teal_rmsnorm_f16(hd, gd, EPS, xd, m))
+    ys2 = [torch.full((n,), float("nan"), dtype=torch.float32, device="cuda") for n in ns]
+    T.check(T.teal_sparse_gemv_bf16_multi(wts, ts, ys2, ns, xd, m, ws))
+    torch.cuda.synchronize()
+    assert np.array_equal(xd.cpu().numpy().view(np.uint16), x.view(np.uint16))
+    for a, b in zip(ys, ys2):
+        assert torch.equal(a, b)
+    # the mask of the normalised state, bit-exact
+    mask = torch.empty(m, dtype=torch.uint8, device="cuda")
+    T.check(T.teal_sparsify(xd, m, ts[0], mask, None, None))
+    torch.cuda.synchronize()
+    assert np.array_equal(mask.cpu().numpy(), orc.sparsify(x, ts[0])[1])
+
+
+def test_fused_grouped_product_with_nan_in_the_hidden_state(T):
+    m, ns = 4096, [1024, 264]
+    h, gamma = ti.norm_inputs(m, 88)
+    h[17] = np.nan                         # every x is NaN: nothing survives, y = 0
+    wts = [dev(ti.to_input_channel_major(ti.weights_bf16(n, m, seed=n))) for n in ns]
+    ws = torch.zeros(T.teal_workspace_bytes(m, sum(ns)), dtype=torch.uint8, device="cuda")
+    ys = [torch.full((n,), float("nan"), dtype=torch.float32, device="cuda") for n in ns]
+    T.check(T.teal_sparse_gemv_bf16_rmsnorm_multi(wts, [0.0, 0.5], ys, ns, dev(h), dev(gamma),
+                                                  EPS, m, ws))
+    torch.cuda.synchronize()
+    assert not ys[0].any().item() and not ys[1].any().item()
+    off = T.teal_survivors_offset()
+    assert ws[off:off + 8].view(torch.int32).cpu().tolist() == [0, 0]
