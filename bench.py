@@ -4,7 +4,7 @@
     python bench.py [--gpus 1] [--steps K] [--warmup W]
                     [--workload llama2_7b|llama3_8b|llama_70b] [--format bf16|w8|w4]
                     [--sparsities 0.5,0.4,0] [--layers L] [--unfused] [--batch B]
-                    [--calibration] [--swiglu] [--graph]
+                    [--calibration] [--swiglu] [--rmsnorm] [--graph]
 
 A step is one pass of the whole hot path over a synthetic decoder block at
 batch 1: for each of the seven projections, threshold the hidden state, compact
@@ -23,7 +23,8 @@ a stack of L blocks with their own weights and states (the 80-block
 70B-shaped stack is 137 GB resident), and no copies are needed.  --batch B
 runs the small-batch variant (one mask per batch from the averaged magnitude),
 --calibration the threshold calibration pass, --swiglu the W_down step with its
-input formed in the kernel.
+input formed in the kernel, --rmsnorm the q+k+v and gate+up steps with the
+normalisation of their input formed in the kernel.
 
 Prints ONE JSON line.  More than one GPU is not supported.
 """
@@ -503,6 +504,113 @@ def run_swiglu(T, torch, args) -> int:
     return 0
 
 
+def run_rmsnorm(T, torch, args) -> int:
+    """The two grouped calls that read a normalised hidden state (q+k+v and gate+up,
+    Appendix A.3) including the normalisation, two ways: the normalisation kernel followed
+    by the grouped sparse GEMV (two launches, x written to and read back from memory), and
+    the fused call."""
+    shapes = ti.LAYER_SHAPES[args.workload]
+    cfg = ti.CONFIG_INDEX[args.workload]
+    eps = float(np.float32(1e-5))
+    from oracle import teal_oracle as orc            # harness: x on the host only to pick t
+    stream = torch.cuda.current_stream().cuda_stream
+    sparsities = [float(v) for v in args.sparsities.split(",")]
+    if 0.0 not in sparsities:
+        sparsities.append(0.0)
+    head = sparsities[0]
+    out_groups, rel_worst = {}, 0.0
+    for gname, projs in (("q+k+v", ("q", "k", "v")), ("gate+up", ("gate", "up"))):
+        m = shapes[projs[0]][1]
+        ns = [shapes[pj][0] for pj in projs]
+        h, gamma = ti.norm_inputs(m, ti.x_seed(cfg, 0, projs[0]))
+        x = orc.rmsnorm_f16(h, gamma, eps)
+        ws_host = [ti.weights_bf16(n, m, ti.weight_seed(cfg, 0, pj)) for n, pj in zip(ns, projs)]
+        group_bytes = sum(ns) * m * 2
+        copies = max(2, -(-CACHE_DEFEAT_BYTES // group_bytes))
+        packed = []
+        for w, n in zip(ws_host, ns):
+            wd = torch.from_numpy(w.view(np.int16)).cuda()
+            wt0 = torch.empty((m, n), dtype=torch.int16, device="cuda")
+            T.check(T.teal_pack_bf16(wd, wt0, m, n))
+            packed.append([wt0] + [wt0.clone() for _ in range(copies - 1)])
+        hd, gd = torch.from_numpy(h).cuda(), torch.from_numpy(gamma).cuda()
+        xd = torch.empty(m, dtype=torch.int16, device="cuda")
+        ys = [torch.empty(n, dtype=torch.float32, device="cuda") for n in ns]
+        ws = torch.zeros(T.teal_workspace_bytes(m, sum(ns)), dtype=torch.uint8, device="cuda")
+        wlists = [[packed[j][c] for j in range(len(ns))] for c in range(copies)]
+
+        def two_launch(k, ts):
+            T.teal_rmsnorm_f16(hd, gd, eps, xd, m, stream)
+            T.check(T.teal_sparse_gemv_bf16_multi(wlists[k % copies], ts, ys, ns, xd, m, ws,
+                                                  stream=stream))
+
+        def fused(k, ts):
+            T.check(T.teal_sparse_gemv_bf16_rmsnorm_multi(wlists[k % copies], ts, ys, ns, hd, gd,
+                                                          eps, m, ws, stream=stream))
+
+        def timed(fn, ts):
+            for k in range(args.warmup):
+                fn(k, ts)
+            torch.cuda.synchronize()
+            start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            start.record()
+            for k in range(args.steps):
+                fn(k, ts)
+            stop.record()
+            torch.cuda.synchronize()
+            return start.elapsed_time(stop) * 1e-3 / args.steps
+
+        detail, sec_f = {}, {}
+        for p in sparsities:
+            t = ti.quantile_threshold(x, p)
+            ts = [t] * len(ns)
+            nnz = int(np.count_nonzero(np.abs(x.astype(np.float32)) > np.float32(t)))
+            sf, s2 = timed(fused, ts), timed(two_launch, ts)
+            sec_f[p] = sf
+            b = nnz * sum(ns) * 2 + 8 * m + 4 * sum(ns)     # surviving rows + h + gamma (fp32) + y
+            detail[pct(p)] = {"nnz": nnz, "fused_us": sf * 1e6, "two_launch_us": s2 * 1e6,
+                              "saved_us": (s2 - sf) * 1e6, "effective_bytes": b,
+                              "effective_GBps": b / sf / 1e9,
+                              "frac_of_hbm_peak": b / sf / 1e9 / HBM_PEAK_GBS}
+        for p in sparsities:
+            detail[pct(p)]["speedup_vs_dense"] = sec_f[0.0] / sec_f[p]
+        # check the fused result against the oracle once
+        t = ti.quantile_threshold(x, head)
+        fused(0, [t] * len(ns))
+        torch.cuda.synchronize()
+        for w, y in zip(ws_host, ys):
+            want = orc.sparse_gemv_bf16_rmsnorm(w, h, gamma, eps, t)
+            rel = float(np.linalg.norm(y.cpu().numpy().astype(np.float64) - want) / np.linalg.norm(want))
+            rel_worst = max(rel_worst, rel)
+        out_groups[gname] = {"n": ns, "m": m, "weight_copies_walked": copies, **detail}
+        del packed, wlists
+        torch.cuda.empty_cache()
+    us = sum(g[pct(head)]["fused_us"] for g in out_groups.values())
+    us2 = sum(g[pct(head)]["two_launch_us"] for g in out_groups.values())
+    b = sum(g[pct(head)]["effective_bytes"] for g in out_groups.values())
+    gbps = b / us / 1e3
+    out = {
+        "metric": f"q+k+v and gate+up steps with the normalisation of their input formed in the "
+                  f"kernel, effective HBM GB/s at {pct(head)} sparsity",
+        "value": gbps, "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": us * 1e-3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{args.workload}-shaped q+k+v and gate+up groups (bf16), input "
+                               f"x = fp16(gamma * h * rsqrt(mean(h^2) + 1e-5)) from fp32 h ~ "
+                               f"N(0, 2.5^2) with 1 in 512 channels x 40, gamma ~ 0.5 + 0.1 N(0,1); "
+                               f"t at the {pct(head)} quantile of |x|"},
+        "roofline": {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": gbps / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "sparse_gemv_rmsnorm_multi_kernel<FmtBF16> (2 launches per step)",
+                     "bytes_per_launch_avg": b / 2, "kernel_avg_us": us / 2},
+        "two_launch_us_per_step": us2, "saved_us_per_step": us2 - us,
+        "detail": out_groups,
+        "rel_l2_vs_oracle_worst": rel_worst,
+    }
+    print(json.dumps(out))
+    return 0
+
+
 def pct(p: float) -> str:
     return f"{int(round(p * 100))}%"
 
@@ -528,6 +636,9 @@ def main() -> int:
                          "mask of the averaged magnitude (Section 5.4.4); bf16 only. 0 = one state")
     ap.add_argument("--graph", action="store_true",
                     help="also time the headline pass replayed from a captured HIP graph")
+    ap.add_argument("--rmsnorm", action="store_true",
+                    help="time the q+k+v and gate+up steps with the normalisation of their input "
+                         "formed in the kernel against the two-launch path (Appendix A.3)")
     ap.add_argument("--swiglu", action="store_true",
                     help="time the W_down step with its input formed from gate and up in the kernel "
                          "against the two-launch path (Appendix A.3)")
@@ -554,6 +665,8 @@ def main() -> int:
     T.load_library()
     if args.swiglu:
         return run_swiglu(T, torch, args)
+    if args.rmsnorm:
+        return run_rmsnorm(T, torch, args)
     if args.calibration:
         if args.calibration_tokens % 64 or args.calibration_tokens <= 0:
             print("bench.py: --calibration-tokens must be a positive multiple of 64", file=sys.stderr)

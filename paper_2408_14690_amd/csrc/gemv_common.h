@@ -119,12 +119,16 @@ __device__ __forceinline__ void report_total(const SurvivorReport &r, int splits
 // Where a block's activations come from.  A source loads what it needs for
 // channel i (load) and turns it into an fp32 value that is exactly an fp16 value
 // (value); kHeavy says that value() is worth skipping for segments past the slice.
+// Between the loads and the first value() every thread of the block calls prepare()
+// once: block-wide work whose result value() needs (it may contain barriers) runs
+// there, with the slice's own loads already in flight.
 struct HalfSource {                   // the hidden state itself, fp16 in memory
     static constexpr bool kHeavy = false;
     typedef __half Raw;
     const __half *x;
     __device__ __forceinline__ Raw load(int i) const { return x[i]; }
-    __device__ __forceinline__ float value(Raw r) const { return __half2float(r); }
+    __device__ __forceinline__ float prepare() const { return 0.f; }
+    __device__ __forceinline__ float value(Raw r, float) const { return __half2float(r); }
 };
 
 // SiLU(g) * u rounded to fp16 (Appendix A.3: the input of W_down), in stated
@@ -167,7 +171,8 @@ struct SwigluSource {                 // gate = x W_gate^T and up = x W_up^T, fp
     const float *gate;
     const float *up;
     __device__ __forceinline__ Raw load(int i) const { return make_float2(gate[i], up[i]); }
-    __device__ __forceinline__ float value(Raw r) const { return swiglu_value(r.x, r.y); }
+    __device__ __forceinline__ float prepare() const { return 0.f; }
+    __device__ __forceinline__ float value(Raw r, float) const { return swiglu_value(r.x, r.y); }
 };
 
 // ---- the normalised hidden state (the input of W_q/W_k/W_v and W_gate/W_up) ----
@@ -292,9 +297,12 @@ struct RmsnormSource {                // hidden state and norm weights, fp32 in 
     typedef float2 Raw;
     const float *h;
     const float *gamma;
-    float r;                          // from rms_scale
+    int m;
+    float eps;
+    double *wave_sums;                // LDS, kMaxNormChunks * kNormWaves doubles
     __device__ __forceinline__ Raw load(int i) const { return make_float2(h[i], gamma[i]); }
-    __device__ __forceinline__ float value(Raw raw) const
+    __device__ __forceinline__ float prepare() const { return rms_scale(h, m, eps, wave_sums); }
+    __device__ __forceinline__ float value(Raw raw, float r) const
     {
         return rmsnorm_value(raw.x, raw.y, r);
     }
@@ -330,12 +338,14 @@ __device__ __forceinline__ int compact_slice(const XS &x, float t, int k0,
 #pragma unroll
     for (int j = 0; j < PER_WAVE; ++j)
         raw[j] = x.load(min(k0 + (w + j * WAVES) * 64 + lane, k1 - 1));
+    const float prepared = x.prepare();
     const int w_uniform = __builtin_amdgcn_readfirstlane(w);
 #pragma unroll
     for (int j = 0; j < PER_WAVE; ++j) {
         const int i = k0 + (w + j * WAVES) * 64 + lane;
         float v = 0.f;
-        if (!XS::kHeavy || w_uniform + j * WAVES < nseg) v = x.value(raw[j]);   // wavefront-uniform
+        if (!XS::kHeavy || w_uniform + j * WAVES < nseg)          // wavefront-uniform
+            v = x.value(raw[j], prepared);
         xv[j] = i < k1 ? v : 0.f;                     // x = 0 never survives (t >= 0)
     }
 #pragma unroll
@@ -674,16 +684,16 @@ __global__ __launch_bounds__(WAVES * 64) void sparse_gemv_multi_kernel(
 // The grouped launch with its shared input formed in the kernel from the hidden state
 // before the normalisation layer: one launch instead of a normalisation kernel plus the
 // products, and the normalised state never travels through HBM.  Every block reads all
-// of h (from L2 after the first block of its XCD) for the scale, then only its slice.
+// of h (from L2 after the first block of its XCD) for the scale, and its own slice of h
+// and gamma, whose loads are issued first.
 template <class F, int LPR, int U>
 __global__ __launch_bounds__(kNormWaves * 64) void sparse_gemv_rmsnorm_multi_kernel(
     MultiArgs<F> ma, const float *__restrict__ h, const float *__restrict__ gamma, float eps,
     float *partial, int *counters, int m, int ks, int tile_cols, int splits)
 {
     __shared__ double wave_sums[kMaxNormChunks * kNormWaves];
-    const float r = rms_scale(h, m, eps, wave_sums);
-    multi_block<F, LPR, kNormWaves, U>(ma, RmsnormSource{h, gamma, r}, partial, counters, m, ks,
-                                       tile_cols, splits);
+    multi_block<F, LPR, kNormWaves, U>(ma, RmsnormSource{h, gamma, m, eps, wave_sums}, partial,
+                                       counters, m, ks, tile_cols, splits);
 }
 
 // Host-side launch geometry shared by the formats.
