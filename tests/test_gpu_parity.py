@@ -604,9 +604,16 @@ def test_calls_replay_from_a_hip_graph(T):
     tb = ti.batch_quantile_threshold(X, 0.5)
     ws = workspace(T, m, 2 * n + 1040)
     wsb = torch.zeros(T.teal_workspace_bytes_batch(m, n, 4), dtype=torch.uint8, device="cuda")
-    outs = [torch.zeros(n, dtype=torch.float32, device="cuda") for _ in range(3)]
+    outs = [torch.zeros(n, dtype=torch.float32, device="cuda") for _ in range(6)]
     y8 = torch.zeros(1040, dtype=torch.float32, device="cuda")
     Yb = torch.zeros((4, n), dtype=torch.float32, device="cuda")
+    gate, up = ti.mlp_gate_up(m, 45)
+    h, gamma = ti.norm_inputs(m, 46)
+    gated, upd, hd, gammad = dev(gate), dev(up), dev(h), dev(gamma)
+    eps = float(np.float32(1e-5))
+    th = ti.quantile_threshold(orc.swiglu_f16(gate, up), 0.5)
+    tn = ti.quantile_threshold(orc.rmsnorm_f16(h, gamma, eps), 0.4)
+    ws2 = workspace(T, m, 2 * n)           # kept apart: its survivor counts are read below
 
     def enqueue(stream):
         T.check(T.teal_sparse_gemv_bf16(wt, xd, t, outs[0], m, n, ws, stream=stream))
@@ -614,10 +621,14 @@ def test_calls_replay_from_a_hip_graph(T):
                                               ws, stream=stream))
         T.check(T.teal_sparse_gemv_w8(qd, sd, xd, t, y8, m, 1040, ws, stream=stream))
         T.check(T.teal_sparse_gemv_bf16_batch(wt, Xd, 4, tb, Yb, m, n, wsb, stream=stream))
+        T.check(T.teal_sparse_gemv_bf16_swiglu(wt, gated, upd, th, outs[3], m, n, ws, stream=stream))
+        T.check(T.teal_sparse_gemv_bf16_rmsnorm_multi([wt, wt], [tn, 0.0], [outs[4], outs[5]],
+                                                      [n, n], hd, gammad, eps, m, ws2, stream=stream))
 
     def snapshot():
         torch.cuda.synchronize()
-        return [o.clone() for o in outs] + [y8.clone(), Yb.clone()]
+        return [o.clone() for o in outs] + [y8.clone(), Yb.clone(),
+                                            torch.tensor(survivors(T, ws2, 2))]
 
     def poison():
         for o in outs + [y8, Yb]:
@@ -626,6 +637,10 @@ def test_calls_replay_from_a_hip_graph(T):
     enqueue(torch.cuda.current_stream())
     eager = snapshot()
     assert rel_l2(eager[0].cpu().numpy(), orc.sparse_gemv_bf16(w, x, t)) <= TIGHT
+    assert rel_l2(eager[3].cpu().numpy(), orc.sparse_gemv_bf16_swiglu(w, gate, up, th)) <= TIGHT
+    assert rel_l2(eager[4].cpu().numpy(), orc.sparse_gemv_bf16_rmsnorm(w, h, gamma, eps, tn)) <= TIGHT
+    xn = orc.rmsnorm_f16(h, gamma, eps)
+    assert eager[-1].tolist() == [orc.sparsify(xn, tn)[3], orc.sparsify(xn, 0.0)[3]]
 
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
@@ -637,6 +652,7 @@ def test_calls_replay_from_a_hip_graph(T):
         enqueue(side)
     for replay in range(4):
         poison()
+        ws2[T.teal_survivors_offset():T.teal_survivors_offset() + 8].zero_()
         torch.cuda.synchronize()
         graph.replay()
         got = snapshot()
