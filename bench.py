@@ -312,14 +312,30 @@ def cpu_baseline(block, p: float, budget_s: float = 12.0):
     from oracle import teal_oracle as orc
     threads = orc.num_threads()
     block[0].oracle(orc, p)                                   # warm-up
-    passes, spent = 0, 0.0
+    passes, spent, outputs = 0, 0.0, None
     while spent < budget_s and passes < 1000:
         t0 = time.perf_counter()
-        for P in block:
-            P.oracle(orc, p)
+        ys = [P.oracle(orc, p) for P in block]
         spent += time.perf_counter() - t0
         passes += 1
-    return spent / passes, passes, threads
+        outputs = outputs or ys
+    return spent / passes, passes, threads, outputs
+
+
+def survivor_counts_match(T, torch, stack, p: float):
+    """After one more pass at sparsity p: the count of surviving channels each call left in
+    its workspace against the count taken on the host from the same x and t.  Returns
+    (all equal, number of matrices compared)."""
+    one_step(T, stack, p, 0)
+    torch.cuda.synchronize()
+    off = T.teal_survivors_offset()
+    ok, compared = True, 0
+    for C in stack:
+        members = getattr(C, "members", [C])
+        got = C.ws[off:off + 4 * len(members)].view(torch.int32).cpu().tolist()
+        ok = ok and got == [P.nnz[p] for P in members]
+        compared += len(members)
+    return ok, compared
 
 
 CALIBRATION_LEVELS = [0.25, 0.4, 0.5, 0.65, 0.9]
@@ -808,8 +824,16 @@ def main() -> int:
         f"per_projection_alone_{pct(head)}": per_proj,
         f"per_group_alone_{pct(head)}": per_group,
     }
+    ok, compared = survivor_counts_match(T, torch, stack, head)
+    out["parity_in_this_run"] = {"survivor_counts_equal_host_counts": ok, "matrices": compared}
     if not args.no_cpu_baseline:
-        sec, passes, threads = cpu_baseline(block0, head)
+        sec, passes, threads, want = cpu_baseline(block0, head)
+        # the pass above left block 0's outputs of the timed launch configuration on the device
+        worst = 0.0
+        for P, w in zip(block0, want):
+            got = P.y.cpu().numpy().astype(np.float64).reshape(np.shape(w))
+            worst = max(worst, float(np.linalg.norm(got - w) / np.linalg.norm(w)))
+        out["parity_in_this_run"]["block0_rel_l2_vs_oracle_worst"] = worst
         block_head_bytes = sum(P.bytes(head) for P in block0)
         out["cpu_baseline"] = {
             "value": block_head_bytes / sec / 1e9,
