@@ -19,7 +19,9 @@ struct FmtBF16 {
             acc[2 * q + 1] = fmaf(xv, __uint_as_float(v[q] & 0xffff0000u), acc[2 * q + 1]);
         }
     }
-    static __device__ __forceinline__ float finish(float sum, const Args &, int) { return sum; }
+    struct ColumnScale {};
+    static __device__ __forceinline__ ColumnScale column_scale(const Args &, int) { return {}; }
+    static __device__ __forceinline__ float finish(float sum, ColumnScale) { return sum; }
 };
 
 bool gemv_shape_supported(const GemvShape &s)

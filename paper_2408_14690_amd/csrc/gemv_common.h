@@ -470,10 +470,17 @@ __device__ __forceinline__ void block_finish(const float (&acc)[F::kElemsPerLane
     constexpr int EPL = F::kElemsPerLane;
     constexpr int TN = LPR * EPL;
     constexpr int THREADS = WAVES * 64;
+    constexpr int OWN = (TN + THREADS - 1) / THREADS;     // columns c = thread + k * THREADS
     __shared__ int last_flag;
     const int lane = threadIdx.x & 63;
     const int w = threadIdx.x >> 6;
     if (cols > n - col0) cols = n - col0;
+    // What finish() needs per output column (the int8 scales) is loaded now, so that its
+    // latency lies under the combine and not after the last sum.
+    typename F::ColumnScale scale[OWN];
+#pragma unroll
+    for (int k = 0; k < OWN; ++k)
+        scale[k] = F::column_scale(a, col0 + min((int)threadIdx.x + k * THREADS, cols - 1));
     if (lane < LPR) {
         float4 *dst = reinterpret_cast<float4 *>(red + w * TN + lane * EPL);
 #pragma unroll
@@ -483,11 +490,15 @@ __device__ __forceinline__ void block_finish(const float (&acc)[F::kElemsPerLane
     __syncthreads();
     if (tile == 0 && threadIdx.x == 0) report_slice(report, s, splits, cnt);
     if (splits == 1) {
-        for (int c = threadIdx.x; c < cols; c += THREADS) {
-            float sum = 0.f;
 #pragma unroll
-            for (int ww = 0; ww < WAVES; ++ww) sum += red[ww * TN + c];
-            store_coherent(y + col0 + c, F::finish(sum, a, col0 + c));
+        for (int k = 0; k < OWN; ++k) {
+            const int c = (int)threadIdx.x + k * THREADS;
+            if (c < cols) {
+                float sum = 0.f;
+#pragma unroll
+                for (int ww = 0; ww < WAVES; ++ww) sum += red[ww * TN + c];
+                store_coherent(y + col0 + c, F::finish(sum, scale[k]));
+            }
         }
         return;
     }
@@ -516,18 +527,20 @@ __device__ __forceinline__ void block_finish(const float (&acc)[F::kElemsPerLane
     // flight at once, and the groups' sums are added in group order through
     // LDS: a fixed order, whichever block happens to be last.
     constexpr int PARTS = THREADS >= TN ? THREADS / TN : 1;
-    constexpr int MAXLD = 8;
-    for (int c0 = 0; c0 < TN; c0 += THREADS) {
+    constexpr int MAXLD = PARTS > 1 ? 8 : 16;             // up to 16 splits in one round trip
+#pragma unroll
+    for (int k = 0; k < OWN; ++k) {
+        const int c0 = k * THREADS;
         const int c = c0 + (int)threadIdx.x % (PARTS > 1 ? TN : THREADS);
         const int q = PARTS > 1 ? (int)threadIdx.x / TN : 0;
         float sum = 0.f;
         if (c < cols) {
             const float *p = partial + col0 + c;
-            for (int k = q; k < splits; k += PARTS * MAXLD) {
+            for (int j = q; j < splits; j += PARTS * MAXLD) {
                 float v[MAXLD];
 #pragma unroll
                 for (int u = 0; u < MAXLD; ++u) {
-                    const int sk = k + u * PARTS;
+                    const int sk = j + u * PARTS;
                     v[u] = sk < splits ? load_coherent(p + (size_t)sk * n) : 0.f;
                 }
 #pragma unroll
@@ -542,10 +555,10 @@ __device__ __forceinline__ void block_finish(const float (&acc)[F::kElemsPerLane
                 float total = red[c];
 #pragma unroll
                 for (int qq = 1; qq < PARTS; ++qq) total += red[qq * TN + c];
-                store_coherent(y + col0 + c, F::finish(total, a, col0 + c));
+                store_coherent(y + col0 + c, F::finish(total, scale[k]));
             }
         } else if (c < cols) {
-            store_coherent(y + col0 + c, F::finish(sum, a, col0 + c));
+            store_coherent(y + col0 + c, F::finish(sum, scale[k]));
         }
     }
     // Leave the counter at zero for the next call on this workspace.

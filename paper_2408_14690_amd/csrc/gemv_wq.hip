@@ -27,9 +27,14 @@ struct FmtW8 {
         }
     }
     // The per-output-channel scale factors out of the sum over input channels.
-    static __device__ __forceinline__ float finish(float sum, const Args &a, int col)
+    typedef __half ColumnScale;
+    static __device__ __forceinline__ ColumnScale column_scale(const Args &a, int col)
     {
-        return sum * __half2float(a.scale[col]);
+        return a.scale[col];
+    }
+    static __device__ __forceinline__ float finish(float sum, ColumnScale sc)
+    {
+        return sum * __half2float(sc);
     }
 };
 
@@ -41,30 +46,39 @@ struct FmtW4 {
         const __half *scale;
     };
     // Converting a nibble to fp32 the plain way costs two instructions per element.
-    // Instead: q + 8 (the nibble with its top bit flipped) is placed in the top four
-    // mantissa bits of an fp16 1.0, two nibbles per 32-bit operation, which gives
-    // v = 1 + (q + 8) / 16 in [1, 2), i.e. q = 16 (v - 1.5).  The FMA then reads the
-    // fp16 halves directly, and the affine map is undone once per group from
-    // sum x*v and sum x (both exact products, fp32 sums).
-    static constexpr float kAffineScale = 16.f;    // q = kAffineScale * (v - kAffineOffset)
-    static constexpr float kAffineOffset = 1.5f;
+    // Instead: q + 8 (the nibble with its top bit flipped) is left where it lies and read
+    // as an fp16 subnormal: a nibble in bits 0..3 of a 16-bit half is the value
+    // (q + 8) 2^-24, in bits 4..7 it is (q + 8) 2^-20 (no implicit one, so no offset
+    // that would cost accumulator precision).  One AND isolates two nibbles (one per
+    // half), one shift by 8 serves the upper two nibbles of each half, and the FMA reads
+    // the fp16 halves directly: 14 vector instructions per 8 weights.  The scaling by
+    // 2^24 / 2^20 and the offset 8 are undone once per group from sum x*v and sum x
+    // (exact products, fp32 sums).  Relies on fp16 subnormals being honoured by the
+    // mixed-precision FMA (they are in the default floating-point mode).  (Pairing two
+    // rows per fp16 dot-product instruction saves another 1 % of the step time, but that
+    // instruction's sum is less accurate: 5e-5 relative on a dense 14336-channel input.)
+    static constexpr float kScaleEven = 16777216.f;   // 2^24: columns 0, 2 of each group of 4
+    static constexpr float kScaleOdd = 1048576.f;     // 2^20: columns 1, 3
+    static constexpr float kOffset = 8.f;             // q = scale * v - kOffset
     static __device__ __forceinline__ void fma(float (&acc)[32], u32x4 v, float xv)
     {
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const uint32_t d = v[q] ^ 0x88888888u;
+            const uint32_t d8 = d >> 8;
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                // nibble k -> bits 6..9, nibble k + 4 -> bits 22..25
-                const uint32_t sh = k == 0 ? d << 6 : k == 1 ? d << 2 : k == 2 ? d >> 2 : d >> 6;
-                const uint32_t pair = (sh & 0x03C003C0u) | 0x3C003C00u;
+                // nibble k in the low half, nibble k + 4 in the high half
+                const uint32_t pair = (k < 2 ? d : d8) & ((k & 1) ? 0x00F000F0u : 0x000F000Fu);
                 const __half2 h = *reinterpret_cast<const __half2 *>(&pair);
                 acc[8 * q + k] = fmaf(__low2float(h), xv, acc[8 * q + k]);
                 acc[8 * q + k + 4] = fmaf(__high2float(h), xv, acc[8 * q + k + 4]);
             }
         }
     }
-    static __device__ __forceinline__ float finish(float sum, const Args &, int) { return sum; }
+    struct ColumnScale {};
+    static __device__ __forceinline__ ColumnScale column_scale(const Args &, int) { return {}; }
+    static __device__ __forceinline__ float finish(float sum, ColumnScale) { return sum; }
 };
 
 constexpr int kGroup = 128;
@@ -90,8 +104,8 @@ struct W4Batch {
 // the other formats.  The list is ascending, so each 128-channel group is a
 // run of it, delimited by the segment prefixes (two 64-channel segments per
 // group), and a wavefront's share crosses few group boundaries.  Within a group
-// a wavefront accumulates sum_i x_i v[i][j] unscaled (v = the nibble mapped
-// into [1, 2), see FmtW4); at the end of its rows of that group it undoes the
+// a wavefront accumulates sum_i x_i v[i][j] unscaled (v = the offset nibble
+// read as a tiny fp16, see FmtW4); at the end of its rows of that group it undoes the
 // affine map and folds the sums into the running sums with the group's scales:
 // once per (wavefront, group it touches), not once per row.  Batches never
 // straddle a group, and two batches are in flight per wavefront across group
@@ -179,16 +193,16 @@ __device__ __forceinline__ void w4_block(const FmtW4::Args &a, const __half *__r
             }
         }
         if (!b.ends_run) return;
-        // sum x*q = 16 (sum x*v - 1.5 sum x); then times the group's scale
-        const float corr = -F::kAffineScale * F::kAffineOffset * xsum;
+        // sum x*q = scale * sum x*v - 8 sum x; then times the group's scale
+        const float corr = -F::kOffset * xsum;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const unsigned sw[4] = {b.sc[q].x, b.sc[q].y, b.sc[q].z, b.sc[q].w};
 #pragma unroll
             for (int h = 0; h < 4; ++h) {
                 const __half2 sh = *reinterpret_cast<const __half2 *>(&sw[h]);
-                const float q0 = fmaf(gacc[8 * q + 2 * h], F::kAffineScale, corr);
-                const float q1 = fmaf(gacc[8 * q + 2 * h + 1], F::kAffineScale, corr);
+                const float q0 = fmaf(gacc[8 * q + 2 * h], F::kScaleEven, corr);
+                const float q1 = fmaf(gacc[8 * q + 2 * h + 1], F::kScaleOdd, corr);
                 acc[8 * q + 2 * h] = fmaf(__low2float(sh), q0, acc[8 * q + 2 * h]);
                 acc[8 * q + 2 * h + 1] = fmaf(__high2float(sh), q1, acc[8 * q + 2 * h + 1]);
                 gacc[8 * q + 2 * h] = 0.f;
