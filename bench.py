@@ -627,6 +627,23 @@ def run_rmsnorm(T, torch, args) -> int:
     return 0
 
 
+def gpu_clocks():
+    """Current clock levels as rocm-smi reports them (whatever the box gives; not changed
+    here).  A child process, started before this process touches the GPU; None if the tool
+    is missing or says nothing usable."""
+    import shutil
+    import subprocess
+    exe = shutil.which("rocm-smi") or "/opt/rocm/bin/rocm-smi"
+    try:
+        res = subprocess.run([exe, "--showclocks", "--json"], capture_output=True, text=True,
+                             timeout=20)
+        cards = json.loads(res.stdout)
+        card = cards[sorted(cards)[0]]
+        return {k: v for k, v in card.items() if "clock" in k.lower()} or None
+    except Exception:
+        return None
+
+
 def pct(p: float) -> str:
     return f"{int(round(p * 100))}%"
 
@@ -670,6 +687,7 @@ def main() -> int:
         print("bench.py: this build runs on ONE GPU only; --gpus must be 1", file=sys.stderr)
         return 2
 
+    clocks = gpu_clocks()
     import torch
     import paper_2408_14690_amd as T
     if not torch.cuda.is_available():
@@ -824,6 +842,19 @@ def main() -> int:
         f"per_projection_alone_{pct(head)}": per_proj,
         f"per_group_alone_{pct(head)}": per_group,
     }
+    # the same reading while the headline pass keeps the GPU busy (about a second of steps)
+    import threading
+    busy = {}
+    th = threading.Thread(target=lambda: busy.update(clocks=gpu_clocks()))
+    th.start()
+    k = 0
+    while th.is_alive():
+        for _ in range(200):
+            one_step(T, stack, head, k)
+            k += 1
+        torch.cuda.synchronize()
+    th.join()
+    out["gpu_clocks_rocm_smi"] = {"idle_before_the_run": clocks, "under_the_headline_pass": busy.get("clocks")}
     ok, compared = survivor_counts_match(T, torch, stack, head)
     out["parity_in_this_run"] = {"survivor_counts_equal_host_counts": ok, "matrices": compared}
     if not args.no_cpu_baseline:
