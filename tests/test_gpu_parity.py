@@ -541,6 +541,29 @@ def test_survivor_counts_grouped_calls(T):
 
 
 
+def test_very_wide_output(T):
+    """A million output columns from a handful of input channels: thousands of tiles, one
+    arrival counter each, more blocks than the chip holds at once."""
+    m, n = 130, (1 << 20) + 16
+    w = ti.weights_bf16(n, m, seed=777)
+    wt = dev(ti.to_input_channel_major(w))
+    x = ti.gaussian_x(m, 778)
+    xd = dev(x)
+    ws = workspace(T, m, n)
+    for p in (0.5, 0.0):
+        t = ti.quantile_threshold(x, p)
+        got = run_bf16(T, wt, xd, t, m, n, ws)
+        assert rel_l2(got, orc.sparse_gemv_bf16(w, x, t)) <= TIGHT, p
+        assert survivors(T, ws) == [orc.sparsify(x, t)[3]]
+    # with split-K forced on: 2049 tiles x 2 splits
+    t = ti.quantile_threshold(x, 0.5)
+    got = run_bf16(T, wt, xd, t, m, n, ws, splits=2)
+    assert rel_l2(got, orc.sparse_gemv_bf16(w, x, t)) <= TIGHT
+    q, scale = ti.quantize_w8(w)
+    got = run_w8(T, dev(q), dev(scale), xd, t, m, n, ws)
+    assert rel_l2(got, orc.sparse_gemv_w8(q, scale, x, t)) <= TIGHT
+
+
 # An input longer than 128 x 4096 channels: a block compacts at most 4096 channels, so
 # the call runs with more split-K blocks than a caller may ask for, and the workspace
 # holds one partial row for each of them.
