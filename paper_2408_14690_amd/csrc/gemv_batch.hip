@@ -389,42 +389,61 @@ __global__ __launch_bounds__(WAVES * 64) void sparse_gemv_batch_multi_kernel(
 constexpr int kBatchWaves = 8;
 constexpr int kBatchUnroll = 4;
 
-// One block thresholds the batch like sparsify_kernel does one vector, 1024
-// channels per step.
+// One block thresholds the batch like sparsify_kernel does one vector: groups of 4 chunks
+// of 1024 channels, the loads of a group (all batch rows) in flight together.
 constexpr int kSparsifyWaves = 16;
-__global__ __launch_bounds__(kSparsifyWaves * 64) void sparsify_batch_kernel(
+constexpr int kSparsifyChunk = kSparsifyWaves * 64;
+constexpr int kSparsifyGroup = 4;
+__global__ __launch_bounds__(kSparsifyChunk) void sparsify_batch_kernel(
     const __half *__restrict__ X, int batch, int m, double bound, uint8_t *__restrict__ mask,
     int32_t *__restrict__ idx, int32_t *__restrict__ count)
 {
-    __shared__ int wave_cnt[2][kSparsifyWaves];
+    __shared__ int wave_cnt[2][kSparsifyGroup][kSparsifyWaves];
     const int lane = threadIdx.x & 63;
     const int w = threadIdx.x >> 6;
     int base = 0;
     int buf = 0;
-    for (int c0 = 0; c0 < m; c0 += kSparsifyWaves * 64, buf ^= 1) {
-        const int i = c0 + (int)threadIdx.x;
-        bool keep = false;
-        if (i < m) {
-            double s = 0.0;
-            for (int b = 0; b < batch; ++b)
-                s += (double)fabsf(__half2float(X[(size_t)b * m + i]));
-            keep = s > bound;
-            if (mask) mask[i] = keep ? 1 : 0;
-        }
-        const unsigned long long bal = __ballot(keep);
-        if (lane == 0) wave_cnt[buf][w] = __popcll(bal);
-        __syncthreads();
-        int below = 0, total = 0;
+    for (int c0 = 0; c0 < m; c0 += kSparsifyGroup * kSparsifyChunk, buf ^= 1) {
+        __half raw[kSparsifyGroup][kMaxBatch];
 #pragma unroll
-        for (int ww = 0; ww < kSparsifyWaves; ++ww) {
-            const int c = wave_cnt[buf][ww];
-            below += ww < w ? c : 0;
-            total += c;
+        for (int j = 0; j < kSparsifyGroup; ++j) {
+            const int i = min(c0 + j * kSparsifyChunk + (int)threadIdx.x, m - 1);
+#pragma unroll
+            for (int b = 0; b < kMaxBatch; ++b)       // rows past the batch repeat the last row
+                raw[j][b] = X[(size_t)min(b, batch - 1) * m + i];
         }
-        if (keep && idx) idx[base + below + lanes_below(bal)] = i;
-        base += total;
-        // wave_cnt is double-buffered: the next step writes the other half, and
-        // that step's barrier orders it against this step's reads.
+        unsigned long long bal[kSparsifyGroup];
+#pragma unroll
+        for (int j = 0; j < kSparsifyGroup; ++j) {
+            const int i = c0 + j * kSparsifyChunk + (int)threadIdx.x;
+            double s = 0.0;
+#pragma unroll
+            for (int b = 0; b < kMaxBatch; ++b)
+                s += b < batch ? (double)fabsf(__half2float(raw[j][b])) : 0.0;
+            const bool keep = i < m && s > bound;
+            if (i < m && mask) mask[i] = keep ? 1 : 0;
+            bal[j] = __ballot(keep);
+            if (lane == 0) wave_cnt[buf][j][w] = __popcll(bal[j]);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < kSparsifyGroup; ++j) {
+            if (c0 + j * kSparsifyChunk < m) {        // block-uniform
+                int below = 0, total = 0;
+#pragma unroll
+                for (int ww = 0; ww < kSparsifyWaves; ++ww) {
+                    const int c = wave_cnt[buf][j][ww];
+                    below += ww < w ? c : 0;
+                    total += c;
+                }
+                if (idx && ((bal[j] >> lane) & 1ull))
+                    idx[base + below + lanes_below(bal[j])] =
+                        c0 + j * kSparsifyChunk + (int)threadIdx.x;
+                base += total;
+            }
+        }
+        // wave_cnt is double-buffered: the next group writes the other half, and that
+        // group's barrier orders it against this group's reads.
     }
     if (threadIdx.x == 0 && count) *count = base;
 }

@@ -92,6 +92,33 @@ def test_sparsify_bit_exact(T, m, dist):
         assert np.all(idx[count:] == -1)              # capacity beyond count untouched
 
 
+@pytest.mark.parametrize("m", [7, 8, 9, 4097, 8191, 8193, 32768, 32775, 100003])
+@pytest.mark.parametrize("x_off,mask_off", [(0, 0), (0, 3), (1, 0), (4, 1)])
+def test_sparsify_every_alignment_and_long_vectors(T, m, x_off, mask_off):
+    """x on and off a 16-byte boundary (eight channels per thread, or one), the mask on and
+    off an 8-byte boundary, lengths around the vector width and beyond one group of passes."""
+    x = ti.make_x(m, 7100 + m, "laplace")
+    buf = torch.zeros(m + 8, dtype=torch.int16, device="cuda")
+    buf[x_off:x_off + m] = torch.from_numpy(x.view(np.int16)).cuda()
+    xd = buf[x_off:x_off + m]
+    assert xd.data_ptr() % 16 == (2 * x_off) % 16
+    for p in (0.0, 0.5, 0.97):
+        t = ti.quantile_threshold(x, p)
+        _, mask_o, idx_o, count_o = orc.sparsify(x, t)
+        mbuf = torch.full((m + 8,), 7, dtype=torch.uint8, device="cuda")
+        mask = mbuf[mask_off:mask_off + m]
+        idx = torch.full((m,), -1, dtype=torch.int32, device="cuda")
+        count = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+        T.check(T.teal_sparsify(xd, m, t, mask, idx, count))
+        torch.cuda.synchronize()
+        assert int(count.item()) == count_o
+        assert np.array_equal(mask.cpu().numpy(), mask_o)
+        got = idx.cpu().numpy()
+        assert np.array_equal(got[:count_o], idx_o) and np.all(got[count_o:] == -1)
+        outside = mbuf.cpu().numpy()
+        assert np.all(outside[:mask_off] == 7) and np.all(outside[mask_off + m:] == 7)
+
+
 def test_sparsify_ties_special_values_and_empty(T):
     x = np.array([1.0, -1.0, 1.0009765625, 0.0, -0.0, np.nan, np.inf, -np.inf, 6e-8, -65504.0] * 13,
                  dtype=np.float16)
