@@ -448,6 +448,93 @@ __global__ __launch_bounds__(kSparsifyChunk) void sparsify_batch_kernel(
     if (threadIdx.x == 0 && count) *count = base;
 }
 
+// The same result with eight channels per thread (one 16-byte load per batch row), for X on
+// a 16-byte boundary and m a multiple of 8 (so that every row is): the block-wide prefix and
+// the stores are shared by eight channels, as in the single-vector kernel of this shape.
+constexpr int kVecChannels = 8;
+constexpr int kVecPass = kSparsifyChunk * kVecChannels;
+
+template <int P>
+__global__ __launch_bounds__(kSparsifyChunk) void sparsify_batch_vec_kernel(
+    const __half *__restrict__ X, int batch, int m, double bound, uint8_t *__restrict__ mask,
+    bool mask_aligned, int32_t *__restrict__ idx, int32_t *__restrict__ count)
+{
+    __shared__ int wave_tot[2][P][kSparsifyWaves];
+    const int lane = threadIdx.x & 63;
+    const int w = threadIdx.x >> 6;
+    int base = 0;
+    int buf = 0;
+    for (int c0 = 0; c0 < m; c0 += P * kVecPass, buf ^= 1) {
+        unsigned bits[P];
+        int cnt[P], incl[P];
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            const int i0 = c0 + (p * kSparsifyChunk + (int)threadIdx.x) * kVecChannels;
+            const int ic = min(i0, m - kVecChannels);     // m >= 8 and m % 8 == 0
+            uint4 raw[kMaxBatch];
+#pragma unroll
+            for (int b = 0; b < kMaxBatch; ++b)           // rows past the batch repeat the last row
+                raw[b] = *reinterpret_cast<const uint4 *>(X + (size_t)min(b, batch - 1) * m + ic);
+            double sum[kVecChannels];
+#pragma unroll
+            for (int e = 0; e < kVecChannels; ++e) sum[e] = 0.0;
+#pragma unroll
+            for (int b = 0; b < kMaxBatch; ++b) {
+                if (b < batch) {                          // block-uniform
+                    const unsigned wd[4] = {raw[b].x, raw[b].y, raw[b].z, raw[b].w};
+#pragma unroll
+                    for (int e = 0; e < kVecChannels; ++e) {
+                        const unsigned short h = (unsigned short)(wd[e >> 1] >> (16 * (e & 1)));
+                        sum[e] += (double)fabsf(__half2float(__ushort_as_half(h)));
+                    }
+                }
+            }
+            unsigned bb = 0;
+#pragma unroll
+            for (int e = 0; e < kVecChannels; ++e) bb |= (sum[e] > bound ? 1u : 0u) << e;
+            if (i0 >= m) bb = 0;
+            bits[p] = bb;
+            cnt[p] = __popc(bb);
+            incl[p] = wave_inclusive_scan(cnt[p]);
+            if (lane == 63) wave_tot[buf][p][w] = incl[p];
+            if (mask && i0 < m) {
+                if (mask_aligned) {
+                    const unsigned lo = bb & 0xFu, hi = (bb >> 4) & 0xFu;
+                    uint2 mv;
+                    mv.x = (lo & 1u) | ((lo & 2u) << 7) | ((lo & 4u) << 14) | ((lo & 8u) << 21);
+                    mv.y = (hi & 1u) | ((hi & 2u) << 7) | ((hi & 4u) << 14) | ((hi & 8u) << 21);
+                    *reinterpret_cast<uint2 *>(mask + i0) = mv;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < kVecChannels; ++e) mask[i0 + e] = (uint8_t)((bb >> e) & 1u);
+                }
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            if (c0 + p * kVecPass < m) {                  // block-uniform
+                int below = 0, total = 0;
+#pragma unroll
+                for (int ww = 0; ww < kSparsifyWaves; ++ww) {
+                    const int c = wave_tot[buf][p][ww];
+                    below += ww < w ? c : 0;
+                    total += c;
+                }
+                if (idx) {
+                    const int i0 = c0 + (p * kSparsifyChunk + (int)threadIdx.x) * kVecChannels;
+                    int o = base + below + incl[p] - cnt[p];
+#pragma unroll
+                    for (int e = 0; e < kVecChannels; ++e)
+                        if ((bits[p] >> e) & 1u) idx[o++] = i0 + e;
+                }
+                base += total;
+            }
+        }
+    }
+    if (threadIdx.x == 0 && count) *count = base;
+}
+
 }  // namespace
 
 bool gemv_batch_shape_supported(int batch, const GemvShape &s)
@@ -545,9 +632,20 @@ hipError_t launch_gemv_bf16_batch_multi(int count, const void *const *Wt, const 
 hipError_t launch_sparsify_batch(const void *X_f16, int batch, int m, float t, uint8_t *mask,
                                  int32_t *idx, int32_t *count, hipStream_t stream)
 {
-    hipLaunchKernelGGL(sparsify_batch_kernel, dim3(1), dim3(kSparsifyWaves * 64), 0, stream,
-                       static_cast<const __half *>(X_f16), batch, m, (double)batch * (double)t,
-                       mask, idx, count);
+    const __half *X = static_cast<const __half *>(X_f16);
+    const double bound = (double)batch * (double)t;
+    if (m >= kVecChannels && m % kVecChannels == 0 && (reinterpret_cast<uintptr_t>(X_f16) & 15) == 0) {
+        const bool mask_aligned = (reinterpret_cast<uintptr_t>(mask) & 7) == 0;
+        if (m <= kVecPass)
+            hipLaunchKernelGGL(sparsify_batch_vec_kernel<1>, dim3(1), dim3(kSparsifyChunk), 0, stream,
+                               X, batch, m, bound, mask, mask_aligned, idx, count);
+        else
+            hipLaunchKernelGGL(sparsify_batch_vec_kernel<2>, dim3(1), dim3(kSparsifyChunk), 0, stream,
+                               X, batch, m, bound, mask, mask_aligned, idx, count);
+        return hipGetLastError();
+    }
+    hipLaunchKernelGGL(sparsify_batch_kernel, dim3(1), dim3(kSparsifyWaves * 64), 0, stream, X,
+                       batch, m, bound, mask, idx, count);
     return hipGetLastError();
 }
 

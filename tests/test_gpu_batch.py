@@ -59,6 +59,33 @@ def run_batch(T, wt_dev, X, t, m, n, ws=None, **shape):
     return Y.cpu().numpy()
 
 
+@pytest.mark.parametrize("batch", [1, 3, 8])
+@pytest.mark.parametrize("m", [8, 1000, 8192, 8200, 28672, 70000])
+@pytest.mark.parametrize("x_off,mask_off", [(0, 0), (0, 5), (4, 0)])
+def test_sparsify_batch_every_alignment_and_long_vectors(T, batch, m, x_off, mask_off):
+    """X on and off a 16-byte boundary (eight channels per thread, or one), the mask on and
+    off an 8-byte boundary, lengths from one vector to several passes of the block."""
+    X = ti.make_X(batch, m, 41 * batch + m, "laplace")
+    buf = torch.zeros(batch * m + 8, dtype=torch.int16, device="cuda")
+    buf[x_off:x_off + batch * m] = torch.from_numpy(X.view(np.int16).reshape(-1)).cuda()
+    Xd = buf[x_off:x_off + batch * m]
+    for p in (0.0, 0.5, 0.97):
+        t = ti.batch_quantile_threshold(X, p)
+        _, mask_o, idx_o, count_o = orc.sparsify_batch(X, t)
+        mbuf = torch.full((m + 8,), 7, dtype=torch.uint8, device="cuda")
+        mask = mbuf[mask_off:mask_off + m]
+        idx = torch.full((m,), -1, dtype=torch.int32, device="cuda")
+        count = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+        T.check(T.teal_sparsify_batch(Xd, batch, m, t, mask, idx, count))
+        torch.cuda.synchronize()
+        assert int(count.item()) == count_o
+        assert np.array_equal(mask.cpu().numpy(), mask_o)
+        got = idx.cpu().numpy()
+        assert np.array_equal(got[:count_o], idx_o) and np.all(got[count_o:] == -1)
+        outside = mbuf.cpu().numpy()
+        assert np.all(outside[:mask_off] == 7) and np.all(outside[mask_off + m:] == 7)
+
+
 @pytest.mark.parametrize("batch", [1, 2, 3, 4, 5, 8])
 @pytest.mark.parametrize("m", [1, 64, 65, 1000, 4096, 14336])
 def test_sparsify_batch_bit_exact(T, batch, m):
