@@ -34,8 +34,9 @@
  *     teal_workspace_bytes(m, n) bytes, 256-byte aligned.  It must be
  *     zero-filled once before its first use (hipMemset, torch.zeros); every
  *     call that returns TEAL_OK leaves it ready for the next call, of any
- *     shape that fits.  Its contents are otherwise the library's.  Calls that
- *     may run concurrently need distinct workspaces.
+ *     shape that fits.  Its contents are otherwise the library's (the one
+ *     part a caller may read is described under teal_survivors_offset).
+ *     Calls that may run concurrently need distinct workspaces.
  *   - No global state; any host thread may call with any current device, as
  *     long as the pointers belong to it.
  */
@@ -54,7 +55,7 @@ typedef enum teal_status {
     TEAL_ERR_NULL = 1,        /* a required pointer is NULL */
     TEAL_ERR_SHAPE = 2,       /* m or n out of range or not a multiple of the format's vector width */
     TEAL_ERR_ALIGN = 3,       /* a pointer is not aligned as required */
-    TEAL_ERR_THRESHOLD = 4,   /* t is negative, NaN or infinite; a level p is outside [0, 1] */
+    TEAL_ERR_THRESHOLD = 4,   /* t (or eps) is negative, NaN or infinite; a level p is outside [0, 1] */
     TEAL_ERR_WORKSPACE = 5,   /* workspace too small */
     TEAL_ERR_UNSUPPORTED = 6, /* group size or launch parameters not supported */
     TEAL_ERR_HIP = 7          /* the HIP runtime reported an error at launch */
