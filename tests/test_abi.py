@@ -404,3 +404,33 @@ def test_rmsnorm_argument_errors():
     assert call(eps=float("inf")) == T.TEAL_ERR_THRESHOLD
     assert call(ws_bytes=64) == T.TEAL_ERR_WORKSPACE
     assert call(count=5, t=(0.5,) * 5, n=(64,) * 5) == T.TEAL_ERR_UNSUPPORTED
+
+
+def test_plans_of_random_shapes_are_always_launchable():
+    """Host logic: for any accepted shape the chosen launch shape satisfies what the kernels
+    and the workspace assume (tile width a multiple of the vector width and within the lanes,
+    slices within the LDS list, partial rows within the workspace)."""
+    import numpy as np
+    rng = np.random.Generator(np.random.PCG64(2024))
+    epl = {16: 8, 8: 16, 4: 32}
+    for _ in range(3000):
+        bits = int(rng.choice([16, 8, 4]))
+        m = int(np.exp(rng.uniform(0, np.log(1 << 21))))
+        count = int(rng.integers(1, 5))
+        ns = [max(epl[bits], int(np.exp(rng.uniform(np.log(8), np.log(1 << 17)))) // epl[bits] * epl[bits])
+              for _ in range(count)]
+        if bits == 4:
+            m = max(128, m // 128 * 128)
+        st, pl = T.teal_gemv_plan_multi(bits, m, ns)
+        assert st == T.TEAL_OK, (bits, m, ns)
+        assert pl["lanes_per_row"] in (8, 16, 32, 64) and pl["waves"] == 8 and pl["unroll"] == 4
+        assert pl["tile_cols"] % epl[bits] == 0 and 0 < pl["tile_cols"] <= pl["lanes_per_row"] * epl[bits]
+        ks = -(-m // pl["splits"])
+        mult = 128 if bits == 4 else 64
+        ks = -(-ks // mult) * mult
+        assert ks <= 4096 or pl["splits"] == -(-m // 4096), (bits, m, ns, pl)
+        splits = -(-m // min(ks, 4096))
+        need = (1 << 24) // 64 * 4 + splits * sum(ns) * 4
+        assert need <= T.teal_workspace_bytes(m, sum(ns)), (bits, m, ns, pl)
+        if count == 1:
+            assert T.teal_gemv_plan(bits, m, ns[0]) == (st, pl)
