@@ -628,20 +628,22 @@ def run_rmsnorm(T, torch, args) -> int:
 
 
 def gpu_clocks():
-    """Current clock levels as rocm-smi reports them (whatever the box gives; not changed
-    here).  A child process, started before this process touches the GPU; None if the tool
-    is missing or says nothing usable."""
-    import shutil
-    import subprocess
-    exe = shutil.which("rocm-smi") or "/opt/rocm/bin/rocm-smi"
-    try:
-        res = subprocess.run([exe, "--showclocks", "--json"], capture_output=True, text=True,
-                             timeout=20)
-        cards = json.loads(res.stdout)
-        card = cards[sorted(cards)[0]]
-        return {k: v for k, v in card.items() if "clock" in k.lower()} or None
-    except Exception:
-        return None
+    """Current core and memory clock levels of the first GPU as the driver shows them in
+    sysfs (whatever the box gives; nothing is changed here).  Plain file reads: no other
+    program is started.  None where the files are absent."""
+    import glob
+    out = {}
+    for name in ("sclk", "mclk"):
+        for path in sorted(glob.glob(f"/sys/class/drm/card*/device/pp_dpm_{name}")):
+            try:
+                lines = open(path).read().split("\n")
+            except OSError:
+                continue
+            current = [ln.split(":", 1)[1].replace("*", "").strip() for ln in lines if ln.rstrip().endswith("*")]
+            if current:
+                out[name] = current[0]
+                break
+    return out or None
 
 
 def pct(p: float) -> str:
@@ -854,7 +856,7 @@ def main() -> int:
             k += 1
         torch.cuda.synchronize()
     th.join()
-    out["gpu_clocks_rocm_smi"] = {"idle_before_the_run": clocks, "under_the_headline_pass": busy.get("clocks")}
+    out["gpu_clocks"] = {"idle_before_the_run": clocks, "under_the_headline_pass": busy.get("clocks")}
     ok, compared = survivor_counts_match(T, torch, stack, head)
     out["parity_in_this_run"] = {"survivor_counts_equal_host_counts": ok, "matrices": compared}
     if not args.no_cpu_baseline:
