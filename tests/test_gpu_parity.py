@@ -323,6 +323,35 @@ def test_gemv_bf16_70b_shape_sampled_rows(T):
     assert np.all(np.isfinite(got))
 
 
+def test_gemv_bf16_70b_shape_grouped_sampled_rows(T):
+    """The largest launch the benchmark times: gate + up of the 70B-shaped block in one
+    call (2 x 28672 x 8192, own thresholds), sampled outputs one by one and the survivor
+    counts."""
+    n, m = ti.LAYER_SHAPES["llama_70b"]["gate"]
+    x = ti.gaussian_x(m, ti.x_seed(4, 0, "gate"))
+    xd = dev(x)
+    ws_host, wts = [], []
+    for proj in ("gate", "up"):
+        w = ti.weights_bf16(n, m, ti.weight_seed(4, 0, proj))
+        wd = dev(w)
+        wt = torch.empty((m, n), dtype=torch.int16, device="cuda")
+        T.check(T.teal_pack_bf16(wd, wt, m, n))
+        del wd
+        ws_host.append(w)
+        wts.append(wt)
+    ts = [ti.quantile_threshold(x, 0.5), ti.quantile_threshold(x, 0.4)]
+    ys = [torch.full((n,), float("nan"), dtype=torch.float32, device="cuda") for _ in range(2)]
+    ws = workspace(T, m, 2 * n)
+    T.check(T.teal_sparse_gemv_bf16_multi(wts, ts, ys, [n, n], xd, m, ws))
+    torch.cuda.synchronize()
+    assert survivors(T, ws, 2) == [orc.sparsify(x, t)[3] for t in ts]
+    rows = np.unique(np.concatenate([np.arange(0, n, 89), [n - 1, n - 8, 447, 448]])).astype(np.int32)
+    for k in range(2):
+        got = ys[k].cpu().numpy()
+        assert np.all(np.isfinite(got))
+        assert rel_l2(got[rows], orc.sparse_gemv_bf16_rows(ws_host[k], x, ts[k], rows)) <= TIGHT, k
+
+
 # ---------------------------------------------------------------------------
 # several matrices sharing one hidden state in one launch
 # ---------------------------------------------------------------------------
