@@ -434,3 +434,27 @@ def test_plans_of_random_shapes_are_always_launchable():
         assert need <= T.teal_workspace_bytes(m, sum(ns)), (bits, m, ns, pl)
         if count == 1:
             assert T.teal_gemv_plan(bits, m, ns[0]) == (st, pl)
+
+
+def test_header_is_plain_c_and_links_against_the_library(tmp_path):
+    """include/teal.h compiles as C99 with warnings as errors, and a C program that takes the
+    address of every declared function links against the built library (no C++ names, no
+    torch types in the signatures)."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    names = _declared_functions()
+    src = tmp_path / "use_teal.c"
+    body = "\n".join(f"    p[{i}] = (void (*)(void))&{n};" for i, n in enumerate(names))
+    src.write_text('#include "teal.h"\n#include <stdio.h>\nint main(void)\n{\n'
+                   f"    void (*p[{len(names)}])(void);\n{body}\n"
+                   f"    printf(\"%d %s\\n\", teal_version(), teal_status_string(TEAL_OK));\n"
+                   f"    return p[0] == 0;\n}}\n")
+    exe = tmp_path / "use_teal"
+    libdir = os.path.dirname(T.library_path())
+    subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror",
+                    "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe),
+                    "-L", libdir, "-l:libteal.so", f"-Wl,-rpath,{libdir}"], check=True)
+    res = subprocess.run([str(exe)], capture_output=True, text=True, check=True)
+    assert res.stdout.split()[0] == str(T.teal_version())
