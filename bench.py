@@ -115,8 +115,17 @@ class Projection:
         self.xp, self.yp, self.wsp = self.x.data_ptr(), self.y.data_ptr(), self.ws.data_ptr()
         self.ws_bytes = self.ws.numel()
         self.stream = torch.cuda.current_stream().cuda_stream
+        self.prepared = {}
 
     def launch(self, T, copy: int, p: float) -> int:
+        """The call, marshalled once per (weight copy, sparsity, stream) and re-issued."""
+        key = (copy % len(self.wp), p, self.stream)
+        call = self.prepared.get(key)
+        if call is None:
+            call = self.prepared[key] = T.prepare(lambda: self.enqueue(T, copy, p))
+        return call()
+
+    def enqueue(self, T, copy: int, p: float) -> int:
         w = self.wp[copy % len(self.wp)]
         if self.batch:
             return T.teal_sparse_gemv_bf16_batch(w[0], self.xp, self.batch, self.t[p], self.yp,
@@ -159,8 +168,17 @@ class FusedGroup:
         self.ws = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
         self.wsp, self.ws_bytes = self.ws.data_ptr(), self.ws.numel()
         self.stream = members[0].stream
+        self.prepared = {}
 
     def launch(self, T, copy: int, p: float) -> int:
+        """The call, marshalled once per (weight copy, sparsity, stream) and re-issued."""
+        key = (copy % len(self.members[0].wp), p, self.stream)
+        call = self.prepared.get(key)
+        if call is None:
+            call = self.prepared[key] = T.prepare(lambda: self.enqueue(T, copy, p))
+        return call()
+
+    def enqueue(self, T, copy: int, p: float) -> int:
         if self.batch:
             wts = [P.wp[copy % len(P.wp)][0] for P in self.members]
             return T.teal_sparse_gemv_bf16_batch_multi(wts, [P.t[p] for P in self.members],

@@ -8,7 +8,7 @@ raises.
 from .binding import (  # noqa: F401
     TEAL_OK, TEAL_ERR_NULL, TEAL_ERR_SHAPE, TEAL_ERR_ALIGN, TEAL_ERR_THRESHOLD,
     TEAL_ERR_WORKSPACE, TEAL_ERR_UNSUPPORTED, TEAL_ERR_HIP,
-    TealError, check, library_path, load_library,
+    TealError, check, library_path, load_library, prepare,
     teal_status_string, teal_version, teal_workspace_bytes,
     teal_sparsify, teal_sparse_gemv_bf16, teal_sparse_gemv_bf16_ex,
     teal_sparse_gemv_w8, teal_sparse_gemv_w4, teal_pack_bf16, teal_gemv_plan,

@@ -155,6 +155,49 @@ def _stream(stream):
     return stream.cuda_stream
 
 
+_recording = None
+
+
+def _call(name, *cargs):
+    """Every call that enqueues GPU work goes through here: normally straight into the
+    library; while prepare() records, the marshalled arguments are kept instead."""
+    fn = getattr(load_library(), name)
+    if _recording is not None:
+        _recording.append((fn, cargs))
+        return TEAL_OK
+    return fn(*cargs)
+
+
+def prepare(enqueue):
+    """Marshals once, calls many times.  `enqueue` is a function that makes one or more
+    teal_* calls of this module (device tensors, shapes, thresholds and stream as they will
+    be at every later call); nothing reaches the GPU while it runs.  Returns a function
+    without arguments that issues exactly those library calls with the arguments as
+    marshalled (host arrays are kept alive by it) and returns the first status that is not
+    TEAL_OK, else TEAL_OK.  For decode loops that repeat the same calls on the same
+    buffers: the per-call cost of building the argument lists is paid once."""
+    global _recording
+    if _recording is not None:
+        raise RuntimeError("prepare() does not nest")
+    _recording = []
+    try:
+        enqueue()
+        calls = tuple(_recording)
+    finally:
+        _recording = None
+    if len(calls) == 1:
+        fn, cargs = calls[0]
+        return lambda: fn(*cargs)
+
+    def run():
+        for fn, cargs in calls:
+            st = fn(*cargs)
+            if st != TEAL_OK:
+                return st
+        return TEAL_OK
+    return run
+
+
 def check(status: int) -> None:
     if status != TEAL_OK:
         raise TealError(status)
@@ -177,14 +220,15 @@ def teal_survivors_offset() -> int:
 
 
 def teal_sparsify(x_f16, m, t, mask=None, idx=None, count=None, stream=None) -> int:
-    return load_library().teal_sparsify(_ptr(x_f16, 2 * m, "x"), int(m), float(t),
+    return _call("teal_sparsify", _ptr(x_f16, 2 * m, "x"), int(m), float(t),
                                         _ptr(mask, m, "mask"), _ptr(idx, 4 * m, "idx"),
                                         _ptr(count, 4, "count"), _stream(stream))
 
 
 def teal_sparse_gemv_bf16(Wt_bf16, x_f16, t, y, m, n, workspace, workspace_bytes=None,
                           stream=None) -> int:
-    return load_library().teal_sparse_gemv_bf16(
+    return _call(
+        "teal_sparse_gemv_bf16",
         _ptr(Wt_bf16, 2 * m * n, "Wt"), _ptr(x_f16, 2 * m, "x"), float(t), _ptr(y, 4 * n, "y"),
         int(m), int(n), _ptr(workspace),
         _nbytes(workspace, workspace_bytes), _stream(stream))
@@ -193,7 +237,8 @@ def teal_sparse_gemv_bf16(Wt_bf16, x_f16, t, y, m, n, workspace, workspace_bytes
 def teal_sparse_gemv_bf16_ex(Wt_bf16, x_f16, t, y, m, n, workspace, workspace_bytes=None,
                              stream=None, lanes_per_row=0, tile_cols=0, splits=0, waves=0,
                              unroll=0) -> int:
-    return load_library().teal_sparse_gemv_bf16_ex(
+    return _call(
+        "teal_sparse_gemv_bf16_ex",
         _ptr(Wt_bf16, 2 * m * n, "Wt"), _ptr(x_f16, 2 * m, "x"), float(t), _ptr(y, 4 * n, "y"),
         int(m), int(n), _ptr(workspace),
         _nbytes(workspace, workspace_bytes), _stream(stream), int(lanes_per_row), int(tile_cols),
@@ -202,7 +247,8 @@ def teal_sparse_gemv_bf16_ex(Wt_bf16, x_f16, t, y, m, n, workspace, workspace_by
 
 def teal_sparse_gemv_w8(Wq, scale_f16, x_f16, t, y, m, n, workspace, workspace_bytes=None,
                         stream=None) -> int:
-    return load_library().teal_sparse_gemv_w8(
+    return _call(
+        "teal_sparse_gemv_w8",
         _ptr(Wq, m * n, "Wq"), _ptr(scale_f16, 2 * n, "scale"), _ptr(x_f16, 2 * m, "x"), float(t),
         _ptr(y, 4 * n, "y"), int(m), int(n), _ptr(workspace),
         _nbytes(workspace, workspace_bytes), _stream(stream))
@@ -210,14 +256,15 @@ def teal_sparse_gemv_w8(Wq, scale_f16, x_f16, t, y, m, n, workspace, workspace_b
 
 def teal_sparse_gemv_w4(Wq, scale_f16, group, x_f16, t, y, m, n, workspace,
                         workspace_bytes=None, stream=None) -> int:
-    return load_library().teal_sparse_gemv_w4(
+    return _call(
+        "teal_sparse_gemv_w4",
         _ptr(Wq, m * n // 2, "Wq"), _ptr(scale_f16, 2 * n * (m // max(int(group), 1)), "scale"),
         int(group), _ptr(x_f16, 2 * m, "x"), float(t), _ptr(y, 4 * n, "y"), int(m), int(n),
         _ptr(workspace), _nbytes(workspace, workspace_bytes), _stream(stream))
 
 
 def teal_pack_bf16(W_rowmajor, Wt, m, n, stream=None) -> int:
-    return load_library().teal_pack_bf16(_ptr(W_rowmajor, 2 * m * n, "W"), _ptr(Wt, 2 * m * n, "Wt"),
+    return _call("teal_pack_bf16", _ptr(W_rowmajor, 2 * m * n, "W"), _ptr(Wt, 2 * m * n, "Wt"),
                                          int(m), int(n),
                                          _stream(stream))
 
@@ -252,7 +299,8 @@ def teal_sparse_gemv_bf16_multi(Wt_list, t_list, y_list, n_list, x_f16, m, works
     Y = (ctypes.c_void_p * count)(*[_ptr(y, 4 * n, "y") for y, n in zip(y_list, n_list)])
     Tt = (ctypes.c_float * count)(*[float(t) for t in t_list])
     N = (ctypes.c_int * count)(*[int(n) for n in n_list])
-    return load_library().teal_sparse_gemv_bf16_multi(
+    return _call(
+        "teal_sparse_gemv_bf16_multi",
         count, W, Tt, Y, N, _ptr(x_f16, 2 * m, "x"), int(m), _ptr(workspace),
         _nbytes(workspace, workspace_bytes), _stream(stream))
 
@@ -262,7 +310,7 @@ def teal_workspace_bytes_batch(m: int, n: int, batch: int) -> int:
 
 
 def teal_sparsify_batch(X_f16, batch, m, t, mask=None, idx=None, count=None, stream=None) -> int:
-    return load_library().teal_sparsify_batch(_ptr(X_f16, 2 * batch * m, "X"), int(batch), int(m),
+    return _call("teal_sparsify_batch", _ptr(X_f16, 2 * batch * m, "X"), int(batch), int(m),
                                               float(t), _ptr(mask, m, "mask"),
                                               _ptr(idx, 4 * m, "idx"), _ptr(count, 4, "count"),
                                               _stream(stream))
@@ -270,7 +318,8 @@ def teal_sparsify_batch(X_f16, batch, m, t, mask=None, idx=None, count=None, str
 
 def teal_sparse_gemv_bf16_batch(Wt_bf16, X_f16, batch, t, Y, m, n, workspace,
                                 workspace_bytes=None, stream=None) -> int:
-    return load_library().teal_sparse_gemv_bf16_batch(
+    return _call(
+        "teal_sparse_gemv_bf16_batch",
         _ptr(Wt_bf16, 2 * m * n, "Wt"), _ptr(X_f16, 2 * batch * m, "X"), int(batch), float(t),
         _ptr(Y, 4 * batch * n, "Y"), int(m), int(n),
         _ptr(workspace), _nbytes(workspace, workspace_bytes), _stream(stream))
@@ -279,7 +328,8 @@ def teal_sparse_gemv_bf16_batch(Wt_bf16, X_f16, batch, t, Y, m, n, workspace,
 def teal_sparse_gemv_bf16_batch_ex(Wt_bf16, X_f16, batch, t, Y, m, n, workspace,
                                    workspace_bytes=None, stream=None, lanes_per_row=0,
                                    tile_cols=0, splits=0) -> int:
-    return load_library().teal_sparse_gemv_bf16_batch_ex(
+    return _call(
+        "teal_sparse_gemv_bf16_batch_ex",
         _ptr(Wt_bf16, 2 * m * n, "Wt"), _ptr(X_f16, 2 * batch * m, "X"), int(batch), float(t),
         _ptr(Y, 4 * batch * n, "Y"), int(m), int(n),
         _ptr(workspace), _nbytes(workspace, workspace_bytes), _stream(stream),
@@ -297,7 +347,8 @@ def teal_sparse_gemv_w8_multi(Wq_list, scale_list, t_list, y_list, n_list, x_f16
     Y = (ctypes.c_void_p * count)(*[_ptr(y, 4 * n, "y") for y, n in zip(y_list, n_list)])
     Tt = (ctypes.c_float * count)(*[float(t) for t in t_list])
     N = (ctypes.c_int * count)(*[int(n) for n in n_list])
-    return load_library().teal_sparse_gemv_w8_multi(
+    return _call(
+        "teal_sparse_gemv_w8_multi",
         count, W, S, Tt, Y, N, _ptr(x_f16, 2 * m, "x"), int(m), _ptr(workspace),
         _nbytes(workspace, workspace_bytes), _stream(stream))
 
@@ -315,7 +366,8 @@ def teal_sparse_gemv_w4_multi(Wq_list, scale_list, group, t_list, y_list, n_list
     Y = (ctypes.c_void_p * count)(*[_ptr(y, 4 * n, "y") for y, n in zip(y_list, n_list)])
     Tt = (ctypes.c_float * count)(*[float(t) for t in t_list])
     N = (ctypes.c_int * count)(*[int(n) for n in n_list])
-    return load_library().teal_sparse_gemv_w4_multi(
+    return _call(
+        "teal_sparse_gemv_w4_multi",
         count, W, S, int(group), Tt, Y, N, _ptr(x_f16, 2 * m, "x"), int(m), _ptr(workspace),
         _nbytes(workspace, workspace_bytes), _stream(stream))
 
@@ -330,27 +382,29 @@ def teal_sparse_gemv_bf16_batch_multi(Wt_list, t_list, Y_list, n_list, X_f16, ba
     Y = (ctypes.c_void_p * count)(*[_ptr(y, 4 * batch * n, "Y") for y, n in zip(Y_list, n_list)])
     Tt = (ctypes.c_float * count)(*[float(t) for t in t_list])
     N = (ctypes.c_int * count)(*[int(n) for n in n_list])
-    return load_library().teal_sparse_gemv_bf16_batch_multi(
+    return _call(
+        "teal_sparse_gemv_bf16_batch_multi",
         count, W, Tt, Y, N, _ptr(X_f16, 2 * batch * m, "X"), int(batch), int(m), _ptr(workspace),
         _nbytes(workspace, workspace_bytes), _stream(stream))
 
 
 def teal_swiglu_f16(gate, up, h_f16, m, stream=None) -> int:
-    return load_library().teal_swiglu_f16(_ptr(gate, 4 * m, "gate"), _ptr(up, 4 * m, "up"),
+    return _call("teal_swiglu_f16", _ptr(gate, 4 * m, "gate"), _ptr(up, 4 * m, "up"),
                                           _ptr(h_f16, 2 * m, "h"), int(m),
                                           _stream(stream))
 
 
 def teal_sparse_gemv_bf16_swiglu(Wt_bf16, gate, up, t, y, m, n, workspace, workspace_bytes=None,
                                  stream=None) -> int:
-    return load_library().teal_sparse_gemv_bf16_swiglu(
+    return _call(
+        "teal_sparse_gemv_bf16_swiglu",
         _ptr(Wt_bf16, 2 * m * n, "Wt"), _ptr(gate, 4 * m, "gate"), _ptr(up, 4 * m, "up"), float(t),
         _ptr(y, 4 * n, "y"), int(m), int(n), _ptr(workspace),
         _nbytes(workspace, workspace_bytes), _stream(stream))
 
 
 def teal_rmsnorm_f16(h, gamma, eps, x_f16, m, stream=None) -> int:
-    return load_library().teal_rmsnorm_f16(_ptr(h, 4 * m, "h"), _ptr(gamma, 4 * m, "gamma"),
+    return _call("teal_rmsnorm_f16", _ptr(h, 4 * m, "h"), _ptr(gamma, 4 * m, "gamma"),
                                            float(eps), _ptr(x_f16, 2 * m, "x"), int(m),
                                            _stream(stream))
 
@@ -365,13 +419,14 @@ def teal_sparse_gemv_bf16_rmsnorm_multi(Wt_list, t_list, y_list, n_list, h, gamm
     Y = (ctypes.c_void_p * count)(*[_ptr(y, 4 * n, "y") for y, n in zip(y_list, n_list)])
     Tt = (ctypes.c_float * count)(*[float(t) for t in t_list])
     N = (ctypes.c_int * count)(*[int(n) for n in n_list])
-    return load_library().teal_sparse_gemv_bf16_rmsnorm_multi(
+    return _call(
+        "teal_sparse_gemv_bf16_rmsnorm_multi",
         count, W, Tt, Y, N, _ptr(h, 4 * m, "h"), _ptr(gamma, 4 * m, "gamma"), float(eps), int(m),
         _ptr(workspace), _nbytes(workspace, workspace_bytes), _stream(stream))
 
 
 def teal_abs_histogram(x_f16, count, hist, stream=None) -> int:
-    return load_library().teal_abs_histogram(_ptr(x_f16, 2 * count, "x"), int(count),
+    return _call("teal_abs_histogram", _ptr(x_f16, 2 * count, "x"), int(count),
                                              _ptr(hist, 8 * TEAL_HIST_BINS, "hist"),
                                              _stream(stream))
 
@@ -380,5 +435,5 @@ def teal_histogram_thresholds(hist, p_list, t, stream=None) -> int:
     """p_list: host levels in [0, 1]; t: device float32 array of the same length."""
     np_ = len(p_list)
     P = (ctypes.c_double * max(np_, 1))(*[float(p) for p in p_list])
-    return load_library().teal_histogram_thresholds(_ptr(hist, 8 * TEAL_HIST_BINS, "hist"), P, np_,
+    return _call("teal_histogram_thresholds", _ptr(hist, 8 * TEAL_HIST_BINS, "hist"), P, np_,
                                                     _ptr(t, 4 * np_, "t"), _stream(stream))

@@ -458,3 +458,26 @@ def test_header_is_plain_c_and_links_against_the_library(tmp_path):
                     "-L", libdir, "-l:libteal.so", f"-Wl,-rpath,{libdir}"], check=True)
     res = subprocess.run([str(exe)], capture_output=True, text=True, check=True)
     assert res.stdout.split()[0] == str(T.teal_version())
+
+
+def test_prepared_calls_marshal_once():
+    """prepare() records the marshalled arguments of the calls a function makes (nothing is
+    enqueued meanwhile) and returns a function that re-issues them; shown here on calls that
+    the host checks reject, so no GPU is touched."""
+    made = []
+
+    def two_calls():
+        made.append(T.teal_sparse_gemv_bf16(W, X, 0.5, Y, 4096, 4096, WS, 16, stream=0))
+        made.append(T.teal_sparse_gemv_bf16(W, X, -1.0, Y, 4096, 4096, WS, BIG, stream=0))
+
+    run = T.prepare(two_calls)
+    assert made == [T.TEAL_OK, T.TEAL_OK]                 # recorded, not executed
+    assert run() == T.TEAL_ERR_WORKSPACE                  # the first failing status
+    assert run() == T.TEAL_ERR_WORKSPACE
+    one = T.prepare(lambda: T.teal_sparse_gemv_bf16_multi([W, W], [0.5, float("nan")], [Y, Y],
+                                                          [64, 64], X, 4096, WS, BIG, stream=0))
+    assert one() == T.TEAL_ERR_THRESHOLD
+    with pytest.raises(RuntimeError):
+        T.prepare(lambda: T.prepare(lambda: None))
+    # and the module is back to calling straight through
+    assert T.teal_sparse_gemv_bf16(W, X, -1.0, Y, 4096, 4096, WS, BIG, stream=0) == T.TEAL_ERR_THRESHOLD

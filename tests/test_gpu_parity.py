@@ -667,6 +667,30 @@ def test_very_long_input_every_format(T):
 # captured into a HIP graph
 # ---------------------------------------------------------------------------
 
+def test_prepared_calls_give_the_same_bits(T):
+    """A call recorded once with prepare() and re-issued equals the direct call."""
+    m, ns = 4096, [1032, 264]
+    x = ti.gaussian_x(m, 61)
+    xd = dev(x)
+    ts = [ti.quantile_threshold(x, 0.5), ti.quantile_threshold(x, 0.25)]
+    ws_host = [ti.weights_bf16(n, m, seed=62 + n) for n in ns]
+    wts = [dev(ti.to_input_channel_major(w)) for w in ws_host]
+    ws = workspace(T, m, sum(ns))
+    ys = [torch.full((n,), float("nan"), dtype=torch.float32, device="cuda") for n in ns]
+    T.check(T.teal_sparse_gemv_bf16_multi(wts, ts, ys, ns, xd, m, ws))
+    torch.cuda.synchronize()
+    direct = [y.clone() for y in ys]
+    run = T.prepare(lambda: T.teal_sparse_gemv_bf16_multi(wts, ts, ys, ns, xd, m, ws))
+    for _ in range(3):
+        for y in ys:
+            y.fill_(float("nan"))
+        T.check(run())
+        torch.cuda.synchronize()
+        for a, b in zip(direct, ys):
+            assert torch.equal(a, b)
+    assert rel_l2(ys[0].cpu().numpy(), orc.sparse_gemv_bf16(ws_host[0], x, ts[0])) <= TIGHT
+
+
 def test_calls_replay_from_a_hip_graph(T):
     """The calls only enqueue kernels on the given stream (no allocation, no host
     synchronisation, no memset), so a sequence of them can be captured once and replayed.
