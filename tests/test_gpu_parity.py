@@ -305,6 +305,36 @@ def test_gemv_bf16_full_size(T, model, proj):
         assert np.array_equal(idx[:count], idx_o)
 
 
+def test_relative_error_follows_theorem_a1_at_full_size(T, golden_dir):
+    """A property that holds at any size (Theorem A.1): for Gaussian x and Gaussian W the
+    error of the sparsified product relative to the dense one is sqrt(p - 2 t_p phi(t_p)).
+    Checked on the GPU's own dense (t = 0) and sparse outputs at 14336 x 4096, 4 draws of x."""
+    import os
+    rows = []
+    with open(os.path.join(golden_dir, "thm_a1_relative_error.txt")) as f:
+        for line in f:
+            if not line.startswith("#"):
+                rows.append(tuple(float(v) for v in line.split()))
+    n, m = 14336, 4096
+    g = torch.Generator(device="cuda")
+    g.manual_seed(99)
+    w = (torch.randn((n, m), generator=g, device="cuda") * 0.02).to(torch.bfloat16).view(torch.int16)
+    wt = torch.empty((m, n), dtype=torch.int16, device="cuda")
+    T.check(T.teal_pack_bf16(w, wt, m, n))
+    ws = workspace(T, m, n)
+    xs = [ti.gaussian_x(m, 8000 + k) for k in range(4)]
+    dense = [run_bf16(T, wt, dev(x), 0.0, m, n, ws).astype(np.float64) for x in xs]
+    for p, _, err in rows:
+        num = den = 0.0
+        for x, yd in zip(xs, dense):
+            t = ti.quantile_threshold(x, p)
+            ys = run_bf16(T, wt, dev(x), t, m, n, ws).astype(np.float64)
+            assert survivors(T, ws) == [int(np.count_nonzero(np.abs(x.astype(np.float32)) > np.float32(t)))]
+            num += np.linalg.norm(yd - ys)
+            den += np.linalg.norm(yd)
+        assert abs(num / den - err) <= 0.05 * err, (p, num / den, err)
+
+
 def test_gemv_bf16_70b_shape_sampled_rows(T):
     """28672 x 8192 (gate/up of the 70B-shaped block): sampled outputs one by one."""
     n, m = ti.LAYER_SHAPES["llama_70b"]["gate"]
