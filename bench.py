@@ -906,7 +906,7 @@ def main() -> int:
     th.start()
     k = 0
     while th.is_alive():
-        for _ in range(200):
+        for _ in range(max(1, 200 // args.layers)):
             one_step(T, stack, head, k)
             k += 1
         torch.cuda.synchronize()
