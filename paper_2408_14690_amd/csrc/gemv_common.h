@@ -435,14 +435,76 @@ __device__ __forceinline__ void stream_rows(float (&acc)[F::kElemsPerLane], cons
     }
 }
 
-// Adds the accumulators of the 64 / LPR row groups of a wavefront.
-template <int LPR, int N>
-__device__ __forceinline__ void fold_row_groups(float (&acc)[N])
+// Where column c of a tile lies in a wavefront's row of the LDS combine buffer.  Lanes
+// write their sums one float at a time (see store_wave_sums), EPL columns apart from their
+// neighbours; one float of padding per EPL columns keeps those writes off a common bank.
+template <int EPL, int LPR>
+__device__ __forceinline__ int combine_index(int c)
 {
+    return LPR == 64 ? c : c + c / EPL;
+}
+template <int EPL, int LPR>
+constexpr int combine_row = LPR == 64 ? LPR * EPL : LPR * EPL + LPR;
+
+// Two accumulators a and b of a lane are exchanged with the partner lane 16 (or 32) lanes
+// away such that one addition leaves a's pair sum in the even rows of 16 lanes (lower 32
+// lanes) and b's pair sum in the odd rows (upper 32 lanes).  Register moves only: a lane
+// shuffle goes through the LDS crossbar, which the 8 wavefronts of a block saturate
+// (measured: 0.85 us for the 64 shuffles per lane of the int4 kernel).
+__device__ __forceinline__ float pair_sum16(float a, float b)
+{
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(a), __float_as_uint(b), false,
+                                                    false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+__device__ __forceinline__ float pair_sum32(float a, float b)
+{
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(a), __float_as_uint(b), false,
+                                                    false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// Adds the accumulators of the 64 / LPR row groups of a wavefront (lanes that share their
+// columns: lane = group * LPR + l) and leaves the sums in this wavefront's row `dst` of the
+// combine buffer.  The row groups are added in the order ((g0 + g1) + (g2 + g3)) + ...;
+// every exchange halves the number of registers, so that in the end each sum is held by
+// exactly one lane: with R = 64 / LPR, register k of lane (rho, l), rho = lane / 16 (for
+// LPR = 32: lane / 32), holds column l * N + R' * k + rho of the tile, R' = min(R, 4).
+template <int LPR, int N>
+__device__ __forceinline__ void store_wave_sums(const float (&acc)[N], float *dst)
+{
+    const int lane = threadIdx.x & 63;
+    if constexpr (LPR == 64) {
+        float4 *d4 = reinterpret_cast<float4 *>(dst + lane * N);
 #pragma unroll
-    for (int off = LPR; off < 64; off <<= 1) {
+        for (int q = 0; q < N / 4; ++q)
+            d4[q] = make_float4(acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
+    } else if constexpr (LPR == 32) {
+        const int l = lane & 31, rho = lane >> 5;
 #pragma unroll
-        for (int e = 0; e < N; ++e) acc[e] += __shfl_xor(acc[e], off);
+        for (int j = 0; j < N / 2; ++j)
+            dst[combine_index<N, LPR>(l * N + 2 * j + rho)] = pair_sum32(acc[2 * j], acc[2 * j + 1]);
+    } else {
+        float v[N];
+#pragma unroll
+        for (int e = 0; e < N; ++e) v[e] = acc[e];
+        if constexpr (LPR == 8) {          // groups 8 lanes apart: a rotation within the row of 16
+#pragma unroll
+            for (int e = 0; e < N; ++e)
+                v[e] += __uint_as_float((unsigned)__builtin_amdgcn_update_dpp(
+                    0, (int)__float_as_uint(v[e]), 0x128 /* row_ror:8 */, 0xF, 0xF, false));
+        }
+        const int l = lane & (LPR - 1), rho = lane >> 4;
+        const bool writer = LPR == 16 || (lane & 8) == 0;   // with LPR = 8 both halves of a row hold the sums
+#pragma unroll
+        for (int k = 0; k < N / 4; ++k) {
+            const float r0 = pair_sum16(v[4 * k], v[4 * k + 1]);
+            const float r1 = pair_sum16(v[4 * k + 2], v[4 * k + 3]);
+            // rows 0, 2: columns 4k (r0) and 4k + 2 (r1); rows 1, 3: 4k + 1 and 4k + 3
+            const float s = pair_sum32(r0, r1);
+            // lower 32 lanes: r0's columns (4k + row), upper 32 lanes: r1's (4k + 2 + row - 2)
+            if (writer) dst[combine_index<N, LPR>(l * N + 4 * k + ((rho & 1) | (rho & 2)))] = s;
+        }
     }
 }
 
@@ -461,7 +523,7 @@ __device__ __forceinline__ void wave_share(int cnt, int w, int waves, int &start
 // y.  The split-K combine of Section 4.4, without atomics on y and without a
 // second launch.  The tile is columns [col0, col0 + cols) of y, cols <= TN.
 template <class F, int LPR, int WAVES>
-__device__ __forceinline__ void block_finish(const float (&acc)[F::kElemsPerLane], float *red,
+__device__ __forceinline__ void block_finish(float *red,
                                              float *partial, int *counters, float *y, int tile,
                                              int col0, int cols, int s, int splits, int n,
                                              const typename F::Args &a, int cnt,
@@ -472,7 +534,6 @@ __device__ __forceinline__ void block_finish(const float (&acc)[F::kElemsPerLane
     constexpr int THREADS = WAVES * 64;
     constexpr int OWN = (TN + THREADS - 1) / THREADS;     // columns c = thread + k * THREADS
     __shared__ int last_flag;
-    const int lane = threadIdx.x & 63;
     const int w = threadIdx.x >> 6;
     if (cols > n - col0) cols = n - col0;
     // What finish() needs per output column (the int8 scales) is loaded now, so that its
@@ -481,13 +542,8 @@ __device__ __forceinline__ void block_finish(const float (&acc)[F::kElemsPerLane
 #pragma unroll
     for (int k = 0; k < OWN; ++k)
         scale[k] = F::column_scale(a, col0 + min((int)threadIdx.x + k * THREADS, cols - 1));
-    if (lane < LPR) {
-        float4 *dst = reinterpret_cast<float4 *>(red + w * TN + lane * EPL);
-#pragma unroll
-        for (int q = 0; q < EPL / 4; ++q)
-            dst[q] = make_float4(acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
-    }
-    __syncthreads();
+    __syncthreads();                   // every wavefront has left its sums in red[]
+    constexpr int ROW = combine_row<EPL, LPR>;
     if (tile == 0 && threadIdx.x == 0) report_slice(report, s, splits, cnt);
     if (splits == 1) {
 #pragma unroll
@@ -496,7 +552,7 @@ __device__ __forceinline__ void block_finish(const float (&acc)[F::kElemsPerLane
             if (c < cols) {
                 float sum = 0.f;
 #pragma unroll
-                for (int ww = 0; ww < WAVES; ++ww) sum += red[ww * TN + c];
+                for (int ww = 0; ww < WAVES; ++ww) sum += red[ww * ROW + combine_index<EPL, LPR>(c)];
                 store_coherent(y + col0 + c, F::finish(sum, scale[k]));
             }
         }
@@ -512,7 +568,7 @@ __device__ __forceinline__ void block_finish(const float (&acc)[F::kElemsPerLane
     for (int c = threadIdx.x; c < cols; c += THREADS) {
         float sum = 0.f;
 #pragma unroll
-        for (int ww = 0; ww < WAVES; ++ww) sum += red[ww * TN + c];
+        for (int ww = 0; ww < WAVES; ++ww) sum += red[ww * ROW + combine_index<EPL, LPR>(c)];
         store_coherent(row + c, sum);
     }
     wait_vector_memory();   // this thread's write-through stores have completed
@@ -613,8 +669,8 @@ __device__ __forceinline__ void gemv_block(const typename F::Args &a, const XS &
 #pragma unroll
     for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
     stream_rows<F, LPR, U>(acc, list, start, mine, lane_base, row_bytes);
-    fold_row_groups<LPR>(acc);
-    block_finish<F, LPR, WAVES>(acc, red, partial, counters, y, tile, col0, tile_cols, s, splits, n,
+    store_wave_sums<LPR>(acc, red + (threadIdx.x >> 6) * combine_row<EPL, LPR>);
+    block_finish<F, LPR, WAVES>(red, partial, counters, y, tile, col0, tile_cols, s, splits, n,
                                 a, cnt, report);
 }
 
@@ -731,7 +787,8 @@ inline GemvGeometry gemv_geometry(int m, int n, const GemvShape &sh, int elems_p
     if (ks > kMaxSlice) ks = kMaxSlice;
     g.ks = ks;
     g.splits = (m + ks - 1) / ks;
-    g.lds = (size_t)ks * sizeof(int2) + (size_t)sh.waves * tn * sizeof(float);
+    // list + one row of the combine buffer per wavefront (padded by one float per lane)
+    g.lds = (size_t)ks * sizeof(int2) + (size_t)sh.waves * (tn + sh.lanes_per_row) * sizeof(float);
     return g;
 }
 

@@ -221,8 +221,8 @@ __device__ __forceinline__ void w4_block(const FmtW4::Args &a, const __half *__r
         issue(b0);
         consume(b1);
     }
-    fold_row_groups<LPR>(acc);
-    block_finish<F, LPR, WAVES>(acc, red, partial, counters, y, tile, col0, tile_cols, s, splits, n,
+    store_wave_sums<LPR>(acc, red + (threadIdx.x >> 6) * combine_row<EPL, LPR>);
+    block_finish<F, LPR, WAVES>(red, partial, counters, y, tile, col0, tile_cols, s, splits, n,
                                 a, cnt, report);
 }
 
