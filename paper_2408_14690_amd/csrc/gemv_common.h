@@ -124,6 +124,7 @@ __device__ __forceinline__ void report_total(const SurvivorReport &r, int splits
 // there, with the slice's own loads already in flight.
 struct HalfSource {                   // the hidden state itself, fp16 in memory
     static constexpr bool kHeavy = false;
+    static constexpr bool kPlainHalf = true;
     typedef __half Raw;
     const __half *x;
     __device__ __forceinline__ Raw load(int i) const { return x[i]; }
@@ -167,6 +168,7 @@ __device__ __forceinline__ float swiglu_value(float g, float u)
 
 struct SwigluSource {                 // gate = x W_gate^T and up = x W_up^T, fp32 in memory
     static constexpr bool kHeavy = true;
+    static constexpr bool kPlainHalf = false;
     typedef float2 Raw;
     const float *gate;
     const float *up;
@@ -294,6 +296,7 @@ __device__ __forceinline__ float rmsnorm_value(float h, float gamma, float r)
 
 struct RmsnormSource {                // hidden state and norm weights, fp32 in memory
     static constexpr bool kHeavy = false;
+    static constexpr bool kPlainHalf = false;
     typedef float2 Raw;
     const float *h;
     const float *gamma;
@@ -370,6 +373,54 @@ __device__ __forceinline__ int compact_slice(const XS &x, float t, int k0,
         }
     }
     __syncthreads();
+    return total;
+}
+
+// Wavefront-uniform contiguous share of `cnt` items for wavefront w of WAVES.
+__device__ __forceinline__ void wave_share(int cnt, int w, int waves, int &start, int &mine)
+{
+    const int per = cnt / waves, rem = cnt - per * waves;
+    start = w * per + min(w, rem);
+    mine = per + (w < rem ? 1 : 0);
+}
+
+// compact_slice for short slices (at most P segments of 64 channels) of an fp16 state,
+// without a barrier: every wavefront ballots ALL segments of the slice itself (P loads per
+// lane, the same number compact_slice issues), so it knows every count and writes exactly
+// those entries of list[] that fall into its own share [start, start + mine) -- the entries
+// it alone will read.  The result (list contents, total) is that of compact_slice.
+template <int P, int WAVES>
+__device__ __forceinline__ int compact_slice_private(const __half *__restrict__ x, float t, int k0,
+                                                     int k1, int2 *list)
+{
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    __half raw[P];
+#pragma unroll
+    for (int j = 0; j < P; ++j) raw[j] = x[min(k0 + j * 64 + lane, k1 - 1)];
+    float xv[P];
+    unsigned long long bal[P];
+    int base[P + 1];
+    base[0] = 0;
+#pragma unroll
+    for (int j = 0; j < P; ++j) {
+        const int i = k0 + j * 64 + lane;
+        xv[j] = i < k1 ? __half2float(raw[j]) : 0.f;          // x = 0 never survives (t >= 0)
+        bal[j] = __ballot(survives(xv[j], t));
+        base[j + 1] = base[j] + __popcll(bal[j]);
+    }
+    const int total = base[P];
+    int start, mine;
+    wave_share(total, w, WAVES, start, mine);
+    const int end = start + mine;
+#pragma unroll
+    for (int j = 0; j < P; ++j) {
+        if (base[j] < end && base[j + 1] > start) {           // wavefront-uniform
+            const int rank = base[j] + lanes_below(bal[j]);
+            if (survives(xv[j], t) && rank >= start && rank < end)
+                list[rank] = make_int2(k0 + j * 64 + lane, __float_as_int(xv[j]));
+        }
+    }
     return total;
 }
 
@@ -508,14 +559,6 @@ __device__ __forceinline__ void store_wave_sums(const float (&acc)[N], float *ds
     }
 }
 
-// Wavefront-uniform contiguous share of `cnt` items for wavefront w of WAVES.
-__device__ __forceinline__ void wave_share(int cnt, int w, int waves, int &start, int &mine)
-{
-    const int per = cnt / waves, rem = cnt - per * waves;
-    start = w * per + min(w, rem);
-    mine = per + (w < rem ? 1 : 0);
-}
-
 // Sums the wavefronts' accumulators through LDS.  With one split the sums are
 // the outputs.  Otherwise the block writes its fp32 partial row, and the block
 // that arrives last at the tile's counter adds the partial rows of all splits
@@ -651,8 +694,17 @@ __device__ __forceinline__ void gemv_block(const typename F::Args &a, const XS &
 
     const int k0 = s * ks;
     const int k1 = min(m, k0 + ks);
-    int seg_excl;
-    const int cnt = compact_slice<WAVES>(x, t, k0, k1, list, seg_cnt, seg_excl);
+    int cnt;
+    if constexpr (XS::kPlainHalf) {
+        // short slices: each wavefront compacts its own share, no barrier before the stream
+        const int nseg = (k1 - k0 + 63) >> 6;                 // block-uniform
+        int seg_excl;
+        if (nseg <= 8) cnt = compact_slice_private<8, WAVES>(x.x, t, k0, k1, list);
+        else cnt = compact_slice<WAVES>(x, t, k0, k1, list, seg_cnt, seg_excl);
+    } else {
+        int seg_excl;
+        cnt = compact_slice<WAVES>(x, t, k0, k1, list, seg_cnt, seg_excl);
+    }
 
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
