@@ -388,10 +388,10 @@ __device__ __forceinline__ void wave_share(int cnt, int w, int waves, int &start
 // without a barrier: every wavefront ballots ALL segments of the slice itself (P loads per
 // lane, the same number compact_slice issues), so it knows every count and writes exactly
 // those entries of list[] that fall into its own share [start, start + mine) -- the entries
-// it alone will read.  The result (list contents, total) is that of compact_slice.
+// it alone will read.  The result (list contents, total, seg_excl) is that of compact_slice.
 template <int P, int WAVES>
 __device__ __forceinline__ int compact_slice_private(const __half *__restrict__ x, float t, int k0,
-                                                     int k1, int2 *list)
+                                                     int k1, int2 *list, int &seg_excl)
 {
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -410,6 +410,9 @@ __device__ __forceinline__ int compact_slice_private(const __half *__restrict__ 
         base[j + 1] = base[j] + __popcll(bal[j]);
     }
     const int total = base[P];
+    seg_excl = total;                                         // lane j: prefix of segment j
+#pragma unroll
+    for (int j = 0; j < P; ++j) seg_excl = lane == j ? base[j] : seg_excl;
     int start, mine;
     wave_share(total, w, WAVES, start, mine);
     const int end = start + mine;
@@ -699,7 +702,7 @@ __device__ __forceinline__ void gemv_block(const typename F::Args &a, const XS &
         // short slices: each wavefront compacts its own share, no barrier before the stream
         const int nseg = (k1 - k0 + 63) >> 6;                 // block-uniform
         int seg_excl;
-        if (nseg <= 8) cnt = compact_slice_private<8, WAVES>(x.x, t, k0, k1, list);
+        if (nseg <= 8) cnt = compact_slice_private<8, WAVES>(x.x, t, k0, k1, list, seg_excl);
         else cnt = compact_slice<WAVES>(x, t, k0, k1, list, seg_cnt, seg_excl);
     } else {
         int seg_excl;

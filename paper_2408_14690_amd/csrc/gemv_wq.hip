@@ -127,7 +127,11 @@ __device__ __forceinline__ void w4_block(const FmtW4::Args &a, const __half *__r
     const int k0 = s * ks;                       // multiple of 128
     const int k1 = min(m, k0 + ks);
     int seg_excl;
-    const int cnt = compact_slice<WAVES>(HalfSource{x}, t, k0, k1, list, seg_cnt, seg_excl);
+    int cnt;
+    if (k1 - k0 <= 8 * 64)             // block-uniform: short slices need no barrier
+        cnt = compact_slice_private<8, WAVES>(x, t, k0, k1, list, seg_excl);
+    else
+        cnt = compact_slice<WAVES>(HalfSource{x}, t, k0, k1, list, seg_cnt, seg_excl);
 
     const int lane = threadIdx.x & 63;
     const int g = lane / LPR;
