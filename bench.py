@@ -51,8 +51,8 @@ KERNEL = {"bf16": "sparse_gemv_kernel<FmtBF16>", "w8": "sparse_gemv_kernel<FmtW8
 # grouped launches): profiles/sparse_gemv_multi_kernel_llama2_7b_hbm_traffic.txt and
 # profiles/sparse_gemv_kernel_llama2_7b_hbm_traffic.txt.
 MEASURED_TRAFFIC_BYTES = {
-    ("llama2_7b", "bf16", 0.5, 1, True): (199437.14 + 1129.88) * 1024 / 4,
-    ("llama2_7b", "bf16", 0.5, 1, False): (200376.19 + 1557.28) * 1024 / 7,
+    ("llama2_7b", "bf16", 0.5, 1, True): (199496.56 + 1129.88) * 1024 / 4,
+    ("llama2_7b", "bf16", 0.5, 1, False): (200452.62 + 1557.28) * 1024 / 7,
 }
 
 
