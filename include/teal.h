@@ -135,6 +135,41 @@ teal_status teal_sparse_gemv_bf16_multi(int count, const void *const *Wt_bf16, c
                                         void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Several grouped calls that do not depend on each other, in one kernel
+ * launch.  Group g is what teal_sparse_gemv_bf16_multi computes for its
+ * counts[g] matrices and its own input x_g of length m_g; the results are
+ * bitwise those of the groups' separate calls.  The case is a bare stack of
+ * projections timed as kernels in isolation (as Section 4.4 times one
+ * product; the shapes of Appendix A.3, every group with an input of its own,
+ * nothing between the products): a group's
+ * thread blocks start as those of the group before it retire, so the ends of
+ * a call during which little memory traffic flows lie under another group's
+ * weight rows.  There is NO ordering between the groups: no group may read
+ * what another group of the same call writes, and no two outputs may overlap.
+ * (Inside a decoder the projections do depend on each other and are issued as
+ * separate grouped calls.)
+ *   groups  1..16.
+ *   counts  HOST array [groups]: matrices in each group, 1..4.
+ *   Wt_bf16, t, y, n   HOST arrays over all matrices, group after group
+ *           (length counts[0] + ... + counts[groups-1]), as for
+ *           teal_sparse_gemv_bf16_multi.
+ *   x_f16, m  HOST arrays [groups]: device pointer to each group's input and
+ *           its length.
+ *   workspace  at least teal_workspace_bytes_stack(groups, counts, n, m), zero
+ *           before first use like every workspace.  The groups' regions follow
+ *           each other; region g is laid out and sized like the workspace of
+ *           group g's own call (teal_workspace_bytes(m_g, sum of its n)), so
+ *           its survivor report sits teal_survivors_offset() bytes into it.
+ * teal_workspace_bytes_stack returns 0 for dimensions out of range.
+ */
+size_t teal_workspace_bytes_stack(int groups, const int *counts, const int *n, const int *m);
+teal_status teal_sparse_gemv_bf16_stack(int groups, const int *counts,
+                                        const void *const *Wt_bf16, const float *t,
+                                        float *const *y, const int *n, const void *const *x_f16,
+                                        const int *m, void *workspace, size_t workspace_bytes,
+                                        void *stream);
+
+/*
  * The grouped call with its shared input formed on the fly from the hidden
  * state before the normalisation layer.  Appendix A.3 feeds W_q, W_k, W_v (and
  * W_gate, W_up) with the block's normalised hidden state (Section 4.1 relates

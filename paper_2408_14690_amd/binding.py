@@ -31,7 +31,8 @@ EXPORTS = (
     "teal_sparse_gemv_w8_multi", "teal_sparse_gemv_w4_multi",
     "teal_swiglu_f16", "teal_sparse_gemv_bf16_swiglu", "teal_sparse_gemv_bf16_batch_multi",
     "teal_gemv_plan_multi", "teal_survivors_offset", "teal_rmsnorm_f16",
-    "teal_sparse_gemv_bf16_rmsnorm_multi",
+    "teal_sparse_gemv_bf16_rmsnorm_multi", "teal_workspace_bytes_stack",
+    "teal_sparse_gemv_bf16_stack",
 )
 TEAL_HIST_BINS = 32768
 TEAL_MAX_BATCH = 8
@@ -87,6 +88,12 @@ def load_library():
     lib.teal_sparse_gemv_bf16_multi.restype = i
     lib.teal_sparse_gemv_bf16_multi.argtypes = [i, c.POINTER(vp), c.POINTER(f), c.POINTER(vp),
                                                 c.POINTER(i), vp, i, vp, sz, vp]
+    lib.teal_workspace_bytes_stack.restype = sz
+    lib.teal_workspace_bytes_stack.argtypes = [i, c.POINTER(i), c.POINTER(i), c.POINTER(i)]
+    lib.teal_sparse_gemv_bf16_stack.restype = i
+    lib.teal_sparse_gemv_bf16_stack.argtypes = [i, c.POINTER(i), c.POINTER(vp), c.POINTER(f),
+                                                c.POINTER(vp), c.POINTER(i), c.POINTER(vp),
+                                                c.POINTER(i), vp, sz, vp]
     lib.teal_sparse_gemv_w8_multi.restype = i
     lib.teal_sparse_gemv_w8_multi.argtypes = [i, c.POINTER(vp), c.POINTER(vp), c.POINTER(f),
                                               c.POINTER(vp), c.POINTER(i), vp, i, vp, sz, vp]
@@ -303,6 +310,40 @@ def teal_sparse_gemv_bf16_multi(Wt_list, t_list, y_list, n_list, x_f16, m, works
         "teal_sparse_gemv_bf16_multi",
         count, W, Tt, Y, N, _ptr(x_f16, 2 * m, "x"), int(m), _ptr(workspace),
         _nbytes(workspace, workspace_bytes), _stream(stream))
+
+
+def teal_workspace_bytes_stack(counts, n_list, m_list) -> int:
+    """Workspace of a stack call: counts[g] matrices per group, n over all matrices, m per group."""
+    C = (ctypes.c_int * len(counts))(*[int(c) for c in counts])
+    N = (ctypes.c_int * len(n_list))(*[int(n) for n in n_list])
+    M = (ctypes.c_int * len(m_list))(*[int(m) for m in m_list])
+    if len(m_list) != len(counts) or sum(int(c) for c in counts) != len(n_list):
+        raise ValueError("counts, n and m do not describe the same groups")
+    return int(load_library().teal_workspace_bytes_stack(len(counts), C, N, M))
+
+
+def teal_sparse_gemv_bf16_stack(counts, Wt_list, t_list, y_list, n_list, x_list, m_list,
+                                workspace, workspace_bytes=None, stream=None) -> int:
+    """len(counts) independent groups in one launch; matrices listed group after group."""
+    groups = len(counts)
+    total = sum(int(c) for c in counts)
+    if not (len(Wt_list) == len(t_list) == len(y_list) == len(n_list) == total):
+        raise ValueError("per-matrix lists must have one entry per matrix of every group")
+    if not (len(x_list) == len(m_list) == groups):
+        raise ValueError("per-group lists must have one entry per group")
+    group_of = [g for g, c in enumerate(counts) for _ in range(int(c))]
+    W = (ctypes.c_void_p * total)(*[_ptr(w, 2 * m_list[g] * n, "Wt")
+                                    for w, n, g in zip(Wt_list, n_list, group_of)])
+    Y = (ctypes.c_void_p * total)(*[_ptr(y, 4 * n, "y") for y, n in zip(y_list, n_list)])
+    Tt = (ctypes.c_float * total)(*[float(t) for t in t_list])
+    N = (ctypes.c_int * total)(*[int(n) for n in n_list])
+    C = (ctypes.c_int * groups)(*[int(c) for c in counts])
+    X = (ctypes.c_void_p * groups)(*[_ptr(x, 2 * m, "x") for x, m in zip(x_list, m_list)])
+    M = (ctypes.c_int * groups)(*[int(m) for m in m_list])
+    return _call(
+        "teal_sparse_gemv_bf16_stack",
+        groups, C, W, Tt, Y, N, X, M, _ptr(workspace), _nbytes(workspace, workspace_bytes),
+        _stream(stream))
 
 
 def teal_workspace_bytes_batch(m: int, n: int, batch: int) -> int:

@@ -760,11 +760,12 @@ struct MultiArgs {
 
 template <class F, int LPR, int WAVES, int U, class XS>
 __device__ __forceinline__ void multi_block(const MultiArgs<F> &ma, const XS &x, float *partial,
-                                            int *counters, int m, int ks, int tile_cols, int splits)
+                                            int *counters, int m, int ks, int tile_cols, int splits,
+                                            int block)
 {
     const int tiles = ma.tile_begin[ma.count];
-    const int gtile = blockIdx.x % tiles;
-    const int s = blockIdx.x / tiles;
+    const int gtile = block % tiles;
+    const int s = block / tiles;
     int k = 0;
     size_t partial_off = 0;            // each matrix owns splits * n floats of partial rows
 #pragma unroll
@@ -785,7 +786,8 @@ __global__ __launch_bounds__(WAVES * 64) void sparse_gemv_multi_kernel(
     MultiArgs<F> ma, const __half *__restrict__ x, float *partial, int *counters, int m, int ks,
     int tile_cols, int splits)
 {
-    multi_block<F, LPR, WAVES, U>(ma, HalfSource{x}, partial, counters, m, ks, tile_cols, splits);
+    multi_block<F, LPR, WAVES, U>(ma, HalfSource{x}, partial, counters, m, ks, tile_cols, splits,
+                                  (int)blockIdx.x);
 }
 
 // The grouped launch with its shared input formed in the kernel from the hidden state
@@ -800,7 +802,54 @@ __global__ __launch_bounds__(kNormWaves * 64) void sparse_gemv_rmsnorm_multi_ker
 {
     __shared__ double wave_sums[kMaxNormChunks * kNormWaves];
     multi_block<F, LPR, kNormWaves, U>(ma, RmsnormSource{h, gamma, m, eps, wave_sums}, partial,
-                                       counters, m, ks, tile_cols, splits);
+                                       counters, m, ks, tile_cols, splits, (int)blockIdx.x);
+}
+
+// Several grouped calls that do not depend on each other (the projections of a bare stack
+// of decoder blocks, Appendix A.3, each group with its own input) in one launch.  The
+// groups' blocks follow each other in the grid, so the hardware starts a group's blocks
+// as the blocks of the one before it retire: the ends of a call that leave most of the
+// chip idle (compaction before the first weight load, the split-K combine, the gap to the
+// next kernel) lie under another group's row stream.  Each group runs the block body of
+// its own grouped launch with its own shape, workspace region and report.
+constexpr int kMaxStack = kMaxStackGroups;
+
+template <class F>
+struct StackGroup {
+    MultiArgs<F> ma;
+    const __half *x;
+    float *partial;
+    int *counters;
+    int m, ks, tile_cols, splits;
+    int lanes_per_row;               // 16, 32 or 64
+};
+
+template <class F>
+struct StackArgs {
+    StackGroup<F> g[kMaxStack];
+    int block_begin[kMaxStack + 1];  // first block of each group; [count] = grid size
+    int count;
+};
+
+template <class F, int WAVES, int U>
+__global__ __launch_bounds__(WAVES * 64) void sparse_gemv_stack_kernel(StackArgs<F> sa)
+{
+    int k = 0;
+#pragma unroll
+    for (int j = 1; j < kMaxStack; ++j)
+        if (j < sa.count && (int)blockIdx.x >= sa.block_begin[j]) k = j;
+    const StackGroup<F> &sg = sa.g[k];
+    const int block = (int)blockIdx.x - sa.block_begin[k];
+    const HalfSource x{sg.x};
+    if (sg.lanes_per_row == 64)
+        multi_block<F, 64, WAVES, U>(sg.ma, x, sg.partial, sg.counters, sg.m, sg.ks, sg.tile_cols,
+                                     sg.splits, block);
+    else if (sg.lanes_per_row == 32)
+        multi_block<F, 32, WAVES, U>(sg.ma, x, sg.partial, sg.counters, sg.m, sg.ks, sg.tile_cols,
+                                     sg.splits, block);
+    else
+        multi_block<F, 16, WAVES, U>(sg.ma, x, sg.partial, sg.counters, sg.m, sg.ks, sg.tile_cols,
+                                     sg.splits, block);
 }
 
 // Host-side launch geometry shared by the formats.

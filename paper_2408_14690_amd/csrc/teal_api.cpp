@@ -190,7 +190,7 @@ const char *teal_status_string(teal_status s)
     return "unknown status";
 }
 
-int teal_version(void) { return 300; }
+int teal_version(void) { return 310; }
 
 size_t teal_survivors_offset(void) { return teal::kCounterBytes; }
 
@@ -372,6 +372,71 @@ teal_status teal_sparse_gemv_bf16_multi(int count, const void *const *Wt_bf16, c
     return from_hip(teal::launch_gemv_bf16_multi(count, Wt_bf16, t, y, n, x_f16, m,
                                                  ws_partials(workspace, m), ws_counters(workspace),
                                                  sh, static_cast<hipStream_t>(stream)));
+}
+
+// Region of group g in a stack call's workspace: the groups' regions follow each other,
+// each laid out and sized as the workspace of that group's own grouped call.
+static bool stack_group_dims(int count, const int *n, int m, long long &n_total)
+{
+    if (count < 1 || count > teal::kMaxMatrices) return false;
+    n_total = 0;
+    for (int k = 0; k < count; ++k) {
+        if (n[k] < 8 || n[k] > teal::kMaxDim || n[k] % 8 != 0) return false;
+        n_total += n[k];
+    }
+    return m >= 1 && m <= teal::kMaxDim && n_total <= teal::kMaxDim;
+}
+
+size_t teal_workspace_bytes_stack(int groups, const int *counts, const int *n, const int *m)
+{
+    if (groups < 1 || groups > teal::kMaxStackGroups || !counts || !n || !m) return 0;
+    size_t bytes = 0;
+    for (int g = 0, first = 0; g < groups; first += counts[g], ++g) {
+        long long n_total;
+        if (counts[g] < 1 || counts[g] > teal::kMaxMatrices) return 0;
+        if (!stack_group_dims(counts[g], n + first, m[g], n_total)) return 0;
+        bytes += teal_workspace_bytes(m[g], (int)n_total);
+    }
+    return bytes;
+}
+
+teal_status teal_sparse_gemv_bf16_stack(int groups, const int *counts,
+                                        const void *const *Wt_bf16, const float *t,
+                                        float *const *y, const int *n, const void *const *x_f16,
+                                        const int *m, void *workspace, size_t workspace_bytes,
+                                        void *stream)
+{
+    if (groups < 1 || groups > teal::kMaxStackGroups) return TEAL_ERR_UNSUPPORTED;
+    if (!counts || !Wt_bf16 || !t || !y || !n || !x_f16 || !m || !workspace) return TEAL_ERR_NULL;
+    for (int g = 0; g < groups; ++g)
+        if (counts[g] < 1 || counts[g] > teal::kMaxMatrices) return TEAL_ERR_UNSUPPORTED;
+    if (!aligned(workspace, kAlignWorkspace)) return TEAL_ERR_ALIGN;
+    teal::StackGroupDesc d[teal::kMaxStackGroups];
+    size_t offset = 0;
+    for (int g = 0, first = 0; g < groups; first += counts[g], ++g) {
+        const int count = counts[g];
+        if (!x_f16[g]) return TEAL_ERR_NULL;
+        for (int k = 0; k < count; ++k)
+            if (!Wt_bf16[first + k] || !y[first + k]) return TEAL_ERR_NULL;
+        long long n_total;
+        if (!stack_group_dims(count, n + first, m[g], n_total)) return TEAL_ERR_SHAPE;
+        for (int k = 0; k < count; ++k)
+            if (!aligned(Wt_bf16[first + k], 16) || !aligned(y[first + k], 4))
+                return TEAL_ERR_ALIGN;
+        if (!aligned(x_f16[g], 2)) return TEAL_ERR_ALIGN;
+        for (int k = 0; k < count; ++k)
+            if (!threshold_ok(t[first + k])) return TEAL_ERR_THRESHOLD;
+        unsigned char *region = static_cast<unsigned char *>(workspace) + offset;
+        offset += teal_workspace_bytes(m[g], (int)n_total);
+        if (offset > workspace_bytes) return TEAL_ERR_WORKSPACE;
+        // The launch shape of teal_sparse_gemv_bf16_multi for this group: same sums, bit for bit.
+        const GemvShape sh = count > 1 ? auto_shape_multi(m[g], n + first, count, 8, 16, 64, 64)
+                                       : auto_shape(m[g], (int)n_total, 8, 16, 64, 64);
+        d[g] = teal::StackGroupDesc{count, Wt_bf16 + first, t + first, y + first, n + first,
+                                    x_f16[g], m[g], ws_partials(region, m[g]),
+                                    ws_counters(region), sh};
+    }
+    return from_hip(teal::launch_gemv_bf16_stack(groups, d, static_cast<hipStream_t>(stream)));
 }
 
 teal_status teal_rmsnorm_f16(const float *h, const float *gamma, float eps, void *x_f16, int m,

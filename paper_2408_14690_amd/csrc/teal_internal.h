@@ -62,6 +62,23 @@ hipError_t launch_gemv_bf16_multi(int count, const void *const *Wt, const float 
                                   float *partial, int *counters, const GemvShape &shape,
                                   hipStream_t stream);
 
+// Up to kMaxStackGroups grouped bf16 calls that do not depend on each other, in one launch.
+// Shapes with 8 wavefronts, 4 loads per batch and 16, 32 or 64 lanes per row.
+constexpr int kMaxStackGroups = 16;
+struct StackGroupDesc {
+    int count;                 // matrices of the group, 1..kMaxMatrices
+    const void *const *Wt;
+    const float *t;
+    float *const *y;
+    const int *n;
+    const void *x_f16;
+    int m;
+    float *partial;            // the group's own partial rows and counters
+    int *counters;
+    GemvShape shape;
+};
+hipError_t launch_gemv_bf16_stack(int groups, const StackGroupDesc *g, hipStream_t stream);
+
 // Small batch (Section 5.4.4).  The slice of a block, ceil(m / splits) rounded up to 64,
 // must not exceed kMaxSliceBatch.
 bool gemv_batch_shape_supported(int batch, const GemvShape &s);

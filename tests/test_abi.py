@@ -143,6 +143,44 @@ def test_multi_argument_errors():
     assert T.teal_sparse_gemv_bf16_multi([], [], [], [], X, 4096, WS, BIG, 0) == T.TEAL_ERR_UNSUPPORTED
 
 
+def test_stack_argument_errors_and_workspace():
+    """teal_sparse_gemv_bf16_stack: every check happens on the host before any HIP call; the
+    workspace is the sum of the groups' own workspaces."""
+    ok = dict(counts=[2, 1], Wt_list=[W, W + 0x1000, W + 0x2000], t_list=[0.5, 0.25, 0.4],
+              y_list=[Y, Y + 0x1000, Y + 0x2000], n_list=[4096, 1024, 11008], x_list=[X, X + 0x100],
+              m_list=[4096, 2048], workspace=WS, workspace_bytes=BIG, stream=0)
+
+    def call(**kw):
+        a = dict(ok)
+        a.update(kw)
+        return T.teal_sparse_gemv_bf16_stack(**a)
+
+    need = T.teal_workspace_bytes_stack([2, 1], [4096, 1024, 11008], [4096, 2048])
+    assert need == T.teal_workspace_bytes(4096, 5120) + T.teal_workspace_bytes(2048, 11008)
+    assert call(Wt_list=[W, W, None]) == T.TEAL_ERR_NULL
+    assert call(y_list=[Y, None, Y]) == T.TEAL_ERR_NULL
+    assert call(x_list=[X, None]) == T.TEAL_ERR_NULL
+    assert call(n_list=[4096, 1024, 11004]) == T.TEAL_ERR_SHAPE
+    assert call(m_list=[4096, 0]) == T.TEAL_ERR_SHAPE
+    assert call(Wt_list=[W, W + 8, W]) == T.TEAL_ERR_ALIGN
+    assert call(x_list=[X, X + 1]) == T.TEAL_ERR_ALIGN
+    assert call(workspace=WS + 64) == T.TEAL_ERR_ALIGN
+    assert call(t_list=[0.5, 0.25, math.nan]) == T.TEAL_ERR_THRESHOLD
+    assert call(workspace_bytes=need - 1) == T.TEAL_ERR_WORKSPACE
+    assert call(workspace_bytes=T.teal_workspace_bytes(4096, 5120)) == T.TEAL_ERR_WORKSPACE
+    five = dict(counts=[5], Wt_list=[W] * 5, t_list=[0.5] * 5, y_list=[Y] * 5, n_list=[64] * 5,
+                x_list=[X], m_list=[4096])
+    assert call(**five) == T.TEAL_ERR_UNSUPPORTED
+    many = dict(counts=[1] * 17, Wt_list=[W] * 17, t_list=[0.5] * 17, y_list=[Y] * 17,
+                n_list=[64] * 17, x_list=[X] * 17, m_list=[64] * 17)
+    assert call(**many) == T.TEAL_ERR_UNSUPPORTED
+    assert T.teal_workspace_bytes_stack([1] * 17, [64] * 17, [64] * 17) == 0
+    assert T.teal_workspace_bytes_stack([5], [64] * 5, [64]) == 0
+    assert T.teal_workspace_bytes_stack([1], [60], [64]) == 0
+    with pytest.raises(ValueError):
+        T.teal_sparse_gemv_bf16_stack([2], [W], [0.5], [Y], [64], [X], [64], WS, BIG, 0)
+
+
 def test_w8_multi_argument_errors():
     ok = dict(Wq_list=[W, W + 0x1000], scale_list=[SC, SC + 0x100], t_list=[0.5, 0.25],
               y_list=[Y, Y + 0x1000], n_list=[4096, 1024], x_f16=X, m=4096, workspace=WS,
