@@ -48,11 +48,13 @@ KERNEL = {"bf16": "sparse_gemv_kernel<FmtBF16>", "w8": "sparse_gemv_kernel<FmtW8
 # HBM bytes per launch at 50% (average over the launches of a step), from rocprofv3 --pmc
 # FETCH_SIZE / WRITE_SIZE runs of this script, scaled by the factors a plain copy of known
 # size gives on the same box (2.0 and 1.0).  Keyed by (workload, format, sparsity, layers,
-# grouped launches): profiles/sparse_gemv_multi_kernel_llama2_7b_hbm_traffic.txt and
-# profiles/sparse_gemv_kernel_llama2_7b_hbm_traffic.txt.
+# grouped launches | "stack"): profiles/sparse_gemv_multi_kernel_llama2_7b_hbm_traffic.txt,
+# profiles/sparse_gemv_kernel_llama2_7b_hbm_traffic.txt and
+# profiles/sparse_gemv_stack_kernel_llama2_7b_kernel_trace_hbm_traffic.txt.
 MEASURED_TRAFFIC_BYTES = {
-    ("llama2_7b", "bf16", 0.5, 1, True): (199496.56 + 1129.88) * 1024 / 4,
-    ("llama2_7b", "bf16", 0.5, 1, False): (200452.62 + 1557.28) * 1024 / 7,
+    ("llama2_7b", "bf16", 0.5, 1, True): (199469.51 + 1129.88) * 1024 / 4,
+    ("llama2_7b", "bf16", 0.5, 1, False): (200469.62 + 1557.28) * 1024 / 7,
+    ("llama2_7b", "bf16", 0.5, 1, "stack"): (199512.0 + 1129.88) * 1024,
 }
 
 
@@ -257,6 +259,24 @@ class StackCall:
         return ok, compared
 
 
+class Replica:
+    """A projection as one of several independent products in a stack launch: the same
+    x and thresholds, its own output, and the weight copies walked from its own offset (so
+    that the replicas of one launch read different memory)."""
+
+    def __init__(self, torch, P, j: int):
+        self.name, self.m, self.ns, self.stream = P.name, P.m, [P.n], P.stream
+        self.y = torch.empty(P.n, dtype=torch.float32, device="cuda")
+        self.ys = [self.y.data_ptr()]
+        j %= len(P.wp)
+        self.wp, self.t, self.nnz, self.xp = P.wp[j:] + P.wp[:j], P.t, P.nnz, P.xp
+        self.members = [self]
+        self._bytes = P.bytes
+
+    def bytes(self, p: float) -> int:
+        return self._bytes(p)
+
+
 def fuse(T, torch, stack):
     """Group consecutive projections of each block that share their input (Appendix A.3)."""
     out, i = [], 0
@@ -398,6 +418,10 @@ def survivor_counts_match(T, torch, stack, p: float):
     off = T.teal_survivors_offset()
     ok, compared = True, 0
     for C in stack:
+        if hasattr(C, "survivors_match"):
+            one_ok, count = C.survivors_match(T, torch, p)
+            ok, compared = ok and one_ok, compared + count
+            continue
         members = getattr(C, "members", [C])
         got = C.ws[off:off + 4 * len(members)].view(torch.int32).cpu().tolist()
         ok = ok and got == [P.nnz[p] for P in members]
@@ -770,6 +794,10 @@ def main() -> int:
                          "read the same hidden state: q+k+v, o, gate+up, down")
     ap.add_argument("--unfused", action="store_true",
                     help="one launch per projection (7 per block) as the headline")
+    ap.add_argument("--stack-launch", action="store_true",
+                    help="headline = the groups of the pass as independent work in one launch per "
+                         "16 groups (teal_sparse_gemv_bf16_stack): a bare stack of projections, "
+                         "not a decoder's dependent sequence")
     ap.add_argument("--batch", type=int, default=0,
                     help="B >= 1: a small batch of B hidden states per projection with the batch-wide "
                          "mask of the averaged magnitude (Section 5.4.4); bf16 only. 0 = one state")
@@ -832,7 +860,16 @@ def main() -> int:
                               args.batch)
     block0 = projections[:7]
     groups = fuse(T, torch, projections)
-    stack = groups if fused else projections
+    stack_calls = None
+    if fmt == "bf16" and not args.batch and (args.stack_launch or not args.no_other_mode):
+        stack_calls = [StackCall(T, torch, groups[i:i + 16]) for i in range(0, len(groups), 16)]
+    if args.stack_launch:
+        if stack_calls is None or args.unfused:
+            print("bench.py: --stack-launch needs bf16, batch 1 and grouped launches", file=sys.stderr)
+            return 2
+        stack = stack_calls
+    else:
+        stack = groups if fused else projections
     launches_per_step = len(stack)
 
     def timed_passes(calls):
@@ -862,15 +899,14 @@ def main() -> int:
     # teal_sparse_gemv_bf16_multi), or the grouped launches when the headline does not.
     other_detail = {}
     if groups is not None and not args.no_other_mode:
-        _, other_detail = timed_passes(projections if fused else groups)
+        _, other_detail = timed_passes(projections if fused and not args.stack_launch else groups)
 
     # The whole pass as a bare stack: the groups do not depend on each other here (every group
     # has its own synthetic input), so up to 16 of them go out as one launch and the ends of
     # one group's work lie under the next group's row stream.  Reported beside the headline,
     # never as it: inside a decoder the groups depend on each other and are separate launches.
     stack_detail = {}
-    if fmt == "bf16" and not args.batch and not args.no_other_mode:
-        stack_calls = [StackCall(T, torch, groups[i:i + 16]) for i in range(0, len(groups), 16)]
+    if stack_calls is not None and not args.no_other_mode and not args.stack_launch:
         _, stack_detail = timed_passes(stack_calls)
         one_step(T, stack_calls, head, 0)
         torch.cuda.synchronize()
@@ -919,12 +955,34 @@ def main() -> int:
         if groups is not None:
             per_group = alone(groups[:4])
 
+    # Each projection as one of 16 independent products of its own shape in one launch: its
+    # time when the serial ends of a call lie under other products' row streams.
+    per_proj_stack = {}
+    if stack_calls is not None and not args.no_per_projection:
+        for P in block0:
+            if len(P.wp) < 2:
+                continue
+            call = StackCall(T, torch, [Replica(torch, P, j) for j in range(16)])
+            us = time_projection(T, torch, call, head, 100) * 1e6 / 16
+            us_dense = time_projection(T, torch, call, 0.0, 100) * 1e6 / 16
+            b = P.bytes(head)
+            per_proj_stack[P.name] = {
+                "n": P.n, "m": P.m, "us_per_projection": us, "us_per_projection_dense": us_dense,
+                "effective_GBps": b / us / 1e3, "frac_of_hbm_peak": b / us / 1e3 / HBM_PEAK_GBS,
+                "speedup_vs_dense": us_dense / us,
+                # bytes read before a weight copy comes round again; the last-level cache holds 256 MB
+                "weight_bytes_walked": len(P.wp) * P.nnz[head] * P.n * BITS[fmt] // 8,
+            }
+            del call
+
     multi_kernel = {"bf16": "sparse_gemv_multi_kernel<FmtBF16>", "w8": "sparse_gemv_multi_kernel<FmtW8>",
                     "w4": "sparse_gemv_w4_multi_kernel"}[fmt]
     if args.batch:
         kernel = "sparse_gemv_batch_multi_kernel" if fused else "sparse_gemv_batch_kernel"
     else:
         kernel = multi_kernel if fused else KERNEL[fmt]
+    if args.stack_launch:
+        kernel = "sparse_gemv_stack_kernel<FmtBF16>"
     out = {
         "metric": f"sparse GEMV effective HBM GB/s at {pct(head)} sparsity (one decoder-block "
                   f"pass); us and speedup vs dense per sparsity in detail",
@@ -947,7 +1005,10 @@ def main() -> int:
             "weight_format": fmt,
             "weight_bytes_per_block": block_bytes,
             "blocks_per_step": args.layers,
-            "launches": "one per group of projections that read the same hidden state (q+k+v, o, "
+            "launches": "one per 16 groups (q+k+v, o, gate+up, down of 4 blocks), the groups taken "
+                        "as independent work: a bare stack of projections, not a decoder's "
+                        "dependent sequence" if args.stack_launch else
+                        "one per group of projections that read the same hidden state (q+k+v, o, "
                         "gate+up, down), each projection with its own threshold" if fused
                         else "one per projection",
             "weight_copies_walked": copies,
@@ -958,17 +1019,20 @@ def main() -> int:
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
-            "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, fmt, head, args.layers, fused)),
+            "traffic": MEASURED_TRAFFIC_BYTES.get(
+                (args.workload, fmt, head, args.layers, "stack" if args.stack_launch else fused)),
             "kernel": f"{kernel} ({launches_per_step} launches per step, {pct(head)})",
             "bytes_per_launch_avg": head_bytes / launches_per_step,
             "kernel_avg_us": seconds[head] * 1e6 / launches_per_step,
         },
         "detail": detail,
-        ("detail_one_launch_per_projection" if fused else "detail_grouped_launches"): other_detail,
+        ("detail_one_launch_per_projection" if fused and not args.stack_launch
+         else "detail_grouped_launches"): other_detail,
         "detail_independent_groups_in_one_launch": stack_detail,
         "detail_hip_graph_replay": graph_detail,
         f"per_projection_alone_{pct(head)}": per_proj,
         f"per_group_alone_{pct(head)}": per_group,
+        f"per_projection_in_a_launch_of_16_independent_{pct(head)}": per_proj_stack,
     }
     # the same reading while the headline pass keeps the GPU busy (about a second of steps)
     import threading

@@ -737,7 +737,7 @@ def test_calls_replay_from_a_hip_graph(T):
     tb = ti.batch_quantile_threshold(X, 0.5)
     ws = workspace(T, m, 2 * n + 1040)
     wsb = torch.zeros(T.teal_workspace_bytes_batch(m, n, 4), dtype=torch.uint8, device="cuda")
-    outs = [torch.zeros(n, dtype=torch.float32, device="cuda") for _ in range(6)]
+    outs = [torch.zeros(n, dtype=torch.float32, device="cuda") for _ in range(9)]
     y8 = torch.zeros(1040, dtype=torch.float32, device="cuda")
     Yb = torch.zeros((4, n), dtype=torch.float32, device="cuda")
     gate, up = ti.mlp_gate_up(m, 45)
@@ -747,6 +747,11 @@ def test_calls_replay_from_a_hip_graph(T):
     th = ti.quantile_threshold(orc.swiglu_f16(gate, up), 0.5)
     tn = ti.quantile_threshold(orc.rmsnorm_f16(h, gamma, eps), 0.4)
     ws2 = workspace(T, m, 2 * n)           # kept apart: its survivor counts are read below
+    x1 = np.ascontiguousarray(X[1])
+    x1d = dev(x1)
+    t1 = ti.quantile_threshold(x1, 0.65)
+    ws3 = torch.zeros(T.teal_workspace_bytes_stack([2, 1], [n, n, n], [m, m]), dtype=torch.uint8,
+                      device="cuda")
 
     def enqueue(stream):
         T.check(T.teal_sparse_gemv_bf16(wt, xd, t, outs[0], m, n, ws, stream=stream))
@@ -757,6 +762,8 @@ def test_calls_replay_from_a_hip_graph(T):
         T.check(T.teal_sparse_gemv_bf16_swiglu(wt, gated, upd, th, outs[3], m, n, ws, stream=stream))
         T.check(T.teal_sparse_gemv_bf16_rmsnorm_multi([wt, wt], [tn, 0.0], [outs[4], outs[5]],
                                                       [n, n], hd, gammad, eps, m, ws2, stream=stream))
+        T.check(T.teal_sparse_gemv_bf16_stack([2, 1], [wt, wt, wt], [t, 0.0, t1], outs[6:9], [n, n, n],
+                                              [xd, x1d], [m, m], ws3, stream=stream))
 
     def snapshot():
         torch.cuda.synchronize()
@@ -772,6 +779,8 @@ def test_calls_replay_from_a_hip_graph(T):
     assert rel_l2(eager[0].cpu().numpy(), orc.sparse_gemv_bf16(w, x, t)) <= TIGHT
     assert rel_l2(eager[3].cpu().numpy(), orc.sparse_gemv_bf16_swiglu(w, gate, up, th)) <= TIGHT
     assert rel_l2(eager[4].cpu().numpy(), orc.sparse_gemv_bf16_rmsnorm(w, h, gamma, eps, tn)) <= TIGHT
+    assert torch.equal(eager[6], eager[1]) and torch.equal(eager[7], eager[2])
+    assert rel_l2(eager[8].cpu().numpy(), orc.sparse_gemv_bf16(w, x1, t1)) <= TIGHT
     xn = orc.rmsnorm_f16(h, gamma, eps)
     assert eager[-1].tolist() == [orc.sparsify(xn, tn)[3], orc.sparsify(xn, 0.0)[3]]
 
