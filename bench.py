@@ -393,6 +393,26 @@ def time_projection(T, torch, P, p, launches) -> float:
     return start.elapsed_time(stop) * 1e-3 / launches
 
 
+def time_projection_spread(T, torch, P, p, batches=10, launches=100, singles=20):
+    """The same call timed in `batches` separate batches of back-to-back launches (us per
+    call: median and minimum over the batches) and as single launches, each bracketed by
+    its own pair of events on an idle stream (median; includes the start-up of a kernel on
+    an idle GPU, which back-to-back launches hide)."""
+    per_batch = sorted(time_projection(T, torch, P, p, launches) * 1e6 for _ in range(batches))
+    single = []
+    for k in range(singles):
+        torch.cuda.synchronize()
+        start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        start.record()
+        P.launch(T, k, p)
+        stop.record()
+        torch.cuda.synchronize()
+        single.append(start.elapsed_time(stop) * 1e3)
+    single.sort()
+    return {"us_median_of_batches": per_batch[len(per_batch) // 2], "us_min_of_batches": per_batch[0],
+            "us_single_launch_median": single[len(single) // 2]}
+
+
 def cpu_baseline(block, p: float, budget_s: float = 12.0):
     """The fp64 oracle, as it stands, on the host cores: whole passes over block 0 until
     about `budget_s` seconds of CPU work have been spent."""
@@ -407,6 +427,40 @@ def cpu_baseline(block, p: float, budget_s: float = 12.0):
         passes += 1
         outputs = outputs or ys
     return spent / passes, passes, threads, outputs
+
+
+def cpu_baseline_one_core(block, p: float) -> float:
+    """Seconds for one pass of the oracle over block 0 on a single host core."""
+    from oracle import teal_oracle as orc
+    threads = orc.num_threads()
+    orc.set_num_threads(1)
+    try:
+        t0 = time.perf_counter()
+        for P in block:
+            P.oracle(orc, p)
+        return time.perf_counter() - t0
+    finally:
+        orc.set_num_threads(threads)
+
+
+def deep_layer_check(T, torch, projections, layers, p: float, rows_per_matrix: int = 48):
+    """Blocks past the first draw their weights on the device; for the given blocks, sampled
+    output channels of every projection (the outputs the last pass left on the device)
+    against the oracle run on those channels' weights copied back.  Worst relative L2."""
+    from oracle import teal_oracle as orc
+    worst, checked = 0.0, 0
+    for layer in layers:
+        for P in projections[7 * layer:7 * layer + 7]:
+            g = torch.Generator(device="cpu")
+            g.manual_seed(1000 * layer + P.n % 997)
+            rows = torch.sort(torch.randperm(P.n, generator=g)[:rows_per_matrix]).values
+            wt = P.weights[0][0]                                        # [m][n] bf16 bits
+            w_rows = wt[:, rows.cuda()].t().contiguous().cpu().numpy().view(np.uint16)
+            want = orc.sparse_gemv_bf16_rows(w_rows, P.x_host, P.t[p], np.arange(rows.numel()))
+            got = P.y[rows.cuda()].cpu().numpy().astype(np.float64)
+            worst = max(worst, float(np.linalg.norm(got - want) / np.linalg.norm(want)))
+            checked += rows.numel()
+    return worst, checked
 
 
 def survivor_counts_match(T, torch, stack, p: float):
@@ -932,6 +986,7 @@ def main() -> int:
                 "effective_GBps": b / us / 1e3, "frac_of_hbm_peak": b / us / 1e3 / HBM_PEAK_GBS,
                 "speedup_vs_dense": us_dense / us,
             }
+            table[C.name].update(time_projection_spread(T, torch, C, head))
         return table
 
     graph_detail = {}
@@ -1066,7 +1121,13 @@ def main() -> int:
             "sample": f"{passes} whole passes over block 0 at {pct(head)} (fp64 dense loop over "
                       f"the zeroed x), {sec * 1e3:.1f} ms per pass",
             "ms_per_step": sec * 1e3 * args.layers,
+            "one_core_ms_per_pass": cpu_baseline_one_core(block0, head) * 1e3,
         }
+        if args.layers > 2 and fmt == "bf16" and not args.batch:
+            deep = sorted({args.layers // 2, args.layers - 1})
+            worst, checked = deep_layer_check(T, torch, projections, deep, head)
+            out["parity_in_this_run"]["deep_blocks_sampled_outputs"] = {
+                "blocks": deep, "outputs_checked": checked, "rel_l2_vs_oracle_worst": worst}
     print(json.dumps(out))
     return 0
 
