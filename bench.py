@@ -241,9 +241,19 @@ class StackCall:
 
     def enqueue(self, T, copy: int, p: float) -> int:
         members = [P for G in self.groups for P in G.members]
-        return T.teal_sparse_gemv_bf16_stack(self.counts, [P.wp[copy % len(P.wp)][0] for P in members],
-                                             [P.t[p] for P in members], self.ys, self.ns, self.xs,
-                                             self.ms, self.wsp, self.ws_bytes, self.stream)
+        ws = [P.wp[copy % len(P.wp)] for P in members]
+        ts = [P.t[p] for P in members]
+        fmt = members[0].fmt
+        if fmt == "w8":
+            return T.teal_sparse_gemv_w8_stack(self.counts, [w[0] for w in ws], [w[1] for w in ws], ts,
+                                               self.ys, self.ns, self.xs, self.ms, self.wsp,
+                                               self.ws_bytes, self.stream)
+        if fmt == "w4":
+            return T.teal_sparse_gemv_w4_stack(self.counts, [w[0] for w in ws], [w[1] for w in ws], 128,
+                                               ts, self.ys, self.ns, self.xs, self.ms, self.wsp,
+                                               self.ws_bytes, self.stream)
+        return T.teal_sparse_gemv_bf16_stack(self.counts, [w[0] for w in ws], ts, self.ys, self.ns,
+                                             self.xs, self.ms, self.wsp, self.ws_bytes, self.stream)
 
     def bytes(self, p: float) -> int:
         return sum(G.bytes(p) for G in self.groups)
@@ -269,7 +279,7 @@ class Replica:
         self.y = torch.empty(P.n, dtype=torch.float32, device="cuda")
         self.ys = [self.y.data_ptr()]
         j %= len(P.wp)
-        self.wp, self.t, self.nnz, self.xp = P.wp[j:] + P.wp[:j], P.t, P.nnz, P.xp
+        self.wp, self.t, self.nnz, self.xp, self.fmt = P.wp[j:] + P.wp[:j], P.t, P.nnz, P.xp, P.fmt
         self.members = [self]
         self._bytes = P.bytes
 
@@ -915,11 +925,11 @@ def main() -> int:
     block0 = projections[:7]
     groups = fuse(T, torch, projections)
     stack_calls = None
-    if fmt == "bf16" and not args.batch and (args.stack_launch or not args.no_other_mode):
+    if not args.batch and (args.stack_launch or not args.no_other_mode):
         stack_calls = [StackCall(T, torch, groups[i:i + 16]) for i in range(0, len(groups), 16)]
     if args.stack_launch:
         if stack_calls is None or args.unfused:
-            print("bench.py: --stack-launch needs bf16, batch 1 and grouped launches", file=sys.stderr)
+            print("bench.py: --stack-launch needs batch 1 and grouped launches", file=sys.stderr)
             return 2
         stack = stack_calls
     else:
@@ -1037,7 +1047,8 @@ def main() -> int:
     else:
         kernel = multi_kernel if fused else KERNEL[fmt]
     if args.stack_launch:
-        kernel = "sparse_gemv_stack_kernel<FmtBF16>"
+        kernel = {"bf16": "sparse_gemv_stack_kernel<FmtBF16>", "w8": "sparse_gemv_stack_kernel<FmtW8>",
+                  "w4": "sparse_gemv_w4_stack_kernel"}[fmt]
     out = {
         "metric": f"sparse GEMV effective HBM GB/s at {pct(head)} sparsity (one decoder-block "
                   f"pass); us and speedup vs dense per sparsity in detail",

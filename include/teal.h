@@ -168,6 +168,24 @@ teal_status teal_sparse_gemv_bf16_stack(int groups, const int *counts,
                                         float *const *y, const int *n, const void *const *x_f16,
                                         const int *m, void *workspace, size_t workspace_bytes,
                                         void *stream);
+/*
+ * The same for the quantised formats (Section 5.3): group g is what
+ * teal_sparse_gemv_w8_multi / teal_sparse_gemv_w4_multi computes for it, bit
+ * for bit.  Wq and scale_f16 are HOST arrays over all matrices, group after
+ * group, with the layouts, alignments and width multiples (16 / 32) of those
+ * calls; group == 128 and every m_g % 128 == 0 for int4 (else
+ * TEAL_ERR_UNSUPPORTED).  Workspace as above.
+ */
+teal_status teal_sparse_gemv_w8_stack(int groups, const int *counts, const int8_t *const *Wq,
+                                      const void *const *scale_f16, const float *t,
+                                      float *const *y, const int *n, const void *const *x_f16,
+                                      const int *m, void *workspace, size_t workspace_bytes,
+                                      void *stream);
+teal_status teal_sparse_gemv_w4_stack(int groups, const int *counts, const uint8_t *const *Wq,
+                                      const void *const *scale_f16, int group, const float *t,
+                                      float *const *y, const int *n, const void *const *x_f16,
+                                      const int *m, void *workspace, size_t workspace_bytes,
+                                      void *stream);
 
 /*
  * The grouped call with its shared input formed on the fly from the hidden

@@ -32,7 +32,7 @@ EXPORTS = (
     "teal_swiglu_f16", "teal_sparse_gemv_bf16_swiglu", "teal_sparse_gemv_bf16_batch_multi",
     "teal_gemv_plan_multi", "teal_survivors_offset", "teal_rmsnorm_f16",
     "teal_sparse_gemv_bf16_rmsnorm_multi", "teal_workspace_bytes_stack",
-    "teal_sparse_gemv_bf16_stack",
+    "teal_sparse_gemv_bf16_stack", "teal_sparse_gemv_w8_stack", "teal_sparse_gemv_w4_stack",
 )
 TEAL_HIST_BINS = 32768
 TEAL_MAX_BATCH = 8
@@ -94,6 +94,14 @@ def load_library():
     lib.teal_sparse_gemv_bf16_stack.argtypes = [i, c.POINTER(i), c.POINTER(vp), c.POINTER(f),
                                                 c.POINTER(vp), c.POINTER(i), c.POINTER(vp),
                                                 c.POINTER(i), vp, sz, vp]
+    lib.teal_sparse_gemv_w8_stack.restype = i
+    lib.teal_sparse_gemv_w8_stack.argtypes = [i, c.POINTER(i), c.POINTER(vp), c.POINTER(vp),
+                                              c.POINTER(f), c.POINTER(vp), c.POINTER(i),
+                                              c.POINTER(vp), c.POINTER(i), vp, sz, vp]
+    lib.teal_sparse_gemv_w4_stack.restype = i
+    lib.teal_sparse_gemv_w4_stack.argtypes = [i, c.POINTER(i), c.POINTER(vp), c.POINTER(vp), i,
+                                              c.POINTER(f), c.POINTER(vp), c.POINTER(i),
+                                              c.POINTER(vp), c.POINTER(i), vp, sz, vp]
     lib.teal_sparse_gemv_w8_multi.restype = i
     lib.teal_sparse_gemv_w8_multi.argtypes = [i, c.POINTER(vp), c.POINTER(vp), c.POINTER(f),
                                               c.POINTER(vp), c.POINTER(i), vp, i, vp, sz, vp]
@@ -322,28 +330,64 @@ def teal_workspace_bytes_stack(counts, n_list, m_list) -> int:
     return int(load_library().teal_workspace_bytes_stack(len(counts), C, N, M))
 
 
-def teal_sparse_gemv_bf16_stack(counts, Wt_list, t_list, y_list, n_list, x_list, m_list,
-                                workspace, workspace_bytes=None, stream=None) -> int:
-    """len(counts) independent groups in one launch; matrices listed group after group."""
+def _stack_arrays(counts, W_list, wbytes, t_list, y_list, n_list, x_list, m_list, scale_list=None,
+                  sbytes=None):
+    """Host arrays of a stack call; wbytes(m, n) / sbytes(m, n) = bytes the call reads per matrix."""
     groups = len(counts)
     total = sum(int(c) for c in counts)
-    if not (len(Wt_list) == len(t_list) == len(y_list) == len(n_list) == total):
+    if not (len(W_list) == len(t_list) == len(y_list) == len(n_list) == total):
+        raise ValueError("per-matrix lists must have one entry per matrix of every group")
+    if scale_list is not None and len(scale_list) != total:
         raise ValueError("per-matrix lists must have one entry per matrix of every group")
     if not (len(x_list) == len(m_list) == groups):
         raise ValueError("per-group lists must have one entry per group")
     group_of = [g for g, c in enumerate(counts) for _ in range(int(c))]
-    W = (ctypes.c_void_p * total)(*[_ptr(w, 2 * m_list[g] * n, "Wt")
-                                    for w, n, g in zip(Wt_list, n_list, group_of)])
+    W = (ctypes.c_void_p * total)(*[_ptr(w, wbytes(m_list[g], n), "W")
+                                    for w, n, g in zip(W_list, n_list, group_of)])
+    S = None
+    if scale_list is not None:
+        S = (ctypes.c_void_p * total)(*[_ptr(sc, sbytes(m_list[g], n), "scale")
+                                        for sc, n, g in zip(scale_list, n_list, group_of)])
     Y = (ctypes.c_void_p * total)(*[_ptr(y, 4 * n, "y") for y, n in zip(y_list, n_list)])
     Tt = (ctypes.c_float * total)(*[float(t) for t in t_list])
     N = (ctypes.c_int * total)(*[int(n) for n in n_list])
     C = (ctypes.c_int * groups)(*[int(c) for c in counts])
     X = (ctypes.c_void_p * groups)(*[_ptr(x, 2 * m, "x") for x, m in zip(x_list, m_list)])
     M = (ctypes.c_int * groups)(*[int(m) for m in m_list])
+    return groups, C, W, S, Tt, Y, N, X, M
+
+
+def teal_sparse_gemv_bf16_stack(counts, Wt_list, t_list, y_list, n_list, x_list, m_list,
+                                workspace, workspace_bytes=None, stream=None) -> int:
+    """len(counts) independent groups in one launch; matrices listed group after group."""
+    groups, C, W, _, Tt, Y, N, X, M = _stack_arrays(counts, Wt_list, lambda m, n: 2 * m * n, t_list,
+                                                    y_list, n_list, x_list, m_list)
     return _call(
         "teal_sparse_gemv_bf16_stack",
         groups, C, W, Tt, Y, N, X, M, _ptr(workspace), _nbytes(workspace, workspace_bytes),
         _stream(stream))
+
+
+def teal_sparse_gemv_w8_stack(counts, Wq_list, scale_list, t_list, y_list, n_list, x_list, m_list,
+                              workspace, workspace_bytes=None, stream=None) -> int:
+    groups, C, W, S, Tt, Y, N, X, M = _stack_arrays(
+        counts, Wq_list, lambda m, n: m * n, t_list, y_list, n_list, x_list, m_list, scale_list,
+        lambda m, n: 2 * n)
+    return _call(
+        "teal_sparse_gemv_w8_stack",
+        groups, C, W, S, Tt, Y, N, X, M, _ptr(workspace), _nbytes(workspace, workspace_bytes),
+        _stream(stream))
+
+
+def teal_sparse_gemv_w4_stack(counts, Wq_list, scale_list, group, t_list, y_list, n_list, x_list,
+                              m_list, workspace, workspace_bytes=None, stream=None) -> int:
+    groups, C, W, S, Tt, Y, N, X, M = _stack_arrays(
+        counts, Wq_list, lambda m, n: m * n // 2, t_list, y_list, n_list, x_list, m_list, scale_list,
+        lambda m, n: 2 * n * (m // 128))
+    return _call(
+        "teal_sparse_gemv_w4_stack",
+        groups, C, W, S, int(group), Tt, Y, N, X, M, _ptr(workspace),
+        _nbytes(workspace, workspace_bytes), _stream(stream))
 
 
 def teal_workspace_bytes_batch(m: int, n: int, batch: int) -> int:

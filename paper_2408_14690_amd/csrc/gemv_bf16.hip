@@ -97,64 +97,14 @@ hipError_t launch_gemv_bf16_multi(int count, const void *const *Wt, const float 
 
 hipError_t launch_gemv_bf16_stack(int groups, const StackGroupDesc *d, hipStream_t stream)
 {
-    if (groups < 1 || groups > kMaxStack) return hipErrorInvalidValue;
     StackArgs<FmtBF16> sa{};
-    sa.count = groups;
-    sa.block_begin[0] = 0;
-    size_t lds = 0;
-    // The groups are independent, so their place in the grid is free: those with the most
-    // weight bytes per block go first and the launch ends on short blocks (measured on
-    // Llama-2-7B shapes: 37 us against 40 us in q+k+v, o, gate+up, down order, and 42-46 us
-    // with gate+up last).
-    GemvGeometry geo[kMaxStack];
-    int order[kMaxStack];
-    for (int gi = 0; gi < groups; ++gi) {
-        const StackGroupDesc &dg = d[gi];
-        const GemvShape &sh = dg.shape;
-        if (dg.count < 1 || dg.count > kMaxMulti || sh.waves != 8 || sh.unroll != 4 ||
-            !gemv_shape_supported(sh) || sh.lanes_per_row < 16)
-            return hipErrorInvalidValue;
-        int n_max = 0;
-        for (int k = 0; k < dg.count; ++k) n_max = dg.n[k] > n_max ? dg.n[k] : n_max;
-        geo[gi] = gemv_geometry(dg.m, n_max, sh, FmtBF16::kElemsPerLane, 64);
-        const long long work = (long long)geo[gi].ks * geo[gi].tile_cols;
-        int at = gi;                       // insertion sort, descending, stable
-        while (at > 0 && (long long)geo[order[at - 1]].ks * geo[order[at - 1]].tile_cols < work) {
-            order[at] = order[at - 1];
-            --at;
-        }
-        order[at] = gi;
-    }
-    for (int gi = 0; gi < groups; ++gi) {
-        const StackGroupDesc &dg = d[order[gi]];
-        const GemvShape &sh = dg.shape;
-        const GemvGeometry &g = geo[order[gi]];
-        StackGroup<FmtBF16> &sg = sa.g[gi];
-        sg.ma.count = dg.count;
-        sg.ma.tile_begin[0] = 0;
-        for (int k = 0; k < dg.count; ++k) {
-            sg.ma.a[k].W = dg.Wt[k];
-            sg.ma.y[k] = dg.y[k];
-            sg.ma.t[k] = dg.t[k];
-            sg.ma.n[k] = dg.n[k];
-            sg.ma.tile_begin[k + 1] =
-                sg.ma.tile_begin[k] + (dg.n[k] + g.tile_cols - 1) / g.tile_cols;
-        }
-        sg.x = static_cast<const __half *>(dg.x_f16);
-        sg.partial = dg.partial;
-        sg.counters = dg.counters;
-        sg.m = dg.m;
-        sg.ks = g.ks;
-        sg.tile_cols = g.tile_cols;
-        sg.splits = g.splits;
-        sg.lanes_per_row = sh.lanes_per_row;
-        const long long blocks = (long long)sg.ma.tile_begin[dg.count] * g.splits;
-        if (sa.block_begin[gi] + blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-        sa.block_begin[gi + 1] = sa.block_begin[gi] + (int)blocks;
-        lds = g.lds > lds ? g.lds : lds;
-    }
-    hipLaunchKernelGGL((sparse_gemv_stack_kernel<FmtBF16, 8, 4>), dim3(sa.block_begin[groups]),
-                       dim3(8 * 64), lds, stream, sa);
+    size_t lds;
+    const hipError_t e = fill_stack_args<FmtBF16>(
+        sa, lds, groups, d, 64, 16, 64,
+        [](FmtBF16::Args &a, const StackGroupDesc &g, int k) { a.W = g.Wt[k]; });
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((sparse_gemv_stack_kernel<FmtBF16, 8, 4, false>),
+                       dim3(sa.block_begin[groups]), dim3(8 * 64), lds, stream, sa);
     return hipGetLastError();
 }
 

@@ -243,13 +243,13 @@ __global__ __launch_bounds__(WAVES * 64) void sparse_gemv_w4_kernel(
 // Several int4 matrices that read the same hidden state in one launch; the block finds its
 // matrix from its tile index as in sparse_gemv_multi_kernel.
 template <int LPR, int WAVES, int U>
-__global__ __launch_bounds__(WAVES * 64) void sparse_gemv_w4_multi_kernel(
-    MultiArgs<FmtW4> ma, const __half *__restrict__ x, float *partial, int *counters, int m,
-    int ks, int tile_cols, int splits)
+__device__ __forceinline__ void w4_multi_block(const MultiArgs<FmtW4> &ma, const __half *x,
+                                               float *partial, int *counters, int m, int ks,
+                                               int tile_cols, int splits, int block)
 {
     const int tiles = ma.tile_begin[ma.count];
-    const int gtile = blockIdx.x % tiles;
-    const int s = blockIdx.x / tiles;
+    const int gtile = block % tiles;
+    const int s = block / tiles;
     int k = 0;
     size_t partial_off = 0;
 #pragma unroll
@@ -263,6 +263,59 @@ __global__ __launch_bounds__(WAVES * 64) void sparse_gemv_w4_multi_kernel(
                             counters + ma.tile_begin[k], ma.y[k], m, ma.n[k], ks,
                             gtile - ma.tile_begin[k], s, tile_cols, splits,
                             survivor_report(counters, k, splits));
+}
+
+template <int LPR, int WAVES, int U>
+__global__ __launch_bounds__(WAVES * 64) void sparse_gemv_w4_multi_kernel(
+    MultiArgs<FmtW4> ma, const __half *__restrict__ x, float *partial, int *counters, int m,
+    int ks, int tile_cols, int splits)
+{
+    w4_multi_block<LPR, WAVES, U>(ma, x, partial, counters, m, ks, tile_cols, splits,
+                                  (int)blockIdx.x);
+}
+
+// Independent int4 groups in one launch (see sparse_gemv_stack_kernel).
+template <int WAVES, int U>
+__global__ __launch_bounds__(WAVES * 64) void sparse_gemv_w4_stack_kernel(StackArgs<FmtW4> sa)
+{
+    int block;
+    const StackGroup<FmtW4> &sg = sa.g[stack_group_of_block(sa, block)];
+    if (sg.lanes_per_row == 32)
+        w4_multi_block<32, WAVES, U>(sg.ma, sg.x, sg.partial, sg.counters, sg.m, sg.ks,
+                                     sg.tile_cols, sg.splits, block);
+    else
+        w4_multi_block<16, WAVES, U>(sg.ma, sg.x, sg.partial, sg.counters, sg.m, sg.ks,
+                                     sg.tile_cols, sg.splits, block);
+}
+
+hipError_t launch_gemv_w8_stack(int groups, const StackGroupDesc *d, hipStream_t stream)
+{
+    StackArgs<FmtW8> sa{};
+    size_t lds;
+    const hipError_t e = fill_stack_args<FmtW8>(
+        sa, lds, groups, d, 64, 8, 64, [](FmtW8::Args &a, const StackGroupDesc &g, int k) {
+            a.W = g.Wt[k];
+            a.scale = static_cast<const __half *>(g.scale[k]);
+        });
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((sparse_gemv_stack_kernel<FmtW8, 8, 4, true>), dim3(sa.block_begin[groups]),
+                       dim3(8 * 64), lds, stream, sa);
+    return hipGetLastError();
+}
+
+hipError_t launch_gemv_w4_stack(int groups, const StackGroupDesc *d, hipStream_t stream)
+{
+    StackArgs<FmtW4> sa{};
+    size_t lds;
+    const hipError_t e = fill_stack_args<FmtW4>(
+        sa, lds, groups, d, kGroup, 16, 32, [](FmtW4::Args &a, const StackGroupDesc &g, int k) {
+            a.W = g.Wt[k];
+            a.scale = static_cast<const __half *>(g.scale[k]);
+        });
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((sparse_gemv_w4_stack_kernel<kW4Waves, kW4Unroll>),
+                       dim3(sa.block_begin[groups]), dim3(kW4Waves * 64), lds, stream, sa);
+    return hipGetLastError();
 }
 
 hipError_t launch_gemv_w8(const int8_t *Wq, const void *scale_f16, const void *x_f16, float t,

@@ -190,7 +190,7 @@ const char *teal_status_string(teal_status s)
     return "unknown status";
 }
 
-int teal_version(void) { return 310; }
+int teal_version(void) { return 320; }
 
 size_t teal_survivors_offset(void) { return teal::kCounterBytes; }
 
@@ -376,12 +376,12 @@ teal_status teal_sparse_gemv_bf16_multi(int count, const void *const *Wt_bf16, c
 
 // Region of group g in a stack call's workspace: the groups' regions follow each other,
 // each laid out and sized as the workspace of that group's own grouped call.
-static bool stack_group_dims(int count, const int *n, int m, long long &n_total)
+static bool stack_group_dims(int count, const int *n, int m, int n_multiple, long long &n_total)
 {
     if (count < 1 || count > teal::kMaxMatrices) return false;
     n_total = 0;
     for (int k = 0; k < count; ++k) {
-        if (n[k] < 8 || n[k] > teal::kMaxDim || n[k] % 8 != 0) return false;
+        if (n[k] < n_multiple || n[k] > teal::kMaxDim || n[k] % n_multiple != 0) return false;
         n_total += n[k];
     }
     return m >= 1 && m <= teal::kMaxDim && n_total <= teal::kMaxDim;
@@ -394,20 +394,26 @@ size_t teal_workspace_bytes_stack(int groups, const int *counts, const int *n, c
     for (int g = 0, first = 0; g < groups; first += counts[g], ++g) {
         long long n_total;
         if (counts[g] < 1 || counts[g] > teal::kMaxMatrices) return 0;
-        if (!stack_group_dims(counts[g], n + first, m[g], n_total)) return 0;
+        if (!stack_group_dims(counts[g], n + first, m[g], 8, n_total)) return 0;
         bytes += teal_workspace_bytes(m[g], (int)n_total);
     }
     return bytes;
 }
 
-teal_status teal_sparse_gemv_bf16_stack(int groups, const int *counts,
-                                        const void *const *Wt_bf16, const float *t,
-                                        float *const *y, const int *n, const void *const *x_f16,
-                                        const int *m, void *workspace, size_t workspace_bytes,
-                                        void *stream)
+// The three stack entry points: the checks of the format's grouped call for every group,
+// the groups' workspace regions, the launch shape of each group's own grouped call (same
+// sums, bit for bit).  weight_bits 16: scale_f16 unused.
+static teal_status stack_call(int weight_bits, int groups, const int *counts,
+                              const void *const *W, const void *const *scale_f16, int group,
+                              const float *t, float *const *y, const int *n,
+                              const void *const *x_f16, const int *m, void *workspace,
+                              size_t workspace_bytes, void *stream)
 {
+    const bool quantised = weight_bits != 16;
+    const int n_multiple = weight_bits == 16 ? 8 : weight_bits == 8 ? 16 : 32;
     if (groups < 1 || groups > teal::kMaxStackGroups) return TEAL_ERR_UNSUPPORTED;
-    if (!counts || !Wt_bf16 || !t || !y || !n || !x_f16 || !m || !workspace) return TEAL_ERR_NULL;
+    if (!counts || !W || (quantised && !scale_f16) || !t || !y || !n || !x_f16 || !m || !workspace)
+        return TEAL_ERR_NULL;
     for (int g = 0; g < groups; ++g)
         if (counts[g] < 1 || counts[g] > teal::kMaxMatrices) return TEAL_ERR_UNSUPPORTED;
     if (!aligned(workspace, kAlignWorkspace)) return TEAL_ERR_ALIGN;
@@ -417,26 +423,70 @@ teal_status teal_sparse_gemv_bf16_stack(int groups, const int *counts,
         const int count = counts[g];
         if (!x_f16[g]) return TEAL_ERR_NULL;
         for (int k = 0; k < count; ++k)
-            if (!Wt_bf16[first + k] || !y[first + k]) return TEAL_ERR_NULL;
+            if (!W[first + k] || !y[first + k] || (quantised && !scale_f16[first + k]))
+                return TEAL_ERR_NULL;
         long long n_total;
-        if (!stack_group_dims(count, n + first, m[g], n_total)) return TEAL_ERR_SHAPE;
-        for (int k = 0; k < count; ++k)
-            if (!aligned(Wt_bf16[first + k], 16) || !aligned(y[first + k], 4))
+        if (!stack_group_dims(count, n + first, m[g], n_multiple, n_total)) return TEAL_ERR_SHAPE;
+        for (int k = 0; k < count; ++k) {
+            if (!aligned(W[first + k], 16) || !aligned(y[first + k], 4)) return TEAL_ERR_ALIGN;
+            if (quantised && !aligned(scale_f16[first + k], weight_bits == 4 ? 16 : 2))
                 return TEAL_ERR_ALIGN;
+        }
         if (!aligned(x_f16[g], 2)) return TEAL_ERR_ALIGN;
         for (int k = 0; k < count; ++k)
             if (!threshold_ok(t[first + k])) return TEAL_ERR_THRESHOLD;
+        if (weight_bits == 4 && (group != 128 || m[g] % 128 != 0)) return TEAL_ERR_UNSUPPORTED;
         unsigned char *region = static_cast<unsigned char *>(workspace) + offset;
         offset += teal_workspace_bytes(m[g], (int)n_total);
         if (offset > workspace_bytes) return TEAL_ERR_WORKSPACE;
-        // The launch shape of teal_sparse_gemv_bf16_multi for this group: same sums, bit for bit.
-        const GemvShape sh = count > 1 ? auto_shape_multi(m[g], n + first, count, 8, 16, 64, 64)
-                                       : auto_shape(m[g], (int)n_total, 8, 16, 64, 64);
-        d[g] = teal::StackGroupDesc{count, Wt_bf16 + first, t + first, y + first, n + first,
-                                    x_f16[g], m[g], ws_partials(region, m[g]),
-                                    ws_counters(region), sh};
+        GemvShape sh;
+        if (weight_bits == 16)
+            sh = count > 1 ? auto_shape_multi(m[g], n + first, count, 8, 16, 64, 64)
+                           : auto_shape(m[g], (int)n_total, 8, 16, 64, 64);
+        else if (weight_bits == 8)
+            sh = count > 1 ? auto_shape_multi(m[g], n + first, count, 16, 8, 64, 64)
+                           : auto_shape(m[g], (int)n_total, 16, 8, 64, 64);
+        else
+            sh = count > 1 ? auto_shape_multi(m[g], n + first, count, 32, 16, 32, 128)
+                           : auto_shape(m[g], (int)n_total, 32, 16, 32, 128);
+        d[g] = teal::StackGroupDesc{count, W + first, quantised ? scale_f16 + first : nullptr,
+                                    t + first, y + first, n + first, x_f16[g], m[g],
+                                    ws_partials(region, m[g]), ws_counters(region), sh};
     }
-    return from_hip(teal::launch_gemv_bf16_stack(groups, d, static_cast<hipStream_t>(stream)));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (weight_bits == 16) return from_hip(teal::launch_gemv_bf16_stack(groups, d, st));
+    if (weight_bits == 8) return from_hip(teal::launch_gemv_w8_stack(groups, d, st));
+    return from_hip(teal::launch_gemv_w4_stack(groups, d, st));
+}
+
+teal_status teal_sparse_gemv_bf16_stack(int groups, const int *counts,
+                                        const void *const *Wt_bf16, const float *t,
+                                        float *const *y, const int *n, const void *const *x_f16,
+                                        const int *m, void *workspace, size_t workspace_bytes,
+                                        void *stream)
+{
+    return stack_call(16, groups, counts, Wt_bf16, nullptr, 0, t, y, n, x_f16, m, workspace,
+                      workspace_bytes, stream);
+}
+
+teal_status teal_sparse_gemv_w8_stack(int groups, const int *counts, const int8_t *const *Wq,
+                                      const void *const *scale_f16, const float *t,
+                                      float *const *y, const int *n, const void *const *x_f16,
+                                      const int *m, void *workspace, size_t workspace_bytes,
+                                      void *stream)
+{
+    return stack_call(8, groups, counts, reinterpret_cast<const void *const *>(Wq), scale_f16, 0,
+                      t, y, n, x_f16, m, workspace, workspace_bytes, stream);
+}
+
+teal_status teal_sparse_gemv_w4_stack(int groups, const int *counts, const uint8_t *const *Wq,
+                                      const void *const *scale_f16, int group, const float *t,
+                                      float *const *y, const int *n, const void *const *x_f16,
+                                      const int *m, void *workspace, size_t workspace_bytes,
+                                      void *stream)
+{
+    return stack_call(4, groups, counts, reinterpret_cast<const void *const *>(Wq), scale_f16,
+                      group, t, y, n, x_f16, m, workspace, workspace_bytes, stream);
 }
 
 teal_status teal_rmsnorm_f16(const float *h, const float *gamma, float eps, void *x_f16, int m,

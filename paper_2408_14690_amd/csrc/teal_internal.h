@@ -62,12 +62,13 @@ hipError_t launch_gemv_bf16_multi(int count, const void *const *Wt, const float 
                                   float *partial, int *counters, const GemvShape &shape,
                                   hipStream_t stream);
 
-// Up to kMaxStackGroups grouped bf16 calls that do not depend on each other, in one launch.
-// Shapes with 8 wavefronts, 4 loads per batch and 16, 32 or 64 lanes per row.
+// Up to kMaxStackGroups grouped calls of one weight format that do not depend on each other,
+// in one launch.  Shapes with 8 wavefronts, 4 loads per batch and the format's lanes per row.
 constexpr int kMaxStackGroups = 16;
 struct StackGroupDesc {
     int count;                 // matrices of the group, 1..kMaxMatrices
     const void *const *Wt;
+    const void *const *scale;  // quantised formats; NULL for bf16
     const float *t;
     float *const *y;
     const int *n;
@@ -78,6 +79,8 @@ struct StackGroupDesc {
     GemvShape shape;
 };
 hipError_t launch_gemv_bf16_stack(int groups, const StackGroupDesc *g, hipStream_t stream);
+hipError_t launch_gemv_w8_stack(int groups, const StackGroupDesc *g, hipStream_t stream);
+hipError_t launch_gemv_w4_stack(int groups, const StackGroupDesc *g, hipStream_t stream);
 
 // Small batch (Section 5.4.4).  The slice of a block, ceil(m / splits) rounded up to 64,
 // must not exceed kMaxSliceBatch.

@@ -181,6 +181,40 @@ def test_stack_argument_errors_and_workspace():
         T.teal_sparse_gemv_bf16_stack([2], [W], [0.5], [Y], [64], [X], [64], WS, BIG, 0)
 
 
+def test_quantised_stack_argument_errors():
+    ok = dict(counts=[2, 1], Wq_list=[W, W + 0x1000, W + 0x2000], scale_list=[SC, SC + 0x100, SC + 0x200],
+              t_list=[0.5, 0.25, 0.4], y_list=[Y, Y + 0x1000, Y + 0x2000], n_list=[4096, 1024, 11008],
+              x_list=[X, X + 0x100], m_list=[4096, 2048], workspace=WS, workspace_bytes=BIG, stream=0)
+
+    def w8(**kw):
+        a = dict(ok)
+        a.update(kw)
+        return T.teal_sparse_gemv_w8_stack(**a)
+
+    def w4(**kw):
+        a = dict(ok, group=128)
+        a.update(kw)
+        return T.teal_sparse_gemv_w4_stack(**a)
+
+    for call in (w8, w4):
+        assert call(Wq_list=[W, W, None]) == T.TEAL_ERR_NULL
+        assert call(scale_list=[SC, None, SC]) == T.TEAL_ERR_NULL
+        assert call(x_list=[None, X]) == T.TEAL_ERR_NULL
+        assert call(m_list=[4096, 0]) == T.TEAL_ERR_SHAPE
+        assert call(Wq_list=[W, W + 8, W]) == T.TEAL_ERR_ALIGN
+        assert call(t_list=[0.5, -0.25, 0.4]) == T.TEAL_ERR_THRESHOLD
+        assert call(workspace_bytes=4096) == T.TEAL_ERR_WORKSPACE
+        assert call(counts=[2, 1] + [1] * 15, Wq_list=[W] * 18, scale_list=[SC] * 18, t_list=[0.5] * 18,
+                    y_list=[Y] * 18, n_list=[64] * 18, x_list=[X] * 17, m_list=[128] * 17) \
+            == T.TEAL_ERR_UNSUPPORTED
+    assert w8(n_list=[4096, 1032, 11008]) == T.TEAL_ERR_SHAPE      # not a multiple of 16
+    assert w4(n_list=[4096, 1040, 11008]) == T.TEAL_ERR_SHAPE      # not a multiple of 32
+    assert w8(scale_list=[SC, SC + 1, SC]) == T.TEAL_ERR_ALIGN
+    assert w4(scale_list=[SC, SC + 8, SC]) == T.TEAL_ERR_ALIGN
+    assert w4(group=64) == T.TEAL_ERR_UNSUPPORTED
+    assert w4(m_list=[4096, 2112]) == T.TEAL_ERR_UNSUPPORTED       # not a multiple of 128
+
+
 def test_w8_multi_argument_errors():
     ok = dict(Wq_list=[W, W + 0x1000], scale_list=[SC, SC + 0x100], t_list=[0.5, 0.25],
               y_list=[Y, Y + 0x1000], n_list=[4096, 1024], x_f16=X, m=4096, workspace=WS,

@@ -190,3 +190,86 @@ def test_argument_errors_leave_outputs_alone(T):
         == T.TEAL_ERR_THRESHOLD
     torch.cuda.synchronize()
     assert all(bool((y == 3.0).all()) for y in ys)
+
+
+@pytest.mark.parametrize("fmt", ["w8", "w4"])
+def test_quantised_stacks(T, fmt):
+    """int8 / int4 groups in one launch: bitwise the groups' own grouped calls, within
+    tolerance of the oracle on the same (q, scale), exact survivor counts; two calls in a
+    row on one workspace."""
+    ms = [1024, 4096, 640, 2048]
+    ns = [[544, 96], [1024], [4096, 1024, 1024, 96], [32, 2080]]
+    ps = [[0.5, 0.25], [0.4], [0.5, 0.4, 0.25, 0.9], [0.65, 0.0]]
+    counts = [len(g) for g in ns]
+    flat_n = [n for g in ns for n in g]
+    group_of = [g for g, c in enumerate(counts) for _ in range(c)]
+    xs = [ti.make_x(m, 4600 + g, ("gaussian", "laplace")[g % 2]) for g, m in enumerate(ms)]
+    qs, scs, ts = [], [], []
+    for k, (g, n) in enumerate(zip(group_of, flat_n)):
+        w = ti.weights_bf16(n, ms[g], seed=4700 + k)
+        qs.append(ti.quantize_w8(w) if fmt == "w8" else ti.quantize_w4(w, 128))
+        ts.append(ti.quantile_threshold(xs[g], ps[g][k - sum(counts[:g])]))
+    qd = [dev(q) for q, _ in qs]
+    sd = [dev(sc) for _, sc in qs]
+    xd = [dev(x) for x in xs]
+    ws = torch.zeros(T.teal_workspace_bytes_stack(counts, flat_n, ms), dtype=torch.uint8, device="cuda")
+    region = np.cumsum([0] + [T.teal_workspace_bytes(m, sum(g)) for m, g in zip(ms, ns)])
+
+    def stack(t):
+        ys = [torch.full((n,), float("nan"), dtype=torch.float32, device="cuda") for n in flat_n]
+        if fmt == "w8":
+            T.check(T.teal_sparse_gemv_w8_stack(counts, qd, sd, t, ys, flat_n, xd, ms, ws))
+        else:
+            T.check(T.teal_sparse_gemv_w4_stack(counts, qd, sd, 128, t, ys, flat_n, xd, ms, ws))
+        torch.cuda.synchronize()
+        host = ws.cpu().numpy()
+        off = T.teal_survivors_offset()
+        got = []
+        for g, c in enumerate(counts):
+            at = int(region[g]) + off
+            got += host[at:at + 4 * c].view(np.int32).tolist()
+        return [y.cpu().numpy() for y in ys], got
+
+    def separately(t):
+        out, first = [], 0
+        for g, c in enumerate(counts):
+            sl = slice(first, first + c)
+            w1 = torch.zeros(T.teal_workspace_bytes(ms[g], sum(flat_n[sl])), dtype=torch.uint8, device="cuda")
+            ys = [torch.full((n,), float("nan"), dtype=torch.float32, device="cuda") for n in flat_n[sl]]
+            if fmt == "w8":
+                T.check(T.teal_sparse_gemv_w8_multi(qd[sl], sd[sl], t[sl], ys, flat_n[sl], xd[g], ms[g], w1))
+            else:
+                T.check(T.teal_sparse_gemv_w4_multi(qd[sl], sd[sl], 128, t[sl], ys, flat_n[sl], xd[g],
+                                                    ms[g], w1))
+            torch.cuda.synchronize()
+            out += [y.cpu().numpy() for y in ys]
+            first += c
+        return out
+
+    for t in (ts, [ti.quantile_threshold(xs[g], 0.8) for g in group_of]):
+        ys, counts_got = stack(t)
+        assert counts_got == [orc.sparsify(xs[g], tk)[3] for g, tk in zip(group_of, t)]
+        for k, (a, b) in enumerate(zip(ys, separately(t))):
+            assert np.array_equal(a.view(np.uint32), b.view(np.uint32)), k
+        for k, (g, y) in enumerate(zip(group_of, ys)):
+            q, sc = qs[k]
+            want = (orc.sparse_gemv_w8(q, sc, xs[g], t[k]) if fmt == "w8"
+                    else orc.sparse_gemv_w4(q, sc, 128, xs[g], t[k]))
+            assert rel_l2(y, want) <= TIGHT, (k, g)
+
+
+def test_quantised_stack_argument_errors(T):
+    m, n = 512, 128
+    x = dev(ti.gaussian_x(m, 4800))
+    q8, s8 = ti.quantize_w8(ti.weights_bf16(n, m, seed=4801))
+    q4, s4 = ti.quantize_w4(ti.weights_bf16(n, m, seed=4802), 128)
+    y = torch.full((n,), 3.0, dtype=torch.float32, device="cuda")
+    ws = torch.zeros(T.teal_workspace_bytes_stack([1], [n], [m]), dtype=torch.uint8, device="cuda")
+    assert T.teal_sparse_gemv_w4_stack([1], [dev(q4)], [dev(s4)], 64, [0.1], [y], [n], [x], [m], ws) \
+        == T.TEAL_ERR_UNSUPPORTED
+    assert T.teal_sparse_gemv_w8_stack([1], [dev(q8)], [dev(s8)], [float("inf")], [y], [n], [x], [m], ws) \
+        == T.TEAL_ERR_THRESHOLD
+    assert T.teal_sparse_gemv_w8_stack([1], [dev(q8)], [dev(s8)], [0.1], [y], [n], [x], [m], ws[:4096]) \
+        == T.TEAL_ERR_WORKSPACE
+    torch.cuda.synchronize()
+    assert bool((y == 3.0).all())
