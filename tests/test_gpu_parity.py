@@ -843,3 +843,60 @@ def test_random_shapes_every_format(T, chunk):
             q4, s4 = ti.quantize_w4(w, 128)
             got = run_w4(T, dev(q4), dev(s4), xd, t, m, n, ws)
             assert rel_l2(got, orc.sparse_gemv_w4(q4, s4, 128, x, t)) <= 1e-4, ("w4",) + tag
+
+
+def test_concurrent_streams_and_host_threads(T):
+    """The library keeps no state between calls: calls on different streams with different
+    workspaces, issued from different host threads at the same time, give the bits of the same
+    calls issued one after the other."""
+    import threading
+    m, ns = 4096, [1032, 4096, 520]
+    x = ti.laplace_x(m, 907)
+    xd = dev(x)
+    t = ti.quantile_threshold(x, 0.5)
+    wts = [dev(ti.to_input_channel_major(ti.weights_bf16(n, m, seed=910 + k))) for k, n in enumerate(ns)]
+    q, scale = ti.quantize_w8(ti.weights_bf16(1040, m, 915))
+    qd, sd = dev(q), dev(scale)
+
+    def sequence(stream, ws, ws8, outs, y8, rounds):
+        for _ in range(rounds):
+            for wt, n, y in zip(wts, ns, outs):
+                T.check(T.teal_sparse_gemv_bf16(wt, xd, t, y, m, n, ws, stream=stream))
+            T.check(T.teal_sparse_gemv_bf16_multi(wts[:2], [t, 0.0], outs[3:5], ns[:2], xd, m, ws, stream=stream))
+            T.check(T.teal_sparse_gemv_w8(qd, sd, xd, t, y8, m, 1040, ws8, stream=stream))
+
+    def buffers():
+        outs = [torch.full((n,), float("nan"), dtype=torch.float32, device="cuda") for n in ns + ns[:2]]
+        return (workspace(T, m, sum(ns)), workspace(T, m, 1040), outs,
+                torch.full((1040,), float("nan"), dtype=torch.float32, device="cuda"))
+
+    ws, ws8, outs, y8 = buffers()
+    sequence(torch.cuda.current_stream().cuda_stream, ws, ws8, outs, y8, 1)
+    torch.cuda.synchronize()
+    want = [o.clone() for o in outs] + [y8.clone()]
+    assert rel_l2(want[1].cpu().numpy(), orc.sparse_gemv_bf16(
+        ti.weights_bf16(ns[1], m, seed=911), x, t)) <= TIGHT
+
+    lanes = []
+    for _ in range(3):
+        s = torch.cuda.Stream()
+        s.wait_stream(torch.cuda.current_stream())
+        lanes.append((s, buffers()))
+    errors = []
+
+    def work(s, bufs):
+        try:
+            sequence(s.cuda_stream, *bufs, 25)
+        except Exception as e:                     # noqa: BLE001 - reported below
+            errors.append(e)
+
+    threads = [threading.Thread(target=work, args=lane) for lane in lanes]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    torch.cuda.synchronize()
+    assert not errors, errors
+    for _, (_, _, got, got8) in lanes:
+        for a, b in zip(want, got + [got8]):
+            assert torch.equal(a, b)
