@@ -423,6 +423,43 @@ def time_projection_spread(T, torch, P, p, batches=10, launches=100, singles=20)
             "us_single_launch_median": single[len(single) // 2]}
 
 
+def read_ceiling(T, torch, sizes, launches=200):
+    """What a kernel that only reads reaches on this machine (teal_stream_read_probe: the row
+    stream's 16-byte non-temporal loads, no other work) for launches of the given sizes,
+    back to back, each launch on a different part of a 3 GiB buffer so that nothing comes
+    from a cache; the best over a few grid sizes."""
+    total = CACHE_DEFEAT_BYTES
+    buf = torch.empty(total // 4, dtype=torch.int32, device="cuda").random_()
+    sink = torch.zeros(8192, dtype=torch.int32, device="cuda")
+    base, stream = buf.data_ptr(), torch.cuda.current_stream().cuda_stream
+    out = []
+    for size in sizes:
+        size = min(int(size), total // 2) // 256 * 256
+        slots = (total - size) // 256
+        step = max(1, (size + 255) // 256)
+        best = None
+        for blocks in (256, 512, 1024, 2048, 4096, 8192):
+            calls = [T.prepare(lambda k=k: T.teal_stream_read_probe(
+                base + 256 * ((k * step) % slots), size, blocks, 0xFFFFFFFF, sink, stream))
+                for k in range(max(2, total // size))]
+            for k in range(20):
+                T.check(calls[k % len(calls)]())
+            torch.cuda.synchronize()
+            start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            start.record()
+            for k in range(launches):
+                calls[k % len(calls)]()
+            stop.record()
+            torch.cuda.synchronize()
+            us = start.elapsed_time(stop) * 1e3 / launches
+            if best is None or us < best["us_per_launch"]:
+                best = {"bytes_per_launch": size, "us_per_launch": us, "GBps": size / us / 1e3,
+                        "frac_of_hbm_peak": size / us / 1e3 / HBM_PEAK_GBS, "blocks": blocks}
+        out.append(best)
+    del buf
+    return out
+
+
 def cpu_baseline(block, p: float, budget_s: float = 12.0):
     """The fp64 oracle, as it stands, on the host cores: whole passes over block 0 until
     about `budget_s` seconds of CPU work have been spent."""
@@ -1100,6 +1137,14 @@ def main() -> int:
         f"per_group_alone_{pct(head)}": per_group,
         f"per_projection_in_a_launch_of_16_independent_{pct(head)}": per_proj_stack,
     }
+    if not args.no_other_mode:
+        # the practical ceiling beside the published peak: a plain read of one launch's bytes
+        # (back to back, like the timed launches) and of 1 GiB
+        per_launch = int(head_bytes / launches_per_step)
+        ceil = read_ceiling(T, torch, [per_launch, 1 << 30])
+        out["roofline"]["plain_read_of_the_same_bytes"] = ceil[0]
+        out["roofline"]["plain_read_of_1GiB"] = ceil[1]
+        out["roofline"]["achieved_over_plain_read_of_the_same_bytes"] = achieved / ceil[0]["GBps"]
     # the same reading while the headline pass keeps the GPU busy (about a second of steps)
     import threading
     busy = {}

@@ -33,6 +33,7 @@ EXPORTS = (
     "teal_gemv_plan_multi", "teal_survivors_offset", "teal_rmsnorm_f16",
     "teal_sparse_gemv_bf16_rmsnorm_multi", "teal_workspace_bytes_stack",
     "teal_sparse_gemv_bf16_stack", "teal_sparse_gemv_w8_stack", "teal_sparse_gemv_w4_stack",
+    "teal_stream_read_probe",
 )
 TEAL_HIST_BINS = 32768
 TEAL_MAX_BATCH = 8
@@ -94,6 +95,8 @@ def load_library():
     lib.teal_sparse_gemv_bf16_stack.argtypes = [i, c.POINTER(i), c.POINTER(vp), c.POINTER(f),
                                                 c.POINTER(vp), c.POINTER(i), c.POINTER(vp),
                                                 c.POINTER(i), vp, sz, vp]
+    lib.teal_stream_read_probe.restype = i
+    lib.teal_stream_read_probe.argtypes = [vp, sz, i, c.c_uint32, vp, vp]
     lib.teal_sparse_gemv_w8_stack.restype = i
     lib.teal_sparse_gemv_w8_stack.argtypes = [i, c.POINTER(i), c.POINTER(vp), c.POINTER(vp),
                                               c.POINTER(f), c.POINTER(vp), c.POINTER(i),
@@ -388,6 +391,12 @@ def teal_sparse_gemv_w4_stack(counts, Wq_list, scale_list, group, t_list, y_list
         "teal_sparse_gemv_w4_stack",
         groups, C, W, S, int(group), Tt, Y, N, X, M, _ptr(workspace),
         _nbytes(workspace, workspace_bytes), _stream(stream))
+
+
+def teal_stream_read_probe(buf, nbytes, blocks, match, sink, stream=None) -> int:
+    """Plain streaming read of nbytes at buf by `blocks` thread blocks (measurement aid)."""
+    return _call("teal_stream_read_probe", _ptr(buf, nbytes, "buf"), int(nbytes), int(blocks),
+                 int(match) & 0xFFFFFFFF, _ptr(sink, 4 * blocks, "sink"), _stream(stream))
 
 
 def teal_workspace_bytes_batch(m: int, n: int, batch: int) -> int:

@@ -264,4 +264,38 @@ hipError_t launch_pack_bf16(const void *W_rowmajor, void *Wt, int m, int n, hipS
     return hipGetLastError();
 }
 
+// Measurement aid: a plain streaming read of `vecs` 16-byte vectors with the loads the
+// row stream uses (non-temporal, 8 in flight per thread), no arithmetic beyond an XOR fold
+// that keeps the loads alive.  What this reaches is the rate a kernel that only reads can
+// reach on the part, for the size of one launch: the practical ceiling under the 8 TB/s
+// peak.  A thread writes one word, and only if its fold equals a value the caller chose.
+typedef uint32_t probe_u32x4 __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(512) void stream_read_kernel(const probe_u32x4 *__restrict__ p,
+                                                          size_t vecs, uint32_t match,
+                                                          uint32_t *sink)
+{
+    constexpr int L = 8;
+    const size_t threads = (size_t)gridDim.x * blockDim.x;
+    size_t v = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    probe_u32x4 acc = {0u, 0u, 0u, 0u};
+    for (; v + (L - 1) * threads < vecs; v += L * threads) {
+        probe_u32x4 d[L];
+#pragma unroll
+        for (int u = 0; u < L; ++u) d[u] = __builtin_nontemporal_load(p + v + u * threads);
+#pragma unroll
+        for (int u = 0; u < L; ++u) acc ^= d[u];
+    }
+    for (; v < vecs; v += threads) acc ^= __builtin_nontemporal_load(p + v);
+    if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == match) sink[blockIdx.x] = match;
+}
+
+hipError_t launch_stream_read(const void *buf, size_t bytes, int blocks, uint32_t match,
+                              uint32_t *sink, hipStream_t stream)
+{
+    hipLaunchKernelGGL(stream_read_kernel, dim3((unsigned)blocks), dim3(512), 0, stream,
+                       static_cast<const probe_u32x4 *>(buf), bytes / 16, match, sink);
+    return hipGetLastError();
+}
+
 }  // namespace teal

@@ -190,7 +190,7 @@ const char *teal_status_string(teal_status s)
     return "unknown status";
 }
 
-int teal_version(void) { return 320; }
+int teal_version(void) { return 330; }
 
 size_t teal_survivors_offset(void) { return teal::kCounterBytes; }
 
@@ -681,6 +681,16 @@ teal_status teal_sparse_gemv_w4_multi(int count, const uint8_t *const *Wq,
     return from_hip(teal::launch_gemv_w4_multi(count, Wq, scale_f16, t, y, n, x_f16, m,
                                                ws_partials(workspace, m), ws_counters(workspace), sh,
                                                static_cast<hipStream_t>(stream)));
+}
+
+teal_status teal_stream_read_probe(const void *buf, size_t bytes, int blocks, uint32_t match,
+                                   uint32_t *sink, void *stream)
+{
+    if (!buf || !sink) return TEAL_ERR_NULL;
+    if (bytes < 16 || bytes % 16 != 0 || blocks < 1 || blocks > 65536) return TEAL_ERR_SHAPE;
+    if (!aligned(buf, 16) || !aligned(sink, 4)) return TEAL_ERR_ALIGN;
+    return from_hip(teal::launch_stream_read(buf, bytes, blocks, match, sink,
+                                             static_cast<hipStream_t>(stream)));
 }
 
 teal_status teal_abs_histogram(const void *x_f16, size_t count, uint64_t *hist, void *stream)

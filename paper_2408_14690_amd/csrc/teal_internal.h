@@ -122,6 +122,9 @@ hipError_t launch_abs_histogram(const void *x_f16, size_t count, unsigned long l
 hipError_t launch_histogram_thresholds(const unsigned long long *hist, const double *p, int np,
                                        float *t_out, hipStream_t stream);
 
+hipError_t launch_stream_read(const void *buf, size_t bytes, int blocks, uint32_t match,
+                              uint32_t *sink, hipStream_t stream);
+
 hipError_t launch_pack_bf16(const void *W_rowmajor, void *Wt, int m, int n,
                             hipStream_t stream);
 

@@ -181,6 +181,17 @@ def test_stack_argument_errors_and_workspace():
         T.teal_sparse_gemv_bf16_stack([2], [W], [0.5], [Y], [64], [X], [64], WS, BIG, 0)
 
 
+def test_stream_read_probe_argument_errors():
+    assert T.teal_stream_read_probe(None, 4096, 256, 0, Y, 0) == T.TEAL_ERR_NULL
+    assert T.teal_stream_read_probe(W, 4096, 256, 0, None, 0) == T.TEAL_ERR_NULL
+    assert T.teal_stream_read_probe(W, 0, 256, 0, Y, 0) == T.TEAL_ERR_SHAPE
+    assert T.teal_stream_read_probe(W, 4100, 256, 0, Y, 0) == T.TEAL_ERR_SHAPE
+    assert T.teal_stream_read_probe(W, 4096, 0, 0, Y, 0) == T.TEAL_ERR_SHAPE
+    assert T.teal_stream_read_probe(W, 4096, 65537, 0, Y, 0) == T.TEAL_ERR_SHAPE
+    assert T.teal_stream_read_probe(W + 8, 4096, 256, 0, Y, 0) == T.TEAL_ERR_ALIGN
+    assert T.teal_stream_read_probe(W, 4096, 256, 0, Y + 2, 0) == T.TEAL_ERR_ALIGN
+
+
 def test_quantised_stack_argument_errors():
     ok = dict(counts=[2, 1], Wq_list=[W, W + 0x1000, W + 0x2000], scale_list=[SC, SC + 0x100, SC + 0x200],
               t_list=[0.5, 0.25, 0.4], y_list=[Y, Y + 0x1000, Y + 0x2000], n_list=[4096, 1024, 11008],

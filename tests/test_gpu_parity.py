@@ -900,3 +900,27 @@ def test_concurrent_streams_and_host_threads(T):
     for _, (_, _, got, got8) in lanes:
         for a, b in zip(want, got + [got8]):
             assert torch.equal(a, b)
+
+
+def test_stream_read_probe_reads_every_vector(T):
+    """The measurement aid reads all of its range: a single non-zero word anywhere in it is
+    found by exactly the block whose thread reads that vector."""
+    blocks = 24
+    threads = blocks * 512
+    for vecs in (1, 511, threads * 8 + 37, threads * 19 + 5):
+        buf = torch.zeros(vecs * 4, dtype=torch.int32, device="cuda")
+        for v in sorted({0, vecs // 2, vecs - 1}):
+            buf.zero_()
+            buf[4 * v + 3] = 5
+            sink = torch.full((blocks,), 7, dtype=torch.int32, device="cuda")
+            T.check(T.teal_stream_read_probe(buf, 16 * vecs, blocks, 5, sink))
+            torch.cuda.synchronize()
+            want = [7] * blocks
+            want[(v % threads) // 512] = 5
+            assert sink.cpu().tolist() == want, (vecs, v)
+        sink = torch.full((blocks,), 7, dtype=torch.int32, device="cuda")
+        T.check(T.teal_stream_read_probe(buf, 16 * vecs, blocks, 9, sink))
+        torch.cuda.synchronize()
+        assert sink.cpu().tolist() == [7] * blocks
+    assert T.teal_stream_read_probe(buf, 24, blocks, 0, sink) == T.TEAL_ERR_SHAPE
+    assert T.teal_stream_read_probe(buf, 16, 0, 0, sink) == T.TEAL_ERR_SHAPE
