@@ -273,3 +273,24 @@ def test_quantised_stack_argument_errors(T):
         == T.TEAL_ERR_WORKSPACE
     torch.cuda.synchronize()
     assert bool((y == 3.0).all())
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_random_stacks(T, seed):
+    """Random numbers of groups and matrices, input lengths (ragged), widths and sparsity
+    levels (including nothing dropped and everything dropped)."""
+    rng = np.random.Generator(np.random.PCG64(5000 + seed))
+    groups = int(rng.integers(1, 17))
+    ms, ns, ps = [], [], []
+    for _ in range(groups):
+        m = int(rng.integers(1, 24)) * 128 + (int(rng.integers(1, 128)) if rng.random() < 0.5 else 0)
+        count = int(rng.integers(1, 5))
+        ms.append(m)
+        ns.append([int(rng.integers(1, 160)) * 8 for _ in range(count)])
+        ps.append([float(rng.choice([0.0, 0.1, 0.5, 0.77, 0.95, 1.0])) for _ in range(count)])
+    s = Stack(T, ms, ns, ps, seed=5100 + 1000 * seed)
+    ys = s.run()
+    s.check_against_oracle(ys)
+    assert s.survivors() == s.oracle_counts()
+    for k, (a, b) in enumerate(zip(ys, s.run_separately())):
+        assert np.array_equal(a.view(np.uint32), b.view(np.uint32)), k
