@@ -403,6 +403,33 @@ def time_projection(T, torch, P, p, launches) -> float:
     return start.elapsed_time(stop) * 1e-3 / launches
 
 
+def time_torch_matmul(torch, P, canonical: bool, launches=300) -> float:
+    """Context only: the dense product through torch.matmul (the vendor BLAS) in bf16, walking
+    as many weight copies as the timed calls do; seconds per call.  canonical: W[n][m] times
+    x (the layout a model keeps its weights in); else x times the input-channel-major
+    Wt[m][n] the library reads."""
+    xb = P.x.view(torch.float16).to(torch.bfloat16)
+    if canonical:
+        ws = [w[0].view(torch.bfloat16).t().contiguous() for w in P.weights]
+        out = torch.empty(P.n, dtype=torch.bfloat16, device="cuda")
+        run = lambda k: torch.mv(ws[k % len(ws)], xb, out=out)
+    else:
+        ws = [w[0].view(torch.bfloat16) for w in P.weights]
+        xrow = xb.unsqueeze(0)
+        out = torch.empty((1, P.n), dtype=torch.bfloat16, device="cuda")
+        run = lambda k: torch.matmul(xrow, ws[k % len(ws)], out=out)
+    for k in range(20):
+        run(k)
+    torch.cuda.synchronize()
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    start.record()
+    for k in range(launches):
+        run(k)
+    stop.record()
+    torch.cuda.synchronize()
+    return start.elapsed_time(stop) * 1e-3 / launches
+
+
 def time_projection_spread(T, torch, P, p, batches=10, launches=100, singles=20):
     """The same call timed in `batches` separate batches of back-to-back launches (us per
     call: median and minimum over the batches) and as single launches, each bracketed by
@@ -1054,6 +1081,12 @@ def main() -> int:
             else:
                 per_proj[P.name]["launch"] = T.teal_gemv_plan(BITS[fmt], P.m, P.n)[1]
             per_proj[P.name]["nnz"] = P.nnz[head]
+            if fmt == "bf16" and not args.batch:
+                per_proj[P.name]["us_dense_torch_matmul_same_layout"] = \
+                    time_torch_matmul(torch, P, False) * 1e6
+                if args.layers == 1:
+                    per_proj[P.name]["us_dense_torch_matmul_canonical_layout"] = \
+                        time_torch_matmul(torch, P, True) * 1e6
         if groups is not None:
             per_group = alone(groups[:4])
 
