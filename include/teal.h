@@ -277,6 +277,27 @@ teal_status teal_sparse_gemv_w8_multi(int count, const int8_t *const *Wq,
                                       void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The 8-bit calls with their input formed on the fly, as for bf16 weights
+ * (Section 5.3 combines the method with weight quantisation; Appendix A.3
+ * gives the inputs): teal_sparse_gemv_w8_swiglu is teal_sparse_gemv_w8 on
+ * h = fp16(SiLU(gate) * up), teal_sparse_gemv_w8_rmsnorm_multi is
+ * teal_sparse_gemv_w8_multi on the normalised hidden state, both in the
+ * arithmetic stated for teal_sparse_gemv_bf16_swiglu and
+ * teal_sparse_gemv_bf16_rmsnorm_multi, in one launch, with results bitwise those
+ * of the producer call followed by the plain 8-bit call.  Arguments as for those
+ * calls, with Wq / scale_f16 in place of Wt_bf16 (n % 16 == 0).
+ */
+teal_status teal_sparse_gemv_w8_swiglu(const int8_t *Wq, const void *scale_f16, const float *gate,
+                                       const float *up, float t, float *y, int m, int n,
+                                       void *workspace, size_t workspace_bytes, void *stream);
+teal_status teal_sparse_gemv_w8_rmsnorm_multi(int count, const int8_t *const *Wq,
+                                              const void *const *scale_f16, const float *t,
+                                              float *const *y, const int *n, const float *h,
+                                              const float *gamma, float eps, int m,
+                                              void *workspace, size_t workspace_bytes,
+                                              void *stream);
+
+/*
  * The same product for 4-bit group-quantised weights (Section 5.3):
  * W[j][i] = nibble(i, j) * scale[i / group][j].
  *   Wq    [m][n/2] bytes, two two's-complement nibbles per byte along the

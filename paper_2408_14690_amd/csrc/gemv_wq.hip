@@ -365,6 +365,71 @@ hipError_t launch_gemv_w8_multi(int count, const int8_t *const *Wq, const void *
     return hipGetLastError();
 }
 
+static bool w8_lanes_supported(const GemvShape &s)
+{
+    const int l = s.lanes_per_row;
+    return (l == 8 || l == 16 || l == 32 || l == 64) && s.splits >= 1 && s.tile_cols >= 0 &&
+           s.tile_cols % FmtW8::kElemsPerLane == 0 && s.tile_cols <= l * FmtW8::kElemsPerLane;
+}
+
+// The int8 kernels with their input formed in the kernel (the activation sources of the bf16
+// kernels: Appendix A.3's MLP intermediate, the normalised hidden state).  Shapes with 8
+// wavefronts and 4 loads per batch, which is what the launch-shape rule produces.
+hipError_t launch_gemv_w8_swiglu(const int8_t *Wq, const void *scale_f16, const float *gate,
+                                 const float *up, float t, float *y, int m, int n, float *partial,
+                                 int *counters, const GemvShape &sh, hipStream_t stream)
+{
+    if (sh.waves != 8 || sh.unroll != 4 || !w8_lanes_supported(sh)) return hipErrorInvalidValue;
+    const GemvGeometry g = gemv_geometry(m, n, sh, FmtW8::kElemsPerLane, 64);
+    FmtW8::Args a{Wq, static_cast<const __half *>(scale_f16)};
+#define TEAL_LAUNCH_S(LPR)                                                                     \
+    hipLaunchKernelGGL((sparse_gemv_swiglu_kernel<FmtW8, LPR, 8, 4>), dim3(g.tiles * g.splits), \
+                       dim3(8 * 64), g.lds, stream, a, gate, up, t, partial, counters, y, m, n, \
+                       g.ks, g.tiles, g.tile_cols, g.splits)
+    if (sh.lanes_per_row == 64) TEAL_LAUNCH_S(64);
+    else if (sh.lanes_per_row == 32) TEAL_LAUNCH_S(32);
+    else if (sh.lanes_per_row == 16) TEAL_LAUNCH_S(16);
+    else TEAL_LAUNCH_S(8);
+#undef TEAL_LAUNCH_S
+    return hipGetLastError();
+}
+
+hipError_t launch_gemv_w8_rmsnorm_multi(int count, const int8_t *const *Wq,
+                                        const void *const *scale_f16, const float *t,
+                                        float *const *y, const int *n, const float *h,
+                                        const float *gamma, float eps, int m, float *partial,
+                                        int *counters, const GemvShape &sh, hipStream_t stream)
+{
+    if (m < 8 || m > kMaxNormDim || m % 8 != 0 || sh.waves != kNormWaves || sh.unroll != 4 ||
+        !w8_lanes_supported(sh))
+        return hipErrorInvalidValue;
+    int n_max = 0;
+    for (int k = 0; k < count; ++k) n_max = n[k] > n_max ? n[k] : n_max;
+    const GemvGeometry g = gemv_geometry(m, n_max, sh, FmtW8::kElemsPerLane, 64);
+    MultiArgs<FmtW8> ma{};
+    ma.count = count;
+    ma.tile_begin[0] = 0;
+    for (int k = 0; k < count; ++k) {
+        ma.a[k].W = Wq[k];
+        ma.a[k].scale = static_cast<const __half *>(scale_f16[k]);
+        ma.y[k] = y[k];
+        ma.t[k] = t[k];
+        ma.n[k] = n[k];
+        ma.tile_begin[k + 1] = ma.tile_begin[k] + (n[k] + g.tile_cols - 1) / g.tile_cols;
+    }
+    const int tiles = ma.tile_begin[count];
+#define TEAL_LAUNCH_N(LPR)                                                                     \
+    hipLaunchKernelGGL((sparse_gemv_rmsnorm_multi_kernel<FmtW8, LPR, 4>),                      \
+                       dim3(tiles * g.splits), dim3(kNormWaves * 64), g.lds, stream, ma, h,    \
+                       gamma, eps, partial, counters, m, g.ks, g.tile_cols, g.splits)
+    if (sh.lanes_per_row == 64) TEAL_LAUNCH_N(64);
+    else if (sh.lanes_per_row == 32) TEAL_LAUNCH_N(32);
+    else if (sh.lanes_per_row == 16) TEAL_LAUNCH_N(16);
+    else TEAL_LAUNCH_N(8);
+#undef TEAL_LAUNCH_N
+    return hipGetLastError();
+}
+
 hipError_t launch_gemv_w4(const uint8_t *Wq, const void *scale_f16, const void *x_f16, float t,
                           float *y, int m, int n, float *partial, int *counters,
                           const GemvShape &sh, hipStream_t stream)

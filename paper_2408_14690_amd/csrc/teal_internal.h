@@ -107,6 +107,16 @@ hipError_t launch_gemv_w8_multi(int count, const int8_t *const *Wq, const void *
                                 int m, float *partial, int *counters, const GemvShape &shape,
                                 hipStream_t stream);
 
+hipError_t launch_gemv_w8_swiglu(const int8_t *Wq, const void *scale_f16, const float *gate,
+                                 const float *up, float t, float *y, int m, int n, float *partial,
+                                 int *counters, const GemvShape &shape, hipStream_t stream);
+
+hipError_t launch_gemv_w8_rmsnorm_multi(int count, const int8_t *const *Wq,
+                                        const void *const *scale_f16, const float *t,
+                                        float *const *y, const int *n, const float *h,
+                                        const float *gamma, float eps, int m, float *partial,
+                                        int *counters, const GemvShape &shape, hipStream_t stream);
+
 hipError_t launch_gemv_w4(const uint8_t *Wq, const void *scale_f16, const void *x_f16,
                           float t, float *y, int m, int n, float *partial, int *counters,
                           const GemvShape &shape, hipStream_t stream);

@@ -181,6 +181,45 @@ def test_stack_argument_errors_and_workspace():
         T.teal_sparse_gemv_bf16_stack([2], [W], [0.5], [Y], [64], [X], [64], WS, BIG, 0)
 
 
+def test_int8_fused_producer_argument_errors():
+    G, U, H, GA = 0x70000, 0x80000, 0x90000, 0xA0000
+    ok = dict(Wq=W, scale_f16=SC, gate=G, up=U, t=0.5, y=Y, m=4096, n=1024, workspace=WS,
+              workspace_bytes=BIG, stream=0)
+
+    def sw(**kw):
+        a = dict(ok)
+        a.update(kw)
+        return T.teal_sparse_gemv_w8_swiglu(**a)
+
+    assert sw(up=None) == T.TEAL_ERR_NULL
+    assert sw(scale_f16=None) == T.TEAL_ERR_NULL
+    assert sw(n=1032) == T.TEAL_ERR_SHAPE
+    assert sw(gate=G + 2) == T.TEAL_ERR_ALIGN
+    assert sw(scale_f16=SC + 1) == T.TEAL_ERR_ALIGN
+    assert sw(t=-1.0) == T.TEAL_ERR_THRESHOLD
+    assert sw(workspace_bytes=64) == T.TEAL_ERR_WORKSPACE
+    okn = dict(Wq_list=[W, W + 0x1000], scale_list=[SC, SC + 0x100], t_list=[0.5, 0.25],
+               y_list=[Y, Y + 0x1000], n_list=[4096, 1024], h=H, gamma=GA, eps=1e-5, m=4096,
+               workspace=WS, workspace_bytes=BIG, stream=0)
+
+    def nm(**kw):
+        a = dict(okn)
+        a.update(kw)
+        return T.teal_sparse_gemv_w8_rmsnorm_multi(**a)
+
+    assert nm(h=None) == T.TEAL_ERR_NULL
+    assert nm(scale_list=[SC, None]) == T.TEAL_ERR_NULL
+    assert nm(n_list=[4096, 1032]) == T.TEAL_ERR_SHAPE
+    assert nm(m=16392) == T.TEAL_ERR_SHAPE
+    assert nm(m=4100) == T.TEAL_ERR_SHAPE
+    assert nm(h=H + 4) == T.TEAL_ERR_ALIGN
+    assert nm(eps=-1.0) == T.TEAL_ERR_THRESHOLD
+    assert nm(t_list=[0.5, math.inf]) == T.TEAL_ERR_THRESHOLD
+    assert nm(workspace_bytes=64) == T.TEAL_ERR_WORKSPACE
+    five = dict(Wq_list=[W] * 5, scale_list=[SC] * 5, t_list=[0.5] * 5, y_list=[Y] * 5, n_list=[64] * 5)
+    assert nm(**five) == T.TEAL_ERR_UNSUPPORTED
+
+
 def test_stream_read_probe_argument_errors():
     assert T.teal_stream_read_probe(None, 4096, 256, 0, Y, 0) == T.TEAL_ERR_NULL
     assert T.teal_stream_read_probe(W, 4096, 256, 0, None, 0) == T.TEAL_ERR_NULL

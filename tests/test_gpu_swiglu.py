@@ -139,3 +139,30 @@ def test_fused_product_with_nan_and_saturated_gates(T):
     want = orc.sparse_gemv_bf16_swiglu(w, g, u, t)
     got = run_fused(T, wt, g, u, t, m, n, ws)
     assert np.isfinite(got).all() and rel_l2(got, want) <= TIGHT
+
+
+@pytest.mark.parametrize("n,m", [(16, 1), (80, 200), (1040, 2049), (528, 4096), (4096, 14336)])
+def test_fused_product_int8_weights(T, n, m):
+    """teal_sparse_gemv_w8_swiglu: the oracle's int8 product on the oracle's intermediate,
+    bitwise the producer kernel followed by teal_sparse_gemv_w8, exact survivor count."""
+    q, scale = ti.quantize_w8(ti.weights_bf16(n, m, 900 + n + m))
+    qd, sd = dev(q), dev(scale)
+    g, u = ti.mlp_gate_up(m, 17 + m)
+    h = orc.swiglu_f16(g, u)
+    gd, ud = dev(g), dev(u)
+    ws = torch.zeros(T.teal_workspace_bytes(m, n), dtype=torch.uint8, device="cuda")
+    hd = torch.empty(m, dtype=torch.int16, device="cuda")
+    T.check(T.teal_swiglu_f16(gd, ud, hd, m))
+    for p in (0.0, 0.5, 0.9, 1.0):
+        t = ti.quantile_threshold(h, p)
+        y = torch.full((n,), float("nan"), dtype=torch.float32, device="cuda")
+        T.check(T.teal_sparse_gemv_w8_swiglu(qd, sd, gd, ud, t, y, m, n, ws))
+        torch.cuda.synchronize()
+        got = y.cpu().numpy()
+        assert rel_l2(got, orc.sparse_gemv_w8(q, scale, h, t)) <= TIGHT, p
+        off = T.teal_survivors_offset()
+        assert ws[off:off + 4].view(torch.int32).item() == orc.sparsify(h, t)[3], p
+        y2 = torch.full((n,), float("nan"), dtype=torch.float32, device="cuda")
+        T.check(T.teal_sparse_gemv_w8(qd, sd, hd, t, y2, m, n, ws))
+        torch.cuda.synchronize()
+        assert np.array_equal(got, y2.cpu().numpy()), p
