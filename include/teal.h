@@ -312,6 +312,25 @@ teal_status teal_sparse_gemv_w4(const uint8_t *Wq, const void *scale_f16, int gr
                                 void *stream);
 
 /*
+ * The 4-bit calls with their input formed on the fly, as for the other formats:
+ * teal_sparse_gemv_w4_swiglu is teal_sparse_gemv_w4 on h = fp16(SiLU(gate) * up),
+ * teal_sparse_gemv_w4_rmsnorm_multi is teal_sparse_gemv_w4_multi on the normalised
+ * hidden state (arithmetic as stated for the bf16 calls), in one launch, with
+ * results bitwise those of the producer call followed by the plain 4-bit call.
+ * group == 128, m % 128 == 0 (and m <= 16384 for the normalised input).
+ */
+teal_status teal_sparse_gemv_w4_swiglu(const uint8_t *Wq, const void *scale_f16, int group,
+                                       const float *gate, const float *up, float t, float *y,
+                                       int m, int n, void *workspace, size_t workspace_bytes,
+                                       void *stream);
+teal_status teal_sparse_gemv_w4_rmsnorm_multi(int count, const uint8_t *const *Wq,
+                                              const void *const *scale_f16, int group,
+                                              const float *t, float *const *y, const int *n,
+                                              const float *h, const float *gamma, float eps,
+                                              int m, void *workspace, size_t workspace_bytes,
+                                              void *stream);
+
+/*
  * teal_sparse_gemv_bf16_multi for 4-bit group-quantised weights: count matrices
  * (1..4) that read the same hidden state, one kernel launch.  Wq, scale_f16, t,
  * y, n are HOST arrays of length count (device pointers / values per matrix,

@@ -20,4 +20,5 @@ from .binding import (  # noqa: F401
     teal_rmsnorm_f16, teal_sparse_gemv_bf16_rmsnorm_multi, teal_workspace_bytes_stack,
     teal_sparse_gemv_bf16_stack, teal_sparse_gemv_w8_stack, teal_sparse_gemv_w4_stack,
     teal_stream_read_probe, teal_sparse_gemv_w8_swiglu, teal_sparse_gemv_w8_rmsnorm_multi,
+    teal_sparse_gemv_w4_swiglu, teal_sparse_gemv_w4_rmsnorm_multi,
 )

@@ -34,6 +34,7 @@ EXPORTS = (
     "teal_sparse_gemv_bf16_rmsnorm_multi", "teal_workspace_bytes_stack",
     "teal_sparse_gemv_bf16_stack", "teal_sparse_gemv_w8_stack", "teal_sparse_gemv_w4_stack",
     "teal_stream_read_probe", "teal_sparse_gemv_w8_swiglu", "teal_sparse_gemv_w8_rmsnorm_multi",
+    "teal_sparse_gemv_w4_swiglu", "teal_sparse_gemv_w4_rmsnorm_multi",
 )
 TEAL_HIST_BINS = 32768
 TEAL_MAX_BATCH = 8
@@ -101,6 +102,12 @@ def load_library():
     lib.teal_sparse_gemv_w8_rmsnorm_multi.argtypes = [i, c.POINTER(vp), c.POINTER(vp), c.POINTER(f),
                                                       c.POINTER(vp), c.POINTER(i), vp, vp, f, i,
                                                       vp, sz, vp]
+    lib.teal_sparse_gemv_w4_swiglu.restype = i
+    lib.teal_sparse_gemv_w4_swiglu.argtypes = [vp, vp, i, vp, vp, f, vp, i, i, vp, sz, vp]
+    lib.teal_sparse_gemv_w4_rmsnorm_multi.restype = i
+    lib.teal_sparse_gemv_w4_rmsnorm_multi.argtypes = [i, c.POINTER(vp), c.POINTER(vp), i,
+                                                      c.POINTER(f), c.POINTER(vp), c.POINTER(i),
+                                                      vp, vp, f, i, vp, sz, vp]
     lib.teal_stream_read_probe.restype = i
     lib.teal_stream_read_probe.argtypes = [vp, sz, i, c.c_uint32, vp, vp]
     lib.teal_sparse_gemv_w8_stack.restype = i
@@ -548,6 +555,32 @@ def teal_sparse_gemv_w8_rmsnorm_multi(Wq_list, scale_list, t_list, y_list, n_lis
         "teal_sparse_gemv_w8_rmsnorm_multi",
         count, W, S, Tt, Y, N, _ptr(h, 4 * m, "h"), _ptr(gamma, 4 * m, "gamma"), float(eps), int(m),
         _ptr(workspace), _nbytes(workspace, workspace_bytes), _stream(stream))
+
+
+def teal_sparse_gemv_w4_swiglu(Wq, scale_f16, group, gate, up, t, y, m, n, workspace,
+                               workspace_bytes=None, stream=None) -> int:
+    return _call(
+        "teal_sparse_gemv_w4_swiglu",
+        _ptr(Wq, m * n // 2, "Wq"), _ptr(scale_f16, 2 * n * (m // 128), "scale"), int(group),
+        _ptr(gate, 4 * m, "gate"), _ptr(up, 4 * m, "up"), float(t), _ptr(y, 4 * n, "y"), int(m),
+        int(n), _ptr(workspace), _nbytes(workspace, workspace_bytes), _stream(stream))
+
+
+def teal_sparse_gemv_w4_rmsnorm_multi(Wq_list, scale_list, group, t_list, y_list, n_list, h, gamma,
+                                      eps, m, workspace, workspace_bytes=None, stream=None) -> int:
+    count = len(Wq_list)
+    if not (len(scale_list) == len(t_list) == len(y_list) == len(n_list) == count):
+        raise ValueError("per-matrix lists must have the same length")
+    W = (ctypes.c_void_p * count)(*[_ptr(w, m * n // 2, "Wq") for w, n in zip(Wq_list, n_list)])
+    S = (ctypes.c_void_p * count)(*[_ptr(sc, 2 * n * (m // 128), "scale")
+                                    for sc, n in zip(scale_list, n_list)])
+    Y = (ctypes.c_void_p * count)(*[_ptr(y, 4 * n, "y") for y, n in zip(y_list, n_list)])
+    Tt = (ctypes.c_float * count)(*[float(t) for t in t_list])
+    N = (ctypes.c_int * count)(*[int(n) for n in n_list])
+    return _call(
+        "teal_sparse_gemv_w4_rmsnorm_multi",
+        count, W, S, int(group), Tt, Y, N, _ptr(h, 4 * m, "h"), _ptr(gamma, 4 * m, "gamma"),
+        float(eps), int(m), _ptr(workspace), _nbytes(workspace, workspace_bytes), _stream(stream))
 
 
 def teal_abs_histogram(x_f16, count, hist, stream=None) -> int:

@@ -110,8 +110,8 @@ struct W4Batch {
 // once per (wavefront, group it touches), not once per row.  Batches never
 // straddle a group, and two batches are in flight per wavefront across group
 // boundaries.
-template <int LPR, int WAVES, int U>
-__device__ __forceinline__ void w4_block(const FmtW4::Args &a, const __half *__restrict__ x,
+template <int LPR, int WAVES, int U, class XS>
+__device__ __forceinline__ void w4_block(const FmtW4::Args &a, const XS &x,
                                          float t, float *partial, int *counters, float *y, int m,
                                          int n, int ks, int tile, int s, int tile_cols, int splits,
                                          const SurvivorReport &report)
@@ -128,10 +128,14 @@ __device__ __forceinline__ void w4_block(const FmtW4::Args &a, const __half *__r
     const int k1 = min(m, k0 + ks);
     int seg_excl;
     int cnt;
-    if (k1 - k0 <= 8 * 64)             // block-uniform: short slices need no barrier
-        cnt = compact_slice_private<8, WAVES>(x, t, k0, k1, list, seg_excl);
-    else
-        cnt = compact_slice<WAVES>(HalfSource{x}, t, k0, k1, list, seg_cnt, seg_excl);
+    if constexpr (XS::kPlainHalf) {
+        if (k1 - k0 <= 8 * 64)         // block-uniform: short slices need no barrier
+            cnt = compact_slice_private<8, WAVES>(x.x, t, k0, k1, list, seg_excl);
+        else
+            cnt = compact_slice<WAVES>(x, t, k0, k1, list, seg_cnt, seg_excl);
+    } else {
+        cnt = compact_slice<WAVES>(x, t, k0, k1, list, seg_cnt, seg_excl);
+    }
 
     const int lane = threadIdx.x & 63;
     const int g = lane / LPR;
@@ -235,15 +239,28 @@ __global__ __launch_bounds__(WAVES * 64) void sparse_gemv_w4_kernel(
     FmtW4::Args a, const __half *__restrict__ x, float t, float *partial, int *counters, float *y,
     int m, int n, int ks, int tiles, int tile_cols, int splits)
 {
-    w4_block<LPR, WAVES, U>(a, x, t, partial, counters, y, m, n, ks, blockIdx.x % tiles,
-                            blockIdx.x / tiles, tile_cols, splits,
+    w4_block<LPR, WAVES, U>(a, HalfSource{x}, t, partial, counters, y, m, n, ks,
+                            blockIdx.x % tiles, blockIdx.x / tiles, tile_cols, splits,
+                            survivor_report(counters, 0, splits));
+}
+
+// The int4 product with its input formed in the kernel from the two products that precede
+// W_down (Appendix A.3), as sparse_gemv_swiglu_kernel does for the other formats.
+template <int LPR, int WAVES, int U>
+__global__ __launch_bounds__(WAVES * 64) void sparse_gemv_w4_swiglu_kernel(
+    FmtW4::Args a, const float *__restrict__ gate, const float *__restrict__ up, float t,
+    float *partial, int *counters, float *y, int m, int n, int ks, int tiles, int tile_cols,
+    int splits)
+{
+    w4_block<LPR, WAVES, U>(a, SwigluSource{gate, up}, t, partial, counters, y, m, n, ks,
+                            blockIdx.x % tiles, blockIdx.x / tiles, tile_cols, splits,
                             survivor_report(counters, 0, splits));
 }
 
 // Several int4 matrices that read the same hidden state in one launch; the block finds its
 // matrix from its tile index as in sparse_gemv_multi_kernel.
-template <int LPR, int WAVES, int U>
-__device__ __forceinline__ void w4_multi_block(const MultiArgs<FmtW4> &ma, const __half *x,
+template <int LPR, int WAVES, int U, class XS>
+__device__ __forceinline__ void w4_multi_block(const MultiArgs<FmtW4> &ma, const XS &x,
                                                float *partial, int *counters, int m, int ks,
                                                int tile_cols, int splits, int block)
 {
@@ -270,8 +287,20 @@ __global__ __launch_bounds__(WAVES * 64) void sparse_gemv_w4_multi_kernel(
     MultiArgs<FmtW4> ma, const __half *__restrict__ x, float *partial, int *counters, int m,
     int ks, int tile_cols, int splits)
 {
-    w4_multi_block<LPR, WAVES, U>(ma, x, partial, counters, m, ks, tile_cols, splits,
+    w4_multi_block<LPR, WAVES, U>(ma, HalfSource{x}, partial, counters, m, ks, tile_cols, splits,
                                   (int)blockIdx.x);
+}
+
+// The grouped int4 launch with its shared input formed from the hidden state before the
+// normalisation layer, as sparse_gemv_rmsnorm_multi_kernel does for the other formats.
+template <int LPR, int U>
+__global__ __launch_bounds__(kNormWaves * 64) void sparse_gemv_w4_rmsnorm_multi_kernel(
+    MultiArgs<FmtW4> ma, const float *__restrict__ h, const float *__restrict__ gamma, float eps,
+    float *partial, int *counters, int m, int ks, int tile_cols, int splits)
+{
+    __shared__ double wave_sums[kMaxNormChunks * kNormWaves];
+    w4_multi_block<LPR, kNormWaves, U>(ma, RmsnormSource{h, gamma, m, eps, wave_sums}, partial,
+                                       counters, m, ks, tile_cols, splits, (int)blockIdx.x);
 }
 
 // Independent int4 groups in one launch (see sparse_gemv_stack_kernel).
@@ -281,10 +310,10 @@ __global__ __launch_bounds__(WAVES * 64) void sparse_gemv_w4_stack_kernel(StackA
     int block;
     const StackGroup<FmtW4> &sg = sa.g[stack_group_of_block(sa, block)];
     if (sg.lanes_per_row == 32)
-        w4_multi_block<32, WAVES, U>(sg.ma, sg.x, sg.partial, sg.counters, sg.m, sg.ks,
+        w4_multi_block<32, WAVES, U>(sg.ma, HalfSource{sg.x}, sg.partial, sg.counters, sg.m, sg.ks,
                                      sg.tile_cols, sg.splits, block);
     else
-        w4_multi_block<16, WAVES, U>(sg.ma, sg.x, sg.partial, sg.counters, sg.m, sg.ks,
+        w4_multi_block<16, WAVES, U>(sg.ma, HalfSource{sg.x}, sg.partial, sg.counters, sg.m, sg.ks,
                                      sg.tile_cols, sg.splits, block);
 }
 
@@ -448,6 +477,59 @@ hipError_t launch_gemv_w4(const uint8_t *Wq, const void *scale_f16, const void *
     if (sh.lanes_per_row == 32) TEAL_LAUNCH_W4(32);
     else TEAL_LAUNCH_W4(16);
 #undef TEAL_LAUNCH_W4
+    return hipGetLastError();
+}
+
+hipError_t launch_gemv_w4_swiglu(const uint8_t *Wq, const void *scale_f16, const float *gate,
+                                 const float *up, float t, float *y, int m, int n, float *partial,
+                                 int *counters, const GemvShape &sh, hipStream_t stream)
+{
+    GemvShape w4 = sh;
+    w4.waves = kW4Waves;
+    const GemvGeometry g = gemv_geometry(m, n, w4, FmtW4::kElemsPerLane, kGroup);
+    FmtW4::Args a{Wq, static_cast<const __half *>(scale_f16)};
+#define TEAL_LAUNCH_W4S(LPR)                                                                   \
+    hipLaunchKernelGGL((sparse_gemv_w4_swiglu_kernel<LPR, kW4Waves, kW4Unroll>),               \
+                       dim3(g.tiles * g.splits), dim3(kW4Waves * 64), g.lds, stream, a, gate,  \
+                       up, t, partial, counters, y, m, n, g.ks, g.tiles, g.tile_cols, g.splits)
+    if (sh.lanes_per_row == 32) TEAL_LAUNCH_W4S(32);
+    else TEAL_LAUNCH_W4S(16);
+#undef TEAL_LAUNCH_W4S
+    return hipGetLastError();
+}
+
+hipError_t launch_gemv_w4_rmsnorm_multi(int count, const uint8_t *const *Wq,
+                                        const void *const *scale_f16, const float *t,
+                                        float *const *y, const int *n, const float *h,
+                                        const float *gamma, float eps, int m, float *partial,
+                                        int *counters, const GemvShape &sh, hipStream_t stream)
+{
+    if (m < 8 || m > kMaxNormDim || m % kGroup != 0 || kW4Waves != kNormWaves)
+        return hipErrorInvalidValue;
+    int n_max = 0;
+    for (int k = 0; k < count; ++k) n_max = n[k] > n_max ? n[k] : n_max;
+    GemvShape w4 = sh;
+    w4.waves = kW4Waves;
+    const GemvGeometry g = gemv_geometry(m, n_max, w4, FmtW4::kElemsPerLane, kGroup);
+    MultiArgs<FmtW4> ma{};
+    ma.count = count;
+    ma.tile_begin[0] = 0;
+    for (int k = 0; k < count; ++k) {
+        ma.a[k].W = Wq[k];
+        ma.a[k].scale = static_cast<const __half *>(scale_f16[k]);
+        ma.y[k] = y[k];
+        ma.t[k] = t[k];
+        ma.n[k] = n[k];
+        ma.tile_begin[k + 1] = ma.tile_begin[k] + (n[k] + g.tile_cols - 1) / g.tile_cols;
+    }
+    const int tiles = ma.tile_begin[count];
+#define TEAL_LAUNCH_W4N(LPR)                                                                   \
+    hipLaunchKernelGGL((sparse_gemv_w4_rmsnorm_multi_kernel<LPR, kW4Unroll>),                  \
+                       dim3(tiles * g.splits), dim3(kNormWaves * 64), g.lds, stream, ma, h,    \
+                       gamma, eps, partial, counters, m, g.ks, g.tile_cols, g.splits)
+    if (sh.lanes_per_row == 32) TEAL_LAUNCH_W4N(32);
+    else TEAL_LAUNCH_W4N(16);
+#undef TEAL_LAUNCH_W4N
     return hipGetLastError();
 }
 

@@ -190,7 +190,7 @@ const char *teal_status_string(teal_status s)
     return "unknown status";
 }
 
-int teal_version(void) { return 340; }
+int teal_version(void) { return 350; }
 
 size_t teal_survivors_offset(void) { return teal::kCounterBytes; }
 
@@ -702,6 +702,59 @@ teal_status teal_sparse_gemv_w4(const uint8_t *Wq, const void *scale_f16, int gr
     return from_hip(teal::launch_gemv_w4(Wq, scale_f16, x_f16, t, y, m, n, ws_partials(workspace, m),
                                          ws_counters(workspace), sh,
                                          static_cast<hipStream_t>(stream)));
+}
+
+teal_status teal_sparse_gemv_w4_swiglu(const uint8_t *Wq, const void *scale_f16, int group,
+                                       const float *gate, const float *up, float t, float *y,
+                                       int m, int n, void *workspace, size_t workspace_bytes,
+                                       void *stream)
+{
+    if (!up || !scale_f16) return TEAL_ERR_NULL;
+    const GemvArgs a{Wq, gate, t, y, m, n, workspace, workspace_bytes};
+    const teal_status st = check_gemv(a, 32);
+    if (st != TEAL_OK) return st;
+    if (!aligned(gate, 4) || !aligned(up, 4) || !aligned(scale_f16, 16)) return TEAL_ERR_ALIGN;
+    if (group != 128 || m % 128 != 0) return TEAL_ERR_UNSUPPORTED;
+    // The launch shape of teal_sparse_gemv_w4: same sums, bit for bit.
+    const GemvShape sh = auto_shape(m, n, 32, 16, 32, 128);
+    return from_hip(teal::launch_gemv_w4_swiglu(Wq, scale_f16, gate, up, t, y, m, n,
+                                                ws_partials(workspace, m), ws_counters(workspace),
+                                                sh, static_cast<hipStream_t>(stream)));
+}
+
+teal_status teal_sparse_gemv_w4_rmsnorm_multi(int count, const uint8_t *const *Wq,
+                                              const void *const *scale_f16, int group,
+                                              const float *t, float *const *y, const int *n,
+                                              const float *h, const float *gamma, float eps,
+                                              int m, void *workspace, size_t workspace_bytes,
+                                              void *stream)
+{
+    if (count < 1 || count > teal::kMaxMatrices) return TEAL_ERR_UNSUPPORTED;
+    if (!Wq || !scale_f16 || !t || !y || !n || !h || !gamma || !workspace) return TEAL_ERR_NULL;
+    long long n_total = 0;
+    for (int k = 0; k < count; ++k) {
+        if (!Wq[k] || !scale_f16[k] || !y[k]) return TEAL_ERR_NULL;
+        if (n[k] < 32 || n[k] > teal::kMaxDim || n[k] % 32 != 0) return TEAL_ERR_SHAPE;
+        n_total += n[k];
+    }
+    if (m < 8 || m > teal::kMaxNormInput || m % 8 != 0 || n_total > teal::kMaxDim)
+        return TEAL_ERR_SHAPE;
+    for (int k = 0; k < count; ++k)
+        if (!aligned(Wq[k], 16) || !aligned(scale_f16[k], 16) || !aligned(y[k], 4))
+            return TEAL_ERR_ALIGN;
+    if (!aligned(h, 16) || !aligned(gamma, 4) || !aligned(workspace, kAlignWorkspace))
+        return TEAL_ERR_ALIGN;
+    for (int k = 0; k < count; ++k)
+        if (!threshold_ok(t[k])) return TEAL_ERR_THRESHOLD;
+    if (!norm_eps_ok(eps)) return TEAL_ERR_THRESHOLD;
+    if (group != 128 || m % 128 != 0) return TEAL_ERR_UNSUPPORTED;
+    if (workspace_bytes < teal_workspace_bytes(m, (int)n_total)) return TEAL_ERR_WORKSPACE;
+    // The launch shape of teal_sparse_gemv_w4_multi: same sums, bit for bit.
+    const GemvShape sh = count > 1 ? auto_shape_multi(m, n, count, 32, 16, 32, 128)
+                                   : auto_shape(m, (int)n_total, 32, 16, 32, 128);
+    return from_hip(teal::launch_gemv_w4_rmsnorm_multi(
+        count, Wq, scale_f16, t, y, n, h, gamma, eps, m, ws_partials(workspace, m),
+        ws_counters(workspace), sh, static_cast<hipStream_t>(stream)));
 }
 
 teal_status teal_sparse_gemv_w4_multi(int count, const uint8_t *const *Wq,

@@ -121,6 +121,16 @@ hipError_t launch_gemv_w4(const uint8_t *Wq, const void *scale_f16, const void *
                           float t, float *y, int m, int n, float *partial, int *counters,
                           const GemvShape &shape, hipStream_t stream);
 
+hipError_t launch_gemv_w4_swiglu(const uint8_t *Wq, const void *scale_f16, const float *gate,
+                                 const float *up, float t, float *y, int m, int n, float *partial,
+                                 int *counters, const GemvShape &shape, hipStream_t stream);
+
+hipError_t launch_gemv_w4_rmsnorm_multi(int count, const uint8_t *const *Wq,
+                                        const void *const *scale_f16, const float *t,
+                                        float *const *y, const int *n, const float *h,
+                                        const float *gamma, float eps, int m, float *partial,
+                                        int *counters, const GemvShape &shape, hipStream_t stream);
+
 hipError_t launch_gemv_w4_multi(int count, const uint8_t *const *Wq, const void *const *scale_f16,
                                 const float *t, float *const *y, const int *n, const void *x_f16,
                                 int m, float *partial, int *counters, const GemvShape &shape,

@@ -220,6 +220,42 @@ def test_int8_fused_producer_argument_errors():
     assert nm(**five) == T.TEAL_ERR_UNSUPPORTED
 
 
+def test_int4_fused_producer_argument_errors():
+    G, U, H, GA = 0x70000, 0x80000, 0x90000, 0xA0000
+    ok = dict(Wq=W, scale_f16=SC, group=128, gate=G, up=U, t=0.5, y=Y, m=4096, n=1024, workspace=WS,
+              workspace_bytes=BIG, stream=0)
+
+    def sw(**kw):
+        a = dict(ok)
+        a.update(kw)
+        return T.teal_sparse_gemv_w4_swiglu(**a)
+
+    assert sw(up=None) == T.TEAL_ERR_NULL
+    assert sw(n=1040) == T.TEAL_ERR_SHAPE
+    assert sw(scale_f16=SC + 8) == T.TEAL_ERR_ALIGN
+    assert sw(t=math.nan) == T.TEAL_ERR_THRESHOLD
+    assert sw(group=32) == T.TEAL_ERR_UNSUPPORTED
+    assert sw(m=4160) == T.TEAL_ERR_UNSUPPORTED
+    assert sw(workspace_bytes=64) == T.TEAL_ERR_WORKSPACE
+    okn = dict(Wq_list=[W, W + 0x1000], scale_list=[SC, SC + 0x100], group=128, t_list=[0.5, 0.25],
+               y_list=[Y, Y + 0x1000], n_list=[4096, 1024], h=H, gamma=GA, eps=1e-5, m=4096,
+               workspace=WS, workspace_bytes=BIG, stream=0)
+
+    def nm(**kw):
+        a = dict(okn)
+        a.update(kw)
+        return T.teal_sparse_gemv_w4_rmsnorm_multi(**a)
+
+    assert nm(gamma=None) == T.TEAL_ERR_NULL
+    assert nm(n_list=[4096, 1040]) == T.TEAL_ERR_SHAPE
+    assert nm(m=16512) == T.TEAL_ERR_SHAPE
+    assert nm(scale_list=[SC, SC + 8]) == T.TEAL_ERR_ALIGN
+    assert nm(eps=math.inf) == T.TEAL_ERR_THRESHOLD
+    assert nm(group=64) == T.TEAL_ERR_UNSUPPORTED
+    assert nm(m=4104) == T.TEAL_ERR_UNSUPPORTED
+    assert nm(workspace_bytes=64) == T.TEAL_ERR_WORKSPACE
+
+
 def test_stream_read_probe_argument_errors():
     assert T.teal_stream_read_probe(None, 4096, 256, 0, Y, 0) == T.TEAL_ERR_NULL
     assert T.teal_stream_read_probe(W, 4096, 256, 0, None, 0) == T.TEAL_ERR_NULL

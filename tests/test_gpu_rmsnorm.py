@@ -190,3 +190,42 @@ def test_fused_grouped_product_int8_weights(T, name, ns, m, ps):
     torch.cuda.synchronize()
     for a, b in zip(ys, ys2):
         assert torch.equal(a, b)
+
+
+W4_CASES = [
+    ("llama q,k,v", [4096, 1024, 1024], 4096, [0.5, 0.4, 0.25]),
+    ("llama3 gate,up", [14336, 14336], 4096, [0.5, 0.5]),
+    ("ragged", [288, 96, 32], 1024, [0.0, 0.5, 0.9]),
+    ("single", [1056], 2048, [0.5]),
+    ("three chunks", [544, 288], 12288, [0.5, 1.0]),
+]
+
+
+@pytest.mark.parametrize("name,ns,m,ps", W4_CASES, ids=[c[0] for c in W4_CASES])
+def test_fused_grouped_product_int4_weights(T, name, ns, m, ps):
+    """teal_sparse_gemv_w4_rmsnorm_multi: the oracle's int4 product on the oracle's normalised
+    state, bitwise the normalisation kernel followed by teal_sparse_gemv_w4_multi, exact counts."""
+    h, gamma = ti.norm_inputs(m, 800 + m)
+    hd, gd = dev(h), dev(gamma)
+    x = orc.rmsnorm_f16(h, gamma, EPS)
+    ts = [ti.quantile_threshold(x, p) for p in ps]
+    qs = [ti.quantize_w4(ti.weights_bf16(n, m, seed=5000 * k + n + m), 128) for k, n in enumerate(ns)]
+    qd = [dev(q) for q, _ in qs]
+    sd = [dev(sc) for _, sc in qs]
+    ws = torch.zeros(T.teal_workspace_bytes(m, sum(ns)), dtype=torch.uint8, device="cuda")
+    ys = [torch.full((n,), float("nan"), dtype=torch.float32, device="cuda") for n in ns]
+    T.check(T.teal_sparse_gemv_w4_rmsnorm_multi(qd, sd, 128, ts, ys, ns, hd, gd, EPS, m, ws))
+    torch.cuda.synchronize()
+    off = T.teal_survivors_offset()
+    kept = ws[off:off + 4 * len(ns)].view(torch.int32).cpu().tolist()
+    assert kept == [orc.sparsify(x, t)[3] for t in ts]
+    for k in range(len(ns)):
+        want = orc.sparse_gemv_w4(qs[k][0], qs[k][1], 128, x, ts[k])
+        assert rel_l2(ys[k].cpu().numpy(), want) <= TIGHT, (name, k)
+    xd = torch.empty(m, dtype=torch.int16, device="cuda")
+    T.check(T.teal_rmsnorm_f16(hd, gd, EPS, xd, m))
+    ys2 = [torch.full((n,), float("nan"), dtype=torch.float32, device="cuda") for n in ns]
+    T.check(T.teal_sparse_gemv_w4_multi(qd, sd, 128, ts, ys2, ns, xd, m, ws))
+    torch.cuda.synchronize()
+    for a, b in zip(ys, ys2):
+        assert torch.equal(a, b)

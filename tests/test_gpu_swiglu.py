@@ -166,3 +166,31 @@ def test_fused_product_int8_weights(T, n, m):
         T.check(T.teal_sparse_gemv_w8(qd, sd, hd, t, y2, m, n, ws))
         torch.cuda.synchronize()
         assert np.array_equal(got, y2.cpu().numpy()), p
+
+
+@pytest.mark.parametrize("n,m", [(32, 128), (96, 256), (1056, 2048), (544, 4096), (4096, 14336)])
+def test_fused_product_int4_weights(T, n, m):
+    """teal_sparse_gemv_w4_swiglu: the oracle's int4 product on the oracle's intermediate,
+    bitwise the producer kernel followed by teal_sparse_gemv_w4, exact survivor count."""
+    q, scale = ti.quantize_w4(ti.weights_bf16(n, m, 950 + n + m), 128)
+    qd, sd = dev(q), dev(scale)
+    g, u = ti.mlp_gate_up(m, 19 + m)
+    h = orc.swiglu_f16(g, u)
+    gd, ud = dev(g), dev(u)
+    ws = torch.zeros(T.teal_workspace_bytes(m, n), dtype=torch.uint8, device="cuda")
+    hd = torch.empty(m, dtype=torch.int16, device="cuda")
+    T.check(T.teal_swiglu_f16(gd, ud, hd, m))
+    for p in (0.0, 0.5, 0.9, 1.0):
+        t = ti.quantile_threshold(h, p)
+        y = torch.full((n,), float("nan"), dtype=torch.float32, device="cuda")
+        T.check(T.teal_sparse_gemv_w4_swiglu(qd, sd, 128, gd, ud, t, y, m, n, ws))
+        torch.cuda.synchronize()
+        got = y.cpu().numpy()
+        assert rel_l2(got, orc.sparse_gemv_w4(q, scale, 128, h, t)) <= TIGHT, p
+        off = T.teal_survivors_offset()
+        assert ws[off:off + 4].view(torch.int32).item() == orc.sparsify(h, t)[3], p
+        y2 = torch.full((n,), float("nan"), dtype=torch.float32, device="cuda")
+        T.check(T.teal_sparse_gemv_w4(qd, sd, 128, hd, t, y2, m, n, ws))
+        torch.cuda.synchronize()
+        assert np.array_equal(got, y2.cpu().numpy()), p
+    assert T.teal_sparse_gemv_w4_swiglu(qd, sd, 64, gd, ud, 0.1, y, m, n, ws) == T.TEAL_ERR_UNSUPPORTED
