@@ -1081,11 +1081,15 @@ def main() -> int:
                 per_proj[P.name]["launch"] = T.teal_gemv_plan(BITS[fmt], P.m, P.n)[1]
             per_proj[P.name]["nnz"] = P.nnz[head]
             if fmt == "bf16" and not args.batch:
-                per_proj[P.name]["us_dense_torch_matmul_same_layout"] = \
-                    time_torch_matmul(torch, P, False) * 1e6
-                if args.layers == 1:
-                    per_proj[P.name]["us_dense_torch_matmul_canonical_layout"] = \
-                        time_torch_matmul(torch, P, True) * 1e6
+                # context only: a failure of the vendor path must not cost the run its result
+                try:
+                    per_proj[P.name]["us_dense_torch_matmul_same_layout"] = \
+                        time_torch_matmul(torch, P, False) * 1e6
+                    if args.layers == 1:
+                        per_proj[P.name]["us_dense_torch_matmul_canonical_layout"] = \
+                            time_torch_matmul(torch, P, True) * 1e6
+                except RuntimeError as e:
+                    per_proj[P.name]["us_dense_torch_matmul_error"] = str(e)[:200]
         if groups is not None:
             per_group = alone(groups[:4])
 
