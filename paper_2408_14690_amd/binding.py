@@ -8,6 +8,7 @@ from __future__ import annotations
 
 import ctypes
 import os
+import threading
 
 TEAL_OK = 0
 TEAL_ERR_NULL = 1
@@ -186,15 +187,17 @@ def _stream(stream):
     return stream.cuda_stream
 
 
-_recording = None
+_tls = threading.local()      # .recording: the list prepare() fills on THIS host thread
 
 
 def _call(name, *cargs):
     """Every call that enqueues GPU work goes through here: normally straight into the
-    library; while prepare() records, the marshalled arguments are kept instead."""
+    library; while prepare() records on the calling thread, the marshalled arguments are kept
+    instead.  Calls from other host threads are not affected by a recording."""
     fn = getattr(load_library(), name)
-    if _recording is not None:
-        _recording.append((fn, cargs))
+    recording = getattr(_tls, "recording", None)
+    if recording is not None:
+        recording.append((fn, cargs))
         return TEAL_OK
     return fn(*cargs)
 
@@ -207,15 +210,14 @@ def prepare(enqueue):
     marshalled (host arrays are kept alive by it) and returns the first status that is not
     TEAL_OK, else TEAL_OK.  For decode loops that repeat the same calls on the same
     buffers: the per-call cost of building the argument lists is paid once."""
-    global _recording
-    if _recording is not None:
+    if getattr(_tls, "recording", None) is not None:
         raise RuntimeError("prepare() does not nest")
-    _recording = []
+    _tls.recording = []
     try:
         enqueue()
-        calls = tuple(_recording)
+        calls = tuple(_tls.recording)
     finally:
-        _recording = None
+        _tls.recording = None
     if len(calls) == 1:
         fn, cargs = calls[0]
         return lambda: fn(*cargs)

@@ -151,6 +151,16 @@ teal_status check_gemv(const GemvArgs &a, int n_multiple)
     return TEAL_OK;
 }
 
+// The head of the workspace holds one arrival counter per output tile.  The shapes the
+// library picks itself have tiles of at least kMinTile columns, which always fit; a
+// caller-chosen tile width may not.
+bool tiles_fit_counters(int n, const GemvShape &sh)
+{
+    const int tc = sh.tile_cols > 0 ? sh.tile_cols : sh.lanes_per_row * 8;
+    const long long tiles = ((long long)n + tc - 1) / tc;
+    return tiles <= (long long)(teal::kCounterBytes / sizeof(int));
+}
+
 teal_status from_hip(hipError_t e) { return e == hipSuccess ? TEAL_OK : TEAL_ERR_HIP; }
 
 // Workspace layout: [arrival counters, kCounterBytes][survivor report, report_bytes(m)]
@@ -233,6 +243,7 @@ teal_status teal_sparse_gemv_bf16_ex(const void *Wt_bf16, const void *x_f16, flo
     if (unroll) sh.unroll = unroll;
     if (!teal::gemv_shape_supported(sh)) return TEAL_ERR_UNSUPPORTED;
     if (sh.splits > max_splits_for(m)) return TEAL_ERR_UNSUPPORTED;           // partial rows
+    if (!tiles_fit_counters(n, sh)) return TEAL_ERR_UNSUPPORTED;
     return from_hip(teal::launch_gemv_bf16(Wt_bf16, x_f16, t, y, m, n, ws_partials(workspace, m),
                                            ws_counters(workspace), sh,
                                            static_cast<hipStream_t>(stream)));
@@ -579,6 +590,7 @@ teal_status teal_sparse_gemv_bf16_batch_ex(const void *Wt_bf16, const void *X_f1
     if (splits) sh.splits = splits;
     if (tile_cols) sh.tile_cols = tile_cols;
     if (!teal::gemv_batch_shape_supported(batch, sh)) return TEAL_ERR_UNSUPPORTED;
+    if (!tiles_fit_counters(n, sh)) return TEAL_ERR_UNSUPPORTED;
     const int ks = ((m + sh.splits - 1) / sh.splits + 63) / 64 * 64;
     if (ks > teal::kMaxSliceBatch) return TEAL_ERR_UNSUPPORTED;
     if ((m + ks - 1) / ks > batch_split_rows(m)) return TEAL_ERR_UNSUPPORTED;   // partial rows

@@ -106,6 +106,13 @@ def test_gemv_bf16_ex_rejects_unsupported_shapes():
     # argument errors win over shape errors
     assert T.teal_sparse_gemv_bf16_ex(None, X, 0.5, Y, 4096, 4096, WS, BIG, 0,
                                       lanes_per_row=48) == T.TEAL_ERR_NULL
+    # a caller-chosen tile so narrow that the tiles outnumber the workspace's arrival counters
+    wide = (W, X, 0.5, Y, 64, 1 << 22, WS, BIG, 0)
+    counters = T.teal_survivors_offset() // 4
+    assert (1 << 22) // 8 > counters >= (1 << 22) // 16
+    assert T.teal_sparse_gemv_bf16_ex(*wide, lanes_per_row=8, tile_cols=8) == T.TEAL_ERR_UNSUPPORTED
+    assert T.teal_sparse_gemv_bf16_batch_ex(W, X, 2, 0.5, Y, 64, 1 << 22, WS, BIG, 0,
+                                            lanes_per_row=16, tile_cols=8) == T.TEAL_ERR_UNSUPPORTED
 
 
 def test_quantised_argument_errors():
@@ -639,3 +646,27 @@ def test_prepared_calls_marshal_once():
         T.prepare(lambda: T.prepare(lambda: None))
     # and the module is back to calling straight through
     assert T.teal_sparse_gemv_bf16(W, X, -1.0, Y, 4096, 4096, WS, BIG, stream=0) == T.TEAL_ERR_THRESHOLD
+
+
+def test_a_recording_does_not_swallow_other_threads_calls():
+    """While one host thread records with prepare(), a call made by another thread goes
+    straight to the library (and here comes back with the host check's status)."""
+    import threading
+    entered, release, seen = threading.Event(), threading.Event(), []
+
+    def slow_enqueue():
+        T.teal_sparse_gemv_bf16(W, X, -1.0, Y, 4096, 4096, WS, BIG, stream=0)
+        entered.set()
+        release.wait(10)
+
+    def other():
+        entered.wait(10)
+        seen.append(T.teal_sparse_gemv_bf16(W, X, -1.0, Y, 4096, 4096, WS, BIG, stream=0))
+        release.set()
+
+    th = threading.Thread(target=other)
+    th.start()
+    run = T.prepare(slow_enqueue)
+    th.join()
+    assert seen == [T.TEAL_ERR_THRESHOLD]                 # executed, not recorded
+    assert run() == T.TEAL_ERR_THRESHOLD                  # only the recording thread's call
