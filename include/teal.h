@@ -58,7 +58,8 @@ typedef enum teal_status {
     TEAL_ERR_THRESHOLD = 4,   /* t (or eps) is negative, NaN or infinite; a level p is outside [0, 1] */
     TEAL_ERR_WORKSPACE = 5,   /* workspace too small */
     TEAL_ERR_UNSUPPORTED = 6, /* group size or launch parameters not supported */
-    TEAL_ERR_HIP = 7          /* the HIP runtime reported an error at launch */
+    TEAL_ERR_HIP = 7,         /* the HIP runtime reported an error at launch */
+    TEAL_ERR_STATIC_LIMIT = 8 /* m or n beyond teal_static_scratch_limit() (static-scratch call) */
 } teal_status;
 
 /* Static, NUL-terminated description of a status (host memory, never freed). */
@@ -114,6 +115,36 @@ teal_status teal_sparse_gemv_bf16(const void *Wt_bf16, const void *x_f16, float 
                                   float *y, int m, int n,
                                   void *workspace, size_t workspace_bytes,
                                   void *stream);
+
+/*
+ * teal_sparse_gemv_bf16 for callers that cannot allocate device memory and so
+ * have no workspace to hand over: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  The split-K scratch (arrival
+ * counters, survivor report, fp32 partial rows) lives in an array of the
+ * library's own, a file-scope device array of about 5.3 MB that every GPU the
+ * library is used on holds until the process ends; the call itself calls no
+ * hipMalloc, hipFree or other allocating routine, and no memset.  The device
+ * address of the array is looked up once per device and kept: by
+ * teal_static_scratch_init() (no arguments; the device to set up must be
+ * current; TEAL_OK or TEAL_ERR_HIP), which a caller that captures graphs
+ * calls before the capture, else by the device's first
+ * teal_sparse_gemv_bf16_static call.
+ *   Arguments, checks, launch shape and result as for teal_sparse_gemv_bf16
+ *   (y is bitwise the same), except: m and n at most
+ *   teal_static_scratch_limit() = 65536, beyond which the call returns
+ *   TEAL_ERR_STATIC_LIMIT and does nothing.
+ *   All calls on one GPU share that GPU's array: calls that may overlap in
+ *   time on one GPU (different streams, different host threads) race on it and
+ *   are NOT allowed; calls on one stream run in order and are fine.  The array
+ *   keeps the last call's contents; what must be zero at the start of a call
+ *   (one arrival counter per output tile) is left at zero by the call before
+ *   it, and nothing else is read before it is written.  The survivor count of
+ *   the call is not available to the caller.
+ */
+size_t teal_static_scratch_limit(void);
+teal_status teal_static_scratch_init(void);
+teal_status teal_sparse_gemv_bf16_static(const void *Wt_bf16, const void *x_f16, float t,
+                                         float *y, int m, int n, void *stream);
 
 /*
  * Several matrices that read the same hidden state, in one kernel launch:

@@ -7,7 +7,7 @@ raises.
 """
 from .binding import (  # noqa: F401
     TEAL_OK, TEAL_ERR_NULL, TEAL_ERR_SHAPE, TEAL_ERR_ALIGN, TEAL_ERR_THRESHOLD,
-    TEAL_ERR_WORKSPACE, TEAL_ERR_UNSUPPORTED, TEAL_ERR_HIP,
+    TEAL_ERR_WORKSPACE, TEAL_ERR_UNSUPPORTED, TEAL_ERR_HIP, TEAL_ERR_STATIC_LIMIT,
     TealError, check, library_path, load_library, prepare,
     teal_status_string, teal_version, teal_workspace_bytes,
     teal_sparsify, teal_sparse_gemv_bf16, teal_sparse_gemv_bf16_ex,
@@ -21,4 +21,5 @@ from .binding import (  # noqa: F401
     teal_sparse_gemv_bf16_stack, teal_sparse_gemv_w8_stack, teal_sparse_gemv_w4_stack,
     teal_stream_read_probe, teal_sparse_gemv_w8_swiglu, teal_sparse_gemv_w8_rmsnorm_multi,
     teal_sparse_gemv_w4_swiglu, teal_sparse_gemv_w4_rmsnorm_multi,
+    teal_static_scratch_limit, teal_static_scratch_init, teal_sparse_gemv_bf16_static,
 )

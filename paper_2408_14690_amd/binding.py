@@ -18,6 +18,7 @@ TEAL_ERR_THRESHOLD = 4
 TEAL_ERR_WORKSPACE = 5
 TEAL_ERR_UNSUPPORTED = 6
 TEAL_ERR_HIP = 7
+TEAL_ERR_STATIC_LIMIT = 8
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libteal.so")
@@ -36,6 +37,7 @@ EXPORTS = (
     "teal_sparse_gemv_bf16_stack", "teal_sparse_gemv_w8_stack", "teal_sparse_gemv_w4_stack",
     "teal_stream_read_probe", "teal_sparse_gemv_w8_swiglu", "teal_sparse_gemv_w8_rmsnorm_multi",
     "teal_sparse_gemv_w4_swiglu", "teal_sparse_gemv_w4_rmsnorm_multi",
+    "teal_static_scratch_limit", "teal_static_scratch_init", "teal_sparse_gemv_bf16_static",
 )
 TEAL_HIST_BINS = 32768
 TEAL_MAX_BATCH = 8
@@ -80,6 +82,12 @@ def load_library():
     lib.teal_sparsify.argtypes = [vp, i, f, vp, vp, vp, vp]
     lib.teal_sparse_gemv_bf16.restype = i
     lib.teal_sparse_gemv_bf16.argtypes = [vp, vp, f, vp, i, i, vp, sz, vp]
+    lib.teal_static_scratch_limit.restype = sz
+    lib.teal_static_scratch_limit.argtypes = []
+    lib.teal_static_scratch_init.restype = i
+    lib.teal_static_scratch_init.argtypes = []
+    lib.teal_sparse_gemv_bf16_static.restype = i
+    lib.teal_sparse_gemv_bf16_static.argtypes = [vp, vp, f, vp, i, i, vp]
     lib.teal_sparse_gemv_bf16_ex.restype = i
     lib.teal_sparse_gemv_bf16_ex.argtypes = [vp, vp, f, vp, i, i, vp, sz, vp, i, i, i, i, i]
     lib.teal_sparse_gemv_w8.restype = i
@@ -265,6 +273,21 @@ def teal_sparse_gemv_bf16(Wt_bf16, x_f16, t, y, m, n, workspace, workspace_bytes
         _ptr(Wt_bf16, 2 * m * n, "Wt"), _ptr(x_f16, 2 * m, "x"), float(t), _ptr(y, 4 * n, "y"),
         int(m), int(n), _ptr(workspace),
         _nbytes(workspace, workspace_bytes), _stream(stream))
+
+
+def teal_static_scratch_limit() -> int:
+    return int(load_library().teal_static_scratch_limit())
+
+
+def teal_static_scratch_init() -> int:
+    return int(load_library().teal_static_scratch_init())
+
+
+def teal_sparse_gemv_bf16_static(Wt_bf16, x_f16, t, y, m, n, stream=None) -> int:
+    return _call(
+        "teal_sparse_gemv_bf16_static",
+        _ptr(Wt_bf16, 2 * m * n, "Wt"), _ptr(x_f16, 2 * m, "x"), float(t), _ptr(y, 4 * n, "y"),
+        int(m), int(n), _stream(stream))
 
 
 def teal_sparse_gemv_bf16_ex(Wt_bf16, x_f16, t, y, m, n, workspace, workspace_bytes=None,

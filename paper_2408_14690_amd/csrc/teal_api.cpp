@@ -1,8 +1,10 @@
 // C ABI of the library (include/teal.h): argument checks on the host, choice
-// of the launch shape, then the kernel launches.  Nothing here allocates,
-// synchronises or keeps state.
+// of the launch shape, then the kernel launches.  Nothing here allocates or
+// synchronises; the only state kept is the per-device address of the
+// library's own scratch array (teal_sparse_gemv_bf16_static).
 #include "teal.h"
 
+#include <atomic>
 #include <cmath>
 
 #include "teal_internal.h"
@@ -181,6 +183,49 @@ float *ws_partials(void *workspace, int m)
                                      teal::kCounterBytes + report_bytes(m));
 }
 
+// ---- the library's own scratch, for teal_sparse_gemv_bf16_static ----
+//
+// One array per GPU the library runs on, held until the process ends, laid out like a
+// caller's workspace for the largest call the entry point takes: [arrival counters]
+// [survivor report][kStaticRows partial rows of kStaticMaxDim floats].  Zero at load; every
+// call leaves the counters at zero again (the block that finishes a tile last resets the
+// tile's counter), and the report and the partial rows are written before they are read, so
+// the contents a call finds from the call before it never reach a result.
+constexpr int kStaticMaxDim = 65536;           // largest m and n of a static-scratch call
+constexpr int kStaticRows = 16;                // most splits the library picks for m <= kStaticMaxDim
+constexpr size_t kStaticReportBytes =
+    ((teal::kReportHeaderInts + (size_t)teal::kMaxMatrices * teal::kMaxSplits) * sizeof(int) +
+     kAlignWorkspace - 1) / kAlignWorkspace * kAlignWorkspace;
+constexpr size_t kStaticScratchBytes =
+    teal::kCounterBytes + kStaticReportBytes + (size_t)kStaticRows * kStaticMaxDim * sizeof(float);
+
+// `used`: no kernel of this file names the array, and it must still be emitted and registered
+static __device__ __align__(256) __attribute__((used)) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::atomic<void *> g_scratch_ptr[kMaxDevices];
+
+// Device address of `scratch` on the current device.  In host code the array's name is only a
+// handle for this lookup; the address is what kernels and copies must be given.  Looked up on
+// a device's first call (that device current), then kept; concurrent first calls look it up
+// twice and store the same value.
+hipError_t static_scratch(void **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+    *out = p;
+    return hipSuccess;
+}
+
 }  // namespace
 
 extern "C" {
@@ -196,6 +241,7 @@ const char *teal_status_string(teal_status s)
     case TEAL_ERR_WORKSPACE: return "workspace too small";
     case TEAL_ERR_UNSUPPORTED: return "unsupported group size or launch shape";
     case TEAL_ERR_HIP: return "HIP runtime error at launch";
+    case TEAL_ERR_STATIC_LIMIT: return "m or n beyond what the library's static scratch holds";
     }
     return "unknown status";
 }
@@ -299,6 +345,35 @@ teal_status teal_sparse_gemv_bf16(const void *Wt_bf16, const void *x_f16, float 
 {
     return teal_sparse_gemv_bf16_ex(Wt_bf16, x_f16, t, y, m, n, workspace, workspace_bytes,
                                     stream, 0, 0, 0, 0, 0);
+}
+
+size_t teal_static_scratch_limit(void) { return (size_t)kStaticMaxDim; }
+
+teal_status teal_static_scratch_init(void)
+{
+    void *base = nullptr;
+    return from_hip(static_scratch(&base));
+}
+
+teal_status teal_sparse_gemv_bf16_static(const void *Wt_bf16, const void *x_f16, float t, float *y,
+                                         int m, int n, void *stream)
+{
+    // the checks of teal_sparse_gemv_bf16, in its order, without those of a workspace
+    if (!Wt_bf16 || !x_f16 || !y) return TEAL_ERR_NULL;
+    if (m < 1 || m > teal::kMaxDim || n < 8 || n > teal::kMaxDim || n % 8 != 0)
+        return TEAL_ERR_SHAPE;
+    if (m > kStaticMaxDim || n > kStaticMaxDim) return TEAL_ERR_STATIC_LIMIT;
+    if (!aligned(Wt_bf16, 16) || !aligned(x_f16, 2) || !aligned(y, 4)) return TEAL_ERR_ALIGN;
+    if (!threshold_ok(t)) return TEAL_ERR_THRESHOLD;
+    const GemvShape sh = auto_shape(m, n, 8, 16, 64, 64);      // as teal_sparse_gemv_bf16 picks
+    if (sh.splits > kStaticRows) return TEAL_ERR_STATIC_LIMIT;  // cannot happen within the limit
+    void *base = nullptr;
+    if (static_scratch(&base) != hipSuccess) return TEAL_ERR_HIP;
+    float *partial = reinterpret_cast<float *>(static_cast<unsigned char *>(base) +
+                                               teal::kCounterBytes + kStaticReportBytes);
+    return from_hip(teal::launch_gemv_bf16(Wt_bf16, x_f16, t, y, m, n, partial,
+                                           static_cast<int *>(base), sh,
+                                           static_cast<hipStream_t>(stream)));
 }
 
 teal_status teal_sparse_gemv_bf16_batch_multi(int count, const void *const *Wt_bf16,

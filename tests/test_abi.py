@@ -46,7 +46,7 @@ def test_every_declared_symbol_is_exported():
 def test_version_and_status_strings():
     assert T.teal_version() >= 100
     seen = set()
-    for code in range(8):
+    for code in range(9):
         s = T.teal_status_string(code)
         assert s and s not in seen
         seen.add(s)
@@ -113,6 +113,33 @@ def test_gemv_bf16_ex_rejects_unsupported_shapes():
     assert T.teal_sparse_gemv_bf16_ex(*wide, lanes_per_row=8, tile_cols=8) == T.TEAL_ERR_UNSUPPORTED
     assert T.teal_sparse_gemv_bf16_batch_ex(W, X, 2, 0.5, Y, 64, 1 << 22, WS, BIG, 0,
                                             lanes_per_row=16, tile_cols=8) == T.TEAL_ERR_UNSUPPORTED
+
+
+def test_static_scratch_call_argument_errors():
+    """The entry point whose scratch is the library's own array: the host checks of
+    teal_sparse_gemv_bf16 without those of a workspace, plus its size limit."""
+    lim = T.teal_static_scratch_limit()
+    assert lim == 65536
+    ok = dict(Wt_bf16=W, x_f16=X, t=0.5, y=Y, m=4096, n=4096, stream=0)
+
+    def call(**kw):
+        a = dict(ok)
+        a.update(kw)
+        return T.teal_sparse_gemv_bf16_static(**a)
+
+    assert call(Wt_bf16=None) == T.TEAL_ERR_NULL
+    assert call(x_f16=None) == T.TEAL_ERR_NULL
+    assert call(y=None) == T.TEAL_ERR_NULL
+    assert call(n=4100) == T.TEAL_ERR_SHAPE
+    assert call(m=0) == T.TEAL_ERR_SHAPE
+    assert call(m=lim + 1) == T.TEAL_ERR_STATIC_LIMIT
+    assert call(n=lim + 8) == T.TEAL_ERR_STATIC_LIMIT
+    assert call(m=(1 << 24) + 1) == T.TEAL_ERR_SHAPE
+    assert call(Wt_bf16=W + 8) == T.TEAL_ERR_ALIGN
+    assert call(y=Y + 2) == T.TEAL_ERR_ALIGN
+    assert call(t=-1.0) == T.TEAL_ERR_THRESHOLD
+    assert call(t=math.inf) == T.TEAL_ERR_THRESHOLD
+    assert "static scratch" in T.teal_status_string(T.TEAL_ERR_STATIC_LIMIT)
 
 
 def test_quantised_argument_errors():
