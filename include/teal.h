@@ -375,6 +375,97 @@ teal_status teal_sparse_gemv_w4_multi(int count, const uint8_t *const *Wq,
                                       void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The MLP of a Transformer block in ONE kernel launch (Appendix A.3):
+ *     MLP(x) = (SiLU(x W_gate^T) . x W_up^T) W_down^T,
+ * with every product thresholded (Section 4.2): gate = s_{t_gate}(x) W_gate^T,
+ * up = s_{t_up}(x) W_up^T, h = fp16(SiLU(gate) * up) in the arithmetic stated for
+ * teal_sparse_gemv_bf16_swiglu, y = s_{t_down}(h) W_down^T.  The results (gate,
+ * up and y) are bitwise those of teal_sparse_gemv_bf16_multi on (W_gate, W_up)
+ * followed by teal_sparse_gemv_bf16_swiglu on W_down, run with the same launch
+ * shapes (which is what the library picks when `shape` is NULL).  The thread
+ * blocks of the W_down product follow those of gate and up in the same grid and
+ * each waits only for the gate / up output tiles that cover its own slice of h,
+ * so nothing separates the dependent products but those waits.
+ *   Wt_gate, Wt_up [m][f] bf16, Wt_down [f][d] bf16, input-channel-major,
+ *           16-byte aligned.  m = model width, f = MLP width, d = output width.
+ *   x_f16   [m] fp16.
+ *   gate, up [f] fp32: written by the call (the intermediates; they must not
+ *           overlap anything else the call reads or writes), y [d] fp32.
+ *   1 <= m <= 2^24, 8 <= f <= 2^23, 8 <= d <= 2^24, f % 8 == 0, d % 8 == 0
+ *   (16 for int8, 32 for int4 weights).
+ *   workspace  at least teal_workspace_bytes_mlp(m, f, d) bytes, zero before
+ *           first use like every workspace: the workspace of the gate + up
+ *           call (survivor counts of gate and up at teal_survivors_offset()),
+ *           that of the W_down call at byte teal_mlp_down_region_offset(m, f)
+ *           (its survivor count teal_survivors_offset() bytes further), then
+ *           the readiness counters and a status word.
+ *   shape   HOST pointer, read during the call; NULL = the library's choice
+ *           (teal_mlp_plan).  For tuning and tests: lanes per row, tile width
+ *           and split count of the gate / up products and of the W_down
+ *           product as for teal_sparse_gemv_bf16_ex (8 wavefronts, 4 loads per
+ *           batch); gu_phase_tiles > 0 orders the gate / up blocks in phases
+ *           of that many output tiles of each matrix, so that the first
+ *           columns of gate and up are finished first (0 = one phase);
+ *           extra_lds_bytes (0..49152) of unused shared memory per block lower
+ *           the number of blocks resident per compute unit; spin_limit is the
+ *           number of polls after which a waiting block gives up.
+ * Waits are bounded.  A block of W_down that does not see its inputs within
+ * spin_limit polls stores 1 to the int32 status word at byte
+ * teal_mlp_status_offset(m, f, d) of the workspace and leaves, and so does
+ * every block that then finds the word set: the kernel always ends.  A caller
+ * that wants the guarantee reads the word after synchronising; when it is not
+ * zero, gate / up / y are invalid and the workspace must be zero-filled again.
+ * With thread blocks dispatched in index order (every producer precedes its
+ * consumers in the grid, and producers never wait) no wait can expire.
+ *
+ * teal_sparse_mlp_w8 / teal_sparse_mlp_w4: the same for the quantised formats
+ * (Section 5.3), matrices and scales as for teal_sparse_gemv_w8 /
+ * teal_sparse_gemv_w4 (int4: group == 128, m % 128 == 0, f % 128 == 0), bitwise
+ * the format's grouped call followed by its _swiglu call.
+ *
+ * teal_mlp_plan: the shape the library picks (HOST pointer out).
+ * teal_mlp_block_info: host-only description of thread block `block` of the
+ * launch a shape gives, for checking the schedule without a GPU.  info is a
+ * HOST array of 8 ints: [0] blocks in the grid (always set; the rest is -1 when
+ * `block` is out of range), [1] 0 = gate, 1 = up, 2 = down, [2] output tile,
+ * [3] K-slice; for a gate / up block [4], [5] = the columns [c0, c1) of its
+ * tile and [6], [7] = the first and last K-slice of W_down told when the tile
+ * is finished; for a block of W_down [4], [5] = the input channels [k0, k1) of
+ * its slice, [6] = its K-slice and [7] = the number of gate and up tiles it
+ * waits for.
+ */
+typedef struct teal_mlp_shape {
+    int gu_lanes_per_row, gu_tile_cols, gu_splits, gu_phase_tiles;
+    int down_lanes_per_row, down_tile_cols, down_splits;
+    int extra_lds_bytes;
+    int spin_limit;
+} teal_mlp_shape;
+size_t teal_workspace_bytes_mlp(int m, int f, int d);
+size_t teal_mlp_down_region_offset(int m, int f);
+size_t teal_mlp_status_offset(int m, int f, int d);
+teal_status teal_mlp_plan(int weight_bits, int m, int f, int d, teal_mlp_shape *shape);
+teal_status teal_mlp_block_info(int weight_bits, int m, int f, int d, const teal_mlp_shape *shape,
+                                int block, int *info);
+teal_status teal_sparse_mlp_bf16(const void *Wt_gate, const void *Wt_up, const void *Wt_down,
+                                 const void *x_f16, float t_gate, float t_up, float t_down,
+                                 float *gate, float *up, float *y, int m, int f, int d,
+                                 void *workspace, size_t workspace_bytes, void *stream,
+                                 const teal_mlp_shape *shape);
+teal_status teal_sparse_mlp_w8(const int8_t *Wq_gate, const int8_t *Wq_up, const int8_t *Wq_down,
+                               const void *scale_gate, const void *scale_up,
+                               const void *scale_down, const void *x_f16, float t_gate,
+                               float t_up, float t_down, float *gate, float *up, float *y, int m,
+                               int f, int d, void *workspace, size_t workspace_bytes,
+                               void *stream, const teal_mlp_shape *shape);
+teal_status teal_sparse_mlp_w4(const uint8_t *Wq_gate, const uint8_t *Wq_up,
+                               const uint8_t *Wq_down, const void *scale_gate,
+                               const void *scale_up, const void *scale_down, int group,
+                               const void *x_f16, float t_gate, float t_up, float t_down,
+                               float *gate, float *up, float *y, int m, int f, int d,
+                               void *workspace, size_t workspace_bytes, void *stream,
+                               const teal_mlp_shape *shape);
+
+/*
  * One-time layout step (Sections 3 and 4.4: weights used under input sparsity
  * must be stored channel-contiguous): canonical row-major W[n][m] bf16 ->
  * Wt[m][n].  Device to device, out of place; both 2-byte aligned; any m, n >= 1.

@@ -38,9 +38,22 @@ EXPORTS = (
     "teal_stream_read_probe", "teal_sparse_gemv_w8_swiglu", "teal_sparse_gemv_w8_rmsnorm_multi",
     "teal_sparse_gemv_w4_swiglu", "teal_sparse_gemv_w4_rmsnorm_multi",
     "teal_static_scratch_limit", "teal_static_scratch_init", "teal_sparse_gemv_bf16_static",
+    "teal_workspace_bytes_mlp", "teal_mlp_down_region_offset", "teal_mlp_status_offset",
+    "teal_mlp_plan", "teal_mlp_block_info", "teal_sparse_mlp_bf16", "teal_sparse_mlp_w8",
+    "teal_sparse_mlp_w4",
 )
 TEAL_HIST_BINS = 32768
 TEAL_MAX_BATCH = 8
+
+
+class MlpShape(ctypes.Structure):
+    """teal_mlp_shape of include/teal.h."""
+    _fields_ = [(name, ctypes.c_int) for name in (
+        "gu_lanes_per_row", "gu_tile_cols", "gu_splits", "gu_phase_tiles",
+        "down_lanes_per_row", "down_tile_cols", "down_splits", "extra_lds_bytes", "spin_limit")]
+
+    def as_dict(self):
+        return {name: getattr(self, name) for name, _ in self._fields_}
 
 
 class TealError(RuntimeError):
@@ -152,6 +165,25 @@ def load_library():
     lib.teal_sparse_gemv_bf16_batch.argtypes = [vp, vp, i, f, vp, i, i, vp, sz, vp]
     lib.teal_sparse_gemv_bf16_batch_ex.restype = i
     lib.teal_sparse_gemv_bf16_batch_ex.argtypes = [vp, vp, i, f, vp, i, i, vp, sz, vp, i, i, i]
+    shp = c.POINTER(MlpShape)
+    lib.teal_workspace_bytes_mlp.restype = sz
+    lib.teal_workspace_bytes_mlp.argtypes = [i, i, i]
+    lib.teal_mlp_down_region_offset.restype = sz
+    lib.teal_mlp_down_region_offset.argtypes = [i, i]
+    lib.teal_mlp_status_offset.restype = sz
+    lib.teal_mlp_status_offset.argtypes = [i, i, i]
+    lib.teal_mlp_plan.restype = i
+    lib.teal_mlp_plan.argtypes = [i, i, i, i, shp]
+    lib.teal_mlp_block_info.restype = i
+    lib.teal_mlp_block_info.argtypes = [i, i, i, i, shp, i, c.POINTER(c.c_int)]
+    lib.teal_sparse_mlp_bf16.restype = i
+    lib.teal_sparse_mlp_bf16.argtypes = [vp, vp, vp, vp, f, f, f, vp, vp, vp, i, i, i, vp, sz, vp, shp]
+    lib.teal_sparse_mlp_w8.restype = i
+    lib.teal_sparse_mlp_w8.argtypes = [vp, vp, vp, vp, vp, vp, vp, f, f, f, vp, vp, vp, i, i, i, vp,
+                                       sz, vp, shp]
+    lib.teal_sparse_mlp_w4.restype = i
+    lib.teal_sparse_mlp_w4.argtypes = [vp, vp, vp, vp, vp, vp, i, vp, f, f, f, vp, vp, vp, i, i, i,
+                                       vp, sz, vp, shp]
     ip = c.POINTER(c.c_int)
     lib.teal_gemv_plan.restype = i
     lib.teal_gemv_plan.argtypes = [i, i, i, ip, ip, ip, ip, ip]
@@ -620,3 +652,81 @@ def teal_histogram_thresholds(hist, p_list, t, stream=None) -> int:
     P = (ctypes.c_double * max(np_, 1))(*[float(p) for p in p_list])
     return _call("teal_histogram_thresholds", _ptr(hist, 8 * TEAL_HIST_BINS, "hist"), P, np_,
                                                     _ptr(t, 4 * np_, "t"), _stream(stream))
+
+
+def teal_workspace_bytes_mlp(m: int, f: int, d: int) -> int:
+    return int(load_library().teal_workspace_bytes_mlp(int(m), int(f), int(d)))
+
+
+def teal_mlp_down_region_offset(m: int, f: int) -> int:
+    return int(load_library().teal_mlp_down_region_offset(int(m), int(f)))
+
+
+def teal_mlp_status_offset(m: int, f: int, d: int) -> int:
+    return int(load_library().teal_mlp_status_offset(int(m), int(f), int(d)))
+
+
+def _mlp_shape(shape):
+    """None, an MlpShape, or a dict of its fields (missing fields are zero)."""
+    if shape is None or isinstance(shape, MlpShape):
+        return shape
+    return MlpShape(**{k: int(v) for k, v in dict(shape).items()})
+
+
+def teal_mlp_plan(weight_bits: int, m: int, f: int, d: int):
+    """Returns (status, MlpShape): the launch shape the library picks."""
+    sh = MlpShape()
+    st = load_library().teal_mlp_plan(int(weight_bits), int(m), int(f), int(d), ctypes.byref(sh))
+    return st, sh
+
+
+def teal_mlp_block_info(weight_bits: int, m: int, f: int, d: int, shape, block: int):
+    """Returns (status, list of the 8 ints teal.h describes)."""
+    sh = _mlp_shape(shape)
+    info = (ctypes.c_int * 8)()
+    st = load_library().teal_mlp_block_info(int(weight_bits), int(m), int(f), int(d),
+                                            ctypes.byref(sh) if sh is not None else None,
+                                            int(block), info)
+    return st, list(info)
+
+
+def teal_sparse_mlp_bf16(Wt_gate, Wt_up, Wt_down, x_f16, t_gate, t_up, t_down, gate, up, y, m, f, d,
+                         workspace, workspace_bytes=None, stream=None, shape=None) -> int:
+    sh = _mlp_shape(shape)
+    return _call(
+        "teal_sparse_mlp_bf16",
+        _ptr(Wt_gate, 2 * m * f, "Wt_gate"), _ptr(Wt_up, 2 * m * f, "Wt_up"),
+        _ptr(Wt_down, 2 * f * d, "Wt_down"), _ptr(x_f16, 2 * m, "x"), float(t_gate), float(t_up),
+        float(t_down), _ptr(gate, 4 * f, "gate"), _ptr(up, 4 * f, "up"), _ptr(y, 4 * d, "y"),
+        int(m), int(f), int(d), _ptr(workspace), _nbytes(workspace, workspace_bytes),
+        _stream(stream), ctypes.pointer(sh) if sh is not None else None)
+
+
+def teal_sparse_mlp_w8(Wq_gate, Wq_up, Wq_down, scale_gate, scale_up, scale_down, x_f16, t_gate,
+                       t_up, t_down, gate, up, y, m, f, d, workspace, workspace_bytes=None,
+                       stream=None, shape=None) -> int:
+    sh = _mlp_shape(shape)
+    return _call(
+        "teal_sparse_mlp_w8",
+        _ptr(Wq_gate, m * f, "Wq_gate"), _ptr(Wq_up, m * f, "Wq_up"), _ptr(Wq_down, f * d, "Wq_down"),
+        _ptr(scale_gate, 2 * f, "scale_gate"), _ptr(scale_up, 2 * f, "scale_up"),
+        _ptr(scale_down, 2 * d, "scale_down"), _ptr(x_f16, 2 * m, "x"), float(t_gate), float(t_up),
+        float(t_down), _ptr(gate, 4 * f, "gate"), _ptr(up, 4 * f, "up"), _ptr(y, 4 * d, "y"),
+        int(m), int(f), int(d), _ptr(workspace), _nbytes(workspace, workspace_bytes),
+        _stream(stream), ctypes.pointer(sh) if sh is not None else None)
+
+
+def teal_sparse_mlp_w4(Wq_gate, Wq_up, Wq_down, scale_gate, scale_up, scale_down, group, x_f16,
+                       t_gate, t_up, t_down, gate, up, y, m, f, d, workspace, workspace_bytes=None,
+                       stream=None, shape=None) -> int:
+    sh = _mlp_shape(shape)
+    g = max(int(group), 1)
+    return _call(
+        "teal_sparse_mlp_w4",
+        _ptr(Wq_gate, m * f // 2, "Wq_gate"), _ptr(Wq_up, m * f // 2, "Wq_up"),
+        _ptr(Wq_down, f * d // 2, "Wq_down"), _ptr(scale_gate, 2 * f * (m // g), "scale_gate"),
+        _ptr(scale_up, 2 * f * (m // g), "scale_up"), _ptr(scale_down, 2 * d * (f // g), "scale_down"),
+        int(group), _ptr(x_f16, 2 * m, "x"), float(t_gate), float(t_up), float(t_down),
+        _ptr(gate, 4 * f, "gate"), _ptr(up, 4 * f, "up"), _ptr(y, 4 * d, "y"),
+        int(m), int(f), int(d), _ptr(workspace), _nbytes(workspace, workspace_bytes),
+        _stream(stream), ctypes.pointer(sh) if sh is not None else None)

@@ -1,6 +1,7 @@
 // y = s_t(x) W^T for bf16 weights stored input-channel-major (Sections 3, 4.2, 4.4).
 #include "gemv_common.h"
 #include "gemv_dispatch.h"
+#include "gemv_mlp.h"
 
 namespace teal {
 
@@ -139,6 +140,27 @@ hipError_t launch_gemv_bf16_rmsnorm_multi(int count, const void *const *Wt, cons
     else TEAL_LAUNCH_N(16);
 #undef TEAL_LAUNCH_N
     return hipGetLastError();
+}
+
+bool mlp_grid_of(int weight_bits, const MlpLaunch &L, int m, int f, int d, MlpGrid &grid)
+{
+    GemvGeometry ggu, gd;
+    const int epl = weight_bits == 16 ? 8 : weight_bits == 8 ? 16 : 32;
+    if (weight_bits != 16 && weight_bits != 8 && weight_bits != 4) return false;
+    if (!mlp_shape_ok(L.gu, epl) || !mlp_shape_ok(L.down, epl)) return false;
+    return mlp_grid(grid, ggu, gd, L, m, f, d, epl, weight_bits == 4 ? 128 : 64);
+}
+
+hipError_t launch_mlp_bf16(const MlpHostArgs &h, const MlpLaunch &L, hipStream_t stream)
+{
+    if (!mlp_shape_ok(L.gu, 8) || !mlp_shape_ok(L.down, 8)) return hipErrorInvalidValue;
+    MlpArgs<FmtBF16> A{};
+    size_t lds;
+    if (!fill_mlp_args<FmtBF16>(A, lds, h, L, 64,
+                                [](FmtBF16::Args &a, const void *W, const void *) { a.W = W; }))
+        return hipErrorInvalidValue;
+    return launch_mlp_kernel<GemvBody<FmtBF16>, false>(A, L.gu.lanes_per_row,
+                                                       L.down.lanes_per_row, lds, stream);
 }
 
 }  // namespace teal

@@ -568,8 +568,9 @@ __device__ __forceinline__ void store_wave_sums(const float (&acc)[N], float *ds
 // in a fixed order (results do not depend on which block is last) and writes
 // y.  The split-K combine of Section 4.4, without atomics on y and without a
 // second launch.  The tile is columns [col0, col0 + cols) of y, cols <= TN.
+// Returns (block-uniform) whether this block wrote the tile's outputs.
 template <class F, int LPR, int WAVES>
-__device__ __forceinline__ void block_finish(float *red,
+__device__ __forceinline__ bool block_finish(float *red,
                                              float *partial, int *counters, float *y, int tile,
                                              int col0, int cols, int s, int splits, int n,
                                              const typename F::Args &a, int cnt,
@@ -602,7 +603,7 @@ __device__ __forceinline__ void block_finish(float *red,
                 store_coherent(y + col0 + c, F::finish(sum, scale[k]));
             }
         }
-        return;
+        return true;
     }
 
     // The 8 XCDs have separate L2s.  A device-wide fence would write back and
@@ -621,7 +622,7 @@ __device__ __forceinline__ void block_finish(float *red,
     __syncthreads();
     if (threadIdx.x == 0) last_flag = atomicAdd(&counters[tile], 1) == splits - 1;
     __syncthreads();
-    if (!last_flag) return;
+    if (!last_flag) return false;
     if (tile == 0 && w == 0) report_total(report, splits);
 
     // Second pass.  A thread owns a column and adds its partial rows in split order (a fixed
@@ -648,6 +649,7 @@ __device__ __forceinline__ void block_finish(float *red,
     }
     // Leave the counter at zero for the next call on this workspace.
     if (threadIdx.x == 0) atomicExch(&counters[tile], 0);
+    return true;
 }
 
 // This lane's first column: lane l of a row group covers EPL columns starting at
@@ -666,8 +668,9 @@ __device__ __forceinline__ int lane_column(int col0, int cols, int n, int l)
 
 // Work of one block for formats with no per-group state (bf16, int8): output
 // tile `tile` (tile_cols columns) x K-slice `s` (ks channels) of one matrix.
+// Returns (block-uniform) whether this block wrote the tile's outputs.
 template <class F, int LPR, int WAVES, int U, class XS>
-__device__ __forceinline__ void gemv_block(const typename F::Args &a, const XS &x,
+__device__ __forceinline__ bool gemv_block(const typename F::Args &a, const XS &x,
                                            float t, float *partial, int *counters, float *y, int m,
                                            int n, int ks, int tile, int s, int tile_cols,
                                            int splits, const SurvivorReport &report)
@@ -708,8 +711,8 @@ __device__ __forceinline__ void gemv_block(const typename F::Args &a, const XS &
     for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
     stream_rows<F, LPR, U>(acc, list, start, mine, lane_base, row_bytes);
     store_wave_sums<LPR>(acc, red + (threadIdx.x >> 6) * combine_row<EPL, LPR>);
-    block_finish<F, LPR, WAVES>(red, partial, counters, y, tile, col0, tile_cols, s, splits, n,
-                                a, cnt, report);
+    return block_finish<F, LPR, WAVES>(red, partial, counters, y, tile, col0, tile_cols, s, splits,
+                                       n, a, cnt, report);
 }
 
 // One matrix per launch.  Grid: tiles * splits blocks; block id -> (tile,

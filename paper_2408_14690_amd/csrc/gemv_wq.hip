@@ -5,6 +5,7 @@
 // Dequantisation happens in registers; only surviving rows are read.
 #include "gemv_common.h"
 #include "gemv_dispatch.h"
+#include "gemv_mlp.h"
 
 namespace teal {
 
@@ -110,8 +111,9 @@ struct W4Batch {
 // once per (wavefront, group it touches), not once per row.  Batches never
 // straddle a group, and two batches are in flight per wavefront across group
 // boundaries.
+// Returns (block-uniform) whether this block wrote the tile's outputs.
 template <int LPR, int WAVES, int U, class XS>
-__device__ __forceinline__ void w4_block(const FmtW4::Args &a, const XS &x,
+__device__ __forceinline__ bool w4_block(const FmtW4::Args &a, const XS &x,
                                          float t, float *partial, int *counters, float *y, int m,
                                          int n, int ks, int tile, int s, int tile_cols, int splits,
                                          const SurvivorReport &report)
@@ -230,8 +232,8 @@ __device__ __forceinline__ void w4_block(const FmtW4::Args &a, const XS &x,
         consume(b1);
     }
     store_wave_sums<LPR>(acc, red + (threadIdx.x >> 6) * combine_row<EPL, LPR>);
-    block_finish<F, LPR, WAVES>(red, partial, counters, y, tile, col0, tile_cols, s, splits, n,
-                                a, cnt, report);
+    return block_finish<F, LPR, WAVES>(red, partial, counters, y, tile, col0, tile_cols, s, splits,
+                                       n, a, cnt, report);
 }
 
 template <int LPR, int WAVES, int U>
@@ -563,6 +565,68 @@ hipError_t launch_gemv_w4_multi(int count, const uint8_t *const *Wq, const void 
     if (sh.lanes_per_row == 32) TEAL_LAUNCH_W4M(32);
     else TEAL_LAUNCH_W4M(16);
 #undef TEAL_LAUNCH_W4M
+    return hipGetLastError();
+}
+
+// The int4 block body for the one-launch MLP.
+struct W4Body {
+    typedef FmtW4 Format;
+    template <int LPR, class XS>
+    static __device__ __forceinline__ bool run(const FmtW4::Args &a, const XS &x, float t,
+                                               float *partial, int *counters, float *y, int m,
+                                               int n, int ks, int tile, int s, int tile_cols,
+                                               int splits, const SurvivorReport &report)
+    {
+        static_assert(LPR == 16 || LPR == 32, "a lane covers 32 int4 columns");
+        return w4_block<LPR, kW4Waves, kW4Unroll>(a, x, t, partial, counters, y, m, n, ks, tile,
+                                                  s, tile_cols, splits, report);
+    }
+};
+
+static void set_wq_args(const void *&W, const __half *&scale, const void *w, const void *sc)
+{
+    W = w;
+    scale = static_cast<const __half *>(sc);
+}
+
+hipError_t launch_mlp_w8(const MlpHostArgs &h, const MlpLaunch &L, hipStream_t stream)
+{
+    if (!mlp_shape_ok(L.gu, 16) || !mlp_shape_ok(L.down, 16)) return hipErrorInvalidValue;
+    MlpArgs<FmtW8> A{};
+    size_t lds;
+    if (!fill_mlp_args<FmtW8>(A, lds, h, L, 64, [](FmtW8::Args &a, const void *W, const void *sc) {
+            set_wq_args(a.W, a.scale, W, sc);
+        }))
+        return hipErrorInvalidValue;
+    return launch_mlp_kernel<GemvBody<FmtW8>, true>(A, L.gu.lanes_per_row, L.down.lanes_per_row,
+                                                    lds, stream);
+}
+
+hipError_t launch_mlp_w4(const MlpHostArgs &h, const MlpLaunch &L, hipStream_t stream)
+{
+    if (!mlp_shape_ok(L.gu, 32) || !mlp_shape_ok(L.down, 32)) return hipErrorInvalidValue;
+    if (h.m % kGroup != 0 || h.f % kGroup != 0) return hipErrorInvalidValue;
+    const auto lanes_ok = [](int l) { return l == 16 || l == 32; };
+    if (!lanes_ok(L.gu.lanes_per_row) || !lanes_ok(L.down.lanes_per_row))
+        return hipErrorInvalidValue;
+    MlpArgs<FmtW4> A{};
+    size_t lds;
+    if (!fill_mlp_args<FmtW4>(A, lds, h, L, kGroup,
+                              [](FmtW4::Args &a, const void *W, const void *sc) {
+                                  set_wq_args(a.W, a.scale, W, sc);
+                              }))
+        return hipErrorInvalidValue;
+    const dim3 grid(mlp_blocks(A.grid)), block(kW4Waves * 64);
+#define TEAL_MLP_W4(LG, LD)                                                                    \
+    hipLaunchKernelGGL((sparse_mlp_kernel<W4Body, LG, LD>), grid, block, lds, stream, A)
+    if (L.gu.lanes_per_row == 32) {
+        if (L.down.lanes_per_row == 32) TEAL_MLP_W4(32, 32);
+        else TEAL_MLP_W4(32, 16);
+    } else {
+        if (L.down.lanes_per_row == 32) TEAL_MLP_W4(16, 32);
+        else TEAL_MLP_W4(16, 16);
+    }
+#undef TEAL_MLP_W4
     return hipGetLastError();
 }
 

@@ -917,3 +917,247 @@ teal_status teal_pack_bf16(const void *W_rowmajor, void *Wt, int m, int n, void 
 }
 
 }  // extern "C"
+
+// ---- the MLP of a block in one launch ----
+
+namespace {
+
+constexpr size_t kMlpControlBytes = (size_t)teal::kMlpControlInts * sizeof(int);
+constexpr int kMlpDefaultSpinLimit = 1 << 20;      // about a second of polling
+
+struct MlpFormat {
+    int bits, elems_per_lane, min_lanes, max_lanes, ks_multiple, n_multiple;
+};
+bool mlp_format(int weight_bits, MlpFormat &f)
+{
+    if (weight_bits == 16) f = MlpFormat{16, 8, 16, 64, 64, 8};
+    else if (weight_bits == 8) f = MlpFormat{8, 16, 8, 64, 64, 16};
+    else if (weight_bits == 4) f = MlpFormat{4, 32, 16, 32, 128, 32};
+    else return false;
+    return true;
+}
+
+bool mlp_dims_ok(const MlpFormat &fm, int m, int f, int d)
+{
+    return m >= 1 && m <= teal::kMaxDim && f >= fm.n_multiple && 2LL * f <= teal::kMaxDim &&
+           f % fm.n_multiple == 0 && d >= fm.n_multiple && d <= teal::kMaxDim &&
+           d % fm.n_multiple == 0;
+}
+
+GemvShape to_shape(int lanes, int tile_cols, int splits)
+{
+    GemvShape sh;
+    sh.lanes_per_row = lanes;
+    sh.tile_cols = tile_cols;
+    sh.splits = splits;
+    sh.waves = 8;
+    sh.unroll = 4;
+    return sh;
+}
+
+// The library's choice: the launch shapes of the grouped gate + up call and of the W_down
+// call, so that the results are bitwise those of the two calls.
+void mlp_default_shape(const MlpFormat &fm, int m, int f, int d, teal_mlp_shape *out)
+{
+    const int n2[2] = {f, f};
+    const GemvShape gu =
+        auto_shape_multi(m, n2, 2, fm.elems_per_lane, fm.min_lanes, fm.max_lanes, fm.ks_multiple);
+    const GemvShape dn = auto_shape(f, d, fm.elems_per_lane, fm.min_lanes, fm.max_lanes, fm.ks_multiple);
+    out->gu_lanes_per_row = gu.lanes_per_row;
+    out->gu_tile_cols = gu.tile_cols;
+    out->gu_splits = gu.splits;
+    out->gu_phase_tiles = 0;
+    out->down_lanes_per_row = dn.lanes_per_row;
+    out->down_tile_cols = dn.tile_cols;
+    out->down_splits = dn.splits;
+    out->extra_lds_bytes = 0;
+    out->spin_limit = kMlpDefaultSpinLimit;
+}
+
+bool mlp_launch_of(const MlpFormat &fm, const teal_mlp_shape &sh, int m, int f, int d,
+                   teal::MlpLaunch &L, teal::MlpGrid &grid)
+{
+    if (sh.gu_phase_tiles < 0 || sh.extra_lds_bytes < 0 || sh.extra_lds_bytes > 48 * 1024 ||
+        sh.spin_limit < 0)
+        return false;
+    L.gu = to_shape(sh.gu_lanes_per_row, sh.gu_tile_cols, sh.gu_splits);
+    L.down = to_shape(sh.down_lanes_per_row, sh.down_tile_cols, sh.down_splits);
+    L.phase_tiles = sh.gu_phase_tiles;
+    L.extra_lds = sh.extra_lds_bytes;
+    L.spin_limit = (unsigned)sh.spin_limit;
+    const auto lanes_ok = [&](int l) {
+        return l >= fm.min_lanes && l <= fm.max_lanes && (l & (l - 1)) == 0;
+    };
+    if (!lanes_ok(L.gu.lanes_per_row) || !lanes_ok(L.down.lanes_per_row)) return false;
+    if (!teal::mlp_grid_of(fm.bits, L, m, f, d, grid)) return false;
+    // partial rows and arrival counters of the two regions
+    if (grid.splits_gu > max_splits_for(m) || grid.splits_d > max_splits_for(f)) return false;
+    if (2LL * grid.tiles_gu > (long long)(teal::kCounterBytes / sizeof(int)) ||
+        grid.tiles_d > (long long)(teal::kCounterBytes / sizeof(int)))
+        return false;
+    return true;
+}
+
+struct MlpCall {
+    const void *W_gate, *W_up, *W_down;
+    const void *scale_gate, *scale_up, *scale_down;
+    const void *x_f16;
+    float t_gate, t_up, t_down;
+    float *gate, *up, *y;
+    int m, f, d;
+    void *workspace;
+    size_t workspace_bytes;
+    void *stream;
+};
+
+teal_status mlp_call(int weight_bits, const MlpCall &c, int group, const teal_mlp_shape *shape)
+{
+    MlpFormat fm;
+    if (!mlp_format(weight_bits, fm)) return TEAL_ERR_UNSUPPORTED;
+    const bool quantised = weight_bits != 16;
+    if (!c.W_gate || !c.W_up || !c.W_down || !c.x_f16 || !c.gate || !c.up || !c.y || !c.workspace)
+        return TEAL_ERR_NULL;
+    if (quantised && (!c.scale_gate || !c.scale_up || !c.scale_down)) return TEAL_ERR_NULL;
+    if (!mlp_dims_ok(fm, c.m, c.f, c.d)) return TEAL_ERR_SHAPE;
+    if (!aligned(c.W_gate, 16) || !aligned(c.W_up, 16) || !aligned(c.W_down, 16) ||
+        !aligned(c.x_f16, 2) || !aligned(c.gate, 4) || !aligned(c.up, 4) || !aligned(c.y, 4) ||
+        !aligned(c.workspace, kAlignWorkspace))
+        return TEAL_ERR_ALIGN;
+    const size_t scale_align = weight_bits == 4 ? 16 : 2;
+    if (quantised && (!aligned(c.scale_gate, scale_align) || !aligned(c.scale_up, scale_align) ||
+                      !aligned(c.scale_down, scale_align)))
+        return TEAL_ERR_ALIGN;
+    if (!threshold_ok(c.t_gate) || !threshold_ok(c.t_up) || !threshold_ok(c.t_down))
+        return TEAL_ERR_THRESHOLD;
+    if (weight_bits == 4 && (group != 128 || c.m % 128 != 0 || c.f % 128 != 0))
+        return TEAL_ERR_UNSUPPORTED;
+    if (c.workspace_bytes < teal_workspace_bytes_mlp(c.m, c.f, c.d)) return TEAL_ERR_WORKSPACE;
+    teal_mlp_shape chosen;
+    if (!shape) {
+        mlp_default_shape(fm, c.m, c.f, c.d, &chosen);
+        shape = &chosen;
+    }
+    teal::MlpLaunch L;
+    teal::MlpGrid grid;
+    if (!mlp_launch_of(fm, *shape, c.m, c.f, c.d, L, grid)) return TEAL_ERR_UNSUPPORTED;
+    unsigned char *region_gu = static_cast<unsigned char *>(c.workspace);
+    unsigned char *region_d = region_gu + teal_workspace_bytes(c.m, 2 * c.f);
+    unsigned char *control = region_d + teal_workspace_bytes(c.f, c.d);
+    const teal::MlpHostArgs h{c.W_gate, c.W_up, c.W_down, c.scale_gate, c.scale_up, c.scale_down,
+                              c.x_f16, c.t_gate, c.t_up, c.t_down, c.gate, c.up, c.y, c.m, c.f,
+                              c.d, ws_partials(region_gu, c.m), ws_counters(region_gu),
+                              ws_partials(region_d, c.f), ws_counters(region_d),
+                              reinterpret_cast<int *>(control)};
+    hipStream_t st = static_cast<hipStream_t>(c.stream);
+    if (weight_bits == 16) return from_hip(teal::launch_mlp_bf16(h, L, st));
+    if (weight_bits == 8) return from_hip(teal::launch_mlp_w8(h, L, st));
+    return from_hip(teal::launch_mlp_w4(h, L, st));
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t teal_workspace_bytes_mlp(int m, int f, int d)
+{
+    if (f < 1 || f > teal::kMaxDim / 2) return 0;
+    const size_t gu = teal_workspace_bytes(m, 2 * f), dn = teal_workspace_bytes(f, d);
+    if (gu == 0 || dn == 0) return 0;
+    return gu + dn + kMlpControlBytes;
+}
+
+size_t teal_mlp_down_region_offset(int m, int f)
+{
+    if (f < 1 || f > teal::kMaxDim / 2) return 0;
+    return teal_workspace_bytes(m, 2 * f);
+}
+
+size_t teal_mlp_status_offset(int m, int f, int d)
+{
+    const size_t total = teal_workspace_bytes_mlp(m, f, d);
+    if (total == 0) return 0;
+    return total - kMlpControlBytes + (size_t)teal::kMlpStatusIndex * sizeof(int);
+}
+
+teal_status teal_mlp_plan(int weight_bits, int m, int f, int d, teal_mlp_shape *shape)
+{
+    MlpFormat fm;
+    if (!shape) return TEAL_ERR_NULL;
+    if (!mlp_format(weight_bits, fm)) return TEAL_ERR_UNSUPPORTED;
+    if (!mlp_dims_ok(fm, m, f, d)) return TEAL_ERR_SHAPE;
+    mlp_default_shape(fm, m, f, d, shape);
+    return TEAL_OK;
+}
+
+teal_status teal_mlp_block_info(int weight_bits, int m, int f, int d, const teal_mlp_shape *shape,
+                                int block, int *info)
+{
+    MlpFormat fm;
+    if (!shape || !info) return TEAL_ERR_NULL;
+    if (!mlp_format(weight_bits, fm)) return TEAL_ERR_UNSUPPORTED;
+    if (!mlp_dims_ok(fm, m, f, d)) return TEAL_ERR_SHAPE;
+    teal::MlpLaunch L;
+    teal::MlpGrid g;
+    if (!mlp_launch_of(fm, *shape, m, f, d, L, g)) return TEAL_ERR_UNSUPPORTED;
+    const int blocks = teal::mlp_blocks(g);
+    info[0] = blocks;
+    if (block < 0 || block >= blocks) {
+        for (int k = 1; k < 8; ++k) info[k] = -1;
+        return TEAL_OK;
+    }
+    const teal::MlpBlock b = teal::mlp_block(g, block);
+    info[1] = b.kind;
+    info[2] = b.tile;
+    info[3] = b.split;
+    if (b.kind == teal::kMlpDown) {
+        const int k0 = b.split * g.ks_d;
+        info[4] = k0;
+        info[5] = k0 + g.ks_d < f ? k0 + g.ks_d : f;
+        info[6] = b.split;
+        info[7] = teal::mlp_expected(g, b.split);
+    } else {
+        const int c0 = b.tile * g.tile_cols_gu;
+        info[4] = c0;
+        info[5] = c0 + g.tile_cols_gu < f ? c0 + g.tile_cols_gu : f;
+        teal::mlp_signal_range(g, b.tile, info[6], info[7]);
+    }
+    return TEAL_OK;
+}
+
+teal_status teal_sparse_mlp_bf16(const void *Wt_gate, const void *Wt_up, const void *Wt_down,
+                                 const void *x_f16, float t_gate, float t_up, float t_down,
+                                 float *gate, float *up, float *y, int m, int f, int d,
+                                 void *workspace, size_t workspace_bytes, void *stream,
+                                 const teal_mlp_shape *shape)
+{
+    const MlpCall c{Wt_gate, Wt_up, Wt_down, nullptr, nullptr, nullptr, x_f16, t_gate, t_up,
+                    t_down, gate, up, y, m, f, d, workspace, workspace_bytes, stream};
+    return mlp_call(16, c, 0, shape);
+}
+
+teal_status teal_sparse_mlp_w8(const int8_t *Wq_gate, const int8_t *Wq_up,
+                                  const int8_t *Wq_down, const void *scale_gate,
+                                  const void *scale_up, const void *scale_down, const void *x_f16,
+                                  float t_gate, float t_up, float t_down, float *gate, float *up,
+                                  float *y, int m, int f, int d, void *workspace,
+                                  size_t workspace_bytes, void *stream, const teal_mlp_shape *shape)
+{
+    const MlpCall c{Wq_gate, Wq_up, Wq_down, scale_gate, scale_up, scale_down, x_f16, t_gate,
+                    t_up, t_down, gate, up, y, m, f, d, workspace, workspace_bytes, stream};
+    return mlp_call(8, c, 0, shape);
+}
+
+teal_status teal_sparse_mlp_w4(const uint8_t *Wq_gate, const uint8_t *Wq_up,
+                                  const uint8_t *Wq_down, const void *scale_gate,
+                                  const void *scale_up, const void *scale_down, int group,
+                                  const void *x_f16, float t_gate, float t_up, float t_down,
+                                  float *gate, float *up, float *y, int m, int f, int d,
+                                  void *workspace, size_t workspace_bytes, void *stream,
+                                  const teal_mlp_shape *shape)
+{
+    const MlpCall c{Wq_gate, Wq_up, Wq_down, scale_gate, scale_up, scale_down, x_f16, t_gate,
+                    t_up, t_down, gate, up, y, m, f, d, workspace, workspace_bytes, stream};
+    return mlp_call(4, c, group, shape);
+}
+
+}  // extern "C"

@@ -6,6 +6,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include "mlp_schedule.h"
+
 namespace teal {
 
 constexpr int kMaxSplits = 128;     // most split-K blocks a caller may ask for (longer inputs force more)
@@ -135,6 +137,36 @@ hipError_t launch_gemv_w4_multi(int count, const uint8_t *const *Wq, const void 
                                 const float *t, float *const *y, const int *n, const void *x_f16,
                                 int m, float *partial, int *counters, const GemvShape &shape,
                                 hipStream_t stream);
+
+// The MLP of a block in one launch (Appendix A.3): gate and up from x, then W_down on
+// SiLU(gate) . up, the blocks of W_down waiting for the gate / up tiles they read.
+struct MlpLaunch {
+    GemvShape gu, down;          // 8 wavefronts, 4 loads per batch
+    int phase_tiles;             // gate / up tiles per phase of the grid order; 0 = one phase
+    int extra_lds;               // dynamic LDS requested beyond need (fewer blocks per unit)
+    unsigned spin_limit;         // polls before a waiting block gives up
+};
+struct MlpHostArgs {
+    const void *W_gate, *W_up, *W_down;
+    const void *scale_gate, *scale_up, *scale_down;   // quantised formats, else NULL
+    const void *x_f16;
+    float t_gate, t_up, t_down;
+    float *gate, *up, *y;
+    int m, f, d;                 // model width in, MLP width, model width out
+    float *partial_gu;
+    int *counters_gu;            // head of the gate / up region of the workspace
+    float *partial_d;
+    int *counters_d;             // head of the W_down region
+    int *control;                // kMlpControlInts ints: readiness counters, done, status
+};
+constexpr int kMlpControlInts = 256;
+constexpr int kMlpStatusIndex = kMaxSplits + 1;
+// The grid of such a launch for a weight format (16, 8 or 4 bits); false if the shapes do
+// not give a launchable grid.
+bool mlp_grid_of(int weight_bits, const MlpLaunch &L, int m, int f, int d, MlpGrid &grid);
+hipError_t launch_mlp_bf16(const MlpHostArgs &h, const MlpLaunch &L, hipStream_t stream);
+hipError_t launch_mlp_w8(const MlpHostArgs &h, const MlpLaunch &L, hipStream_t stream);
+hipError_t launch_mlp_w4(const MlpHostArgs &h, const MlpLaunch &L, hipStream_t stream);
 
 hipError_t launch_abs_histogram(const void *x_f16, size_t count, unsigned long long *hist,
                                 hipStream_t stream);
