@@ -380,9 +380,12 @@ teal_status teal_sparse_gemv_w4_multi(int count, const uint8_t *const *Wq,
  * with every product thresholded (Section 4.2): gate = s_{t_gate}(x) W_gate^T,
  * up = s_{t_up}(x) W_up^T, h = fp16(SiLU(gate) * up) in the arithmetic stated for
  * teal_sparse_gemv_bf16_swiglu, y = s_{t_down}(h) W_down^T.  The results (gate,
- * up and y) are bitwise those of teal_sparse_gemv_bf16_multi on (W_gate, W_up)
- * followed by teal_sparse_gemv_bf16_swiglu on W_down, run with the same launch
- * shapes (which is what the library picks when `shape` is NULL).  The thread
+ * up and y) are bitwise those of the separate calls with the same launch
+ * shapes: teal_sparse_gemv_bf16_ex on W_gate and on W_up, teal_swiglu_f16, and
+ * teal_sparse_gemv_bf16_ex on W_down (equally teal_sparse_gemv_bf16_multi and
+ * teal_sparse_gemv_bf16_swiglu when the shapes are the ones those calls pick;
+ * the shape the library picks here when `shape` is NULL is teal_mlp_plan's,
+ * which for the gate / up products may differ from theirs).  The thread
  * blocks of the W_down product follow those of gate and up in the same grid and
  * each waits only for the gate / up output tiles that cover its own slice of h,
  * so nothing separates the dependent products but those waits.

@@ -164,3 +164,23 @@ hipError_t launch_mlp_bf16(const MlpHostArgs &h, const MlpLaunch &L, hipStream_t
 }
 
 }  // namespace teal
+
+#ifdef TEAL_TRACE_BLOCKS
+// The trace build's read-out (see trace_mark in gemv_common.h): copies the marks of this
+// file's kernels to HOST memory after synchronising the device, and clears them.
+extern "C" int teal_trace_read(unsigned long long *host, size_t count)
+{
+    const size_t all = (size_t)teal::kTraceBlocks * teal::kTraceMarks;
+    if (!host || count > all) return 1;
+    if (hipDeviceSynchronize() != hipSuccess) return 2;
+    if (hipMemcpyFromSymbol(host, HIP_SYMBOL(teal::teal_trace),
+                            count * sizeof(unsigned long long)) != hipSuccess)
+        return 3;
+    static unsigned long long zeros[4096];
+    for (size_t at = 0; at < all; at += 4096)
+        if (hipMemcpyToSymbol(HIP_SYMBOL(teal::teal_trace), zeros, sizeof(zeros),
+                              at * sizeof(unsigned long long)) != hipSuccess)
+            return 4;
+    return 0;
+}
+#endif

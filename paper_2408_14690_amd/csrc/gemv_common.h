@@ -21,6 +21,22 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kMaxSegs = kMaxSlice / 64;   // 64-channel segments per slice
 
+// Measurement aid, compiled in only with -DTEAL_TRACE_BLOCKS (a separate build of the library
+// used to look at where the time of a launch goes; the library proper contains none of it):
+// thread 0 of a block leaves the 100 MHz device clock at up to 8 marks in a device array (one
+// per source file; teal_trace_read copies out that of the bf16 kernels).
+#ifdef TEAL_TRACE_BLOCKS
+constexpr int kTraceBlocks = 8192, kTraceMarks = 8;
+static __device__ unsigned long long teal_trace[kTraceBlocks * kTraceMarks];
+__device__ __forceinline__ void trace_mark(int slot)
+{
+    if (threadIdx.x == 0 && blockIdx.x < kTraceBlocks)
+        teal_trace[blockIdx.x * kTraceMarks + slot] = wall_clock64();
+}
+#else
+__device__ __forceinline__ void trace_mark(int) {}
+#endif
+
 // Weight bytes are used exactly once: load them non-temporal so they do not
 // displace x and the partial sums from the caches (the counterpart of the
 // eviction-policy hint of Section 4.4).
@@ -620,8 +636,10 @@ __device__ __forceinline__ bool block_finish(float *red,
     }
     wait_vector_memory();   // this thread's write-through stores have completed
     __syncthreads();
+    trace_mark(4);
     if (threadIdx.x == 0) last_flag = atomicAdd(&counters[tile], 1) == splits - 1;
     __syncthreads();
+    trace_mark(5);
     if (!last_flag) return false;
     if (tile == 0 && w == 0) report_total(report, splits);
 
@@ -695,6 +713,7 @@ __device__ __forceinline__ bool gemv_block(const typename F::Args &a, const XS &
         cnt = compact_slice<WAVES>(x, t, k0, k1, list, seg_cnt, seg_excl);
     }
 
+    trace_mark(2);
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     int start, mine;
@@ -710,6 +729,7 @@ __device__ __forceinline__ bool gemv_block(const typename F::Args &a, const XS &
 #pragma unroll
     for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
     stream_rows<F, LPR, U>(acc, list, start, mine, lane_base, row_bytes);
+    trace_mark(3);
     store_wave_sums<LPR>(acc, red + (threadIdx.x >> 6) * combine_row<EPL, LPR>);
     return block_finish<F, LPR, WAVES>(red, partial, counters, y, tile, col0, tile_cols, s, splits,
                                        n, a, cnt, report);

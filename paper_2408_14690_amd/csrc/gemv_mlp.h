@@ -22,11 +22,15 @@
 
 namespace teal {
 
-// Control words at the end of an MLP call's workspace.
-constexpr int kMlpMaxSlices = kMaxSplits;       // ready[s], one per K-slice of W_down
-constexpr int kMlpDoneIndex = kMlpMaxSlices;    // output tiles of W_down written (wraps to 0)
-static_assert(kMlpStatusIndex == kMlpMaxSlices + 1, "status word follows the done count");
-static_assert(kMlpStatusIndex < kMlpControlInts, "control block too small");
+// Control area at the end of an MLP call's workspace: the status word (0 = fine, 1 = a wait
+// expired), then one readiness counter per thread block of the W_down product, each on a
+// 128-byte line of its own.  A counter is polled by exactly one block, so no two pollers ever
+// ask for the same line (many pollers on one line were measured to slow every coherent
+// access of the launch: the split-K publish of the producers took 3 us instead of 1.3), and
+// the block that has seen its counter reach the value it waits for puts it back to zero
+// itself: nothing else is needed to leave the area ready for the next call.
+constexpr int kMlpLineInts = 32;
+__host__ __device__ inline int mlp_ready_index(int consumer) { return kMlpLineInts * (1 + consumer); }
 
 // gate and up as written by other blocks of the same launch: read past the local L2.
 struct SwigluReadySource {
@@ -89,62 +93,69 @@ __global__ __launch_bounds__(8 * 64) void sparse_mlp_kernel(MlpArgs<typename Bod
 {
     const MlpGrid &g = A.grid;
     const MlpBlock blk = mlp_block(g, (int)blockIdx.x);
+    trace_mark(0);
+#ifdef TEAL_TRACE_BLOCKS
+    // where the block runs: XCC_ID (hardware register 20, bits 3:0) and HW_ID (register 4)
+    if (threadIdx.x == 0 && blockIdx.x < kTraceBlocks)
+        teal_trace[blockIdx.x * kTraceMarks + 1] =
+            ((unsigned long long)__builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) << 32) |
+            (unsigned)__builtin_amdgcn_s_getreg(4 | (0 << 6) | (31 << 11));
+#endif
     if (blk.kind != kMlpDown) {
         const int k = blk.kind;
         const bool wrote = Body::template run<LPR_GU>(
             A.a_gu[k], HalfSource{A.x}, A.t_gu[k], A.partial_gu + (size_t)k * g.splits_gu * g.f,
             A.counters_gu + k * g.tiles_gu, A.y_gu[k], A.m, g.f, A.ks_gu, blk.tile, blk.split,
             g.tile_cols_gu, g.splits_gu, survivor_report(A.counters_gu, k, g.splits_gu));
+        trace_mark(6);
         if (!wrote) return;
         // The tile's columns of gate / up are written (write-through stores): once every
         // thread's stores are acknowledged, tell the K-slices of W_down that read them.
         wait_vector_memory();
         __syncthreads();
-        if (threadIdx.x == 0) {
+        if (threadIdx.x < 64) {
             int lo, hi;
             mlp_signal_range(g, blk.tile, lo, hi);
             for (int s = lo; s <= hi; ++s)
-                __hip_atomic_fetch_add(A.control + s, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                for (int j = threadIdx.x; j < g.tiles_d; j += 64)
+                    __hip_atomic_fetch_add(A.control + mlp_ready_index(s * g.tiles_d + j), 1,
+                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
+        trace_mark(7);
         return;
     }
 
     __shared__ int inputs_ready;
     if (threadIdx.x == 0) {
         const int expected = mlp_expected(g, blk.split);
-        const int *ready = A.control + blk.split;
-        const int *status = A.control + kMlpStatusIndex;
+        int *ready = A.control + mlp_ready_index(blk.split * g.tiles_d + blk.tile);
         unsigned spins = 0;
         int ok = 0;
         for (;;) {
-            const int r = load_coherent(ready), st = load_coherent(status);
-            if (r == expected) {
+            if (load_coherent(ready) == expected) {
                 ok = 1;
                 break;
             }
-            if (st != 0 || spins >= A.spin_limit) break;
+            // the shared status word only now and then: it is one line for all blocks
+            if (spins >= A.spin_limit || ((spins & 255u) == 255u && load_coherent(A.control) != 0))
+                break;
             ++spins;
-            __builtin_amdgcn_s_sleep(8);
+            __builtin_amdgcn_s_sleep(2);
         }
-        if (!ok) store_coherent(A.control + kMlpStatusIndex, 1);
+        if (ok) store_coherent(ready, 0);      // every producer has told: ready for the next call
+        else store_coherent(A.control, 1);
         inputs_ready = ok;
     }
     __syncthreads();
+    trace_mark(7);
     if (!inputs_ready) return;
 
     const bool wrote = Body::template run<LPR_D>(
         A.a_d, SwigluReadySource{A.y_gu[0], A.y_gu[1]}, A.t_d, A.partial_d, A.counters_d, A.y_d,
         g.f, A.n_d, g.ks_d, blk.tile, blk.split, A.tile_cols_d, g.splits_d,
         survivor_report(A.counters_d, 0, g.splits_d));
-    if (!wrote) return;
-    // Every block of this tile has passed its wait.  The block that finishes the last tile
-    // therefore knows that nobody polls the readiness counters any more and leaves them at
-    // zero for the next call; the count of finished tiles wraps to zero by itself.
-    if (threadIdx.x == 0) {
-        const unsigned last = (unsigned)g.tiles_d - 1u;
-        if (atomicInc(reinterpret_cast<unsigned *>(A.control + kMlpDoneIndex), last) == last)
-            for (int s = 0; s < g.splits_d; ++s) store_coherent(A.control + s, 0);
-    }
+    trace_mark(6);
+    (void)wrote;
 }
 
 // Host side.  Geometry of the two products from their launch shapes, argument block.
@@ -153,7 +164,7 @@ inline bool mlp_grid(MlpGrid &g, GemvGeometry &ggu, GemvGeometry &gd, const MlpL
 {
     ggu = gemv_geometry(m, f, L.gu, elems_per_lane, ks_multiple);
     gd = gemv_geometry(f, d, L.down, elems_per_lane, ks_multiple);
-    if (gd.splits > kMlpMaxSlices) return false;
+    if ((long long)gd.tiles * gd.splits > kMlpMaxConsumers) return false;
     g.f = f;
     g.tiles_gu = ggu.tiles;
     g.tile_cols_gu = ggu.tile_cols;

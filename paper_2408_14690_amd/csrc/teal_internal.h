@@ -157,10 +157,10 @@ struct MlpHostArgs {
     int *counters_gu;            // head of the gate / up region of the workspace
     float *partial_d;
     int *counters_d;             // head of the W_down region
-    int *control;                // kMlpControlInts ints: readiness counters, done, status
+    int *control;                // kMlpControlBytes: status word, one readiness counter per W_down block
 };
-constexpr int kMlpControlInts = 256;
-constexpr int kMlpStatusIndex = kMaxSplits + 1;
+constexpr int kMlpMaxConsumers = 4096;       // most thread blocks of the W_down product
+constexpr size_t kMlpControlBytes = 128 * (size_t)(1 + kMlpMaxConsumers);
 // The grid of such a launch for a weight format (16, 8 or 4 bits); false if the shapes do
 // not give a launchable grid.
 bool mlp_grid_of(int weight_bits, const MlpLaunch &L, int m, int f, int d, MlpGrid &grid);

@@ -173,13 +173,34 @@ def test_mlp_matches_separate_calls_and_the_oracle(T, m, f, d, over):
     assert rel_l2(y0.cpu().numpy(), want0) <= TIGHT
 
 
-def test_default_shape_is_bitwise_the_grouped_call_and_the_fused_down_call(T):
-    m, f, d = 4096, 14336, 4096
-    M = Mlp(T, m, f, d, seed=32000)
+@pytest.mark.parametrize("m,f,d", [(4096, 14336, 4096), (4096, 11008, 4096)])
+def test_library_shape_is_bitwise_the_separate_calls(T, m, f, d):
+    """shape = NULL: the launch shape teal_mlp_plan reports; bitwise the separate calls with it."""
+    M = Mlp(T, m, f, d, seed=32000 + f)
+    st, sh = T.teal_mlp_plan(16, m, f, d)
+    T.check(st)
     ws = torch.zeros(T.teal_workspace_bytes_mlp(m, f, d), dtype=torch.uint8, device="cuda")
     g0, u0, _ = run_mlp(T, M, 0.0, ws)
     t_down = M.t_down_from(g0.cpu().numpy(), u0.cpu().numpy())
     gate, up, y = run_mlp(T, M, t_down, ws)
+    rg, ru, ry = separate_calls(T, M, t_down, sh)
+    assert bits_equal(gate, rg) and bits_equal(up, ru) and bits_equal(y, ry)
+    rows = np.unique(np.concatenate([np.arange(0, f, 97), [f - 1]])).astype(np.int32)
+    check_against_oracle(T, M, gate, up, y, t_down, ws, rows=rows)
+
+
+def test_shapes_of_the_grouped_calls_are_bitwise_those_calls(T):
+    """With the launch shapes the grouped gate + up call and the fused W_down call pick
+    themselves, the one-launch MLP is bitwise those two calls."""
+    m, f, d = 4096, 14336, 4096
+    M = Mlp(T, m, f, d, seed=32000)
+    st, sh = T.teal_mlp_plan(16, m, f, d)
+    st, gu = T.teal_gemv_plan_multi(16, m, [f, f])
+    sh.gu_lanes_per_row, sh.gu_tile_cols, sh.gu_splits = gu["lanes_per_row"], gu["tile_cols"], gu["splits"]
+    ws = torch.zeros(T.teal_workspace_bytes_mlp(m, f, d), dtype=torch.uint8, device="cuda")
+    g0, u0, _ = run_mlp(T, M, 0.0, ws, sh)
+    t_down = M.t_down_from(g0.cpu().numpy(), u0.cpu().numpy())
+    gate, up, y = run_mlp(T, M, t_down, ws, sh)
     rg = torch.empty(f, dtype=torch.float32, device="cuda")
     ru = torch.empty(f, dtype=torch.float32, device="cuda")
     ws2 = torch.zeros(T.teal_workspace_bytes(m, 2 * f), dtype=torch.uint8, device="cuda")
@@ -190,8 +211,6 @@ def test_default_shape_is_bitwise_the_grouped_call_and_the_fused_down_call(T):
     T.check(T.teal_sparse_gemv_bf16_swiglu(M.wt[2], rg, ru, t_down, ry, f, d, ws3))
     torch.cuda.synchronize()
     assert bits_equal(gate, rg) and bits_equal(up, ru) and bits_equal(y, ry)
-    rows = np.unique(np.concatenate([np.arange(0, f, 97), [f - 1]])).astype(np.int32)
-    check_against_oracle(T, M, gate, up, y, t_down, ws, rows=rows)
 
 
 @pytest.mark.parametrize("over", [

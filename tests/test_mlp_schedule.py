@@ -153,7 +153,7 @@ def test_the_model_sees_a_schedule_that_can_wait_for_ever():
     """The same model with the consumers placed BEFORE their producers and fewer slots than
     consumers: nothing can complete.  (The mistake is planted in the model's dispatch order,
     on the CPU; the kernel's order is the one checked above.)"""
-    sh = shape_of(16, 4096, 14336, 4096)
+    sh = shape_of(16, 4096, 14336, 4096, gu_lanes_per_row=64, gu_tile_cols=448, gu_splits=4)
     blocks = blocks_of(16, 4096, 14336, 4096, sh)
     n_down = sum(b["kind"] == DOWN for b in blocks)
     wrong = sorted(range(len(blocks)), key=lambda i: blocks[i]["kind"] != DOWN)
@@ -167,18 +167,26 @@ def test_plan_and_argument_errors():
     m, f, d = 4096, 14336, 4096
     st, sh = T.teal_mlp_plan(16, m, f, d)
     assert st == T.TEAL_OK
-    # the library's choice: the shapes of the grouped gate + up call and of the W_down call
-    st, gu = T.teal_gemv_plan_multi(16, m, [f, f])
+    # the library's choice: W_down as its own call; gate / up without split-K in tiles of 256
+    # bytes of a row where that gives about one block per compute unit (224 here), else the
+    # shape of the grouped gate + up call (the 70B-sized layer; int8, where 256 bytes are 256
+    # columns and the blocks would be too few)
     st2, dn = T.teal_gemv_plan(16, f, d)
-    assert st == st2 == T.TEAL_OK
-    assert (sh.gu_lanes_per_row, sh.gu_tile_cols, sh.gu_splits) == (gu["lanes_per_row"], gu["tile_cols"], gu["splits"])
+    assert st2 == T.TEAL_OK
+    assert (sh.gu_lanes_per_row, sh.gu_tile_cols, sh.gu_splits) == (16, 128, 1)
     assert (sh.down_lanes_per_row, sh.down_tile_cols, sh.down_splits) == (dn["lanes_per_row"], dn["tile_cols"], dn["splits"])
+    for bits, (mm, ff, dd) in ((16, (8192, 28672, 8192)), (8, (m, f, d)), (4, (m, f, d))):
+        st, big = T.teal_mlp_plan(bits, mm, ff, dd)
+        st2, gu = T.teal_gemv_plan_multi(bits, mm, [ff, ff])
+        assert st == st2 == T.TEAL_OK
+        assert (big.gu_lanes_per_row, big.gu_tile_cols, big.gu_splits) == (gu["lanes_per_row"], gu["tile_cols"], gu["splits"])
     assert T.teal_mlp_plan(5, m, f, d)[0] == T.TEAL_ERR_UNSUPPORTED
     assert T.teal_mlp_plan(16, m, f + 4, d)[0] == T.TEAL_ERR_SHAPE
     need = T.teal_workspace_bytes_mlp(m, f, d)
-    assert need == T.teal_workspace_bytes(m, 2 * f) + T.teal_workspace_bytes(f, d) + 1024
+    control = 128 * (1 + 4096)          # status word + one counter line per W_down block
+    assert need == T.teal_workspace_bytes(m, 2 * f) + T.teal_workspace_bytes(f, d) + control
     assert T.teal_mlp_down_region_offset(m, f) == T.teal_workspace_bytes(m, 2 * f)
-    assert need - 1024 < T.teal_mlp_status_offset(m, f, d) < need
+    assert T.teal_mlp_status_offset(m, f, d) == need - control
     assert T.teal_workspace_bytes_mlp(m, 0, d) == 0
 
     ok = dict(Wt_gate=W, Wt_up=W, Wt_down=W, x_f16=X, t_gate=0.5, t_up=0.5, t_down=0.1, gate=Y,
@@ -204,7 +212,7 @@ def test_plan_and_argument_errors():
     bad.gu_lanes_per_row = 48
     assert call(shape=bad) == T.TEAL_ERR_UNSUPPORTED
     bad = T.MlpShape(**sh.as_dict())
-    bad.down_splits = 224                                   # more K-slices than readiness counters
+    bad.down_splits = 224                                   # more blocks than readiness counters
     bad.down_tile_cols = 128
     assert call(shape=bad) == T.TEAL_ERR_UNSUPPORTED
     bad = T.MlpShape(**sh.as_dict())
