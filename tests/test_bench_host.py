@@ -53,14 +53,41 @@ def test_more_than_one_gpu_is_refused():
     assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
 
 
-def test_measured_traffic_table_is_close_to_the_algorithmic_bytes():
-    """The HBM bytes per launch copied from the rocprofv3 summaries stay within 3 % of the
-    algorithmic bytes of the same launches (they include the partial rows and x per tile)."""
-    # no GPU: the 50 % bytes of the Llama-2-7B block recomputed from its shapes
-    shapes = ti.LAYER_SHAPES["llama2_7b"]
-    per_proj = sum(bench.algorithmic_bytes("bf16", m // 2, m, n) for n, m in shapes.values())
-    grouped = per_proj - 2 * 4096 * 3          # x read once for q+k+v and once for gate+up
-    t = bench.MEASURED_TRAFFIC_BYTES
-    assert abs(t[("llama2_7b", "bf16", 0.5, 1, True)] * 4 / grouped - 1) < 0.03
-    assert abs(t[("llama2_7b", "bf16", 0.5, 1, False)] * 7 / per_proj - 1) < 0.03
-    assert abs(t[("llama2_7b", "bf16", 0.5, 1, "stack")] / grouped - 1) < 0.03
+def test_measured_traffic_comes_from_a_profile_summary_of_the_same_kernels(tmp_path):
+    """roofline.traffic is read from a rocprofv3 counter summary under profiles/, and only from
+    one taken for the same workload, format, sparsity, launch mode AND library version: a
+    summary of older kernels gives no figure, with the reason."""
+    import bench_lib
+    (tmp_path / "a.txt").write_text(
+        "header\n"
+        "TRAFFIC workload=llama_70b format=bf16 sparsity=0.5 layers=80 launches=grouped "
+        "library_version=400 fetch_bytes_per_launch=1000 write_bytes_per_launch=24\n"
+        "TRAFFIC workload=llama3_8b format=bf16 sparsity=0.5 layers=1 launches=grouped "
+        "library_version=399 fetch_bytes_per_launch=5 write_bytes_per_launch=5\n")
+    got, src = bench_lib.measured_traffic("llama_70b", "bf16", 0.5, 80, "grouped", 400, str(tmp_path))
+    assert got == 1024.0 and src.endswith("a.txt")
+    got, why = bench_lib.measured_traffic("llama3_8b", "bf16", 0.5, 1, "grouped", 400, str(tmp_path))
+    assert got is None and "399" in why
+    got, why = bench_lib.measured_traffic("llama2_7b", "w8", 0.5, 1, "stack", 400, str(tmp_path))
+    assert got is None and "no rocprofv3" in why
+
+
+def test_committed_traffic_summaries_are_close_to_the_algorithmic_bytes():
+    """Every TRAFFIC line committed under profiles/ stays within 3 % of the algorithmic bytes
+    it states beside the counters (partial rows re-read, x read once per tile)."""
+    import glob
+    lines = [l for f in glob.glob(os.path.join(ROOT, "profiles", "*.txt")) for l in open(f)
+             if l.startswith("TRAFFIC ")]
+    for l in lines:
+        kv = dict(t.split("=", 1) for t in l.split()[1:] if "=" in t)
+        total = float(kv["fetch_bytes_per_launch"]) + float(kv["write_bytes_per_launch"])
+        assert abs(total / float(kv["algorithmic_bytes_per_launch"]) - 1) < 0.03, l
+
+
+def test_headline_defaults_name_the_largest_single_gpu_configuration():
+    assert bench.DEFAULT_LAYERS["llama_70b"] == 80
+    src = open(os.path.join(ROOT, "bench.py")).read()
+    assert 'default="llama_70b"' in src
+    # 80 blocks of the 70B-shaped layer: 137 GB of bf16 weights
+    per_block = sum(2 * n * m for n, m in ti.LAYER_SHAPES["llama_70b"].values())
+    assert round(80 * per_block / 1e9) == 137
