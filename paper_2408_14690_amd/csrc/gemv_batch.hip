@@ -258,7 +258,10 @@ __device__ __forceinline__ void block_finish_batch(const BatchAcc<NB> &acc, floa
     }
     wait_vector_memory();
     __syncthreads();
-    if (threadIdx.x == 0) last_flag = atomicAdd(&counters[tile], 1) == splits - 1;
+    // the ticket wraps to zero with the last arrival: ready for the next call
+    if (threadIdx.x == 0)
+        last_flag = atomicInc(reinterpret_cast<unsigned *>(&counters[tile]), (unsigned)splits - 1u) ==
+                    (unsigned)splits - 1u;
     __syncthreads();
     if (!last_flag) return;
     if (tile == 0 && threadIdx.x < 64) report_total(report, splits);
@@ -299,7 +302,6 @@ __device__ __forceinline__ void block_finish_batch(const BatchAcc<NB> &acc, floa
             store_coherent(Y + (size_t)bb * n + col0 + c, sum[o]);
         }
     }
-    if (threadIdx.x == 0) atomicExch(&counters[tile], 0);
 }
 
 // Work of one block: output tile `tile` x K-slice `s` of one matrix, all batch rows.

@@ -637,7 +637,14 @@ __device__ __forceinline__ bool block_finish(float *red,
     wait_vector_memory();   // this thread's write-through stores have completed
     __syncthreads();
     trace_mark(4);
-    if (threadIdx.x == 0) last_flag = atomicAdd(&counters[tile], 1) == splits - 1;
+    // The ticket wraps: the arrival that finds splits - 1 puts the counter back to zero in the
+    // same atomic, so the counter is ready for the next call without a second access.
+    // (Relaxed: an agent-scope release here makes the compiler write the whole L2 back, an
+    // acquire invalidates it; measured +1.0 .. +5 us and +0.5 .. +0.9 us per call.  The data
+    // this ticket orders never sits in an L2: see store_coherent / load_coherent.)
+    if (threadIdx.x == 0)
+        last_flag = atomicInc(reinterpret_cast<unsigned *>(&counters[tile]), (unsigned)splits - 1u) ==
+                    (unsigned)splits - 1u;
     __syncthreads();
     trace_mark(5);
     if (!last_flag) return false;
@@ -665,8 +672,6 @@ __device__ __forceinline__ bool block_finish(float *red,
             store_coherent(y + col0 + c, F::finish(sum, scale[k]));
         }
     }
-    // Leave the counter at zero for the next call on this workspace.
-    if (threadIdx.x == 0) atomicExch(&counters[tile], 0);
     return true;
 }
 

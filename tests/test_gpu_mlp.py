@@ -238,6 +238,24 @@ def test_full_size_mlp_in_phases(T, over):
     check_against_oracle(T, M, gate, up, y, t_down, ws, rows=rows)
 
 
+def test_70b_sized_mlp(T):
+    """The MLP of the 70B-shaped block (8192 -> 28672 -> 8192) in one launch, the library's
+    shape: bitwise the separate calls, sampled gate / up outputs and all of y against the
+    oracle, survivor counts exact."""
+    m, f, d = 8192, 28672, 8192
+    M = Mlp(T, m, f, d, seed=35000)
+    st, sh = T.teal_mlp_plan(16, m, f, d)
+    T.check(st)
+    ws = torch.zeros(T.teal_workspace_bytes_mlp(m, f, d), dtype=torch.uint8, device="cuda")
+    g0, u0, _ = run_mlp(T, M, 0.0, ws)
+    t_down = M.t_down_from(g0.cpu().numpy(), u0.cpu().numpy())
+    gate, up, y = run_mlp(T, M, t_down, ws)
+    rg, ru, ry = separate_calls(T, M, t_down, sh)
+    assert bits_equal(gate, rg) and bits_equal(up, ru) and bits_equal(y, ry)
+    rows = np.unique(np.concatenate([np.arange(0, f, 401), [f - 1]])).astype(np.int32)
+    check_against_oracle(T, M, gate, up, y, t_down, ws, rows=rows)
+
+
 def test_nothing_survives_and_everything_survives(T):
     m, f, d = 1024, 2048, 512
     M = Mlp(T, m, f, d, seed=33000)

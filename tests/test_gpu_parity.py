@@ -382,6 +382,67 @@ def test_gemv_bf16_70b_shape_grouped_sampled_rows(T):
         assert rel_l2(got[rows], orc.sparse_gemv_bf16_rows(ws_host[k], x, ts[k], rows)) <= TIGHT, k
 
 
+def max_abs_err_scaled(got, want):
+    """Largest element-wise error relative to the vector's RMS: a single wrong output shows
+    here even where a norm over many outputs would hide it."""
+    rms = np.sqrt(np.mean(want ** 2))
+    return float(np.max(np.abs(got.astype(np.float64) - want)) / rms) if rms > 0 else float(np.any(got))
+
+
+@pytest.mark.parametrize("proj", ["q", "k", "down"])
+def test_gemv_bf16_remaining_70b_shapes_sampled_rows(T, proj):
+    """8192 x 8192 (q / o), 1024 x 8192 (k / v) and 8192 x 28672 (down) of the 70B-shaped
+    block at full size, the launch shape the benchmark times: survivor count exact, sampled
+    outputs one by one against the oracle (norm and element-wise), every output finite."""
+    n, m = ti.LAYER_SHAPES["llama_70b"][proj]
+    w = ti.weights_bf16(n, m, ti.weight_seed(4, 0, proj))
+    x = ti.make_x(m, ti.x_seed(4, 0, proj), ti.PROJ_DIST[proj])
+    wd = dev(w)
+    wt = torch.empty((m, n), dtype=torch.int16, device="cuda")
+    T.check(T.teal_pack_bf16(wd, wt, m, n))
+    del wd
+    ws = workspace(T, m, n)
+    xd = dev(x)
+    for p in (0.5, 0.0):
+        t = ti.quantile_threshold(x, p)
+        got = run_bf16(T, wt, xd, t, m, n, ws)
+        assert survivors(T, ws) == [orc.sparsify(x, t)[3]]
+        rows = np.unique(np.concatenate([np.arange(0, n, 61), [n - 1, n - 8, 127, 128, 255, 256]])).astype(np.int32)
+        want = orc.sparse_gemv_bf16_rows(w, x, t, rows)
+        assert rel_l2(got[rows], want) <= TIGHT, (proj, p)
+        assert max_abs_err_scaled(got[rows], want) <= 1e-4, (proj, p)
+        assert np.all(np.isfinite(got))
+
+
+def test_gemv_bf16_70b_qkv_group_sampled_rows(T):
+    """q + k + v of the 70B-shaped block in one call (8192, 1024, 1024 columns of an 8192-wide
+    state, own thresholds): the other grouped launch of the headline benchmark."""
+    m = 8192
+    x = ti.gaussian_x(m, ti.x_seed(4, 0, "q"))
+    xd = dev(x)
+    hosts, wts, ns = [], [], []
+    for proj in ("q", "k", "v"):
+        n, _ = ti.LAYER_SHAPES["llama_70b"][proj]
+        w = ti.weights_bf16(n, m, ti.weight_seed(4, 0, proj))
+        wt = torch.empty((m, n), dtype=torch.int16, device="cuda")
+        T.check(T.teal_pack_bf16(dev(w), wt, m, n))
+        hosts.append(w)
+        wts.append(wt)
+        ns.append(n)
+    ts = [ti.quantile_threshold(x, p) for p in (0.5, 0.4, 0.65)]
+    ys = [torch.full((n,), float("nan"), dtype=torch.float32, device="cuda") for n in ns]
+    ws = workspace(T, m, sum(ns))
+    T.check(T.teal_sparse_gemv_bf16_multi(wts, ts, ys, ns, xd, m, ws))
+    torch.cuda.synchronize()
+    assert survivors(T, ws, 3) == [orc.sparsify(x, t)[3] for t in ts]
+    for k in range(3):
+        got = ys[k].cpu().numpy()
+        rows = np.unique(np.concatenate([np.arange(0, ns[k], 53), [ns[k] - 1]])).astype(np.int32)
+        want = orc.sparse_gemv_bf16_rows(hosts[k], x, ts[k], rows)
+        assert np.all(np.isfinite(got))
+        assert rel_l2(got[rows], want) <= TIGHT and max_abs_err_scaled(got[rows], want) <= 1e-4, k
+
+
 # ---------------------------------------------------------------------------
 # several matrices sharing one hidden state in one launch
 # ---------------------------------------------------------------------------
