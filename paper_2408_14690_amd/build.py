@@ -27,6 +27,8 @@ FLAGS = [
     # keep the compiler from forming packed-fp32 instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
+    # extra compiler flags for experiments (e.g. -DNAME=value), space-separated
+    *os.environ.get("TEAL_HIPCC_EXTRA", "").split(),
 ]
 
 

@@ -33,8 +33,14 @@ __device__ __forceinline__ void trace_mark(int slot)
     if (threadIdx.x == 0 && blockIdx.x < kTraceBlocks)
         teal_trace[blockIdx.x * kTraceMarks + slot] = wall_clock64();
 }
+__device__ __forceinline__ void trace_mark_thread(int slot, int thread)
+{
+    if ((int)threadIdx.x == thread && blockIdx.x < kTraceBlocks)
+        teal_trace[blockIdx.x * kTraceMarks + slot] = wall_clock64();
+}
 #else
 __device__ __forceinline__ void trace_mark(int) {}
+__device__ __forceinline__ void trace_mark_thread(int, int) {}
 #endif
 
 // Weight bytes are used exactly once: load them non-temporal so they do not
@@ -606,6 +612,7 @@ __device__ __forceinline__ bool block_finish(float *red,
     for (int k = 0; k < OWN; ++k)
         scale[k] = F::column_scale(a, col0 + min((int)threadIdx.x + k * THREADS, cols - 1));
     __syncthreads();                   // every wavefront has left its sums in red[]
+    trace_mark(7);
     constexpr int ROW = combine_row<EPL, LPR>;
     if (tile == 0 && threadIdx.x == 0) report_slice(report, s, splits, cnt);
     if (splits == 1) {
@@ -735,6 +742,7 @@ __device__ __forceinline__ bool gemv_block(const typename F::Args &a, const XS &
     for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
     stream_rows<F, LPR, U>(acc, list, start, mine, lane_base, row_bytes);
     trace_mark(3);
+    trace_mark_thread(1, (WAVES - 1) * 64);
     store_wave_sums<LPR>(acc, red + (threadIdx.x >> 6) * combine_row<EPL, LPR>);
     return block_finish<F, LPR, WAVES>(red, partial, counters, y, tile, col0, tile_cols, s, splits,
                                        n, a, cnt, report);
@@ -750,9 +758,11 @@ __global__ __launch_bounds__(WAVES * 64) void sparse_gemv_kernel(
     typename F::Args a, const __half *__restrict__ x, float t, float *partial, int *counters,
     float *y, int m, int n, int ks, int tiles, int tile_cols, int splits)
 {
+    trace_mark(0);
     gemv_block<F, LPR, WAVES, U>(a, HalfSource{x}, t, partial, counters, y, m, n, ks,
                                  blockIdx.x % tiles, blockIdx.x / tiles, tile_cols, splits,
                                  survivor_report(counters, 0, splits));
+    trace_mark(6);
 }
 
 // The W_down step with its input formed in the kernel from the two products that

@@ -139,6 +139,7 @@ __device__ __forceinline__ bool w4_block(const FmtW4::Args &a, const XS &x,
         cnt = compact_slice<WAVES>(x, t, k0, k1, list, seg_cnt, seg_excl);
     }
 
+    trace_mark(2);
     const int lane = threadIdx.x & 63;
     const int g = lane / LPR;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -157,50 +158,50 @@ __device__ __forceinline__ bool w4_block(const FmtW4::Args &a, const XS &x,
     wave_share(cnt, w, WAVES, start, mine);
     // Walk state (all wavefront-uniform): next list position, end of the share, current
     // group of the slice and the end of this wavefront's rows in it.
-    int cur = start;
-    const int end = start + mine;
-    int gi = -1, gend = start;
     // list offset at which group j of the slice begins: the prefix of segment 2j (lanes past
     // the last segment hold the total)
     auto group_begin = [&](int j) {
         return 2 * j < 64 ? __builtin_amdgcn_readlane(seg_excl, 2 * j) : cnt;
     };
+    int cur = start;
+    const int end = start + mine;
+    int gi = 0, gend = min(end, group_begin(1));
 
+    // Every call issues exactly U row loads and the four scale loads of the batch's group,
+    // whether or not rows are left: the compiler then knows how many loads are outstanding at
+    // every wait and waits for a batch's own loads only.  (With a conditional scale load and an
+    // early return for an exhausted share it waited for older loads between the loads of a
+    // batch, and little more than one batch was ever in flight.)  A batch past the end of the
+    // share re-reads the share's last row with zero multipliers.
     auto issue = [&](W4Batch<U> &b) {
-        if (cur >= end) {
-            b.rows = 0;
-            b.ends_run = false;
-            return;
+        const bool live = cur < end;                  // wavefront-uniform
+        if (live) {
+            while (cur >= gend) {                     // next group with rows in this share
+                ++gi;
+                gend = min(end, group_begin(gi + 1));
+            }
         }
-        while (cur >= gend) {                     // next group with rows in this share
-            ++gi;
-            gend = min(end, group_begin(gi + 1));
-        }
-        const int nb = min(U * R, gend - cur);
-        const int last = cur + nb - 1;
+        const int nb = live ? min(U * R, gend - cur) : 0;
+        const int last = live ? cur + nb - 1 : end - 1;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int e = cur + u * R + g;
             const int2 ent = list[min(e, last)];
-            b.xv[u] = e <= last ? __int_as_float(ent.y) : 0.f;
+            b.xv[u] = (live && e <= last) ? __int_as_float(ent.y) : 0.f;
             b.v[u] = load_stream16(lane_base + (size_t)(unsigned)ent.x * row_bytes);
         }
         b.rows = nb;
-        b.ends_run = cur + nb == gend;
-        if (b.ends_run) {
-            const uint4 *sp = reinterpret_cast<const uint4 *>(scale_base + (size_t)gi * n);
+        b.ends_run = live && cur + nb == gend;
+        const uint4 *sp = reinterpret_cast<const uint4 *>(scale_base + (size_t)gi * n);
 #pragma unroll
-            for (int q = 0; q < 4; ++q) b.sc[q] = sp[q];
-        }
+        for (int q = 0; q < 4; ++q) b.sc[q] = sp[q];
         cur += nb;
     };
     auto consume = [&](const W4Batch<U> &b) {
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            if (u * R < b.rows) {                 // wavefront-uniform
-                F::fma(gacc, b.v[u], b.xv[u]);
-                xsum += b.xv[u];
-            }
+        for (int u = 0; u < U; ++u) {             // slots past the end of a run multiply by zero
+            F::fma(gacc, b.v[u], b.xv[u]);
+            xsum += b.xv[u];
         }
         if (!b.ends_run) return;
         // sum x*q = scale * sum x*v - 8 sum x; then times the group's scale
@@ -222,15 +223,28 @@ __device__ __forceinline__ bool w4_block(const FmtW4::Args &a, const XS &x,
         xsum = 0.f;
     };
 
-    W4Batch<U> b0, b1;
-    issue(b0);
-    while (b0.rows > 0) {
-        issue(b1);
-        consume(b0);
-        if (b1.rows <= 0) break;
+    // Two batches in flight.  The fences keep the compiler from sinking a batch's loads into
+    // the consumption of the batch before it.  (A third batch in flight was measured slower:
+    // the row stream of this format is held back by its vector instructions, about 2.2 per
+    // weight with the addressing, issued by two wavefronts per SIMD -- the older of the two
+    // finishes its share 4-5 us before the younger -- not by the loads in flight.)
+    if (mine > 0) {                               // wavefront-uniform
+        W4Batch<U> b0, b1;
         issue(b0);
-        consume(b1);
+        while (b0.rows > 0) {
+            issue(b1);
+            __builtin_amdgcn_sched_barrier(0);
+            consume(b0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (b1.rows <= 0) break;
+            issue(b0);
+            __builtin_amdgcn_sched_barrier(0);
+            consume(b1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
     }
+    trace_mark(3);
+    trace_mark_thread(1, (WAVES - 1) * 64);
     store_wave_sums<LPR>(acc, red + (threadIdx.x >> 6) * combine_row<EPL, LPR>);
     return block_finish<F, LPR, WAVES>(red, partial, counters, y, tile, col0, tile_cols, s, splits,
                                        n, a, cnt, report);
@@ -241,9 +255,11 @@ __global__ __launch_bounds__(WAVES * 64) void sparse_gemv_w4_kernel(
     FmtW4::Args a, const __half *__restrict__ x, float t, float *partial, int *counters, float *y,
     int m, int n, int ks, int tiles, int tile_cols, int splits)
 {
+    trace_mark(0);
     w4_block<LPR, WAVES, U>(a, HalfSource{x}, t, partial, counters, y, m, n, ks,
                             blockIdx.x % tiles, blockIdx.x / tiles, tile_cols, splits,
                             survivor_report(counters, 0, splits));
+    trace_mark(6);
 }
 
 // The int4 product with its input formed in the kernel from the two products that precede
@@ -631,3 +647,22 @@ hipError_t launch_mlp_w4(const MlpHostArgs &h, const MlpLaunch &L, hipStream_t s
 }
 
 }  // namespace teal
+
+#ifdef TEAL_TRACE_BLOCKS
+// The trace build's read-out for the kernels of this file (see trace_mark in gemv_common.h).
+extern "C" int teal_trace_read_wq(unsigned long long *host, size_t count)
+{
+    const size_t all = (size_t)teal::kTraceBlocks * teal::kTraceMarks;
+    if (!host || count > all) return 1;
+    if (hipDeviceSynchronize() != hipSuccess) return 2;
+    if (hipMemcpyFromSymbol(host, HIP_SYMBOL(teal::teal_trace),
+                            count * sizeof(unsigned long long)) != hipSuccess)
+        return 3;
+    static unsigned long long zeros[4096];
+    for (size_t at = 0; at < all; at += 4096)
+        if (hipMemcpyToSymbol(HIP_SYMBOL(teal::teal_trace), zeros, sizeof(zeros),
+                              at * sizeof(unsigned long long)) != hipSuccess)
+            return 4;
+    return 0;
+}
+#endif
