@@ -477,23 +477,6 @@ teal_status teal_pack_bf16(const void *W_rowmajor, void *Wt, int m, int n,
                            void *stream);
 
 /*
- * Measurement aid, not part of the method: a plain streaming read of `bytes`
- * bytes at `buf` with the 16-byte non-temporal loads of the row stream and no
- * other work, by `blocks` thread blocks of 512 threads.  Section 3 argues that
- * decoding is bound by the rate at which weights can be moved; this gives the
- * rate a kernel that only reads reaches on the part for a launch of that
- * size, to set beside the published peak.  Each thread folds the words it
- * reads with XOR (which keeps the loads alive); a thread whose fold equals
- * `match` stores `match` to sink[its block index], so with a value that does
- * not occur nothing is written.
- *   buf    device memory, 16-byte aligned; bytes a multiple of 16, >= 16.
- *   blocks 1..65536.
- *   sink   [blocks] uint32, device memory.
- */
-teal_status teal_stream_read_probe(const void *buf, size_t bytes, int blocks, uint32_t match,
-                                   uint32_t *sink, void *stream);
-
-/*
  * teal_sparse_gemv_bf16 with the launch shape chosen by the caller instead
  * of by the library; for tuning and for tests that walk the kernel variants.
  * Results are identical in meaning (the summation order differs with the

@@ -3,6 +3,7 @@
 // synchronises; the only state kept is the per-device address of the
 // library's own scratch array (teal_sparse_gemv_bf16_static).
 #include "teal.h"
+#include "teal_probe.h"
 
 #include <atomic>
 #include <cmath>

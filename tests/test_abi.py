@@ -27,9 +27,14 @@ def _built():
 
 
 def _declared_functions():
-    text = open(os.path.join(ROOT, "include", "teal.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(teal_[a-z0-9_]+)\s*\(", text)))
+    """Every function the installed headers declare: teal.h (the method) and teal_probe.h
+    (measurement aids, kept apart)."""
+    names = set()
+    for header in ("teal.h", "teal_probe.h"):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names.update(re.findall(r"\b(teal_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_every_declared_symbol_is_exported():
@@ -436,6 +441,44 @@ def test_plan_is_reported():
     assert T.teal_gemv_plan_multi(16, 4096, [64, 0])[0] == T.TEAL_ERR_SHAPE
 
 
+# (lanes per row, tile columns, splits, thread blocks) the launch rule gives for the
+# projections of the benchmark configurations: the shapes the measured figures belong to.
+PLANNED_GRIDS = {
+    ("llama2_7b", 16): {"q": (16, 128, 8, 256), "gate": (64, 384, 8, 232), "down": (16, 128, 8, 256),
+                        "q+k+v": (32, 256, 5, 240), "gate+up": (64, 448, 5, 250)},
+    ("llama3_8b", 16): {"q": (16, 128, 8, 256), "k": (16, 128, 16, 128), "gate": (64, 448, 8, 256),
+                        "down": (16, 128, 8, 256), "q+k+v": (16, 128, 5, 240), "gate+up": (64, 448, 4, 256)},
+    ("llama_70b", 16): {"q": (32, 256, 8, 256), "k": (16, 128, 16, 128), "gate": (64, 512, 4, 224),
+                        "down": (32, 256, 8, 256), "q+k+v": (16, 128, 3, 240), "gate+up": (64, 448, 2, 256)},
+    ("llama3_8b", 8): {"q": (8, 128, 8, 256), "gate": (32, 512, 8, 224), "down": (8, 128, 8, 256),
+                       "q+k+v": (8, 128, 5, 240), "gate+up": (64, 896, 8, 256)},
+    ("llama3_8b", 4): {"q": (16, 512, 16, 128), "gate": (16, 512, 8, 224), "down": (16, 512, 16, 128),
+                       "q+k+v": (16, 512, 16, 192), "gate+up": (32, 1024, 8, 224)},
+}
+
+
+@pytest.mark.parametrize("model,bits", sorted(PLANNED_GRIDS))
+def test_planned_grids_of_the_benchmark_configurations(model, bits):
+    """The launch rule is a set of constants from sweeps on one chip (256 compute units): about
+    one block of 8 wavefronts per unit, at most 16 splits, tiles on 128-byte boundaries.  This
+    pins what it yields for the benchmark's shapes, so a change of the rule shows up here."""
+    import teal_inputs as ti
+    shapes = ti.LAYER_SHAPES[model]
+    for name, want in PLANNED_GRIDS[(model, bits)].items():
+        members = name.split("+")
+        ns = [shapes[p][0] for p in members]
+        m = shapes[members[0]][1]
+        if len(ns) == 1:
+            st, p = T.teal_gemv_plan(bits, m, ns[0])
+        else:
+            st, p = T.teal_gemv_plan_multi(bits, m, ns)
+        assert st == T.TEAL_OK
+        blocks = sum(-(-n // p["tile_cols"]) for n in ns) * p["splits"]
+        assert (p["lanes_per_row"], p["tile_cols"], p["splits"], blocks) == want, (name, p, blocks)
+        assert p["waves"] == 8 and p["unroll"] == 4
+        assert blocks <= 256 and p["tile_cols"] * bits % (8 * 128) == 0   # fills the chip once; 128-byte edges
+
+
 def test_sparsify_and_pack_argument_errors():
     assert T.teal_sparsify(None, 16, 0.5, Y, None, None, stream=0) == T.TEAL_ERR_NULL
     assert T.teal_sparsify(X, -1, 0.5, Y, None, None, stream=0) == T.TEAL_ERR_SHAPE
@@ -639,7 +682,7 @@ def test_header_is_plain_c_and_links_against_the_library(tmp_path):
     names = _declared_functions()
     src = tmp_path / "use_teal.c"
     body = "\n".join(f"    p[{i}] = (void (*)(void))&{n};" for i, n in enumerate(names))
-    src.write_text('#include "teal.h"\n#include <stdio.h>\nint main(void)\n{\n'
+    src.write_text('#include "teal.h"\n#include "teal_probe.h"\n#include <stdio.h>\nint main(void)\n{\n'
                    f"    void (*p[{len(names)}])(void);\n{body}\n"
                    f"    printf(\"%d %s\\n\", teal_version(), teal_status_string(TEAL_OK));\n"
                    f"    return p[0] == 0;\n}}\n")
