@@ -12,9 +12,10 @@
 // precedes, in block order, a producer it waits for.
 //
 // Readiness.  A gate / up tile is finished when the block that combines its K-slices has
-// written its columns of y; that block then adds one to ready[s] for every K-slice s of
-// W_down that reads any of those columns.  A block of W_down with K-slice s waits until
-// ready[s] equals mlp_expected(s) = the number of gate and up tiles that overlap the slice.
+// written its columns of y; that block then adds one to the readiness counter of every
+// block of W_down whose K-slice reads any of those columns (one counter per W_down block:
+// a counter polled by one block only).  A block of W_down with K-slice s waits until its
+// counter equals mlp_expected(s) = the number of gate and up tiles that overlap the slice.
 #pragma once
 
 #if defined(__HIPCC__)

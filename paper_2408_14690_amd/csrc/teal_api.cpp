@@ -247,7 +247,7 @@ const char *teal_status_string(teal_status s)
     return "unknown status";
 }
 
-int teal_version(void) { return 400; }
+int teal_version(void) { return 410; }
 
 size_t teal_survivors_offset(void) { return teal::kCounterBytes; }
 
