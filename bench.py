@@ -119,7 +119,9 @@ def llama3_8b_block_detail(T, torch, fmt: str, p_head: float):
     mlp_out = {"note": "gate and up read x, W_down reads h = SiLU(gate) * up formed from their "
                        "outputs (Appendix A.3): the dependent sequence a decoder runs",
                "effective_bytes": mlp.bytes(p_head)}
-    for mode in ("one_launch", "two_launches", "three_launches"):
+    modes = ("one_launch", "two_launches", "three_launches") + \
+        (("one_launch_padded_rows",) if fmt == "bf16" else ())
+    for mode in modes:
         mlp.mode = mode
         us = time_projection(T, torch, mlp, p_head, 300) * 1e6
         us_dense = time_projection(T, torch, mlp, 0.0, 300) * 1e6
@@ -130,6 +132,20 @@ def llama3_8b_block_detail(T, torch, fmt: str, p_head: float):
     if fmt == "bf16":
         st, sh = T.teal_mlp_plan(16, mlp.m, mlp.f, mlp.d)
         mlp_out["one_launch"]["shape"] = sh.as_dict()
+        mlp_out["one_launch_padded_rows"]["shape"] = mlp.padded_shape.as_dict()
+        mlp_out["one_launch_padded_rows"]["note"] = (
+            "the same matrices stored with rows 256 bytes further apart (row pitch f + 128 and "
+            "d + 128 elements): every block's reads then spread evenly over the memory channels")
+        # the padded layout must not change a bit of the result
+        outs = {}
+        for mode in ("one_launch", "one_launch_padded_rows"):
+            mlp.mode = mode
+            T.check(mlp._enqueue(T, 0, p_head))
+            torch.cuda.synchronize()
+            outs[mode] = (mlp.g.clone(), mlp.u.clone(), mlp.y.clone())
+        mlp_out["one_launch_padded_rows"]["bitwise_equal_to_one_launch"] = all(
+            torch.equal(a.view(torch.int32), b.view(torch.int32))
+            for a, b in zip(outs["one_launch"], outs["one_launch_padded_rows"]))
     mlp.mode = "one_launch"
     one_step(T, [mlp], p_head, 0)
     torch.cuda.synchronize()

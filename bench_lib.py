@@ -541,7 +541,11 @@ class MlpCall:
     other as in a decoder.  Issued three ways: one launch (teal_sparse_mlp_*), two (the
     grouped gate + up call, then W_down with its input formed in the kernel), or three (gate,
     up, W_down each on its own).  The threshold of W_down is the quantile of |h| for the h
-    the library's own producer forms from the gate / up outputs at that sparsity."""
+    the library's own producer forms from the gate / up outputs at that sparsity.
+    "one_launch_padded_rows" (bf16) is the one launch on copies of the same matrices stored
+    with rows 256 bytes further apart (teal_mlp_shape's row pitches; same bytes read)."""
+
+    PAD = 128      # bf16 elements added to a row's pitch: an odd multiple of 256 bytes
 
     def __init__(self, T, torch, gate, up, down, sparsities):
         self.gate, self.up, self.down = gate, up, down
@@ -556,6 +560,8 @@ class MlpCall:
         self.ws_gu = torch.zeros(T.teal_workspace_bytes(self.m, 2 * self.f), dtype=torch.uint8,
                                  device="cuda")
         self.mode = "one_launch"
+        self.torch = torch
+        self.padded, self.padded_shape = None, None
         self.t_down, self.nnz_h, self.prepared = {}, {}, {}
         h = torch.empty(self.f, dtype=torch.int16, device="cuda")
         for p in sparsities:
@@ -566,12 +572,41 @@ class MlpCall:
             self.t_down[p] = ti.quantile_threshold(hh, p)
             self.nnz_h[p] = int(np.count_nonzero(np.abs(hh.astype(np.float32)) > np.float32(self.t_down[p])))
 
+    def _pad_weights(self, T):
+        """Padded-row copies of the bf16 matrices, one per weight copy, and the shape that
+        names their pitches."""
+        torch = self.torch
+
+        def pad(w, pitch):
+            out = torch.zeros((w.shape[0], pitch), dtype=w.dtype, device="cuda")
+            out[:, :w.shape[1]] = w
+            return out
+
+        pg, pd = self.f + self.PAD, self.d + self.PAD
+        G, U, D = self.gate, self.up, self.down
+        self.padded = [(pad(G.weights[c][0], pg), pad(U.weights[c % len(U.weights)][0], pg),
+                        pad(D.weights[c % len(D.weights)][0], pd)) for c in range(len(G.weights))]
+        st, sh = T.teal_mlp_plan(16, self.m, self.f, self.d)
+        T.check(st)
+        sh.gu_row_pitch, sh.down_row_pitch = pg, pd
+        self.padded_shape = sh
+
     def _enqueue(self, T, copy, p, t_down=None):
         G, U, D = self.gate, self.up, self.down
         wg, wu, wd = G.wp[copy % len(G.wp)], U.wp[copy % len(U.wp)], D.wp[copy % len(D.wp)]
         td = self.t_down[p] if t_down is None else t_down
         gp, up_, yp = self.g.data_ptr(), self.u.data_ptr(), self.y.data_ptr()
         m, f, d, st = self.m, self.f, self.d, self.stream
+        if self.mode == "one_launch_padded_rows":
+            if self.fmt != "bf16":
+                raise ValueError("padded rows are timed for bf16 only")
+            if self.padded is None:
+                self._pad_weights(T)
+            w = self.padded[copy % len(self.padded)]
+            return T.teal_sparse_mlp_bf16(w[0].data_ptr(), w[1].data_ptr(), w[2].data_ptr(), G.xp,
+                                          G.t[p], U.t[p], td, gp, up_, yp, m, f, d,
+                                          self.ws.data_ptr(), self.ws.numel(), st,
+                                          shape=self.padded_shape)
         if self.mode == "one_launch":
             wsp, wsb = self.ws.data_ptr(), self.ws.numel()
             if self.fmt == "bf16":

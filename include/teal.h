@@ -411,7 +411,16 @@ teal_status teal_sparse_gemv_w4_multi(int count, const uint8_t *const *Wq,
  *           columns of gate and up are finished first (0 = one phase);
  *           extra_lds_bytes (0..49152) of unused shared memory per block lower
  *           the number of blocks resident per compute unit; spin_limit is the
- *           number of polls after which a waiting block gives up.
+ *           number of polls after which a waiting block gives up;
+ *           gu_row_pitch / down_row_pitch: elements from one row of W_gate and
+ *           W_up (of W_down) to the next, for matrices stored with padded
+ *           rows: 0 = f (d), else >= f (d) and a multiple of 8 (16 for int8;
+ *           int4 rows are always packed: must be 0).  The matrices then
+ *           span m * gu_row_pitch (f * down_row_pitch) elements, the last
+ *           row included.  A pitch of an odd multiple of 256 bytes (f + 128
+ *           bf16 elements when 2 f is a multiple of 1024) spreads every
+ *           block's reads evenly over the memory channels; teal_mlp_plan
+ *           leaves both at 0, since the layout is the caller's.
  * Waits are bounded.  A block of W_down that does not see its inputs within
  * spin_limit polls stores 1 to the int32 status word at byte
  * teal_mlp_status_offset(m, f, d) of the workspace and leaves, and so does
@@ -442,6 +451,7 @@ typedef struct teal_mlp_shape {
     int down_lanes_per_row, down_tile_cols, down_splits;
     int extra_lds_bytes;
     int spin_limit;
+    int gu_row_pitch, down_row_pitch;
 } teal_mlp_shape;
 size_t teal_workspace_bytes_mlp(int m, int f, int d);
 size_t teal_mlp_down_region_offset(int m, int f);
@@ -475,6 +485,13 @@ teal_status teal_sparse_mlp_w4(const uint8_t *Wq_gate, const uint8_t *Wq_up,
  */
 teal_status teal_pack_bf16(const void *W_rowmajor, void *Wt, int m, int n,
                            void *stream);
+/*
+ * The same with padded rows: element (i, j) of Wt goes to Wt[i * row_pitch + j],
+ * row_pitch >= n elements (the layout teal_mlp_shape's row pitches describe).
+ * Wt spans (m - 1) * row_pitch + n elements; the padding is left untouched.
+ */
+teal_status teal_pack_bf16_pitch(const void *W_rowmajor, void *Wt, int m, int n, int row_pitch,
+                                 void *stream);
 
 /*
  * teal_sparse_gemv_bf16 with the launch shape chosen by the caller instead

@@ -11,7 +11,7 @@ from .binding import (  # noqa: F401
     TealError, check, library_path, load_library, prepare,
     teal_status_string, teal_version, teal_workspace_bytes,
     teal_sparsify, teal_sparse_gemv_bf16, teal_sparse_gemv_bf16_ex,
-    teal_sparse_gemv_w8, teal_sparse_gemv_w4, teal_pack_bf16, teal_gemv_plan,
+    teal_sparse_gemv_w8, teal_sparse_gemv_w4, teal_pack_bf16, teal_pack_bf16_pitch, teal_gemv_plan,
     teal_sparse_gemv_bf16_multi, teal_abs_histogram, teal_histogram_thresholds, TEAL_HIST_BINS,
     teal_workspace_bytes_batch, teal_sparsify_batch, teal_sparse_gemv_bf16_batch,
     teal_sparse_gemv_bf16_batch_ex, TEAL_MAX_BATCH, teal_sparse_gemv_w8_multi,

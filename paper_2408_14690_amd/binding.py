@@ -27,7 +27,7 @@ _lib = None
 EXPORTS = (
     "teal_status_string", "teal_version", "teal_workspace_bytes", "teal_sparsify",
     "teal_sparse_gemv_bf16", "teal_sparse_gemv_bf16_ex", "teal_sparse_gemv_w8",
-    "teal_sparse_gemv_w4", "teal_pack_bf16", "teal_gemv_plan", "teal_sparse_gemv_bf16_multi",
+    "teal_sparse_gemv_w4", "teal_pack_bf16", "teal_pack_bf16_pitch", "teal_gemv_plan", "teal_sparse_gemv_bf16_multi",
     "teal_abs_histogram", "teal_histogram_thresholds", "teal_workspace_bytes_batch",
     "teal_sparsify_batch", "teal_sparse_gemv_bf16_batch", "teal_sparse_gemv_bf16_batch_ex",
     "teal_sparse_gemv_w8_multi", "teal_sparse_gemv_w4_multi",
@@ -50,7 +50,8 @@ class MlpShape(ctypes.Structure):
     """teal_mlp_shape of include/teal.h."""
     _fields_ = [(name, ctypes.c_int) for name in (
         "gu_lanes_per_row", "gu_tile_cols", "gu_splits", "gu_phase_tiles",
-        "down_lanes_per_row", "down_tile_cols", "down_splits", "extra_lds_bytes", "spin_limit")]
+        "down_lanes_per_row", "down_tile_cols", "down_splits", "extra_lds_bytes", "spin_limit",
+        "gu_row_pitch", "down_row_pitch")]
 
     def as_dict(self):
         return {name: getattr(self, name) for name, _ in self._fields_}
@@ -109,6 +110,8 @@ def load_library():
     lib.teal_sparse_gemv_w4.argtypes = [vp, vp, i, vp, f, vp, i, i, vp, sz, vp]
     lib.teal_pack_bf16.restype = i
     lib.teal_pack_bf16.argtypes = [vp, vp, i, i, vp]
+    lib.teal_pack_bf16_pitch.restype = i
+    lib.teal_pack_bf16_pitch.argtypes = [vp, vp, i, i, i, vp]
     lib.teal_sparse_gemv_bf16_multi.restype = i
     lib.teal_sparse_gemv_bf16_multi.argtypes = [i, c.POINTER(vp), c.POINTER(f), c.POINTER(vp),
                                                 c.POINTER(i), vp, i, vp, sz, vp]
@@ -355,6 +358,12 @@ def teal_pack_bf16(W_rowmajor, Wt, m, n, stream=None) -> int:
     return _call("teal_pack_bf16", _ptr(W_rowmajor, 2 * m * n, "W"), _ptr(Wt, 2 * m * n, "Wt"),
                                          int(m), int(n),
                                          _stream(stream))
+
+
+def teal_pack_bf16_pitch(W_rowmajor, Wt, m, n, row_pitch, stream=None) -> int:
+    return _call("teal_pack_bf16_pitch", _ptr(W_rowmajor, 2 * m * n, "W"),
+                 _ptr(Wt, 2 * ((m - 1) * max(int(row_pitch), n) + n), "Wt"), int(m), int(n),
+                 int(row_pitch), _stream(stream))
 
 
 def teal_gemv_plan(weight_bits: int, m: int, n: int):
@@ -673,6 +682,13 @@ def _mlp_shape(shape):
     return MlpShape(**{k: int(v) for k, v in dict(shape).items()})
 
 
+def _mlp_pitches(sh, f, d):
+    """Row pitches (elements) a shape gives the matrices: what sizes the weight buffers."""
+    pg = sh.gu_row_pitch if sh is not None and sh.gu_row_pitch > f else f
+    pd = sh.down_row_pitch if sh is not None and sh.down_row_pitch > d else d
+    return int(pg), int(pd)
+
+
 def teal_mlp_plan(weight_bits: int, m: int, f: int, d: int):
     """Returns (status, MlpShape): the launch shape the library picks."""
     sh = MlpShape()
@@ -693,10 +709,11 @@ def teal_mlp_block_info(weight_bits: int, m: int, f: int, d: int, shape, block: 
 def teal_sparse_mlp_bf16(Wt_gate, Wt_up, Wt_down, x_f16, t_gate, t_up, t_down, gate, up, y, m, f, d,
                          workspace, workspace_bytes=None, stream=None, shape=None) -> int:
     sh = _mlp_shape(shape)
+    pg, pd = _mlp_pitches(sh, f, d)
     return _call(
         "teal_sparse_mlp_bf16",
-        _ptr(Wt_gate, 2 * m * f, "Wt_gate"), _ptr(Wt_up, 2 * m * f, "Wt_up"),
-        _ptr(Wt_down, 2 * f * d, "Wt_down"), _ptr(x_f16, 2 * m, "x"), float(t_gate), float(t_up),
+        _ptr(Wt_gate, 2 * ((m - 1) * pg + f), "Wt_gate"), _ptr(Wt_up, 2 * ((m - 1) * pg + f), "Wt_up"),
+        _ptr(Wt_down, 2 * ((f - 1) * pd + d), "Wt_down"), _ptr(x_f16, 2 * m, "x"), float(t_gate), float(t_up),
         float(t_down), _ptr(gate, 4 * f, "gate"), _ptr(up, 4 * f, "up"), _ptr(y, 4 * d, "y"),
         int(m), int(f), int(d), _ptr(workspace), _nbytes(workspace, workspace_bytes),
         _stream(stream), ctypes.pointer(sh) if sh is not None else None)
@@ -706,9 +723,11 @@ def teal_sparse_mlp_w8(Wq_gate, Wq_up, Wq_down, scale_gate, scale_up, scale_down
                        t_up, t_down, gate, up, y, m, f, d, workspace, workspace_bytes=None,
                        stream=None, shape=None) -> int:
     sh = _mlp_shape(shape)
+    pg, pd = _mlp_pitches(sh, f, d)
     return _call(
         "teal_sparse_mlp_w8",
-        _ptr(Wq_gate, m * f, "Wq_gate"), _ptr(Wq_up, m * f, "Wq_up"), _ptr(Wq_down, f * d, "Wq_down"),
+        _ptr(Wq_gate, (m - 1) * pg + f, "Wq_gate"), _ptr(Wq_up, (m - 1) * pg + f, "Wq_up"),
+        _ptr(Wq_down, (f - 1) * pd + d, "Wq_down"),
         _ptr(scale_gate, 2 * f, "scale_gate"), _ptr(scale_up, 2 * f, "scale_up"),
         _ptr(scale_down, 2 * d, "scale_down"), _ptr(x_f16, 2 * m, "x"), float(t_gate), float(t_up),
         float(t_down), _ptr(gate, 4 * f, "gate"), _ptr(up, 4 * f, "up"), _ptr(y, 4 * d, "y"),

@@ -10,6 +10,7 @@ struct FmtBF16 {
     static constexpr int kBitsPerElem = 16;
     struct Args {
         const void *W;
+        int ld = 0;             // elements from one row of W to the next; 0 = n
     };
     // bf16 -> fp32 is a 16-bit shift; bf16 * fp16 is exact in fp32 (8 + 11 significand bits).
     static __device__ __forceinline__ void fma(float (&acc)[8], u32x4 v, float xv)
@@ -157,7 +158,10 @@ hipError_t launch_mlp_bf16(const MlpHostArgs &h, const MlpLaunch &L, hipStream_t
     MlpArgs<FmtBF16> A{};
     size_t lds;
     if (!fill_mlp_args<FmtBF16>(A, lds, h, L, 64,
-                                [](FmtBF16::Args &a, const void *W, const void *) { a.W = W; }))
+                                [](FmtBF16::Args &a, const void *W, const void *, int pitch) {
+                                    a.W = W;
+                                    a.ld = pitch;
+                                }))
         return hipErrorInvalidValue;
     return launch_mlp_kernel<GemvBody<FmtBF16>, false>(A, L.gu.lanes_per_row,
                                                        L.down.lanes_per_row, lds, stream);

@@ -733,7 +733,7 @@ __device__ __forceinline__ bool gemv_block(const typename F::Args &a, const XS &
 
     const int col0 = tile * tile_cols;
     const int col = lane_column<EPL>(col0, tile_cols, n, lane % LPR);
-    const unsigned row_bytes = (unsigned)((size_t)n * F::kBitsPerElem / 8);
+    const unsigned row_bytes = (unsigned)((size_t)(a.ld ? a.ld : n) * F::kBitsPerElem / 8);
     const unsigned char *lane_base =
         static_cast<const unsigned char *>(a.W) + (size_t)col * F::kBitsPerElem / 8;
 

@@ -183,9 +183,9 @@ bool fill_mlp_args(MlpArgs<F> &A, size_t &lds, const MlpHostArgs &h, const MlpLa
 {
     GemvGeometry ggu, gd;
     if (!mlp_grid(A.grid, ggu, gd, L, h.m, h.f, h.d, F::kElemsPerLane, ks_multiple)) return false;
-    set_args(A.a_gu[0], h.W_gate, h.scale_gate);
-    set_args(A.a_gu[1], h.W_up, h.scale_up);
-    set_args(A.a_d, h.W_down, h.scale_down);
+    set_args(A.a_gu[0], h.W_gate, h.scale_gate, h.gu_pitch);
+    set_args(A.a_gu[1], h.W_up, h.scale_up, h.gu_pitch);
+    set_args(A.a_d, h.W_down, h.scale_down, h.down_pitch);
     A.y_gu[0] = h.gate;
     A.y_gu[1] = h.up;
     A.t_gu[0] = h.t_gate;

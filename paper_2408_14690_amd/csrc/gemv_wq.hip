@@ -15,6 +15,7 @@ struct FmtW8 {
     struct Args {
         const void *W;
         const __half *scale;
+        int ld = 0;             // elements from one row of W to the next; 0 = n
     };
     static __device__ __forceinline__ void fma(float (&acc)[16], u32x4 v, float xv)
     {
@@ -610,8 +611,9 @@ hipError_t launch_mlp_w8(const MlpHostArgs &h, const MlpLaunch &L, hipStream_t s
     if (!mlp_shape_ok(L.gu, 16) || !mlp_shape_ok(L.down, 16)) return hipErrorInvalidValue;
     MlpArgs<FmtW8> A{};
     size_t lds;
-    if (!fill_mlp_args<FmtW8>(A, lds, h, L, 64, [](FmtW8::Args &a, const void *W, const void *sc) {
+    if (!fill_mlp_args<FmtW8>(A, lds, h, L, 64, [](FmtW8::Args &a, const void *W, const void *sc, int pitch) {
             set_wq_args(a.W, a.scale, W, sc);
+            a.ld = pitch;
         }))
         return hipErrorInvalidValue;
     return launch_mlp_kernel<GemvBody<FmtW8>, true>(A, L.gu.lanes_per_row, L.down.lanes_per_row,
@@ -622,13 +624,14 @@ hipError_t launch_mlp_w4(const MlpHostArgs &h, const MlpLaunch &L, hipStream_t s
 {
     if (!mlp_shape_ok(L.gu, 32) || !mlp_shape_ok(L.down, 32)) return hipErrorInvalidValue;
     if (h.m % kGroup != 0 || h.f % kGroup != 0) return hipErrorInvalidValue;
+    if (h.gu_pitch != 0 || h.down_pitch != 0) return hipErrorInvalidValue;   // rows are packed
     const auto lanes_ok = [](int l) { return l == 16 || l == 32; };
     if (!lanes_ok(L.gu.lanes_per_row) || !lanes_ok(L.down.lanes_per_row))
         return hipErrorInvalidValue;
     MlpArgs<FmtW4> A{};
     size_t lds;
     if (!fill_mlp_args<FmtW4>(A, lds, h, L, kGroup,
-                              [](FmtW4::Args &a, const void *W, const void *sc) {
+                              [](FmtW4::Args &a, const void *W, const void *sc, int) {
                                   set_wq_args(a.W, a.scale, W, sc);
                               }))
         return hipErrorInvalidValue;

@@ -187,7 +187,7 @@ constexpr int kPackTile = 64;
 // writes run along n (contiguous in Wt).
 __global__ __launch_bounds__(256) void pack_bf16_kernel(const uint16_t *__restrict__ W,
                                                         uint16_t *__restrict__ Wt, int m, int n,
-                                                        int tiles_m)
+                                                        int pitch, int tiles_m)
 {
     __shared__ uint16_t tile[kPackTile][kPackTile + 2];
     const int i0 = (int)(blockIdx.x % tiles_m) * kPackTile;   // input-channel origin
@@ -201,7 +201,7 @@ __global__ __launch_bounds__(256) void pack_bf16_kernel(const uint16_t *__restri
     __syncthreads();
     for (int r = r0; r < kPackTile; r += 4) {
         const int i = i0 + r, j = j0 + c;
-        if (i < m && j < n) Wt[(size_t)i * n + j] = tile[c][r];
+        if (i < m && j < n) Wt[(size_t)i * pitch + j] = tile[c][r];
     }
 }
 
@@ -254,13 +254,14 @@ hipError_t launch_rmsnorm_f16(const float *h, const float *gamma, float eps, voi
     return hipGetLastError();
 }
 
-hipError_t launch_pack_bf16(const void *W_rowmajor, void *Wt, int m, int n, hipStream_t stream)
+hipError_t launch_pack_bf16(const void *W_rowmajor, void *Wt, int m, int n, int pitch,
+                            hipStream_t stream)
 {
     const int tiles_m = (m + kPackTile - 1) / kPackTile;
     const int tiles_n = (n + kPackTile - 1) / kPackTile;
     hipLaunchKernelGGL(pack_bf16_kernel, dim3((unsigned)tiles_m * (unsigned)tiles_n), dim3(256), 0,
                        stream, static_cast<const uint16_t *>(W_rowmajor),
-                       static_cast<uint16_t *>(Wt), m, n, tiles_m);
+                       static_cast<uint16_t *>(Wt), m, n, pitch, tiles_m);
     return hipGetLastError();
 }
 

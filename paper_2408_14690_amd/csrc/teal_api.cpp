@@ -247,7 +247,7 @@ const char *teal_status_string(teal_status s)
     return "unknown status";
 }
 
-int teal_version(void) { return 410; }
+int teal_version(void) { return 411; }
 
 size_t teal_survivors_offset(void) { return teal::kCounterBytes; }
 
@@ -914,7 +914,20 @@ teal_status teal_pack_bf16(const void *W_rowmajor, void *Wt, int m, int n, void 
         (long long)m * (long long)n > (1LL << 40))
         return TEAL_ERR_SHAPE;
     if (!aligned(W_rowmajor, 2) || !aligned(Wt, 2)) return TEAL_ERR_ALIGN;
-    return from_hip(teal::launch_pack_bf16(W_rowmajor, Wt, m, n, static_cast<hipStream_t>(stream)));
+    return from_hip(
+        teal::launch_pack_bf16(W_rowmajor, Wt, m, n, n, static_cast<hipStream_t>(stream)));
+}
+
+teal_status teal_pack_bf16_pitch(const void *W_rowmajor, void *Wt, int m, int n, int row_pitch,
+                                 void *stream)
+{
+    if (!W_rowmajor || !Wt) return TEAL_ERR_NULL;
+    if (m < 1 || n < 1 || m > teal::kMaxDim || n > teal::kMaxDim || row_pitch < n ||
+        row_pitch > (1 << 29) || (long long)m * (long long)row_pitch > (1LL << 40))
+        return TEAL_ERR_SHAPE;
+    if (!aligned(W_rowmajor, 2) || !aligned(Wt, 2)) return TEAL_ERR_ALIGN;
+    return from_hip(teal::launch_pack_bf16(W_rowmajor, Wt, m, n, row_pitch,
+                                           static_cast<hipStream_t>(stream)));
 }
 
 }  // extern "C"
@@ -982,6 +995,8 @@ void mlp_default_shape(const MlpFormat &fm, int m, int f, int d, teal_mlp_shape 
     out->down_splits = dn.splits;
     out->extra_lds_bytes = 0;
     out->spin_limit = kMlpDefaultSpinLimit;
+    out->gu_row_pitch = 0;
+    out->down_row_pitch = 0;
 }
 
 bool mlp_launch_of(const MlpFormat &fm, const teal_mlp_shape &sh, int m, int f, int d,
@@ -990,6 +1005,14 @@ bool mlp_launch_of(const MlpFormat &fm, const teal_mlp_shape &sh, int m, int f, 
     if (sh.gu_phase_tiles < 0 || sh.extra_lds_bytes < 0 || sh.extra_lds_bytes > 48 * 1024 ||
         sh.spin_limit < 0)
         return false;
+    // Row pitches: 0 (rows packed) or at least the row, rows 16-byte aligned, and a row's
+    // bytes within what the kernels address with 32 bits; int4 rows are always packed.
+    const auto pitch_ok = [&](int pitch, int n) {
+        if (pitch == 0) return true;
+        return fm.bits != 4 && pitch >= n && pitch % fm.n_multiple == 0 &&
+               (long long)pitch * fm.bits / 8 <= (1LL << 30);
+    };
+    if (!pitch_ok(sh.gu_row_pitch, f) || !pitch_ok(sh.down_row_pitch, d)) return false;
     L.gu = to_shape(sh.gu_lanes_per_row, sh.gu_tile_cols, sh.gu_splits);
     L.down = to_shape(sh.down_lanes_per_row, sh.down_tile_cols, sh.down_splits);
     L.phase_tiles = sh.gu_phase_tiles;
@@ -1055,7 +1078,8 @@ teal_status mlp_call(int weight_bits, const MlpCall &c, int group, const teal_ml
     unsigned char *control = region_d + teal_workspace_bytes(c.f, c.d);
     const teal::MlpHostArgs h{c.W_gate, c.W_up, c.W_down, c.scale_gate, c.scale_up, c.scale_down,
                               c.x_f16, c.t_gate, c.t_up, c.t_down, c.gate, c.up, c.y, c.m, c.f,
-                              c.d, ws_partials(region_gu, c.m), ws_counters(region_gu),
+                              c.d, shape->gu_row_pitch, shape->down_row_pitch,
+                              ws_partials(region_gu, c.m), ws_counters(region_gu),
                               ws_partials(region_d, c.f), ws_counters(region_d),
                               reinterpret_cast<int *>(control)};
     hipStream_t st = static_cast<hipStream_t>(c.stream);

@@ -153,6 +153,7 @@ struct MlpHostArgs {
     float t_gate, t_up, t_down;
     float *gate, *up, *y;
     int m, f, d;                 // model width in, MLP width, model width out
+    int gu_pitch, down_pitch;    // elements between rows of W_gate / W_up and of W_down; 0 = f, d
     float *partial_gu;
     int *counters_gu;            // head of the gate / up region of the workspace
     float *partial_d;
@@ -177,7 +178,7 @@ hipError_t launch_histogram_thresholds(const unsigned long long *hist, const dou
 hipError_t launch_stream_read(const void *buf, size_t bytes, int blocks, uint32_t match,
                               uint32_t *sink, hipStream_t stream);
 
-hipError_t launch_pack_bf16(const void *W_rowmajor, void *Wt, int m, int n,
+hipError_t launch_pack_bf16(const void *W_rowmajor, void *Wt, int m, int n, int pitch,
                             hipStream_t stream);
 
 }  // namespace teal

@@ -375,3 +375,80 @@ def test_quantised_mlp(T, fmt, m, f, d, over):
     at = T.teal_mlp_down_region_offset(m, f) + o
     got = tuple(ws[o:o + 8].view(torch.int32).cpu().tolist()) + (int(ws[at:at + 4].view(torch.int32).item()),)
     assert got == counts
+
+
+def padded(T, wt, pitch):
+    """The same matrix stored with rows `pitch` elements apart, the padding holding bf16 NaNs
+    (0x7FC0): a kernel that read it into a sum would show it."""
+    k, n = wt.shape
+    out = torch.full((k, pitch), 0x7FC0, dtype=torch.int16, device="cuda")
+    out[:, :n] = wt
+    return out
+
+
+@pytest.mark.parametrize("m,f,d,pg,pd,over", [
+    (520, 1224, 264, 1224 + 8, 264 + 40, dict(gu_lanes_per_row=16, gu_tile_cols=120, gu_splits=3,
+                                             down_lanes_per_row=16, down_tile_cols=72, down_splits=5)),
+    (1024, 1536, 512, 1536 + 128, 0, dict(gu_lanes_per_row=64, gu_tile_cols=512, gu_splits=4,
+                                         down_lanes_per_row=16, down_tile_cols=128, down_splits=1)),
+    (4096, 14336, 4096, 14336 + 128, 4096 + 128, {}),
+])
+def test_padded_rows_give_the_same_bits(T, m, f, d, pg, pd, over):
+    """Row pitches above the row length (teal_mlp_shape): gate, up and y are bit for bit those
+    of the packed layout, the padding is never read into a result, and teal_pack_bf16_pitch
+    writes that layout."""
+    M = Mlp(T, m, f, d, seed=36000 + m)
+    st, sh = T.teal_mlp_plan(16, m, f, d)
+    T.check(st)
+    assert sh.gu_row_pitch == 0 and sh.down_row_pitch == 0
+    for k, v in over.items():
+        setattr(sh, k, v)
+    ws = torch.zeros(T.teal_workspace_bytes_mlp(m, f, d), dtype=torch.uint8, device="cuda")
+    g0, u0, _ = run_mlp(T, M, 0.0, ws, sh)
+    t_down = M.t_down_from(g0.cpu().numpy(), u0.cpu().numpy())
+    gate, up, y = run_mlp(T, M, t_down, ws, sh)
+    check_against_oracle(T, M, gate, up, y, t_down, ws,
+                         rows=None if f <= 4096 else np.arange(0, f, 193).astype(np.int32))
+    packed = M.wt
+    M.wt = [padded(T, packed[0], pg), padded(T, packed[1], pg),
+            padded(T, packed[2], pd) if pd else packed[2]]
+    sh.gu_row_pitch, sh.down_row_pitch = pg, pd
+    gate2, up2, y2 = run_mlp(T, M, t_down, ws, sh)
+    assert bits_equal(gate, gate2) and bits_equal(up, up2) and bits_equal(y, y2)
+    assert status_word(T, M, ws) == 0
+    # the pack step writes this layout and leaves the padding alone
+    wt = torch.full((m, pg), 0x1234, dtype=torch.int16, device="cuda")
+    T.check(T.teal_pack_bf16_pitch(dev(M.w[0]), wt, m, f, pg))
+    torch.cuda.synchronize()
+    assert torch.equal(wt[:, :f], packed[0]) and bool((wt[:, f:] == 0x1234).all())
+
+
+def test_padded_rows_int8(T):
+    m, f, d = 1024, 2048, 1024
+    q, x = quantised(T, "w8", m, f, d, 36500)
+    t = ti.quantile_threshold(x, 0.5)
+    st, sh = T.teal_mlp_plan(8, m, f, d)
+    T.check(st)
+    qd = [dev(a) for a, _ in q]
+    sd = [dev(s_) for _, s_ in q]
+    xd = dev(x)
+    ws = torch.zeros(T.teal_workspace_bytes_mlp(m, f, d), dtype=torch.uint8, device="cuda")
+
+    def run(mats):
+        outs = [torch.full((n,), float("nan"), dtype=torch.float32, device="cuda") for n in (f, f, d)]
+        T.check(T.teal_sparse_mlp_w8(mats[0], mats[1], mats[2], sd[0], sd[1], sd[2], xd, t, t, 0.05,
+                                     outs[0], outs[1], outs[2], m, f, d, ws, shape=sh))
+        torch.cuda.synchronize()
+        return outs
+
+    want = run(qd)
+    pg, pd = f + 256, d + 16
+
+    def pad(a, pitch):
+        out = torch.full((a.shape[0], pitch), 127, dtype=torch.int8, device="cuda")
+        out[:, :a.shape[1]] = a
+        return out
+
+    sh.gu_row_pitch, sh.down_row_pitch = pg, pd
+    got = run([pad(qd[0], pg), pad(qd[1], pg), pad(qd[2], pd)])
+    assert all(bits_equal(a, b) for a, b in zip(want, got))

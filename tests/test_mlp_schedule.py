@@ -218,6 +218,20 @@ def test_plan_and_argument_errors():
     bad = T.MlpShape(**sh.as_dict())
     bad.extra_lds_bytes = 1 << 20
     assert call(shape=bad) == T.TEAL_ERR_UNSUPPORTED
+    # row pitches: 0 (packed rows) is the library's choice; else at least the row and rows 16-byte aligned
+    assert (sh.gu_row_pitch, sh.down_row_pitch) == (0, 0)
+    for field, value in (("gu_row_pitch", f - 8), ("gu_row_pitch", f + 4), ("gu_row_pitch", -8),
+                         ("down_row_pitch", d - 8), ("down_row_pitch", d + 12)):
+        bad = T.MlpShape(**sh.as_dict())
+        setattr(bad, field, value)
+        assert call(shape=bad) == T.TEAL_ERR_UNSUPPORTED
+        assert T.teal_mlp_block_info(16, m, f, d, bad, 0)[0] == T.TEAL_ERR_UNSUPPORTED
+    good = T.MlpShape(**sh.as_dict())
+    good.gu_row_pitch, good.down_row_pitch = f + 128, d + 128
+    assert T.teal_mlp_block_info(16, m, f, d, good, -1)[1][0] == T.teal_mlp_block_info(16, m, f, d, sh, -1)[1][0]
+    assert T.teal_pack_bf16_pitch(W, X, 64, 64, 63, stream=0) == T.TEAL_ERR_SHAPE
+    assert T.teal_pack_bf16_pitch(None, X, 64, 64, 64, stream=0) == T.TEAL_ERR_NULL
+    assert T.teal_pack_bf16_pitch(W, X + 1, 64, 64, 72, stream=0) == T.TEAL_ERR_ALIGN
     # quantised: scales required, int4 group size
     q = dict(Wq_gate=W, Wq_up=W, Wq_down=W, scale_gate=X, scale_up=X, scale_down=X, x_f16=X,
              t_gate=0.5, t_up=0.5, t_down=0.1, gate=Y, up=Y + 0x100000, y=Y + 0x200000, m=m, f=f,
@@ -226,3 +240,10 @@ def test_plan_and_argument_errors():
     assert T.teal_sparse_mlp_w8(**dict(q, d=4104)) == T.TEAL_ERR_SHAPE
     assert T.teal_sparse_mlp_w4(group=64, **q) == T.TEAL_ERR_UNSUPPORTED
     assert T.teal_sparse_mlp_w4(group=128, **dict(q, scale_down=X + 2)) == T.TEAL_ERR_ALIGN
+    st, s4 = T.teal_mlp_plan(4, m, f, d)
+    assert st == T.TEAL_OK
+    s4.gu_row_pitch = f + 128                               # int4 rows are always packed
+    assert T.teal_sparse_mlp_w4(group=128, shape=s4, **q) == T.TEAL_ERR_UNSUPPORTED
+    st, s8 = T.teal_mlp_plan(8, m, f, d)
+    s8.down_row_pitch = d + 8                               # int8 rows: a multiple of 16
+    assert T.teal_sparse_mlp_w8(shape=s8, **q) == T.TEAL_ERR_UNSUPPORTED
