@@ -39,7 +39,8 @@ import time
 import numpy as np
 
 import teal_inputs as ti
-from bench_lib import (BITS, CACHE_DEFEAT_BYTES, HBM_PEAK_GBS, MlpCall, StackCall,  # noqa: F401
+from bench_lib import (BITS, CACHE_DEFEAT_BYTES, HBM_PEAK_GBS, FusedGroup, MlpCall, Projection,  # noqa: F401
+                       StackCall,
                        algorithmic_bytes, build_stack, cpu_baseline, cpu_baseline_one_core,
                        deep_layer_check, fuse, gpu_clocks, measured_traffic, one_step, pct,
                        read_ceiling, survivor_counts_match, time_projection)
@@ -102,6 +103,38 @@ def alone(T, torch, C, p_head, launches=300):
             "weight_bytes_walked": min(P.walked_bytes(p_head) for P in members)}
 
 
+def padded_rows_detail(T, torch, by_name, groups, fmt, sparsities, p_head, packed_per_step):
+    """W_gate and W_up stored with rows 256 bytes further apart (the library's _pitch entry
+    points; the same weights and input): the pair in one launch, one of them alone, and the
+    block pass with the pair's launch replaced.  With such rows the pair runs in tiles of
+    256 bytes of a row without split-K."""
+    pad = 256 * 8 // BITS[fmt]
+    G, U = by_name["gate"], by_name["up"]
+    wide = [Projection(T, torch, P.name, P.n, P.m, fmt, P.x_host, sparsities, len(P.weights),
+                       w_host=P.w_host, row_pad=pad) for P in (G, U)]
+    pair = FusedGroup(T, torch, wide)
+    out = {"row_pitch_elements": wide[0].pitch,
+           "launch": T.teal_gemv_plan_multi_pitch(BITS[fmt], G.m, [G.n, U.n], [wide[0].pitch] * 2)[1]}
+    # same sums as the packed call, in another order: compared by value
+    packed_pair = next(g for g in groups if g.name == "gate+up")
+    worst = 0.0
+    for call, members in ((packed_pair, (G, U)), (pair, wide)):
+        T.check(call.enqueue(T, 0, p_head))
+    torch.cuda.synchronize()
+    for a, b in zip((G, U), wide):
+        ya, yb = a.y.double(), b.y.double()
+        worst = max(worst, float((ya - yb).norm() / ya.norm()))
+    out["rel_l2_vs_packed_rows"] = worst
+    out["gate+up"] = alone(T, torch, pair, p_head)
+    out["gate"] = alone(T, torch, wide[0], p_head)
+    out["gate"]["launch"] = T.teal_gemv_plan_multi_pitch(BITS[fmt], G.m, [G.n], [wide[0].pitch])[1]
+    swapped = [pair if g.name == "gate+up" else g for g in groups]
+    per_step = time_pass(T, torch, swapped, p_head, 200, 50, 5)
+    dense = time_pass(T, torch, swapped, 0.0, 200, 50, 5)
+    out["block_pass_one_launch_per_group"] = pass_figures(swapped, p_head, per_step, dense)
+    return out
+
+
 def llama3_8b_block_detail(T, torch, fmt: str, p_head: float):
     """The 4096 x 14336-class shapes (both orientations) in a driver-run record: a
     Llama-3-8B-shaped block, bf16 unless another format was asked for, 50 % and dense."""
@@ -159,6 +192,9 @@ def llama3_8b_block_detail(T, torch, fmt: str, p_head: float):
             continue
         out["per_projection_alone"][P.name] = alone(T, torch, P, p_head)
         out["per_projection_alone"][P.name]["launch"] = T.teal_gemv_plan(BITS[fmt], P.m, P.n)[1]
+    if fmt in ("bf16", "w8"):
+        out["padded_rows"] = padded_rows_detail(T, torch, by_name, groups, fmt, sparsities, p_head,
+                                                per_step)
     del mlp, groups, block
     torch.cuda.empty_cache()
     return out
@@ -180,6 +216,9 @@ def main() -> int:
     ap.add_argument("--unfused", action="store_true", help="one launch per projection (7 per block)")
     ap.add_argument("--stack-launch", action="store_true",
                     help="16 groups per launch as independent work (a bare stack of projections)")
+    ap.add_argument("--rows", default="padded", choices=("padded", "packed"),
+                    help="padded: W_gate and W_up stored with rows 256 bytes further apart where that "
+                         "lets the pair run without split-K (bf16 / int8, one launch per group)")
     ap.add_argument("--no-detail", action="store_true",
                     help="skip the Llama-3-8B-shaped block detail and the plain-read ceiling")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -215,8 +254,18 @@ def main() -> int:
     # consecutive steps walk several copies of a small workload's weights; a stack beyond the
     # last-level cache many times over needs none
     copies = args.copies or max(1, -(-CACHE_DEFEAT_BYTES // (block_bytes * layers)))
+    # Layout of W_gate / W_up: rows 256 bytes further apart when the library then runs the
+    # pair without split-K (teal_gemv_plan_multi_pitch); the layout is the library's own step
+    # (teal_pack_bf16_pitch), the bytes read are the same.
+    row_pad, rows = {}, "packed"
+    if args.rows == "padded" and fmt in ("bf16", "w8") and not args.stack_launch and not args.unfused:
+        pad = 256 * 8 // BITS[fmt]
+        n_gu, m_gu = shapes["gate"]
+        st, plan = T.teal_gemv_plan_multi_pitch(BITS[fmt], m_gu, [n_gu, n_gu], [n_gu + pad] * 2)
+        if st == 0 and plan["splits"] == 1:
+            row_pad, rows = {"gate": pad, "up": pad}, "padded"
     t_build = time.perf_counter()
-    projections = build_stack(T, torch, args.workload, fmt, sparsities, layers, copies)
+    projections = build_stack(T, torch, args.workload, fmt, sparsities, layers, copies, row_pad=row_pad)
     block0 = projections[:7]
     groups = fuse(T, torch, projections)
     if args.stack_launch:
@@ -246,7 +295,8 @@ def main() -> int:
               ("w4", "grouped"): "sparse_gemv_w4_multi_kernel",
               ("w4", "per_projection"): "sparse_gemv_w4_kernel",
               ("w4", "stack"): "sparse_gemv_w4_stack_kernel"}[(fmt, mode)]
-    traffic, traffic_source = measured_traffic(args.workload, fmt, head, layers, mode, T.teal_version())
+    traffic, traffic_source = measured_traffic(args.workload, fmt, head, layers, mode, T.teal_version(),
+                                               rows=rows)
     launches_text = {"grouped": "one per group of projections that read the same hidden state (q+k+v, o, "
                                 "gate+up, down), each projection with its own threshold: the calls a "
                                 "decoder would make",
@@ -273,6 +323,8 @@ def main() -> int:
                         f"one fresh seeded fp16 x per projection input (Gaussian / Laplace by role), t at "
                         f"the {pct(head)} quantile of |x| per projection",
             "weight_format": fmt,
+            "weight_rows": ("W_gate and W_up stored with rows 256 bytes further apart (teal_pack_bf16_pitch), "
+                            "the other matrices packed" if rows == "padded" else "packed"),
             "weight_bytes_per_block": block_bytes,
             "blocks_per_step": layers,
             "launches": launches_text,

@@ -34,10 +34,15 @@ class Projection:
     """One weight matrix resident on the device in the format under test."""
 
     def __init__(self, T, torch, name, n, m, fmt, x_host, sparsities, copies, w_host=None,
-                 device_seed=None, batch=0):
+                 device_seed=None, batch=0, row_pad=0):
         """batch = 0: one hidden state x_host[m] (Definition 1); batch >= 1: x_host is
-        [batch][m] and the batch-wide criterion of Section 5.4.4 applies."""
+        [batch][m] and the batch-wide criterion of Section 5.4.4 applies.  row_pad > 0 (bf16,
+        int8, batch 0): the matrix is stored with rows n + row_pad elements apart and the
+        calls are the library's _pitch entry points."""
         self.name, self.n, self.m, self.fmt, self.batch = name, n, m, fmt, batch
+        self.pitch = n + row_pad
+        if row_pad and (batch or fmt == "w4"):
+            raise ValueError("padded rows: bf16 and int8, batch 1")
         self.x_host, self.w_host = x_host, w_host
         self.host_q = None
         if w_host is None:
@@ -49,8 +54,9 @@ class Projection:
         else:
             wd = torch.from_numpy(w_host.view(np.int16)).cuda()
         if fmt == "bf16":
-            wt = torch.empty((m, n), dtype=torch.int16, device="cuda")
-            T.check(T.teal_pack_bf16(wd, wt, m, n))
+            wt = torch.zeros((m, self.pitch), dtype=torch.int16, device="cuda")
+            T.check(T.teal_pack_bf16_pitch(wd, wt, m, n, self.pitch) if row_pad
+                    else T.teal_pack_bf16(wd, wt, m, n))
             first = (wt,)
         else:
             if w_host is None:
@@ -60,7 +66,12 @@ class Projection:
             else:
                 q, scale = ti.quantize_w4(w_host, 128)
             self.host_q = (q, scale)
-            first = (torch.from_numpy(q).cuda(), torch.from_numpy(scale.view(np.int16)).cuda())
+            qd = torch.from_numpy(q).cuda()
+            if row_pad:
+                wide = torch.zeros((m, self.pitch), dtype=torch.int8, device="cuda")
+                wide[:, :n] = qd
+                qd = wide
+            first = (qd, torch.from_numpy(scale.view(np.int16)).cuda())
         del wd
         self.weights = [first] + [tuple(t.clone() for t in first) for _ in range(copies - 1)]
         self.x = torch.from_numpy(x_host.view(np.int16)).cuda()
@@ -98,6 +109,14 @@ class Projection:
             return T.teal_sparse_gemv_bf16_batch(w[0], self.xp, self.batch, self.t[p], self.yp,
                                                  self.m, self.n, self.wsp, self.ws_bytes,
                                                  self.stream)
+        if self.pitch != self.n:
+            if self.fmt == "bf16":
+                return T.teal_sparse_gemv_bf16_multi_pitch([w[0]], [self.pitch], [self.t[p]], [self.yp],
+                                                           [self.n], self.xp, self.m, self.wsp,
+                                                           self.ws_bytes, self.stream)
+            return T.teal_sparse_gemv_w8_multi_pitch([w[0]], [self.pitch], [w[1]], [self.t[p]],
+                                                     [self.yp], [self.n], self.xp, self.m, self.wsp,
+                                                     self.ws_bytes, self.stream)
         if self.fmt == "bf16":
             return T.teal_sparse_gemv_bf16(w[0], self.xp, self.t[p], self.yp, self.m, self.n,
                                            self.wsp, self.ws_bytes, self.stream)
@@ -172,6 +191,13 @@ class FusedGroup:
                                                [P.t[p] for P in self.members], self.ys, self.ns,
                                                self.members[0].xp, self.m, self.wsp,
                                                self.ws_bytes, self.stream)
+        padded = any(P.pitch != P.n for P in self.members)
+        if self.members[0].fmt == "w8" and padded:
+            ws = [P.wp[copy % len(P.wp)] for P in self.members]
+            return T.teal_sparse_gemv_w8_multi_pitch([w[0] for w in ws], [P.pitch for P in self.members],
+                                                     [w[1] for w in ws], [P.t[p] for P in self.members],
+                                                     self.ys, self.ns, self.members[0].xp, self.m,
+                                                     self.wsp, self.ws_bytes, self.stream)
         if self.members[0].fmt == "w8":
             ws = [P.wp[copy % len(P.wp)] for P in self.members]
             return T.teal_sparse_gemv_w8_multi([w[0] for w in ws], [w[1] for w in ws],
@@ -179,6 +205,11 @@ class FusedGroup:
                                                self.members[0].xp, self.m, self.wsp,
                                                self.ws_bytes, self.stream)
         wts = [P.wp[copy % len(P.wp)][0] for P in self.members]
+        if padded:
+            return T.teal_sparse_gemv_bf16_multi_pitch(wts, [P.pitch for P in self.members],
+                                                       [P.t[p] for P in self.members], self.ys,
+                                                       self.ns, self.members[0].xp, self.m, self.wsp,
+                                                       self.ws_bytes, self.stream)
         return T.teal_sparse_gemv_bf16_multi(wts, [P.t[p] for P in self.members], self.ys, self.ns,
                                              self.members[0].xp, self.m, self.wsp, self.ws_bytes,
                                              self.stream)
@@ -280,10 +311,10 @@ def fuse(T, torch, stack):
     return out
 
 
-def build_stack(T, torch, model, fmt, sparsities, layers, copies, batch=0):
+def build_stack(T, torch, model, fmt, sparsities, layers, copies, batch=0, row_pad=None):
     """`layers` synthetic blocks.  Block 0 comes from the seeded host recipe (so the CPU
     baseline sees the same numbers); further blocks of a bf16 stack draw their weights on
-    the device."""
+    the device.  row_pad: {projection name: elements added to its row pitch}."""
     cfg = ti.CONFIG_INDEX[model]
     stack = []
     for layer in range(layers):
@@ -296,7 +327,8 @@ def build_stack(T, torch, model, fmt, sparsities, layers, copies, batch=0):
                 x = ti.make_x(m, ti.x_seed(cfg, layer, proj), ti.PROJ_DIST[proj])
             w = ti.weights_bf16(n, m, ti.weight_seed(cfg, layer, proj)) if host else None
             stack.append(Projection(T, torch, proj, n, m, fmt, x, sparsities, copies, w_host=w,
-                                    device_seed=ti.weight_seed(cfg, layer, proj), batch=batch))
+                                    device_seed=ti.weight_seed(cfg, layer, proj), batch=batch,
+                                    row_pad=(row_pad or {}).get(proj, 0)))
             if layer > 0:
                 stack[-1].w_host = None          # keep host memory flat for deep stacks
                 stack[-1].host_q = None
@@ -505,7 +537,7 @@ def deep_layer_check(T, torch, projections, layers, p: float):
     worst, checked = 0.0, 0
     for layer in layers:
         for P in projections[7 * layer:7 * layer + 7]:
-            wt = P.weights[0][0]                                        # [m][n] bf16 bits
+            wt = P.weights[0][0][:, :P.n]                               # [m][n] bf16 bits
             w = wt.t().contiguous().cpu().numpy().view(np.uint16)       # canonical [n][m]
             want = orc.sparse_gemv_bf16(w, P.x_host, P.t[p])
             del w
@@ -666,7 +698,7 @@ class MlpCall:
 
 
 def measured_traffic(workload: str, fmt: str, sparsity: float, layers: int, launches: str,
-                     library_version: int, folder: str = ""):
+                     library_version: int, folder: str = "", rows: str = "packed"):
     """HBM bytes per launch (fetched + written) of the dominant kernel, as measured with
     rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and written down in a summary under profiles/.
     A summary carries one line per measured case,
@@ -677,7 +709,7 @@ def measured_traffic(workload: str, fmt: str, sparsity: float, layers: int, laun
     kernels (another library version) is not this run's traffic.  Returns (bytes or None, the
     file the figure comes from or the reason there is none)."""
     want = {"workload": workload, "format": fmt, "sparsity": f"{sparsity:g}", "layers": str(layers),
-            "launches": launches, "library_version": str(library_version)}
+            "launches": launches, "library_version": str(library_version), "rows": rows}
     folder = folder or os.path.join(ROOT, "profiles")
     stale = None
     for name in sorted(os.listdir(folder)) if os.path.isdir(folder) else []:
@@ -687,6 +719,7 @@ def measured_traffic(workload: str, fmt: str, sparsity: float, layers: int, laun
             if not line.startswith("TRAFFIC "):
                 continue
             kv = dict(tok.split("=", 1) for tok in line.split()[1:] if "=" in tok)
+            kv.setdefault("rows", "packed")
             if all(kv.get(k) == v for k, v in want.items() if k != "library_version"):
                 if kv.get("library_version") == want["library_version"]:
                     return (float(kv["fetch_bytes_per_launch"]) + float(kv["write_bytes_per_launch"]),

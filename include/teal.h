@@ -164,6 +164,24 @@ teal_status teal_sparse_gemv_bf16_static(const void *Wt_bf16, const void *x_f16,
 teal_status teal_sparse_gemv_bf16_multi(int count, const void *const *Wt_bf16, const float *t,
                                         float *const *y, const int *n, const void *x_f16, int m,
                                         void *workspace, size_t workspace_bytes, void *stream);
+/*
+ * The same on matrices stored with padded rows (the layout
+ * teal_pack_bf16_pitch writes; Sections 3 and 4.4 fix only that a channel's
+ * weights are contiguous).  row_pitch is a HOST array of length count:
+ * elements from one row of matrix k to the next, >= n_k and a multiple of 8
+ * (else TEAL_ERR_SHAPE); matrix k spans (m - 1) * row_pitch[k] + n_k elements
+ * and the padding is never read.  Same sums as the packed call; the launch
+ * shape may differ (teal_gemv_plan_multi_pitch): with every row pitch an odd
+ * multiple of 256 bytes (n + 128 elements where 2 n is a multiple of 1024) a
+ * 256-byte tile of a row falls on a different quarter of a KiB on every row,
+ * all tiles stream at the same speed, and a group with about one such tile
+ * per compute unit and m <= 4096 runs without split-K.
+ */
+teal_status teal_sparse_gemv_bf16_multi_pitch(int count, const void *const *Wt_bf16,
+                                              const int *row_pitch, const float *t,
+                                              float *const *y, const int *n, const void *x_f16,
+                                              int m, void *workspace, size_t workspace_bytes,
+                                              void *stream);
 
 /*
  * Several grouped calls that do not depend on each other, in one kernel
@@ -306,6 +324,13 @@ teal_status teal_sparse_gemv_w8_multi(int count, const int8_t *const *Wq,
                                       const void *const *scale_f16, const float *t,
                                       float *const *y, const int *n, const void *x_f16, int m,
                                       void *workspace, size_t workspace_bytes, void *stream);
+/* With padded rows, as teal_sparse_gemv_bf16_multi_pitch: row_pitch[k] >= n_k
+ * elements (bytes), a multiple of 16. */
+teal_status teal_sparse_gemv_w8_multi_pitch(int count, const int8_t *const *Wq,
+                                            const int *row_pitch, const void *const *scale_f16,
+                                            const float *t, float *const *y, const int *n,
+                                            const void *x_f16, int m, void *workspace,
+                                            size_t workspace_bytes, void *stream);
 
 /*
  * The 8-bit calls with their input formed on the fly, as for bf16 weights
@@ -504,8 +529,9 @@ teal_status teal_pack_bf16_pitch(const void *W_rowmajor, void *Wt, int m, int n,
  *   tile_cols      output columns per thread block: a multiple of 8, at most
  *                  8 * lanes_per_row.
  *   splits         1..128: thread blocks along the input dimension (split-K,
- *                  Section 4.4).  A block takes at most 4096 input channels,
- *                  so m above 128 * 4096 runs with ceil(m / 4096) splits.
+ *                  Section 4.4).  A block takes at most 8192 input channels
+ *                  (the library's own choice stays at 4096 or fewer), so a
+ *                  request below ceil(m / 8192) runs with that many splits.
  *   waves          4, 8 or 16 wavefronts per thread block.
  *   unroll         4 or 8 row loads per batch (two batches in flight per
  *                  wavefront); 4 with 16 wavefronts.
@@ -609,6 +635,11 @@ teal_status teal_gemv_plan(int weight_bits, int m, int n, int *lanes_per_row, in
 teal_status teal_gemv_plan_multi(int weight_bits, int m, const int *n, int count,
                                  int *lanes_per_row, int *tile_cols, int *splits, int *waves,
                                  int *unroll);
+/* The same for teal_sparse_gemv_{bf16,w8}_multi_pitch (weight_bits 16 or 8;
+ * row_pitch a HOST array of length count). */
+teal_status teal_gemv_plan_multi_pitch(int weight_bits, int m, const int *n, const int *row_pitch,
+                                       int count, int *lanes_per_row, int *tile_cols, int *splits,
+                                       int *waves, int *unroll);
 
 #ifdef __cplusplus
 }

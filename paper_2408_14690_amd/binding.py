@@ -32,7 +32,8 @@ EXPORTS = (
     "teal_sparsify_batch", "teal_sparse_gemv_bf16_batch", "teal_sparse_gemv_bf16_batch_ex",
     "teal_sparse_gemv_w8_multi", "teal_sparse_gemv_w4_multi",
     "teal_swiglu_f16", "teal_sparse_gemv_bf16_swiglu", "teal_sparse_gemv_bf16_batch_multi",
-    "teal_gemv_plan_multi", "teal_survivors_offset", "teal_rmsnorm_f16",
+    "teal_gemv_plan_multi", "teal_gemv_plan_multi_pitch", "teal_sparse_gemv_bf16_multi_pitch",
+    "teal_sparse_gemv_w8_multi_pitch", "teal_survivors_offset", "teal_rmsnorm_f16",
     "teal_sparse_gemv_bf16_rmsnorm_multi", "teal_workspace_bytes_stack",
     "teal_sparse_gemv_bf16_stack", "teal_sparse_gemv_w8_stack", "teal_sparse_gemv_w4_stack",
     "teal_stream_read_probe", "teal_sparse_gemv_w8_swiglu", "teal_sparse_gemv_w8_rmsnorm_multi",
@@ -115,6 +116,13 @@ def load_library():
     lib.teal_sparse_gemv_bf16_multi.restype = i
     lib.teal_sparse_gemv_bf16_multi.argtypes = [i, c.POINTER(vp), c.POINTER(f), c.POINTER(vp),
                                                 c.POINTER(i), vp, i, vp, sz, vp]
+    lib.teal_sparse_gemv_bf16_multi_pitch.restype = i
+    lib.teal_sparse_gemv_bf16_multi_pitch.argtypes = [i, c.POINTER(vp), c.POINTER(i), c.POINTER(f),
+                                                      c.POINTER(vp), c.POINTER(i), vp, i, vp, sz, vp]
+    lib.teal_sparse_gemv_w8_multi_pitch.restype = i
+    lib.teal_sparse_gemv_w8_multi_pitch.argtypes = [i, c.POINTER(vp), c.POINTER(i), c.POINTER(vp),
+                                                    c.POINTER(f), c.POINTER(vp), c.POINTER(i), vp, i,
+                                                    vp, sz, vp]
     lib.teal_workspace_bytes_stack.restype = sz
     lib.teal_workspace_bytes_stack.argtypes = [i, c.POINTER(i), c.POINTER(i), c.POINTER(i)]
     lib.teal_sparse_gemv_bf16_stack.restype = i
@@ -192,6 +200,8 @@ def load_library():
     lib.teal_gemv_plan.argtypes = [i, i, i, ip, ip, ip, ip, ip]
     lib.teal_gemv_plan_multi.restype = i
     lib.teal_gemv_plan_multi.argtypes = [i, i, ip, i, ip, ip, ip, ip, ip]
+    lib.teal_gemv_plan_multi_pitch.restype = i
+    lib.teal_gemv_plan_multi_pitch.argtypes = [i, i, ip, ip, i, ip, ip, ip, ip, ip]
     _lib = lib
     return lib
 
@@ -400,6 +410,55 @@ def teal_sparse_gemv_bf16_multi(Wt_list, t_list, y_list, n_list, x_f16, m, works
         "teal_sparse_gemv_bf16_multi",
         count, W, Tt, Y, N, _ptr(x_f16, 2 * m, "x"), int(m), _ptr(workspace),
         _nbytes(workspace, workspace_bytes), _stream(stream))
+
+
+def teal_sparse_gemv_bf16_multi_pitch(Wt_list, pitch_list, t_list, y_list, n_list, x_f16, m, workspace,
+                                      workspace_bytes=None, stream=None) -> int:
+    """teal_sparse_gemv_bf16_multi on matrices with rows pitch_list[k] elements apart."""
+    count = len(Wt_list)
+    if not (len(pitch_list) == len(t_list) == len(y_list) == len(n_list) == count):
+        raise ValueError("per-matrix lists must have the same length")
+    W = (ctypes.c_void_p * count)(*[_ptr(w, 2 * ((m - 1) * max(int(p), n) + n), "Wt")
+                                    for w, n, p in zip(Wt_list, n_list, pitch_list)])
+    P = (ctypes.c_int * count)(*[int(p) for p in pitch_list])
+    Y = (ctypes.c_void_p * count)(*[_ptr(y, 4 * n, "y") for y, n in zip(y_list, n_list)])
+    Tt = (ctypes.c_float * count)(*[float(t) for t in t_list])
+    N = (ctypes.c_int * count)(*[int(n) for n in n_list])
+    return _call(
+        "teal_sparse_gemv_bf16_multi_pitch",
+        count, W, P, Tt, Y, N, _ptr(x_f16, 2 * m, "x"), int(m), _ptr(workspace),
+        _nbytes(workspace, workspace_bytes), _stream(stream))
+
+
+def teal_sparse_gemv_w8_multi_pitch(Wq_list, pitch_list, scale_list, t_list, y_list, n_list, x_f16, m,
+                                    workspace, workspace_bytes=None, stream=None) -> int:
+    """teal_sparse_gemv_w8_multi on matrices with rows pitch_list[k] elements (bytes) apart."""
+    count = len(Wq_list)
+    if not (len(pitch_list) == len(scale_list) == len(t_list) == len(y_list) == len(n_list) == count):
+        raise ValueError("per-matrix lists must have the same length")
+    W = (ctypes.c_void_p * count)(*[_ptr(w, (m - 1) * max(int(p), n) + n, "Wq")
+                                    for w, n, p in zip(Wq_list, n_list, pitch_list)])
+    P = (ctypes.c_int * count)(*[int(p) for p in pitch_list])
+    S = (ctypes.c_void_p * count)(*[_ptr(sc, 2 * n, "scale") for sc, n in zip(scale_list, n_list)])
+    Y = (ctypes.c_void_p * count)(*[_ptr(y, 4 * n, "y") for y, n in zip(y_list, n_list)])
+    Tt = (ctypes.c_float * count)(*[float(t) for t in t_list])
+    N = (ctypes.c_int * count)(*[int(n) for n in n_list])
+    return _call(
+        "teal_sparse_gemv_w8_multi_pitch",
+        count, W, P, S, Tt, Y, N, _ptr(x_f16, 2 * m, "x"), int(m), _ptr(workspace),
+        _nbytes(workspace, workspace_bytes), _stream(stream))
+
+
+def teal_gemv_plan_multi_pitch(weight_bits: int, m: int, n_list, pitch_list):
+    """Returns (status, dict) for a grouped launch on matrices with padded rows."""
+    count = len(n_list)
+    N = (ctypes.c_int * max(count, 1))(*[int(n) for n in n_list])
+    P = (ctypes.c_int * max(count, 1))(*[int(p) for p in pitch_list])
+    vals = [ctypes.c_int(0) for _ in range(5)]
+    st = load_library().teal_gemv_plan_multi_pitch(int(weight_bits), int(m), N, P, count,
+                                                   *[ctypes.byref(v) for v in vals])
+    keys = ("lanes_per_row", "tile_cols", "splits", "waves", "unroll")
+    return st, {k: v.value for k, v in zip(keys, vals)}
 
 
 def teal_workspace_bytes_stack(counts, n_list, m_list) -> int:

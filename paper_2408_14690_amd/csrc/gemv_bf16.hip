@@ -40,13 +40,17 @@ hipError_t launch_gemv_bf16(const void *Wt, const void *x_f16, float t, float *y
                             float *partial, int *counters, const GemvShape &sh,
                             hipStream_t stream)
 {
-    const GemvGeometry g = gemv_geometry(m, n, sh, FmtBF16::kElemsPerLane, 64);
+    const GemvGeometry g = gemv_geometry(m, n, sh, FmtBF16::kElemsPerLane, 64, kMaxLongSlice);
     FmtBF16::Args a{Wt};
     const __half *x = static_cast<const __half *>(x_f16);
 #define TEAL_LAUNCH(F, LPR, WAVES, U)                                                          \
-    hipLaunchKernelGGL((sparse_gemv_kernel<F, LPR, WAVES, U>), dim3(g.tiles * g.splits), \
-                       dim3(WAVES * 64), g.lds, stream, a, x, t, partial, counters, y, m, n,   \
-                       g.ks, g.tiles, g.tile_cols, g.splits)
+    do {                                                                                       \
+        if (!allow_large_lds(sparse_gemv_kernel<F, LPR, WAVES, U>, g.lds))                     \
+            return hipErrorInvalidValue;                                                       \
+        hipLaunchKernelGGL((sparse_gemv_kernel<F, LPR, WAVES, U>), dim3(g.tiles * g.splits),   \
+                           dim3(WAVES * 64), g.lds, stream, a, x, t, partial, counters, y, m,  \
+                           n, g.ks, g.tiles, g.tile_cols, g.splits);                           \
+    } while (0)
     TEAL_DISPATCH(TEAL_LAUNCH, FmtBF16, sh);
 #undef TEAL_LAUNCH
     return hipGetLastError();
@@ -67,20 +71,22 @@ hipError_t launch_gemv_bf16_swiglu(const void *Wt, const float *gate, const floa
     return hipGetLastError();
 }
 
-hipError_t launch_gemv_bf16_multi(int count, const void *const *Wt, const float *t,
-                                  float *const *y, const int *n, const void *x_f16, int m,
-                                  float *partial, int *counters, const GemvShape &sh,
-                                  hipStream_t stream)
+hipError_t launch_gemv_bf16_multi(int count, const void *const *Wt, const int *row_pitch,
+                                  const float *t, float *const *y, const int *n,
+                                  const void *x_f16, int m, float *partial, int *counters,
+                                  const GemvShape &sh, hipStream_t stream)
 {
     int n_max = 0;
     for (int k = 0; k < count; ++k) n_max = n[k] > n_max ? n[k] : n_max;
     // slice length, split count and LDS size do not depend on n
-    const GemvGeometry g = gemv_geometry(m, n_max, sh, FmtBF16::kElemsPerLane, 64);
+    const GemvGeometry g =
+        gemv_geometry(m, n_max, sh, FmtBF16::kElemsPerLane, 64, kMaxLongSlice);
     MultiArgs<FmtBF16> ma{};
     ma.count = count;
     ma.tile_begin[0] = 0;
     for (int k = 0; k < count; ++k) {
         ma.a[k].W = Wt[k];
+        ma.a[k].ld = row_pitch ? row_pitch[k] : 0;
         ma.y[k] = y[k];
         ma.t[k] = t[k];
         ma.n[k] = n[k];
@@ -89,9 +95,13 @@ hipError_t launch_gemv_bf16_multi(int count, const void *const *Wt, const float 
     const int tiles = ma.tile_begin[count];
     const __half *x = static_cast<const __half *>(x_f16);
 #define TEAL_LAUNCH(F, LPR, WAVES, U)                                                          \
-    hipLaunchKernelGGL((sparse_gemv_multi_kernel<F, LPR, WAVES, U>), dim3(tiles * g.splits),   \
-                       dim3(WAVES * 64), g.lds, stream, ma, x, partial, counters, m, g.ks,     \
-                       g.tile_cols, g.splits)
+    do {                                                                                       \
+        if (!allow_large_lds(sparse_gemv_multi_kernel<F, LPR, WAVES, U>, g.lds))               \
+            return hipErrorInvalidValue;                                                       \
+        hipLaunchKernelGGL((sparse_gemv_multi_kernel<F, LPR, WAVES, U>),                       \
+                           dim3(tiles * g.splits), dim3(WAVES * 64), g.lds, stream, ma, x,     \
+                           partial, counters, m, g.ks, g.tile_cols, g.splits);                 \
+    } while (0)
     TEAL_DISPATCH(TEAL_LAUNCH, FmtBF16, sh);
 #undef TEAL_LAUNCH
     return hipGetLastError();

@@ -718,11 +718,22 @@ __device__ __forceinline__ bool gemv_block(const typename F::Args &a, const XS &
         // short slices: each wavefront compacts its own share, no barrier before the stream
         const int nseg = (k1 - k0 + 63) >> 6;                 // block-uniform
         int seg_excl;
-        if (nseg <= 8) cnt = compact_slice_private<8, WAVES>(x.x, t, k0, k1, list, seg_excl);
-        else cnt = compact_slice<WAVES>(x, t, k0, k1, list, seg_cnt, seg_excl);
+        if (nseg <= 8) {
+            cnt = compact_slice_private<8, WAVES>(x.x, t, k0, k1, list, seg_excl);
+        } else {
+            // a slice longer than kMaxSlice is compacted in pieces of that length, one
+            // behind the other in the list (block-uniform trip count)
+            cnt = 0;
+            for (int c0 = k0; c0 < k1; c0 += kMaxSlice)
+                cnt += compact_slice<WAVES>(x, t, c0, min(k1, c0 + kMaxSlice), list + cnt, seg_cnt,
+                                            seg_excl);
+        }
     } else {
         int seg_excl;
-        cnt = compact_slice<WAVES>(x, t, k0, k1, list, seg_cnt, seg_excl);
+        cnt = 0;
+        for (int c0 = k0; c0 < k1; c0 += kMaxSlice)
+            cnt += compact_slice<WAVES>(x, t, c0, min(k1, c0 + kMaxSlice), list + cnt, seg_cnt,
+                                        seg_excl);
     }
 
     trace_mark(2);
@@ -902,6 +913,18 @@ __global__ __launch_bounds__(WAVES * 64) void sparse_gemv_stack_kernel(StackArgs
                                     sg.splits, block);
 }
 
+// A launch that asks for more dynamic LDS than the 64 KiB every kernel may use has to raise
+// the kernel's limit first (a list of more than kMaxSlice entries).  Host side; false when
+// the runtime refuses.
+template <class Kernel>
+inline bool allow_large_lds(Kernel kernel, size_t lds_bytes)
+{
+    if (lds_bytes <= 64 * 1024) return true;
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                               hipFuncAttributeMaxDynamicSharedMemorySize,
+                               (int)lds_bytes) == hipSuccess;
+}
+
 // Host-side launch geometry shared by the formats.
 struct GemvGeometry {
     int tiles;         // blocks along the output dimension
@@ -912,7 +935,7 @@ struct GemvGeometry {
 };
 
 inline GemvGeometry gemv_geometry(int m, int n, const GemvShape &sh, int elems_per_lane,
-                                  int ks_multiple)
+                                  int ks_multiple, int max_slice = kMaxSlice)
 {
     GemvGeometry g;
     const int tn = sh.lanes_per_row * elems_per_lane;
@@ -921,7 +944,7 @@ inline GemvGeometry gemv_geometry(int m, int n, const GemvShape &sh, int elems_p
     int splits = sh.splits < 1 ? 1 : sh.splits;
     int ks = (m + splits - 1) / splits;
     ks = (ks + ks_multiple - 1) / ks_multiple * ks_multiple;
-    if (ks > kMaxSlice) ks = kMaxSlice;
+    if (ks > max_slice) ks = max_slice;
     g.ks = ks;
     g.splits = (m + ks - 1) / ks;
     // list + one row of the combine buffer per wavefront (padded by one float per lane)

@@ -382,20 +382,21 @@ hipError_t launch_gemv_w8(const int8_t *Wq, const void *scale_f16, const void *x
     return hipGetLastError();
 }
 
-hipError_t launch_gemv_w8_multi(int count, const int8_t *const *Wq, const void *const *scale_f16,
-                                const float *t, float *const *y, const int *n, const void *x_f16,
-                                int m, float *partial, int *counters, const GemvShape &sh,
-                                hipStream_t stream)
+hipError_t launch_gemv_w8_multi(int count, const int8_t *const *Wq, const int *row_pitch,
+                                const void *const *scale_f16, const float *t, float *const *y,
+                                const int *n, const void *x_f16, int m, float *partial,
+                                int *counters, const GemvShape &sh, hipStream_t stream)
 {
     int n_max = 0;
     for (int k = 0; k < count; ++k) n_max = n[k] > n_max ? n[k] : n_max;
     // slice length, split count and LDS size do not depend on n
-    const GemvGeometry g = gemv_geometry(m, n_max, sh, FmtW8::kElemsPerLane, 64);
+    const GemvGeometry g = gemv_geometry(m, n_max, sh, FmtW8::kElemsPerLane, 64, kMaxLongSlice);
     MultiArgs<FmtW8> ma{};
     ma.count = count;
     ma.tile_begin[0] = 0;
     for (int k = 0; k < count; ++k) {
         ma.a[k].W = Wq[k];
+        ma.a[k].ld = row_pitch ? row_pitch[k] : 0;
         ma.a[k].scale = static_cast<const __half *>(scale_f16[k]);
         ma.y[k] = y[k];
         ma.t[k] = t[k];
@@ -405,9 +406,13 @@ hipError_t launch_gemv_w8_multi(int count, const int8_t *const *Wq, const void *
     const int tiles = ma.tile_begin[count];
     const __half *x = static_cast<const __half *>(x_f16);
 #define TEAL_LAUNCH(F, LPR, WAVES, U)                                                          \
-    hipLaunchKernelGGL((sparse_gemv_multi_kernel<F, LPR, WAVES, U>), dim3(tiles * g.splits),   \
-                       dim3(WAVES * 64), g.lds, stream, ma, x, partial, counters, m, g.ks,     \
-                       g.tile_cols, g.splits)
+    do {                                                                                       \
+        if (!allow_large_lds(sparse_gemv_multi_kernel<F, LPR, WAVES, U>, g.lds))               \
+            return hipErrorInvalidValue;                                                       \
+        hipLaunchKernelGGL((sparse_gemv_multi_kernel<F, LPR, WAVES, U>),                       \
+                           dim3(tiles * g.splits), dim3(WAVES * 64), g.lds, stream, ma, x,     \
+                           partial, counters, m, g.ks, g.tile_cols, g.splits);                 \
+    } while (0)
     TEAL_DISPATCH(TEAL_LAUNCH, FmtW8, sh);
 #undef TEAL_LAUNCH
     return hipGetLastError();

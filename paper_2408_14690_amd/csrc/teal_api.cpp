@@ -121,6 +121,69 @@ GemvShape auto_shape_multi(int m, const int *n, int count, int elems_per_lane, i
     return sh;
 }
 
+// A grouped call on matrices with padded rows.  When every matrix's rows lie an odd multiple
+// of 256 bytes apart, a 256-byte tile meets all four 256-byte quarters of a KiB over its
+// rows, so tiles of that width finish together whatever the split count; then, if the group
+// has about one such tile per compute unit and a block can take the whole input dimension,
+// split-K is not needed at all: a tile is finished by the block that streamed it, with no
+// partial rows, ticket or second pass (measured 22.1 -> 20.3 us for the Llama-3-8B gate + up
+// pair at 50 %, 18.5 -> 17.1 us for the Llama-2-7B pair, 13.1 -> 11.9 us for one 14336-wide
+// matrix in tiles of 128 bytes).  Otherwise the shape of the packed call.
+bool pitches_rotate(const int *row_pitch, int count, int bits)
+{
+    if (!row_pitch) return false;
+    for (int k = 0; k < count; ++k) {
+        const long long bytes = (long long)row_pitch[k] * bits / 8;
+        if (bytes % 512 != 256) return false;
+    }
+    return true;
+}
+
+// Row pitches of a grouped call: NULL (packed rows), or per matrix at least the row, a
+// multiple of `multiple` elements (rows stay 16-byte aligned), a row within 2^30 bytes.
+bool pitches_ok(const int *row_pitch, const int *n, int count, int multiple, int bits)
+{
+    if (!row_pitch) return true;
+    for (int k = 0; k < count; ++k)
+        if (row_pitch[k] < n[k] || row_pitch[k] % multiple != 0 ||
+            (long long)row_pitch[k] * bits / 8 > (1LL << 30))
+            return false;
+    return true;
+}
+
+GemvShape auto_shape_multi_pitch(int m, const int *n, const int *row_pitch, int count, int bits,
+                                 int elems_per_lane, int min_lanes, int max_lanes,
+                                 int ks_multiple)
+{
+    if (pitches_rotate(row_pitch, count, bits) && m <= teal::kMaxLongSlice) {
+        // tiles of 256 bytes of a row, else of 512 (the 70B-sized gate + up pair), else of 128
+        // (one cache line: a single 14336-wide matrix; with slices above kMaxSlice measured
+        // slower than split-K: the 70B-sized q + k + v group 18.6 against 18.0 us)
+        const int widths[3] = {256, 512, 128};
+        for (int wi = 0; wi < 3; ++wi) {
+            const int bytes = widths[wi];
+            if (bytes == 128 && m > teal::kMaxSlice) continue;
+            const int narrow = bytes * 8 / bits;
+            long long tiles = 0;
+            for (int k = 0; k < count; ++k) tiles += (n[k] + narrow - 1) / narrow;
+            if (tiles >= 160 && tiles <= 384 && narrow / elems_per_lane >= 8 &&
+                narrow / elems_per_lane <= max_lanes) {
+                GemvShape sh;
+                sh.lanes_per_row = narrow / elems_per_lane;
+                sh.tile_cols = narrow;
+                sh.splits = 1;
+                sh.waves = 8;
+                sh.unroll = 4;
+                return sh;
+            }
+        }
+    }
+    int n_total = 0;
+    for (int k = 0; k < count; ++k) n_total += n[k];
+    return count > 1 ? auto_shape_multi(m, n, count, elems_per_lane, min_lanes, max_lanes, ks_multiple)
+                     : auto_shape(m, n_total, elems_per_lane, min_lanes, max_lanes, ks_multiple);
+}
+
 // Partial rows a batched call may need: one per (split, batch row).
 int batch_split_rows(int m)
 {
@@ -247,7 +310,7 @@ const char *teal_status_string(teal_status s)
     return "unknown status";
 }
 
-int teal_version(void) { return 411; }
+int teal_version(void) { return 412; }
 
 size_t teal_survivors_offset(void) { return teal::kCounterBytes; }
 
@@ -332,6 +395,32 @@ teal_status teal_gemv_plan_multi(int weight_bits, int m, const int *n, int count
     else if (weight_bits == 8) sh = auto_shape_multi(m, n, count, 16, 8, 64, 64);
     else if (weight_bits == 4) sh = auto_shape_multi(m, n, count, 32, 16, 32, 128);
     else return TEAL_ERR_UNSUPPORTED;
+    if (lanes_per_row) *lanes_per_row = sh.lanes_per_row;
+    if (tile_cols) *tile_cols = sh.tile_cols;
+    if (splits) *splits = sh.splits;
+    if (waves) *waves = sh.waves;
+    if (unroll) *unroll = sh.unroll;
+    return TEAL_OK;
+}
+
+teal_status teal_gemv_plan_multi_pitch(int weight_bits, int m, const int *n, const int *row_pitch,
+                                       int count, int *lanes_per_row, int *tile_cols, int *splits,
+                                       int *waves, int *unroll)
+{
+    if (!n || !row_pitch) return TEAL_ERR_NULL;
+    if (count < 1 || count > teal::kMaxMatrices) return TEAL_ERR_UNSUPPORTED;
+    if (weight_bits != 16 && weight_bits != 8) return TEAL_ERR_UNSUPPORTED;
+    const int mult = weight_bits == 16 ? 8 : 16;
+    long long n_total = 0;
+    for (int k = 0; k < count; ++k) {
+        if (n[k] < mult || n[k] > teal::kMaxDim || n[k] % mult != 0) return TEAL_ERR_SHAPE;
+        n_total += n[k];
+    }
+    if (m < 1 || m > teal::kMaxDim || n_total > teal::kMaxDim) return TEAL_ERR_SHAPE;
+    if (!pitches_ok(row_pitch, n, count, mult, weight_bits)) return TEAL_ERR_SHAPE;
+    const GemvShape sh = weight_bits == 16
+                             ? auto_shape_multi_pitch(m, n, row_pitch, count, 16, 8, 16, 64, 64)
+                             : auto_shape_multi_pitch(m, n, row_pitch, count, 8, 16, 8, 64, 64);
     if (lanes_per_row) *lanes_per_row = sh.lanes_per_row;
     if (tile_cols) *tile_cols = sh.tile_cols;
     if (splits) *splits = sh.splits;
@@ -434,9 +523,10 @@ teal_status teal_sparse_gemv_bf16_swiglu(const void *Wt_bf16, const float *gate,
                                                   sh, static_cast<hipStream_t>(stream)));
 }
 
-teal_status teal_sparse_gemv_bf16_multi(int count, const void *const *Wt_bf16, const float *t,
-                                        float *const *y, const int *n, const void *x_f16, int m,
-                                        void *workspace, size_t workspace_bytes, void *stream)
+static teal_status gemv_bf16_multi(int count, const void *const *Wt_bf16, const int *row_pitch,
+                                   const float *t, float *const *y, const int *n,
+                                   const void *x_f16, int m, void *workspace,
+                                   size_t workspace_bytes, void *stream)
 {
     if (count < 1 || count > teal::kMaxMatrices) return TEAL_ERR_UNSUPPORTED;
     if (!Wt_bf16 || !t || !y || !n || !x_f16 || !workspace) return TEAL_ERR_NULL;
@@ -447,6 +537,7 @@ teal_status teal_sparse_gemv_bf16_multi(int count, const void *const *Wt_bf16, c
         n_total += n[k];
     }
     if (m < 1 || m > teal::kMaxDim || n_total > teal::kMaxDim) return TEAL_ERR_SHAPE;
+    if (!pitches_ok(row_pitch, n, count, 8, 16)) return TEAL_ERR_SHAPE;
     for (int k = 0; k < count; ++k)
         if (!aligned(Wt_bf16[k], 16) || !aligned(y[k], 4)) return TEAL_ERR_ALIGN;
     if (!aligned(x_f16, 2) || !aligned(workspace, kAlignWorkspace)) return TEAL_ERR_ALIGN;
@@ -454,11 +545,29 @@ teal_status teal_sparse_gemv_bf16_multi(int count, const void *const *Wt_bf16, c
         if (!threshold_ok(t[k])) return TEAL_ERR_THRESHOLD;
     if (workspace_bytes < teal_workspace_bytes(m, (int)n_total)) return TEAL_ERR_WORKSPACE;
     // Shape as for one matrix with all the output columns; a tile never spans two matrices.
-    const GemvShape sh = count > 1 ? auto_shape_multi(m, n, count, 8, 16, 64, 64)
-                                   : auto_shape(m, (int)n_total, 8, 16, 64, 64);
-    return from_hip(teal::launch_gemv_bf16_multi(count, Wt_bf16, t, y, n, x_f16, m,
+    const GemvShape sh = auto_shape_multi_pitch(m, n, row_pitch, count, 16, 8, 16, 64, 64);
+    return from_hip(teal::launch_gemv_bf16_multi(count, Wt_bf16, row_pitch, t, y, n, x_f16, m,
                                                  ws_partials(workspace, m), ws_counters(workspace),
                                                  sh, static_cast<hipStream_t>(stream)));
+}
+
+teal_status teal_sparse_gemv_bf16_multi(int count, const void *const *Wt_bf16, const float *t,
+                                        float *const *y, const int *n, const void *x_f16, int m,
+                                        void *workspace, size_t workspace_bytes, void *stream)
+{
+    return gemv_bf16_multi(count, Wt_bf16, nullptr, t, y, n, x_f16, m, workspace, workspace_bytes,
+                           stream);
+}
+
+teal_status teal_sparse_gemv_bf16_multi_pitch(int count, const void *const *Wt_bf16,
+                                              const int *row_pitch, const float *t,
+                                              float *const *y, const int *n, const void *x_f16,
+                                              int m, void *workspace, size_t workspace_bytes,
+                                              void *stream)
+{
+    if (!row_pitch) return TEAL_ERR_NULL;
+    return gemv_bf16_multi(count, Wt_bf16, row_pitch, t, y, n, x_f16, m, workspace,
+                           workspace_bytes, stream);
 }
 
 // Region of group g in a stack call's workspace: the groups' regions follow each other,
@@ -748,10 +857,10 @@ teal_status teal_sparse_gemv_w8_rmsnorm_multi(int count, const int8_t *const *Wq
         ws_counters(workspace), sh, static_cast<hipStream_t>(stream)));
 }
 
-teal_status teal_sparse_gemv_w8_multi(int count, const int8_t *const *Wq,
-                                      const void *const *scale_f16, const float *t,
-                                      float *const *y, const int *n, const void *x_f16, int m,
-                                      void *workspace, size_t workspace_bytes, void *stream)
+static teal_status gemv_w8_multi(int count, const int8_t *const *Wq, const int *row_pitch,
+                                 const void *const *scale_f16, const float *t, float *const *y,
+                                 const int *n, const void *x_f16, int m, void *workspace,
+                                 size_t workspace_bytes, void *stream)
 {
     if (count < 1 || count > teal::kMaxMatrices) return TEAL_ERR_UNSUPPORTED;
     if (!Wq || !scale_f16 || !t || !y || !n || !x_f16 || !workspace) return TEAL_ERR_NULL;
@@ -762,6 +871,7 @@ teal_status teal_sparse_gemv_w8_multi(int count, const int8_t *const *Wq,
         n_total += n[k];
     }
     if (m < 1 || m > teal::kMaxDim || n_total > teal::kMaxDim) return TEAL_ERR_SHAPE;
+    if (!pitches_ok(row_pitch, n, count, 16, 8)) return TEAL_ERR_SHAPE;
     for (int k = 0; k < count; ++k)
         if (!aligned(Wq[k], 16) || !aligned(scale_f16[k], 2) || !aligned(y[k], 4))
             return TEAL_ERR_ALIGN;
@@ -769,11 +879,30 @@ teal_status teal_sparse_gemv_w8_multi(int count, const int8_t *const *Wq,
     for (int k = 0; k < count; ++k)
         if (!threshold_ok(t[k])) return TEAL_ERR_THRESHOLD;
     if (workspace_bytes < teal_workspace_bytes(m, (int)n_total)) return TEAL_ERR_WORKSPACE;
-    const GemvShape sh = count > 1 ? auto_shape_multi(m, n, count, 16, 8, 64, 64)
-                                   : auto_shape(m, (int)n_total, 16, 8, 64, 64);
-    return from_hip(teal::launch_gemv_w8_multi(count, Wq, scale_f16, t, y, n, x_f16, m,
+    const GemvShape sh = auto_shape_multi_pitch(m, n, row_pitch, count, 8, 16, 8, 64, 64);
+    return from_hip(teal::launch_gemv_w8_multi(count, Wq, row_pitch, scale_f16, t, y, n, x_f16, m,
                                                ws_partials(workspace, m), ws_counters(workspace), sh,
                                                static_cast<hipStream_t>(stream)));
+}
+
+teal_status teal_sparse_gemv_w8_multi(int count, const int8_t *const *Wq,
+                                      const void *const *scale_f16, const float *t,
+                                      float *const *y, const int *n, const void *x_f16, int m,
+                                      void *workspace, size_t workspace_bytes, void *stream)
+{
+    return gemv_w8_multi(count, Wq, nullptr, scale_f16, t, y, n, x_f16, m, workspace,
+                         workspace_bytes, stream);
+}
+
+teal_status teal_sparse_gemv_w8_multi_pitch(int count, const int8_t *const *Wq,
+                                            const int *row_pitch, const void *const *scale_f16,
+                                            const float *t, float *const *y, const int *n,
+                                            const void *x_f16, int m, void *workspace,
+                                            size_t workspace_bytes, void *stream)
+{
+    if (!row_pitch) return TEAL_ERR_NULL;
+    return gemv_w8_multi(count, Wq, row_pitch, scale_f16, t, y, n, x_f16, m, workspace,
+                         workspace_bytes, stream);
 }
 
 teal_status teal_sparse_gemv_w4(const uint8_t *Wq, const void *scale_f16, int group,

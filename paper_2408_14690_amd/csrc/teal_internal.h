@@ -12,6 +12,8 @@ namespace teal {
 
 constexpr int kMaxSplits = 128;     // most split-K blocks a caller may ask for (longer inputs force more)
 constexpr int kMaxSlice = 4096;     // most input channels one block compacts (LDS list capacity)
+constexpr int kMaxLongSlice = 8192; // the same for the launches that run without split-K on
+                                    // padded rows (the list then takes 64 KiB of LDS)
 constexpr int kMaxDim = 1 << 24;    // largest m or n accepted
 constexpr int kMaxMatrices = 4;     // matrices per fused launch
 constexpr int kMinTile = 64;        // narrowest output tile of any kernel variant
@@ -59,10 +61,10 @@ hipError_t launch_rmsnorm_f16(const float *h, const float *gamma, float eps, voi
 hipError_t launch_swiglu_f16(const float *gate, const float *up, void *h_f16, int m,
                              hipStream_t stream);
 
-hipError_t launch_gemv_bf16_multi(int count, const void *const *Wt, const float *t,
-                                  float *const *y, const int *n, const void *x_f16, int m,
-                                  float *partial, int *counters, const GemvShape &shape,
-                                  hipStream_t stream);
+hipError_t launch_gemv_bf16_multi(int count, const void *const *Wt, const int *row_pitch,
+                                  const float *t, float *const *y, const int *n,
+                                  const void *x_f16, int m, float *partial, int *counters,
+                                  const GemvShape &sh, hipStream_t stream);
 
 // Up to kMaxStackGroups grouped calls of one weight format that do not depend on each other,
 // in one launch.  Shapes with 8 wavefronts, 4 loads per batch and the format's lanes per row.
@@ -104,10 +106,10 @@ hipError_t launch_gemv_w8(const int8_t *Wq, const void *scale_f16, const void *x
                           float t, float *y, int m, int n, float *partial, int *counters,
                           const GemvShape &shape, hipStream_t stream);
 
-hipError_t launch_gemv_w8_multi(int count, const int8_t *const *Wq, const void *const *scale_f16,
-                                const float *t, float *const *y, const int *n, const void *x_f16,
-                                int m, float *partial, int *counters, const GemvShape &shape,
-                                hipStream_t stream);
+hipError_t launch_gemv_w8_multi(int count, const int8_t *const *Wq, const int *row_pitch,
+                                const void *const *scale_f16, const float *t, float *const *y,
+                                const int *n, const void *x_f16, int m, float *partial,
+                                int *counters, const GemvShape &sh, hipStream_t stream);
 
 hipError_t launch_gemv_w8_swiglu(const int8_t *Wq, const void *scale_f16, const float *gate,
                                  const float *up, float t, float *y, int m, int n, float *partial,

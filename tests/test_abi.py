@@ -182,6 +182,61 @@ def test_multi_argument_errors():
     assert T.teal_sparse_gemv_bf16_multi([], [], [], [], X, 4096, WS, BIG, 0) == T.TEAL_ERR_UNSUPPORTED
 
 
+def test_multi_pitch_argument_errors_and_plan():
+    """The grouped call on matrices with padded rows: the checks of the packed call plus the
+    pitches; the planned shape drops split-K only where the pitches rotate the tiles over the
+    address quarters and one 256-byte tile per compute unit exists."""
+    ok = dict(Wt_list=[W, W + 0x1000], pitch_list=[4096 + 128, 1024 + 8], t_list=[0.5, 0.25],
+              y_list=[Y, Y + 0x1000], n_list=[4096, 1024], x_f16=X, m=4096, workspace=WS,
+              workspace_bytes=BIG, stream=0)
+
+    def call(**kw):
+        a = dict(ok)
+        a.update(kw)
+        return T.teal_sparse_gemv_bf16_multi_pitch(**a)
+
+    assert call(Wt_list=[W, None]) == T.TEAL_ERR_NULL
+    assert call(n_list=[4096, 1020]) == T.TEAL_ERR_SHAPE
+    assert call(pitch_list=[4096 - 8, 1024]) == T.TEAL_ERR_SHAPE        # shorter than the row
+    assert call(pitch_list=[4096 + 4, 1024]) == T.TEAL_ERR_SHAPE        # rows not 16-byte aligned
+    assert call(Wt_list=[W, W + 8]) == T.TEAL_ERR_ALIGN
+    assert call(t_list=[0.5, float("inf")]) == T.TEAL_ERR_THRESHOLD
+    assert call(workspace_bytes=T.teal_workspace_bytes(4096, 5120) - 1) == T.TEAL_ERR_WORKSPACE
+    q = dict(Wq_list=[W, W + 0x1000], pitch_list=[4096 + 256, 1024], scale_list=[SC, SC],
+             t_list=[0.5, 0.25], y_list=[Y, Y + 0x1000], n_list=[4096, 1024], x_f16=X, m=4096,
+             workspace=WS, workspace_bytes=BIG, stream=0)
+    assert T.teal_sparse_gemv_w8_multi_pitch(**dict(q, pitch_list=[4096 + 8, 1024])) == T.TEAL_ERR_SHAPE
+    assert T.teal_sparse_gemv_w8_multi_pitch(**dict(q, scale_list=[SC, None])) == T.TEAL_ERR_NULL
+    assert T.teal_sparse_gemv_w8_multi_pitch(**dict(q, workspace_bytes=16)) == T.TEAL_ERR_WORKSPACE
+
+    m, f = 4096, 14336
+    packed = T.teal_gemv_plan_multi(16, m, [f, f])
+    assert T.teal_gemv_plan_multi_pitch(16, m, [f, f], [f, f]) == packed           # 2 f bytes: a multiple of 1 KiB
+    assert T.teal_gemv_plan_multi_pitch(16, m, [f, f], [f + 512, f + 512]) == packed
+    assert T.teal_gemv_plan_multi_pitch(16, m, [f, f], [f + 128, f]) == packed     # every matrix must rotate
+    st, p = T.teal_gemv_plan_multi_pitch(16, m, [f, f], [f + 128, f + 384])
+    assert st == T.TEAL_OK and (p["lanes_per_row"], p["tile_cols"], p["splits"]) == (16, 128, 1)
+    st, p = T.teal_gemv_plan_multi_pitch(16, m, [11008, 11008], [11008 + 128] * 2)   # 172 tiles
+    assert (p["lanes_per_row"], p["tile_cols"], p["splits"]) == (16, 128, 1)
+    st, p = T.teal_gemv_plan_multi_pitch(16, m, [f], [f + 128])                       # one matrix: 128-byte tiles
+    assert st == T.TEAL_OK and (p["lanes_per_row"], p["tile_cols"], p["splits"]) == (8, 64, 1)
+    # too few tiles (q + k + v of the 8B block: 96 of 128 bytes; one 8192-wide matrix: 128), a slice too long
+    assert T.teal_gemv_plan_multi_pitch(16, m, [4096, 1024, 1024], [4096 + 128, 1024 + 128, 1024 + 128]) == \
+        T.teal_gemv_plan_multi(16, m, [4096, 1024, 1024])
+    assert T.teal_gemv_plan_multi_pitch(16, 8192 + 64, [f, f], [f + 128] * 2) == \
+        T.teal_gemv_plan_multi(16, 8192 + 64, [f, f])
+    assert T.teal_gemv_plan_multi_pitch(16, 8192, [8192], [8192 + 128]) == T.teal_gemv_plan_multi(16, 8192, [8192])
+    # slices of up to 8192 channels: the 70B-sized pair in tiles of 512 bytes; its q + k + v keeps split-K
+    st, p = T.teal_gemv_plan_multi_pitch(16, 8192, [28672] * 2, [28672 + 128] * 2)
+    assert st == T.TEAL_OK and (p["lanes_per_row"], p["tile_cols"], p["splits"]) == (32, 256, 1)
+    qkv = [8192, 1024, 1024]
+    assert T.teal_gemv_plan_multi_pitch(16, 8192, qkv, [n + 128 for n in qkv]) == T.teal_gemv_plan_multi(16, 8192, qkv)
+    st, p = T.teal_gemv_plan_multi_pitch(8, m, [2 * f, 2 * f], [2 * f + 256] * 2)      # int8: 256 columns per tile
+    assert st == T.TEAL_OK and (p["lanes_per_row"], p["tile_cols"], p["splits"]) == (16, 256, 1)
+    assert T.teal_gemv_plan_multi_pitch(4, m, [f, f], [f, f])[0] == T.TEAL_ERR_UNSUPPORTED
+    assert T.teal_gemv_plan_multi_pitch(16, m, [f, f], [f - 8, f])[0] == T.TEAL_ERR_SHAPE
+
+
 def test_stack_argument_errors_and_workspace():
     """teal_sparse_gemv_bf16_stack: every check happens on the host before any HIP call; the
     workspace is the sum of the groups' own workspaces."""

@@ -443,6 +443,47 @@ def test_gemv_bf16_70b_qkv_group_sampled_rows(T):
         assert rel_l2(got[rows], want) <= TIGHT and max_abs_err_scaled(got[rows], want) <= 1e-4, k
 
 
+@pytest.mark.parametrize("group,ps", [(("gate", "up"), (0.5, 0.4)), (("q", "k", "v"), (0.5, 0.4, 0.65))],
+                         ids=["gate+up", "q+k+v"])
+def test_gemv_bf16_70b_groups_with_padded_rows(T, group, ps):
+    """The grouped launches of the 70B-shaped block on matrices stored with rows 256 bytes
+    further apart (teal_pack_bf16_pitch): the gate + up pair without split-K, a block
+    compacting all 8192 channels (a list of 64 KiB in LDS); q + k + v with the shape of the
+    packed call.  Survivor counts exact, sampled outputs one by one against
+    the oracle, and bit for bit the packed matrix under the same launch shape."""
+    m = 8192
+    x = ti.gaussian_x(m, ti.x_seed(4, 0, group[0]))
+    xd = dev(x)
+    hosts, wide, ns, pitches = [], [], [], []
+    for proj in group:
+        n, _ = ti.LAYER_SHAPES["llama_70b"][proj]
+        w = ti.weights_bf16(n, m, ti.weight_seed(4, 0, proj))
+        wt = torch.full((m, n + 128), 0x7FC0, dtype=torch.int16, device="cuda")
+        T.check(T.teal_pack_bf16_pitch(dev(w), wt, m, n, n + 128))
+        hosts.append(w)
+        wide.append(wt)
+        ns.append(n)
+        pitches.append(n + 128)
+    st, plan = T.teal_gemv_plan_multi_pitch(16, m, ns, pitches)
+    assert st == 0 and (plan["splits"] == 1) == (len(group) == 2)
+    ts = [ti.quantile_threshold(x, p) for p in ps]
+    ys = [torch.full((n,), float("nan"), dtype=torch.float32, device="cuda") for n in ns]
+    ws = workspace(T, m, sum(ns))
+    for _ in range(2):                                       # twice on one workspace
+        T.check(T.teal_sparse_gemv_bf16_multi_pitch(wide, pitches, ts, ys, ns, xd, m, ws))
+    torch.cuda.synchronize()
+    assert survivors(T, ws, len(ns)) == [orc.sparsify(x, t)[3] for t in ts]
+    ws1 = workspace(T, m, max(ns))
+    for k, n in enumerate(ns):
+        got = ys[k].cpu().numpy()
+        rows = np.unique(np.concatenate([np.arange(0, n, 59), [n - 1, n - 8, 255, 256]])).astype(np.int32)
+        want = orc.sparse_gemv_bf16_rows(hosts[k], x, ts[k], rows)
+        assert np.all(np.isfinite(got))
+        assert rel_l2(got[rows], want) <= TIGHT and max_abs_err_scaled(got[rows], want) <= 1e-4, k
+        packed = wide[k][:, :n].contiguous()
+        assert np.array_equal(got, run_bf16(T, packed, xd, ts[k], m, n, ws1, **plan)), k
+
+
 # ---------------------------------------------------------------------------
 # several matrices sharing one hidden state in one launch
 # ---------------------------------------------------------------------------
@@ -486,6 +527,96 @@ def test_gemv_bf16_multi(T, name, ns, m, ps):
     torch.cuda.synchronize()
     for a, b in zip(ys, ys2):
         assert torch.equal(a, b)
+
+
+MULTI_PITCH = [
+    # name, widths, row pitches (elements), m, sparsity levels
+    ("llama3 gate,up rotating", [14336, 14336], [14336 + 128, 14336 + 384], 4096, [0.5, 0.4]),
+    ("llama2 gate,up rotating", [11008, 11008], [11008 + 128, 11008 + 128], 4096, [0.5, 0.5]),
+    ("llama3 q,k,v padded", [4096, 1024, 1024], [4096 + 128, 1024 + 8, 1024], 4096, [0.5, 0.4, 0.25]),
+    ("ragged", [520, 24, 136, 8], [520 + 8, 24 + 104, 136, 8 + 128], 333, [0.0, 0.5, 0.9, 1.0]),
+    ("single", [1032], [1032 + 128], 2049, [0.5]),
+    ("llama3 gate alone rotating", [14336], [14336 + 128], 4096, [0.5]),
+]
+
+
+def padded_rows(wt_dev, pitch, fill):
+    """The matrix stored with rows `pitch` elements apart; the padding holds `fill`."""
+    k, n = wt_dev.shape
+    out = torch.full((k, pitch), fill, dtype=wt_dev.dtype, device="cuda")
+    out[:, :n] = wt_dev
+    return out
+
+
+@pytest.mark.parametrize("name,ns,pitches,m,ps", MULTI_PITCH, ids=[c[0] for c in MULTI_PITCH])
+def test_gemv_bf16_multi_pitch(T, name, ns, pitches, m, ps):
+    """Padded rows: the oracle's result, bit for bit the packed matrix under the launch shape
+    the padded call reports, and the padding (bf16 NaNs here) never enters a sum."""
+    x = ti.gaussian_x(m, 910 + m)
+    xd = dev(x)
+    ws = workspace(T, m, sum(ns))
+    ws1 = workspace(T, m, max(ns))
+    hosts, packed, padded, ts, ys = [], [], [], [], []
+    for k, (n, p) in enumerate(zip(ns, ps)):
+        w = ti.weights_bf16(n, m, seed=1100 * k + n + m)
+        hosts.append(w)
+        packed.append(dev(ti.to_input_channel_major(w)))
+        padded.append(padded_rows(packed[-1], pitches[k], 0x7FC0))
+        ts.append(ti.quantile_threshold(x, p))
+        ys.append(torch.full((n,), float("nan"), dtype=torch.float32, device="cuda"))
+    T.check(T.teal_sparse_gemv_bf16_multi_pitch(padded, pitches, ts, ys, ns, xd, m, ws))
+    torch.cuda.synchronize()
+    st, plan = T.teal_gemv_plan_multi_pitch(16, m, ns, pitches)
+    assert st == 0
+    if "rotating" in name:
+        assert plan["splits"] == 1 and plan["tile_cols"] == (128 if len(ns) > 1 else 64)
+    for k, n in enumerate(ns):
+        got = ys[k].cpu().numpy()
+        assert rel_l2(got, orc.sparse_gemv_bf16(hosts[k], x, ts[k])) <= TIGHT, (name, k)
+        alone = run_bf16(T, packed[k], xd, ts[k], m, n, ws1, **plan)
+        assert np.array_equal(got, alone), (name, k)
+    assert survivors(T, ws, len(ns)) == [orc.sparsify(x, t)[3] for t in ts]
+    # the workspace is left ready; the packed call on the same workspace still works
+    ys2 = [torch.full((n,), float("nan"), dtype=torch.float32, device="cuda") for n in ns]
+    T.check(T.teal_sparse_gemv_bf16_multi(packed, ts, ys2, ns, xd, m, ws))
+    T.check(T.teal_sparse_gemv_bf16_multi_pitch(padded, pitches, ts, ys2, ns, xd, m, ws))
+    torch.cuda.synchronize()
+    for a, b in zip(ys, ys2):
+        assert torch.equal(a, b)
+
+
+def test_gemv_w8_multi_pitch(T):
+    ns, m = [14336 * 2, 14336 * 2], 4096
+    pitches = [n + 256 for n in ns]
+    x = ti.laplace_x(m, 720)
+    xd = dev(x)
+    ws = workspace(T, m, sum(ns))
+    hosts, packed, padded, scs, ts, ys = [], [], [], [], [], []
+    for k, n in enumerate(ns):
+        q, scale = ti.quantize_w8(ti.weights_bf16(n, m, seed=2100 * k + n))
+        hosts.append((q, scale))
+        packed.append(dev(q))
+        padded.append(padded_rows(packed[-1], pitches[k], 127))
+        scs.append(dev(scale))
+        ts.append(ti.quantile_threshold(x, 0.5 - 0.1 * k))
+        ys.append(torch.full((n,), float("nan"), dtype=torch.float32, device="cuda"))
+    st, plan = T.teal_gemv_plan_multi_pitch(8, m, ns, pitches)
+    assert st == 0 and plan["splits"] == 1
+    T.check(T.teal_sparse_gemv_w8_multi_pitch(padded, pitches, scs, ts, ys, ns, xd, m, ws))
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([np.arange(0, ns[0], 61), [ns[0] - 1]])).astype(np.int32)
+    for k, n in enumerate(ns):
+        got = ys[k].cpu().numpy()
+        q, scale = hosts[k]
+        want = orc.sparse_gemv_w8(np.ascontiguousarray(q[:, rows]), np.ascontiguousarray(scale[rows]), x, ts[k])
+        assert np.all(np.isfinite(got))
+        assert rel_l2(got[rows], want) <= TIGHT, k
+    # the packed call computes the same sums (another launch shape: tolerance, not bits)
+    ys2 = [torch.full((n,), float("nan"), dtype=torch.float32, device="cuda") for n in ns]
+    T.check(T.teal_sparse_gemv_w8_multi(packed, scs, ts, ys2, ns, xd, m, ws))
+    torch.cuda.synchronize()
+    for a, b in zip(ys, ys2):
+        assert rel_l2(a.cpu().numpy(), b.cpu().numpy().astype(np.float64)) <= TIGHT
 
 
 # ---------------------------------------------------------------------------
@@ -732,9 +863,12 @@ def test_very_long_input_every_format(T):
     assert rel_l2(got, want) <= TIGHT
     kept = orc.sparsify(x, t)[3]
     assert survivors(T, ws) == [kept]
-    # asking for fewer splits than the length needs gives the same call
-    again = run_bf16(T, wt, xd, t, m, n, ws, splits=128)
-    assert np.array_equal(got, again)
+    # a block takes at most 8192 channels: asking for fewer splits than that needs gives the
+    # call with slices of 8192
+    few = run_bf16(T, wt, xd, t, m, n, ws, splits=1)
+    assert rel_l2(few, want) <= TIGHT
+    assert np.array_equal(few, run_bf16(T, wt, xd, t, m, n, ws, splits=2))   # both: slices of 8192
+    assert survivors(T, ws) == [kept]
     ys = [torch.full((k,), float("nan"), dtype=torch.float32, device="cuda") for k in (n, n)]
     t2 = ti.quantile_threshold(x, 0.9)
     T.check(T.teal_sparse_gemv_bf16_multi([wt, wt], [t, t2], ys, [n, n], xd, m, ws))
