@@ -25,4 +25,5 @@ from .binding import (  # noqa: F401
     MlpShape, teal_workspace_bytes_mlp, teal_mlp_down_region_offset, teal_mlp_status_offset,
     teal_mlp_plan, teal_mlp_block_info, teal_sparse_mlp_bf16, teal_sparse_mlp_w8, teal_sparse_mlp_w4,
     teal_sparse_gemv_bf16_multi_pitch, teal_sparse_gemv_w8_multi_pitch, teal_gemv_plan_multi_pitch,
+    teal_sparse_gemv_bf16_rmsnorm_multi_pitch,
 )

@@ -33,7 +33,8 @@ EXPORTS = (
     "teal_sparse_gemv_w8_multi", "teal_sparse_gemv_w4_multi",
     "teal_swiglu_f16", "teal_sparse_gemv_bf16_swiglu", "teal_sparse_gemv_bf16_batch_multi",
     "teal_gemv_plan_multi", "teal_gemv_plan_multi_pitch", "teal_sparse_gemv_bf16_multi_pitch",
-    "teal_sparse_gemv_w8_multi_pitch", "teal_survivors_offset", "teal_rmsnorm_f16",
+    "teal_sparse_gemv_w8_multi_pitch", "teal_sparse_gemv_bf16_rmsnorm_multi_pitch",
+    "teal_survivors_offset", "teal_rmsnorm_f16",
     "teal_sparse_gemv_bf16_rmsnorm_multi", "teal_workspace_bytes_stack",
     "teal_sparse_gemv_bf16_stack", "teal_sparse_gemv_w8_stack", "teal_sparse_gemv_w4_stack",
     "teal_stream_read_probe", "teal_sparse_gemv_w8_swiglu", "teal_sparse_gemv_w8_rmsnorm_multi",
@@ -91,6 +92,10 @@ def load_library():
     lib.teal_sparse_gemv_bf16_rmsnorm_multi.argtypes = [i, c.POINTER(vp), c.POINTER(f),
                                                         c.POINTER(vp), c.POINTER(i), vp, vp, f, i,
                                                         vp, sz, vp]
+    lib.teal_sparse_gemv_bf16_rmsnorm_multi_pitch.restype = i
+    lib.teal_sparse_gemv_bf16_rmsnorm_multi_pitch.argtypes = [i, c.POINTER(vp), c.POINTER(i),
+                                                              c.POINTER(f), c.POINTER(vp),
+                                                              c.POINTER(i), vp, vp, f, i, vp, sz, vp]
     lib.teal_survivors_offset.restype = sz
     lib.teal_survivors_offset.argtypes = []
     lib.teal_sparsify.restype = i
@@ -654,6 +659,25 @@ def teal_sparse_gemv_bf16_rmsnorm_multi(Wt_list, t_list, y_list, n_list, h, gamm
     return _call(
         "teal_sparse_gemv_bf16_rmsnorm_multi",
         count, W, Tt, Y, N, _ptr(h, 4 * m, "h"), _ptr(gamma, 4 * m, "gamma"), float(eps), int(m),
+        _ptr(workspace), _nbytes(workspace, workspace_bytes), _stream(stream))
+
+
+def teal_sparse_gemv_bf16_rmsnorm_multi_pitch(Wt_list, pitch_list, t_list, y_list, n_list, h, gamma,
+                                              eps, m, workspace, workspace_bytes=None,
+                                              stream=None) -> int:
+    """teal_sparse_gemv_bf16_rmsnorm_multi on matrices with rows pitch_list[k] elements apart."""
+    count = len(Wt_list)
+    if not (len(pitch_list) == len(t_list) == len(y_list) == len(n_list) == count):
+        raise ValueError("per-matrix lists must have the same length")
+    W = (ctypes.c_void_p * count)(*[_ptr(w, 2 * ((m - 1) * max(int(p), n) + n), "Wt")
+                                    for w, n, p in zip(Wt_list, n_list, pitch_list)])
+    P = (ctypes.c_int * count)(*[int(p) for p in pitch_list])
+    Y = (ctypes.c_void_p * count)(*[_ptr(y, 4 * n, "y") for y, n in zip(y_list, n_list)])
+    Tt = (ctypes.c_float * count)(*[float(t) for t in t_list])
+    N = (ctypes.c_int * count)(*[int(n) for n in n_list])
+    return _call(
+        "teal_sparse_gemv_bf16_rmsnorm_multi_pitch",
+        count, W, P, Tt, Y, N, _ptr(h, 4 * m, "h"), _ptr(gamma, 4 * m, "gamma"), float(eps), int(m),
         _ptr(workspace), _nbytes(workspace, workspace_bytes), _stream(stream))
 
 

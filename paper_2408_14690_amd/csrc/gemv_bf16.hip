@@ -120,8 +120,9 @@ hipError_t launch_gemv_bf16_stack(int groups, const StackGroupDesc *d, hipStream
     return hipGetLastError();
 }
 
-hipError_t launch_gemv_bf16_rmsnorm_multi(int count, const void *const *Wt, const float *t,
-                                          float *const *y, const int *n, const float *h,
+hipError_t launch_gemv_bf16_rmsnorm_multi(int count, const void *const *Wt, const int *row_pitch,
+                                          const float *t, float *const *y, const int *n,
+                                          const float *h,
                                           const float *gamma, float eps, int m, float *partial,
                                           int *counters, const GemvShape &sh, hipStream_t stream)
 {
@@ -136,6 +137,7 @@ hipError_t launch_gemv_bf16_rmsnorm_multi(int count, const void *const *Wt, cons
     ma.tile_begin[0] = 0;
     for (int k = 0; k < count; ++k) {
         ma.a[k].W = Wt[k];
+        ma.a[k].ld = row_pitch ? row_pitch[k] : 0;
         ma.y[k] = y[k];
         ma.t[k] = t[k];
         ma.n[k] = n[k];

@@ -447,7 +447,7 @@ hipError_t launch_gemv_w8_swiglu(const int8_t *Wq, const void *scale_f16, const 
     return hipGetLastError();
 }
 
-hipError_t launch_gemv_w8_rmsnorm_multi(int count, const int8_t *const *Wq,
+hipError_t launch_gemv_w8_rmsnorm_multi(int count, const int8_t *const *Wq, const int *row_pitch,
                                         const void *const *scale_f16, const float *t,
                                         float *const *y, const int *n, const float *h,
                                         const float *gamma, float eps, int m, float *partial,
@@ -464,6 +464,7 @@ hipError_t launch_gemv_w8_rmsnorm_multi(int count, const int8_t *const *Wq,
     ma.tile_begin[0] = 0;
     for (int k = 0; k < count; ++k) {
         ma.a[k].W = Wq[k];
+        ma.a[k].ld = row_pitch ? row_pitch[k] : 0;
         ma.a[k].scale = static_cast<const __half *>(scale_f16[k]);
         ma.y[k] = y[k];
         ma.t[k] = t[k];

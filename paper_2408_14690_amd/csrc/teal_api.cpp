@@ -696,11 +696,11 @@ teal_status teal_rmsnorm_f16(const float *h, const float *gamma, float eps, void
                                              static_cast<hipStream_t>(stream)));
 }
 
-teal_status teal_sparse_gemv_bf16_rmsnorm_multi(int count, const void *const *Wt_bf16,
-                                                const float *t, float *const *y, const int *n,
-                                                const float *h, const float *gamma, float eps,
-                                                int m, void *workspace, size_t workspace_bytes,
-                                                void *stream)
+static teal_status gemv_bf16_rmsnorm_multi(int count, const void *const *Wt_bf16,
+                                           const int *row_pitch, const float *t, float *const *y,
+                                           const int *n, const float *h, const float *gamma,
+                                           float eps, int m, void *workspace,
+                                           size_t workspace_bytes, void *stream)
 {
     if (count < 1 || count > teal::kMaxMatrices) return TEAL_ERR_UNSUPPORTED;
     if (!Wt_bf16 || !t || !y || !n || !h || !gamma || !workspace) return TEAL_ERR_NULL;
@@ -712,6 +712,7 @@ teal_status teal_sparse_gemv_bf16_rmsnorm_multi(int count, const void *const *Wt
     }
     if (m < 8 || m > teal::kMaxNormInput || m % 8 != 0 || n_total > teal::kMaxDim)
         return TEAL_ERR_SHAPE;
+    if (!pitches_ok(row_pitch, n, count, 8, 16)) return TEAL_ERR_SHAPE;
     for (int k = 0; k < count; ++k)
         if (!aligned(Wt_bf16[k], 16) || !aligned(y[k], 4)) return TEAL_ERR_ALIGN;
     if (!aligned(h, 16) || !aligned(gamma, 4) || !aligned(workspace, kAlignWorkspace))
@@ -720,12 +721,37 @@ teal_status teal_sparse_gemv_bf16_rmsnorm_multi(int count, const void *const *Wt
         if (!threshold_ok(t[k])) return TEAL_ERR_THRESHOLD;
     if (!norm_eps_ok(eps)) return TEAL_ERR_THRESHOLD;
     if (workspace_bytes < teal_workspace_bytes(m, (int)n_total)) return TEAL_ERR_WORKSPACE;
-    // The launch shape of teal_sparse_gemv_bf16_multi: same sums, bit for bit.
-    const GemvShape sh = count > 1 ? auto_shape_multi(m, n, count, 8, 16, 64, 64)
-                                   : auto_shape(m, (int)n_total, 8, 16, 64, 64);
+    // The launch shape of teal_sparse_gemv_bf16_multi (_pitch): same sums, bit for bit.  This
+    // kernel has no instance with 8 lanes per row and none for slices above kMaxSlice: there
+    // the shape of the packed call.
+    GemvShape sh = auto_shape_multi_pitch(m, n, row_pitch, count, 16, 8, 16, 64, 64);
+    if (sh.lanes_per_row < 16 || (sh.splits == 1 && m > teal::kMaxSlice))
+        sh = auto_shape_multi_pitch(m, n, nullptr, count, 16, 8, 16, 64, 64);
     return from_hip(teal::launch_gemv_bf16_rmsnorm_multi(
-        count, Wt_bf16, t, y, n, h, gamma, eps, m, ws_partials(workspace, m),
+        count, Wt_bf16, row_pitch, t, y, n, h, gamma, eps, m, ws_partials(workspace, m),
         ws_counters(workspace), sh, static_cast<hipStream_t>(stream)));
+}
+
+teal_status teal_sparse_gemv_bf16_rmsnorm_multi(int count, const void *const *Wt_bf16,
+                                                const float *t, float *const *y, const int *n,
+                                                const float *h, const float *gamma, float eps,
+                                                int m, void *workspace, size_t workspace_bytes,
+                                                void *stream)
+{
+    return gemv_bf16_rmsnorm_multi(count, Wt_bf16, nullptr, t, y, n, h, gamma, eps, m, workspace,
+                                   workspace_bytes, stream);
+}
+
+teal_status teal_sparse_gemv_bf16_rmsnorm_multi_pitch(int count, const void *const *Wt_bf16,
+                                                      const int *row_pitch, const float *t,
+                                                      float *const *y, const int *n,
+                                                      const float *h, const float *gamma,
+                                                      float eps, int m, void *workspace,
+                                                      size_t workspace_bytes, void *stream)
+{
+    if (!row_pitch) return TEAL_ERR_NULL;
+    return gemv_bf16_rmsnorm_multi(count, Wt_bf16, row_pitch, t, y, n, h, gamma, eps, m,
+                                   workspace, workspace_bytes, stream);
 }
 
 size_t teal_workspace_bytes_batch(int m, int n, int batch)
@@ -853,7 +879,7 @@ teal_status teal_sparse_gemv_w8_rmsnorm_multi(int count, const int8_t *const *Wq
     const GemvShape sh = count > 1 ? auto_shape_multi(m, n, count, 16, 8, 64, 64)
                                    : auto_shape(m, (int)n_total, 16, 8, 64, 64);
     return from_hip(teal::launch_gemv_w8_rmsnorm_multi(
-        count, Wq, scale_f16, t, y, n, h, gamma, eps, m, ws_partials(workspace, m),
+        count, Wq, nullptr, scale_f16, t, y, n, h, gamma, eps, m, ws_partials(workspace, m),
         ws_counters(workspace), sh, static_cast<hipStream_t>(stream)));
 }
 

@@ -52,10 +52,11 @@ hipError_t launch_gemv_bf16_swiglu(const void *Wt, const float *gate, const floa
 // The grouped bf16 launch with its shared input formed from the hidden state h before the
 // normalisation layer and the layer's weights gamma.  8 <= m <= 16384, m % 8 == 0; shapes
 // with 8 wavefronts, 4 loads per batch and 16, 32 or 64 lanes per row.
-hipError_t launch_gemv_bf16_rmsnorm_multi(int count, const void *const *Wt, const float *t,
-                                          float *const *y, const int *n, const float *h,
-                                          const float *gamma, float eps, int m, float *partial,
-                                          int *counters, const GemvShape &sh, hipStream_t stream);
+hipError_t launch_gemv_bf16_rmsnorm_multi(int count, const void *const *Wt, const int *row_pitch,
+                                          const float *t, float *const *y, const int *n,
+                                          const float *h, const float *gamma, float eps, int m,
+                                          float *partial, int *counters, const GemvShape &sh,
+                                          hipStream_t stream);
 hipError_t launch_rmsnorm_f16(const float *h, const float *gamma, float eps, void *x_f16, int m,
                               hipStream_t stream);
 hipError_t launch_swiglu_f16(const float *gate, const float *up, void *h_f16, int m,
@@ -115,11 +116,11 @@ hipError_t launch_gemv_w8_swiglu(const int8_t *Wq, const void *scale_f16, const 
                                  const float *up, float t, float *y, int m, int n, float *partial,
                                  int *counters, const GemvShape &shape, hipStream_t stream);
 
-hipError_t launch_gemv_w8_rmsnorm_multi(int count, const int8_t *const *Wq,
+hipError_t launch_gemv_w8_rmsnorm_multi(int count, const int8_t *const *Wq, const int *row_pitch,
                                         const void *const *scale_f16, const float *t,
                                         float *const *y, const int *n, const float *h,
                                         const float *gamma, float eps, int m, float *partial,
-                                        int *counters, const GemvShape &shape, hipStream_t stream);
+                                        int *counters, const GemvShape &sh, hipStream_t stream);
 
 hipError_t launch_gemv_w4(const uint8_t *Wq, const void *scale_f16, const void *x_f16,
                           float t, float *y, int m, int n, float *partial, int *counters,

@@ -696,6 +696,27 @@ def test_rmsnorm_argument_errors():
     assert call(count=5, t=(0.5,) * 5, n=(64,) * 5) == T.TEAL_ERR_UNSUPPORTED
 
 
+def test_rmsnorm_multi_pitch_argument_errors():
+    H, G = 0x60000, 0x70000
+    ok = dict(Wt_list=[W, W + 0x1000], pitch_list=[4096 + 128, 1024 + 128], t_list=[0.5, 0.25],
+              y_list=[Y, Y + 0x1000], n_list=[4096, 1024], h=H, gamma=G, eps=1e-5, m=4096,
+              workspace=WS, workspace_bytes=BIG, stream=0)
+
+    def call(**kw):
+        a = dict(ok)
+        a.update(kw)
+        return T.teal_sparse_gemv_bf16_rmsnorm_multi_pitch(**a)
+
+    assert call(h=None) == T.TEAL_ERR_NULL
+    assert call(Wt_list=[None, W]) == T.TEAL_ERR_NULL
+    assert call(pitch_list=[4096 - 8, 1024]) == T.TEAL_ERR_SHAPE
+    assert call(pitch_list=[4096 + 4, 1024]) == T.TEAL_ERR_SHAPE
+    assert call(m=4100) == T.TEAL_ERR_SHAPE
+    assert call(h=H + 4) == T.TEAL_ERR_ALIGN
+    assert call(eps=-1.0) == T.TEAL_ERR_THRESHOLD
+    assert call(workspace_bytes=64) == T.TEAL_ERR_WORKSPACE
+
+
 def test_plans_of_random_shapes_are_always_launchable():
     """Host logic: for any accepted shape the chosen launch shape satisfies what the kernels
     and the workspace assume (tile width a multiple of the vector width and within the lanes,

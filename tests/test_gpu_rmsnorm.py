@@ -138,6 +138,50 @@ def test_fused_grouped_product(T, name, ns, m, ps):
     assert np.array_equal(mask.cpu().numpy(), orc.sparsify(x, ts[0])[1])
 
 
+@pytest.mark.parametrize("name,ns,pads,m,ps", [
+    ("llama3 gate,up rotating", [14336, 14336], [128, 128], 4096, [0.5, 0.4]),
+    ("llama q,k,v padded", [4096, 1024, 1024], [128, 8, 0], 4096, [0.5, 0.4, 0.25]),
+    ("llama3 gate alone", [14336], [128], 4096, [0.5]),
+    ("ragged", [264, 72, 8], [8, 0, 136], 1000, [0.0, 0.5, 0.9]),
+], ids=["gate_up", "qkv", "gate", "ragged"])
+def test_fused_grouped_product_on_padded_rows(T, name, ns, pads, m, ps):
+    """Matrices with padded rows (bf16 NaNs in the padding): the oracle's result, the survivor
+    counts, and bit for bit the normalisation kernel followed by the grouped call on the same
+    matrices wherever that call's shape has an instance in this kernel (one 14336-wide matrix
+    would run in tiles of 8 lanes: there the packed call's shape, compared by value)."""
+    h, gamma = ti.norm_inputs(m, 610 + m)
+    hd, gd = dev(h), dev(gamma)
+    x = orc.rmsnorm_f16(h, gamma, EPS)
+    ts = [ti.quantile_threshold(x, p) for p in ps]
+    pitches = [n + p for n, p in zip(ns, pads)]
+    ws_host = [ti.weights_bf16(n, m, seed=3100 * k + n + m) for k, n in enumerate(ns)]
+    wide = []
+    for w, n, pitch in zip(ws_host, ns, pitches):
+        wt = torch.full((m, pitch), 0x7FC0, dtype=torch.int16, device="cuda")
+        wt[:, :n] = dev(ti.to_input_channel_major(w))
+        wide.append(wt)
+    ws = torch.zeros(T.teal_workspace_bytes(m, sum(ns)), dtype=torch.uint8, device="cuda")
+    ys = [torch.full((n,), float("nan"), dtype=torch.float32, device="cuda") for n in ns]
+    T.check(T.teal_sparse_gemv_bf16_rmsnorm_multi_pitch(wide, pitches, ts, ys, ns, hd, gd, EPS, m, ws))
+    torch.cuda.synchronize()
+    off = T.teal_survivors_offset()
+    assert ws[off:off + 4 * len(ns)].view(torch.int32).cpu().tolist() == [orc.sparsify(x, t)[3] for t in ts]
+    for k, n in enumerate(ns):
+        got = ys[k].cpu().numpy()
+        assert rel_l2(got, orc.sparse_gemv_bf16_rmsnorm(ws_host[k], h, gamma, EPS, ts[k])) <= TIGHT, (name, k)
+    xd = torch.empty(m, dtype=torch.int16, device="cuda")
+    T.check(T.teal_rmsnorm_f16(hd, gd, EPS, xd, m))
+    ys2 = [torch.full((n,), float("nan"), dtype=torch.float32, device="cuda") for n in ns]
+    T.check(T.teal_sparse_gemv_bf16_multi_pitch(wide, pitches, ts, ys2, ns, xd, m, ws))
+    torch.cuda.synchronize()
+    st, plan = T.teal_gemv_plan_multi_pitch(16, m, ns, pitches)
+    for a, b in zip(ys, ys2):
+        if plan["lanes_per_row"] >= 16:
+            assert torch.equal(a, b)
+        else:
+            assert rel_l2(a.cpu().numpy(), b.cpu().numpy().astype(np.float64)) <= TIGHT
+
+
 def test_fused_grouped_product_with_nan_in_the_hidden_state(T):
     m, ns = 4096, [1024, 264]
     h, gamma = ti.norm_inputs(m, 88)
