@@ -161,7 +161,8 @@ bool mlp_grid_of(int weight_bits, const MlpLaunch &L, int m, int f, int d, MlpGr
     const int epl = weight_bits == 16 ? 8 : weight_bits == 8 ? 16 : 32;
     if (weight_bits != 16 && weight_bits != 8 && weight_bits != 4) return false;
     if (!mlp_shape_ok(L.gu, epl) || !mlp_shape_ok(L.down, epl)) return false;
-    return mlp_grid(grid, ggu, gd, L, m, f, d, epl, weight_bits == 4 ? 128 : 64);
+    return mlp_grid(grid, ggu, gd, L, m, f, d, epl, weight_bits == 4 ? 128 : 64,
+                    weight_bits == 4 ? kMaxSlice : kMaxLongSlice);
 }
 
 hipError_t launch_mlp_bf16(const MlpHostArgs &h, const MlpLaunch &L, hipStream_t stream)

@@ -160,9 +160,9 @@ __global__ __launch_bounds__(8 * 64) void sparse_mlp_kernel(MlpArgs<typename Bod
 
 // Host side.  Geometry of the two products from their launch shapes, argument block.
 inline bool mlp_grid(MlpGrid &g, GemvGeometry &ggu, GemvGeometry &gd, const MlpLaunch &L, int m,
-                     int f, int d, int elems_per_lane, int ks_multiple)
+                     int f, int d, int elems_per_lane, int ks_multiple, int max_slice_gu = kMaxSlice)
 {
-    ggu = gemv_geometry(m, f, L.gu, elems_per_lane, ks_multiple);
+    ggu = gemv_geometry(m, f, L.gu, elems_per_lane, ks_multiple, max_slice_gu);
     gd = gemv_geometry(f, d, L.down, elems_per_lane, ks_multiple);
     if ((long long)gd.tiles * gd.splits > kMlpMaxConsumers) return false;
     g.f = f;
@@ -182,7 +182,10 @@ bool fill_mlp_args(MlpArgs<F> &A, size_t &lds, const MlpHostArgs &h, const MlpLa
                    int ks_multiple, SetArgs set_args)
 {
     GemvGeometry ggu, gd;
-    if (!mlp_grid(A.grid, ggu, gd, L, h.m, h.f, h.d, F::kElemsPerLane, ks_multiple)) return false;
+    // gate / up slices of up to kMaxLongSlice channels where the block body compacts in pieces
+    if (!mlp_grid(A.grid, ggu, gd, L, h.m, h.f, h.d, F::kElemsPerLane, ks_multiple,
+                  F::kBitsPerElem == 4 ? kMaxSlice : kMaxLongSlice))
+        return false;
     set_args(A.a_gu[0], h.W_gate, h.scale_gate, h.gu_pitch);
     set_args(A.a_gu[1], h.W_up, h.scale_up, h.gu_pitch);
     set_args(A.a_d, h.W_down, h.scale_down, h.down_pitch);
@@ -214,7 +217,10 @@ hipError_t launch_mlp_kernel(const MlpArgs<typename Body::Format> &A, int lanes_
 {
     const dim3 grid(mlp_blocks(A.grid)), block(8 * 64);
 #define TEAL_MLP_LAUNCH(LG, LD)                                                                \
-    hipLaunchKernelGGL((sparse_mlp_kernel<Body, LG, LD>), grid, block, lds, stream, A)
+    do {                                                                                       \
+        if (!allow_large_lds(sparse_mlp_kernel<Body, LG, LD>, lds)) return hipErrorInvalidValue; \
+        hipLaunchKernelGGL((sparse_mlp_kernel<Body, LG, LD>), grid, block, lds, stream, A);   \
+    } while (0)
 #define TEAL_MLP_DOWN(LG)                                                                      \
     do {                                                                                       \
         if (lanes_d == 64) TEAL_MLP_LAUNCH(LG, 64);                                            \

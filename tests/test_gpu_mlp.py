@@ -392,6 +392,8 @@ def padded(T, wt, pitch):
     (1024, 1536, 512, 1536 + 128, 0, dict(gu_lanes_per_row=64, gu_tile_cols=512, gu_splits=4,
                                          down_lanes_per_row=16, down_tile_cols=128, down_splits=1)),
     (4096, 14336, 4096, 14336 + 128, 4096 + 128, {}),
+    # 70B-sized: gate / up without split-K, a block compacting all 8192 channels
+    (8192, 28672, 8192, 28672 + 128, 8192 + 128, dict(gu_lanes_per_row=32, gu_tile_cols=256, gu_splits=1)),
 ])
 def test_padded_rows_give_the_same_bits(T, m, f, d, pg, pd, over):
     """Row pitches above the row length (teal_mlp_shape): gate, up and y are bit for bit those
@@ -409,6 +411,8 @@ def test_padded_rows_give_the_same_bits(T, m, f, d, pg, pd, over):
     gate, up, y = run_mlp(T, M, t_down, ws, sh)
     check_against_oracle(T, M, gate, up, y, t_down, ws,
                          rows=None if f <= 4096 else np.arange(0, f, 193).astype(np.int32))
+    rg, ru, ry = separate_calls(T, M, t_down, sh)
+    assert bits_equal(gate, rg) and bits_equal(up, ru) and bits_equal(y, ry)
     packed = M.wt
     M.wt = [padded(T, packed[0], pg), padded(T, packed[1], pg),
             padded(T, packed[2], pd) if pd else packed[2]]
