@@ -14,6 +14,9 @@
 #include <hip/hip_runtime.h>
 
 #include "teal_internal.h"
+#include <map>
+#include <mutex>
+#include <utility>
 
 namespace teal {
 
@@ -916,13 +919,28 @@ __global__ __launch_bounds__(WAVES * 64) void sparse_gemv_stack_kernel(StackArgs
 // A launch that asks for more dynamic LDS than the 64 KiB every kernel may use has to raise
 // the kernel's limit first (a list of more than kMaxSlice entries).  Host side; false when
 // the runtime refuses.
+// The limit is raised once per kernel and device and remembered, so that later launches
+// (also those recorded into a graph after a first eager call) make no runtime call here.
+inline bool allow_large_lds_of(const void *kernel, size_t lds_bytes)
+{
+    if (lds_bytes <= 64 * 1024) return true;
+    static std::mutex lock;
+    static std::map<std::pair<int, const void *>, size_t> granted;
+    int device = 0;
+    if (hipGetDevice(&device) != hipSuccess) return false;
+    std::lock_guard<std::mutex> hold(lock);
+    size_t &have = granted[{device, kernel}];
+    if (have >= lds_bytes) return true;
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) !=
+        hipSuccess)
+        return false;
+    have = lds_bytes;
+    return true;
+}
 template <class Kernel>
 inline bool allow_large_lds(Kernel kernel, size_t lds_bytes)
 {
-    if (lds_bytes <= 64 * 1024) return true;
-    return hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                               hipFuncAttributeMaxDynamicSharedMemorySize,
-                               (int)lds_bytes) == hipSuccess;
+    return allow_large_lds_of(reinterpret_cast<const void *>(kernel), lds_bytes);
 }
 
 // Host-side launch geometry shared by the formats.

@@ -1002,6 +1002,54 @@ def test_calls_replay_from_a_hip_graph(T):
             assert torch.equal(a, b), replay
 
 
+def test_long_slices_replay_from_a_hip_graph(T):
+    """A block that takes more than 4096 channels needs more dynamic LDS than the default
+    limit; the limit is raised at the first (eager) launch of that kernel, so the same call
+    recorded into a graph afterwards replays with the bits of the eager call."""
+    m, n = 8192, 264
+    w = ti.weights_bf16(n, m, 51)
+    wt = dev(ti.to_input_channel_major(w))
+    x = ti.gaussian_x(m, 52)
+    xd = dev(x)
+    t = ti.quantile_threshold(x, 0.5)
+    ws = workspace(T, m, 2 * n)
+    wide = padded_rows(wt, n + 128, 0x7FC0)
+    ys = [torch.zeros(n, dtype=torch.float32, device="cuda") for _ in range(3)]
+
+    def enqueue(stream):
+        T.check(T.teal_sparse_gemv_bf16_ex(wt, xd, t, ys[0], m, n, ws, stream=stream, lanes_per_row=16,
+                                           tile_cols=128, splits=1, waves=8, unroll=4))
+        T.check(T.teal_sparse_gemv_bf16_multi_pitch([wide, wide], [n + 128] * 2, [t, 0.0], ys[1:], [n, n],
+                                                    xd, m, ws, stream=stream))
+
+    enqueue(torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    eager = [y.clone() for y in ys]
+    assert rel_l2(eager[0].cpu().numpy(), orc.sparse_gemv_bf16(w, x, t)) <= TIGHT
+    assert rel_l2(eager[1].cpu().numpy(), orc.sparse_gemv_bf16(w, x, t)) <= TIGHT
+    assert rel_l2(eager[2].cpu().numpy(), orc.sparse_gemv_bf16(w, x, 0.0)) <= TIGHT
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        enqueue(side)
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        enqueue(side)
+    for replay in range(3):
+        for y in ys:
+            y.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(eager, ys):
+            assert torch.equal(a, b), replay
+        enqueue(torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        for a, b in zip(eager, ys):
+            assert torch.equal(a, b), replay
+
+
 # ---------------------------------------------------------------------------
 # seeded random shapes through the default launch of every format
 # ---------------------------------------------------------------------------
