@@ -104,31 +104,36 @@ def alone(T, torch, C, p_head, launches=300):
 
 
 def padded_rows_detail(T, torch, by_name, groups, fmt, sparsities, p_head, packed_per_step):
-    """W_gate and W_up stored with rows 256 bytes further apart (the library's _pitch entry
-    points; the same weights and input): the pair in one launch, one of them alone, and the
-    block pass with the pair's launch replaced.  With such rows the pair runs in tiles of
-    256 bytes of a row without split-K."""
+    """The matrices of the grouped launches (W_q, W_k, W_v; W_gate, W_up) stored with rows 256
+    bytes further apart (the library's _pitch entry points; the same weights and inputs): each
+    group in one launch, one gate alone, and the block pass with the two launches replaced.
+    With such rows the gate + up pair runs in tiles of 256 bytes of a row without split-K."""
     pad = 256 * 8 // BITS[fmt]
-    G, U = by_name["gate"], by_name["up"]
-    wide = [Projection(T, torch, P.name, P.n, P.m, fmt, P.x_host, sparsities, len(P.weights),
-                       w_host=P.w_host, row_pad=pad) for P in (G, U)]
-    pair = FusedGroup(T, torch, wide)
-    out = {"row_pitch_elements": wide[0].pitch,
-           "launch": T.teal_gemv_plan_multi_pitch(BITS[fmt], G.m, [G.n, U.n], [wide[0].pitch] * 2)[1]}
-    # same sums as the packed call, in another order: compared by value
-    packed_pair = next(g for g in groups if g.name == "gate+up")
+    wide = {name: Projection(T, torch, name, by_name[name].n, by_name[name].m, fmt, by_name[name].x_host,
+                             sparsities, len(by_name[name].weights), w_host=by_name[name].w_host,
+                             row_pad=pad) for name in ("q", "k", "v", "gate", "up")}
+    new_groups = {"q+k+v": FusedGroup(T, torch, [wide["q"], wide["k"], wide["v"]]),
+                  "gate+up": FusedGroup(T, torch, [wide["gate"], wide["up"]])}
+    out = {"row_pad_elements": pad}
+    # same sums as the packed calls, possibly in another order: compared by value
     worst = 0.0
-    for call, members in ((packed_pair, (G, U)), (pair, wide)):
-        T.check(call.enqueue(T, 0, p_head))
-    torch.cuda.synchronize()
-    for a, b in zip((G, U), wide):
-        ya, yb = a.y.double(), b.y.double()
-        worst = max(worst, float((ya - yb).norm() / ya.norm()))
+    for name, group in new_groups.items():
+        packed = next(g for g in groups if g.name == name)
+        T.check(packed.enqueue(T, 0, p_head))
+        T.check(group.enqueue(T, 0, p_head))
+        torch.cuda.synchronize()
+        for a, b in zip(packed.members, group.members):
+            ya, yb = a.y.double(), b.y.double()
+            worst = max(worst, float((ya - yb).norm() / ya.norm()))
     out["rel_l2_vs_packed_rows"] = worst
-    out["gate+up"] = alone(T, torch, pair, p_head)
-    out["gate"] = alone(T, torch, wide[0], p_head)
-    out["gate"]["launch"] = T.teal_gemv_plan_multi_pitch(BITS[fmt], G.m, [G.n], [wide[0].pitch])[1]
-    swapped = [pair if g.name == "gate+up" else g for g in groups]
+    for name, group in new_groups.items():
+        out[name] = alone(T, torch, group, p_head)
+        out[name]["launch"] = T.teal_gemv_plan_multi_pitch(BITS[fmt], group.m, group.ns,
+                                                           [P.pitch for P in group.members])[1]
+    out["gate"] = alone(T, torch, wide["gate"], p_head)
+    out["gate"]["launch"] = T.teal_gemv_plan_multi_pitch(BITS[fmt], wide["gate"].m, [wide["gate"].n],
+                                                         [wide["gate"].pitch])[1]
+    swapped = [new_groups.get(g.name, g) for g in groups]
     per_step = time_pass(T, torch, swapped, p_head, 200, 50, 5)
     dense = time_pass(T, torch, swapped, 0.0, 200, 50, 5)
     out["block_pass_one_launch_per_group"] = pass_figures(swapped, p_head, per_step, dense)
@@ -254,16 +259,15 @@ def main() -> int:
     # consecutive steps walk several copies of a small workload's weights; a stack beyond the
     # last-level cache many times over needs none
     copies = args.copies or max(1, -(-CACHE_DEFEAT_BYTES // (block_bytes * layers)))
-    # Layout of W_gate / W_up: rows 256 bytes further apart when the library then runs the
-    # pair without split-K (teal_gemv_plan_multi_pitch); the layout is the library's own step
-    # (teal_pack_bf16_pitch), the bytes read are the same.
+    # Layout of the matrices of the grouped launches (W_q, W_k, W_v and W_gate, W_up): rows 256
+    # bytes further apart, so that a narrow tile meets all four 256-byte quarters of a KiB over
+    # its rows; the gate + up pair then runs without split-K where the library's rule allows
+    # (teal_gemv_plan_multi_pitch).  The layout is the library's own step (teal_pack_bf16_pitch),
+    # the bytes read are the same.
     row_pad, rows = {}, "packed"
     if args.rows == "padded" and fmt in ("bf16", "w8") and not args.stack_launch and not args.unfused:
         pad = 256 * 8 // BITS[fmt]
-        n_gu, m_gu = shapes["gate"]
-        st, plan = T.teal_gemv_plan_multi_pitch(BITS[fmt], m_gu, [n_gu, n_gu], [n_gu + pad] * 2)
-        if st == 0 and plan["splits"] == 1:
-            row_pad, rows = {"gate": pad, "up": pad}, "padded"
+        row_pad, rows = {name: pad for name in ("q", "k", "v", "gate", "up")}, "padded"
     t_build = time.perf_counter()
     projections = build_stack(T, torch, args.workload, fmt, sparsities, layers, copies, row_pad=row_pad)
     block0 = projections[:7]
@@ -323,8 +327,8 @@ def main() -> int:
                         f"one fresh seeded fp16 x per projection input (Gaussian / Laplace by role), t at "
                         f"the {pct(head)} quantile of |x| per projection",
             "weight_format": fmt,
-            "weight_rows": ("W_gate and W_up stored with rows 256 bytes further apart (teal_pack_bf16_pitch), "
-                            "the other matrices packed" if rows == "padded" else "packed"),
+            "weight_rows": ("W_q, W_k, W_v, W_gate and W_up stored with rows 256 bytes further apart "
+                            "(teal_pack_bf16_pitch), W_o and W_down packed" if rows == "padded" else "packed"),
             "weight_bytes_per_block": block_bytes,
             "blocks_per_step": layers,
             "launches": launches_text,
