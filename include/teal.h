@@ -175,7 +175,10 @@ teal_status teal_sparse_gemv_bf16_multi(int count, const void *const *Wt_bf16, c
  * multiple of 256 bytes (n + 128 elements where 2 n is a multiple of 1024) a
  * 256-byte tile of a row falls on a different quarter of a KiB on every row,
  * all tiles stream at the same speed, and a group with about one such tile
- * per compute unit and m <= 4096 runs without split-K.
+ * (of 256 bytes, else 512, else 128 for m <= 4096) per compute unit and
+ * m <= 8192 runs without split-K.  A pitch that is not a multiple of 256
+ * bytes is accepted but puts the wider tiles of other launch shapes off the
+ * 128-byte lines of the memory system (measured 20-30 % slower).
  */
 teal_status teal_sparse_gemv_bf16_multi_pitch(int count, const void *const *Wt_bf16,
                                               const int *row_pitch, const float *t,
