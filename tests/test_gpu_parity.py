@@ -585,6 +585,66 @@ def test_gemv_bf16_multi_pitch(T, name, ns, pitches, m, ps):
         assert torch.equal(a, b)
 
 
+def test_multi_pitch_edge_cases(T):
+    """Padded rows at the edges: nothing / everything survives and ties at the threshold on the
+    shape without split-K; one matrix of the group on rotating rows and one not (the packed
+    call's shape on padded rows); a pitch far above the row; four matrices; run-to-run and
+    workspace-to-workspace reproducibility."""
+    m = 4096
+    ns = [14336, 14336]
+    x = ti.gaussian_x(m, 930)
+    x[100:164] = np.float16(0.5)                       # a run of ties at the threshold below
+    x[200:232] = np.float16(-0.5)
+    xd = dev(x)
+    hosts = [ti.weights_bf16(n, m, seed=1200 + k) for k, n in enumerate(ns)]
+    packed = [dev(ti.to_input_channel_major(w)) for w in hosts]
+
+    def run(pitches, ts, ws):
+        wide = [padded_rows(p, pitch, 0x7FC0) for p, pitch in zip(packed, pitches)]
+        ys = [torch.full((n,), float("nan"), dtype=torch.float32, device="cuda") for n in ns]
+        T.check(T.teal_sparse_gemv_bf16_multi_pitch(wide, pitches, ts, ys, ns, xd, m, ws))
+        torch.cuda.synchronize()
+        return [y.cpu().numpy() for y in ys]
+
+    ws = workspace(T, m, sum(ns))
+    rot = [n + 128 for n in ns]
+    rows = np.arange(0, ns[0], 131).astype(np.int32)
+    # ties: |x| == t is dropped (Definition 1), also without split-K
+    got = run(rot, [0.5, 0.5], ws)
+    assert survivors(T, ws, 2) == [orc.sparsify(x, 0.5)[3]] * 2
+    for k in range(2):
+        assert rel_l2(got[k][rows], orc.sparse_gemv_bf16_rows(hosts[k], x, 0.5, rows)) <= TIGHT
+    # nothing survives / everything survives
+    got = run(rot, [70000.0, 0.0], ws)
+    assert not got[0].any() and survivors(T, ws, 2) == [0, orc.sparsify(x, 0.0)[3]]
+    assert rel_l2(got[1][rows], orc.sparse_gemv_bf16_rows(hosts[1], x, 0.0, rows)) <= TIGHT
+    # run to run, and on another workspace: the same bits
+    a = run(rot, [0.25, 0.625], ws)
+    b = run(rot, [0.25, 0.625], workspace(T, m, sum(ns)))
+    assert all(np.array_equal(u, v) for u, v in zip(a, b))
+    # only one matrix on rotating rows, and a pitch far above the row: the packed call's shape
+    for pitches in ([ns[0] + 128, ns[1]], [ns[0] + 4096 + 8, ns[1] + 40]):
+        st, plan = T.teal_gemv_plan_multi_pitch(16, m, ns, pitches)
+        assert st == 0 and plan == T.teal_gemv_plan_multi(16, m, ns)[1]
+        c = run(pitches, [0.25, 0.625], ws)
+        for k in range(2):
+            assert rel_l2(c[k], a[k].astype(np.float64)) <= TIGHT
+            assert rel_l2(c[k][rows], orc.sparse_gemv_bf16_rows(hosts[k], x, [0.25, 0.625][k], rows)) <= TIGHT
+    # four matrices that share x, rotating rows: 4 x 5120 columns = 160 tiles of 256 bytes
+    ns4 = [5120] * 4
+    hosts4 = [ti.weights_bf16(n, m, seed=1300 + k) for k, n in enumerate(ns4)]
+    wide4 = [padded_rows(dev(ti.to_input_channel_major(w)), n + 384, 0x7FC0) for w, n in zip(hosts4, ns4)]
+    ts4 = [ti.quantile_threshold(x, p) for p in (0.25, 0.5, 0.65, 0.9)]
+    ys4 = [torch.full((n,), float("nan"), dtype=torch.float32, device="cuda") for n in ns4]
+    st, plan = T.teal_gemv_plan_multi_pitch(16, m, ns4, [n + 384 for n in ns4])
+    assert st == 0 and (plan["tile_cols"], plan["splits"]) == (128, 1)
+    T.check(T.teal_sparse_gemv_bf16_multi_pitch(wide4, [n + 384 for n in ns4], ts4, ys4, ns4, xd, m, ws))
+    torch.cuda.synchronize()
+    assert survivors(T, ws, 4) == [orc.sparsify(x, t)[3] for t in ts4]
+    for k in range(4):
+        assert rel_l2(ys4[k].cpu().numpy(), orc.sparse_gemv_bf16(hosts4[k], x, ts4[k])) <= TIGHT, k
+
+
 def test_gemv_w8_multi_pitch(T):
     ns, m = [14336 * 2, 14336 * 2], 4096
     pitches = [n + 256 for n in ns]
