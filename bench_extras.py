@@ -394,6 +394,9 @@ def main() -> int:
                     help="time threshold calibration (histogram + thresholds) instead of the GEMV path")
     ap.add_argument("--calibration-tokens", type=int, default=16384)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--rows", default="packed", choices=("packed", "padded"),
+                    help="padded: W_q, W_k, W_v, W_gate, W_up stored with rows 256 bytes further apart "
+                         "(bf16 / int8, batch 1; the stack launch needs packed rows and is skipped)")
     ap.add_argument("--no-per-projection", action="store_true")
     ap.add_argument("--no-other-mode", action="store_true",
                     help="skip timing the pass in the launch mode that is not the headline")
@@ -437,12 +440,19 @@ def main() -> int:
     if args.batch and (fmt != "bf16" or not 1 <= args.batch <= T.TEAL_MAX_BATCH):
         print("bench_extras.py: --batch needs bf16 and 1 <= B <= 8", file=sys.stderr)
         return 2
+    row_pad = {}
+    if args.rows == "padded":
+        if args.batch or fmt == "w4" or args.stack_launch:
+            print("bench_extras.py: --rows padded needs bf16 or int8, batch 1, no --stack-launch",
+                  file=sys.stderr)
+            return 2
+        row_pad = {name: 256 * 8 // BITS[fmt] for name in ("q", "k", "v", "gate", "up")}
     projections = build_stack(T, torch, args.workload, fmt, sparsities, args.layers, copies,
-                              args.batch)
+                              args.batch, row_pad=row_pad)
     block0 = projections[:7]
     groups = fuse(T, torch, projections)
     stack_calls = None
-    if not args.batch and (args.stack_launch or not args.no_other_mode):
+    if not args.batch and not row_pad and (args.stack_launch or not args.no_other_mode):
         stack_calls = [StackCall(T, torch, groups[i:i + 16]) for i in range(0, len(groups), 16)]
     if args.stack_launch:
         if stack_calls is None or args.unfused:
@@ -596,6 +606,7 @@ def main() -> int:
                         f"Laplace by role), t at the {pct(head)} quantile of "
                         f"{'the batch-averaged |x|' if args.batch else '|x|'} per projection",
             "weight_format": fmt,
+            "weight_rows": args.rows,
             "weight_bytes_per_block": block_bytes,
             "blocks_per_step": args.layers,
             "launches": "one per 16 groups (q+k+v, o, gate+up, down of 4 blocks), the groups taken "
