@@ -4,7 +4,8 @@
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--repeats R]
                     [--workload llama_70b|llama3_8b|llama2_7b] [--layers L]
                     [--format bf16|w8|w4] [--sparsities 0.5,0]
-                    [--unfused | --stack-launch] [--no-detail] [--no-cpu-baseline]
+                    [--unfused | --stack-launch] [--rows padded|packed] [--no-detail]
+                    [--no-cpu-baseline]
 
 A step is one pass of the whole hot path over a synthetic stack of decoder blocks at batch
 1: for each of the seven projections of every block, threshold the hidden state, compact the
@@ -18,11 +19,15 @@ own, --stack-launch issues 16 groups per launch as independent work (a bare stac
 decoder's dependent sequence).  The headline value is the effective HBM bandwidth of that
 pass at the first listed sparsity: algorithmic bytes / time, the time being the median over
 R repetitions of a region of exactly K back-to-back steps.  The same pass at t = 0 (the same
-kernels run dense) gives the speed-up over dense.
+kernels run dense) gives the speed-up over dense.  The matrices of the grouped launches (q,
+k, v, gate, up) are stored with rows 256 bytes further apart (the library's own layout step,
+teal_pack_bf16_pitch; --rows packed for packed rows): a narrow tile then meets every quarter
+of the address space over its rows and the gate + up pair runs without split-K.
 
 Beside the headline, `llama3_8b_block` carries the 4096 x 14336-class figures: every
-projection and every group of a Llama-3-8B-shaped block timed alone, the block pass, and the
-MLP on its own data flow in one, two and three launches.  Side measurements (calibration,
+projection and every group of a Llama-3-8B-shaped block timed alone (packed and padded rows),
+the block pass, and the MLP on its own data flow in one, two and three launches; it is timed
+before the stack is laid out.  Side measurements (calibration,
 producer fusion, small batches, graph replay, the sparsity sweep) live in bench_extras.py.
 
 Prints ONE JSON line.  More than one GPU is not supported.
