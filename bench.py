@@ -170,7 +170,7 @@ def llama3_8b_block_detail(T, torch, fmt: str, p_head: float):
                        "outputs (Appendix A.3): the dependent sequence a decoder runs",
                "effective_bytes": mlp.bytes(p_head)}
     modes = ("one_launch", "two_launches", "three_launches") + \
-        (("one_launch_padded_rows",) if fmt == "bf16" else ())
+        (("one_launch_padded_rows",) if fmt in ("bf16", "w8") else ())
     for mode in modes:
         mlp.mode = mode
         us = call_us(T, torch, mlp, p_head)
@@ -179,14 +179,15 @@ def llama3_8b_block_detail(T, torch, fmt: str, p_head: float):
         mlp_out[mode] = {"us": us, "us_dense": us_dense, "effective_GBps": b / us / 1e3,
                          "frac_of_hbm_peak": b / us / 1e3 / HBM_PEAK_GBS,
                          "speedup_vs_dense": us_dense / us}
-    if fmt == "bf16":
-        st, sh = T.teal_mlp_plan(16, mlp.m, mlp.f, mlp.d)
+    if fmt in ("bf16", "w8"):
+        st, sh = T.teal_mlp_plan(BITS[fmt], mlp.m, mlp.f, mlp.d)
         mlp_out["one_launch"]["shape"] = sh.as_dict()
         mlp_out["one_launch_padded_rows"]["shape"] = mlp.padded_shape.as_dict()
         mlp_out["one_launch_padded_rows"]["note"] = (
-            "the same matrices stored with rows 256 bytes further apart (row pitch f + 128 and "
-            "d + 128 elements): every block's reads then spread evenly over the memory channels")
-        # the padded layout must not change a bit of the result
+            "the same matrices stored with rows 256 bytes further apart, in the shape teal_mlp_plan "
+            "gives for those pitches: every block's reads then spread evenly over the memory channels")
+        # the padded layout must not change a bit of the result where the shape stays the same;
+        # another shape adds the same terms in another order
         outs = {}
         for mode in ("one_launch", "one_launch_padded_rows"):
             mlp.mode = mode
@@ -196,6 +197,9 @@ def llama3_8b_block_detail(T, torch, fmt: str, p_head: float):
         mlp_out["one_launch_padded_rows"]["bitwise_equal_to_one_launch"] = all(
             torch.equal(a.view(torch.int32), b.view(torch.int32))
             for a, b in zip(outs["one_launch"], outs["one_launch_padded_rows"]))
+        mlp_out["one_launch_padded_rows"]["rel_l2_vs_one_launch"] = max(
+            float(((a.double() - b.double()).norm() / b.double().norm()).item())
+            for a, b in zip(outs["one_launch_padded_rows"], outs["one_launch"]))
     mlp.mode = "one_launch"
     one_step(T, [mlp], p_head, 0)
     torch.cuda.synchronize()

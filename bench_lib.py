@@ -574,10 +574,11 @@ class MlpCall:
     grouped gate + up call, then W_down with its input formed in the kernel), or three (gate,
     up, W_down each on its own).  The threshold of W_down is the quantile of |h| for the h
     the library's own producer forms from the gate / up outputs at that sparsity.
-    "one_launch_padded_rows" (bf16) is the one launch on copies of the same matrices stored
-    with rows 256 bytes further apart (teal_mlp_shape's row pitches; same bytes read)."""
+    "one_launch_padded_rows" (bf16, int8) is the one launch on copies of the same matrices
+    stored with rows 256 bytes further apart (teal_mlp_shape's row pitches; same bytes read),
+    in the shape teal_mlp_plan picks for that layout."""
 
-    PAD = 128      # bf16 elements added to a row's pitch: an odd multiple of 256 bytes
+    PAD_BYTES = 256      # added to a row's pitch: rows then lie an odd multiple of 256 bytes apart
 
     def __init__(self, T, torch, gate, up, down, sparsities):
         self.gate, self.up, self.down = gate, up, down
@@ -605,22 +606,22 @@ class MlpCall:
             self.nnz_h[p] = int(np.count_nonzero(np.abs(hh.astype(np.float32)) > np.float32(self.t_down[p])))
 
     def _pad_weights(self, T):
-        """Padded-row copies of the bf16 matrices, one per weight copy, and the shape that
-        names their pitches."""
+        """Padded-row copies of the matrices (bf16, int8), one per weight copy, and the shape
+        the library plans for their pitches."""
         torch = self.torch
+        pad_elems = self.PAD_BYTES * 8 // BITS[self.fmt]
 
         def pad(w, pitch):
             out = torch.zeros((w.shape[0], pitch), dtype=w.dtype, device="cuda")
             out[:, :w.shape[1]] = w
             return out
 
-        pg, pd = self.f + self.PAD, self.d + self.PAD
+        pg, pd = self.f + pad_elems, self.d + pad_elems
         G, U, D = self.gate, self.up, self.down
         self.padded = [(pad(G.weights[c][0], pg), pad(U.weights[c % len(U.weights)][0], pg),
                         pad(D.weights[c % len(D.weights)][0], pd)) for c in range(len(G.weights))]
-        st, sh = T.teal_mlp_plan(16, self.m, self.f, self.d)
+        st, sh = T.teal_mlp_plan(BITS[self.fmt], self.m, self.f, self.d, pg, pd)
         T.check(st)
-        sh.gu_row_pitch, sh.down_row_pitch = pg, pd
         self.padded_shape = sh
 
     def _enqueue(self, T, copy, p, t_down=None):
@@ -630,11 +631,16 @@ class MlpCall:
         gp, up_, yp = self.g.data_ptr(), self.u.data_ptr(), self.y.data_ptr()
         m, f, d, st = self.m, self.f, self.d, self.stream
         if self.mode == "one_launch_padded_rows":
-            if self.fmt != "bf16":
-                raise ValueError("padded rows are timed for bf16 only")
+            if self.fmt not in ("bf16", "w8"):
+                raise ValueError("padded rows are timed for bf16 and int8")
             if self.padded is None:
                 self._pad_weights(T)
             w = self.padded[copy % len(self.padded)]
+            if self.fmt == "w8":
+                return T.teal_sparse_mlp_w8(w[0].data_ptr(), w[1].data_ptr(), w[2].data_ptr(), wg[1],
+                                            wu[1], wd[1], G.xp, G.t[p], U.t[p], td, gp, up_, yp, m, f, d,
+                                            self.ws.data_ptr(), self.ws.numel(), st,
+                                            shape=self.padded_shape)
             return T.teal_sparse_mlp_bf16(w[0].data_ptr(), w[1].data_ptr(), w[2].data_ptr(), G.xp,
                                           G.t[p], U.t[p], td, gp, up_, yp, m, f, d,
                                           self.ws.data_ptr(), self.ws.numel(), st,

@@ -456,8 +456,8 @@ teal_status teal_sparse_gemv_w4_multi(int count, const uint8_t *const *Wq,
  *           span m * gu_row_pitch (f * down_row_pitch) elements, the last
  *           row included.  A pitch of an odd multiple of 256 bytes (f + 128
  *           bf16 elements when 2 f is a multiple of 1024) spreads every
- *           block's reads evenly over the memory channels; teal_mlp_plan
- *           leaves both at 0, since the layout is the caller's.
+ *           block's reads evenly over the memory channels; shape == NULL
+ *           means packed rows.
  * Waits are bounded.  A block of W_down that does not see its inputs within
  * spin_limit polls stores 1 to the int32 status word at byte
  * teal_mlp_status_offset(m, f, d) of the workspace and leaves, and so does
@@ -472,7 +472,13 @@ teal_status teal_sparse_gemv_w4_multi(int count, const uint8_t *const *Wq,
  * teal_sparse_gemv_w4 (int4: group == 128, m % 128 == 0, f % 128 == 0), bitwise
  * the format's grouped call followed by its _swiglu call.
  *
- * teal_mlp_plan: the shape the library picks (HOST pointer out).
+ * teal_mlp_plan: the shape the library picks (HOST pointer, in and out): on entry
+ * gu_row_pitch and down_row_pitch say how the caller stores the matrices (0 =
+ * packed rows; they are left as they are, and a pitch the call would refuse
+ * gives TEAL_ERR_UNSUPPORTED), the other fields are written.  On rows an odd
+ * multiple of 256 bytes apart the gate / up products get the shape of
+ * teal_sparse_gemv_bf16_multi_pitch where this kernel has it (narrow tiles
+ * without split-K, slices of up to 8192 channels).
  * teal_mlp_block_info: host-only description of thread block `block` of the
  * launch a shape gives, for checking the schedule without a GPU.  info is a
  * HOST array of 8 ints: [0] blocks in the grid (always set; the rest is -1 when

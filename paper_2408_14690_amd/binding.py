@@ -772,9 +772,12 @@ def _mlp_pitches(sh, f, d):
     return int(pg), int(pd)
 
 
-def teal_mlp_plan(weight_bits: int, m: int, f: int, d: int):
-    """Returns (status, MlpShape): the launch shape the library picks."""
+def teal_mlp_plan(weight_bits: int, m: int, f: int, d: int, gu_row_pitch: int = 0,
+                  down_row_pitch: int = 0):
+    """Returns (status, MlpShape): the launch shape the library picks for matrices with these
+    row pitches (0 = packed rows)."""
     sh = MlpShape()
+    sh.gu_row_pitch, sh.down_row_pitch = int(gu_row_pitch), int(down_row_pitch)
     st = load_library().teal_mlp_plan(int(weight_bits), int(m), int(f), int(d), ctypes.byref(sh))
     return st, sh
 

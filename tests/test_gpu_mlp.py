@@ -456,3 +456,70 @@ def test_padded_rows_int8(T):
     sh.gu_row_pitch, sh.down_row_pitch = pg, pd
     got = run([pad(qd[0], pg), pad(qd[1], pg), pad(qd[2], pd)])
     assert all(bits_equal(a, b) for a, b in zip(want, got))
+
+
+@pytest.mark.parametrize("fmt,m,f,d,want_gu", [
+    ("w8", 4096, 14336, 4096, (8, 128, 1)),
+    ("bf16", 8192, 28672, 8192, (32, 256, 1)),
+])
+def test_planned_shape_for_padded_rows(T, fmt, m, f, d, want_gu):
+    """teal_mlp_plan told the row pitches picks narrow gate / up tiles without split-K; the
+    launch in that shape matches the oracle, and gate / up are bit for bit those of the grouped
+    call on the same padded rows (which plans the same shape)."""
+    bits = 8 if fmt == "w8" else 16
+    pad = 256 * 8 // bits
+    pg, pd = f + pad, d + pad
+    st, sh = T.teal_mlp_plan(bits, m, f, d, pg, pd)
+    T.check(st)
+    assert (sh.gu_lanes_per_row, sh.gu_tile_cols, sh.gu_splits) == want_gu
+    assert (sh.gu_row_pitch, sh.down_row_pitch) == (pg, pd)
+    grouped = T.teal_gemv_plan_multi_pitch(bits, m, [f, f], [pg, pg])[1]
+    assert (grouped["lanes_per_row"], grouped["tile_cols"], grouped["splits"]) == want_gu
+    ws = torch.zeros(T.teal_workspace_bytes_mlp(m, f, d), dtype=torch.uint8, device="cuda")
+    ws2 = torch.zeros(T.teal_workspace_bytes(m, 2 * f), dtype=torch.uint8, device="cuda")
+    outs = [torch.full((n,), float("nan"), dtype=torch.float32, device="cuda") for n in (f, f, d)]
+    rg, ru = (torch.full((f,), float("nan"), dtype=torch.float32, device="cuda") for _ in range(2))
+    rows = np.arange(0, f, 97).astype(np.int32)
+    if fmt == "w8":
+        q, x = quantised(T, "w8", m, f, d, 36700)
+        t = ti.quantile_threshold(x, 0.5)
+
+        def pad8(a, pitch):
+            out = torch.full((a.shape[0], pitch), 127, dtype=torch.int8, device="cuda")
+            out[:, :a.shape[1]] = dev(a)
+            return out
+
+        mats = [pad8(q[0][0], pg), pad8(q[1][0], pg), pad8(q[2][0], pd)]
+        sd = [dev(s_) for _, s_ in q]
+        xd = dev(x)
+
+        def run(t_down):
+            T.check(T.teal_sparse_mlp_w8(mats[0], mats[1], mats[2], sd[0], sd[1], sd[2], xd, t, t,
+                                         t_down, outs[0], outs[1], outs[2], m, f, d, ws, shape=sh))
+            torch.cuda.synchronize()
+
+        run(0.0)
+        h = orc.swiglu_f16(outs[0].cpu().numpy(), outs[1].cpu().numpy())
+        t_down = ti.quantile_threshold(h, 0.5)
+        run(t_down)
+        T.check(T.teal_sparse_gemv_w8_multi_pitch(mats[:2], [pg, pg], sd[:2], [t, t], [rg, ru], [f, f],
+                                                  xd, m, ws2))
+        torch.cuda.synchronize()
+        g_np, u_np = outs[0].cpu().numpy(), outs[1].cpu().numpy()
+        assert rel_l2(g_np, orc.sparse_gemv_w8(q[0][0], q[0][1], x, t)) <= TIGHT_WQ
+        assert rel_l2(u_np, orc.sparse_gemv_w8(q[1][0], q[1][1], x, t)) <= TIGHT_WQ
+        h = orc.swiglu_f16(g_np, u_np)
+        assert rel_l2(outs[2].cpu().numpy(), orc.sparse_gemv_w8(q[2][0], q[2][1], h, t_down)) <= TIGHT_WQ
+    else:
+        M = Mlp(T, m, f, d, seed=36800)
+        M.wt = [padded(T, M.wt[0], pg), padded(T, M.wt[1], pg), padded(T, M.wt[2], pd)]
+        g0, u0, _ = run_mlp(T, M, 0.0, ws, sh)
+        t_down = M.t_down_from(g0.cpu().numpy(), u0.cpu().numpy())
+        outs = list(run_mlp(T, M, t_down, ws, sh))
+        check_against_oracle(T, M, outs[0], outs[1], outs[2], t_down, ws, rows=rows)
+        T.check(T.teal_sparse_gemv_bf16_multi_pitch(M.wt[:2], [pg, pg], [M.t_gate, M.t_up], [rg, ru],
+                                                    [f, f], M.xd, m, ws2))
+        torch.cuda.synchronize()
+    assert bits_equal(outs[0], rg) and bits_equal(outs[1], ru)
+    off = T.teal_mlp_status_offset(m, f, d)
+    assert int(ws[off:off + 4].view(torch.int32).item()) == 0

@@ -226,6 +226,23 @@ def test_plan_and_argument_errors():
         setattr(bad, field, value)
         assert call(shape=bad) == T.TEAL_ERR_UNSUPPORTED
         assert T.teal_mlp_block_info(16, m, f, d, bad, 0)[0] == T.TEAL_ERR_UNSUPPORTED
+    # the plan follows the layout the caller names: narrow tiles without split-K on rotating rows
+    st, p70 = T.teal_mlp_plan(16, 8192, 28672, 8192, gu_row_pitch=28672 + 128, down_row_pitch=8192 + 128)
+    assert st == T.TEAL_OK and (p70.gu_lanes_per_row, p70.gu_tile_cols, p70.gu_splits) == (32, 256, 1)
+    assert (p70.gu_row_pitch, p70.down_row_pitch) == (28672 + 128, 8192 + 128)
+    st, p8 = T.teal_mlp_plan(8, m, f, d, gu_row_pitch=f + 256)
+    assert st == T.TEAL_OK and (p8.gu_lanes_per_row, p8.gu_tile_cols, p8.gu_splits) == (8, 128, 1)
+    st, pb = T.teal_mlp_plan(16, m, f, d, gu_row_pitch=f + 128)
+    assert (pb.gu_lanes_per_row, pb.gu_tile_cols, pb.gu_splits) == (16, 128, 1)
+    st, pc = T.teal_mlp_plan(16, 8192, 28672, 8192, gu_row_pitch=28672 + 512)      # not rotating
+    st0, p0 = T.teal_mlp_plan(16, 8192, 28672, 8192)
+    assert (pc.gu_lanes_per_row, pc.gu_tile_cols, pc.gu_splits) == (p0.gu_lanes_per_row, p0.gu_tile_cols, p0.gu_splits)
+    # bf16 tiles of 128 bytes (8 lanes) have no instance in this kernel: the packed choice stays
+    st, pn = T.teal_mlp_plan(16, m, 8192, d, gu_row_pitch=8192 + 128)
+    st0, pn0 = T.teal_mlp_plan(16, m, 8192, d)
+    assert (pn.gu_lanes_per_row, pn.gu_tile_cols, pn.gu_splits) == (pn0.gu_lanes_per_row, pn0.gu_tile_cols, pn0.gu_splits)
+    assert T.teal_mlp_plan(16, m, f, d, gu_row_pitch=f - 8)[0] == T.TEAL_ERR_UNSUPPORTED
+    assert T.teal_mlp_plan(4, m, f, d, gu_row_pitch=f + 128)[0] == T.TEAL_ERR_UNSUPPORTED
     good = T.MlpShape(**sh.as_dict())
     good.gu_row_pitch, good.down_row_pitch = f + 128, d + 128
     assert T.teal_mlp_block_info(16, m, f, d, good, -1)[1][0] == T.teal_mlp_block_info(16, m, f, d, sh, -1)[1][0]
