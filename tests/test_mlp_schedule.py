@@ -264,3 +264,21 @@ def test_plan_and_argument_errors():
     st, s8 = T.teal_mlp_plan(8, m, f, d)
     s8.down_row_pitch = d + 8                               # int8 rows: a multiple of 16
     assert T.teal_sparse_mlp_w8(shape=s8, **q) == T.TEAL_ERR_UNSUPPORTED
+
+
+def test_every_plan_for_padded_rows_is_a_shape_the_launch_accepts():
+    """teal_mlp_plan told the row pitches never names a shape teal_mlp_block_info (which
+    validates like the launch) refuses, whatever the sizes."""
+    for bits in (16, 8):
+        pad = 256 * 8 // bits
+        for m in (512, 2048, 4096, 5120, 8192, 16384):
+            for f in (1024, 3584, 5504, 8192, 14336, 28672, 57344):
+                for d in (512, 4096, 8192):
+                    for extra in (pad, 2 * pad, 5 * pad):
+                        st, sh = T.teal_mlp_plan(bits, m, f, d, f + extra, d + pad)
+                        assert st == T.TEAL_OK, (bits, m, f, d, extra)
+                        assert (sh.gu_row_pitch, sh.down_row_pitch) == (f + extra, d + pad)
+                        if sh.gu_splits == 1:
+                            assert m <= 8192
+                        st, _ = T.teal_mlp_block_info(bits, m, f, d, sh, 0)
+                        assert st == T.TEAL_OK, (bits, m, f, d, extra, sh.as_dict())
