@@ -277,7 +277,7 @@ teal_status teal_sparse_gemv_bf16_rmsnorm_multi(int count, const void *const *Wt
                                                 void *stream);
 /* On matrices with padded rows (row_pitch as for teal_sparse_gemv_bf16_multi_pitch): bitwise
  * teal_rmsnorm_f16 followed by teal_sparse_gemv_bf16_multi_pitch wherever that call's launch
- * shape has at least 16 lanes per row and m <= 4096, else the sums of the packed call's shape. */
+ * shape has at least 16 lanes per row, else the sums of the packed call's shape. */
 teal_status teal_sparse_gemv_bf16_rmsnorm_multi_pitch(int count, const void *const *Wt_bf16,
                                                       const int *row_pitch, const float *t,
                                                       float *const *y, const int *n,

@@ -131,7 +131,8 @@ hipError_t launch_gemv_bf16_rmsnorm_multi(int count, const void *const *Wt, cons
         return hipErrorInvalidValue;
     int n_max = 0;
     for (int k = 0; k < count; ++k) n_max = n[k] > n_max ? n[k] : n_max;
-    const GemvGeometry g = gemv_geometry(m, n_max, sh, FmtBF16::kElemsPerLane, 64);
+    const GemvGeometry g =
+        gemv_geometry(m, n_max, sh, FmtBF16::kElemsPerLane, 64, kMaxLongSlice);
     MultiArgs<FmtBF16> ma{};
     ma.count = count;
     ma.tile_begin[0] = 0;
@@ -145,9 +146,13 @@ hipError_t launch_gemv_bf16_rmsnorm_multi(int count, const void *const *Wt, cons
     }
     const int tiles = ma.tile_begin[count];
 #define TEAL_LAUNCH_N(LPR)                                                                     \
-    hipLaunchKernelGGL((sparse_gemv_rmsnorm_multi_kernel<FmtBF16, LPR, 4>),                    \
-                       dim3(tiles * g.splits), dim3(kNormWaves * 64), g.lds, stream, ma, h,    \
-                       gamma, eps, partial, counters, m, g.ks, g.tile_cols, g.splits)
+    do {                                                                                       \
+        if (!allow_large_lds(sparse_gemv_rmsnorm_multi_kernel<FmtBF16, LPR, 4>, g.lds))        \
+            return hipErrorInvalidValue;                                                       \
+        hipLaunchKernelGGL((sparse_gemv_rmsnorm_multi_kernel<FmtBF16, LPR, 4>),                \
+                           dim3(tiles * g.splits), dim3(kNormWaves * 64), g.lds, stream, ma,   \
+                           h, gamma, eps, partial, counters, m, g.ks, g.tile_cols, g.splits);  \
+    } while (0)
     if (sh.lanes_per_row == 64) TEAL_LAUNCH_N(64);
     else if (sh.lanes_per_row == 32) TEAL_LAUNCH_N(32);
     else TEAL_LAUNCH_N(16);

@@ -348,10 +348,15 @@ __device__ __forceinline__ bool survives(float xv, float t) { return fabsf(xv) >
 // ballots stay in registers between the two steps, and all of a wavefront's
 // loads of x are issued together.  Returns the total (same in all threads).
 // Needs k1 - k0 <= kMaxSlice.  All threads of the block must call it; ends
-// with a barrier after which list[] is complete.
+// with a barrier after which list[] is complete.  `prepared`, when given, carries
+// what the source prepares once per block (the scale of the normalisation) from
+// one piece of a long slice to the next: computed when `have_prepared` is false
+// (block-uniform), reused otherwise.
 template <int WAVES, class XS>
 __device__ __forceinline__ int compact_slice(const XS &x, float t, int k0,
-                                             int k1, int2 *list, int *seg_cnt, int &seg_excl)
+                                             int k1, int2 *list, int *seg_cnt, int &seg_excl,
+                                             float *prepared_io = nullptr,
+                                             bool have_prepared = false)
 {
     constexpr int PER_WAVE = kMaxSegs / WAVES;
     const int lane = threadIdx.x & 63;
@@ -366,7 +371,10 @@ __device__ __forceinline__ int compact_slice(const XS &x, float t, int k0,
 #pragma unroll
     for (int j = 0; j < PER_WAVE; ++j)
         raw[j] = x.load(min(k0 + (w + j * WAVES) * 64 + lane, k1 - 1));
-    const float prepared = x.prepare();
+    float prepared;
+    if (prepared_io && have_prepared) prepared = *prepared_io;
+    else prepared = x.prepare();
+    if (prepared_io) *prepared_io = prepared;
     const int w_uniform = __builtin_amdgcn_readfirstlane(w);
 #pragma unroll
     for (int j = 0; j < PER_WAVE; ++j) {
@@ -733,10 +741,11 @@ __device__ __forceinline__ bool gemv_block(const typename F::Args &a, const XS &
         }
     } else {
         int seg_excl;
+        float prepared = 0.f;
         cnt = 0;
         for (int c0 = k0; c0 < k1; c0 += kMaxSlice)
             cnt += compact_slice<WAVES>(x, t, c0, min(k1, c0 + kMaxSlice), list + cnt, seg_cnt,
-                                        seg_excl);
+                                        seg_excl, &prepared, c0 != k0);
     }
 
     trace_mark(2);

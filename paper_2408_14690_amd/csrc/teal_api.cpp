@@ -722,10 +722,9 @@ static teal_status gemv_bf16_rmsnorm_multi(int count, const void *const *Wt_bf16
     if (!norm_eps_ok(eps)) return TEAL_ERR_THRESHOLD;
     if (workspace_bytes < teal_workspace_bytes(m, (int)n_total)) return TEAL_ERR_WORKSPACE;
     // The launch shape of teal_sparse_gemv_bf16_multi (_pitch): same sums, bit for bit.  This
-    // kernel has no instance with 8 lanes per row and none for slices above kMaxSlice: there
-    // the shape of the packed call.
+    // kernel has no instance with 8 lanes per row: there the shape of the packed call.
     GemvShape sh = auto_shape_multi_pitch(m, n, row_pitch, count, 16, 8, 16, 64, 64);
-    if (sh.lanes_per_row < 16 || (sh.splits == 1 && m > teal::kMaxSlice))
+    if (sh.lanes_per_row < 16)
         sh = auto_shape_multi_pitch(m, n, nullptr, count, 16, 8, 16, 64, 64);
     return from_hip(teal::launch_gemv_bf16_rmsnorm_multi(
         count, Wt_bf16, row_pitch, t, y, n, h, gamma, eps, m, ws_partials(workspace, m),

@@ -143,7 +143,10 @@ def test_fused_grouped_product(T, name, ns, m, ps):
     ("llama q,k,v padded", [4096, 1024, 1024], [128, 8, 0], 4096, [0.5, 0.4, 0.25]),
     ("llama3 gate alone", [14336], [128], 4096, [0.5]),
     ("ragged", [264, 72, 8], [8, 0, 136], 1000, [0.0, 0.5, 0.9]),
-], ids=["gate_up", "qkv", "gate", "ragged"])
+    # 8192 input channels: a block normalises and compacts the whole state in two pieces
+    ("long slices", [14336, 14336], [128, 128], 8192, [0.5, 0.4]),
+    ("long slices, ragged", [10248, 10248, 264], [120, 120, 120], 5000, [0.5, 0.0, 0.9]),
+], ids=["gate_up", "qkv", "gate", "ragged", "long", "long_ragged"])
 def test_fused_grouped_product_on_padded_rows(T, name, ns, pads, m, ps):
     """Matrices with padded rows (bf16 NaNs in the padding): the oracle's result, the survivor
     counts, and bit for bit the normalisation kernel followed by the grouped call on the same
