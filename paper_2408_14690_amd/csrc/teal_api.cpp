@@ -310,7 +310,7 @@ const char *teal_status_string(teal_status s)
     return "unknown status";
 }
 
-int teal_version(void) { return 414; }
+int teal_version(void) { return 415; }
 
 size_t teal_survivors_offset(void) { return teal::kCounterBytes; }
 
